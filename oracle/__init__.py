@@ -1,0 +1,360 @@
+"""CommFuse CPU oracle (TEST INFRASTRUCTURE ONLY -- never on the product path).
+
+A plain, slow, fp64 statement of what the decomposed, ring-ordered, fused
+computation of the paper must produce.  Only ``tests/``, the smoke check and
+the benchmark's ``cpu_baseline`` leg may import this package; the GPU library
+and its Python binding never do, and this package imports neither of them.
+
+Two levels are provided.
+
+* Definitions (Sec. 3.1, "Common collective communications"; Sec. 4.1 and 4.2):
+  the undecomposed result -- a dense product followed by a reduce-scatter, an
+  all-gather followed by a dense product, a reduce-scatter of gradients.
+  The paper states its method is exact, so these ARE the expected values.
+* Lock-step simulations of Alg. 1 (FuseAllGather) and Alg. 2 / Alg. 3
+  (FuseReduceScatter, row-parallel projection) for all ``p`` ranks with an
+  in-memory mailbox standing for the P2P transfers, in the algorithms' own
+  order and notation (``r`` rank, ``i`` step, ``j`` send-to, ``k`` recv-from,
+  ``l`` slice index, ``B_in`` / ``B_out`` buffers).  They are checked against
+  the definitions; they also yield what every rank receives at every step,
+  which is what the one-rank views below take as their ``R_i`` / ``S_i``.
+* One-rank views: what a single rank ``r`` computes at each step when the
+  data delivered by rank ``r-1`` is handed in as an input.
+
+Readings of the paper taken here (each is listed in the design notes):
+the slice list of Alg. 2 is the input ``X^r`` cut into ``N`` equal row blocks;
+Alg. 3's compute line uses slice ``l`` (not the send rank ``j``);
+``compute_partial_output(X, W) = X @ W`` with activations on the left;
+``N = T = p`` (slicing granularity ``m = 1``); a receive posted at step ``i-1``
+is complete before ``B_in`` is read at step ``i``.
+
+Pins (see tests): the paper's 4-rank all-gather / reduce-scatter examples,
+the Appendix A(b) round-by-round trace, the exactness claim, closed-form
+index invariants, numpy.matmul on special cases, and a pure-Python brute
+force.  Nothing in this file is "parity unpinned".
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Callable, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libcf_oracle.so")
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < os.path.getmtime(
+        os.path.join(_HERE, "cf_oracle.c")
+    ):
+        from . import build as _b
+
+        _b.build(force=True)
+    lib = ctypes.CDLL(_LIB_PATH)
+    dp = ctypes.POINTER(ctypes.c_double)
+    i64 = ctypes.c_int64
+    lib.cfo_gemm_f64.argtypes = [dp, i64, dp, i64, dp, i64, i64, i64, i64]
+    lib.cfo_gemm_f64.restype = None
+    lib.cfo_dot_f64.argtypes = [dp, i64, dp, i64, i64, i64, i64]
+    lib.cfo_dot_f64.restype = ctypes.c_double
+    lib.cfo_add_f64.argtypes = [dp, dp, dp, i64]
+    lib.cfo_add_f64.restype = None
+    lib.cfo_num_threads.argtypes = []
+    lib.cfo_num_threads.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _dptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _f64(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def num_threads() -> int:
+    """Threads the C loops use (OpenMP's max threads)."""
+    return int(_load().cfo_num_threads())
+
+
+# ---------------------------------------------------------------------------
+# Elementary pieces
+# ---------------------------------------------------------------------------
+
+def gemm(X, W) -> np.ndarray:
+    """``compute_partial_output`` of a linear projection: ``X @ W`` in fp64.
+
+    Sec. 4.1 (row-sharded projection) and Sec. 4.2 (column-sharded projection);
+    activations on the left, ``X[M x K]``, ``W[K x N]``.  Triple loop in C.
+    """
+    X = _f64(X)
+    W = _f64(W)
+    if X.ndim != 2 or W.ndim != 2 or X.shape[1] != W.shape[0]:
+        raise ValueError(f"gemm shape mismatch {X.shape} @ {W.shape}")
+    M, K = X.shape
+    N = W.shape[1]
+    O = np.empty((M, N), dtype=np.float64)
+    if M and N:
+        _load().cfo_gemm_f64(_dptr(X), max(K, 1), _dptr(W), max(N, 1), _dptr(O), N, M, N, K)
+    return O
+
+
+def dot_element(X, W, i: int, j: int) -> float:
+    """One element ``(X @ W)[i, j]`` from its definition (for sampled checks)."""
+    X = _f64(X)
+    W = _f64(W)
+    return float(_load().cfo_dot_f64(_dptr(X), X.shape[1], _dptr(W), W.shape[1], i, j, X.shape[1]))
+
+
+def add(a, b) -> np.ndarray:
+    """``B_in + O`` of Alg. 2, element by element in fp64."""
+    a = _f64(a)
+    b = _f64(b)
+    if a.shape != b.shape:
+        raise ValueError("add shape mismatch")
+    out = np.empty_like(a)
+    if a.size:
+        _load().cfo_add_f64(_dptr(a), _dptr(b), _dptr(out), a.size)
+    return out
+
+
+def round_to_bf16(x) -> np.ndarray:
+    """Round fp64 values to the nearest bfloat16 (ties to even), returned as fp64.
+
+    Used only for the chained AG-GEMM -> GEMM-RS pair, where the intermediate
+    activations are handed over in bf16.
+    """
+    f = np.asarray(x, dtype=np.float64).astype(np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    u = (u + np.uint64(0x7FFF) + lsb) & np.uint64(0xFFFF0000)
+    return u.astype(np.uint32).view(np.float32).astype(np.float64).reshape(f.shape)
+
+
+# ---------------------------------------------------------------------------
+# Index functions of the two algorithms
+# ---------------------------------------------------------------------------
+
+def send_rank(p: int, r: int) -> int:
+    """``j = (r + 1) mod N`` (Alg. 1 and Alg. 2)."""
+    return (r + 1) % p
+
+
+def recv_rank(p: int, r: int) -> int:
+    """``k = (r - 1 + N) mod N`` (Alg. 1 and Alg. 2)."""
+    return (r - 1 + p) % p
+
+
+def slice_index_ag(p: int, r: int, i: int) -> int:
+    """``l = (r - i + N) mod N`` (Alg. 1): own slice first."""
+    return (r - i + p) % p
+
+
+def slice_index_rs(p: int, r: int, i: int) -> int:
+    """``l = (r - i - 1 + N) mod N`` (Alg. 2): own slice last."""
+    return (r - i - 1 + p) % p
+
+
+def split_rows(X, p: int) -> List[np.ndarray]:
+    """``init_sequence_as_sequence_list(X, N)``: N equal blocks along the sequence (row) axis."""
+    X = np.asarray(X)
+    if X.shape[0] % p:
+        raise ValueError("rows not divisible by p")
+    mc = X.shape[0] // p
+    return [X[c * mc:(c + 1) * mc] for c in range(p)]
+
+
+# ---------------------------------------------------------------------------
+# Collectives, by definition (Sec. 3.1)
+# ---------------------------------------------------------------------------
+
+def all_gather(per_rank: Sequence[np.ndarray]) -> List[np.ndarray]:
+    """Every rank ends with the concatenation, in rank order, of all ranks' data."""
+    full = np.concatenate([np.asarray(x) for x in per_rank], axis=0)
+    return [full.copy() for _ in per_rank]
+
+
+def reduce_scatter(per_rank_slices: Sequence[Sequence[np.ndarray]]) -> List[np.ndarray]:
+    """Rank ``c`` ends with the sum over ranks ``q`` of slice ``c`` of rank ``q``."""
+    p = len(per_rank_slices)
+    out = []
+    for c in range(p):
+        acc = np.zeros_like(np.asarray(per_rank_slices[0][c], dtype=np.float64))
+        for q in range(p):
+            acc = acc + np.asarray(per_rank_slices[q][c], dtype=np.float64)
+        out.append(acc)
+    return out
+
+
+# ---------------------------------------------------------------------------
+# Definitions of the three paths (undecomposed)
+# ---------------------------------------------------------------------------
+
+def rs_definition(A_list: Sequence[np.ndarray], W_list: Sequence[np.ndarray]) -> List[np.ndarray]:
+    """Row-parallel projection then reduce-scatter (Sec. 4.1 with Sec. 3.1).
+
+    Rank ``q`` holds ``A^q[M x K_q]`` and ``W^q[K_q x N]``; the full partial
+    product ``A^q @ W^q`` is cut into ``p`` row blocks and reduce-scattered.
+    """
+    p = len(A_list)
+    partial = [split_rows(gemm(A_list[q], W_list[q]), p) for q in range(p)]
+    return reduce_scatter(partial)
+
+
+def ag_definition(X_list: Sequence[np.ndarray], W_list: Sequence[np.ndarray]) -> List[np.ndarray]:
+    """All-gather of sequence shards, then column-parallel projection (Sec. 4.2)."""
+    gathered = all_gather([_f64(x) for x in X_list])
+    return [gemm(gathered[r], W_list[r]) for r in range(len(X_list))]
+
+
+def dp_definition(g_list: Sequence[np.ndarray]) -> List[np.ndarray]:
+    """Reduce-scatter of the gradient buckets of ``p`` data-parallel ranks (Sec. 3.1, Zero-DP)."""
+    p = len(g_list)
+    return reduce_scatter([split_rows(np.asarray(g, dtype=np.float64), p) for g in g_list])
+
+
+# ---------------------------------------------------------------------------
+# Lock-step simulation of the algorithms over all p ranks
+# ---------------------------------------------------------------------------
+
+Compute = Callable[[np.ndarray, np.ndarray], np.ndarray]
+
+
+def fuse_rs_lockstep(
+    X_list: Sequence[np.ndarray],
+    W_list: Sequence[Optional[np.ndarray]],
+    compute: Optional[Compute] = None,
+) -> Tuple[List[np.ndarray], List[List[Optional[np.ndarray]]], List[List[Optional[np.ndarray]]]]:
+    """Alg. 2 (FuseReduceScatter) run by all ranks in lock-step.
+
+    Returns ``(O, received, sent)``: ``O[r]`` is rank ``r``'s result;
+    ``received[r][i]`` is the content of ``B_in`` that rank ``r`` adds at step
+    ``i`` (``None`` at ``i = 0``); ``sent[r][i]`` is ``B_out`` after step ``i``
+    (``None`` at the last step, where nothing is sent).
+    """
+    if compute is None:
+        compute = gemm
+    N = len(X_list)
+    X_s = [split_rows(X_list[r], N) for r in range(N)]
+    B_in: List[Optional[np.ndarray]] = [None] * N
+    O: List[Optional[np.ndarray]] = [None] * N
+    received = [[None] * N for _ in range(N)]
+    sent = [[None] * N for _ in range(N)]
+    for i in range(N):
+        in_flight: List[Optional[np.ndarray]] = [None] * N
+        for r in range(N):
+            j = send_rank(N, r)
+            l = slice_index_rs(N, r, i)
+            O[r] = compute(X_s[r][l], W_list[r])
+            if i > 0:
+                received[r][i] = B_in[r]
+                O[r] = add(B_in[r], O[r])
+            if i < N - 1:
+                B_out = O[r].copy()
+                sent[r][i] = B_out
+                in_flight[j] = B_out          # p2p_send to j == p2p_recv at j from its k
+        B_in = in_flight                        # transfers of step i land before step i+1 reads
+    return [o for o in O], received, sent
+
+
+def fuse_ag_lockstep(
+    X_list: Sequence[np.ndarray],
+    W_list: Sequence[np.ndarray],
+    compute: Optional[Compute] = None,
+) -> Tuple[List[np.ndarray], List[List[Optional[np.ndarray]]]]:
+    """Alg. 1 (FuseAllGather) run by all ranks in lock-step.
+
+    Returns ``(O, held)``: ``O[r]`` is the concatenated output of rank ``r``;
+    ``held[r][i]`` is the slice in ``B_out`` that rank ``r`` multiplies at step ``i``
+    (its own ``X^r`` at ``i = 0``, then what rank ``r-1`` forwarded).
+    """
+    if compute is None:
+        compute = gemm
+    N = len(X_list)
+    B_out = [_f64(X_list[r]) for r in range(N)]
+    O_s: List[List[Optional[np.ndarray]]] = [[None] * N for _ in range(N)]
+    held = [[None] * N for _ in range(N)]
+    for i in range(N):
+        B_in: List[Optional[np.ndarray]] = [None] * N
+        for r in range(N):
+            j = send_rank(N, r)
+            l = slice_index_ag(N, r, i)
+            if i < N - 1:
+                B_in[j] = B_out[r]              # send what is in hand, neighbour receives it
+            held[r][i] = B_out[r]
+            O_s[r][l] = compute(B_out[r], W_list[r])
+        if i < N - 1:
+            B_out = B_in                         # after the wait: forward the received slice
+    O = [np.concatenate(O_s[r], axis=0) for r in range(N)]
+    return O, held
+
+
+def fuse_dp_lockstep(g_list: Sequence[np.ndarray]):
+    """Alg. 2 with ``compute_partial_output`` = "take slice ``l`` of the local gradient bucket".
+
+    The paper gives no separate data-parallel algorithm; this is the reading
+    used for the gradient path.  Returns ``(O, received, sent)`` as :func:`fuse_rs_lockstep`.
+    """
+    return fuse_rs_lockstep(g_list, [None] * len(g_list), compute=lambda x, _w: _f64(x).copy())
+
+
+# ---------------------------------------------------------------------------
+# One-rank views: rank r alone, neighbour traffic handed in
+# ---------------------------------------------------------------------------
+
+def rs_rank_steps(A, W, R: Sequence[Optional[np.ndarray]], p: int, r: int) -> List[np.ndarray]:
+    """What rank ``r`` holds after each step of Alg. 2 / Alg. 3.
+
+    ``A[p*M_c x K]`` local activations, ``W[K x N]`` row shard, ``R[i]`` the
+    partial sum received for step ``i`` (``R[0]`` is ignored).  ``out[i]`` is
+    ``B_out`` for ``i < p-1`` and the result ``O^r`` for ``i = p-1``.
+    """
+    X_s = split_rows(_f64(A), p)
+    outs = []
+    for i in range(p):
+        l = slice_index_rs(p, r, i)
+        O = gemm(X_s[l], W)
+        if i > 0:
+            O = add(_f64(R[i]), O)
+        outs.append(O)
+    return outs
+
+
+def ag_rank(X_own, S: Sequence[Optional[np.ndarray]], W, p: int, r: int) -> np.ndarray:
+    """Rank ``r``'s output of Alg. 1: slice ``l_i`` of ``O`` is ``T_i @ W`` with
+    ``T_0 = X^r`` and ``T_i = S[i]`` (the slice received for step ``i``)."""
+    O_s: List[Optional[np.ndarray]] = [None] * p
+    for i in range(p):
+        l = slice_index_ag(p, r, i)
+        T = _f64(X_own) if i == 0 else _f64(S[i])
+        O_s[l] = gemm(T, W)
+    return np.concatenate(O_s, axis=0)
+
+
+def dp_rank(bucket, R: Sequence[Optional[np.ndarray]], p: int, r: int) -> np.ndarray:
+    """Gradient bucket of rank ``r`` after its ``p`` steps: at step ``i >= 1`` slice
+    ``l_i = (r-i-1) mod p`` becomes ``R[i] + slice``; step 0 only sends."""
+    out = _f64(bucket).copy()
+    n = out.shape[0]
+    if n % p:
+        raise ValueError("bucket length not divisible by p")
+    c = n // p
+    for i in range(1, p):
+        l = slice_index_rs(p, r, i)
+        out[l * c:(l + 1) * c] = add(_f64(R[i]), out[l * c:(l + 1) * c])
+    return out
+
+
+def mlp_pair_rank(X_own, S, W_up, W_down, R, p: int, r: int):
+    """Chained pair on rank ``r``: AG-GEMM (up) producing ``H``, rounded to bf16 for
+    the hand-over, then GEMM-RS (down) on ``H``.  No activation function and no
+    gate sit between them (the paper states none).  Returns ``(H_bf16, outs)``."""
+    H = round_to_bf16(ag_rank(X_own, S, W_up, p, r))
+    return H, rs_rank_steps(H, W_down, R, p, r)
