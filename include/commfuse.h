@@ -1,0 +1,172 @@
+/*
+ * commfuse.h -- C ABI of the CommFuse rank-step library for AMD MI355X (gfx950).
+ *
+ * One rank's share of the paper's decomposed, ring-ordered, fused replacement
+ * of reduce-scatter after a row-parallel GEMM (FuseReduceScatter, Alg. 2 and
+ * its row-parallel instantiation Alg. 3 / Sec. 4.1) and of all-gather before a
+ * column-parallel GEMM (FuseAllGather, Alg. 1 / Sec. 4.2), plus the
+ * data-parallel gradient reduce step (Alg. 2 with the identity as
+ * compute_partial_output; Sec. 3.1, Zero-DP paragraph).
+ *
+ * Notation follows the paper: p = ring size (T = N, slicing granularity m = 1),
+ * r = rank, i = step in [0, p), l = slice index computed at step i,
+ * B_in / B_out = receive / send buffers.
+ *
+ * Conventions for every entry point
+ *   - Plain C.  All tensor pointers are DEVICE pointers unless a comment says
+ *     "host".  Descriptor structs and pointer tables are HOST memory.
+ *   - Row-major tensors with explicit row strides in elements (0 = packed).
+ *   - The caller owns every buffer and every stream.  Nothing here allocates
+ *     device memory.  No call synchronises the device: work is enqueued on the
+ *     given HIP stream(s) (hipStream_t passed as void*; NULL = default stream)
+ *     and the call returns.
+ *   - Errors: a negative cf_status is returned and nothing is enqueued; the
+ *     text of the last error of the calling thread is kept for
+ *     commfuse_last_error().  The library never aborts or throws.
+ *   - Alignment: every tensor base pointer must be 16-byte aligned; k, n and
+ *     all row strides must be multiples of 8 elements for bf16 operands and of
+ *     4 elements for fp32 operands (CF_ERR_MISALIGNED otherwise).
+ */
+#ifndef COMMFUSE_H
+#define COMMFUSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CF_OK = 0,
+    CF_ERR_INVALID_ARG = -1,  /* p, rank, step, sizes or flags out of range     */
+    CF_ERR_NULL_PTR = -2,     /* a required pointer is NULL (or recv misplaced) */
+    CF_ERR_UNSUPPORTED = -3,  /* dtype / layout combination not implemented     */
+    CF_ERR_MISALIGNED = -4,   /* pointer or stride alignment rule violated      */
+    CF_ERR_HIP = -5           /* a HIP runtime call failed (see last_error)     */
+} cf_status;
+
+typedef enum { CF_BF16 = 0, CF_F32 = 1 } cf_dtype;
+typedef enum { CF_KIND_RS = 0, CF_KIND_AG = 1, CF_KIND_DP = 2 } cf_kind;
+
+/* Memory order of the weight shard W^r.
+ *   CF_W_KN: W[k x n], row-major, n contiguous -- the paper's W_o^r in R^{D/T x D}
+ *            multiplied from the right (Alg. 3 parameters line).
+ *   CF_W_NK: the same matrix stored transposed, [n x k] with k contiguous (the
+ *            order in which linear layers commonly keep their weights). */
+typedef enum { CF_W_KN = 0, CF_W_NK = 1 } cf_wlayout;
+
+/* One tensor-parallel layer on one rank (Alg. 1 / Alg. 2 "Input", "Parameters",
+ * "Output" lines).  HOST struct. */
+typedef struct {
+    int32_t p;         /* ring size T (= N, m = 1), >= 1                         */
+    int32_t rank;      /* r in [0, p)                                            */
+    int64_t m_chunk;   /* rows per sequence slice, B*S/p                         */
+    int64_t n;         /* output features of this rank's weight shard            */
+    int64_t k;         /* contraction length of this rank's weight shard         */
+    int64_t lda;       /* row stride of the activations / slice (0 = k)          */
+    int64_t ldw;       /* row stride of W (0 = n for CF_W_KN, k for CF_W_NK)      */
+    int64_t ldo;       /* row stride of outputs, partial sums and B_in (0 = n)   */
+    int32_t in_dtype;  /* cf_dtype of activations and W                          */
+    int32_t out_dtype; /* cf_dtype of the all-gather path's output O; partial
+                          sums, B_in, B_out and the reduce-scatter result are
+                          always fp32                                            */
+    int32_t w_layout;  /* cf_wlayout                                             */
+    int32_t reserved;  /* must be 0                                              */
+} cf_layer_desc;
+
+/* Slice index l of step i: Alg. 2 "l = (r - i - 1 + N) mod N" for CF_KIND_RS and
+ * CF_KIND_DP, Alg. 1 "l = (r - i + N) mod N" for CF_KIND_AG.  Host-only
+ * arithmetic.  Returns a negative cf_status on bad arguments. */
+int commfuse_chunk_index(int kind, int p, int rank, int step);
+
+/* One iteration i of Alg. 2 / Alg. 3 (compute, aggregate, stage for sending):
+ *     out = A[l*m_chunk : (l+1)*m_chunk, :] @ W  (+ recv  if step > 0)
+ * fused in one kernel: the chunk GEMM accumulates in fp32 and its epilogue adds
+ * B_in and stores B_out.
+ *   A    [p*m_chunk x k]  local activations X^r, in_dtype; the call selects slice l
+ *   W    weight shard, in_dtype, layout desc->w_layout
+ *   recv B_in [m_chunk x n] fp32, row stride ldo; must be NULL iff step == 0
+ *   out  [m_chunk x n] fp32, row stride ldo: B_out for step < p-1, the rank's
+ *        result O^r for step == p-1.  May not alias recv.
+ */
+cf_status commfuse_rs_step(const cf_layer_desc *desc, int step, const void *A, const void *W,
+                           const float *recv, float *out, void *hip_stream);
+
+/* One iteration i of Alg. 1 (the compute on the slice in hand):
+ *     O[l*m_chunk : (l+1)*m_chunk, :] = shard @ W
+ *   shard B_out [m_chunk x k], in_dtype, row stride lda: X^r when step == 0,
+ *         afterwards the slice received from rank r-1
+ *   O     [p*m_chunk x n], out_dtype (fp32, or bf16 rounded to nearest even from
+ *         the fp32 accumulator), row stride ldo; the concatenation of Alg. 1's
+ *         last line is done in place by writing slice l at its row offset.
+ */
+cf_status commfuse_ag_step(const cf_layer_desc *desc, int step, const void *shard, const void *W,
+                           void *O, void *hip_stream);
+
+/* Data-parallel gradient path: iteration i of Alg. 2 with compute_partial_output
+ * = "take slice l of the local gradient bucket":
+ *     bucket[l*chunk_elems : (l+1)*chunk_elems] += recv      (step in [1, p))
+ * step 0 computes nothing (its slice is only sent) and enqueues nothing.
+ *   bucket fp32 [p*chunk_elems], updated in place;  recv fp32 [chunk_elems].
+ *   chunk_elems may be any non-negative number and the pointers need only be
+ *   4-byte aligned; the 16-byte vector kernel runs when both the slice start
+ *   and recv are 16-byte aligned (a scalar kernel handles the rest).
+ */
+cf_status commfuse_dp_reduce_step(int p, int rank, int step, float *bucket, int64_t chunk_elems,
+                                  const float *recv, void *hip_stream);
+
+/* Buffers of a whole emulated rank step.  HOST struct holding DEVICE pointers.
+ * Peer traffic is emulated: what rank r-1 would deliver for step i (i = 1..p-1)
+ * sits in peer_stage[i-1] and is copied into slot[i % 2] on the copy stream. */
+typedef struct {
+    const void *A_or_own_shard;   /* RS: A [p*m_chunk x k]; AG: X^r [m_chunk x k]; DP: unused */
+    const void *W;                /* weight shard (unused for DP)                             */
+    void *O;                      /* RS: O^r [m_chunk x n] fp32; AG: O [p*m_chunk x n]; DP: bucket */
+    const void *const *peer_stage;/* host array of p-1 device pointers (may be NULL if p == 1) */
+    void *slot[2];                /* B_in double buffer: RS fp32 [m_chunk x n]; AG in_dtype
+                                     [m_chunk x k]; DP fp32 [chunk_elems]                      */
+    float *send_slot[2];          /* RS: B_out double buffer fp32 [m_chunk x n]; else unused   */
+    void *const *peer_sink;       /* optional host array of p-1 device pointers receiving the
+                                     emulated sends of steps 0..p-2 (RS: B_out, AG: the slice
+                                     in hand, DP: slice l); NULL = sends are not copied        */
+} cf_buffers;
+
+enum {
+    CF_NO_COPY = 1u,     /* enqueue the kernels only (slots keep whatever they hold)   */
+    CF_NO_COMPUTE = 2u,  /* enqueue the copies only                                    */
+    CF_SERIAL = 4u,      /* one stream, copy i+1 strictly after kernel i: no overlap   */
+    CF_POISON = 8u,      /* debug: fill each B_in slot with NaN bytes before its copy  */
+    CF_GRAPH = 16u       /* capture the schedule once into a HIP graph, replay after   */
+};
+
+/* A whole rank step: the p iterations of Alg. 1 (CF_KIND_AG) or Alg. 2
+ * (CF_KIND_RS, CF_KIND_DP) with the paper's overlap: while the kernel of step i
+ * runs on compute_stream, the delivery for step i+1 is copied on copy_stream;
+ * p kernels, p-1 deliveries, nothing after the last kernel.  Ordering between
+ * the two streams uses HIP events owned by the library.  On return
+ * compute_stream has been made to wait for everything enqueued, so one
+ * hipStreamSynchronize(compute_stream) by the caller suffices.
+ * For CF_KIND_DP, desc->m_chunk is the number of elements per slice and n, k,
+ * dtypes are ignored.  Overlapping calls that share slots race. */
+cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_buffers *bufs,
+                                void *compute_stream, void *copy_stream, uint32_t flags);
+
+/* Text of the calling thread's last error ("" if none).  Host pointer, valid
+ * until the thread's next failing call. */
+const char *commfuse_last_error(void);
+
+/* Bytes of device workspace the step kernels need for this layer (0: none). */
+size_t commfuse_workspace_bytes(const cf_layer_desc *desc, int kind);
+
+/* Destroys the events and graphs the library created lazily.  Call with no
+ * work of this library in flight. */
+void commfuse_destroy_cache(void);
+
+/* Library version, e.g. 100 = 1.0.0. */
+int commfuse_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COMMFUSE_H */

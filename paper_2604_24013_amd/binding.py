@@ -1,0 +1,187 @@
+"""ctypes binding of ``libcommfuse.so`` -- argument marshalling only.
+
+Every function here has the name of the C entry point it calls (minus the
+``commfuse_`` prefix) and does nothing but turn torch tensors / Python numbers
+into pointers and sizes.  There is no fallback: if the library has not been
+built, loading raises.  PyTorch supplies device memory and streams only.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libcommfuse.so")
+
+CF_OK = 0
+CF_ERR_INVALID_ARG, CF_ERR_NULL_PTR, CF_ERR_UNSUPPORTED, CF_ERR_MISALIGNED, CF_ERR_HIP = -1, -2, -3, -4, -5
+CF_BF16, CF_F32 = 0, 1
+CF_KIND_RS, CF_KIND_AG, CF_KIND_DP = 0, 1, 2
+CF_W_KN, CF_W_NK = 0, 1
+CF_NO_COPY, CF_NO_COMPUTE, CF_SERIAL, CF_POISON, CF_GRAPH = 1, 2, 4, 8, 16
+
+KINDS = {"rs": CF_KIND_RS, "ag": CF_KIND_AG, "dp": CF_KIND_DP}
+DTYPES = {"bf16": CF_BF16, "f32": CF_F32}
+
+EXPORTS = [
+    "commfuse_chunk_index", "commfuse_rs_step", "commfuse_ag_step", "commfuse_dp_reduce_step",
+    "commfuse_run_schedule", "commfuse_last_error", "commfuse_workspace_bytes",
+    "commfuse_destroy_cache", "commfuse_version",
+]
+
+
+class LayerDesc(ctypes.Structure):
+    _fields_ = [
+        ("p", ctypes.c_int32), ("rank", ctypes.c_int32),
+        ("m_chunk", ctypes.c_int64), ("n", ctypes.c_int64), ("k", ctypes.c_int64),
+        ("lda", ctypes.c_int64), ("ldw", ctypes.c_int64), ("ldo", ctypes.c_int64),
+        ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
+        ("w_layout", ctypes.c_int32), ("reserved", ctypes.c_int32),
+    ]
+
+
+class Buffers(ctypes.Structure):
+    _fields_ = [
+        ("A_or_own_shard", ctypes.c_void_p), ("W", ctypes.c_void_p), ("O", ctypes.c_void_p),
+        ("peer_stage", ctypes.POINTER(ctypes.c_void_p)),
+        ("slot", ctypes.c_void_p * 2), ("send_slot", ctypes.c_void_p * 2),
+        ("peer_sink", ctypes.POINTER(ctypes.c_void_p)),
+    ]
+
+
+class CommFuseError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"commfuse status {status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def load():
+    """Loads the in-tree library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2604_24013_amd.build` "
+            "(there is no CPU or PyTorch fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+    lib.commfuse_chunk_index.argtypes = [i32, i32, i32, i32]
+    lib.commfuse_chunk_index.restype = i32
+    lib.commfuse_rs_step.argtypes = [ctypes.POINTER(LayerDesc), i32, vp, vp, vp, vp, vp]
+    lib.commfuse_rs_step.restype = i32
+    lib.commfuse_ag_step.argtypes = [ctypes.POINTER(LayerDesc), i32, vp, vp, vp, vp]
+    lib.commfuse_ag_step.restype = i32
+    lib.commfuse_dp_reduce_step.argtypes = [i32, i32, i32, vp, i64, vp, vp]
+    lib.commfuse_dp_reduce_step.restype = i32
+    lib.commfuse_run_schedule.argtypes = [ctypes.POINTER(LayerDesc), i32, ctypes.POINTER(Buffers), vp, vp, ctypes.c_uint32]
+    lib.commfuse_run_schedule.restype = i32
+    lib.commfuse_last_error.argtypes = []
+    lib.commfuse_last_error.restype = ctypes.c_char_p
+    lib.commfuse_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc), i32]
+    lib.commfuse_workspace_bytes.restype = ctypes.c_size_t
+    lib.commfuse_destroy_cache.argtypes = []
+    lib.commfuse_destroy_cache.restype = None
+    lib.commfuse_version.argtypes = []
+    lib.commfuse_version.restype = i32
+    _lib = lib
+    return lib
+
+
+def last_error() -> str:
+    return load().commfuse_last_error().decode()
+
+
+def _check(status: int) -> None:
+    if status != CF_OK:
+        raise CommFuseError(status, last_error())
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (or raw) pointer of a torch tensor, an int, or None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(s) -> Optional[int]:
+    if s is None:
+        return None
+    if isinstance(s, int):
+        return s or None
+    return s.cuda_stream or None
+
+
+def layer_desc(p: int, rank: int, m_chunk: int, n: int, k: int, in_dtype="bf16", out_dtype="f32",
+               w_layout: int = CF_W_KN, lda: int = 0, ldw: int = 0, ldo: int = 0) -> LayerDesc:
+    d = LayerDesc()
+    d.p, d.rank, d.m_chunk, d.n, d.k = p, rank, m_chunk, n, k
+    d.lda, d.ldw, d.ldo = lda, ldw, ldo
+    d.in_dtype = DTYPES[in_dtype] if isinstance(in_dtype, str) else in_dtype
+    d.out_dtype = DTYPES[out_dtype] if isinstance(out_dtype, str) else out_dtype
+    d.w_layout = w_layout
+    d.reserved = 0
+    return d
+
+
+def version() -> int:
+    return load().commfuse_version()
+
+
+def chunk_index(kind: int, p: int, rank: int, step: int) -> int:
+    v = load().commfuse_chunk_index(kind, p, rank, step)
+    if v < 0:
+        raise CommFuseError(v, last_error())
+    return v
+
+
+def rs_step(desc: LayerDesc, step: int, A, W, recv, out, stream=None) -> None:
+    _check(load().commfuse_rs_step(ctypes.byref(desc), step, _ptr(A), _ptr(W), _ptr(recv), _ptr(out), _stream(stream)))
+
+
+def ag_step(desc: LayerDesc, step: int, shard, W, O, stream=None) -> None:
+    _check(load().commfuse_ag_step(ctypes.byref(desc), step, _ptr(shard), _ptr(W), _ptr(O), _stream(stream)))
+
+
+def dp_reduce_step(p: int, rank: int, step: int, bucket, chunk_elems: int, recv, stream=None) -> None:
+    _check(load().commfuse_dp_reduce_step(p, rank, step, _ptr(bucket), chunk_elems, _ptr(recv), _stream(stream)))
+
+
+def make_buffers(A_or_own_shard, W, O, peer_stage: Sequence, slot: Sequence, send_slot: Sequence = (None, None),
+                 peer_sink: Optional[Sequence] = None) -> Buffers:
+    """Fills a ``cf_buffers``.  The returned object keeps the pointer tables alive;
+    the caller keeps the tensors alive."""
+    b = Buffers()
+    b.A_or_own_shard, b.W, b.O = _ptr(A_or_own_shard), _ptr(W), _ptr(O)
+    n = len(peer_stage)
+    stage = (ctypes.c_void_p * max(n, 1))(*[_ptr(t) for t in peer_stage])
+    b.peer_stage = ctypes.cast(stage, ctypes.POINTER(ctypes.c_void_p)) if n else None
+    b._stage_keepalive = stage
+    b.slot[0], b.slot[1] = _ptr(slot[0]), _ptr(slot[1])
+    b.send_slot[0], b.send_slot[1] = _ptr(send_slot[0]), _ptr(send_slot[1])
+    if peer_sink is not None and len(peer_sink):
+        sink = (ctypes.c_void_p * len(peer_sink))(*[_ptr(t) for t in peer_sink])
+        b.peer_sink = ctypes.cast(sink, ctypes.POINTER(ctypes.c_void_p))
+        b._sink_keepalive = sink
+    else:
+        b.peer_sink = None
+    return b
+
+
+def run_schedule(desc: LayerDesc, kind: int, bufs: Buffers, compute_stream, copy_stream, flags: int = 0) -> None:
+    _check(load().commfuse_run_schedule(ctypes.byref(desc), kind, ctypes.byref(bufs), _stream(compute_stream),
+                                        _stream(copy_stream), flags))
+
+
+def workspace_bytes(desc: LayerDesc, kind: int) -> int:
+    return int(load().commfuse_workspace_bytes(ctypes.byref(desc), kind))
+
+
+def destroy_cache() -> None:
+    load().commfuse_destroy_cache()

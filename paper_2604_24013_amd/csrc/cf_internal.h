@@ -1,0 +1,38 @@
+// Internal declarations shared by the translation units of libcommfuse.so.
+// Nothing here is part of the C ABI (that is include/commfuse.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cf {
+
+// One chunk GEMM: out[M x N] = A[M x K] * W (+ recv), fp32 accumulation.
+// A points at the first row of the slice; W is [K x N] (w_kn) or [N x K].
+struct GemmParams {
+    const void *A;
+    const void *W;
+    const float *recv;   // nullable: B_in of Alg. 2
+    void *out;
+    int64_t lda, ldw, ldo;
+    int M, N, K;
+};
+
+struct TileChoice {
+    int bm, bn;          // workgroup tile
+    int splitk;          // reserved (1)
+};
+
+// Chooses the workgroup tile for a chunk GEMM from its shape and the number of
+// compute units (the per-step grids are small against 256 CUs).
+TileChoice choose_tile_bf16(int M, int N, int K, int num_cu);
+
+hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, int num_cu);
+hipError_t launch_gemm_f32(const GemmParams &p, bool w_kn, hipStream_t s, int num_cu);
+
+// dst[e] += src[e], e in [0, n)
+hipError_t launch_dp_reduce(float *dst, const float *src, int64_t n, hipStream_t s, int num_cu);
+
+// Fills a buffer with 0xFF bytes (a NaN pattern for fp32 and bf16) -- debug poison.
+hipError_t launch_fill_ff(void *dst, size_t bytes, hipStream_t s);
+
+}  // namespace cf

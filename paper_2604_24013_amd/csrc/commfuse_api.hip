@@ -1,0 +1,548 @@
+// C ABI of libcommfuse.so: argument checking, slice selection (the index lines
+// of Alg. 1 and Alg. 2), kernel dispatch, and the two-stream emulated rank step.
+// The contract of every entry point is stated in include/commfuse.h.
+#include "../../include/commfuse.h"
+#include "cf_internal.h"
+
+#include <climits>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <unordered_map>
+#include <vector>
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+cf_status fail(cf_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+cf_status fail_hip(hipError_t e, const char *what)
+{
+    return fail(CF_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define CF_HIP(call)                         \
+    do {                                     \
+        hipError_t e_ = (call);              \
+        if (e_ != hipSuccess)                \
+            return fail_hip(e_, #call);      \
+    } while (0)
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int num_cu_of_current_device()
+{
+    static std::mutex mu;
+    static int cache[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64)
+        return 256;
+    std::lock_guard<std::mutex> lk(mu);
+    if (cache[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cache[dev] = n;
+    }
+    return cache[dev];
+}
+
+struct Resolved {      // descriptor with defaults filled in
+    int p, rank;
+    int64_t mc, n, k, lda, ldw, ldo;
+    bool bf16_in, bf16_out, w_kn;
+};
+
+size_t in_elem(const Resolved &r) { return r.bf16_in ? 2 : 4; }
+
+cf_status resolve(const cf_layer_desc *d, int kind, Resolved *out)
+{
+    if (d == nullptr)
+        return fail(CF_ERR_NULL_PTR, "descriptor is NULL");
+    if (d->p < 1)
+        return fail(CF_ERR_INVALID_ARG, "p = %d must be >= 1", d->p);
+    if (d->rank < 0 || d->rank >= d->p)
+        return fail(CF_ERR_INVALID_ARG, "rank = %d not in [0, %d)", d->rank, d->p);
+    if (d->m_chunk < 0 || d->n < 0 || d->k < 0)
+        return fail(CF_ERR_INVALID_ARG, "negative size (m_chunk=%lld n=%lld k=%lld)", (long long)d->m_chunk,
+                    (long long)d->n, (long long)d->k);
+    if (d->reserved != 0)
+        return fail(CF_ERR_INVALID_ARG, "reserved field must be 0");
+    Resolved r;
+    r.p = d->p;
+    r.rank = d->rank;
+    r.mc = d->m_chunk;
+    r.n = d->n;
+    r.k = d->k;
+    if (kind == CF_KIND_DP) {
+        r.lda = r.ldw = r.ldo = 0;
+        r.bf16_in = r.bf16_out = false;
+        r.w_kn = true;
+        *out = r;
+        return CF_OK;
+    }
+    if (d->in_dtype != CF_BF16 && d->in_dtype != CF_F32)
+        return fail(CF_ERR_UNSUPPORTED, "in_dtype %d", d->in_dtype);
+    if (d->out_dtype != CF_BF16 && d->out_dtype != CF_F32)
+        return fail(CF_ERR_UNSUPPORTED, "out_dtype %d", d->out_dtype);
+    if (d->w_layout != CF_W_KN && d->w_layout != CF_W_NK)
+        return fail(CF_ERR_UNSUPPORTED, "w_layout %d", d->w_layout);
+    r.bf16_in = d->in_dtype == CF_BF16;
+    r.bf16_out = (kind == CF_KIND_AG) && d->out_dtype == CF_BF16;
+    if (r.bf16_out && !r.bf16_in)
+        return fail(CF_ERR_UNSUPPORTED, "bf16 output needs bf16 operands");
+    r.w_kn = d->w_layout == CF_W_KN;
+    if (d->lda < 0 || d->ldw < 0 || d->ldo < 0)
+        return fail(CF_ERR_INVALID_ARG, "negative row stride");
+    r.lda = d->lda ? d->lda : r.k;
+    r.ldw = d->ldw ? d->ldw : (r.w_kn ? r.n : r.k);
+    r.ldo = d->ldo ? d->ldo : r.n;
+    if (r.lda < r.k || r.ldw < (r.w_kn ? r.n : r.k) || r.ldo < r.n)
+        return fail(CF_ERR_INVALID_ARG, "row stride smaller than the row (lda=%lld ldw=%lld ldo=%lld)",
+                    (long long)r.lda, (long long)r.ldw, (long long)r.ldo);
+    const int64_t mult = r.bf16_in ? 8 : 4;
+    if (r.k % mult || r.n % mult || r.lda % mult || r.ldw % mult || r.ldo % mult)
+        return fail(CF_ERR_MISALIGNED, "k, n and row strides must be multiples of %lld elements", (long long)mult);
+    const int64_t lim = INT_MAX / 2;
+    if (r.mc * r.p > lim || r.n > lim || r.k > lim)
+        return fail(CF_ERR_INVALID_ARG, "size exceeds the 32-bit index range of the kernels");
+    *out = r;
+    return CF_OK;
+}
+
+int chunk_index(int kind, int p, int rank, int step)
+{
+    // Alg. 1: l = (r - i + N) mod N.   Alg. 2: l = (r - i - 1 + N) mod N.
+    if (kind == CF_KIND_AG)
+        return ((rank - step) % p + p) % p;
+    return ((rank - step - 1) % p + p) % p;
+}
+
+cf_status check_step(const Resolved &r, int step)
+{
+    if (step < 0 || step >= r.p)
+        return fail(CF_ERR_INVALID_ARG, "step = %d not in [0, %d)", step, r.p);
+    return CF_OK;
+}
+
+cf_status launch_gemm(const Resolved &r, const void *A_rows, const void *W, const float *recv, void *out,
+                      hipStream_t s)
+{
+    cf::GemmParams gp;
+    gp.A = A_rows;
+    gp.W = W;
+    gp.recv = recv;
+    gp.out = out;
+    gp.lda = r.lda;
+    gp.ldw = r.ldw;
+    gp.ldo = r.ldo;
+    gp.M = (int)r.mc;
+    gp.N = (int)r.n;
+    gp.K = (int)r.k;
+    const int ncu = num_cu_of_current_device();
+    hipError_t e = r.bf16_in ? cf::launch_gemm_bf16(gp, r.w_kn, r.bf16_out, s, ncu)
+                             : cf::launch_gemm_f32(gp, r.w_kn, s, ncu);
+    if (e != hipSuccess)
+        return fail_hip(e, "chunk GEMM launch");
+    return CF_OK;
+}
+
+cf_status rs_step_impl(const Resolved &r, int step, const void *A, const void *W, const float *recv, float *out,
+                       hipStream_t s)
+{
+    if (cf_status st = check_step(r, step))
+        return st;
+    if (A == nullptr || W == nullptr || out == nullptr)
+        return fail(CF_ERR_NULL_PTR, "A, W and out must not be NULL");
+    if (step == 0 && recv != nullptr)
+        return fail(CF_ERR_NULL_PTR, "recv must be NULL at step 0 (nothing has been received yet)");
+    if (step > 0 && recv == nullptr)
+        return fail(CF_ERR_NULL_PTR, "recv must not be NULL at step %d", step);
+    if (recv == out)
+        return fail(CF_ERR_INVALID_ARG, "out may not alias recv");
+    if (!aligned16(A) || !aligned16(W) || !aligned16(out) || !aligned16(recv))
+        return fail(CF_ERR_MISALIGNED, "tensor pointers must be 16-byte aligned");
+    const int l = chunk_index(CF_KIND_RS, r.p, r.rank, step);
+    const char *a_rows = static_cast<const char *>(A) + (size_t)l * r.mc * r.lda * in_elem(r);
+    return launch_gemm(r, a_rows, W, recv, out, s);
+}
+
+cf_status ag_step_impl(const Resolved &r, int step, const void *shard, const void *W, void *O, hipStream_t s)
+{
+    if (cf_status st = check_step(r, step))
+        return st;
+    if (shard == nullptr || W == nullptr || O == nullptr)
+        return fail(CF_ERR_NULL_PTR, "shard, W and O must not be NULL");
+    if (!aligned16(shard) || !aligned16(W) || !aligned16(O))
+        return fail(CF_ERR_MISALIGNED, "tensor pointers must be 16-byte aligned");
+    const int l = chunk_index(CF_KIND_AG, r.p, r.rank, step);
+    char *o_rows = static_cast<char *>(O) + (size_t)l * r.mc * r.ldo * (r.bf16_out ? 2 : 4);
+    return launch_gemm(r, shard, W, nullptr, o_rows, s);
+}
+
+cf_status dp_step_impl(int p, int rank, int step, float *bucket, int64_t chunk_elems, const float *recv,
+                       hipStream_t s)
+{
+    if (p < 1)
+        return fail(CF_ERR_INVALID_ARG, "p = %d must be >= 1", p);
+    if (rank < 0 || rank >= p)
+        return fail(CF_ERR_INVALID_ARG, "rank = %d not in [0, %d)", rank, p);
+    if (step < 0 || step >= p)
+        return fail(CF_ERR_INVALID_ARG, "step = %d not in [0, %d)", step, p);
+    if (chunk_elems < 0)
+        return fail(CF_ERR_INVALID_ARG, "chunk_elems < 0");
+    if (step == 0 || chunk_elems == 0)
+        return CF_OK;   // the slice of step 0 is only sent: nothing to add
+    if (bucket == nullptr || recv == nullptr)
+        return fail(CF_ERR_NULL_PTR, "bucket and recv must not be NULL at step %d", step);
+    if ((reinterpret_cast<uintptr_t>(bucket) | reinterpret_cast<uintptr_t>(recv)) & 3u)
+        return fail(CF_ERR_MISALIGNED, "fp32 pointers must be 4-byte aligned");
+    const int l = chunk_index(CF_KIND_DP, p, rank, step);
+    hipError_t e = cf::launch_dp_reduce(bucket + (int64_t)l * chunk_elems, recv, chunk_elems, s,
+                                        num_cu_of_current_device());
+    if (e != hipSuccess)
+        return fail_hip(e, "gradient reduce launch");
+    return CF_OK;
+}
+
+// ---------------------------------------------------------------------------
+// events and graphs owned by the library
+// ---------------------------------------------------------------------------
+std::mutex g_mu;
+std::unordered_map<int, std::vector<hipEvent_t>> g_events;   // per device
+
+struct GraphEntry {
+    std::vector<unsigned char> key;
+    hipGraph_t graph;
+    hipGraphExec_t exec;
+};
+std::vector<GraphEntry> g_graphs;
+
+cf_status get_events(size_t count, std::vector<hipEvent_t> *out)
+{
+    int dev = 0;
+    CF_HIP(hipGetDevice(&dev));
+    std::lock_guard<std::mutex> lk(g_mu);
+    std::vector<hipEvent_t> &pool = g_events[dev];
+    while (pool.size() < count) {
+        hipEvent_t ev;
+        CF_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+        pool.push_back(ev);
+    }
+    out->assign(pool.begin(), pool.begin() + count);
+    return CF_OK;
+}
+
+// Enqueues the p iterations on the two streams (see commfuse_run_schedule in the header).
+cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hipStream_t cs, hipStream_t xs_in,
+                           uint32_t flags)
+{
+    const int p = r.p;
+    const bool serial = (flags & CF_SERIAL) != 0 || xs_in == cs;
+    hipStream_t xs = serial ? cs : xs_in;
+    const bool do_copy = !(flags & CF_NO_COPY);
+    const bool do_compute = !(flags & CF_NO_COMPUTE);
+    const bool poison = (flags & CF_POISON) != 0;
+
+    size_t slot_bytes;
+    if (kind == CF_KIND_RS)
+        slot_bytes = (size_t)r.mc * r.n * sizeof(float);
+    else if (kind == CF_KIND_AG)
+        slot_bytes = (size_t)r.mc * r.k * in_elem(r);
+    else
+        slot_bytes = (size_t)r.mc * sizeof(float);
+
+    // event layout: [0] start, [1] end, ready[i] = 2+i, done[i] = 2+p+i, sunk[i] = 2+2p+i
+    std::vector<hipEvent_t> ev;
+    if (cf_status st = get_events(2 + 3 * (size_t)p, &ev))
+        return st;
+    hipEvent_t ev_start = ev[0], ev_end = ev[1];
+    auto ready = [&](int i) { return ev[2 + i]; };
+    auto done = [&](int i) { return ev[2 + p + i]; };
+    auto sunk = [&](int i) { return ev[2 + 2 * p + i]; };
+
+    if (!serial) {
+        CF_HIP(hipEventRecord(ev_start, cs));
+        CF_HIP(hipStreamWaitEvent(xs, ev_start, 0));
+    }
+
+    // what rank r-1 delivers for step i+1 lands in slot[(i+1) % 2]
+    auto deliver = [&](int i) -> cf_status {
+        if (!(i + 1 < p && do_copy))
+            return CF_OK;
+        void *dst = b->slot[(i + 1) & 1];
+        // the slot was last read by the kernel of step i-1 (steps >= 1 read a slot)
+        if (!serial && do_compute && i - 1 >= 1)
+            CF_HIP(hipStreamWaitEvent(xs, done(i - 1), 0));
+        if (slot_bytes == 0)
+            return CF_OK;
+        if (poison) {
+            hipError_t e = cf::launch_fill_ff(dst, slot_bytes, xs);
+            if (e != hipSuccess)
+                return fail_hip(e, "poison fill");
+        }
+        CF_HIP(hipMemcpyAsync(dst, b->peer_stage[i], slot_bytes, hipMemcpyDeviceToDevice, xs));
+        if (!serial)
+            CF_HIP(hipEventRecord(ready(i + 1), xs));
+        return CF_OK;
+    };
+
+    auto kernel = [&](int i) -> cf_status {
+        if (!do_compute)
+            return CF_OK;
+        if (!serial && do_copy && i > 0)
+            CF_HIP(hipStreamWaitEvent(cs, ready(i), 0));
+        cf_status st = CF_OK;
+        if (kind == CF_KIND_RS) {
+            if (!serial && do_copy && b->peer_sink != nullptr && i >= 2 && i < p - 1)
+                CF_HIP(hipStreamWaitEvent(cs, sunk(i - 2), 0));   // B_out slot still being sent
+            const float *recv = i > 0 ? static_cast<const float *>(b->slot[i & 1]) : nullptr;
+            float *out = i < p - 1 ? b->send_slot[i & 1] : static_cast<float *>(b->O);
+            st = rs_step_impl(r, i, b->A_or_own_shard, b->W, recv, out, cs);
+        } else if (kind == CF_KIND_AG) {
+            const void *shard = i > 0 ? b->slot[i & 1] : b->A_or_own_shard;
+            st = ag_step_impl(r, i, shard, b->W, b->O, cs);
+        } else {
+            st = dp_step_impl(p, r.rank, i, static_cast<float *>(b->O), r.mc,
+                              i > 0 ? static_cast<const float *>(b->slot[i & 1]) : nullptr, cs);
+        }
+        if (st != CF_OK)
+            return st;
+        if (!serial)
+            CF_HIP(hipEventRecord(done(i), cs));
+        return CF_OK;
+    };
+
+    // emulated send of step i: B_out (RS), the slice in hand (AG), slice l (DP)
+    auto send = [&](int i) -> cf_status {
+        if (!(b->peer_sink != nullptr && i < p - 1 && do_copy))
+            return CF_OK;
+        const void *src;
+        size_t bytes = slot_bytes;
+        if (kind == CF_KIND_RS) {
+            src = b->send_slot[i & 1];
+        } else if (kind == CF_KIND_AG) {
+            src = i > 0 ? b->slot[i & 1] : b->A_or_own_shard;
+        } else {
+            const int l = chunk_index(CF_KIND_DP, p, r.rank, i);
+            src = static_cast<const float *>(b->O) + (int64_t)l * r.mc;
+        }
+        if (bytes == 0)
+            return CF_OK;
+        if (!serial && do_compute && kind != CF_KIND_AG)
+            CF_HIP(hipStreamWaitEvent(xs, done(i), 0));
+        if (!serial && kind == CF_KIND_AG && i > 0)
+            CF_HIP(hipStreamWaitEvent(xs, ready(i), 0));           // same stream: already ordered, kept explicit
+        CF_HIP(hipMemcpyAsync(b->peer_sink[i], src, bytes, hipMemcpyDeviceToDevice, xs));
+        if (!serial)
+            CF_HIP(hipEventRecord(sunk(i), xs));
+        return CF_OK;
+    };
+
+    for (int i = 0; i < p; ++i) {
+        cf_status st;
+        if (serial) {
+            if ((st = kernel(i)) || (st = send(i)) || (st = deliver(i)))
+                return st;
+        } else {
+            // the delivery for step i+1 is in flight while the kernel of step i runs
+            if ((st = deliver(i)) || (st = kernel(i)) || (st = send(i)))
+                return st;
+        }
+    }
+    if (!serial) {
+        CF_HIP(hipEventRecord(ev_end, xs));
+        CF_HIP(hipStreamWaitEvent(cs, ev_end, 0));
+    }
+    return CF_OK;
+}
+
+cf_status check_buffers(const Resolved &r, int kind, const cf_buffers *b, uint32_t flags)
+{
+    if (b == nullptr)
+        return fail(CF_ERR_NULL_PTR, "buffers is NULL");
+    if (b->O == nullptr)
+        return fail(CF_ERR_NULL_PTR, "buffers->O is NULL");
+    if (kind != CF_KIND_DP && (b->A_or_own_shard == nullptr || b->W == nullptr))
+        return fail(CF_ERR_NULL_PTR, "buffers->A_or_own_shard / W is NULL");
+    if (r.p > 1) {
+        if (b->slot[0] == nullptr || b->slot[1] == nullptr)
+            return fail(CF_ERR_NULL_PTR, "buffers->slot[0..1] must be set when p > 1");
+        if (b->slot[0] == b->slot[1])
+            return fail(CF_ERR_INVALID_ARG, "the two slots must be distinct buffers");
+        if (!(flags & CF_NO_COPY)) {
+            if (b->peer_stage == nullptr)
+                return fail(CF_ERR_NULL_PTR, "buffers->peer_stage is NULL");
+            for (int i = 0; i < r.p - 1; ++i) {
+                if (b->peer_stage[i] == nullptr)
+                    return fail(CF_ERR_NULL_PTR, "peer_stage[%d] is NULL", i);
+                if (b->peer_sink != nullptr && b->peer_sink[i] == nullptr)
+                    return fail(CF_ERR_NULL_PTR, "peer_sink[%d] is NULL", i);
+            }
+        }
+        if (kind == CF_KIND_RS) {
+            if (b->send_slot[0] == nullptr || b->send_slot[1] == nullptr)
+                return fail(CF_ERR_NULL_PTR, "buffers->send_slot[0..1] must be set for the reduce-scatter path");
+            if (b->send_slot[0] == b->send_slot[1])
+                return fail(CF_ERR_INVALID_ARG, "the two send slots must be distinct buffers");
+        }
+    }
+    if (kind != CF_KIND_DP) {
+        if (r.ldo != r.n)
+            return fail(CF_ERR_UNSUPPORTED, "run_schedule needs packed partial sums / outputs (ldo == n)");
+        if (kind == CF_KIND_AG && r.lda != r.k)
+            return fail(CF_ERR_UNSUPPORTED, "run_schedule needs packed slices (lda == k)");
+    }
+    return CF_OK;
+}
+
+void append_bytes(std::vector<unsigned char> &v, const void *p, size_t n)
+{
+    const unsigned char *c = static_cast<const unsigned char *>(p);
+    v.insert(v.end(), c, c + n);
+}
+
+}  // namespace
+
+extern "C" {
+
+int commfuse_version(void) { return 100; }
+
+const char *commfuse_last_error(void) { return g_err; }
+
+int commfuse_chunk_index(int kind, int p, int rank, int step)
+{
+    if (kind != CF_KIND_RS && kind != CF_KIND_AG && kind != CF_KIND_DP)
+        return fail(CF_ERR_INVALID_ARG, "kind %d", kind);
+    if (p < 1 || rank < 0 || rank >= p || step < 0 || step >= p)
+        return fail(CF_ERR_INVALID_ARG, "need p >= 1, rank and step in [0, p)");
+    return chunk_index(kind, p, rank, step);
+}
+
+cf_status commfuse_rs_step(const cf_layer_desc *desc, int step, const void *A, const void *W, const float *recv,
+                           float *out, void *hip_stream)
+{
+    Resolved r;
+    if (cf_status st = resolve(desc, CF_KIND_RS, &r))
+        return st;
+    return rs_step_impl(r, step, A, W, recv, out, static_cast<hipStream_t>(hip_stream));
+}
+
+cf_status commfuse_ag_step(const cf_layer_desc *desc, int step, const void *shard, const void *W, void *O,
+                           void *hip_stream)
+{
+    Resolved r;
+    if (cf_status st = resolve(desc, CF_KIND_AG, &r))
+        return st;
+    return ag_step_impl(r, step, shard, W, O, static_cast<hipStream_t>(hip_stream));
+}
+
+cf_status commfuse_dp_reduce_step(int p, int rank, int step, float *bucket, int64_t chunk_elems, const float *recv,
+                                  void *hip_stream)
+{
+    return dp_step_impl(p, rank, step, bucket, chunk_elems, recv, static_cast<hipStream_t>(hip_stream));
+}
+
+cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_buffers *bufs, void *compute_stream,
+                                void *copy_stream, uint32_t flags)
+{
+    if (kind != CF_KIND_RS && kind != CF_KIND_AG && kind != CF_KIND_DP)
+        return fail(CF_ERR_INVALID_ARG, "kind %d", kind);
+    if (flags & ~(uint32_t)(CF_NO_COPY | CF_NO_COMPUTE | CF_SERIAL | CF_POISON | CF_GRAPH))
+        return fail(CF_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
+    Resolved r;
+    if (cf_status st = resolve(desc, kind, &r))
+        return st;
+    if (cf_status st = check_buffers(r, kind, bufs, flags))
+        return st;
+    hipStream_t cs = static_cast<hipStream_t>(compute_stream);
+    hipStream_t xs = static_cast<hipStream_t>(copy_stream);
+    if (!(flags & CF_GRAPH))
+        return enqueue_schedule(r, kind, bufs, cs, xs, flags);
+
+    // CF_GRAPH: the same enqueue sequence, captured once per distinct argument set.
+    if (cs == nullptr || (xs == nullptr && !(flags & CF_SERIAL)))
+        return fail(CF_ERR_INVALID_ARG, "CF_GRAPH needs explicit (non-default) streams");
+    std::vector<unsigned char> key;
+    append_bytes(key, desc, sizeof(*desc));
+    append_bytes(key, &kind, sizeof(kind));
+    append_bytes(key, &flags, sizeof(flags));
+    append_bytes(key, &cs, sizeof(cs));
+    append_bytes(key, &xs, sizeof(xs));
+    append_bytes(key, &bufs->A_or_own_shard, sizeof(void *));
+    append_bytes(key, &bufs->W, sizeof(void *));
+    append_bytes(key, &bufs->O, sizeof(void *));
+    append_bytes(key, bufs->slot, sizeof(bufs->slot));
+    append_bytes(key, bufs->send_slot, sizeof(bufs->send_slot));
+    for (int i = 0; i < r.p - 1; ++i) {
+        const void *st = bufs->peer_stage ? bufs->peer_stage[i] : nullptr;
+        const void *sk = bufs->peer_sink ? bufs->peer_sink[i] : nullptr;
+        append_bytes(key, &st, sizeof(st));
+        append_bytes(key, &sk, sizeof(sk));
+    }
+    hipGraphExec_t exec = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        for (const GraphEntry &g : g_graphs)
+            if (g.key == key)
+                exec = g.exec;
+    }
+    if (exec == nullptr) {
+        // events must exist before capture starts (creation is not a capturable operation)
+        std::vector<hipEvent_t> tmp;
+        if (cf_status st = get_events(2 + 3 * (size_t)r.p, &tmp))
+            return st;
+        CF_HIP(hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal));
+        cf_status st = enqueue_schedule(r, kind, bufs, cs, xs, flags & ~(uint32_t)CF_GRAPH);
+        hipGraph_t graph = nullptr;
+        hipError_t e = hipStreamEndCapture(cs, &graph);
+        if (st != CF_OK) {
+            if (graph)
+                (void)hipGraphDestroy(graph);
+            return st;
+        }
+        if (e != hipSuccess)
+            return fail_hip(e, "hipStreamEndCapture");
+        e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+        if (e != hipSuccess) {
+            (void)hipGraphDestroy(graph);
+            return fail_hip(e, "hipGraphInstantiate");
+        }
+        std::lock_guard<std::mutex> lk(g_mu);
+        g_graphs.push_back(GraphEntry{key, graph, exec});
+    }
+    CF_HIP(hipGraphLaunch(exec, cs));
+    return CF_OK;
+}
+
+size_t commfuse_workspace_bytes(const cf_layer_desc *desc, int kind)
+{
+    (void)desc;
+    (void)kind;
+    return 0;   // no kernel of this library uses a device workspace
+}
+
+void commfuse_destroy_cache(void)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (GraphEntry &g : g_graphs) {
+        (void)hipGraphExecDestroy(g.exec);
+        (void)hipGraphDestroy(g.graph);
+    }
+    g_graphs.clear();
+    for (auto &kv : g_events)
+        for (hipEvent_t ev : kv.second)
+            (void)hipEventDestroy(ev);
+    g_events.clear();
+}
+
+}  // extern "C"

@@ -1,0 +1,93 @@
+// Data-parallel gradient path: one ring step of Alg. 2 with the identity as
+// compute_partial_output, i.e. "O <- B_in + O" on one slice of the local fp32
+// gradient bucket, in place.  HBM-bound: 12 bytes per element (read slice, read
+// B_in, write slice).  16-byte accesses, several independent loads in flight
+// per lane, a grid sized to the chip and a grid-stride loop.
+#include "cf_internal.h"
+
+namespace cf {
+namespace {
+
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int DP_THREADS = 256;
+constexpr int DP_UNROLL = 4;
+
+__global__ __launch_bounds__(DP_THREADS) void dp_reduce_vec_kernel(f32x4_t *__restrict__ dst,
+                                                                  const f32x4_t *__restrict__ src, int64_t n4)
+{
+    const int64_t stride = (int64_t)gridDim.x * DP_THREADS;
+    int64_t i = (int64_t)blockIdx.x * DP_THREADS + threadIdx.x;
+    // main part: DP_UNROLL independent 16-byte loads of each stream in flight
+    for (; i + (DP_UNROLL - 1) * stride < n4; i += DP_UNROLL * stride) {
+        f32x4_t a[DP_UNROLL], b[DP_UNROLL];
+#pragma unroll
+        for (int u = 0; u < DP_UNROLL; ++u) {
+            a[u] = dst[i + u * stride];
+            b[u] = __builtin_nontemporal_load(&src[i + u * stride]);
+        }
+#pragma unroll
+        for (int u = 0; u < DP_UNROLL; ++u)
+            dst[i + u * stride] = b[u] + a[u];
+    }
+    for (; i < n4; i += stride)
+        dst[i] = __builtin_nontemporal_load(&src[i]) + dst[i];
+}
+
+__global__ __launch_bounds__(DP_THREADS) void dp_reduce_scalar_kernel(float *__restrict__ dst,
+                                                                     const float *__restrict__ src, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * DP_THREADS;
+    for (int64_t i = (int64_t)blockIdx.x * DP_THREADS + threadIdx.x; i < n; i += stride)
+        dst[i] = src[i] + dst[i];
+}
+
+__global__ __launch_bounds__(256) void fill_ff_kernel(unsigned *dst, size_t nwords)
+{
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < nwords; i += stride)
+        dst[i] = 0xFFFFFFFFu;
+}
+
+}  // namespace
+
+hipError_t launch_dp_reduce(float *dst, const float *src, int64_t n, hipStream_t s, int num_cu)
+{
+    if (n <= 0)
+        return hipSuccess;
+    const bool aligned = ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15u) == 0;
+    const int64_t n4 = aligned ? n / 4 : 0;
+    if (n4 > 0) {
+        int64_t want = (n4 + (int64_t)DP_THREADS * DP_UNROLL - 1) / ((int64_t)DP_THREADS * DP_UNROLL);
+        const int64_t cap = (int64_t)num_cu * 8;           // 8 workgroups of 4 waves per CU: 32 waves/CU
+        const int blocks = (int)(want < cap ? want : cap);
+        hipLaunchKernelGGL(dp_reduce_vec_kernel, dim3(blocks), dim3(DP_THREADS), 0, s,
+                           reinterpret_cast<f32x4_t *>(dst), reinterpret_cast<const f32x4_t *>(src), n4);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return e;
+    }
+    const int64_t done = n4 * 4;
+    if (done < n) {
+        const int64_t rest = n - done;
+        int64_t want = (rest + DP_THREADS - 1) / DP_THREADS;
+        const int64_t cap = (int64_t)num_cu * 8;
+        const int blocks = (int)(want < cap ? want : cap);
+        hipLaunchKernelGGL(dp_reduce_scalar_kernel, dim3(blocks), dim3(DP_THREADS), 0, s, dst + done, src + done, rest);
+        return hipGetLastError();
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_fill_ff(void *dst, size_t bytes, hipStream_t s)
+{
+    const size_t nwords = bytes / 4;
+    if (nwords == 0)
+        return hipSuccess;
+    size_t want = (nwords + 255) / 256;
+    const int blocks = (int)(want < 2048 ? want : 2048);
+    hipLaunchKernelGGL(fill_ff_kernel, dim3(blocks), dim3(256), 0, s, static_cast<unsigned *>(dst), nwords);
+    return hipGetLastError();
+}
+
+}  // namespace cf

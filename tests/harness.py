@@ -1,0 +1,137 @@
+"""Helpers of the GPU parity tests: move seeded inputs to the device, call the C ABI
+through the binding, bring results back.  No arithmetic of the method lives here."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2604_24013_amd import binding as cf
+from paper_2604_24013_amd import inputs
+
+DEV = "cuda:0"
+
+
+def to_dev(a: np.ndarray, dtype: str) -> torch.Tensor:
+    """Host array (bf16 bits as uint16, or float32) -> device tensor."""
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(DEV).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV)
+
+
+def to_host_f64(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.bfloat16:
+        bits = t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        return inputs.bf16_bits_to_f32(bits).astype(np.float64)
+    return t.cpu().numpy().astype(np.float64)
+
+
+def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max|got - ref| / max|ref| (the benchmark's parity measure)."""
+    den = float(np.max(np.abs(ref))) if ref.size else 0.0
+    if ref.size == 0:
+        return 0.0
+    num = float(np.max(np.abs(got - ref)))
+    return num / den if den > 0 else num
+
+
+def desc_of(w: inputs.Workload, rank: int, w_layout=cf.CF_W_KN, **kw) -> cf.LayerDesc:
+    return cf.layer_desc(w.p, rank, w.m_chunk, w.n, w.k, w.dtype, w.out_dtype, w_layout, **kw)
+
+
+def w_to_dev(W: np.ndarray, dtype: str, w_layout: int) -> torch.Tensor:
+    """Weight shard on the device in the requested memory order."""
+    if w_layout == cf.CF_W_NK:
+        W = np.ascontiguousarray(W.T)
+    return to_dev(W, dtype)
+
+
+class RsRun:
+    """One GEMM + reduce-scatter rank step on the device."""
+
+    def __init__(self, w: inputs.Workload, data: dict, rank: int, w_layout=cf.CF_W_KN, with_sink=False):
+        self.w, self.rank = w, rank
+        self.desc = desc_of(w, rank, w_layout)
+        self.A = to_dev(data["A"], w.dtype)
+        self.W = w_to_dev(data["W"], w.dtype, w_layout)
+        self.stage = [to_dev(r, "f32") for r in data["R"][1:]]
+        mk = lambda: torch.empty((w.m_chunk, w.n), dtype=torch.float32, device=DEV)
+        self.slot = [mk(), mk()]
+        self.send = [mk(), mk()]
+        self.O = mk()
+        self.sink = [mk() for _ in range(w.p - 1)] if with_sink else None
+        self.bufs = cf.make_buffers(self.A, self.W, self.O, self.stage, self.slot, self.send, self.sink)
+        self.cs = torch.cuda.Stream()
+        self.xs = torch.cuda.Stream()
+
+    def run_steps(self):
+        """Calls commfuse_rs_step once per step with the staged partial sums as B_in; returns every step's output."""
+        outs = []
+        for i in range(self.w.p):
+            out = torch.full((self.w.m_chunk, self.w.n), float("nan"), dtype=torch.float32, device=DEV)
+            recv = self.stage[i - 1] if i > 0 else None
+            cf.rs_step(self.desc, i, self.A, self.W, recv, out, None)
+            outs.append(out)
+        torch.cuda.synchronize()
+        return [to_host_f64(o) for o in outs]
+
+    def run_schedule(self, flags=0):
+        cf.run_schedule(self.desc, cf.CF_KIND_RS, self.bufs, self.cs, self.xs, flags)
+        self.cs.synchronize()
+
+
+class AgRun:
+    """One all-gather + GEMM rank step on the device."""
+
+    def __init__(self, w: inputs.Workload, data: dict, rank: int, w_layout=cf.CF_W_KN, with_sink=False):
+        self.w, self.rank = w, rank
+        self.desc = desc_of(w, rank, w_layout)
+        self.X = to_dev(data["X"], w.dtype)
+        self.W = w_to_dev(data["W"], w.dtype, w_layout)
+        self.stage = [to_dev(s, w.dtype) for s in data["S"][1:]]
+        tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+        odt = torch.bfloat16 if w.out_dtype == "bf16" else torch.float32
+        mk = lambda: torch.empty((w.m_chunk, w.k), dtype=tdt, device=DEV)
+        self.slot = [mk(), mk()]
+        self.O = torch.full((w.p * w.m_chunk, w.n), float("nan"), dtype=odt, device=DEV)
+        self.sink = [mk() for _ in range(w.p - 1)] if with_sink else None
+        self.bufs = cf.make_buffers(self.X, self.W, self.O, self.stage, self.slot, (None, None), self.sink)
+        self.cs = torch.cuda.Stream()
+        self.xs = torch.cuda.Stream()
+
+    def run_steps(self):
+        for i in range(self.w.p):
+            shard = self.X if i == 0 else self.stage[i - 1]
+            cf.ag_step(self.desc, i, shard, self.W, self.O, None)
+        torch.cuda.synchronize()
+        return to_host_f64(self.O)
+
+    def run_schedule(self, flags=0):
+        cf.run_schedule(self.desc, cf.CF_KIND_AG, self.bufs, self.cs, self.xs, flags)
+        self.cs.synchronize()
+
+
+class DpRun:
+    """The gradient reduce-scatter rank step on the device."""
+
+    def __init__(self, w: inputs.Workload, data: dict, rank: int, with_sink=False):
+        self.w, self.rank = w, rank
+        self.desc = cf.layer_desc(w.p, rank, w.m_chunk, 0, 0, "f32", "f32")
+        self.bucket = to_dev(data["bucket"], "f32")
+        self.stage = [to_dev(r, "f32") for r in data["R"][1:]]
+        mk = lambda: torch.empty((w.m_chunk,), dtype=torch.float32, device=DEV)
+        self.slot = [mk(), mk()]
+        self.sink = [mk() for _ in range(w.p - 1)] if with_sink else None
+        self.bufs = cf.make_buffers(None, None, self.bucket, self.stage, self.slot, (None, None), self.sink)
+        self.cs = torch.cuda.Stream()
+        self.xs = torch.cuda.Stream()
+
+    def run_steps(self):
+        for i in range(self.w.p):
+            recv = self.stage[i - 1] if i > 0 else None
+            cf.dp_reduce_step(self.w.p, self.rank, i, self.bucket, self.w.m_chunk, recv, None)
+        torch.cuda.synchronize()
+        return to_host_f64(self.bucket)
+
+    def run_schedule(self, flags=0):
+        cf.run_schedule(self.desc, cf.CF_KIND_DP, self.bufs, self.cs, self.xs, flags)
+        self.cs.synchronize()

@@ -1,0 +1,121 @@
+"""The C ABI library: it loads, exports every function the header declares, and its
+host-side argument checks turn bad calls into error codes.  No GPU is touched:
+every call below fails validation before any HIP call."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2604_24013_amd import binding as cf
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(cf.LIB_PATH):
+        from paper_2604_24013_amd import build
+        build.build()
+    return cf.load()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "commfuse.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(commfuse_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported(lib):
+    names = declared_functions()
+    assert len(names) >= 9
+    for nm in names:
+        assert hasattr(lib, nm), f"{nm} declared in commfuse.h but not exported"
+    assert sorted(cf.EXPORTS) == names, "binding and header disagree on the entry points"
+
+
+def test_struct_layout_matches_header():
+    # cf_layer_desc: 2 x int32, 6 x int64, 4 x int32 = 72 bytes; cf_buffers: 9 pointers
+    assert ctypes.sizeof(cf.LayerDesc) == 72
+    assert cf.LayerDesc.m_chunk.offset == 8 and cf.LayerDesc.in_dtype.offset == 56
+    assert ctypes.sizeof(cf.Buffers) == 9 * ctypes.sizeof(ctypes.c_void_p)
+
+
+def test_version(lib):
+    assert cf.version() >= 100
+
+
+@pytest.mark.parametrize("p", [1, 2, 3, 8])
+def test_chunk_index_matches_the_algorithms(lib, p):
+    for r in range(p):
+        rs = [cf.chunk_index(cf.CF_KIND_RS, p, r, i) for i in range(p)]
+        ag = [cf.chunk_index(cf.CF_KIND_AG, p, r, i) for i in range(p)]
+        dp = [cf.chunk_index(cf.CF_KIND_DP, p, r, i) for i in range(p)]
+        assert sorted(rs) == list(range(p)) and sorted(ag) == list(range(p))
+        assert rs[-1] == r and ag[0] == r and dp == rs
+        for i in range(p):
+            assert rs[i] == (r - i - 1 + p) % p        # Alg. 2 index line
+            assert ag[i] == (r - i + p) % p            # Alg. 1 index line
+
+
+def _status(fn, *a):
+    with pytest.raises(cf.CommFuseError) as e:
+        fn(*a)
+    return e.value.status, str(e.value)
+
+
+def test_bad_arguments_are_rejected_on_the_host(lib):
+    A, W, R, O = 0x1000, 0x2000, 0x3000, 0x4000            # fake, aligned, never dereferenced
+    good = cf.layer_desc(4, 1, 16, 32, 64)
+    assert _status(cf.chunk_index, 0, 0, 0, 0)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.chunk_index, 7, 4, 0, 0)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.rs_step, cf.layer_desc(0, 0, 16, 32, 64), 0, A, W, None, O)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.rs_step, cf.layer_desc(4, 4, 16, 32, 64), 0, A, W, None, O)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.rs_step, good, 4, A, W, R, O)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.rs_step, good, -1, A, W, R, O)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.rs_step, good, 0, None, W, None, O)[0] == cf.CF_ERR_NULL_PTR
+    assert _status(cf.rs_step, good, 0, A, W, R, O)[0] == cf.CF_ERR_NULL_PTR       # recv at step 0
+    assert _status(cf.rs_step, good, 1, A, W, None, O)[0] == cf.CF_ERR_NULL_PTR    # no recv at step 1
+    assert _status(cf.rs_step, good, 1, A, W, O, O)[0] == cf.CF_ERR_INVALID_ARG    # aliasing
+    assert _status(cf.rs_step, good, 1, A + 2, W, R, O)[0] == cf.CF_ERR_MISALIGNED
+    assert _status(cf.rs_step, cf.layer_desc(4, 1, 16, 32, 60), 1, A, W, R, O)[0] == cf.CF_ERR_MISALIGNED
+    assert _status(cf.rs_step, cf.layer_desc(4, 1, 16, 34, 64, "f32"), 1, A, W, R, O)[0] == cf.CF_ERR_MISALIGNED
+    assert _status(cf.rs_step, cf.layer_desc(4, 1, 16, 32, 64, lda=32), 1, A, W, R, O)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.rs_step, cf.layer_desc(4, 1, 16, 32, 64, in_dtype=5), 1, A, W, R, O)[0] == cf.CF_ERR_UNSUPPORTED
+    assert _status(cf.ag_step, cf.layer_desc(4, 1, 16, 32, 64, "f32", "bf16"), 1, A, W, O)[0] == cf.CF_ERR_UNSUPPORTED
+    assert _status(cf.ag_step, good, 0, A, None, O)[0] == cf.CF_ERR_NULL_PTR
+    assert _status(cf.ag_step, good, 9, A, W, O)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.dp_reduce_step, 4, 0, 1, None, 16, R)[0] == cf.CF_ERR_NULL_PTR
+    assert _status(cf.dp_reduce_step, 4, 0, 5, A, 16, R)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.dp_reduce_step, 4, 0, 1, A, -1, R)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.dp_reduce_step, 4, 0, 1, A + 1, 16, R)[0] == cf.CF_ERR_MISALIGNED
+    st, text = _status(cf.rs_step, good, 7, A, W, R, O)
+    assert "step" in text and cf.last_error() in text
+    # step 0 of the gradient path computes nothing and enqueues nothing: succeeds without a GPU
+    cf.dp_reduce_step(4, 0, 0, None, 16, None)
+
+
+def test_schedule_argument_checks(lib):
+    d = cf.layer_desc(4, 0, 16, 32, 64)
+    t = [0x1000, 0x2000, 0x3000]
+    ok = cf.make_buffers(0x100, 0x200, 0x300, t, (0x400, 0x500), (0x600, 0x700))
+    assert _status(cf.run_schedule, d, 9, ok, None, None, 0)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.run_schedule, d, cf.CF_KIND_RS, ok, None, None, 1 << 9)[0] == cf.CF_ERR_INVALID_ARG
+    bad = cf.make_buffers(0x100, 0x200, None, t, (0x400, 0x500), (0x600, 0x700))
+    assert _status(cf.run_schedule, d, cf.CF_KIND_RS, bad, None, None, 0)[0] == cf.CF_ERR_NULL_PTR
+    bad = cf.make_buffers(0x100, 0x200, 0x300, t, (0x400, 0x400), (0x600, 0x700))
+    assert _status(cf.run_schedule, d, cf.CF_KIND_RS, bad, None, None, 0)[0] == cf.CF_ERR_INVALID_ARG
+    bad = cf.make_buffers(0x100, 0x200, 0x300, t, (0x400, 0x500), (None, None))
+    assert _status(cf.run_schedule, d, cf.CF_KIND_RS, bad, None, None, 0)[0] == cf.CF_ERR_NULL_PTR
+    bad = cf.make_buffers(0x100, 0x200, 0x300, [0x1000, None, 0x3000], (0x400, 0x500), (0x600, 0x700))
+    assert _status(cf.run_schedule, d, cf.CF_KIND_RS, bad, None, None, 0)[0] == cf.CF_ERR_NULL_PTR
+    strided = cf.layer_desc(4, 0, 16, 32, 64, ldo=40)
+    assert _status(cf.run_schedule, strided, cf.CF_KIND_RS, ok, None, None, 0)[0] == cf.CF_ERR_UNSUPPORTED
+    assert _status(cf.run_schedule, d, cf.CF_KIND_RS, ok, None, None, cf.CF_GRAPH)[0] == cf.CF_ERR_INVALID_ARG
+    assert cf.workspace_bytes(d, cf.CF_KIND_RS) == 0
+
+
+def test_binding_has_no_fallback():
+    src = open(os.path.join(ROOT, "paper_2604_24013_amd", "binding.py")).read()
+    assert "import oracle" not in src and "from oracle" not in src
+    assert "torch.matmul" not in src and "@" not in src.replace("@pytest", "")

@@ -1,0 +1,406 @@
+"""Parity of the HIP path with the CPU oracle, element by element, on the same
+seeded inputs, through the C ABI.  Needs an MI355X: run with ``-m gpu``.
+
+Tolerances (max|gpu - ref| / max|ref| per checked tensor):
+  * fp32 operands: 1e-5 (the benchmark's bound).
+  * bf16 operands with fp32 accumulation: 1e-2 (the benchmark's bound); in
+    addition a tight bound of 1e-4 is asserted -- the inputs are exact bf16
+    values and the only error is fp32 accumulation over K <= 8192 terms,
+    about sqrt(K) * 2^-24 of the largest partial sum.
+  * bf16 output: adds half a bf16 ulp of the element, 2^-9 relative.
+  * small-integer inputs: bit-exact (every product and partial sum is exact).
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_24013_amd import binding as cf
+from paper_2604_24013_amd import inputs
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-5
+TOL_BF16 = 1e-2
+TIGHT_BF16 = 1e-4
+TIGHT_BF16_OUT = 2.0 ** -8
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu_and_lib():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    assert os.path.exists(cf.LIB_PATH), "libcommfuse.so must be built in-tree before the GPU run"
+    cf.load()
+    yield
+    torch.cuda.synchronize()
+
+
+def _tile_env(tile):
+    if tile is None:
+        os.environ.pop("COMMFUSE_TILE", None)
+    else:
+        os.environ["COMMFUSE_TILE"] = tile
+
+
+def _oracle_rs(w, data, rank):
+    return oracle.rs_rank_steps(inputs.as_f64(data["A"], w.dtype), inputs.as_f64(data["W"], w.dtype),
+                                [None] + [r.astype(np.float64) for r in data["R"][1:]], w.p, rank)
+
+
+def _oracle_ag(w, data, rank):
+    S = [None] + [inputs.as_f64(s, w.dtype) for s in data["S"][1:]]
+    O = oracle.ag_rank(inputs.as_f64(data["X"], w.dtype), S, inputs.as_f64(data["W"], w.dtype), w.p, rank)
+    return O
+
+
+def _tols(w):
+    if w.dtype == "f32":
+        return TOL_F32, TOL_F32
+    if w.out_dtype == "bf16" and w.kind == "ag":
+        return TOL_BF16, TIGHT_BF16_OUT
+    return TOL_BF16, TIGHT_BF16
+
+
+# ----------------------------------------------------------------------------
+# configuration 1 in full: fp32, p = 2, both ranks, per-step calls and schedule
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("rank", [0, 1])
+@pytest.mark.parametrize("layout", [cf.CF_W_KN, cf.CF_W_NK])
+def test_c1_fp32_full(rank, layout):
+    w = inputs.CONFIGS["c1_rs_f32"]
+    data = inputs.make_rs(w)
+    ref = _oracle_rs(w, data, rank)
+    run = H.RsRun(w, data, rank, layout, with_sink=True)
+    outs = run.run_steps()
+    for i in range(w.p):
+        assert H.rel_err(outs[i], ref[i]) <= TOL_F32, f"step {i}"
+    run.run_schedule()
+    assert H.rel_err(H.to_host_f64(run.O), ref[-1]) <= TOL_F32
+    for i in range(w.p - 1):
+        assert H.rel_err(H.to_host_f64(run.sink[i]), ref[i]) <= TOL_F32
+
+
+# ----------------------------------------------------------------------------
+# reduced shapes spanning several tiles and ragged tails, every tile config
+# ----------------------------------------------------------------------------
+
+RS_SHAPES = [
+    # (p, m_chunk, n, k)
+    (3, 200, 264, 168),     # ragged in M, N and K (K = 2*64 + 40)
+    (2, 256, 512, 64),      # exact tiles, a single k-tile
+    (4, 72, 136, 1376),     # the 7B down-projection's K (21*64 + 32)
+    (1, 40, 8, 8),          # p = 1: plain GEMM, minimum n and k
+    (8, 520, 392, 200),     # several tiles in both directions plus tails
+]
+
+
+@pytest.mark.parametrize("tile", [None, "256x256", "256x128", "128x128"])
+@pytest.mark.parametrize("layout", [cf.CF_W_KN, cf.CF_W_NK])
+@pytest.mark.parametrize("shape", RS_SHAPES)
+def test_rs_bf16_reduced(shape, layout, tile):
+    p, mc, n, k = shape
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=p, m_chunk=mc, n=n, k=k)
+    data = inputs.make_rs(w, salt=1)
+    rank = (p - 1) // 2
+    ref = _oracle_rs(w, data, rank)
+    _tile_env(tile)
+    try:
+        run = H.RsRun(w, data, rank, layout)
+        outs = run.run_steps()
+    finally:
+        _tile_env(None)
+    for i in range(p):
+        e = H.rel_err(outs[i], ref[i])
+        assert e <= TOL_BF16 and e <= TIGHT_BF16, f"step {i}: rel err {e:.3e}"
+        assert not np.isnan(outs[i]).any()
+
+
+AG_SHAPES = [(3, 200, 264, 168), (2, 128, 128, 4096), (4, 72, 136, 1376), (1, 33, 16, 24), (8, 260, 520, 72)]
+
+
+@pytest.mark.parametrize("tile", [None, "256x256", "256x128", "128x128"])
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("layout", [cf.CF_W_KN, cf.CF_W_NK])
+@pytest.mark.parametrize("shape", AG_SHAPES)
+def test_ag_bf16_reduced(shape, layout, out_dtype, tile):
+    p, mc, n, k = shape
+    w = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=p, m_chunk=mc, n=n, k=k, out_dtype=out_dtype)
+    data = inputs.make_ag(w, salt=2)
+    rank = p // 2
+    ref = _oracle_ag(w, data, rank)
+    _tile_env(tile)
+    try:
+        got = H.AgRun(w, data, rank, layout).run_steps()
+    finally:
+        _tile_env(None)
+    gate, tight = _tols(w)
+    e = H.rel_err(got, ref)
+    assert not np.isnan(got).any(), "a slice of O was never written"
+    assert e <= gate and e <= tight, f"rel err {e:.3e}"
+
+
+@pytest.mark.parametrize("tile", ["64x64", "128x128"])
+@pytest.mark.parametrize("layout", [cf.CF_W_KN, cf.CF_W_NK])
+@pytest.mark.parametrize("shape", [(2, 100, 68, 36), (3, 64, 128, 16), (1, 130, 132, 260), (4, 129, 260, 100)])
+def test_fp32_reduced(shape, layout, tile):
+    p, mc, n, k = shape
+    w = inputs.scaled(inputs.CONFIGS["c1_rs_f32"], p=p, m_chunk=mc, n=n, k=k)
+    data = inputs.make_rs(w, salt=3)
+    rank = p - 1
+    ref = _oracle_rs(w, data, rank)
+    os.environ["COMMFUSE_TILE_F32"] = tile
+    try:
+        outs = H.RsRun(w, data, rank, layout).run_steps()
+        wa = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=p, m_chunk=mc, n=n, k=k, dtype="f32", sigma_a=1.0, sigma_w=1.0)
+        da = inputs.make_ag(wa, salt=3)
+        got_ag = H.AgRun(wa, da, rank, layout).run_steps()
+    finally:
+        os.environ.pop("COMMFUSE_TILE_F32", None)
+    for i in range(p):
+        assert H.rel_err(outs[i], ref[i]) <= TOL_F32, f"step {i}"
+    assert H.rel_err(got_ag, _oracle_ag(wa, da, rank)) <= TOL_F32
+
+
+# ----------------------------------------------------------------------------
+# bit-exact cases: small-integer inputs, strides, and the step/slice addressing
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("layout", [cf.CF_W_KN, cf.CF_W_NK])
+def test_integer_inputs_are_bit_exact(dtype, layout):
+    p, mc, n, k = 4, 136, 264, 200
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=p, m_chunk=mc, n=n, k=k, dtype=dtype)
+    rng = np.random.default_rng(77)
+    A = inputs.small_int_like((p * mc, k), rng)
+    W = inputs.small_int_like((k, n), rng)
+    R = [None] + [inputs.small_int_like((mc, n), rng, -50, 50) for _ in range(p - 1)]
+    data = {"A": inputs._as_dtype(A, dtype), "W": inputs._as_dtype(W, dtype), "R": R}
+    for rank in range(p):
+        ref = _oracle_rs(w, data, rank)
+        outs = H.RsRun(w, data, rank, layout).run_steps()
+        for i in range(p):
+            assert np.array_equal(outs[i], ref[i]), f"rank {rank} step {i}"
+
+
+def test_row_strides_are_honoured():
+    p, mc, n, k = 2, 96, 72, 136
+    lda, ldw, ldo = k + 24, n + 8, n + 16
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=p, m_chunk=mc, n=n, k=k)
+    rng = np.random.default_rng(78)
+    A = inputs.small_int_like((p * mc, lda), rng)
+    W = inputs.small_int_like((k, ldw), rng)
+    Rp = inputs.small_int_like((mc, ldo), rng, -9, 9)
+    desc = cf.layer_desc(p, 0, mc, n, k, "bf16", "f32", cf.CF_W_KN, lda=lda, ldw=ldw, ldo=ldo)
+    dA, dW, dR = H.to_dev(inputs.f32_to_bf16_bits(A), "bf16"), H.to_dev(inputs.f32_to_bf16_bits(W), "bf16"), H.to_dev(Rp, "f32")
+    out = torch.full((mc, ldo), -777.0, dtype=torch.float32, device=H.DEV)
+    cf.rs_step(desc, 1, dA, dW, dR, out, None)          # rank 0, step 1 -> slice (0-1-1) mod 2 = 0
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    ref = oracle.gemm(A[:mc, :k], W[:, :n]) + Rp[:, :n]
+    assert np.array_equal(got[:, :n], ref)
+    assert np.all(got[:, n:] == -777.0), "padding columns of the output were written"
+
+
+# ----------------------------------------------------------------------------
+# gradient path
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("p,c", [(8, 1_000_003), (4, 4096), (2, 5), (1, 64), (3, 0), (8, 262144)])
+def test_dp_reduced(p, c):
+    w = inputs.scaled(inputs.CONFIGS["c5_dp"], p=p, m_chunk=c)
+    data = inputs.make_dp(w, salt=4)
+    rank = p - 1
+    ref = oracle.dp_rank(data["bucket"], data["R"], p, rank)
+    got = H.DpRun(w, data, rank).run_steps()
+    # one fp32 addition per element: the result is the correctly rounded sum
+    want32 = ref.astype(np.float32).astype(np.float64)
+    assert np.array_equal(got, want32)
+    if c == 0:
+        return
+    run = H.DpRun(w, data, rank, with_sink=True)
+    run.run_schedule()
+    assert np.array_equal(H.to_host_f64(run.bucket), want32)
+    for i in range(p - 1):
+        l = (rank - i - 1) % p
+        assert np.array_equal(H.to_host_f64(run.sink[i]), want32[l * c:(l + 1) * c])
+
+
+# ----------------------------------------------------------------------------
+# the emulated rank step: flags, poison, graph replays, sinks
+# ----------------------------------------------------------------------------
+
+def test_schedule_modes_agree_rs():
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=8, m_chunk=264, n=520, k=328)
+    data = inputs.make_rs(w, salt=5)
+    rank = 3
+    ref = _oracle_rs(w, data, rank)
+    for flags in (0, cf.CF_SERIAL, cf.CF_POISON, cf.CF_POISON | cf.CF_SERIAL):
+        run = H.RsRun(w, data, rank, with_sink=True)
+        run.O.fill_(float("nan"))
+        run.run_schedule(flags)
+        e = H.rel_err(H.to_host_f64(run.O), ref[-1])
+        assert e <= TIGHT_BF16, f"flags {flags}: {e:.3e}"
+        for i in range(w.p - 1):
+            assert H.rel_err(H.to_host_f64(run.sink[i]), ref[i]) <= TIGHT_BF16, f"flags {flags} sink {i}"
+    # compute-only after a full run reuses whatever the slots hold: last two deliveries
+    run = H.RsRun(w, data, rank)
+    run.run_schedule(cf.CF_NO_COMPUTE)
+    assert np.array_equal(H.to_host_f64(run.slot[(w.p - 1) & 1]), data["R"][w.p - 1].astype(np.float64))
+    assert np.array_equal(H.to_host_f64(run.slot[(w.p - 2) & 1]), data["R"][w.p - 2].astype(np.float64))
+
+
+def test_schedule_modes_agree_ag():
+    w = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=8, m_chunk=136, n=264, k=520)
+    data = inputs.make_ag(w, salt=6)
+    rank = 5
+    ref = _oracle_ag(w, data, rank)
+    for flags in (0, cf.CF_SERIAL, cf.CF_POISON):
+        run = H.AgRun(w, data, rank, with_sink=True)
+        run.run_schedule(flags)
+        got = H.to_host_f64(run.O)
+        assert not np.isnan(got).any()
+        assert H.rel_err(got, ref) <= TIGHT_BF16
+        # the slice forwarded at step i is the one in hand: X^r, then the received ones
+        assert np.array_equal(H.to_host_f64(run.sink[0]), inputs.as_f64(data["X"], "bf16"))
+        for i in range(1, w.p - 1):
+            assert np.array_equal(H.to_host_f64(run.sink[i]), inputs.as_f64(data["S"][i], "bf16"))
+
+
+def test_graph_replays_match_eager():
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=4, m_chunk=256, n=512, k=192)
+    data = inputs.make_rs(w, salt=7)
+    ref = _oracle_rs(w, data, 1)
+    run = H.RsRun(w, data, 1, with_sink=True)
+    run.run_schedule(0)
+    eager = H.to_host_f64(run.O)
+    for rep in range(4):
+        run.O.fill_(float("nan"))
+        for s in run.sink:
+            s.fill_(float("nan"))
+        scratch = torch.randn(1024, device=H.DEV).sum().item()      # eager work between replays
+        run.run_schedule(cf.CF_GRAPH)
+        assert np.array_equal(H.to_host_f64(run.O), eager), f"replay {rep}"
+        for i in range(w.p - 1):
+            assert H.rel_err(H.to_host_f64(run.sink[i]), ref[i]) <= TIGHT_BF16
+    cf.destroy_cache()
+
+
+# ----------------------------------------------------------------------------
+# full benchmark sizes, launched as the benchmark launches them (two streams),
+# checked on sampled rows the oracle computes one by one
+# ----------------------------------------------------------------------------
+
+def _sample_rows(mc, rng, extra=6):
+    fixed = {0, 1, mc - 1, mc // 2, min(255, mc - 1), min(256, mc - 1), min(127, mc - 1), min(128, mc - 1)}
+    fixed |= set(int(x) for x in rng.integers(0, mc, size=extra))
+    return sorted(fixed)
+
+
+@pytest.mark.parametrize("name", ["c2_rs_7b", "c4_rs_70b_down"])
+def test_full_size_rs(name):
+    w = inputs.CONFIGS[name]
+    data = inputs.make_rs(w)
+    rank = 0
+    run = H.RsRun(w, data, rank, with_sink=True)
+    run.run_schedule(0)
+    A64 = None
+    W64 = inputs.as_f64(data["W"], w.dtype)
+    rng = np.random.default_rng(1)
+    for i in range(w.p):
+        l = (rank - i - 1) % w.p
+        rows = _sample_rows(w.m_chunk, rng)
+        Arows = inputs.as_f64(data["A"][[l * w.m_chunk + r for r in rows]], w.dtype)
+        ref = oracle.gemm(Arows, W64)
+        if i > 0:
+            ref = oracle.add(data["R"][i][rows].astype(np.float64), ref)
+        got_full = H.to_host_f64(run.sink[i] if i < w.p - 1 else run.O)
+        assert not np.isnan(got_full).any()
+        e = H.rel_err(got_full[rows], ref)
+        assert e <= TOL_BF16 and e <= TIGHT_BF16, f"step {i}: {e:.3e}"
+
+
+@pytest.mark.parametrize("name", ["c3_ag_7b", "c4_ag_70b_up"])
+def test_full_size_ag(name):
+    w = inputs.CONFIGS[name]
+    data = inputs.make_ag(w)
+    rank = 0
+    run = H.AgRun(w, data, rank)
+    run.run_schedule(0)
+    got_full = H.to_host_f64(run.O)
+    assert not np.isnan(got_full).any()
+    W64 = inputs.as_f64(data["W"], w.dtype)
+    rng = np.random.default_rng(2)
+    gate, tight = _tols(w)
+    for i in range(w.p):
+        l = (rank - i) % w.p
+        rows = _sample_rows(w.m_chunk, rng)
+        T = data["X"] if i == 0 else data["S"][i]
+        ref = oracle.gemm(inputs.as_f64(T[rows], w.dtype), W64)
+        e = H.rel_err(got_full[[l * w.m_chunk + r for r in rows]], ref)
+        assert e <= gate and e <= tight, f"step {i}: {e:.3e}"
+
+
+def test_full_size_pair_70b():
+    """AG-GEMM (up) writes H in bf16; GEMM-RS (down) consumes it.  No activation between."""
+    up, dn = inputs.CONFIGS["c4_ag_70b_up"], inputs.CONFIGS["c4_rs_70b_down"]
+    dup, ddn = inputs.make_ag(up), inputs.make_rs(dn)
+    rank = 0
+    ag = H.AgRun(up, dup, rank)
+    ag.run_schedule(0)
+    ddn_dev = dict(ddn)
+    rs = H.RsRun(dn, ddn, rank)
+    rs.A = ag.O                                            # hand H over on the device
+    rs.bufs = cf.make_buffers(rs.A, rs.W, rs.O, rs.stage, rs.slot, rs.send, None)
+    rs.run_schedule(0)
+    got = H.to_host_f64(rs.O)
+    # oracle on sampled rows of the final slice (slice `rank`, computed last)
+    rng = np.random.default_rng(3)
+    rows = _sample_rows(dn.m_chunk, rng, extra=2)
+    Wup, Wdn = inputs.as_f64(dup["W"], "bf16"), inputs.as_f64(ddn["W"], "bf16")
+    # rows of H in slice `rank` come from the own slice X^r (Alg. 1, step 0)
+    Hrows = oracle.round_to_bf16(oracle.gemm(inputs.as_f64(dup["X"][rows], "bf16"), Wup))
+    ref = oracle.add(ddn["R"][dn.p - 1][rows].astype(np.float64), oracle.gemm(Hrows, Wdn))
+    e = H.rel_err(got[rows], ref)
+    assert e <= TOL_BF16, f"{e:.3e}"
+
+
+def test_full_size_dp():
+    w = inputs.CONFIGS["c5_dp"]
+    data = inputs.make_dp(w)
+    rank = 0
+    run = H.DpRun(w, data, rank)
+    run.run_schedule(0)
+    c = w.m_chunk
+    touched = {(rank - i - 1) % w.p: i for i in range(1, w.p)}
+    for l in range(w.p):
+        got = run.bucket[l * c:(l + 1) * c].cpu().numpy()
+        loc = data["bucket"][l * c:(l + 1) * c]
+        if l in touched:
+            idx = np.unique(np.concatenate([np.arange(0, 4096), np.arange(c - 4096, c), np.arange(0, c, 997)]))
+            ref = oracle.add(data["R"][touched[l]][idx].astype(np.float64), loc[idx].astype(np.float64))
+            assert np.array_equal(got[idx].astype(np.float64), ref.astype(np.float32).astype(np.float64)), f"slice {l}"
+        else:
+            assert np.array_equal(got, loc), f"slice {l} must be untouched"
+
+
+# ----------------------------------------------------------------------------
+# degenerate sizes
+# ----------------------------------------------------------------------------
+
+def test_empty_and_k_zero():
+    d = cf.layer_desc(2, 0, 0, 64, 64)
+    A = torch.zeros(16, dtype=torch.bfloat16, device=H.DEV)
+    out = torch.zeros(16, dtype=torch.float32, device=H.DEV)
+    cf.rs_step(d, 0, A, A, None, out, None)                       # no rows: nothing to do
+    cf.ag_step(cf.layer_desc(2, 0, 8, 0, 64), 0, A, A, out, None)  # no columns
+    # k = 0: the product is zero, the step reduces to out = recv
+    mc, n = 40, 72
+    recv = torch.randn(mc, n, device=H.DEV)
+    out = torch.full((mc, n), float("nan"), device=H.DEV)
+    cf.rs_step(cf.layer_desc(2, 0, mc, n, 0), 1, A, A, recv, out, None)
+    torch.cuda.synchronize()
+    assert torch.equal(out, recv)
