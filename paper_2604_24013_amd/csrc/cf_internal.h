@@ -27,6 +27,9 @@ struct TileChoice {
 TileChoice choose_tile_bf16(int M, int N, int K, int num_cu);
 
 hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, int num_cu);
+// Direct-to-LDS variant of the bf16 kernel (operand extents below 2^31 bytes).
+bool gemm_bf16_dl_supported(const GemmParams &p, bool w_kn);
+hipError_t launch_gemm_bf16_dl(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, TileChoice t);
 hipError_t launch_gemm_f32(const GemmParams &p, bool w_kn, hipStream_t s, int num_cu);
 
 // dst[e] += src[e], e in [0, n)

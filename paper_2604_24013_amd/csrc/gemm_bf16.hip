@@ -23,6 +23,7 @@
 
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 
 namespace cf {
 namespace {
@@ -304,6 +305,11 @@ hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipSt
             t.bn = bn;
         }
     }
+    bool staged = false;                             // "staged": the register-staged kernel of this file
+    if (const char *e = getenv("COMMFUSE_KERNEL"))
+        staged = strcmp(e, "staged") == 0;
+    if (!staged && gemm_bf16_dl_supported(p, w_kn))
+        return launch_gemm_bf16_dl(p, w_kn, out_bf16, s, t);
     if (t.bm == 256 && t.bn == 256) return launch_cfg<256, 256, 2, 4>(p, w_kn, out_bf16, s);
     if (t.bm == 256 && t.bn == 128) return launch_cfg<256, 128, 4, 2>(p, w_kn, out_bf16, s);
     return launch_cfg<128, 128, 2, 2>(p, w_kn, out_bf16, s);
