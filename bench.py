@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the CommFuse rank step on one MI355X.
+
+``python bench.py --gpus 1 --steps K --warmup W`` prints ONE JSON line.
+
+A "step" is one emulated rank step of the Llama-70B-shape MLP pair (p = 8):
+the all-gather + GEMM up-projection (Alg. 1: 8 chunk GEMMs, 7 slice deliveries)
+followed by the GEMM + reduce-scatter down-projection (Alg. 2 / Alg. 3: 8 chunk
+GEMMs with the fused B_in add, 7 partial-sum deliveries), i.e. every row of the
+hot path except the gradient reduce, which is reported next to it
+(``dp_reduce``), as are the two Llama-7B-shape rank steps (``other_configs``).
+All inputs are seeded, synthetic and resident in HBM before the timed region.
+Everything runs on one GPU; ``--gpus N`` with N > 1 is refused.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--skip-dp", action="store_true", help="leave out the 1e9-element gradient bucket")
+    ap.add_argument("--skip-cpu", action="store_true", help="leave out the CPU-oracle baseline")
+    ap.add_argument("--only-pair", action="store_true", help="time the headline workload only")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (peer traffic is emulated in HBM); --gpus must be 1",
+              file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2604_24013_amd import binding as cf
+    from paper_2604_24013_amd import inputs
+    from tests import harness as H
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    cf.load()
+    K, W = args.steps, args.warmup
+
+    def time_calls(fn, stream, steps, warmup):
+        """Average milliseconds of fn() over `steps` back-to-back calls, HIP events on `stream`."""
+        for _ in range(warmup):
+            fn()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(steps):
+            fn()
+        e1.record(stream)
+        e1.synchronize()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    def schedule_times(run, kind, steps, warmup):
+        """Rank-step time overlapped / compute-only / copy-only, best of eager and graph replay."""
+        out = {}
+        for name, fl in (("overlapped", 0), ("compute_only", cf.CF_NO_COPY), ("copy_only", cf.CF_NO_COMPUTE)):
+            best = None
+            for mode, extra in (("streams", 0), ("graph", cf.CF_GRAPH)):
+                t = time_calls(lambda: cf.run_schedule(run.desc, kind, run.bufs, run.cs, run.xs, fl | extra),
+                               run.cs, steps, warmup)
+                if best is None or t < best[0]:
+                    best = (t, mode)
+            out[name] = best
+        return out
+
+    def overlap_eff(t):
+        return max(t["compute_only"][0], t["copy_only"][0]) / t["overlapped"][0]
+
+    results = {}
+
+    # ---------------- headline: 70B MLP pair ----------------
+    up, dn = inputs.CONFIGS["c4_ag_70b_up"], inputs.CONFIGS["c4_rs_70b_down"]
+    log("generating 70B-shape inputs ...")
+    ag = H.AgRun(up, inputs.make_ag(up), 0)
+    ddn = inputs.make_rs(dn)
+    rs = H.RsRun(dn, ddn, 0)
+    rs.A = ag.O                                   # H is handed over on the device, in bf16
+    rs.bufs = cf.make_buffers(rs.A, rs.W, rs.O, rs.stage, rs.slot, rs.send, None)
+    rs.cs, rs.xs = ag.cs, ag.xs                   # one compute stream, one copy stream for the pair
+
+    def pair(flags):
+        cf.run_schedule(ag.desc, cf.CF_KIND_AG, ag.bufs, ag.cs, ag.xs, flags)
+        cf.run_schedule(rs.desc, cf.CF_KIND_RS, rs.bufs, rs.cs, rs.xs, flags)
+
+    pair_t = {}
+    for name, fl in (("overlapped", 0), ("compute_only", cf.CF_NO_COPY), ("copy_only", cf.CF_NO_COMPUTE)):
+        best = None
+        for mode, extra in (("streams", 0), ("graph", cf.CF_GRAPH)):
+            t = time_calls(lambda: pair(fl | extra), ag.cs, K, W)
+            if best is None or t < best[0]:
+                best = (t, mode)
+        pair_t[name] = best
+        log(f"pair {name}: {best[0]*1e3:.1f} us ({best[1]})")
+    flops_pair = up.flops + dn.flops
+    ms_step = pair_t["overlapped"][0]
+    value = flops_pair / (ms_step * 1e-3) / 1e12
+
+    # dominant kernel: the fused down-projection chunk GEMM (B_in add + B_out store), launched alone
+    recv = rs.stage[0]
+    out = rs.send[0]
+    t_kernel = time_calls(lambda: cf.rs_step(rs.desc, 1, rs.A, rs.W, recv, out, ag.cs), ag.cs, max(K, 50), W)
+    flops_kernel = 2.0 * dn.m_chunk * dn.n * dn.k
+    ach = flops_kernel / (t_kernel * 1e-3) / 1e12
+    t_kernel_up = time_calls(lambda: cf.ag_step(ag.desc, 1, ag.stage[0], ag.W, ag.O, ag.cs), ag.cs, max(K, 50), W)
+    roofline = {"bound": "mfma", "kernel": "gemm_bf16_dl_kernel (down-projection chunk GEMM, fused B_in add)",
+                "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "us_per_launch": round(t_kernel * 1e3, 2),
+                "up_projection_kernel_tflops": round(2.0 * up.m_chunk * up.n * up.k / (t_kernel_up * 1e-3) / 1e12, 1)}
+    log(f"chunk GEMM down {t_kernel*1e3:.1f} us = {ach:.0f} TFLOP/s; up {t_kernel_up*1e3:.1f} us")
+    del ag, rs, ddn
+    torch.cuda.empty_cache()
+
+    # ---------------- the two 7B-shape rank steps ----------------
+    others = {}
+    if not args.only_pair:
+        for name, Run, make, kind in (("c2_rs_7b", H.RsRun, inputs.make_rs, cf.CF_KIND_RS),
+                                      ("c3_ag_7b", H.AgRun, inputs.make_ag, cf.CF_KIND_AG)):
+            w = inputs.CONFIGS[name]
+            run = Run(w, make(w), 0)
+            t = schedule_times(run, kind, max(K, 100), W)
+            others[name] = {"tflops": round(w.flops / (t["overlapped"][0] * 1e-3) / 1e12, 1),
+                            "frac_mfma_peak": round(w.flops / (t["overlapped"][0] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                            "us_per_rank_step": round(t["overlapped"][0] * 1e3, 1), "mode": t["overlapped"][1],
+                            "overlap_eff": round(overlap_eff(t), 3),
+                            "us_compute_only": round(t["compute_only"][0] * 1e3, 1),
+                            "us_copy_only": round(t["copy_only"][0] * 1e3, 1)}
+            log(name, others[name])
+            del run
+            torch.cuda.empty_cache()
+
+    # ---------------- gradient reduce-scatter step, 1e9 fp32 elements ----------------
+    dp = None
+    if not (args.skip_dp or args.only_pair):
+        w5 = inputs.CONFIGS["c5_dp"]
+        log("generating the 1e9-element gradient bucket on the host (about half a minute) ...")
+        t0 = time.time()
+        run = H.DpRun(w5, inputs.make_dp(w5), 0)
+        log(f"  done in {time.time()-t0:.0f} s")
+        c = w5.m_chunk
+        t_k = time_calls(lambda: cf.dp_reduce_step(w5.p, 0, 1, run.bucket, c, run.stage[0], run.cs), run.cs, 50, 5)
+        gbs = 12.0 * c / (t_k * 1e-3) / 1e9
+        t = schedule_times(run, cf.CF_KIND_DP, 10, 2)
+        steps_with_add = w5.p - 1
+        dp = {"kernel_GBps": round(gbs, 1), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4),
+              "us_per_reduce_kernel": round(t_k * 1e3, 1), "bytes_per_elem": 12,
+              "rank_step_us": round(t["overlapped"][0] * 1e3, 1), "rank_step_mode": t["overlapped"][1],
+              "rank_step_GBps_algorithmic": round(12.0 * c * steps_with_add / (t["overlapped"][0] * 1e-3) / 1e9, 1),
+              "rank_step_GBps_with_copies": round(20.0 * c * steps_with_add / (t["overlapped"][0] * 1e-3) / 1e9, 1),
+              "overlap_eff": round(overlap_eff(t), 3),
+              "us_compute_only": round(t["compute_only"][0] * 1e3, 1), "us_copy_only": round(t["copy_only"][0] * 1e3, 1)}
+        log("dp", dp)
+        del run
+        torch.cuda.empty_cache()
+
+    # ---------------- CPU oracle on a bounded sample of the headline workload ----------------
+    cpu = None
+    if not args.skip_cpu:
+        import oracle
+        rows = 192
+        dsm = inputs.make_rs(inputs.scaled(dn, p=1, m_chunk=rows))
+        A64, W64 = inputs.as_f64(dsm["A"], "bf16"), inputs.as_f64(dsm["W"], "bf16")
+        oracle.gemm(A64[:8], W64)                                    # page in, spin up threads
+        t0 = time.time()
+        oracle.gemm(A64, W64)
+        dt = time.time() - t0
+        cpu = {"value": round(2.0 * rows * dn.n * dn.k / dt / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "seconds": round(dt, 2),
+               "sample": f"{rows} rows of one down-projection chunk GEMM ({rows}x{dn.n}x{dn.k}, fp64 triple loop)"}
+        log("cpu", cpu)
+
+    line = {
+        "metric": "rank-step TFLOP/s (% bf16 MFMA peak) + overlap efficiency; grad-reduce GB/s",
+        "value": round(value, 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "Llama-70B-shape MLP pair rank step, p=8: AG-GEMM up [8x(1024x8192)]x[8192x3584] -> bf16 H, "
+                               "GEMM-RS down [8x(1024x3584)]x[3584x8192] + fp32 partials; emulated ring on one GPU",
+                   "p": 8, "rank": 0, "mode": pair_t["overlapped"][1]},
+        "frac_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
+        "overlap_eff": round(max(pair_t["compute_only"][0], pair_t["copy_only"][0]) / ms_step, 3),
+        "ms_compute_only": round(pair_t["compute_only"][0], 4), "ms_copy_only": round(pair_t["copy_only"][0], 4),
+        "roofline": roofline, "cpu_baseline": cpu, "dp_reduce": dp, "other_configs": others,
+    }
+    print(json.dumps(line), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -156,8 +156,23 @@ cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_bu
  * until the thread's next failing call. */
 const char *commfuse_last_error(void);
 
-/* Bytes of device workspace the step kernels need for this layer (0: none). */
+/* Split-K workspace.  The per-step grids of the chunk GEMMs (one sequence slice of
+ * Alg. 1 / Alg. 2 at a time) are small against 256 compute units; with a workspace
+ * the bf16 kernels may split the k range of an output tile over several
+ * workgroups, which park fp32 partial tiles there and are summed in a fixed order
+ * by the last one to finish.  Optional: without one every tile is computed by a
+ * single workgroup.
+ *   commfuse_workspace_bytes: size that lets every split choice be used for this
+ *     layer (0 if the kind / dtype never splits).  Host-only arithmetic.
+ *   commfuse_set_workspace: registers a caller-owned DEVICE buffer (16-byte
+ *     aligned) for all later calls on this process, or clears the registration
+ *     (NULL / 0).  Its first 64 KiB are zeroed on `hip_stream` (this is the one
+ *     call that enqueues a memset; do not capture it into a graph).  The caller
+ *     keeps the buffer alive and unmodified while registered.  Steps that
+ *     overlap in time on the GPU must not share a workspace.
+ */
 size_t commfuse_workspace_bytes(const cf_layer_desc *desc, int kind);
+cf_status commfuse_set_workspace(void *device_ptr, size_t bytes, void *hip_stream);
 
 /* Destroys the events and graphs the library created lazily.  Call with no
  * work of this library in flight. */

@@ -26,7 +26,7 @@ DTYPES = {"bf16": CF_BF16, "f32": CF_F32}
 
 EXPORTS = [
     "commfuse_chunk_index", "commfuse_rs_step", "commfuse_ag_step", "commfuse_dp_reduce_step",
-    "commfuse_run_schedule", "commfuse_last_error", "commfuse_workspace_bytes",
+    "commfuse_run_schedule", "commfuse_last_error", "commfuse_workspace_bytes", "commfuse_set_workspace",
     "commfuse_destroy_cache", "commfuse_version",
 ]
 
@@ -84,6 +84,8 @@ def load():
     lib.commfuse_last_error.restype = ctypes.c_char_p
     lib.commfuse_workspace_bytes.argtypes = [ctypes.POINTER(LayerDesc), i32]
     lib.commfuse_workspace_bytes.restype = ctypes.c_size_t
+    lib.commfuse_set_workspace.argtypes = [vp, ctypes.c_size_t, vp]
+    lib.commfuse_set_workspace.restype = i32
     lib.commfuse_destroy_cache.argtypes = []
     lib.commfuse_destroy_cache.restype = None
     lib.commfuse_version.argtypes = []
@@ -181,6 +183,13 @@ def run_schedule(desc: LayerDesc, kind: int, bufs: Buffers, compute_stream, copy
 
 def workspace_bytes(desc: LayerDesc, kind: int) -> int:
     return int(load().commfuse_workspace_bytes(ctypes.byref(desc), kind))
+
+
+def set_workspace(buf, nbytes: int = 0, stream=None) -> None:
+    """Registers (or, with ``None``, clears) the split-K workspace; ``buf`` is a device tensor or pointer."""
+    if buf is not None and not isinstance(buf, int) and nbytes == 0:
+        nbytes = buf.numel() * buf.element_size()
+    _check(load().commfuse_set_workspace(_ptr(buf), nbytes, _stream(stream)))
 
 
 def destroy_cache() -> None:

@@ -15,11 +15,18 @@ struct GemmParams {
     void *out;
     int64_t lda, ldw, ldo;
     int M, N, K;
+    // split-K workspace (direct-to-LDS bf16 kernel only): partial tiles and per-tile arrival counters
+    float *ws = nullptr;
+    unsigned *counters = nullptr;
+    size_t ws_bytes = 0;
+    int max_tiles = 0;
+    int splits = 1;
 };
 
 struct TileChoice {
     int bm, bn;          // workgroup tile
-    int splitk;          // reserved (1)
+    int splitk;          // k-splits per output tile (1 = none)
+    bool deep = false;   // 128x128 only: four LDS stages, one workgroup per CU
 };
 
 // Chooses the workgroup tile for a chunk GEMM from its shape and the number of

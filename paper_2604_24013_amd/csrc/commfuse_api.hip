@@ -56,6 +56,17 @@ int num_cu_of_current_device()
     return cache[dev];
 }
 
+// Caller-owned split-K workspace (commfuse_set_workspace): [0, WS_COUNTER_BYTES) arrival counters,
+// the rest fp32 partial tiles.
+constexpr size_t WS_COUNTER_BYTES = 64 * 1024;
+constexpr int WS_MAX_SPLITS = 8;
+struct Workspace {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+};
+std::mutex g_ws_mu;
+Workspace g_ws;
+
 struct Resolved {      // descriptor with defaults filled in
     int p, rank;
     int64_t mc, n, k, lda, ldw, ldo;
@@ -148,6 +159,15 @@ cf_status launch_gemm(const Resolved &r, const void *A_rows, const void *W, cons
     gp.M = (int)r.mc;
     gp.N = (int)r.n;
     gp.K = (int)r.k;
+    {
+        std::lock_guard<std::mutex> lk(g_ws_mu);
+        if (g_ws.ptr != nullptr && g_ws.bytes > WS_COUNTER_BYTES) {
+            gp.counters = static_cast<unsigned *>(g_ws.ptr);
+            gp.ws = reinterpret_cast<float *>(static_cast<char *>(g_ws.ptr) + WS_COUNTER_BYTES);
+            gp.ws_bytes = g_ws.bytes - WS_COUNTER_BYTES;
+            gp.max_tiles = (int)(WS_COUNTER_BYTES / sizeof(unsigned));
+        }
+    }
     const int ncu = num_cu_of_current_device();
     hipError_t e = r.bf16_in ? cf::launch_gemm_bf16(gp, r.w_kn, r.bf16_out, s, ncu)
                              : cf::launch_gemm_f32(gp, r.w_kn, s, ncu);
@@ -526,9 +546,31 @@ cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_bu
 
 size_t commfuse_workspace_bytes(const cf_layer_desc *desc, int kind)
 {
-    (void)desc;
-    (void)kind;
-    return 0;   // no kernel of this library uses a device workspace
+    Resolved r;
+    if (kind != CF_KIND_RS && kind != CF_KIND_AG)
+        return 0;                                  // the gradient path needs none
+    if (resolve(desc, kind, &r) != CF_OK || !r.bf16_in)
+        return 0;
+    return WS_COUNTER_BYTES + (size_t)WS_MAX_SPLITS * (size_t)r.mc * (size_t)r.n * sizeof(float);
+}
+
+cf_status commfuse_set_workspace(void *device_ptr, size_t bytes, void *hip_stream)
+{
+    if (device_ptr == nullptr || bytes == 0) {
+        std::lock_guard<std::mutex> lk(g_ws_mu);
+        g_ws = Workspace{};
+        return CF_OK;
+    }
+    if (!aligned16(device_ptr))
+        return fail(CF_ERR_MISALIGNED, "workspace must be 16-byte aligned");
+    if (bytes <= WS_COUNTER_BYTES)
+        return fail(CF_ERR_INVALID_ARG, "workspace must exceed %zu bytes", WS_COUNTER_BYTES);
+    // arrival counters start at zero; the kernels leave them at zero
+    CF_HIP(hipMemsetAsync(device_ptr, 0, WS_COUNTER_BYTES, static_cast<hipStream_t>(hip_stream)));
+    std::lock_guard<std::mutex> lk(g_ws_mu);
+    g_ws.ptr = device_ptr;
+    g_ws.bytes = bytes;
+    return CF_OK;
 }
 
 void commfuse_destroy_cache(void)

@@ -305,6 +305,13 @@ hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipSt
             t.bn = bn;
         }
     }
+    if (const char *e = getenv("COMMFUSE_DEEP"))      // tuning override: 128x128 with four LDS stages
+        t.deep = atoi(e) != 0;
+    if (const char *e = getenv("COMMFUSE_SPLITK")) {  // tuning override: k-splits per output tile
+        const int sk = atoi(e);
+        if (sk >= 1 && sk <= 8)
+            t.splitk = sk;
+    }
     bool staged = false;                             // "staged": the register-staged kernel of this file
     if (const char *e = getenv("COMMFUSE_KERNEL"))
         staged = strcmp(e, "staged") == 0;

@@ -5,14 +5,18 @@
 //  * A [k x n] weight tile stays in its natural order in LDS and is read back
 //    with the transposing LDS read (ds_read_b64_tr_b16); a [n x k] weight tile
 //    and the activations are read with plain 16-byte reads.
-//  * k-tiles of 64 (full 128-byte lines of the k-contiguous operands) in two LDS
-//    stages.  A k-tile is consumed in four 16-wide slices; fragments are
-//    double-buffered in registers and the LDS reads of slice s+1 are interleaved
-//    with the MFMAs of slice s.  The one barrier per k-tile sits before the last
-//    slice: by then every wave has read all of the tile, so the other stage's
-//    successor can be requested, and the next tile (requested one barrier
+//  * k-tiles of 64 (full 128-byte lines of the k-contiguous operands) in NS = 2..4
+//    LDS stages (as many as the tile shape leaves room for in 160 KiB).  A k-tile is consumed in four 16-wide slices; fragments are
+//    double-buffered in registers and the LDS reads of slice s+1 are issued under
+//    the first MFMAs of slice s.  The one barrier per k-tile sits before the last
+//    slice: by then every wave has read all of the tile, so the freed stage's
+//    next tile can be requested, and the next tile (requested NS-1 barriers
 //    earlier) is published; its first fragments are fetched under the MFMAs of
 //    the last slice, so the matrix pipe does not drain at tile boundaries.
+//  * The direct loads of a tile are not issued as one burst: each wave issues one
+//    after every few MFMAs.  A burst fills the address queue of the texture unit
+//    and the wave -- which issues in order -- then cannot feed the matrix pipe
+//    until its last load has been accepted.
 //  * Same fused epilogue as the register-staged kernel: Alg. 2 "O <- B_in + O",
 //    "B_out <- O", or Alg. 1's in-place slice store -- here with bounds-checked
 //    buffer loads/stores, so all B_in loads of a row block are in flight at once.
@@ -49,7 +53,6 @@ typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
 
 constexpr int BK = 64;                    // k extent of one LDS stage
-constexpr int NS = 2;                     // LDS stages
 constexpr int KS = BK / 16;               // 16-wide k-slices (one MFMA deep) per stage
 constexpr unsigned OOB = 0x80000000u;     // byte offset beyond any buffer this kernel accepts
 
@@ -127,7 +130,7 @@ __device__ __forceinline__ int xcd_remap(int pid, int total)
     return xcd * q + (xcd < rem ? xcd : rem) + idx;
 }
 
-template <int BM, int BN, int WGM, int WGN, bool W_KN, bool OUT_BF16>
+template <int BM, int BN, int WGM, int WGN, int NS, bool SPREAD, bool W_KN, bool OUT_BF16>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams P, int tiles_m, int tiles_n)
 {
     constexpr int NW = WGM * WGN;
@@ -138,7 +141,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     constexpr int B_LD = (B_BYTES / 1024) / NW;
     constexpr int LPT = A_LD + B_LD;                // direct loads per wave per k-tile
     static_assert(A_LD >= 1 && B_LD >= 1 && (A_BYTES / 1024) % NW == 0 && (B_BYTES / 1024) % NW == 0, "tile vs waves");
-    static_assert(NS * STAGE <= 160 * 1024, "LDS budget");
+    static_assert(NS >= 2 && NS <= 4 && NS * STAGE <= 160 * 1024, "LDS budget");
     static_assert(KS == 4, "the slice schedule below is written for four slices per stage");
     constexpr int W_ROWB = BN * 2;                   // bytes of one k-row of a [k x n] weight tile
 
@@ -149,10 +152,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WGM, wn = wave / WGM;
 
-    const int tile = xcd_remap(blockIdx.x, tiles_m * tiles_n);
+    // Work item = (output tile, k-split); the splits of a tile are neighbours in the remapped order.
+    const int splits = P.splits;
+    const int work = xcd_remap(blockIdx.x, tiles_m * tiles_n * splits);
+    const int tile = work / splits, split = work % splits;
     const int m0 = (tile % tiles_m) * BM;
     const int n0 = (tile / tiles_m) * BN;
     const int M = P.M, N = P.N, K = P.K;
+    const int nk_all = (K + BK - 1) / BK;
+    const int ktb = (int)(((long long)nk_all * split) / splits);          // first k-tile of this split
+    const int nk = (int)(((long long)nk_all * (split + 1)) / splits) - ktb; // its number of k-tiles
 
     // Buffer resources; all byte extents are below 2^31 (host-checked).
     const unsigned a_bytes = (unsigned)(((int64_t)(M - 1) * P.lda + K) * 2);
@@ -193,23 +202,57 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     }
     const int w_kstep = W_KN ? (int)(P.ldw * 2) : 2;   // bytes per unit of k along W
 
-    auto issue_loads = [&](int kt) {
-        const int k0 = kt * BK;
-        const unsigned sa = lds_base + (kt & 1) * STAGE + wave * 1024;
-        const bool tail = (k0 + BK) > K;
-#pragma unroll
-        for (int j = 0; j < A_LD; ++j) {
-            unsigned off = a_off[j];
-            if (tail && (k0 + a_k[j]) >= K)
-                off = OOB;
-            direct_load_16(a_rsrc, off, k0 * 2, sa + j * NW * 1024);
+    // Direct load number `idx` (0 .. LPT-1: the A wave-loads, then the W wave-loads) of local k-tile
+    // kt into `stage`.  A tile beyond the end of this split's k range is requested all the same, with
+    // every lane out of range (it reads zeros and moves no data), so that the number of loads per
+    // tile -- and with it every vmcnt below -- is the same in every iteration.
+    auto issue_load = [&](int kt, int stage, auto idx_tag) {
+        constexpr int idx = decltype(idx_tag)::value;
+        const int k0 = (ktb + kt) * BK;
+        const unsigned sa = lds_base + stage * STAGE + wave * 1024;
+        const bool full = kt < nk && (k0 + BK) <= K;     // uniform: the common case needs no per-lane test
+        if (full) {
+            if constexpr (idx < A_LD)
+                direct_load_16(a_rsrc, a_off[idx], k0 * 2, sa + idx * NW * 1024);
+            else
+                direct_load_16(w_rsrc, b_off[idx - A_LD], k0 * w_kstep, sa + A_BYTES + (idx - A_LD) * NW * 1024);
+        } else {
+            const bool none = kt >= nk;
+            const int klim = none ? -1 : K;              // chunks at k >= klim read as zero
+            const int ks0 = none ? 0 : k0;
+            if constexpr (idx < A_LD) {
+                const unsigned off = (k0 + a_k[idx]) >= klim ? OOB : a_off[idx];
+                direct_load_16(a_rsrc, off, ks0 * 2, sa + idx * NW * 1024);
+            } else {
+                constexpr int j = idx - A_LD;
+                const unsigned off = (k0 + b_k[j]) >= klim ? OOB : b_off[j];
+                direct_load_16(w_rsrc, off, ks0 * w_kstep, sa + A_BYTES + j * NW * 1024);
+            }
         }
+    };
+    auto issue_range = [&](int kt, int stage, auto lo_tag, auto hi_tag) {   // loads [lo, hi) of a tile
+        constexpr int lo = decltype(lo_tag)::value, hi = decltype(hi_tag)::value;
+        static_assert(hi - lo <= 8, "at most eight direct loads per tile and wave");
+        const int k0 = (ktb + kt) * BK;
+        const unsigned sa = lds_base + stage * STAGE + wave * 1024;
+        if (kt < nk && (k0 + BK) <= K) {                 // uniform: the common case, no per-lane test
 #pragma unroll
-        for (int j = 0; j < B_LD; ++j) {
-            unsigned off = b_off[j];
-            if (tail && (k0 + b_k[j]) >= K)
-                off = OOB;
-            direct_load_16(w_rsrc, off, k0 * w_kstep, sa + A_BYTES + j * NW * 1024);
+            for (int idx = lo; idx < hi; ++idx) {
+                if (idx < A_LD)
+                    direct_load_16(a_rsrc, a_off[idx < A_LD ? idx : 0], k0 * 2, sa + idx * NW * 1024);
+                else
+                    direct_load_16(w_rsrc, b_off[idx >= A_LD ? idx - A_LD : 0], k0 * w_kstep,
+                                   sa + A_BYTES + (idx - A_LD) * NW * 1024);
+            }
+        } else {
+            if constexpr (lo + 0 < hi) issue_load(kt, stage, std::integral_constant<int, lo + 0>{});
+            if constexpr (lo + 1 < hi) issue_load(kt, stage, std::integral_constant<int, lo + 1>{});
+            if constexpr (lo + 2 < hi) issue_load(kt, stage, std::integral_constant<int, lo + 2>{});
+            if constexpr (lo + 3 < hi) issue_load(kt, stage, std::integral_constant<int, lo + 3>{});
+            if constexpr (lo + 4 < hi) issue_load(kt, stage, std::integral_constant<int, lo + 4>{});
+            if constexpr (lo + 5 < hi) issue_load(kt, stage, std::integral_constant<int, lo + 5>{});
+            if constexpr (lo + 6 < hi) issue_load(kt, stage, std::integral_constant<int, lo + 6>{});
+            if constexpr (lo + 7 < hi) issue_load(kt, stage, std::integral_constant<int, lo + 7>{});
         }
     };
 
@@ -241,8 +284,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         w_addr[0] = A_BYTES + swz_row(wn * WTN + frow, fkc);
     }
 
-    auto read_frags = [&](int kt, int ks, bf16x8_t (&af)[TM], bf16x8_t (&wf)[TN]) {
-        const unsigned char *st = smem + (kt & 1) * STAGE;
+    auto read_frags = [&](int stage, int ks, bf16x8_t (&af)[TM], bf16x8_t (&wf)[TN]) {
+        const unsigned char *st = smem + stage * STAGE;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
             af[i] = *reinterpret_cast<const bf16x8_t *>(st + (a_addr ^ (ks << 5)) + i * 32 * 128);
@@ -269,56 +312,202 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[j], af[i], acc[i][j], 0, 0, 0);
     };
 
-    // One slice phase: the MFMAs of the fragments in (afc, wfc) with the LDS reads of the next
-    // slice's fragments (into afn, wfn) interleaved, RPM reads after each of the first MFMAs.
+    // One slice phase: the LDS reads of the NEXT slice's fragments (into afn, wfn), then the MFMAs of
+    // the fragments in (afc, wfc) in NSEG segments.  The reads are interleaved with the MFMAs of the
+    // first segment; after each segment one direct load of a later k-tile may be issued (load slots
+    // LO .. LO+NSEG-1 of tile kt_l into stage_l), so that the wave never queues a burst of loads
+    // behind which its MFMAs would wait.
     constexpr int NREAD = TM + (W_KN ? 2 * TN : TN);
     constexpr int NMFMA = TM * TN;
-    auto mfma_only = [&](const bf16x8_t (&afc)[TM], const bf16x8_t (&wfc)[TN]) {
-        mfma_block(afc, wfc);
-        __builtin_amdgcn_sched_barrier(0);
+    constexpr int NSEG = NMFMA < 4 ? NMFMA : 4;
+    constexpr int MPS = NMFMA / NSEG;                       // MFMAs per segment
+    constexpr int LH = LPT < NSEG ? LPT : NSEG;             // loads issued in the first load phase
+    static_assert(NMFMA % NSEG == 0 && LPT - LH <= NSEG, "segmenting");
+    auto mfma_seg = [&](const bf16x8_t (&af)[TM], const bf16x8_t (&wf)[TN], auto seg_tag) {
+        constexpr int seg = decltype(seg_tag)::value;
+#pragma unroll
+        for (int q = seg * MPS; q < (seg + 1) * MPS; ++q)
+            acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[q % TN], af[q / TN], acc[q / TN][q % TN], 0, 0, 0);
     };
-    auto phase = [&](const bf16x8_t (&afc)[TM], const bf16x8_t (&wfc)[TN], int kt_n, int ks_n, bf16x8_t (&afn)[TM],
-                     bf16x8_t (&wfn)[TN], auto rpm_tag) {
-        constexpr int RPM = decltype(rpm_tag)::value;
-        read_frags(kt_n, ks_n, afn, wfn);
-        mfma_block(afc, wfc);
-        interleave_mfma_reads<NREAD, RPM>();
+    auto phase = [&](const bf16x8_t (&afc)[TM], const bf16x8_t (&wfc)[TN], bool do_read, int stage_n, int ks_n,
+                     bf16x8_t (&afn)[TM], bf16x8_t (&wfn)[TN], int kt_l, int stage_l, auto lo_tag, auto n_tag) {
+        constexpr int LO = decltype(lo_tag)::value, NL = decltype(n_tag)::value;   // load slots of this phase
+        if (do_read)
+            read_frags(stage_n, ks_n, afn, wfn);
+        mfma_seg(afc, wfc, std::integral_constant<int, 0>{});
+        interleave_mfma_reads<NREAD, (NREAD + MPS - 1) / MPS>();
         __builtin_amdgcn_sched_barrier(0);
+        if constexpr (NL > 0) issue_load(kt_l, stage_l, std::integral_constant<int, LO>{});
+        if constexpr (NSEG > 1) {
+            mfma_seg(afc, wfc, std::integral_constant<int, 1>{});
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (NL > 1) issue_load(kt_l, stage_l, std::integral_constant<int, LO + 1>{});
+        }
+        if constexpr (NSEG > 2) {
+            mfma_seg(afc, wfc, std::integral_constant<int, 2>{});
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (NL > 2) issue_load(kt_l, stage_l, std::integral_constant<int, LO + 2>{});
+        }
+        if constexpr (NSEG > 3) {
+            mfma_seg(afc, wfc, std::integral_constant<int, 3>{});
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (NL > 3) issue_load(kt_l, stage_l, std::integral_constant<int, LO + 3>{});
+        }
     };
-    constexpr int RPM_N = (NREAD + NMFMA - 1) / NMFMA;      // reads spread over the whole phase
-    using rpm1 = std::integral_constant<int, RPM_N>;
-    using rpm2 = std::integral_constant<int, 2 * RPM_N>;    // reads packed into its first half
+    using c0 = std::integral_constant<int, 0>;
+    using cLH = std::integral_constant<int, LH>;
+    using cLR = std::integral_constant<int, LPT - LH>;
+    using cLPT = std::integral_constant<int, LPT>;
 
-    const int nk = (K + BK - 1) / BK;
     bf16x8_t af0[TM], wf0[TN], af1[TM], wf1[TN];
 
-    // Prologue: tile 0 in stage 0, its first fragments in registers, tile 1 requested.
-    if (nk > 0)
-        issue_loads(0);
-    wait_vmcnt<0>();
-    __syncthreads();
-    if (nk > 0)
+    if constexpr (SPREAD) {
+        // Prologue: tiles 0 .. NS-2 and the first LH loads of tile NS-1 are requested (tile t lives in
+        // stage t mod NS); tile 0 is awaited and its first fragments fetched.
+    #pragma unroll
+        for (int t = 0; t < NS - 1; ++t)
+            issue_range(t, t, c0{}, cLPT{});
+        issue_range(NS - 1, NS - 1, c0{}, cLH{});
+        wait_vmcnt<(NS - 2) * LPT + LH>();
+        __syncthreads();
         read_frags(0, 0, af0, wf0);
-    if (nk > 1)
-        issue_loads(1);
-    __builtin_amdgcn_sched_barrier(0);
-
-    for (int kt = 0; kt + 1 < nk; ++kt) {
-        phase(af0, wf0, kt, 1, af1, wf1, rpm1{});
-        phase(af1, wf1, kt, 2, af0, wf0, rpm1{});
-        phase(af0, wf0, kt, 3, af1, wf1, rpm2{});   // reads early: they must be complete at the barrier
-        wait_vmcnt<0>();             // this wave's part of tile kt+1 has landed
-        __syncthreads();             // every wave has read all of tile kt; tile kt+1 is published
-        if (kt + 2 < nk)
-            issue_loads(kt + 2);     // into the stage tile kt just vacated
         __builtin_amdgcn_sched_barrier(0);
-        phase(af1, wf1, kt + 1, 0, af0, wf0, rpm1{});
+
+        // Steady state, tile kt in stage `cur`:
+        //   slice 0: + the remaining loads of tile kt-1+NS (its first LH went out in the previous slice 3)
+        //   slice 1, slice 2
+        //   wait: tile kt+1 complete, NS-2 later tiles may be in flight; barrier: tile kt is read by all
+        //   slice 3: + the first LH loads of tile kt+NS, into the stage tile kt vacated
+        int cur = 0, prev = NS - 1;                      // stage of tile kt / of tile kt-1 (= of tile kt-1+NS)
+        for (int kt = 0; kt + 1 < nk; ++kt) {
+            const int nxt = (cur + 1 == NS) ? 0 : cur + 1;
+            phase(af0, wf0, true, cur, 1, af1, wf1, kt - 1 + NS, prev, cLH{}, cLR{});
+            phase(af1, wf1, true, cur, 2, af0, wf0, 0, 0, c0{}, c0{});
+            phase(af0, wf0, true, cur, 3, af1, wf1, 0, 0, c0{}, c0{});
+            wait_vmcnt<(NS - 2) * LPT>();
+            __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+            phase(af1, wf1, true, nxt, 0, af0, wf0, kt + NS, cur, c0{}, cLH{});
+            prev = cur;
+            cur = nxt;
+        }
+        if (nk > 0) {                                    // last tile: nothing follows it
+            phase(af0, wf0, true, cur, 1, af1, wf1, 0, 0, c0{}, c0{});
+            phase(af1, wf1, true, cur, 2, af0, wf0, 0, 0, c0{}, c0{});
+            phase(af0, wf0, true, cur, 3, af1, wf1, 0, 0, c0{}, c0{});
+            phase(af1, wf1, false, 0, 0, af0, wf0, 0, 0, c0{}, c0{});
+        }
+
+    } else {
+        // Variant for the small tiles (few MFMAs per slice): a tile's loads go out together right
+        // after the barrier that frees their stage, and the LDS reads of the next slice are
+        // interleaved with all MFMAs of the current one.
+        auto phase_b = [&](const bf16x8_t (&afc)[TM], const bf16x8_t (&wfc)[TN], bool do_read, int stage_n, int ks_n,
+                           bf16x8_t (&afn)[TM], bf16x8_t (&wfn)[TN], auto rpm_tag) {
+            constexpr int RPM = decltype(rpm_tag)::value;
+            if (do_read)
+                read_frags(stage_n, ks_n, afn, wfn);
+#pragma unroll
+            for (int q = 0; q < NMFMA; ++q)
+                acc[q / TN][q % TN] =
+                    __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfc[q % TN], afc[q / TN], acc[q / TN][q % TN], 0, 0, 0);
+            interleave_mfma_reads<NREAD, RPM>();
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        constexpr int RPM_N = (NREAD + NMFMA - 1) / NMFMA;      // reads spread over the whole slice
+        using rpm1 = std::integral_constant<int, RPM_N>;
+        using rpm2 = std::integral_constant<int, 2 * RPM_N>;    // reads packed into its first half
+#pragma unroll
+        for (int t = 0; t < NS; ++t)
+            issue_range(t, t, c0{}, cLPT{});
+        wait_vmcnt<(NS - 1) * LPT>();
+        __syncthreads();
+        read_frags(0, 0, af0, wf0);
+        __builtin_amdgcn_sched_barrier(0);
+        int cur = 0;
+        for (int kt = 0; kt + 1 < nk; ++kt) {
+            const int nxt = (cur + 1 == NS) ? 0 : cur + 1;
+            phase_b(af0, wf0, true, cur, 1, af1, wf1, rpm1{});
+            phase_b(af1, wf1, true, cur, 2, af0, wf0, rpm1{});
+            phase_b(af0, wf0, true, cur, 3, af1, wf1, rpm2{});   // reads early: complete at the barrier
+            wait_vmcnt<(NS - 2) * LPT>();    // tile kt+1 complete, NS-2 later tiles may be in flight
+            __syncthreads();                 // tile kt is read by all, tile kt+1 is published
+            issue_range(kt + NS, cur, c0{}, cLPT{});
+            __builtin_amdgcn_sched_barrier(0);
+            phase_b(af1, wf1, true, nxt, 0, af0, wf0, rpm1{});
+            cur = nxt;
+        }
+        if (nk > 0) {
+            phase_b(af0, wf0, true, cur, 1, af1, wf1, rpm1{});
+            phase_b(af1, wf1, true, cur, 2, af0, wf0, rpm1{});
+            phase_b(af0, wf0, true, cur, 3, af1, wf1, rpm1{});
+            phase_b(af1, wf1, false, 0, 0, af0, wf0, rpm1{});
+        }
     }
-    if (nk > 0) {                    // last tile: nothing follows it
-        phase(af0, wf0, nk - 1, 1, af1, wf1, rpm1{});
-        phase(af1, wf1, nk - 1, 2, af0, wf0, rpm1{});
-        phase(af0, wf0, nk - 1, 3, af1, wf1, rpm1{});
-        mfma_only(af1, wf1);
+    wait_vmcnt<0>();                                 // no direct load may outlive its LDS allocation
+
+    // Split-K: every split parks its fp32 partial tile in the workspace; the split that finishes
+    // last sums all partials in split order (so the result does not depend on which one that is),
+    // then runs the epilogue.  No split ever waits for another.
+    // The chip's eight XCDs have separate L2 caches.  Instead of writing back and invalidating whole
+    // L2s around the hand-over, the partial tiles and the arrival counter are accessed with the
+    // device-coherent cache policy (sc0 sc1: stores write through to memory, loads and the atomic
+    // are served there), which keeps every other line of every L2 in place.
+    if (splits > 1) {
+        constexpr int COHERENT = 1 | 16;         // buffer cache-policy bits sc0 | sc1
+        const size_t plane = (size_t)M * N;
+        __amdgpu_buffer_rsrc_t ws_rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(P.ws + (size_t)split * plane, 0, (int)(plane * 4), 0x00020000);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int m = m0 + wm * WTM + i * 32 + (lane & 31);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = n0 + wn * WTN + j * 32 + g * 8 + (lane >> 5) * 4;
+                    const int boff = (m < M && n < N) ? (int)(((unsigned)m * (unsigned)N + n) * 4u) : (int)OOB;
+                    f32x4_t o;
+                    o[0] = acc[i][j][4 * g + 0];
+                    o[1] = acc[i][j][4 * g + 1];
+                    o[2] = acc[i][j][4 * g + 2];
+                    o[3] = acc[i][j][4 * g + 3];
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, o), ws_rsrc, boff, 0, COHERENT);
+                }
+        }
+        __builtin_amdgcn_s_waitcnt(0);           // this wave's partial stores are acknowledged
+        __syncthreads();                         // ... and every wave's
+        __shared__ unsigned arrived;
+        if (tid == 0)
+            arrived = __hip_atomic_fetch_add(&P.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (arrived != (unsigned)(splits - 1))
+            return;                              // not the last to finish: done
+        if (tid == 0)                            // leave the counter ready for the next launch
+            __hip_atomic_store(&P.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int m = m0 + wm * WTM + i * 32 + (lane & 31);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = n0 + wn * WTN + j * 32 + g * 8 + (lane >> 5) * 4;
+                    const int boff = (m < M && n < N) ? (int)(((unsigned)m * (unsigned)N + n) * 4u) : (int)OOB;
+                    f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
+                    for (int sp = 0; sp < splits; ++sp) {
+                        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+                            P.ws + (size_t)sp * plane, 0, (int)(plane * 4), 0x00020000);
+                        const f32x4_t v =
+                            __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rs, boff, 0, COHERENT));
+                        sum = sp == 0 ? v : sum + v;
+                    }
+                    acc[i][j][4 * g + 0] = sum[0];
+                    acc[i][j][4 * g + 1] = sum[1];
+                    acc[i][j][4 * g + 2] = sum[2];
+                    acc[i][j][4 * g + 3] = sum[3];
+                }
+        }
     }
 
     // Epilogue.  Accumulator register 4g+e of lane L holds row (L & 31), column 8g + 4(L >> 5) + e
@@ -377,21 +566,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     }
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int NS, bool SPREAD>
 hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s)
 {
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    const dim3 grid(tiles_m * tiles_n), block(64 * WGM * WGN);
+    const dim3 grid(tiles_m * tiles_n * p.splits), block(64 * WGM * WGN);
     if (w_kn) {
         if (out_bf16)
-            hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, true, true>), grid, block, 0, s, p, tiles_m, tiles_n);
+            hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, true>), grid, block, 0, s, p, tiles_m, tiles_n);
         else
-            hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, true, false>), grid, block, 0, s, p, tiles_m, tiles_n);
+            hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, false>), grid, block, 0, s, p, tiles_m, tiles_n);
     } else {
         if (out_bf16)
-            hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
+            hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
         else
-            hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, false, false>), grid, block, 0, s, p, tiles_m, tiles_n);
+            hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, false, false>), grid, block, 0, s, p, tiles_m, tiles_n);
     }
     return hipGetLastError();
 }
@@ -408,11 +597,24 @@ bool gemm_bf16_dl_supported(const GemmParams &p, bool w_kn)
     return p.M > 0 && p.N > 0 && p.K > 0 && a_bytes < lim && w_bytes < lim && o_bytes < lim;
 }
 
-hipError_t launch_gemm_bf16_dl(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, TileChoice t)
+hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16, hipStream_t s, TileChoice t)
 {
-    if (t.bm == 256 && t.bn == 256) return launch_cfg<256, 256, 2, 4>(p, w_kn, out_bf16, s);
-    if (t.bm == 256 && t.bn == 128) return launch_cfg<256, 128, 4, 2>(p, w_kn, out_bf16, s);
-    return launch_cfg<128, 128, 2, 2>(p, w_kn, out_bf16, s);
+    GemmParams p = p_in;
+    p.splits = t.splitk < 1 ? 1 : t.splitk;
+    const int nk_all = (p.K + BK - 1) / BK;
+    if (p.splits > nk_all)
+        p.splits = nk_all;
+    const int64_t tiles = (int64_t)((p.M + t.bm - 1) / t.bm) * ((p.N + t.bn - 1) / t.bn);
+    if (p.splits > 1 && (p.ws == nullptr || p.counters == nullptr ||
+                         (size_t)p.splits * p.M * p.N * sizeof(float) > p.ws_bytes || tiles > p.max_tiles ||
+                         (int64_t)p.M * p.N * 4 >= ((int64_t)1 << 31)))
+        p.splits = 1;                          // no (or too small a) workspace: plain kernel
+    // LDS stages: as many as fit (160 KiB per CU); the 128x128 tile comes with two stages (two
+    // workgroups share a CU) or four (one workgroup per CU, tiles requested three ahead).
+    if (t.bm == 256 && t.bn == 256) return launch_cfg<256, 256, 2, 4, 2, true>(p, w_kn, out_bf16, s);
+    if (t.bm == 256 && t.bn == 128) return launch_cfg<256, 128, 4, 2, 3, false>(p, w_kn, out_bf16, s);
+    if (t.deep) return launch_cfg<128, 128, 2, 2, 4, false>(p, w_kn, out_bf16, s);
+    return launch_cfg<128, 128, 2, 2, 2, false>(p, w_kn, out_bf16, s);
 }
 
 }  // namespace cf

@@ -119,6 +119,39 @@ def test_rs_bf16_reduced(shape, layout, tile):
         assert not np.isnan(outs[i]).any()
 
 
+@pytest.mark.parametrize("splitk", [2, 3, 8])
+@pytest.mark.parametrize("tile", ["256x256", "128x128"])
+@pytest.mark.parametrize("layout", [cf.CF_W_KN, cf.CF_W_NK])
+def test_split_k_reduced(layout, tile, splitk):
+    """k range of every output tile split over several workgroups (workspace registered)."""
+    p, mc, n, k = 3, 200, 264, 1000          # 16 k-tiles of 64 (the last one ragged)
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=p, m_chunk=mc, n=n, k=k)
+    data = inputs.make_rs(w, salt=8)
+    ref = _oracle_rs(w, data, 1)
+    wa = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=p, m_chunk=mc, n=n, k=k, out_dtype="bf16")
+    da = inputs.make_ag(wa, salt=8)
+    refa = _oracle_ag(wa, da, 1)
+    ws = torch.empty(cf.workspace_bytes(H.desc_of(w, 1), cf.CF_KIND_RS), dtype=torch.uint8, device=H.DEV)
+    cf.set_workspace(ws)
+    torch.cuda.synchronize()
+    _tile_env(tile)
+    os.environ["COMMFUSE_SPLITK"] = str(splitk)
+    try:
+        outs = H.RsRun(w, data, 1, layout).run_steps()
+        outs2 = H.RsRun(w, data, 1, layout).run_steps()      # counters must be back at zero
+        got_ag = H.AgRun(wa, da, 1, layout).run_steps()
+    finally:
+        _tile_env(None)
+        os.environ.pop("COMMFUSE_SPLITK", None)
+        torch.cuda.synchronize()
+        cf.set_workspace(None)
+    for i in range(p):
+        e = H.rel_err(outs[i], ref[i])
+        assert e <= TIGHT_BF16, f"step {i}: rel err {e:.3e}"
+        assert np.array_equal(outs[i], outs2[i]), "split-K result must not depend on arrival order"
+    assert H.rel_err(got_ag, refa) <= TIGHT_BF16_OUT
+
+
 AG_SHAPES = [(3, 200, 264, 168), (2, 128, 128, 4096), (4, 72, 136, 1376), (1, 33, 16, 24), (8, 260, 520, 72)]
 
 
