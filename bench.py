@@ -89,7 +89,12 @@ def main() -> int:
     def overlap_eff(t):
         return max(t["compute_only"][0], t["copy_only"][0]) / t["overlapped"][0]
 
-    results = {}
+    # split-K workspace for the layers whose per-step grids are small (sized for the largest layer here)
+    ws_bytes = max(cf.workspace_bytes(H.desc_of(inputs.CONFIGS[n], 0), cf.CF_KIND_AG if inputs.CONFIGS[n].kind == "ag" else cf.CF_KIND_RS)
+                   for n in ("c2_rs_7b", "c3_ag_7b", "c4_ag_70b_up", "c4_rs_70b_down"))
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=H.DEV)
+    cf.set_workspace(workspace, ws_bytes)
+    torch.cuda.synchronize()
 
     # ---------------- headline: 70B MLP pair ----------------
     up, dn = inputs.CONFIGS["c4_ag_70b_up"], inputs.CONFIGS["c4_rs_70b_down"]

@@ -2,7 +2,7 @@
 // compute_partial_output, i.e. "O <- B_in + O" on one slice of the local fp32
 // gradient bucket, in place.  HBM-bound: 12 bytes per element (read slice, read
 // B_in, write slice).  16-byte accesses, several independent loads in flight
-// per lane, a grid sized to the chip and a grid-stride loop.
+// per lane, one pass over the slice.
 #include "cf_internal.h"
 
 namespace cf {
@@ -16,22 +16,23 @@ constexpr int DP_UNROLL = 4;
 __global__ __launch_bounds__(DP_THREADS) void dp_reduce_vec_kernel(f32x4_t *__restrict__ dst,
                                                                   const f32x4_t *__restrict__ src, int64_t n4)
 {
+    // Every element is touched exactly once: all three streams bypass the caches' retention
+    // (non-temporal), which measured ~25% faster than cached accesses on MI355X.
     const int64_t stride = (int64_t)gridDim.x * DP_THREADS;
     int64_t i = (int64_t)blockIdx.x * DP_THREADS + threadIdx.x;
-    // main part: DP_UNROLL independent 16-byte loads of each stream in flight
     for (; i + (DP_UNROLL - 1) * stride < n4; i += DP_UNROLL * stride) {
         f32x4_t a[DP_UNROLL], b[DP_UNROLL];
 #pragma unroll
         for (int u = 0; u < DP_UNROLL; ++u) {
-            a[u] = dst[i + u * stride];
+            a[u] = __builtin_nontemporal_load(&dst[i + u * stride]);
             b[u] = __builtin_nontemporal_load(&src[i + u * stride]);
         }
 #pragma unroll
         for (int u = 0; u < DP_UNROLL; ++u)
-            dst[i + u * stride] = b[u] + a[u];
+            __builtin_nontemporal_store(b[u] + a[u], &dst[i + u * stride]);   // "O <- B_in + O"
     }
     for (; i < n4; i += stride)
-        dst[i] = __builtin_nontemporal_load(&src[i]) + dst[i];
+        __builtin_nontemporal_store(__builtin_nontemporal_load(&src[i]) + __builtin_nontemporal_load(&dst[i]), &dst[i]);
 }
 
 __global__ __launch_bounds__(DP_THREADS) void dp_reduce_scalar_kernel(float *__restrict__ dst,
@@ -58,8 +59,11 @@ hipError_t launch_dp_reduce(float *dst, const float *src, int64_t n, hipStream_t
     const bool aligned = ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15u) == 0;
     const int64_t n4 = aligned ? n / 4 : 0;
     if (n4 > 0) {
+        // one workgroup per DP_THREADS * DP_UNROLL vectors: a grid that covers the slice once measured
+        // faster than a grid-stride loop over a chip-sized grid (5.9 vs 4.4 TB/s at 125M elements)
         int64_t want = (n4 + (int64_t)DP_THREADS * DP_UNROLL - 1) / ((int64_t)DP_THREADS * DP_UNROLL);
-        const int64_t cap = (int64_t)num_cu * 8;           // 8 workgroups of 4 waves per CU: 32 waves/CU
+        const int64_t cap = (int64_t)1 << 30;
+        (void)num_cu;
         const int blocks = (int)(want < cap ? want : cap);
         hipLaunchKernelGGL(dp_reduce_vec_kernel, dim3(blocks), dim3(DP_THREADS), 0, s,
                            reinterpret_cast<f32x4_t *>(dst), reinterpret_cast<const f32x4_t *>(src), n4);

@@ -285,12 +285,24 @@ hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t
 
 TileChoice choose_tile_bf16(int M, int N, int K, int num_cu)
 {
-    (void)K;
+    // Measured on MI355X: the kernels are bound by the rate at which a CU can pull operand tiles
+    // through its L1 (64 B/clk), so the largest tile that still fills the chip wins; a grid of at
+    // most one 128x128 workgroup per CU runs best with four LDS stages, and when even that leaves
+    // most CUs idle the k range is split (if the caller registered a workspace).
     auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
-    const int want = (num_cu * 7) / 8;          // a grid that fills most of the chip
-    if (tiles(256, 256) >= want) return {256, 256, 1};
-    if (tiles(256, 128) >= want) return {256, 128, 1};
-    return {128, 128, 1};
+    const int want = (num_cu * 7) / 8;
+    TileChoice t{128, 128, 1};
+    if (tiles(256, 256) >= want) return TileChoice{256, 256, 1};
+    if (tiles(256, 128) >= want) return TileChoice{256, 128, 1};
+    const int t128 = tiles(128, 128);
+    if (t128 > num_cu) return t;                 // two workgroups per CU, two stages each
+    t.deep = true;
+    const int ktiles = (K + 63) / 64;
+    if (t128 * 3 <= num_cu && ktiles / 3 >= 16)
+        t.splitk = 3;
+    else if (t128 * 2 <= num_cu && ktiles / 2 >= 16)
+        t.splitk = 2;
+    return t;
 }
 
 hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, int num_cu)

@@ -135,3 +135,22 @@ class DpRun:
     def run_schedule(self, flags=0):
         cf.run_schedule(self.desc, cf.CF_KIND_DP, self.bufs, self.cs, self.xs, flags)
         self.cs.synchronize()
+
+
+class Workspace:
+    """Registers a split-K workspace sized for a layer for the duration of a ``with`` block."""
+
+    def __init__(self, desc: cf.LayerDesc, kind: int):
+        self.nbytes = cf.workspace_bytes(desc, kind)
+        self.buf = torch.empty(max(self.nbytes, 16), dtype=torch.uint8, device=DEV) if self.nbytes else None
+
+    def __enter__(self):
+        if self.buf is not None:
+            cf.set_workspace(self.buf, self.nbytes)
+            torch.cuda.synchronize()
+        return self
+
+    def __exit__(self, *exc):
+        torch.cuda.synchronize()
+        cf.set_workspace(None)
+        return False
