@@ -40,6 +40,8 @@ def main() -> int:
     ap.add_argument("--skip-dp", action="store_true", help="leave out the 1e9-element gradient bucket")
     ap.add_argument("--skip-cpu", action="store_true", help="leave out the CPU-oracle baseline")
     ap.add_argument("--only-pair", action="store_true", help="time the headline workload only")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (known bytes, for scaling hardware counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (peer traffic is emulated in HBM); --gpus must be 1",
@@ -78,13 +80,18 @@ def main() -> int:
         out = {}
         for name, fl in (("overlapped", 0), ("compute_only", cf.CF_NO_COPY), ("copy_only", cf.CF_NO_COMPUTE)):
             best = None
-            for mode, extra in (("streams", 0), ("graph", cf.CF_GRAPH)):
+            for mode, extra in MODES if (fl == 0 and kind != cf.CF_KIND_DP) else MODES[:2]:
                 t = time_calls(lambda: cf.run_schedule(run.desc, kind, run.bufs, run.cs, run.xs, fl | extra),
                                run.cs, steps, warmup)
                 if best is None or t < best[0]:
                     best = (t, mode)
             out[name] = best
         return out
+
+    # how the emulated deliveries are enqueued: hipMemcpyAsync on the copy stream ordered by events
+    # (eager or as a captured graph), or carried by extra workgroups of the step kernels (one stream)
+    MODES = (("streams", 0), ("graph", cf.CF_GRAPH), ("fused-copy", cf.CF_FUSED_COPY),
+             ("fused-copy+graph", cf.CF_FUSED_COPY | cf.CF_GRAPH))
 
     def overlap_eff(t):
         return max(t["compute_only"][0], t["copy_only"][0]) / t["overlapped"][0]
@@ -113,8 +120,9 @@ def main() -> int:
     pair_t = {}
     for name, fl in (("overlapped", 0), ("compute_only", cf.CF_NO_COPY), ("copy_only", cf.CF_NO_COMPUTE)):
         best = None
-        for mode, extra in (("streams", 0), ("graph", cf.CF_GRAPH)):
+        for mode, extra in MODES if fl == 0 else MODES[:2]:
             t = time_calls(lambda: pair(fl | extra), ag.cs, K, W)
+            log(f"  pair {name} [{mode}]: {t*1e3:.1f} us")
             if best is None or t < best[0]:
                 best = (t, mode)
         pair_t[name] = best
@@ -132,7 +140,10 @@ def main() -> int:
     t_kernel_up = time_calls(lambda: cf.ag_step(ag.desc, 1, ag.stage[0], ag.W, ag.O, ag.cs), ag.cs, max(K, 50), W)
     roofline = {"bound": "mfma", "kernel": "gemm_bf16_dl_kernel (down-projection chunk GEMM, fused B_in add)",
                 "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                # HBM bytes per launch from rocprofv3 counters (profiles/gemm_bf16_dl_kernel_70b_pair_counters.md):
+                # FETCH_SIZE x 2.00 (scale from a plain 256 MiB copy) + WRITE_SIZE; algorithmic bytes are 133.2e6
+                "traffic": 182.2e6, "algorithmic_bytes": 133.2e6,
                 "us_per_launch": round(t_kernel * 1e3, 2),
                 "up_projection_kernel_tflops": round(2.0 * up.m_chunk * up.n * up.k / (t_kernel_up * 1e-3) / 1e12, 1)}
     log(f"chunk GEMM down {t_kernel*1e3:.1f} us = {ach:.0f} TFLOP/s; up {t_kernel_up*1e3:.1f} us")
@@ -185,17 +196,26 @@ def main() -> int:
     cpu = None
     if not args.skip_cpu:
         import oracle
-        rows = 192
+        nch = 2                                                      # chunk GEMMs of the down-projection
+        rows = nch * dn.m_chunk
         dsm = inputs.make_rs(inputs.scaled(dn, p=1, m_chunk=rows))
         A64, W64 = inputs.as_f64(dsm["A"], "bf16"), inputs.as_f64(dsm["W"], "bf16")
-        oracle.gemm(A64[:8], W64)                                    # page in, spin up threads
+        oracle.gemm(A64[:64], W64)                                   # page in, spin up threads
         t0 = time.time()
         oracle.gemm(A64, W64)
         dt = time.time() - t0
         cpu = {"value": round(2.0 * rows * dn.n * dn.k / dt / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.num_threads(),
                "kind": "oracle", "seconds": round(dt, 2),
-               "sample": f"{rows} rows of one down-projection chunk GEMM ({rows}x{dn.n}x{dn.k}, fp64 triple loop)"}
+               "sample": f"{nch} of the 16 chunk GEMMs of the headline rank step (down-projection, "
+                         f"{rows}x{dn.n}x{dn.k}, fp64 triple loop)"}
         log("cpu", cpu)
+
+    if args.calibration_copy:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device=H.DEV)
+        b = torch.empty(256 << 20, dtype=torch.uint8, device=H.DEV)
+        a.fill_(1)
+        b.copy_(a)                                                   # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
 
     line = {
         "metric": "rank-step TFLOP/s (% bf16 MFMA peak) + overlap efficiency; grad-reduce GB/s",

@@ -137,7 +137,11 @@ enum {
     CF_NO_COMPUTE = 2u,  /* enqueue the copies only                                    */
     CF_SERIAL = 4u,      /* one stream, copy i+1 strictly after kernel i: no overlap   */
     CF_POISON = 8u,      /* debug: fill each B_in slot with NaN bytes before its copy  */
-    CF_GRAPH = 16u       /* capture the schedule once into a HIP graph, replay after   */
+    CF_GRAPH = 16u,      /* capture the schedule once into a HIP graph, replay after   */
+    CF_FUSED_COPY = 32u  /* bf16 RS / AG only: the delivery for step i+1 is carried by
+                            extra workgroups of step i's kernel launch instead of a
+                            hipMemcpyAsync on copy_stream: one stream, no events
+                            (copy_stream is unused; not with CF_POISON)               */
 };
 
 /* A whole rank step: the p iterations of Alg. 1 (CF_KIND_AG) or Alg. 2

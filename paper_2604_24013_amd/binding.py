@@ -19,7 +19,7 @@ CF_ERR_INVALID_ARG, CF_ERR_NULL_PTR, CF_ERR_UNSUPPORTED, CF_ERR_MISALIGNED, CF_E
 CF_BF16, CF_F32 = 0, 1
 CF_KIND_RS, CF_KIND_AG, CF_KIND_DP = 0, 1, 2
 CF_W_KN, CF_W_NK = 0, 1
-CF_NO_COPY, CF_NO_COMPUTE, CF_SERIAL, CF_POISON, CF_GRAPH = 1, 2, 4, 8, 16
+CF_NO_COPY, CF_NO_COMPUTE, CF_SERIAL, CF_POISON, CF_GRAPH, CF_FUSED_COPY = 1, 2, 4, 8, 16, 32
 
 KINDS = {"rs": CF_KIND_RS, "ag": CF_KIND_AG, "dp": CF_KIND_DP}
 DTYPES = {"bf16": CF_BF16, "f32": CF_F32}

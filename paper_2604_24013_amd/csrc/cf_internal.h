@@ -21,6 +21,12 @@ struct GemmParams {
     size_t ws_bytes = 0;
     int max_tiles = 0;
     int splits = 1;
+    // optional delivery carried by extra workgroups of the same launch (direct-to-LDS bf16 kernel only):
+    // cp_bytes (a multiple of 16) from cp_src to cp_dst, both 16-byte aligned, by cp_wgs workgroups
+    const void *cp_src = nullptr;
+    void *cp_dst = nullptr;
+    size_t cp_bytes = 0;
+    int cp_wgs = 0;
 };
 
 struct TileChoice {

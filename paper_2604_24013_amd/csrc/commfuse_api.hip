@@ -145,8 +145,24 @@ cf_status check_step(const Resolved &r, int step)
     return CF_OK;
 }
 
+// A delivery to be carried by extra workgroups of a step's launch (CF_FUSED_COPY).
+struct CopyJob {
+    const void *src = nullptr;
+    void *dst = nullptr;
+    size_t bytes = 0;
+};
+
+// True if a step of this layer runs the kernel that can carry a delivery (direct-to-LDS bf16 kernel).
+bool step_can_carry_copy(const Resolved &r)
+{
+    if (!r.bf16_in || r.mc <= 0 || r.n <= 0 || r.k <= 0)
+        return false;
+    const int64_t lim = (int64_t)1 << 31;
+    return r.mc * r.lda * 2 < lim && (r.w_kn ? r.k : r.n) * r.ldw * 2 < lim && r.mc * r.ldo * 4 < lim;
+}
+
 cf_status launch_gemm(const Resolved &r, const void *A_rows, const void *W, const float *recv, void *out,
-                      hipStream_t s)
+                      hipStream_t s, const CopyJob *job = nullptr)
 {
     cf::GemmParams gp;
     gp.A = A_rows;
@@ -169,6 +185,12 @@ cf_status launch_gemm(const Resolved &r, const void *A_rows, const void *W, cons
         }
     }
     const int ncu = num_cu_of_current_device();
+    if (job != nullptr && job->bytes > 0) {
+        gp.cp_src = job->src;
+        gp.cp_dst = job->dst;
+        gp.cp_bytes = job->bytes;
+        gp.cp_wgs = ncu / 4;                       // 64 copy workgroups on a 256-CU part
+    }
     hipError_t e = r.bf16_in ? cf::launch_gemm_bf16(gp, r.w_kn, r.bf16_out, s, ncu)
                              : cf::launch_gemm_f32(gp, r.w_kn, s, ncu);
     if (e != hipSuccess)
@@ -177,7 +199,7 @@ cf_status launch_gemm(const Resolved &r, const void *A_rows, const void *W, cons
 }
 
 cf_status rs_step_impl(const Resolved &r, int step, const void *A, const void *W, const float *recv, float *out,
-                       hipStream_t s)
+                       hipStream_t s, const CopyJob *job = nullptr)
 {
     if (cf_status st = check_step(r, step))
         return st;
@@ -193,10 +215,11 @@ cf_status rs_step_impl(const Resolved &r, int step, const void *A, const void *W
         return fail(CF_ERR_MISALIGNED, "tensor pointers must be 16-byte aligned");
     const int l = chunk_index(CF_KIND_RS, r.p, r.rank, step);
     const char *a_rows = static_cast<const char *>(A) + (size_t)l * r.mc * r.lda * in_elem(r);
-    return launch_gemm(r, a_rows, W, recv, out, s);
+    return launch_gemm(r, a_rows, W, recv, out, s, job);
 }
 
-cf_status ag_step_impl(const Resolved &r, int step, const void *shard, const void *W, void *O, hipStream_t s)
+cf_status ag_step_impl(const Resolved &r, int step, const void *shard, const void *W, void *O, hipStream_t s,
+                       const CopyJob *job = nullptr)
 {
     if (cf_status st = check_step(r, step))
         return st;
@@ -206,7 +229,7 @@ cf_status ag_step_impl(const Resolved &r, int step, const void *shard, const voi
         return fail(CF_ERR_MISALIGNED, "tensor pointers must be 16-byte aligned");
     const int l = chunk_index(CF_KIND_AG, r.p, r.rank, step);
     char *o_rows = static_cast<char *>(O) + (size_t)l * r.mc * r.ldo * (r.bf16_out ? 2 : 4);
-    return launch_gemm(r, shard, W, nullptr, o_rows, s);
+    return launch_gemm(r, shard, W, nullptr, o_rows, s, job);
 }
 
 cf_status dp_step_impl(int p, int rank, int step, float *bucket, int64_t chunk_elems, const float *recv,
@@ -267,7 +290,9 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
                            uint32_t flags)
 {
     const int p = r.p;
-    const bool serial = (flags & CF_SERIAL) != 0 || xs_in == cs;
+    // CF_FUSED_COPY: the delivery for step i+1 rides in the launch of step i; one stream, no events.
+    const bool fused = (flags & CF_FUSED_COPY) != 0 && !(flags & (CF_NO_COPY | CF_NO_COMPUTE));
+    const bool serial = (flags & CF_SERIAL) != 0 || xs_in == cs || fused;
     hipStream_t xs = serial ? cs : xs_in;
     const bool do_copy = !(flags & CF_NO_COPY);
     const bool do_compute = !(flags & CF_NO_COMPUTE);
@@ -297,7 +322,7 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
 
     // what rank r-1 delivers for step i+1 lands in slot[(i+1) % 2]
     auto deliver = [&](int i) -> cf_status {
-        if (!(i + 1 < p && do_copy))
+        if (!(i + 1 < p && do_copy) || fused)
             return CF_OK;
         void *dst = b->slot[(i + 1) & 1];
         // the slot was last read by the kernel of step i-1 (steps >= 1 read a slot)
@@ -322,15 +347,21 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
         if (!serial && do_copy && i > 0)
             CF_HIP(hipStreamWaitEvent(cs, ready(i), 0));
         cf_status st = CF_OK;
+        CopyJob job;
+        if (fused && i + 1 < p) {                  // what the neighbour delivers for step i+1
+            job.src = b->peer_stage[i];
+            job.dst = b->slot[(i + 1) & 1];
+            job.bytes = slot_bytes;
+        }
         if (kind == CF_KIND_RS) {
             if (!serial && do_copy && b->peer_sink != nullptr && i >= 2 && i < p - 1)
                 CF_HIP(hipStreamWaitEvent(cs, sunk(i - 2), 0));   // B_out slot still being sent
             const float *recv = i > 0 ? static_cast<const float *>(b->slot[i & 1]) : nullptr;
             float *out = i < p - 1 ? b->send_slot[i & 1] : static_cast<float *>(b->O);
-            st = rs_step_impl(r, i, b->A_or_own_shard, b->W, recv, out, cs);
+            st = rs_step_impl(r, i, b->A_or_own_shard, b->W, recv, out, cs, &job);
         } else if (kind == CF_KIND_AG) {
             const void *shard = i > 0 ? b->slot[i & 1] : b->A_or_own_shard;
-            st = ag_step_impl(r, i, shard, b->W, b->O, cs);
+            st = ag_step_impl(r, i, shard, b->W, b->O, cs, &job);
         } else {
             st = dp_step_impl(p, r.rank, i, static_cast<float *>(b->O), r.mc,
                               i > 0 ? static_cast<const float *>(b->slot[i & 1]) : nullptr, cs);
@@ -477,11 +508,17 @@ cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_bu
 {
     if (kind != CF_KIND_RS && kind != CF_KIND_AG && kind != CF_KIND_DP)
         return fail(CF_ERR_INVALID_ARG, "kind %d", kind);
-    if (flags & ~(uint32_t)(CF_NO_COPY | CF_NO_COMPUTE | CF_SERIAL | CF_POISON | CF_GRAPH))
+    if (flags & ~(uint32_t)(CF_NO_COPY | CF_NO_COMPUTE | CF_SERIAL | CF_POISON | CF_GRAPH | CF_FUSED_COPY))
         return fail(CF_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
     Resolved r;
     if (cf_status st = resolve(desc, kind, &r))
         return st;
+    if (flags & CF_FUSED_COPY) {
+        if (flags & CF_POISON)
+            return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY cannot be combined with CF_POISON");
+        if (kind == CF_KIND_DP || !step_can_carry_copy(r))
+            return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY needs the bf16 chunk-GEMM kernels (kind RS or AG, bf16 operands)");
+    }
     if (cf_status st = check_buffers(r, kind, bufs, flags))
         return st;
     hipStream_t cs = static_cast<hipStream_t>(compute_stream);

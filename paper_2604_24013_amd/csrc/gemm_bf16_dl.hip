@@ -152,6 +152,31 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WGM, wn = wave / WGM;
 
+    // Workgroups beyond the GEMM's own grid carry the emulated delivery of the NEXT step (what the ring
+    // neighbour sends while this step computes): a streaming copy that shares the launch with the GEMM,
+    // so that no second stream, event or inter-queue wait sits between two step kernels.
+    const int gemm_wgs = tiles_m * tiles_n * P.splits;
+    if ((int)blockIdx.x >= gemm_wgs) {
+        const u32x4_t *src = static_cast<const u32x4_t *>(P.cp_src);
+        u32x4_t *dst = static_cast<u32x4_t *>(P.cp_dst);
+        const size_t n16 = P.cp_bytes / 16;
+        const size_t stride = (size_t)P.cp_wgs * (64 * NW);
+        size_t i = (size_t)((int)blockIdx.x - gemm_wgs) * (64 * NW) + tid;
+        for (; i + 3 * stride < n16; i += 4 * stride) {
+            const u32x4_t v0 = __builtin_nontemporal_load(&src[i]);
+            const u32x4_t v1 = __builtin_nontemporal_load(&src[i + stride]);
+            const u32x4_t v2 = __builtin_nontemporal_load(&src[i + 2 * stride]);
+            const u32x4_t v3 = __builtin_nontemporal_load(&src[i + 3 * stride]);
+            __builtin_nontemporal_store(v0, &dst[i]);
+            __builtin_nontemporal_store(v1, &dst[i + stride]);
+            __builtin_nontemporal_store(v2, &dst[i + 2 * stride]);
+            __builtin_nontemporal_store(v3, &dst[i + 3 * stride]);
+        }
+        for (; i < n16; i += stride)
+            __builtin_nontemporal_store(__builtin_nontemporal_load(&src[i]), &dst[i]);
+        return;
+    }
+
     // Work item = (output tile, k-split); the splits of a tile are neighbours in the remapped order.
     const int splits = P.splits;
     const int work = xcd_remap(blockIdx.x, tiles_m * tiles_n * splits);
@@ -570,7 +595,7 @@ template <int BM, int BN, int WGM, int WGN, int NS, bool SPREAD>
 hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s)
 {
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    const dim3 grid(tiles_m * tiles_n * p.splits), block(64 * WGM * WGN);
+    const dim3 grid(tiles_m * tiles_n * p.splits + p.cp_wgs), block(64 * WGM * WGN);
     if (w_kn) {
         if (out_bf16)
             hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, true>), grid, block, 0, s, p, tiles_m, tiles_n);
@@ -609,6 +634,8 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
                          (size_t)p.splits * p.M * p.N * sizeof(float) > p.ws_bytes || tiles > p.max_tiles ||
                          (int64_t)p.M * p.N * 4 >= ((int64_t)1 << 31)))
         p.splits = 1;                          // no (or too small a) workspace: plain kernel
+    if (p.cp_src == nullptr || p.cp_dst == nullptr || p.cp_bytes == 0)
+        p.cp_wgs = 0;
     // LDS stages: as many as fit (160 KiB per CU); the 128x128 tile comes with two stages (two
     // workgroups share a CU) or four (one workgroup per CU, tiles requested three ahead).
     if (t.bm == 256 && t.bn == 256) return launch_cfg<256, 256, 2, 4, 2, true>(p, w_kn, out_bf16, s);

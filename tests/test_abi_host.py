@@ -112,6 +112,9 @@ def test_schedule_argument_checks(lib):
     strided = cf.layer_desc(4, 0, 16, 32, 64, ldo=40)
     assert _status(cf.run_schedule, strided, cf.CF_KIND_RS, ok, None, None, 0)[0] == cf.CF_ERR_UNSUPPORTED
     assert _status(cf.run_schedule, d, cf.CF_KIND_RS, ok, None, None, cf.CF_GRAPH)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.run_schedule, d, cf.CF_KIND_RS, ok, None, None, cf.CF_FUSED_COPY | cf.CF_POISON)[0] == cf.CF_ERR_UNSUPPORTED
+    assert _status(cf.run_schedule, cf.layer_desc(4, 0, 16, 32, 64, "f32"), cf.CF_KIND_RS, ok, None, None, cf.CF_FUSED_COPY)[0] == cf.CF_ERR_UNSUPPORTED
+    assert _status(cf.run_schedule, cf.layer_desc(4, 0, 16, 0, 0), cf.CF_KIND_DP, ok, None, None, cf.CF_FUSED_COPY)[0] == cf.CF_ERR_UNSUPPORTED
     # 64 KiB of arrival counters + 8 partial tiles of m_chunk x n fp32; none for the gradient path / fp32
     assert cf.workspace_bytes(d, cf.CF_KIND_RS) == 64 * 1024 + 8 * 16 * 32 * 4
     assert cf.workspace_bytes(d, cf.CF_KIND_DP) == 0

@@ -271,7 +271,8 @@ def test_schedule_modes_agree_rs():
     data = inputs.make_rs(w, salt=5)
     rank = 3
     ref = _oracle_rs(w, data, rank)
-    for flags in (0, cf.CF_SERIAL, cf.CF_POISON, cf.CF_POISON | cf.CF_SERIAL):
+    for flags in (0, cf.CF_SERIAL, cf.CF_POISON, cf.CF_POISON | cf.CF_SERIAL, cf.CF_FUSED_COPY,
+                  cf.CF_FUSED_COPY | cf.CF_GRAPH):
         run = H.RsRun(w, data, rank, with_sink=True)
         run.O.fill_(float("nan"))
         run.run_schedule(flags)
@@ -291,7 +292,7 @@ def test_schedule_modes_agree_ag():
     data = inputs.make_ag(w, salt=6)
     rank = 5
     ref = _oracle_ag(w, data, rank)
-    for flags in (0, cf.CF_SERIAL, cf.CF_POISON):
+    for flags in (0, cf.CF_SERIAL, cf.CF_POISON, cf.CF_FUSED_COPY, cf.CF_FUSED_COPY | cf.CF_GRAPH):
         run = H.AgRun(w, data, rank, with_sink=True)
         run.run_schedule(flags)
         got = H.to_host_f64(run.O)
@@ -333,14 +334,15 @@ def _sample_rows(mc, rng, extra=6):
     return sorted(fixed)
 
 
+@pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH])
 @pytest.mark.parametrize("name", ["c2_rs_7b", "c4_rs_70b_down"])
-def test_full_size_rs(name):
+def test_full_size_rs(name, flags):
     w = inputs.CONFIGS[name]
     data = inputs.make_rs(w)
     rank = 0
     run = H.RsRun(w, data, rank, with_sink=True)
     with H.Workspace(run.desc, cf.CF_KIND_RS):          # as the benchmark runs it
-        run.run_schedule(0)
+        run.run_schedule(flags)
     A64 = None
     W64 = inputs.as_f64(data["W"], w.dtype)
     rng = np.random.default_rng(1)
@@ -357,14 +359,15 @@ def test_full_size_rs(name):
         assert e <= TOL_BF16 and e <= TIGHT_BF16, f"step {i}: {e:.3e}"
 
 
+@pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH])
 @pytest.mark.parametrize("name", ["c3_ag_7b", "c4_ag_70b_up"])
-def test_full_size_ag(name):
+def test_full_size_ag(name, flags):
     w = inputs.CONFIGS[name]
     data = inputs.make_ag(w)
     rank = 0
     run = H.AgRun(w, data, rank)
     with H.Workspace(run.desc, cf.CF_KIND_AG):          # as the benchmark runs it (the 7B shape splits k)
-        run.run_schedule(0)
+        run.run_schedule(flags)
     got_full = H.to_host_f64(run.O)
     assert not np.isnan(got_full).any()
     W64 = inputs.as_f64(data["W"], w.dtype)
