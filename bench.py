@@ -40,6 +40,7 @@ def main() -> int:
     ap.add_argument("--skip-dp", action="store_true", help="leave out the 1e9-element gradient bucket")
     ap.add_argument("--skip-cpu", action="store_true", help="leave out the CPU-oracle baseline")
     ap.add_argument("--only-pair", action="store_true", help="time the headline workload only")
+    ap.add_argument("--modes", default="", help="comma-separated subset of the schedule modes to time (default: all)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (known bytes, for scaling hardware counters)")
     args = ap.parse_args()
@@ -91,7 +92,13 @@ def main() -> int:
     # how the emulated deliveries are enqueued: hipMemcpyAsync on the copy stream ordered by events
     # (eager or as a captured graph), or carried by extra workgroups of the step kernels (one stream)
     MODES = (("streams", 0), ("graph", cf.CF_GRAPH), ("fused-copy", cf.CF_FUSED_COPY),
-             ("fused-copy+graph", cf.CF_FUSED_COPY | cf.CF_GRAPH))
+             ("fused-copy+graph", cf.CF_FUSED_COPY | cf.CF_GRAPH), ("device-wait", cf.CF_DEVICE_WAIT),
+             ("device-wait+graph", cf.CF_DEVICE_WAIT | cf.CF_GRAPH))
+
+    if args.modes:
+        keep = set(args.modes.split(","))
+        MODES = tuple(m for m in MODES[:2]) + tuple(m for m in MODES[2:] if m[0] in keep) if not keep & {"streams", "graph"} \
+            else tuple(m for m in MODES if m[0] in keep)
 
     def overlap_eff(t):
         return max(t["compute_only"][0], t["copy_only"][0]) / t["overlapped"][0]
@@ -191,6 +198,8 @@ def main() -> int:
         log("dp", dp)
         del run
         torch.cuda.empty_cache()
+
+    cf.device_status(None)                            # no step kernel gave up a device-side wait
 
     # ---------------- CPU oracle on a bounded sample of the headline workload ----------------
     cpu = None

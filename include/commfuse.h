@@ -138,10 +138,18 @@ enum {
     CF_SERIAL = 4u,      /* one stream, copy i+1 strictly after kernel i: no overlap   */
     CF_POISON = 8u,      /* debug: fill each B_in slot with NaN bytes before its copy  */
     CF_GRAPH = 16u,      /* capture the schedule once into a HIP graph, replay after   */
-    CF_FUSED_COPY = 32u  /* bf16 RS / AG only: the delivery for step i+1 is carried by
+    CF_FUSED_COPY = 32u, /* bf16 RS / AG only: the delivery for step i+1 is carried by
                             extra workgroups of step i's kernel launch instead of a
                             hipMemcpyAsync on copy_stream: one stream, no events
                             (copy_stream is unused; not with CF_POISON)               */
+    CF_DEVICE_WAIT = 64u /* bf16 RS / AG only, needs a registered workspace: the compute
+                            stream does not wait for the copy stream between steps;
+                            each delivery is followed by a flag write and the step
+                            kernel waits for its flag on the device (before its first
+                            operand load for AG, before the B_in add for RS, as in
+                            Alg. 2 where the transfer is needed by the add only).  The
+                            wait is a bounded spin: on time-out the kernel finishes
+                            with invalid results and commfuse_device_status() reports it */
 };
 
 /* A whole rank step: the p iterations of Alg. 1 (CF_KIND_AG) or Alg. 2
@@ -155,6 +163,11 @@ enum {
  * dtypes are ignored.  Overlapping calls that share slots race. */
 cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_buffers *bufs,
                                 void *compute_stream, void *copy_stream, uint32_t flags);
+
+/* Synchronises `hip_stream` and reports whether any step kernel since the last call gave up a
+ * CF_DEVICE_WAIT wait (CF_ERR_HIP; the status word in the workspace is cleared).  CF_OK if none did
+ * or no workspace is registered.  This is the one entry point that synchronises. */
+cf_status commfuse_device_status(void *hip_stream);
 
 /* Text of the calling thread's last error ("" if none).  Host pointer, valid
  * until the thread's next failing call. */
@@ -170,7 +183,8 @@ const char *commfuse_last_error(void);
  *     layer (0 if the kind / dtype never splits).  Host-only arithmetic.
  *   commfuse_set_workspace: registers a caller-owned DEVICE buffer (16-byte
  *     aligned) for all later calls on this process, or clears the registration
- *     (NULL / 0).  Its first 64 KiB are zeroed on `hip_stream` (this is the one
+ *     (NULL / 0).  Its first 64 KiB (arrival counters, delivery flags, a status word)
+ *     are zeroed on `hip_stream` (this is the one
  *     call that enqueues a memset; do not capture it into a graph).  The caller
  *     keeps the buffer alive and unmodified while registered.  Steps that
  *     overlap in time on the GPU must not share a workspace.

@@ -19,7 +19,7 @@ CF_ERR_INVALID_ARG, CF_ERR_NULL_PTR, CF_ERR_UNSUPPORTED, CF_ERR_MISALIGNED, CF_E
 CF_BF16, CF_F32 = 0, 1
 CF_KIND_RS, CF_KIND_AG, CF_KIND_DP = 0, 1, 2
 CF_W_KN, CF_W_NK = 0, 1
-CF_NO_COPY, CF_NO_COMPUTE, CF_SERIAL, CF_POISON, CF_GRAPH, CF_FUSED_COPY = 1, 2, 4, 8, 16, 32
+CF_NO_COPY, CF_NO_COMPUTE, CF_SERIAL, CF_POISON, CF_GRAPH, CF_FUSED_COPY, CF_DEVICE_WAIT = 1, 2, 4, 8, 16, 32, 64
 
 KINDS = {"rs": CF_KIND_RS, "ag": CF_KIND_AG, "dp": CF_KIND_DP}
 DTYPES = {"bf16": CF_BF16, "f32": CF_F32}
@@ -27,6 +27,7 @@ DTYPES = {"bf16": CF_BF16, "f32": CF_F32}
 EXPORTS = [
     "commfuse_chunk_index", "commfuse_rs_step", "commfuse_ag_step", "commfuse_dp_reduce_step",
     "commfuse_run_schedule", "commfuse_last_error", "commfuse_workspace_bytes", "commfuse_set_workspace",
+    "commfuse_device_status",
     "commfuse_destroy_cache", "commfuse_version",
 ]
 
@@ -86,6 +87,8 @@ def load():
     lib.commfuse_workspace_bytes.restype = ctypes.c_size_t
     lib.commfuse_set_workspace.argtypes = [vp, ctypes.c_size_t, vp]
     lib.commfuse_set_workspace.restype = i32
+    lib.commfuse_device_status.argtypes = [vp]
+    lib.commfuse_device_status.restype = i32
     lib.commfuse_destroy_cache.argtypes = []
     lib.commfuse_destroy_cache.restype = None
     lib.commfuse_version.argtypes = []
@@ -190,6 +193,11 @@ def set_workspace(buf, nbytes: int = 0, stream=None) -> None:
     if buf is not None and not isinstance(buf, int) and nbytes == 0:
         nbytes = buf.numel() * buf.element_size()
     _check(load().commfuse_set_workspace(_ptr(buf), nbytes, _stream(stream)))
+
+
+def device_status(stream=None) -> None:
+    """Synchronises ``stream``; raises if a step kernel gave up a CF_DEVICE_WAIT wait."""
+    _check(load().commfuse_device_status(_stream(stream)))
 
 
 def destroy_cache() -> None:

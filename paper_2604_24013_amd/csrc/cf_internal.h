@@ -23,6 +23,13 @@ struct GemmParams {
     int splits = 1;
     // optional delivery carried by extra workgroups of the same launch (direct-to-LDS bf16 kernel only):
     // cp_bytes (a multiple of 16) from cp_src to cp_dst, both 16-byte aligned, by cp_wgs workgroups
+    // optional device-side wait (direct-to-LDS bf16 kernel only): the kernel waits, with a bounded spin,
+    // until *wait_flag != 0 before it first touches the delivered buffer (the slice for an all-gather
+    // step, B_in for a reduce-scatter step); on time-out it sets bit 0 of *status and carries on
+    const unsigned *wait_flag = nullptr;
+    unsigned *status = nullptr;
+    unsigned spin_limit = 0;
+    bool wait_at_start = false;   // true: before the first operand load; false: before the B_in loads
     const void *cp_src = nullptr;
     void *cp_dst = nullptr;
     size_t cp_bytes = 0;
@@ -47,6 +54,9 @@ hipError_t launch_gemm_f32(const GemmParams &p, bool w_kn, hipStream_t s, int nu
 
 // dst[e] += src[e], e in [0, n)
 hipError_t launch_dp_reduce(float *dst, const float *src, int64_t n, hipStream_t s, int num_cu);
+
+// Writes `value` to each of dst[0..count) with device-coherent stores (flags polled by other kernels).
+hipError_t launch_set_words(unsigned *dst, int count, unsigned value, hipStream_t s);
 
 // Fills a buffer with 0xFF bytes (a NaN pattern for fp32 and bf16) -- debug poison.
 hipError_t launch_fill_ff(void *dst, size_t bytes, hipStream_t s);

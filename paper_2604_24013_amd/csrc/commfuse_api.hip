@@ -7,6 +7,7 @@
 #include <climits>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <unordered_map>
@@ -59,6 +60,10 @@ int num_cu_of_current_device()
 // Caller-owned split-K workspace (commfuse_set_workspace): [0, WS_COUNTER_BYTES) arrival counters,
 // the rest fp32 partial tiles.
 constexpr size_t WS_COUNTER_BYTES = 64 * 1024;
+constexpr size_t WS_TILE_COUNTER_BYTES = 60 * 1024;   // split-K arrival counters
+constexpr size_t WS_FLAG_OFFSET = 60 * 1024;          // delivery flags (CF_DEVICE_WAIT): one word per step
+constexpr int WS_MAX_FLAGS = 512;
+constexpr size_t WS_STATUS_OFFSET = 63 * 1024;        // one status word (bit 0: a device-side wait timed out)
 constexpr int WS_MAX_SPLITS = 8;
 struct Workspace {
     void *ptr = nullptr;
@@ -150,7 +155,20 @@ struct CopyJob {
     const void *src = nullptr;
     void *dst = nullptr;
     size_t bytes = 0;
+    const unsigned *wait_flag = nullptr;   // CF_DEVICE_WAIT: flag the step kernel waits on
+    unsigned *status = nullptr;
+    bool wait_at_start = false;
 };
+
+unsigned spin_limit()
+{
+    if (const char *e = getenv("COMMFUSE_SPIN_LIMIT")) {   // tests force a time-out with a tiny limit
+        const long v = atol(e);
+        if (v > 0)
+            return (unsigned)v;
+    }
+    return 400000u;                                        // about a second of polling
+}
 
 // True if a step of this layer runs the kernel that can carry a delivery (direct-to-LDS bf16 kernel).
 bool step_can_carry_copy(const Resolved &r)
@@ -181,10 +199,16 @@ cf_status launch_gemm(const Resolved &r, const void *A_rows, const void *W, cons
             gp.counters = static_cast<unsigned *>(g_ws.ptr);
             gp.ws = reinterpret_cast<float *>(static_cast<char *>(g_ws.ptr) + WS_COUNTER_BYTES);
             gp.ws_bytes = g_ws.bytes - WS_COUNTER_BYTES;
-            gp.max_tiles = (int)(WS_COUNTER_BYTES / sizeof(unsigned));
+            gp.max_tiles = (int)(WS_TILE_COUNTER_BYTES / sizeof(unsigned));
         }
     }
     const int ncu = num_cu_of_current_device();
+    if (job != nullptr && job->wait_flag != nullptr) {
+        gp.wait_flag = job->wait_flag;
+        gp.status = job->status;
+        gp.spin_limit = spin_limit();
+        gp.wait_at_start = job->wait_at_start;
+    }
     if (job != nullptr && job->bytes > 0) {
         gp.cp_src = job->src;
         gp.cp_dst = job->dst;
@@ -292,6 +316,17 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
     const int p = r.p;
     // CF_FUSED_COPY: the delivery for step i+1 rides in the launch of step i; one stream, no events.
     const bool fused = (flags & CF_FUSED_COPY) != 0 && !(flags & (CF_NO_COPY | CF_NO_COMPUTE));
+    // CF_DEVICE_WAIT: the compute stream never waits for the copy stream between steps; each delivery
+    // is followed by a flag write, and the step kernel that needs it waits for the flag on the device.
+    const bool dwait = (flags & CF_DEVICE_WAIT) != 0 && !(flags & CF_NO_COMPUTE) && !fused;
+    unsigned *dw_flags = nullptr, *dw_status = nullptr;
+    if (dwait) {
+        std::lock_guard<std::mutex> lk(g_ws_mu);
+        if (g_ws.ptr == nullptr || g_ws.bytes < WS_COUNTER_BYTES)
+            return fail(CF_ERR_INVALID_ARG, "CF_DEVICE_WAIT needs a registered workspace (commfuse_set_workspace)");
+        dw_flags = reinterpret_cast<unsigned *>(static_cast<char *>(g_ws.ptr) + WS_FLAG_OFFSET);
+        dw_status = reinterpret_cast<unsigned *>(static_cast<char *>(g_ws.ptr) + WS_STATUS_OFFSET);
+    }
     const bool serial = (flags & CF_SERIAL) != 0 || xs_in == cs || fused;
     hipStream_t xs = serial ? cs : xs_in;
     const bool do_copy = !(flags & CF_NO_COPY);
@@ -315,6 +350,11 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
     auto done = [&](int i) { return ev[2 + p + i]; };
     auto sunk = [&](int i) { return ev[2 + 2 * p + i]; };
 
+    if (dwait) {                                     // all delivery flags down before any copy raises one
+        hipError_t e = cf::launch_set_words(dw_flags, p, 0u, cs);
+        if (e != hipSuccess)
+            return fail_hip(e, "flag reset");
+    }
     if (!serial) {
         CF_HIP(hipEventRecord(ev_start, cs));
         CF_HIP(hipStreamWaitEvent(xs, ev_start, 0));
@@ -336,6 +376,11 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
                 return fail_hip(e, "poison fill");
         }
         CF_HIP(hipMemcpyAsync(dst, b->peer_stage[i], slot_bytes, hipMemcpyDeviceToDevice, xs));
+        if (dwait && !serial) {
+            hipError_t e = cf::launch_set_words(dw_flags + (i + 1), 1, 1u, xs);   // after the copy, same stream
+            if (e != hipSuccess)
+                return fail_hip(e, "flag write");
+        }
         if (!serial)
             CF_HIP(hipEventRecord(ready(i + 1), xs));
         return CF_OK;
@@ -344,10 +389,15 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
     auto kernel = [&](int i) -> cf_status {
         if (!do_compute)
             return CF_OK;
-        if (!serial && do_copy && i > 0)
+        if (!serial && do_copy && i > 0 && !dwait)
             CF_HIP(hipStreamWaitEvent(cs, ready(i), 0));
         cf_status st = CF_OK;
         CopyJob job;
+        if (dwait && !serial && i > 0) {           // the kernel itself waits for the delivery of step i
+            job.wait_flag = dw_flags + i;
+            job.status = dw_status;
+            job.wait_at_start = kind == CF_KIND_AG;  // the slice is an operand; B_in is needed by the add only
+        }
         if (fused && i + 1 < p) {                  // what the neighbour delivers for step i+1
             job.src = b->peer_stage[i];
             job.dst = b->slot[(i + 1) & 1];
@@ -391,8 +441,7 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
             return CF_OK;
         if (!serial && do_compute && kind != CF_KIND_AG)
             CF_HIP(hipStreamWaitEvent(xs, done(i), 0));
-        if (!serial && kind == CF_KIND_AG && i > 0)
-            CF_HIP(hipStreamWaitEvent(xs, ready(i), 0));           // same stream: already ordered, kept explicit
+        // (all-gather: the slice in hand was delivered on this same stream, so it is already ordered)
         CF_HIP(hipMemcpyAsync(b->peer_sink[i], src, bytes, hipMemcpyDeviceToDevice, xs));
         if (!serial)
             CF_HIP(hipEventRecord(sunk(i), xs));
@@ -508,11 +557,17 @@ cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_bu
 {
     if (kind != CF_KIND_RS && kind != CF_KIND_AG && kind != CF_KIND_DP)
         return fail(CF_ERR_INVALID_ARG, "kind %d", kind);
-    if (flags & ~(uint32_t)(CF_NO_COPY | CF_NO_COMPUTE | CF_SERIAL | CF_POISON | CF_GRAPH | CF_FUSED_COPY))
+    if (flags & ~(uint32_t)(CF_NO_COPY | CF_NO_COMPUTE | CF_SERIAL | CF_POISON | CF_GRAPH | CF_FUSED_COPY | CF_DEVICE_WAIT))
         return fail(CF_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
     Resolved r;
     if (cf_status st = resolve(desc, kind, &r))
         return st;
+    if (flags & CF_DEVICE_WAIT) {
+        if (flags & CF_FUSED_COPY)
+            return fail(CF_ERR_UNSUPPORTED, "CF_DEVICE_WAIT and CF_FUSED_COPY exclude each other");
+        if (kind == CF_KIND_DP || !step_can_carry_copy(r) || r.p > WS_MAX_FLAGS)
+            return fail(CF_ERR_UNSUPPORTED, "CF_DEVICE_WAIT needs the bf16 chunk-GEMM kernels (kind RS or AG, bf16 operands)");
+    }
     if (flags & CF_FUSED_COPY) {
         if (flags & CF_POISON)
             return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY cannot be combined with CF_POISON");
@@ -607,6 +662,27 @@ cf_status commfuse_set_workspace(void *device_ptr, size_t bytes, void *hip_strea
     std::lock_guard<std::mutex> lk(g_ws_mu);
     g_ws.ptr = device_ptr;
     g_ws.bytes = bytes;
+    return CF_OK;
+}
+
+cf_status commfuse_device_status(void *hip_stream)
+{
+    void *ws = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(g_ws_mu);
+        ws = g_ws.ptr;
+    }
+    if (ws == nullptr)
+        return CF_OK;
+    unsigned word = 0;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    CF_HIP(hipMemcpyAsync(&word, static_cast<char *>(ws) + WS_STATUS_OFFSET, sizeof(word), hipMemcpyDeviceToHost, s));
+    CF_HIP(hipStreamSynchronize(s));
+    if (word != 0) {
+        CF_HIP(hipMemsetAsync(static_cast<char *>(ws) + WS_STATUS_OFFSET, 0, sizeof(word), s));
+        CF_HIP(hipStreamSynchronize(s));
+        return fail(CF_ERR_HIP, "a step kernel gave up waiting for its delivery (status 0x%x): results are invalid", word);
+    }
     return CF_OK;
 }
 

@@ -43,6 +43,12 @@ __global__ __launch_bounds__(DP_THREADS) void dp_reduce_scalar_kernel(float *__r
         dst[i] = src[i] + dst[i];
 }
 
+__global__ __launch_bounds__(64) void set_words_kernel(unsigned *dst, int count, unsigned value)
+{
+    for (int i = threadIdx.x; i < count; i += 64)
+        __hip_atomic_store(&dst[i], value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 __global__ __launch_bounds__(256) void fill_ff_kernel(unsigned *dst, size_t nwords)
 {
     const size_t stride = (size_t)gridDim.x * 256;
@@ -81,6 +87,14 @@ hipError_t launch_dp_reduce(float *dst, const float *src, int64_t n, hipStream_t
         return hipGetLastError();
     }
     return hipSuccess;
+}
+
+hipError_t launch_set_words(unsigned *dst, int count, unsigned value, hipStream_t s)
+{
+    if (count <= 0)
+        return hipSuccess;
+    hipLaunchKernelGGL(set_words_kernel, dim3(1), dim3(64), 0, s, dst, count, value);
+    return hipGetLastError();
 }
 
 hipError_t launch_fill_ff(void *dst, size_t bytes, hipStream_t s)

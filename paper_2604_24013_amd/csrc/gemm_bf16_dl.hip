@@ -188,6 +188,26 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     const int ktb = (int)(((long long)nk_all * split) / splits);          // first k-tile of this split
     const int nk = (int)(((long long)nk_all * (split + 1)) / splits) - ktb; // its number of k-tiles
 
+    // Device-side wait for an emulated delivery: one lane polls the flag with device-coherent loads,
+    // sleeping between polls, for at most spin_limit polls (every wave reaches the barrier either way).
+    auto wait_delivery = [&]() {
+        if (P.wait_flag != nullptr) {
+            if (tid == 0) {
+                unsigned n = 0;
+                while (__hip_atomic_load(P.wait_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == 0u) {
+                    if (++n >= P.spin_limit) {
+                        __hip_atomic_fetch_or(P.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(32);
+                }
+            }
+            __syncthreads();
+        }
+    };
+    if (P.wait_at_start)
+        wait_delivery();
+
     // Buffer resources; all byte extents are below 2^31 (host-checked).
     const unsigned a_bytes = (unsigned)(((int64_t)(M - 1) * P.lda + K) * 2);
     const unsigned w_bytes = (unsigned)((W_KN ? ((int64_t)(K - 1) * P.ldw + N) : ((int64_t)(N - 1) * P.ldw + K)) * 2);
@@ -543,6 +563,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     __amdgpu_buffer_rsrc_t o_rsrc = __builtin_amdgcn_make_buffer_rsrc(P.out, 0, (int)o_bytes, 0x00020000);
     const unsigned r_bytes = (unsigned)(((int64_t)(M - 1) * P.ldo + N) * 4);
     const bool has_recv = P.recv != nullptr;
+    if (!P.wait_at_start)
+        wait_delivery();                             // B_in has travelled under the main loop
     __amdgpu_buffer_rsrc_t r_rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.recv), 0, has_recv ? (int)r_bytes : 0, 0x00020000);
 #pragma unroll

@@ -271,11 +271,14 @@ def test_schedule_modes_agree_rs():
     data = inputs.make_rs(w, salt=5)
     rank = 3
     ref = _oracle_rs(w, data, rank)
-    for flags in (0, cf.CF_SERIAL, cf.CF_POISON, cf.CF_POISON | cf.CF_SERIAL, cf.CF_FUSED_COPY,
-                  cf.CF_FUSED_COPY | cf.CF_GRAPH):
+    for flags in (0, cf.CF_SERIAL, cf.CF_POISON, cf.CF_POISON | cf.CF_SERIAL, cf.CF_GRAPH, cf.CF_FUSED_COPY,
+                  cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_DEVICE_WAIT, cf.CF_DEVICE_WAIT | cf.CF_GRAPH,
+                  cf.CF_DEVICE_WAIT | cf.CF_POISON):
         run = H.RsRun(w, data, rank, with_sink=True)
         run.O.fill_(float("nan"))
-        run.run_schedule(flags)
+        with H.Workspace(run.desc, cf.CF_KIND_RS):
+            run.run_schedule(flags)
+            cf.device_status(run.cs)
         e = H.rel_err(H.to_host_f64(run.O), ref[-1])
         assert e <= TIGHT_BF16, f"flags {flags}: {e:.3e}"
         for i in range(w.p - 1):
@@ -292,9 +295,12 @@ def test_schedule_modes_agree_ag():
     data = inputs.make_ag(w, salt=6)
     rank = 5
     ref = _oracle_ag(w, data, rank)
-    for flags in (0, cf.CF_SERIAL, cf.CF_POISON, cf.CF_FUSED_COPY, cf.CF_FUSED_COPY | cf.CF_GRAPH):
+    for flags in (0, cf.CF_SERIAL, cf.CF_POISON, cf.CF_GRAPH, cf.CF_FUSED_COPY, cf.CF_FUSED_COPY | cf.CF_GRAPH,
+                  cf.CF_DEVICE_WAIT, cf.CF_DEVICE_WAIT | cf.CF_GRAPH, cf.CF_DEVICE_WAIT | cf.CF_POISON):
         run = H.AgRun(w, data, rank, with_sink=True)
-        run.run_schedule(flags)
+        with H.Workspace(run.desc, cf.CF_KIND_AG):
+            run.run_schedule(flags)
+            cf.device_status(run.cs)
         got = H.to_host_f64(run.O)
         assert not np.isnan(got).any()
         assert H.rel_err(got, ref) <= TIGHT_BF16
@@ -302,6 +308,31 @@ def test_schedule_modes_agree_ag():
         assert np.array_equal(H.to_host_f64(run.sink[0]), inputs.as_f64(data["X"], "bf16"))
         for i in range(1, w.p - 1):
             assert np.array_equal(H.to_host_f64(run.sink[i]), inputs.as_f64(data["S"][i], "bf16"))
+
+
+def test_device_wait_times_out_instead_of_hanging():
+    """No delivery is ever made (CF_NO_COPY), so no flag is raised: with a tiny spin limit, forced from
+    the host, every kernel gives up its wait, finishes normally, and the status call reports it."""
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=3, m_chunk=128, n=256, k=128)
+    data = inputs.make_rs(w, salt=11)
+    run = H.RsRun(w, data, 0)
+    os.environ["COMMFUSE_SPIN_LIMIT"] = "20"
+    try:
+        with H.Workspace(run.desc, cf.CF_KIND_RS):
+            cf.device_status(run.cs)                       # clean before
+            run.run_schedule(cf.CF_DEVICE_WAIT | cf.CF_NO_COPY)
+            with pytest.raises(cf.CommFuseError) as e:
+                cf.device_status(run.cs)
+            assert "gave up waiting" in str(e.value)
+            cf.device_status(run.cs)                       # the status word was cleared
+            # and a normal run right after is correct again
+            os.environ.pop("COMMFUSE_SPIN_LIMIT", None)
+            run.run_schedule(cf.CF_DEVICE_WAIT)
+            cf.device_status(run.cs)
+            ref = _oracle_rs(w, data, 0)
+            assert H.rel_err(H.to_host_f64(run.O), ref[-1]) <= TIGHT_BF16
+    finally:
+        os.environ.pop("COMMFUSE_SPIN_LIMIT", None)
 
 
 def test_graph_replays_match_eager():
@@ -334,7 +365,7 @@ def _sample_rows(mc, rng, extra=6):
     return sorted(fixed)
 
 
-@pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH])
+@pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_DEVICE_WAIT | cf.CF_GRAPH, cf.CF_DEVICE_WAIT])
 @pytest.mark.parametrize("name", ["c2_rs_7b", "c4_rs_70b_down"])
 def test_full_size_rs(name, flags):
     w = inputs.CONFIGS[name]
@@ -343,6 +374,7 @@ def test_full_size_rs(name, flags):
     run = H.RsRun(w, data, rank, with_sink=True)
     with H.Workspace(run.desc, cf.CF_KIND_RS):          # as the benchmark runs it
         run.run_schedule(flags)
+        cf.device_status(run.cs)
     A64 = None
     W64 = inputs.as_f64(data["W"], w.dtype)
     rng = np.random.default_rng(1)
@@ -359,7 +391,7 @@ def test_full_size_rs(name, flags):
         assert e <= TOL_BF16 and e <= TIGHT_BF16, f"step {i}: {e:.3e}"
 
 
-@pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH])
+@pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_DEVICE_WAIT | cf.CF_GRAPH, cf.CF_DEVICE_WAIT])
 @pytest.mark.parametrize("name", ["c3_ag_7b", "c4_ag_70b_up"])
 def test_full_size_ag(name, flags):
     w = inputs.CONFIGS[name]
@@ -368,6 +400,7 @@ def test_full_size_ag(name, flags):
     run = H.AgRun(w, data, rank)
     with H.Workspace(run.desc, cf.CF_KIND_AG):          # as the benchmark runs it (the 7B shape splits k)
         run.run_schedule(flags)
+        cf.device_status(run.cs)
     got_full = H.to_host_f64(run.O)
     assert not np.isnan(got_full).any()
     W64 = inputs.as_f64(data["W"], w.dtype)
