@@ -358,3 +358,95 @@ def mlp_pair_rank(X_own, S, W_up, W_down, R, p: int, r: int):
     gate sit between them (the paper states none).  Returns ``(H_bf16, outs)``."""
     H = round_to_bf16(ag_rank(X_own, S, W_up, p, r))
     return H, rs_rank_steps(H, W_down, R, p, r)
+
+
+# ---------------------------------------------------------------------------
+# Pairwise bidirectional P2P schedule (Appendix A, subsection (a))
+# ---------------------------------------------------------------------------
+# The appendix decomposes the n(n-1) sends of a reduce-scatter into n-1 rounds of n/2 simultaneous
+# bidirectional exchanges ("round-robin tournament"): in every round each device sends its partial
+# of the PARTNER's slice straight to the partner (its owner) and receives the partner's partial of
+# its own slice.  The paper prints the pairing only for four devices:
+#   round 1 (A,B)(C,D); round 2 (A,C)(B,D); round 3 (A,D)(B,C).
+# Reading taken for general even n: for n a power of two, partner = rank XOR round (this reproduces
+# the printed table); for other even n the circle method of round-robin tournaments.  Odd n is not
+# defined by the paper ("completion in n-1 rounds (for even n)") and is rejected.
+# The computes are ordered like Alg. 2's: the partials that travel first are computed first, the
+# rank's own slice last, so that nothing is left to send after the last compute.
+
+def pair_partner(p: int, r: int, t: int) -> int:
+    """Partner of rank ``r`` in round ``t`` (1 .. p-1) of the pairwise schedule."""
+    if p < 2 or p % 2 or not (1 <= t <= p - 1) or not (0 <= r < p):
+        raise ValueError("pairwise schedule needs even p >= 2, round in [1, p-1], rank in [0, p)")
+    if p & (p - 1) == 0:
+        return r ^ t
+    a = t - 1                                   # circle method: rank p-1 is fixed, the others rotate
+    if r == p - 1:
+        return a
+    if r == a:
+        return p - 1
+    return (2 * a - r) % (p - 1)
+
+
+def slice_index_pair(p: int, r: int, i: int) -> int:
+    """Slice computed at step ``i``: the partner of round ``i+1`` for ``i < p-1``, the own slice last."""
+    if p == 1:
+        return 0
+    return r if i == p - 1 else pair_partner(p, r, i + 1)
+
+
+def fuse_rs_pairwise_lockstep(X_list, W_list, compute: Optional[Compute] = None):
+    """All ranks run the pairwise schedule in lock-step.
+
+    Returns ``(O, received, sent)``: ``O[r]`` the reduced slice ``r``; ``received[r][t]`` what rank
+    ``r`` receives in round ``t`` (index 0 unused); ``sent[r][i]`` the partial computed at step ``i``
+    and sent in round ``i+1`` (``None`` at the last step).
+    """
+    if compute is None:
+        compute = gemm
+    N = len(X_list)
+    X_s = [split_rows(X_list[r], N) for r in range(N)]
+    sent = [[None] * N for _ in range(N)]
+    received = [[None] * N for _ in range(N)]
+    acc: List[Optional[np.ndarray]] = [None] * N
+    O: List[Optional[np.ndarray]] = [None] * N
+    for i in range(N):
+        for r in range(N):                      # step i: every rank computes one partial
+            l = slice_index_pair(N, r, i)
+            part = compute(X_s[r][l], W_list[r])
+            if i < N - 1:
+                sent[r][i] = part               # goes to its owner l in round i+1
+            else:
+                O[r] = part if acc[r] is None else add(acc[r], part)   # own slice: add what was received
+        if i < N - 1:
+            t = i + 1                           # round t: exchange with the partner
+            for r in range(N):
+                q = pair_partner(N, r, t)
+                got = sent[q][i]                # q computed its partial of slice r at step i
+                received[r][t] = got
+                acc[r] = got.copy() if acc[r] is None else add(acc[r], got)
+    return O, received, sent
+
+
+def rs_pair_rank_steps(A, W, R: Sequence[Optional[np.ndarray]], p: int, r: int):
+    """One-rank view of the pairwise schedule: ``outs[i]`` is the partial sent after step ``i``
+    (``i < p-1``) and ``outs[p-1]`` the result ``X_s[r] @ W + sum_t R[t]`` (``R[t]``: received in round t)."""
+    X_s = split_rows(_f64(A), p)
+    outs = []
+    acc = None
+    for i in range(p):
+        if i >= 1:
+            acc = _f64(R[i]).copy() if acc is None else add(acc, _f64(R[i]))
+        part = gemm(X_s[slice_index_pair(p, r, i)], W)
+        outs.append(part if (i < p - 1 or acc is None) else add(acc, part))
+    return outs
+
+
+def dp_pair_rank(bucket, R: Sequence[Optional[np.ndarray]], p: int, r: int) -> np.ndarray:
+    """Gradient bucket of rank ``r`` after the pairwise schedule: its own slice ``r`` has received
+    ``R[1] .. R[p-1]``; the other slices (sent away) are untouched."""
+    out = _f64(bucket).copy()
+    c = out.shape[0] // p
+    for t in range(1, p):
+        out[r * c:(r + 1) * c] = add(_f64(R[t]), out[r * c:(r + 1) * c])
+    return out

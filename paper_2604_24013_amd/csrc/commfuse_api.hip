@@ -595,6 +595,11 @@ cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_bu
     append_bytes(key, &bufs->O, sizeof(void *));
     append_bytes(key, bufs->slot, sizeof(bufs->slot));
     append_bytes(key, bufs->send_slot, sizeof(bufs->send_slot));
+    {   // the registered workspace is baked into the captured kernels (split-K partials, delivery flags)
+        std::lock_guard<std::mutex> lk(g_ws_mu);
+        append_bytes(key, &g_ws.ptr, sizeof(g_ws.ptr));
+        append_bytes(key, &g_ws.bytes, sizeof(g_ws.bytes));
+    }
     for (int i = 0; i < r.p - 1; ++i) {
         const void *st = bufs->peer_stage ? bufs->peer_stage[i] : nullptr;
         const void *sk = bufs->peer_sink ? bufs->peer_sink[i] : nullptr;

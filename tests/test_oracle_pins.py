@@ -387,3 +387,102 @@ def test_planted_mistakes_are_caught(monkeypatch, golden_dir, mistake):
     elif mistake == "drop_add":
         monkeypatch.setattr(oracle, "add", lambda a, b: np.asarray(b, dtype=np.float64))
     assert _pins_fail(None, golden_dir) >= 1
+
+
+# ----------------------------------------------------------------------------
+# pairwise bidirectional schedule (Appendix A(a))
+# ----------------------------------------------------------------------------
+
+def test_pairwise_rounds_match_the_paper(golden_dir):
+    rounds = {}
+    for ln in read_golden(golden_dir, "appendix_a_pairwise_rounds.txt"):
+        head, body = ln.split(":", 1)
+        rounds[int(head.split()[1])] = [tuple(sorted("ABCD".index(x.strip()) for x in pr.split("<->"))) for pr in body.split(";")]
+    assert sorted(rounds) == [1, 2, 3]
+    for t, pairs in rounds.items():
+        got = sorted({tuple(sorted((r, oracle.pair_partner(4, r, t)))) for r in range(4)})
+        assert got == sorted(pairs), t
+    # with the one-hot problem: what travels in round t is the sender's partial of the RECEIVER's slice
+    X_list, W_list = onehot_problem(4)
+    O, received, sent = oracle.fuse_rs_pairwise_lockstep(X_list, W_list)
+    for t, pairs in rounds.items():
+        for a, b in pairs:
+            assert decode(received[a][t], 4) == [(b, a)] and decode(received[b][t], 4) == [(a, b)]
+    for r in range(4):
+        assert decode(O[r], 4) == [(q, r) for q in range(4)]
+        assert sent[r][3] is None
+
+
+def test_pairwise_send_lists_match_the_running_example(golden_dir):
+    """Appendix running example: A sends a2, a3, a4 to B, C, D etc. -- each device's sends are its
+    partials of the other devices' slices, one to each owner."""
+    X_list, W_list = onehot_problem(4)
+    _, _, sent = oracle.fuse_rs_pairwise_lockstep(X_list, W_list)
+    for ln in read_golden(golden_dir, "appendix_a_circular_p2p_trace.txt"):
+        if not ln.startswith("sends"):
+            continue
+        head, body = ln.split(":", 1)
+        q = DEV.index(head.split()[1].lower())
+        want = sorted((DEV.index(t[0]), int(t[1:]) - 1) for t in body.split())
+        got = sorted(term for i in range(3) for term in decode(sent[q][i], 4))
+        assert got == want
+
+
+@pytest.mark.parametrize("p", [2, 4, 6, 8, 10, 12, 16])
+def test_pairwise_is_a_round_robin_tournament(p):
+    met = set()
+    for t in range(1, p):
+        seen = set()
+        for r in range(p):
+            q = oracle.pair_partner(p, r, t)
+            assert q != r and 0 <= q < p
+            assert oracle.pair_partner(p, q, t) == r, "pairing must be symmetric"
+            seen.add(r)
+            met.add((min(r, q), max(r, q)))
+        assert len(seen) == p
+    assert len(met) == p * (p - 1) // 2, "every pair meets exactly once"
+    for r in range(p):
+        ls = [oracle.slice_index_pair(p, r, i) for i in range(p)]
+        assert sorted(ls) == list(range(p)) and ls[-1] == r
+
+
+@pytest.mark.parametrize("p", [3, 5])
+def test_pairwise_rejects_odd_p(p):
+    with pytest.raises(ValueError):
+        oracle.pair_partner(p, 0, 1)
+
+
+@pytest.mark.parametrize("p,mc,n,k", [(2, 2, 3, 4), (4, 3, 7, 6), (6, 1, 5, 2), (8, 2, 5, 3)])
+@pytest.mark.parametrize("integer", [True, False])
+def test_pairwise_exactness(p, mc, n, k, integer):
+    rng = np.random.default_rng(500 * p + mc + (7 if integer else 0))
+    g = _rand_problem(rng, p, mc, n, k, integer)
+    A = [g(p * mc, k) for _ in range(p)]
+    W = [g(k, n) for _ in range(p)]
+    want = oracle.rs_definition(A, W)
+    got, received, sent = oracle.fuse_rs_pairwise_lockstep(A, W)
+    Y = sum(np.matmul(A[q], W[q]) for q in range(p))
+    for r in range(p):
+        if integer:
+            assert np.array_equal(got[r], want[r]) and np.array_equal(got[r], Y[r * mc:(r + 1) * mc])
+        else:
+            np.testing.assert_allclose(got[r], Y[r * mc:(r + 1) * mc], rtol=0, atol=1e-12 * max(1.0, np.abs(Y).max()))
+        outs = oracle.rs_pair_rank_steps(A[r], W[r], received[r], p, r)
+        for i in range(p - 1):
+            assert np.array_equal(outs[i], sent[r][i])
+        assert np.array_equal(outs[p - 1], got[r])
+
+
+def test_pairwise_dp_rank():
+    p, c, r = 4, 5, 2
+    rng = np.random.default_rng(12)
+    g = [rng.integers(-50, 51, size=p * c).astype(np.float64) for _ in range(p)]
+    O, received, _ = oracle.fuse_rs_pairwise_lockstep(g, [None] * p, compute=lambda x, _w: np.asarray(x, dtype=np.float64).copy())
+    want = oracle.dp_definition(g)
+    for q in range(p):
+        assert np.array_equal(O[q], want[q])
+    out = oracle.dp_pair_rank(g[r], received[r], p, r)
+    assert np.array_equal(out[r * c:(r + 1) * c], want[r])
+    mask = np.ones(p * c, dtype=bool)
+    mask[r * c:(r + 1) * c] = False
+    assert np.array_equal(out[mask], g[r][mask])
