@@ -81,7 +81,7 @@ def main() -> int:
         out = {}
         for name, fl in (("overlapped", 0), ("compute_only", cf.CF_NO_COPY), ("copy_only", cf.CF_NO_COMPUTE)):
             best = None
-            for mode, extra in MODES if (fl == 0 and kind != cf.CF_KIND_DP) else MODES[:2]:
+            for mode, extra in MODES if (fl == 0 and kind in (cf.CF_KIND_RS, cf.CF_KIND_AG)) else MODES[:2]:
                 t = time_calls(lambda: cf.run_schedule(run.desc, kind, run.bufs, run.cs, run.xs, fl | extra),
                                run.cs, steps, warmup)
                 if best is None or t < best[0]:
@@ -175,6 +175,22 @@ def main() -> int:
             del run
             torch.cuda.empty_cache()
 
+    # ---------------- GEMM + reduce-scatter under the pairwise bidirectional schedule ----------------
+    pairwise = {}
+    if not args.only_pair:
+        for name in ("c2_rs_7b", "c4_rs_70b_down"):
+            w = inputs.CONFIGS[name]
+            run = H.RsPairRun(w, inputs.make_rs(w), 0)
+            t = schedule_times(run, cf.CF_KIND_RS_PAIR, max(K, 50), W)
+            pairwise[name] = {"tflops": round(w.flops / (t["overlapped"][0] * 1e-3) / 1e12, 1),
+                              "us_per_rank_step": round(t["overlapped"][0] * 1e3, 1), "mode": t["overlapped"][1],
+                              "overlap_eff": round(overlap_eff(t), 3),
+                              "us_compute_only": round(t["compute_only"][0] * 1e3, 1),
+                              "us_copy_only": round(t["copy_only"][0] * 1e3, 1)}
+            log("pairwise", name, pairwise[name])
+            del run
+            torch.cuda.empty_cache()
+
     # ---------------- gradient reduce-scatter step, 1e9 fp32 elements ----------------
     dp = None
     if not (args.skip_dp or args.only_pair):
@@ -238,6 +254,7 @@ def main() -> int:
         "overlap_eff": round(max(pair_t["compute_only"][0], pair_t["copy_only"][0]) / ms_step, 3),
         "ms_compute_only": round(pair_t["compute_only"][0], 4), "ms_copy_only": round(pair_t["copy_only"][0], 4),
         "roofline": roofline, "cpu_baseline": cpu, "dp_reduce": dp, "other_configs": others,
+        "pairwise_schedule": pairwise,
     }
     print(json.dumps(line), flush=True)
     return 0

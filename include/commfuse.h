@@ -47,7 +47,13 @@ typedef enum {
 } cf_status;
 
 typedef enum { CF_BF16 = 0, CF_F32 = 1 } cf_dtype;
-typedef enum { CF_KIND_RS = 0, CF_KIND_AG = 1, CF_KIND_DP = 2 } cf_kind;
+typedef enum {
+    CF_KIND_RS = 0,       /* FuseReduceScatter on the ring (Alg. 2 / Alg. 3)                      */
+    CF_KIND_AG = 1,       /* FuseAllGather on the ring (Alg. 1)                                   */
+    CF_KIND_DP = 2,       /* gradient reduce on the ring (Alg. 2, identity compute)               */
+    CF_KIND_RS_PAIR = 3,  /* FuseReduceScatter, pairwise bidirectional schedule (Appendix A(a))   */
+    CF_KIND_DP_PAIR = 4   /* gradient reduce, pairwise bidirectional schedule                     */
+} cf_kind;
 
 /* Memory order of the weight shard W^r.
  *   CF_W_KN: W[k x n], row-major, n contiguous -- the paper's W_o^r in R^{D/T x D}
@@ -76,9 +82,21 @@ typedef struct {
 } cf_layer_desc;
 
 /* Slice index l of step i: Alg. 2 "l = (r - i - 1 + N) mod N" for CF_KIND_RS and
- * CF_KIND_DP, Alg. 1 "l = (r - i + N) mod N" for CF_KIND_AG.  Host-only
- * arithmetic.  Returns a negative cf_status on bad arguments. */
+ * CF_KIND_DP, Alg. 1 "l = (r - i + N) mod N" for CF_KIND_AG; for the pairwise kinds
+ * the partner of round i+1 while i < p-1 and the rank's own slice at i = p-1.
+ * Host-only arithmetic.  Returns a negative cf_status on bad arguments. */
 int commfuse_chunk_index(int kind, int p, int rank, int step);
+
+/* Pairwise bidirectional schedule (Appendix A(a)): the reduce-scatter's p(p-1) sends
+ * are p-1 rounds of p/2 simultaneous two-way exchanges, each partial going straight
+ * to the owner of its slice.  Partner of `rank` in round t in [1, p-1], p even:
+ *   p a power of two: rank XOR t -- for four devices the appendix's table
+ *     (A,B)(C,D) / (A,C)(B,D) / (A,D)(B,C);
+ *   other even p: the circle method of round-robin tournaments (rank p-1 fixed,
+ *     the others rotate): in round t, p-1 meets t-1 and a meets b when
+ *     a + b = 2(t-1) mod (p-1).
+ * Host-only arithmetic.  Negative cf_status for odd p or arguments out of range. */
+int commfuse_pair_partner(int p, int rank, int round);
 
 /* One iteration i of Alg. 2 / Alg. 3 (compute, aggregate, stage for sending):
  *     out = A[l*m_chunk : (l+1)*m_chunk, :] @ W  (+ recv  if step > 0)
@@ -92,6 +110,24 @@ int commfuse_chunk_index(int kind, int p, int rank, int step);
  */
 cf_status commfuse_rs_step(const cf_layer_desc *desc, int step, const void *A, const void *W,
                            const float *recv, float *out, void *hip_stream);
+
+/* One iteration i of the pairwise schedule (Appendix A(a)), p even or 1.  The
+ * partials that travel first are computed first and the rank's own slice last, as
+ * in Alg. 2, so nothing is left to send after the last compute:
+ *     step >= 1:    acc (+)= recv      (what the partner of round `step` sent: its
+ *                                       partial of THIS rank's slice; the first
+ *                                       arrival initialises acc)
+ *     step <  p-1:  out = A[l] @ W     (l = partner of round step+1; sent to l)
+ *     step == p-1:  out = acc + A[rank] @ W        (the reduced slice O^r)
+ *   recv [m_chunk x n] fp32; NULL iff step == 0.  At step 1 recv may equal acc
+ *        ("received in place"): then nothing is copied.
+ *   acc  [m_chunk x n] fp32 accumulator of received partials, required when p > 2
+ *        (for p == 2 it is ignored: out = recv + A[rank] @ W).  The accumulate is a
+ *        separate elementwise kernel enqueued before the GEMM and needs ldo == n.
+ *   out  [m_chunk x n] fp32; at step p-1 it may equal acc (recv when p == 2): in place.
+ */
+cf_status commfuse_rs_pair_step(const cf_layer_desc *desc, int step, const void *A, const void *W,
+                                const float *recv, float *acc, float *out, void *hip_stream);
 
 /* One iteration i of Alg. 1 (the compute on the slice in hand):
  *     O[l*m_chunk : (l+1)*m_chunk, :] = shard @ W
@@ -115,6 +151,13 @@ cf_status commfuse_ag_step(const cf_layer_desc *desc, int step, const void *shar
  */
 cf_status commfuse_dp_reduce_step(int p, int rank, int step, float *bucket, int64_t chunk_elems,
                                   const float *recv, void *hip_stream);
+
+/* Gradient path under the pairwise schedule: every round's arrival is a peer's copy
+ * of THIS rank's slice, so for step in [1, p)
+ *     bucket[rank*chunk_elems : (rank+1)*chunk_elems] += recv
+ * and step 0 enqueues nothing.  p even or 1; pointer rules as above. */
+cf_status commfuse_dp_pair_step(int p, int rank, int step, float *bucket, int64_t chunk_elems,
+                                const float *recv, void *hip_stream);
 
 /* Buffers of a whole emulated rank step.  HOST struct holding DEVICE pointers.
  * Peer traffic is emulated: what rank r-1 would deliver for step i (i = 1..p-1)
@@ -160,7 +203,13 @@ enum {
  * compute_stream has been made to wait for everything enqueued, so one
  * hipStreamSynchronize(compute_stream) by the caller suffices.
  * For CF_KIND_DP, desc->m_chunk is the number of elements per slice and n, k,
- * dtypes are ignored.  Overlapping calls that share slots race. */
+ * dtypes are ignored.  Overlapping calls that share slots race.
+ * Pairwise kinds (CF_KIND_RS_PAIR, CF_KIND_DP_PAIR; p even or 1): peer_stage[t-1] is
+ * what the partner of round t delivers (its partial / copy of this rank's slice);
+ * CF_KIND_RS_PAIR accumulates in O itself (the delivery of round 1 lands in O, later
+ * ones in slot[t % 2] and are added to O before the step's GEMM; the last GEMM adds
+ * its product to O in place); peer_sink[i] receives what step i sends to the partner
+ * of round i+1.  CF_FUSED_COPY and CF_DEVICE_WAIT are not available for them. */
 cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_buffers *bufs,
                                 void *compute_stream, void *copy_stream, uint32_t flags);
 

@@ -17,15 +17,15 @@ LIB_PATH = os.path.join(HERE, "libcommfuse.so")
 CF_OK = 0
 CF_ERR_INVALID_ARG, CF_ERR_NULL_PTR, CF_ERR_UNSUPPORTED, CF_ERR_MISALIGNED, CF_ERR_HIP = -1, -2, -3, -4, -5
 CF_BF16, CF_F32 = 0, 1
-CF_KIND_RS, CF_KIND_AG, CF_KIND_DP = 0, 1, 2
+CF_KIND_RS, CF_KIND_AG, CF_KIND_DP, CF_KIND_RS_PAIR, CF_KIND_DP_PAIR = 0, 1, 2, 3, 4
 CF_W_KN, CF_W_NK = 0, 1
 CF_NO_COPY, CF_NO_COMPUTE, CF_SERIAL, CF_POISON, CF_GRAPH, CF_FUSED_COPY, CF_DEVICE_WAIT = 1, 2, 4, 8, 16, 32, 64
 
-KINDS = {"rs": CF_KIND_RS, "ag": CF_KIND_AG, "dp": CF_KIND_DP}
+KINDS = {"rs": CF_KIND_RS, "ag": CF_KIND_AG, "dp": CF_KIND_DP, "rs_pair": CF_KIND_RS_PAIR, "dp_pair": CF_KIND_DP_PAIR}
 DTYPES = {"bf16": CF_BF16, "f32": CF_F32}
 
 EXPORTS = [
-    "commfuse_chunk_index", "commfuse_rs_step", "commfuse_ag_step", "commfuse_dp_reduce_step",
+    "commfuse_chunk_index", "commfuse_pair_partner", "commfuse_rs_pair_step", "commfuse_dp_pair_step", "commfuse_rs_step", "commfuse_ag_step", "commfuse_dp_reduce_step",
     "commfuse_run_schedule", "commfuse_last_error", "commfuse_workspace_bytes", "commfuse_set_workspace",
     "commfuse_device_status",
     "commfuse_destroy_cache", "commfuse_version",
@@ -79,6 +79,12 @@ def load():
     lib.commfuse_ag_step.restype = i32
     lib.commfuse_dp_reduce_step.argtypes = [i32, i32, i32, vp, i64, vp, vp]
     lib.commfuse_dp_reduce_step.restype = i32
+    lib.commfuse_pair_partner.argtypes = [i32, i32, i32]
+    lib.commfuse_pair_partner.restype = i32
+    lib.commfuse_rs_pair_step.argtypes = [ctypes.POINTER(LayerDesc), i32, vp, vp, vp, vp, vp, vp]
+    lib.commfuse_rs_pair_step.restype = i32
+    lib.commfuse_dp_pair_step.argtypes = [i32, i32, i32, vp, i64, vp, vp]
+    lib.commfuse_dp_pair_step.restype = i32
     lib.commfuse_run_schedule.argtypes = [ctypes.POINTER(LayerDesc), i32, ctypes.POINTER(Buffers), vp, vp, ctypes.c_uint32]
     lib.commfuse_run_schedule.restype = i32
     lib.commfuse_last_error.argtypes = []
@@ -144,6 +150,22 @@ def chunk_index(kind: int, p: int, rank: int, step: int) -> int:
     if v < 0:
         raise CommFuseError(v, last_error())
     return v
+
+
+def pair_partner(p: int, rank: int, round_: int) -> int:
+    v = load().commfuse_pair_partner(p, rank, round_)
+    if v < 0:
+        raise CommFuseError(v, last_error())
+    return v
+
+
+def rs_pair_step(desc: LayerDesc, step: int, A, W, recv, acc, out, stream=None) -> None:
+    _check(load().commfuse_rs_pair_step(ctypes.byref(desc), step, _ptr(A), _ptr(W), _ptr(recv), _ptr(acc), _ptr(out),
+                                        _stream(stream)))
+
+
+def dp_pair_step(p: int, rank: int, step: int, bucket, chunk_elems: int, recv, stream=None) -> None:
+    _check(load().commfuse_dp_pair_step(p, rank, step, _ptr(bucket), chunk_elems, _ptr(recv), _stream(stream)))
 
 
 def rs_step(desc: LayerDesc, step: int, A, W, recv, out, stream=None) -> None:

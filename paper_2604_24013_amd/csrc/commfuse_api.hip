@@ -78,6 +78,11 @@ struct Resolved {      // descriptor with defaults filled in
     bool bf16_in, bf16_out, w_kn;
 };
 
+bool is_pair_kind(int kind) { return kind == CF_KIND_RS_PAIR || kind == CF_KIND_DP_PAIR; }
+bool is_dp_kind(int kind) { return kind == CF_KIND_DP || kind == CF_KIND_DP_PAIR; }
+bool is_rs_kind(int kind) { return kind == CF_KIND_RS || kind == CF_KIND_RS_PAIR; }
+bool known_kind(int kind) { return kind >= CF_KIND_RS && kind <= CF_KIND_DP_PAIR; }
+
 size_t in_elem(const Resolved &r) { return r.bf16_in ? 2 : 4; }
 
 cf_status resolve(const cf_layer_desc *d, int kind, Resolved *out)
@@ -99,7 +104,7 @@ cf_status resolve(const cf_layer_desc *d, int kind, Resolved *out)
     r.mc = d->m_chunk;
     r.n = d->n;
     r.k = d->k;
-    if (kind == CF_KIND_DP) {
+    if (is_dp_kind(kind)) {
         r.lda = r.ldw = r.ldo = 0;
         r.bf16_in = r.bf16_out = false;
         r.w_kn = true;
@@ -141,6 +146,29 @@ int chunk_index(int kind, int p, int rank, int step)
     if (kind == CF_KIND_AG)
         return ((rank - step) % p + p) % p;
     return ((rank - step - 1) % p + p) % p;
+}
+
+// Appendix A(a): partner of `rank` in round t of the pairwise schedule (p even, t in [1, p-1]).
+int pair_partner(int p, int rank, int t)
+{
+    if ((p & (p - 1)) == 0)
+        return rank ^ t;                           // reproduces the appendix's four-device table
+    const int a = t - 1;                           // circle method: rank p-1 fixed, the others rotate
+    if (rank == p - 1)
+        return a;
+    if (rank == a)
+        return p - 1;
+    return ((2 * a - rank) % (p - 1) + (p - 1)) % (p - 1);
+}
+
+// Slice computed at step i of the pairwise schedule: what travels in round i+1 first, the own slice last.
+int pair_slice(int p, int rank, int step) { return (step == p - 1) ? rank : pair_partner(p, rank, step + 1); }
+
+cf_status check_pair_p(int p)
+{
+    if (p != 1 && (p & 1))
+        return fail(CF_ERR_INVALID_ARG, "the pairwise schedule is defined for even p (or p = 1), not p = %d", p);
+    return CF_OK;
 }
 
 cf_status check_step(const Resolved &r, int step)
@@ -281,6 +309,79 @@ cf_status dp_step_impl(int p, int rank, int step, float *bucket, int64_t chunk_e
     return CF_OK;
 }
 
+cf_status accumulate(float *dst, const float *src, int64_t elems, hipStream_t s)
+{
+    hipError_t e = cf::launch_dp_reduce(dst, src, elems, s, num_cu_of_current_device());
+    if (e != hipSuccess)
+        return fail_hip(e, "accumulate launch");
+    return CF_OK;
+}
+
+cf_status rs_pair_step_impl(const Resolved &r, int step, const void *A, const void *W, const float *recv, float *acc,
+                            float *out, hipStream_t s)
+{
+    if (cf_status st = check_pair_p(r.p))
+        return st;
+    if (cf_status st = check_step(r, step))
+        return st;
+    if (A == nullptr || W == nullptr || out == nullptr)
+        return fail(CF_ERR_NULL_PTR, "A, W and out must not be NULL");
+    if (step == 0 && recv != nullptr)
+        return fail(CF_ERR_NULL_PTR, "recv must be NULL at step 0 (nothing has been received yet)");
+    if (step > 0 && recv == nullptr)
+        return fail(CF_ERR_NULL_PTR, "recv must not be NULL at step %d", step);
+    if (r.p > 2 && step > 0 && acc == nullptr)
+        return fail(CF_ERR_NULL_PTR, "acc must not be NULL at step %d when p > 2", step);
+    if (!aligned16(A) || !aligned16(W) || !aligned16(out) || !aligned16(recv) || !aligned16(acc))
+        return fail(CF_ERR_MISALIGNED, "tensor pointers must be 16-byte aligned");
+    const bool last = step == r.p - 1;
+    const bool use_acc = r.p > 2;
+    if (use_acc && r.ldo != r.n)
+        return fail(CF_ERR_UNSUPPORTED, "the pairwise accumulate needs packed partial sums (ldo == n)");
+    // in place is fine for the buffer the last step's epilogue adds (every element is read, then written,
+    // by the same lane); anything else would be overwritten while still needed
+    if ((!last && (out == recv || (use_acc && out == acc))) || (last && use_acc && out == recv))
+        return fail(CF_ERR_INVALID_ARG, "out may alias only the buffer the last step adds (acc; recv when p == 2)");
+    const size_t elems = (size_t)r.mc * r.n;
+    if (use_acc && step >= 1 && elems > 0) {
+        if (step == 1) {
+            if (recv != acc)                       // the first arrival initialises the accumulator
+                CF_HIP(hipMemcpyAsync(acc, recv, elems * sizeof(float), hipMemcpyDeviceToDevice, s));
+        } else {
+            if (recv == acc)
+                return fail(CF_ERR_INVALID_ARG, "recv may equal acc at step 1 only");
+            if (cf_status st = accumulate(acc, recv, (int64_t)elems, s))
+                return st;
+        }
+    }
+    const int l = pair_slice(r.p, r.rank, step);
+    const char *a_rows = static_cast<const char *>(A) + (size_t)l * r.mc * r.lda * in_elem(r);
+    const float *add = !last ? nullptr : (use_acc ? acc : recv);   // p == 1: recv is NULL at step 0
+    return launch_gemm(r, a_rows, W, add, out, s);
+}
+
+cf_status dp_pair_step_impl(int p, int rank, int step, float *bucket, int64_t chunk_elems, const float *recv,
+                            hipStream_t s)
+{
+    if (p < 1)
+        return fail(CF_ERR_INVALID_ARG, "p = %d must be >= 1", p);
+    if (cf_status st = check_pair_p(p))
+        return st;
+    if (rank < 0 || rank >= p)
+        return fail(CF_ERR_INVALID_ARG, "rank = %d not in [0, %d)", rank, p);
+    if (step < 0 || step >= p)
+        return fail(CF_ERR_INVALID_ARG, "step = %d not in [0, %d)", step, p);
+    if (chunk_elems < 0)
+        return fail(CF_ERR_INVALID_ARG, "chunk_elems < 0");
+    if (step == 0 || chunk_elems == 0)
+        return CF_OK;
+    if (bucket == nullptr || recv == nullptr)
+        return fail(CF_ERR_NULL_PTR, "bucket and recv must not be NULL at step %d", step);
+    if ((reinterpret_cast<uintptr_t>(bucket) | reinterpret_cast<uintptr_t>(recv)) & 3u)
+        return fail(CF_ERR_MISALIGNED, "fp32 pointers must be 4-byte aligned");
+    return accumulate(bucket + (int64_t)rank * chunk_elems, recv, chunk_elems, s);
+}
+
 // ---------------------------------------------------------------------------
 // events and graphs owned by the library
 // ---------------------------------------------------------------------------
@@ -333,8 +434,9 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
     const bool do_compute = !(flags & CF_NO_COMPUTE);
     const bool poison = (flags & CF_POISON) != 0;
 
+    const bool pair = is_pair_kind(kind);
     size_t slot_bytes;
-    if (kind == CF_KIND_RS)
+    if (is_rs_kind(kind))
         slot_bytes = (size_t)r.mc * r.n * sizeof(float);
     else if (kind == CF_KIND_AG)
         slot_bytes = (size_t)r.mc * r.k * in_elem(r);
@@ -364,7 +466,8 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
     auto deliver = [&](int i) -> cf_status {
         if (!(i + 1 < p && do_copy) || fused)
             return CF_OK;
-        void *dst = b->slot[(i + 1) & 1];
+        // pairwise reduce-scatter: the first arrival initialises the accumulator, which is O itself
+        void *dst = (kind == CF_KIND_RS_PAIR && i == 0) ? b->O : b->slot[(i + 1) & 1];
         // the slot was last read by the kernel of step i-1 (steps >= 1 read a slot)
         if (!serial && do_compute && i - 1 >= 1)
             CF_HIP(hipStreamWaitEvent(xs, done(i - 1), 0));
@@ -412,6 +515,16 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
         } else if (kind == CF_KIND_AG) {
             const void *shard = i > 0 ? b->slot[i & 1] : b->A_or_own_shard;
             st = ag_step_impl(r, i, shard, b->W, b->O, cs, &job);
+        } else if (kind == CF_KIND_RS_PAIR) {
+            if (!serial && do_copy && b->peer_sink != nullptr && i >= 2 && i < p - 1)
+                CF_HIP(hipStreamWaitEvent(cs, sunk(i - 2), 0));   // B_out slot still being sent
+            float *acc = static_cast<float *>(b->O);
+            const float *recv = i == 0 ? nullptr : (i == 1 ? acc : static_cast<const float *>(b->slot[i & 1]));
+            float *out = i < p - 1 ? b->send_slot[i & 1] : acc;
+            st = rs_pair_step_impl(r, i, b->A_or_own_shard, b->W, recv, acc, out, cs);
+        } else if (kind == CF_KIND_DP_PAIR) {
+            st = dp_pair_step_impl(p, r.rank, i, static_cast<float *>(b->O), r.mc,
+                                   i > 0 ? static_cast<const float *>(b->slot[i & 1]) : nullptr, cs);
         } else {
             st = dp_step_impl(p, r.rank, i, static_cast<float *>(b->O), r.mc,
                               i > 0 ? static_cast<const float *>(b->slot[i & 1]) : nullptr, cs);
@@ -429,12 +542,12 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
             return CF_OK;
         const void *src;
         size_t bytes = slot_bytes;
-        if (kind == CF_KIND_RS) {
+        if (is_rs_kind(kind)) {
             src = b->send_slot[i & 1];
         } else if (kind == CF_KIND_AG) {
             src = i > 0 ? b->slot[i & 1] : b->A_or_own_shard;
         } else {
-            const int l = chunk_index(CF_KIND_DP, p, r.rank, i);
+            const int l = pair ? pair_slice(p, r.rank, i) : chunk_index(CF_KIND_DP, p, r.rank, i);
             src = static_cast<const float *>(b->O) + (int64_t)l * r.mc;
         }
         if (bytes == 0)
@@ -472,7 +585,7 @@ cf_status check_buffers(const Resolved &r, int kind, const cf_buffers *b, uint32
         return fail(CF_ERR_NULL_PTR, "buffers is NULL");
     if (b->O == nullptr)
         return fail(CF_ERR_NULL_PTR, "buffers->O is NULL");
-    if (kind != CF_KIND_DP && (b->A_or_own_shard == nullptr || b->W == nullptr))
+    if (!is_dp_kind(kind) && (b->A_or_own_shard == nullptr || b->W == nullptr))
         return fail(CF_ERR_NULL_PTR, "buffers->A_or_own_shard / W is NULL");
     if (r.p > 1) {
         if (b->slot[0] == nullptr || b->slot[1] == nullptr)
@@ -489,14 +602,14 @@ cf_status check_buffers(const Resolved &r, int kind, const cf_buffers *b, uint32
                     return fail(CF_ERR_NULL_PTR, "peer_sink[%d] is NULL", i);
             }
         }
-        if (kind == CF_KIND_RS) {
+        if (is_rs_kind(kind)) {
             if (b->send_slot[0] == nullptr || b->send_slot[1] == nullptr)
                 return fail(CF_ERR_NULL_PTR, "buffers->send_slot[0..1] must be set for the reduce-scatter path");
             if (b->send_slot[0] == b->send_slot[1])
                 return fail(CF_ERR_INVALID_ARG, "the two send slots must be distinct buffers");
         }
     }
-    if (kind != CF_KIND_DP) {
+    if (!is_dp_kind(kind)) {
         if (r.ldo != r.n)
             return fail(CF_ERR_UNSUPPORTED, "run_schedule needs packed partial sums / outputs (ldo == n)");
         if (kind == CF_KIND_AG && r.lda != r.k)
@@ -521,11 +634,40 @@ const char *commfuse_last_error(void) { return g_err; }
 
 int commfuse_chunk_index(int kind, int p, int rank, int step)
 {
-    if (kind != CF_KIND_RS && kind != CF_KIND_AG && kind != CF_KIND_DP)
+    if (!known_kind(kind))
         return fail(CF_ERR_INVALID_ARG, "kind %d", kind);
     if (p < 1 || rank < 0 || rank >= p || step < 0 || step >= p)
         return fail(CF_ERR_INVALID_ARG, "need p >= 1, rank and step in [0, p)");
+    if (is_pair_kind(kind)) {
+        if (cf_status st = check_pair_p(p))
+            return st;
+        return pair_slice(p, rank, step);
+    }
     return chunk_index(kind, p, rank, step);
+}
+
+int commfuse_pair_partner(int p, int rank, int round)
+{
+    if (p < 2 || (p & 1))
+        return fail(CF_ERR_INVALID_ARG, "the pairwise schedule needs an even p >= 2, not %d", p);
+    if (rank < 0 || rank >= p || round < 1 || round > p - 1)
+        return fail(CF_ERR_INVALID_ARG, "need rank in [0, p) and round in [1, p-1]");
+    return pair_partner(p, rank, round);
+}
+
+cf_status commfuse_rs_pair_step(const cf_layer_desc *desc, int step, const void *A, const void *W,
+                                const float *recv, float *acc, float *out, void *hip_stream)
+{
+    Resolved r;
+    if (cf_status st = resolve(desc, CF_KIND_RS_PAIR, &r))
+        return st;
+    return rs_pair_step_impl(r, step, A, W, recv, acc, out, static_cast<hipStream_t>(hip_stream));
+}
+
+cf_status commfuse_dp_pair_step(int p, int rank, int step, float *bucket, int64_t chunk_elems, const float *recv,
+                                void *hip_stream)
+{
+    return dp_pair_step_impl(p, rank, step, bucket, chunk_elems, recv, static_cast<hipStream_t>(hip_stream));
 }
 
 cf_status commfuse_rs_step(const cf_layer_desc *desc, int step, const void *A, const void *W, const float *recv,
@@ -555,13 +697,19 @@ cf_status commfuse_dp_reduce_step(int p, int rank, int step, float *bucket, int6
 cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_buffers *bufs, void *compute_stream,
                                 void *copy_stream, uint32_t flags)
 {
-    if (kind != CF_KIND_RS && kind != CF_KIND_AG && kind != CF_KIND_DP)
+    if (!known_kind(kind))
         return fail(CF_ERR_INVALID_ARG, "kind %d", kind);
     if (flags & ~(uint32_t)(CF_NO_COPY | CF_NO_COMPUTE | CF_SERIAL | CF_POISON | CF_GRAPH | CF_FUSED_COPY | CF_DEVICE_WAIT))
         return fail(CF_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
     Resolved r;
     if (cf_status st = resolve(desc, kind, &r))
         return st;
+    if (is_pair_kind(kind)) {
+        if (cf_status st = check_pair_p(r.p))
+            return st;
+        if (flags & (CF_FUSED_COPY | CF_DEVICE_WAIT))
+            return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY / CF_DEVICE_WAIT are not available for the pairwise kinds");
+    }
     if (flags & CF_DEVICE_WAIT) {
         if (flags & CF_FUSED_COPY)
             return fail(CF_ERR_UNSUPPORTED, "CF_DEVICE_WAIT and CF_FUSED_COPY exclude each other");
@@ -644,7 +792,7 @@ cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_bu
 size_t commfuse_workspace_bytes(const cf_layer_desc *desc, int kind)
 {
     Resolved r;
-    if (kind != CF_KIND_RS && kind != CF_KIND_AG)
+    if (kind != CF_KIND_RS && kind != CF_KIND_AG && kind != CF_KIND_RS_PAIR)
         return 0;                                  // the gradient path needs none
     if (resolve(desc, kind, &r) != CF_OK || !r.bf16_in)
         return 0;

@@ -154,3 +154,40 @@ class Workspace:
         torch.cuda.synchronize()
         cf.set_workspace(None)
         return False
+
+
+class RsPairRun(RsRun):
+    """One GEMM + reduce-scatter rank step under the pairwise bidirectional schedule.
+    ``data["R"][t]`` stands for what the partner of round ``t`` delivers."""
+
+    def run_steps(self):
+        """Calls commfuse_rs_pair_step once per step; returns every step's output (the sent partials, then O)."""
+        p = self.w.p
+        outs = []
+        acc = torch.full((self.w.m_chunk, self.w.n), float("nan"), dtype=torch.float32, device=DEV)
+        for i in range(p):
+            out = torch.full((self.w.m_chunk, self.w.n), float("nan"), dtype=torch.float32, device=DEV)
+            recv = self.stage[i - 1] if i > 0 else None
+            cf.rs_pair_step(self.desc, i, self.A, self.W, recv, acc if p > 2 else None, out, None)
+            outs.append(out)
+        torch.cuda.synchronize()
+        return [to_host_f64(o) for o in outs]
+
+    def run_schedule(self, flags=0):
+        cf.run_schedule(self.desc, cf.CF_KIND_RS_PAIR, self.bufs, self.cs, self.xs, flags)
+        self.cs.synchronize()
+
+
+class DpPairRun(DpRun):
+    """The gradient reduce rank step under the pairwise bidirectional schedule."""
+
+    def run_steps(self):
+        for i in range(self.w.p):
+            recv = self.stage[i - 1] if i > 0 else None
+            cf.dp_pair_step(self.w.p, self.rank, i, self.bucket, self.w.m_chunk, recv, None)
+        torch.cuda.synchronize()
+        return to_host_f64(self.bucket)
+
+    def run_schedule(self, flags=0):
+        cf.run_schedule(self.desc, cf.CF_KIND_DP_PAIR, self.bufs, self.cs, self.xs, flags)
+        self.cs.synchronize()

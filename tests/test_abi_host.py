@@ -58,6 +58,50 @@ def test_chunk_index_matches_the_algorithms(lib, p):
             assert ag[i] == (r - i + p) % p            # Alg. 1 index line
 
 
+@pytest.mark.parametrize("p", [2, 4, 6, 8, 12, 16])
+def test_pairwise_partner_is_a_tournament(lib, p):
+    """Appendix A(a): every round is a perfect matching and every pair meets exactly once."""
+    import oracle
+    met = set()
+    for t in range(1, p):
+        for r in range(p):
+            q = cf.pair_partner(p, r, t)
+            assert q == oracle.pair_partner(p, r, t)
+            assert q != r and cf.pair_partner(p, q, t) == r
+            met.add((min(r, q), max(r, q)))
+    assert len(met) == p * (p - 1) // 2
+    for r in range(p):
+        ls = [cf.chunk_index(cf.CF_KIND_RS_PAIR, p, r, i) for i in range(p)]
+        assert ls == [cf.chunk_index(cf.CF_KIND_DP_PAIR, p, r, i) for i in range(p)]
+        assert sorted(ls) == list(range(p)) and ls[-1] == r
+        assert ls[:-1] == [cf.pair_partner(p, r, t) for t in range(1, p)]
+    if p == 4:                                            # the appendix's printed rounds
+        assert [cf.pair_partner(4, 0, t) for t in (1, 2, 3)] == [1, 2, 3]
+        assert [cf.pair_partner(4, 1, t) for t in (1, 2, 3)] == [0, 3, 2]
+
+
+def test_pairwise_bad_arguments(lib):
+    A, W, R, O, ACC = 0x1000, 0x2000, 0x3000, 0x4000, 0x5000
+    assert _status(cf.pair_partner, 3, 0, 1)[0] == cf.CF_ERR_INVALID_ARG        # odd p
+    assert _status(cf.pair_partner, 4, 0, 0)[0] == cf.CF_ERR_INVALID_ARG        # rounds are 1-based
+    assert _status(cf.pair_partner, 4, 0, 4)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.pair_partner, 4, 4, 1)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.chunk_index, cf.CF_KIND_RS_PAIR, 5, 0, 0)[0] == cf.CF_ERR_INVALID_ARG
+    assert cf.chunk_index(cf.CF_KIND_RS_PAIR, 1, 0, 0) == 0
+    good = cf.layer_desc(4, 1, 16, 32, 64)
+    assert _status(cf.rs_pair_step, cf.layer_desc(3, 0, 16, 32, 64), 0, A, W, None, ACC, O)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.rs_pair_step, good, 0, A, W, R, ACC, O)[0] == cf.CF_ERR_NULL_PTR      # nothing received at step 0
+    assert _status(cf.rs_pair_step, good, 1, A, W, None, ACC, O)[0] == cf.CF_ERR_NULL_PTR
+    assert _status(cf.rs_pair_step, good, 2, A, W, R, None, O)[0] == cf.CF_ERR_NULL_PTR     # p > 2 needs acc
+    assert _status(cf.rs_pair_step, good, 2, A, W, R, ACC, ACC)[0] == cf.CF_ERR_INVALID_ARG  # in place before the last step
+    assert _status(cf.rs_pair_step, good, 3, A, W, R, ACC, R)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.rs_pair_step, good, 2, A, W, ACC, ACC, O)[0] == cf.CF_ERR_INVALID_ARG  # recv == acc only at step 1
+    assert _status(cf.rs_pair_step, cf.layer_desc(4, 1, 16, 32, 64, ldo=40), 2, A, W, R, ACC, O)[0] == cf.CF_ERR_UNSUPPORTED
+    assert _status(cf.dp_pair_step, 3, 0, 1, A, 16, R)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.dp_pair_step, 4, 0, 1, None, 16, R)[0] == cf.CF_ERR_NULL_PTR
+    cf.dp_pair_step(4, 0, 0, None, 16, None)             # step 0 enqueues nothing
+
+
 def _status(fn, *a):
     with pytest.raises(cf.CommFuseError) as e:
         fn(*a)

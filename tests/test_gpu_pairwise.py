@@ -1,0 +1,183 @@
+"""Parity of the pairwise bidirectional schedule (Appendix A(a)) on the HIP path with
+the CPU oracle, through the C ABI.  Needs an MI355X: run with ``-m gpu``.
+
+Tolerances as in test_gpu_parity.py; the received partials are summed in fp32 in round
+order, which adds at most (p-1) * 2^-24 relative to the largest partial sum, well inside
+the tight bf16 bound.  Small-integer inputs are compared bit for bit.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_24013_amd import binding as cf
+from paper_2604_24013_amd import inputs
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-5
+TOL_BF16 = 1e-2
+TIGHT_BF16 = 1e-4
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu_and_lib():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    assert os.path.exists(cf.LIB_PATH), "libcommfuse.so must be built in-tree before the GPU run"
+    cf.load()
+    yield
+    torch.cuda.synchronize()
+
+
+def _oracle_pair(w, data, rank):
+    return oracle.rs_pair_rank_steps(inputs.as_f64(data["A"], w.dtype), inputs.as_f64(data["W"], w.dtype),
+                                     [None] + [r.astype(np.float64) for r in data["R"][1:]], w.p, rank)
+
+
+PAIR_SHAPES = [
+    # (p, m_chunk, n, k)
+    (2, 200, 264, 168),     # one round: out = recv + own product, no accumulator
+    (4, 72, 136, 1376),     # the appendix's four devices
+    (6, 130, 72, 96),       # even but not a power of two: circle-method pairing
+    (8, 264, 392, 200),     # several tiles in both directions plus tails
+    (1, 40, 8, 8),          # p = 1: plain GEMM
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("layout", [cf.CF_W_KN, cf.CF_W_NK])
+@pytest.mark.parametrize("shape", PAIR_SHAPES)
+def test_rs_pair_reduced(shape, layout, dtype):
+    p, mc, n, k = shape
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=p, m_chunk=mc, n=n, k=k, dtype=dtype)
+    data = inputs.make_rs(w, salt=11)
+    tol = TOL_F32 if dtype == "f32" else TIGHT_BF16
+    for rank in sorted({0, p // 2, p - 1}):
+        ref = _oracle_pair(w, data, rank)
+        run = H.RsPairRun(w, data, rank, layout, with_sink=True)
+        outs = run.run_steps()
+        for i in range(p):
+            e = H.rel_err(outs[i], ref[i])
+            assert e <= tol, f"rank {rank} step {i}: rel err {e:.3e}"
+            assert not np.isnan(outs[i]).any()
+        for flags in (0, cf.CF_SERIAL, cf.CF_POISON, cf.CF_GRAPH):
+            run.O.fill_(float("nan"))
+            for s in run.sink:
+                s.fill_(float("nan"))
+            run.run_schedule(flags)
+            assert H.rel_err(H.to_host_f64(run.O), ref[-1]) <= tol, f"rank {rank} flags {flags}"
+            for i in range(p - 1):
+                assert H.rel_err(H.to_host_f64(run.sink[i]), ref[i]) <= tol, f"rank {rank} flags {flags} sink {i}"
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_rs_pair_integer_inputs_are_bit_exact(dtype):
+    p, mc, n, k = 4, 136, 264, 200
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=p, m_chunk=mc, n=n, k=k, dtype=dtype)
+    rng = np.random.default_rng(78)
+    A = inputs.small_int_like((p * mc, k), rng)
+    W = inputs.small_int_like((k, n), rng)
+    R = [None] + [inputs.small_int_like((mc, n), rng, -50, 50) for _ in range(p - 1)]
+    data = {"A": inputs._as_dtype(A, dtype), "W": inputs._as_dtype(W, dtype), "R": R}
+    for rank in range(p):
+        ref = _oracle_pair(w, data, rank)
+        run = H.RsPairRun(w, data, rank)
+        outs = run.run_steps()
+        for i in range(p):
+            assert np.array_equal(outs[i], ref[i]), f"rank {rank} step {i}"
+        run.run_schedule(0)
+        assert np.array_equal(H.to_host_f64(run.O), ref[-1])
+
+
+def test_rs_pair_steps_address_the_partner_slices():
+    """Step i of rank r multiplies the slice of the partner of round i+1 (the appendix's table for p = 4)."""
+    p, mc, n, k = 4, 8, 8, 8
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=p, m_chunk=mc, n=n, k=k)
+    # slice l of A is the constant l+1, W the identity: step output = l+1 everywhere
+    A = np.concatenate([np.full((mc, k), float(l + 1), dtype=np.float32) for l in range(p)])
+    data = {"A": inputs._as_dtype(A, "bf16"), "W": inputs._as_dtype(np.eye(k, dtype=np.float32), "bf16"),
+            "R": [None] + [np.zeros((mc, n), dtype=np.float32) for _ in range(p - 1)]}
+    table = {0: [1, 2, 3, 0], 1: [0, 3, 2, 1], 2: [3, 0, 1, 2], 3: [2, 1, 0, 3]}   # A<->B, A<->C, A<->D ... then own
+    for rank in range(p):
+        outs = H.RsPairRun(w, data, rank).run_steps()
+        assert [int(o[0, 0]) - 1 for o in outs] == table[rank]
+        assert [cf.chunk_index(cf.CF_KIND_RS_PAIR, p, rank, i) for i in range(p)] == table[rank]
+
+
+@pytest.mark.parametrize("p,c", [(8, 1_000_003), (4, 4096), (2, 5), (1, 64), (6, 262144)])
+def test_dp_pair_reduced(p, c):
+    w = inputs.scaled(inputs.CONFIGS["c5_dp"], p=p, m_chunk=c)
+    rank = p - 1
+    # integer-valued gradients: every fp32 sum is exact, so the comparison is bit for bit
+    rng = np.random.default_rng(5 * p + 1)
+    data = {"bucket": inputs.small_int_like((p * c,), rng, -1000, 1000),
+            "R": [None] + [inputs.small_int_like((c,), rng, -1000, 1000) for _ in range(p - 1)]}
+    ref = oracle.dp_pair_rank(data["bucket"], data["R"], p, rank)
+    got = H.DpPairRun(w, data, rank).run_steps()
+    assert np.array_equal(got, ref)
+    run = H.DpPairRun(w, data, rank, with_sink=True)
+    run.run_schedule()
+    assert np.array_equal(H.to_host_f64(run.bucket), ref)
+    for i in range(p - 1):
+        l = oracle.slice_index_pair(p, rank, i)
+        assert np.array_equal(H.to_host_f64(run.sink[i]), data["bucket"][l * c:(l + 1) * c].astype(np.float64))
+    # normally distributed gradients: p-1 fp32 additions in round order
+    data = inputs.make_dp(w, salt=9)
+    ref = oracle.dp_pair_rank(data["bucket"], data["R"], p, rank)
+    got = H.DpPairRun(w, data, rank).run_steps()
+    scale = max(1.0, float(np.abs(ref).max()))
+    assert np.max(np.abs(got - ref)) <= (p - 1) * 2.0 ** -24 * scale * 2
+
+
+def _sample_rows(mc, rng, extra=6):
+    fixed = {0, 1, mc - 1, mc // 2, min(255, mc - 1), min(256, mc - 1), min(127, mc - 1), min(128, mc - 1)}
+    fixed |= set(int(x) for x in rng.integers(0, mc, size=extra))
+    return sorted(fixed)
+
+
+@pytest.mark.parametrize("flags", [0, cf.CF_GRAPH])
+@pytest.mark.parametrize("name", ["c2_rs_7b", "c4_rs_70b_down"])
+def test_full_size_rs_pair(name, flags):
+    w = inputs.CONFIGS[name]
+    data = inputs.make_rs(w, salt=12)
+    rank = 5
+    run = H.RsPairRun(w, data, rank, with_sink=True)
+    with H.Workspace(run.desc, cf.CF_KIND_RS_PAIR):       # as the benchmark runs it
+        run.run_schedule(flags)
+    W64 = inputs.as_f64(data["W"], w.dtype)
+    rng = np.random.default_rng(2)
+    for i in range(w.p):
+        l = oracle.slice_index_pair(w.p, rank, i)
+        rows = _sample_rows(w.m_chunk, rng)
+        Arows = inputs.as_f64(data["A"][[l * w.m_chunk + r for r in rows]], w.dtype)
+        ref = oracle.gemm(Arows, W64)
+        if i == w.p - 1:
+            acc = None
+            for t in range(1, w.p):
+                got_t = data["R"][t][rows].astype(np.float64)
+                acc = got_t if acc is None else oracle.add(acc, got_t)
+            ref = oracle.add(acc, ref)
+        got_full = H.to_host_f64(run.sink[i] if i < w.p - 1 else run.O)
+        assert not np.isnan(got_full).any()
+        e = H.rel_err(got_full[rows], ref)
+        assert e <= TOL_BF16 and e <= TIGHT_BF16, f"step {i}: {e:.3e}"
+
+
+def test_pair_rejects_what_it_cannot_do():
+    d = cf.layer_desc(3, 0, 64, 64, 64)
+    t = torch.zeros(64 * 64 * 3, dtype=torch.float32, device=H.DEV)
+    with pytest.raises(cf.CommFuseError) as ei:
+        cf.rs_pair_step(d, 0, t, t, None, t, t, None)            # odd p
+    assert ei.value.status == cf.CF_ERR_INVALID_ARG
+    d = cf.layer_desc(4, 0, 64, 64, 64)
+    with pytest.raises(cf.CommFuseError):
+        cf.rs_pair_step(d, 1, t, t, t[:4096], t[4096:8192], t[4096:8192], None)   # out aliases acc before the last step
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=4, m_chunk=64, n=64, k=64)
+    run = H.RsPairRun(w, inputs.make_rs(w), 0)
+    for flags in (cf.CF_FUSED_COPY, cf.CF_DEVICE_WAIT):
+        with pytest.raises(cf.CommFuseError) as ei:
+            run.run_schedule(flags)
+        assert ei.value.status == cf.CF_ERR_UNSUPPORTED
