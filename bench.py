@@ -180,9 +180,13 @@ def main() -> int:
     if not args.only_pair:
         for name in ("c2_rs_7b", "c4_rs_70b_down"):
             w = inputs.CONFIGS[name]
-            run = H.RsPairRun(w, inputs.make_rs(w), 0)
+            data = inputs.make_rs(w)
+            run = H.RsPairRun(w, data, 0)
+            t_inc = schedule_times(run, cf.CF_KIND_RS_PAIR, max(K, 50), W)
+            del run
+            run = H.RsPairRun(w, data, 0, keep_all=True)        # every arrival kept, summed by the last step
             t = schedule_times(run, cf.CF_KIND_RS_PAIR, max(K, 50), W)
-            pairwise[name] = {"tflops": round(w.flops / (t["overlapped"][0] * 1e-3) / 1e12, 1),
+            pairwise[name] = {"us_per_rank_step_incremental_aggregation": round(t_inc["overlapped"][0] * 1e3, 1),"tflops": round(w.flops / (t["overlapped"][0] * 1e-3) / 1e12, 1),
                               "us_per_rank_step": round(t["overlapped"][0] * 1e3, 1), "mode": t["overlapped"][1],
                               "overlap_eff": round(overlap_eff(t), 3),
                               "us_compute_only": round(t["compute_only"][0] * 1e3, 1),

@@ -119,8 +119,9 @@ cf_status commfuse_rs_step(const cf_layer_desc *desc, int step, const void *A, c
  *                                       arrival initialises acc)
  *     step <  p-1:  out = A[l] @ W     (l = partner of round step+1; sent to l)
  *     step == p-1:  out = acc + A[rank] @ W        (the reduced slice O^r)
- *   recv [m_chunk x n] fp32; NULL iff step == 0.  At step 1 recv may equal acc
- *        ("received in place"): then nothing is copied.
+ *   recv [m_chunk x n] fp32; NULL at step 0.  At step 1 recv may equal acc
+ *        ("received in place"): then nothing is copied.  At 1 <= step < p-1, recv and
+ *        acc both NULL defers the aggregation to commfuse_rs_pair_last_step.
  *   acc  [m_chunk x n] fp32 accumulator of received partials, required when p > 2
  *        (for p == 2 it is ignored: out = recv + A[rank] @ W).  The accumulate is a
  *        separate elementwise kernel enqueued before the GEMM and needs ldo == n.
@@ -128,6 +129,22 @@ cf_status commfuse_rs_step(const cf_layer_desc *desc, int step, const void *A, c
  */
 cf_status commfuse_rs_pair_step(const cf_layer_desc *desc, int step, const void *A, const void *W,
                                 const float *recv, float *acc, float *out, void *hip_stream);
+
+/* The last iteration (step p-1) of the pairwise schedule with the aggregation deferred
+ * to the end (Sec. 3.2 leaves open whether the received buffers are summed at the end
+ * or incrementally inside the loop): every round's arrival was kept in a buffer of its
+ * own, and
+ *     out = ((recv_each[0] + recv_each[1]) + ... + recv_each[p-2]) + A[rank] @ W
+ * -- the same order of fp32 additions as the incremental form, so both give the same
+ * bits.  For bf16 operands the sum runs in the GEMM's epilogue (each received buffer
+ * is read once and nothing is written in between); otherwise `out` serves as the
+ * accumulator of elementwise passes before an in-place GEMM.
+ *   recv_each HOST array of p-1 DEVICE pointers, [m_chunk x n] fp32 each, row stride
+ *             ldo (ldo == n required when p > 2), in round order; unused when p == 1.
+ *             None may alias out.
+ * The steps before it are commfuse_rs_pair_step calls with recv = acc = NULL. */
+cf_status commfuse_rs_pair_last_step(const cf_layer_desc *desc, const void *A, const void *W,
+                                     const float *const *recv_each, float *out, void *hip_stream);
 
 /* One iteration i of Alg. 1 (the compute on the slice in hand):
  *     O[l*m_chunk : (l+1)*m_chunk, :] = shard @ W
@@ -173,6 +190,11 @@ typedef struct {
     void *const *peer_sink;       /* optional host array of p-1 device pointers receiving the
                                      emulated sends of steps 0..p-2 (RS: B_out, AG: the slice
                                      in hand, DP: slice l); NULL = sends are not copied        */
+    void *const *recv_each;       /* CF_KIND_RS_PAIR only, optional (NULL otherwise): host array
+                                     of p-1 device buffers [m_chunk x n] fp32, one per round.
+                                     When set, round t's delivery lands in recv_each[t-1], no
+                                     step accumulates, and the last step adds them all in its
+                                     epilogue (commfuse_rs_pair_last_step); slot[] is unused    */
 } cf_buffers;
 
 enum {
@@ -208,8 +230,9 @@ enum {
  * what the partner of round t delivers (its partial / copy of this rank's slice);
  * CF_KIND_RS_PAIR accumulates in O itself (the delivery of round 1 lands in O, later
  * ones in slot[t % 2] and are added to O before the step's GEMM; the last GEMM adds
- * its product to O in place); peer_sink[i] receives what step i sends to the partner
- * of round i+1.  CF_FUSED_COPY and CF_DEVICE_WAIT are not available for them. */
+ * its product to O in place), or, with recv_each set, keeps every arrival and sums
+ * them in the last GEMM's epilogue; peer_sink[i] receives what step i sends to the
+ * partner of round i+1.  CF_FUSED_COPY and CF_DEVICE_WAIT are not available for them. */
 cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_buffers *bufs,
                                 void *compute_stream, void *copy_stream, uint32_t flags);
 

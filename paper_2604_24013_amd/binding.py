@@ -25,7 +25,7 @@ KINDS = {"rs": CF_KIND_RS, "ag": CF_KIND_AG, "dp": CF_KIND_DP, "rs_pair": CF_KIN
 DTYPES = {"bf16": CF_BF16, "f32": CF_F32}
 
 EXPORTS = [
-    "commfuse_chunk_index", "commfuse_pair_partner", "commfuse_rs_pair_step", "commfuse_dp_pair_step", "commfuse_rs_step", "commfuse_ag_step", "commfuse_dp_reduce_step",
+    "commfuse_chunk_index", "commfuse_pair_partner", "commfuse_rs_pair_step", "commfuse_rs_pair_last_step", "commfuse_dp_pair_step", "commfuse_rs_step", "commfuse_ag_step", "commfuse_dp_reduce_step",
     "commfuse_run_schedule", "commfuse_last_error", "commfuse_workspace_bytes", "commfuse_set_workspace",
     "commfuse_device_status",
     "commfuse_destroy_cache", "commfuse_version",
@@ -48,6 +48,7 @@ class Buffers(ctypes.Structure):
         ("peer_stage", ctypes.POINTER(ctypes.c_void_p)),
         ("slot", ctypes.c_void_p * 2), ("send_slot", ctypes.c_void_p * 2),
         ("peer_sink", ctypes.POINTER(ctypes.c_void_p)),
+        ("recv_each", ctypes.POINTER(ctypes.c_void_p)),
     ]
 
 
@@ -83,6 +84,8 @@ def load():
     lib.commfuse_pair_partner.restype = i32
     lib.commfuse_rs_pair_step.argtypes = [ctypes.POINTER(LayerDesc), i32, vp, vp, vp, vp, vp, vp]
     lib.commfuse_rs_pair_step.restype = i32
+    lib.commfuse_rs_pair_last_step.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, ctypes.POINTER(ctypes.c_void_p), vp, vp]
+    lib.commfuse_rs_pair_last_step.restype = i32
     lib.commfuse_dp_pair_step.argtypes = [i32, i32, i32, vp, i64, vp, vp]
     lib.commfuse_dp_pair_step.restype = i32
     lib.commfuse_run_schedule.argtypes = [ctypes.POINTER(LayerDesc), i32, ctypes.POINTER(Buffers), vp, vp, ctypes.c_uint32]
@@ -164,6 +167,13 @@ def rs_pair_step(desc: LayerDesc, step: int, A, W, recv, acc, out, stream=None) 
                                         _stream(stream)))
 
 
+def rs_pair_last_step(desc: LayerDesc, A, W, recv_each: Sequence, out, stream=None) -> None:
+    n = len(recv_each)
+    table = (ctypes.c_void_p * max(n, 1))(*[_ptr(t) for t in recv_each])
+    arg = ctypes.cast(table, ctypes.POINTER(ctypes.c_void_p)) if n else None
+    _check(load().commfuse_rs_pair_last_step(ctypes.byref(desc), _ptr(A), _ptr(W), arg, _ptr(out), _stream(stream)))
+
+
 def dp_pair_step(p: int, rank: int, step: int, bucket, chunk_elems: int, recv, stream=None) -> None:
     _check(load().commfuse_dp_pair_step(p, rank, step, _ptr(bucket), chunk_elems, _ptr(recv), _stream(stream)))
 
@@ -181,7 +191,7 @@ def dp_reduce_step(p: int, rank: int, step: int, bucket, chunk_elems: int, recv,
 
 
 def make_buffers(A_or_own_shard, W, O, peer_stage: Sequence, slot: Sequence, send_slot: Sequence = (None, None),
-                 peer_sink: Optional[Sequence] = None) -> Buffers:
+                 peer_sink: Optional[Sequence] = None, recv_each: Optional[Sequence] = None) -> Buffers:
     """Fills a ``cf_buffers``.  The returned object keeps the pointer tables alive;
     the caller keeps the tensors alive."""
     b = Buffers()
@@ -198,6 +208,12 @@ def make_buffers(A_or_own_shard, W, O, peer_stage: Sequence, slot: Sequence, sen
         b._sink_keepalive = sink
     else:
         b.peer_sink = None
+    if recv_each is not None and len(recv_each):
+        each = (ctypes.c_void_p * len(recv_each))(*[_ptr(t) for t in recv_each])
+        b.recv_each = ctypes.cast(each, ctypes.POINTER(ctypes.c_void_p))
+        b._each_keepalive = each
+    else:
+        b.recv_each = None
     return b
 
 

@@ -12,6 +12,11 @@ struct GemmParams {
     const void *A;
     const void *W;
     const float *recv;   // nullable: B_in of Alg. 2
+    // further received partials, added after `recv` in index order before the product is added
+    // (pairwise schedule with the aggregation deferred to the last step; direct-to-LDS bf16 kernel only)
+    static constexpr int MAX_RECV_MORE = 15;
+    const float *recv_more[MAX_RECV_MORE] = {};
+    int n_recv_more = 0;
     void *out;
     int64_t lda, ldw, ldo;
     int M, N, K;
@@ -47,6 +52,8 @@ struct TileChoice {
 TileChoice choose_tile_bf16(int M, int N, int K, int num_cu);
 
 hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, int num_cu);
+// True if launch_gemm_bf16 would run the kernel that honours GemmParams::recv_more for these operands.
+bool gemm_bf16_takes_recv_list(const GemmParams &p, bool w_kn);
 // Direct-to-LDS variant of the bf16 kernel (operand extents below 2^31 bytes).
 bool gemm_bf16_dl_supported(const GemmParams &p, bool w_kn);
 hipError_t launch_gemm_bf16_dl(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, TileChoice t);

@@ -207,20 +207,29 @@ bool step_can_carry_copy(const Resolved &r)
     return r.mc * r.lda * 2 < lim && (r.w_kn ? r.k : r.n) * r.ldw * 2 < lim && r.mc * r.ldo * 4 < lim;
 }
 
-cf_status launch_gemm(const Resolved &r, const void *A_rows, const void *W, const float *recv, void *out,
-                      hipStream_t s, const CopyJob *job = nullptr)
+void fill_shape(cf::GemmParams &gp, const Resolved &r)
 {
-    cf::GemmParams gp;
-    gp.A = A_rows;
-    gp.W = W;
-    gp.recv = recv;
-    gp.out = out;
     gp.lda = r.lda;
     gp.ldw = r.ldw;
     gp.ldo = r.ldo;
     gp.M = (int)r.mc;
     gp.N = (int)r.n;
     gp.K = (int)r.k;
+}
+
+cf_status launch_gemm(const Resolved &r, const void *A_rows, const void *W, const float *recv, void *out,
+                      hipStream_t s, const CopyJob *job = nullptr, const float *const *recv_more = nullptr,
+                      int n_recv_more = 0)
+{
+    cf::GemmParams gp;
+    for (int b = 0; b < n_recv_more; ++b)
+        gp.recv_more[b] = recv_more[b];
+    gp.n_recv_more = n_recv_more;
+    gp.A = A_rows;
+    gp.W = W;
+    gp.recv = recv;
+    gp.out = out;
+    fill_shape(gp, r);
     {
         std::lock_guard<std::mutex> lk(g_ws_mu);
         if (g_ws.ptr != nullptr && g_ws.bytes > WS_COUNTER_BYTES) {
@@ -328,14 +337,15 @@ cf_status rs_pair_step_impl(const Resolved &r, int step, const void *A, const vo
         return fail(CF_ERR_NULL_PTR, "A, W and out must not be NULL");
     if (step == 0 && recv != nullptr)
         return fail(CF_ERR_NULL_PTR, "recv must be NULL at step 0 (nothing has been received yet)");
-    if (step > 0 && recv == nullptr)
+    const bool last = step == r.p - 1;
+    const bool deferred = step > 0 && !last && recv == nullptr && acc == nullptr;   // summed by the last step
+    if (step > 0 && recv == nullptr && !deferred)
         return fail(CF_ERR_NULL_PTR, "recv must not be NULL at step %d", step);
-    if (r.p > 2 && step > 0 && acc == nullptr)
+    if (r.p > 2 && step > 0 && acc == nullptr && !deferred)
         return fail(CF_ERR_NULL_PTR, "acc must not be NULL at step %d when p > 2", step);
     if (!aligned16(A) || !aligned16(W) || !aligned16(out) || !aligned16(recv) || !aligned16(acc))
         return fail(CF_ERR_MISALIGNED, "tensor pointers must be 16-byte aligned");
-    const bool last = step == r.p - 1;
-    const bool use_acc = r.p > 2;
+    const bool use_acc = r.p > 2 && !deferred;
     if (use_acc && r.ldo != r.n)
         return fail(CF_ERR_UNSUPPORTED, "the pairwise accumulate needs packed partial sums (ldo == n)");
     // in place is fine for the buffer the last step's epilogue adds (every element is read, then written,
@@ -358,6 +368,50 @@ cf_status rs_pair_step_impl(const Resolved &r, int step, const void *A, const vo
     const char *a_rows = static_cast<const char *>(A) + (size_t)l * r.mc * r.lda * in_elem(r);
     const float *add = !last ? nullptr : (use_acc ? acc : recv);   // p == 1: recv is NULL at step 0
     return launch_gemm(r, a_rows, W, add, out, s);
+}
+
+// Last step of the pairwise schedule with every round's arrival kept: out = (sum of arrivals) + own product.
+cf_status rs_pair_last_step_impl(const Resolved &r, const void *A, const void *W, const float *const *recv_each,
+                                 float *out, hipStream_t s)
+{
+    if (cf_status st = check_pair_p(r.p))
+        return st;
+    if (A == nullptr || W == nullptr || out == nullptr)
+        return fail(CF_ERR_NULL_PTR, "A, W and out must not be NULL");
+    const int count = r.p - 1;
+    if (count > 0 && recv_each == nullptr)
+        return fail(CF_ERR_NULL_PTR, "recv_each must not be NULL when p > 1");
+    if (!aligned16(A) || !aligned16(W) || !aligned16(out))
+        return fail(CF_ERR_MISALIGNED, "tensor pointers must be 16-byte aligned");
+    for (int t = 0; t < count; ++t) {
+        if (recv_each[t] == nullptr)
+            return fail(CF_ERR_NULL_PTR, "recv_each[%d] is NULL", t);
+        if (!aligned16(recv_each[t]))
+            return fail(CF_ERR_MISALIGNED, "tensor pointers must be 16-byte aligned");
+        if (recv_each[t] == out)
+            return fail(CF_ERR_INVALID_ARG, "recv_each[%d] aliases out", t);
+    }
+    if (count > 1 && r.ldo != r.n)
+        return fail(CF_ERR_UNSUPPORTED, "summing several received partials needs packed rows (ldo == n)");
+    const char *a_rows = static_cast<const char *>(A) + (size_t)r.rank * r.mc * r.lda * in_elem(r);
+    if (count <= 1)
+        return launch_gemm(r, a_rows, W, count ? recv_each[0] : nullptr, out, s);
+    cf::GemmParams probe;
+    probe.A = a_rows;
+    probe.W = W;
+    probe.out = out;
+    fill_shape(probe, r);
+    if (r.bf16_in && count - 1 <= cf::GemmParams::MAX_RECV_MORE && cf::gemm_bf16_takes_recv_list(probe, r.w_kn))
+        return launch_gemm(r, a_rows, W, recv_each[0], out, s, nullptr, recv_each + 1, count - 1);
+    // other kernels: sum the arrivals in `out` with elementwise passes, then add the product in place
+    const size_t elems = (size_t)r.mc * r.n;
+    if (elems == 0)
+        return CF_OK;
+    CF_HIP(hipMemcpyAsync(out, recv_each[0], elems * sizeof(float), hipMemcpyDeviceToDevice, s));
+    for (int t = 1; t < count; ++t)
+        if (cf_status st = accumulate(out, recv_each[t], (int64_t)elems, s))
+            return st;
+    return launch_gemm(r, a_rows, W, out, out, s);
 }
 
 cf_status dp_pair_step_impl(int p, int rank, int step, float *bucket, int64_t chunk_elems, const float *recv,
@@ -435,6 +489,7 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
     const bool poison = (flags & CF_POISON) != 0;
 
     const bool pair = is_pair_kind(kind);
+    const bool keep_all = kind == CF_KIND_RS_PAIR && b->recv_each != nullptr && p > 1;   // deferred aggregation
     size_t slot_bytes;
     if (is_rs_kind(kind))
         slot_bytes = (size_t)r.mc * r.n * sizeof(float);
@@ -466,10 +521,11 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
     auto deliver = [&](int i) -> cf_status {
         if (!(i + 1 < p && do_copy) || fused)
             return CF_OK;
-        // pairwise reduce-scatter: the first arrival initialises the accumulator, which is O itself
-        void *dst = (kind == CF_KIND_RS_PAIR && i == 0) ? b->O : b->slot[(i + 1) & 1];
+        // pairwise reduce-scatter: every arrival is kept (recv_each), or the first one initialises the
+        // accumulator, which is O itself
+        void *dst = keep_all ? b->recv_each[i] : (kind == CF_KIND_RS_PAIR && i == 0) ? b->O : b->slot[(i + 1) & 1];
         // the slot was last read by the kernel of step i-1 (steps >= 1 read a slot)
-        if (!serial && do_compute && i - 1 >= 1)
+        if (!serial && do_compute && i - 1 >= 1 && !keep_all)
             CF_HIP(hipStreamWaitEvent(xs, done(i - 1), 0));
         if (slot_bytes == 0)
             return CF_OK;
@@ -492,8 +548,8 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
     auto kernel = [&](int i) -> cf_status {
         if (!do_compute)
             return CF_OK;
-        if (!serial && do_copy && i > 0 && !dwait)
-            CF_HIP(hipStreamWaitEvent(cs, ready(i), 0));
+        if (!serial && do_copy && i > 0 && !dwait && (!keep_all || i == p - 1))
+            CF_HIP(hipStreamWaitEvent(cs, ready(i), 0));   // deliveries are in order on the copy stream
         cf_status st = CF_OK;
         CopyJob job;
         if (dwait && !serial && i > 0) {           // the kernel itself waits for the delivery of step i
@@ -521,7 +577,13 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
             float *acc = static_cast<float *>(b->O);
             const float *recv = i == 0 ? nullptr : (i == 1 ? acc : static_cast<const float *>(b->slot[i & 1]));
             float *out = i < p - 1 ? b->send_slot[i & 1] : acc;
-            st = rs_pair_step_impl(r, i, b->A_or_own_shard, b->W, recv, acc, out, cs);
+            if (!keep_all)
+                st = rs_pair_step_impl(r, i, b->A_or_own_shard, b->W, recv, acc, out, cs);
+            else if (i < p - 1)
+                st = rs_pair_step_impl(r, i, b->A_or_own_shard, b->W, nullptr, nullptr, out, cs);
+            else
+                st = rs_pair_last_step_impl(r, b->A_or_own_shard, b->W,
+                                            reinterpret_cast<const float *const *>(b->recv_each), acc, cs);
         } else if (kind == CF_KIND_DP_PAIR) {
             st = dp_pair_step_impl(p, r.rank, i, static_cast<float *>(b->O), r.mc,
                                    i > 0 ? static_cast<const float *>(b->slot[i & 1]) : nullptr, cs);
@@ -587,11 +649,20 @@ cf_status check_buffers(const Resolved &r, int kind, const cf_buffers *b, uint32
         return fail(CF_ERR_NULL_PTR, "buffers->O is NULL");
     if (!is_dp_kind(kind) && (b->A_or_own_shard == nullptr || b->W == nullptr))
         return fail(CF_ERR_NULL_PTR, "buffers->A_or_own_shard / W is NULL");
+    if (b->recv_each != nullptr && kind != CF_KIND_RS_PAIR)
+        return fail(CF_ERR_INVALID_ARG, "buffers->recv_each is for CF_KIND_RS_PAIR only");
+    const bool keep_all = kind == CF_KIND_RS_PAIR && b->recv_each != nullptr;
     if (r.p > 1) {
-        if (b->slot[0] == nullptr || b->slot[1] == nullptr)
-            return fail(CF_ERR_NULL_PTR, "buffers->slot[0..1] must be set when p > 1");
-        if (b->slot[0] == b->slot[1])
-            return fail(CF_ERR_INVALID_ARG, "the two slots must be distinct buffers");
+        if (keep_all) {
+            for (int i = 0; i < r.p - 1; ++i)
+                if (b->recv_each[i] == nullptr || b->recv_each[i] == b->O)
+                    return fail(CF_ERR_NULL_PTR, "recv_each[%d] is NULL or aliases O", i);
+        } else {
+            if (b->slot[0] == nullptr || b->slot[1] == nullptr)
+                return fail(CF_ERR_NULL_PTR, "buffers->slot[0..1] must be set when p > 1");
+            if (b->slot[0] == b->slot[1])
+                return fail(CF_ERR_INVALID_ARG, "the two slots must be distinct buffers");
+        }
         if (!(flags & CF_NO_COPY)) {
             if (b->peer_stage == nullptr)
                 return fail(CF_ERR_NULL_PTR, "buffers->peer_stage is NULL");
@@ -662,6 +733,15 @@ cf_status commfuse_rs_pair_step(const cf_layer_desc *desc, int step, const void 
     if (cf_status st = resolve(desc, CF_KIND_RS_PAIR, &r))
         return st;
     return rs_pair_step_impl(r, step, A, W, recv, acc, out, static_cast<hipStream_t>(hip_stream));
+}
+
+cf_status commfuse_rs_pair_last_step(const cf_layer_desc *desc, const void *A, const void *W,
+                                     const float *const *recv_each, float *out, void *hip_stream)
+{
+    Resolved r;
+    if (cf_status st = resolve(desc, CF_KIND_RS_PAIR, &r))
+        return st;
+    return rs_pair_last_step_impl(r, A, W, recv_each, out, static_cast<hipStream_t>(hip_stream));
 }
 
 cf_status commfuse_dp_pair_step(int p, int rank, int step, float *bucket, int64_t chunk_elems, const float *recv,
@@ -751,8 +831,10 @@ cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_bu
     for (int i = 0; i < r.p - 1; ++i) {
         const void *st = bufs->peer_stage ? bufs->peer_stage[i] : nullptr;
         const void *sk = bufs->peer_sink ? bufs->peer_sink[i] : nullptr;
+        const void *re = bufs->recv_each ? bufs->recv_each[i] : nullptr;
         append_bytes(key, &st, sizeof(st));
         append_bytes(key, &sk, sizeof(sk));
+        append_bytes(key, &re, sizeof(re));
     }
     hipGraphExec_t exec = nullptr;
     {

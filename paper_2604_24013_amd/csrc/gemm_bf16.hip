@@ -305,6 +305,17 @@ TileChoice choose_tile_bf16(int M, int N, int K, int num_cu)
     return t;
 }
 
+static bool staged_kernel_forced()                   // "staged": the register-staged kernel of this file
+{
+    const char *e = getenv("COMMFUSE_KERNEL");
+    return e != nullptr && strcmp(e, "staged") == 0;
+}
+
+bool gemm_bf16_takes_recv_list(const GemmParams &p, bool w_kn)
+{
+    return p.M > 0 && p.N > 0 && !staged_kernel_forced() && gemm_bf16_dl_supported(p, w_kn);
+}
+
 hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, int num_cu)
 {
     if (p.M <= 0 || p.N <= 0)
@@ -324,11 +335,11 @@ hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipSt
         if (sk >= 1 && sk <= 8)
             t.splitk = sk;
     }
-    bool staged = false;                             // "staged": the register-staged kernel of this file
-    if (const char *e = getenv("COMMFUSE_KERNEL"))
-        staged = strcmp(e, "staged") == 0;
+    const bool staged = staged_kernel_forced();
     if (!staged && gemm_bf16_dl_supported(p, w_kn))
         return launch_gemm_bf16_dl(p, w_kn, out_bf16, s, t);
+    if (p.n_recv_more != 0)
+        return hipErrorInvalidValue;                 // callers ask gemm_bf16_takes_recv_list first
     if (t.bm == 256 && t.bn == 256) return launch_cfg<256, 256, 2, 4>(p, w_kn, out_bf16, s);
     if (t.bm == 256 && t.bn == 128) return launch_cfg<256, 128, 4, 2>(p, w_kn, out_bf16, s);
     return launch_cfg<128, 128, 2, 2>(p, w_kn, out_bf16, s);

@@ -571,7 +571,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     for (int i = 0; i < TM; ++i) {
         const int m = m0 + wm * WTM + i * 32 + (lane & 31);
         unsigned eoff[TN][4];
-        u32x4_t rv[TN][4];
+        f32x4_t rv[TN][4];
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -584,8 +584,25 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int g = 0; g < 4; ++g)
-                    rv[j][g] = __builtin_amdgcn_raw_buffer_load_b128(
-                        r_rsrc, eoff[j][g] == OOB ? (int)OOB : (int)(eoff[j][g] * 4), 0, 0);
+                    rv[j][g] = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                        r_rsrc, eoff[j][g] == OOB ? (int)OOB : (int)(eoff[j][g] * 4), 0, 0));
+            // further received partials, summed in index order: one batch of independent loads per buffer
+            for (int b = 0; b < P.n_recv_more; ++b) {
+                __amdgpu_buffer_rsrc_t m_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<float *>(P.recv_more[b]), 0, (int)r_bytes, 0x00020000);
+                f32x4_t tv[TN][4];
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        tv[j][g] = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                            m_rsrc, eoff[j][g] == OOB ? (int)OOB : (int)(eoff[j][g] * 4), 0, 0));
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g)
+                        rv[j][g] = rv[j][g] + tv[j][g];
+            }
         }
 #pragma unroll
         for (int j = 0; j < TN; ++j)
@@ -597,7 +614,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 o[2] = acc[i][j][4 * g + 2];
                 o[3] = acc[i][j][4 * g + 3];
                 if (has_recv)
-                    o = __builtin_bit_cast(f32x4_t, rv[j][g]) + o;       // "O <- B_in + O"
+                    o = rv[j][g] + o;                                    // "O <- B_in + O"
                 const int boff = eoff[j][g] == OOB ? (int)OOB : (int)(eoff[j][g] * o_elem);
                 if constexpr (OUT_BF16) {
                     bf16x4_t h;

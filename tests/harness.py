@@ -158,7 +158,29 @@ class Workspace:
 
 class RsPairRun(RsRun):
     """One GEMM + reduce-scatter rank step under the pairwise bidirectional schedule.
-    ``data["R"][t]`` stands for what the partner of round ``t`` delivers."""
+    ``data["R"][t]`` stands for what the partner of round ``t`` delivers.  With ``keep_all`` every
+    round's arrival has a buffer of its own and the last step sums them (deferred aggregation)."""
+
+    def __init__(self, w, data, rank, w_layout=cf.CF_W_KN, with_sink=False, keep_all=False):
+        super().__init__(w, data, rank, w_layout, with_sink)
+        self.each = None
+        if keep_all:
+            self.each = [torch.full((w.m_chunk, w.n), float("nan"), dtype=torch.float32, device=DEV) for _ in range(w.p - 1)]
+            self.bufs = cf.make_buffers(self.A, self.W, self.O, self.stage, (None, None), self.send, self.sink, self.each)
+
+    def run_steps_deferred(self):
+        """Steps with recv = acc = NULL, then commfuse_rs_pair_last_step over the staged arrivals."""
+        p = self.w.p
+        outs = []
+        for i in range(p):
+            out = torch.full((self.w.m_chunk, self.w.n), float("nan"), dtype=torch.float32, device=DEV)
+            if i < p - 1:
+                cf.rs_pair_step(self.desc, i, self.A, self.W, None, None, out, None)
+            else:
+                cf.rs_pair_last_step(self.desc, self.A, self.W, self.stage, out, None)
+            outs.append(out)
+        torch.cuda.synchronize()
+        return [to_host_f64(o) for o in outs]
 
     def run_steps(self):
         """Calls commfuse_rs_pair_step once per step; returns every step's output (the sent partials, then O)."""

@@ -38,7 +38,7 @@ def test_struct_layout_matches_header():
     # cf_layer_desc: 2 x int32, 6 x int64, 4 x int32 = 72 bytes; cf_buffers: 9 pointers
     assert ctypes.sizeof(cf.LayerDesc) == 72
     assert cf.LayerDesc.m_chunk.offset == 8 and cf.LayerDesc.in_dtype.offset == 56
-    assert ctypes.sizeof(cf.Buffers) == 9 * ctypes.sizeof(ctypes.c_void_p)
+    assert ctypes.sizeof(cf.Buffers) == 10 * ctypes.sizeof(ctypes.c_void_p)
 
 
 def test_version(lib):
@@ -100,6 +100,12 @@ def test_pairwise_bad_arguments(lib):
     assert _status(cf.dp_pair_step, 3, 0, 1, A, 16, R)[0] == cf.CF_ERR_INVALID_ARG
     assert _status(cf.dp_pair_step, 4, 0, 1, None, 16, R)[0] == cf.CF_ERR_NULL_PTR
     cf.dp_pair_step(4, 0, 0, None, 16, None)             # step 0 enqueues nothing
+    assert _status(cf.rs_pair_step, good, 3, A, W, None, None, O)[0] == cf.CF_ERR_NULL_PTR   # the last step cannot defer
+    assert _status(cf.rs_pair_last_step, good, A, W, [], O)[0] == cf.CF_ERR_NULL_PTR
+    assert _status(cf.rs_pair_last_step, good, A, W, [R, None, ACC], O)[0] == cf.CF_ERR_NULL_PTR
+    assert _status(cf.rs_pair_last_step, good, A, W, [R, O, ACC], O)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.rs_pair_last_step, cf.layer_desc(3, 0, 16, 32, 64), A, W, [R, ACC], O)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.rs_pair_last_step, cf.layer_desc(4, 1, 16, 32, 64, ldo=40), A, W, [R, ACC, 0x6000], O)[0] == cf.CF_ERR_UNSUPPORTED
 
 
 def _status(fn, *a):

@@ -63,14 +63,38 @@ def test_rs_pair_reduced(shape, layout, dtype):
             e = H.rel_err(outs[i], ref[i])
             assert e <= tol, f"rank {rank} step {i}: rel err {e:.3e}"
             assert not np.isnan(outs[i]).any()
-        for flags in (0, cf.CF_SERIAL, cf.CF_POISON, cf.CF_GRAPH):
-            run.O.fill_(float("nan"))
-            for s in run.sink:
-                s.fill_(float("nan"))
-            run.run_schedule(flags)
-            assert H.rel_err(H.to_host_f64(run.O), ref[-1]) <= tol, f"rank {rank} flags {flags}"
-            for i in range(p - 1):
-                assert H.rel_err(H.to_host_f64(run.sink[i]), ref[i]) <= tol, f"rank {rank} flags {flags} sink {i}"
+        # aggregation deferred to the last step: same additions in the same order, so the same bits
+        outs_d = run.run_steps_deferred()
+        for i in range(p):
+            assert np.array_equal(outs_d[i], outs[i]), f"rank {rank} step {i} (deferred)"
+        keep = H.RsPairRun(w, data, rank, layout, with_sink=True, keep_all=True)
+        for r_ in (run, keep):
+            for flags in (0, cf.CF_SERIAL, cf.CF_POISON, cf.CF_GRAPH):
+                r_.O.fill_(float("nan"))
+                for s in r_.sink:
+                    s.fill_(float("nan"))
+                r_.run_schedule(flags)
+                assert np.array_equal(H.to_host_f64(r_.O), outs[-1]), f"rank {rank} flags {flags}"
+                for i in range(p - 1):
+                    assert np.array_equal(H.to_host_f64(r_.sink[i]), outs[i]), f"rank {rank} flags {flags} sink {i}"
+
+
+def test_rs_pair_deferred_with_the_staged_kernel():
+    """The register-staged bf16 kernel takes no list of arrivals: they are summed in `out` first."""
+    p, mc, n, k = 4, 136, 264, 200
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=p, m_chunk=mc, n=n, k=k)
+    data = inputs.make_rs(w, salt=13)
+    ref = _oracle_pair(w, data, 2)
+    os.environ["COMMFUSE_KERNEL"] = "staged"
+    try:
+        run = H.RsPairRun(w, data, 2, keep_all=True)
+        outs = run.run_steps_deferred()
+        run.run_schedule(0)
+    finally:
+        os.environ.pop("COMMFUSE_KERNEL", None)
+    for i in range(p):
+        assert H.rel_err(outs[i], ref[i]) <= TIGHT_BF16
+    assert np.array_equal(H.to_host_f64(run.O), outs[-1])
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
@@ -138,13 +162,14 @@ def _sample_rows(mc, rng, extra=6):
     return sorted(fixed)
 
 
+@pytest.mark.parametrize("keep_all", [False, True])
 @pytest.mark.parametrize("flags", [0, cf.CF_GRAPH])
 @pytest.mark.parametrize("name", ["c2_rs_7b", "c4_rs_70b_down"])
-def test_full_size_rs_pair(name, flags):
+def test_full_size_rs_pair(name, flags, keep_all):
     w = inputs.CONFIGS[name]
     data = inputs.make_rs(w, salt=12)
     rank = 5
-    run = H.RsPairRun(w, data, rank, with_sink=True)
+    run = H.RsPairRun(w, data, rank, with_sink=True, keep_all=keep_all)
     with H.Workspace(run.desc, cf.CF_KIND_RS_PAIR):       # as the benchmark runs it
         run.run_schedule(flags)
     W64 = inputs.as_f64(data["W"], w.dtype)
