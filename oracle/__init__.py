@@ -450,3 +450,117 @@ def dp_pair_rank(bucket, R: Sequence[Optional[np.ndarray]], p: int, r: int) -> n
     for t in range(1, p):
         out[r * c:(r + 1) * c] = add(_f64(R[t]), out[r * c:(r + 1) * c])
     return out
+
+
+# ---------------------------------------------------------------------------
+# Slicing granularity m > 1 (Sec. 3.2, last sentences of its first paragraph)
+# ---------------------------------------------------------------------------
+# The sequence is cut into m * T slices for T ranks; the paper sets m = 1 and prints no index
+# formulas for m > 1 (Alg. 1 / Alg. 2 use one "N" for both the ranks and the slices).
+# Reading taken: the ring and its T hops stay as they are; the slice a rank handles at hop i
+# (index l of Alg. 1 / Alg. 2) is cut into m sub-slices that are processed, aggregated and sent on
+# one after the other, sub-step j = i*m + s handling sub-slice c = l*m + s of the m*T.  What is
+# received for sub-step j is what the predecessor produced at sub-step j - m.
+
+def subslice_index_rs(p: int, m: int, r: int, j: int) -> int:
+    return slice_index_rs(p, r, j // m) * m + (j % m)
+
+
+def subslice_index_ag(p: int, m: int, r: int, j: int) -> int:
+    return slice_index_ag(p, r, j // m) * m + (j % m)
+
+
+def fuse_rs_lockstep_m(X_list, W_list, m: int, compute: Optional[Compute] = None):
+    """Alg. 2 with slicing granularity ``m``, all ranks in lock-step.
+
+    Returns ``(O, received, sent)``; ``O[r]`` is the rank's result (its ``m`` sub-slices joined);
+    ``received[r][j]`` / ``sent[r][j]`` per sub-step ``j`` in ``[0, m*T)`` (``None`` where nothing
+    is received / sent: the first and the last hop).
+    """
+    if compute is None:
+        compute = gemm
+    T = len(X_list)
+    S = m * T
+    X_s = [split_rows(X_list[r], S) for r in range(T)]
+    mailbox = [dict() for _ in range(T)]                 # per rank: sub-step -> arrived partial
+    received = [[None] * S for _ in range(T)]
+    sent = [[None] * S for _ in range(T)]
+    final = [[None] * m for _ in range(T)]
+    for j in range(S):
+        i, s = divmod(j, m)
+        posted = []
+        for r in range(T):
+            c = subslice_index_rs(T, m, r, j)
+            O = compute(X_s[r][c], W_list[r])
+            if i > 0:
+                received[r][j] = mailbox[r].pop(j)
+                O = add(received[r][j], O)
+            if i < T - 1:
+                sent[r][j] = O.copy()
+                posted.append((send_rank(T, r), j + m, sent[r][j]))   # needed there one hop later
+            else:
+                final[r][s] = O
+        for dst, when, buf in posted:
+            mailbox[dst][when] = buf
+    assert all(not mb for mb in mailbox), "every transfer was consumed"
+    return [np.concatenate(f, axis=0) for f in final], received, sent
+
+
+def fuse_ag_lockstep_m(X_list, W_list, m: int, compute: Optional[Compute] = None):
+    """Alg. 1 with slicing granularity ``m``.  Returns ``(O, held)``; ``held[r][j]`` is the
+    sub-slice rank ``r`` multiplies at sub-step ``j``."""
+    if compute is None:
+        compute = gemm
+    T = len(X_list)
+    S = m * T
+    own = [split_rows(X_list[r], m) for r in range(T)]
+    mailbox = [dict() for _ in range(T)]
+    held = [[None] * S for _ in range(T)]
+    O_s = [[None] * S for _ in range(T)]
+    for j in range(S):
+        i, s = divmod(j, m)
+        posted = []
+        for r in range(T):
+            in_hand = own[r][s] if i == 0 else mailbox[r].pop(j)
+            held[r][j] = in_hand
+            if i < T - 1:
+                posted.append((send_rank(T, r), j + m, in_hand))
+            O_s[r][subslice_index_ag(T, m, r, j)] = compute(in_hand, W_list[r])
+        for dst, when, buf in posted:
+            mailbox[dst][when] = buf
+    assert all(not mb for mb in mailbox)
+    return [np.concatenate(O_s[r], axis=0) for r in range(T)], held
+
+
+def rs_rank_steps_m(A, W, R: Sequence[Optional[np.ndarray]], p: int, r: int, m: int) -> List[np.ndarray]:
+    """One-rank view with granularity ``m``: ``R[i]`` (hop ``i >= 1``) holds the ``m`` sub-partials of
+    that hop stacked by rows; returns the output of every sub-step."""
+    X_s = split_rows(_f64(A), m * p)
+    outs = []
+    for j in range(m * p):
+        i, s = divmod(j, m)
+        O = gemm(X_s[subslice_index_rs(p, m, r, j)], W)
+        if i > 0:
+            O = add(split_rows(_f64(R[i]), m)[s], O)
+        outs.append(O)
+    return outs
+
+
+def ag_rank_m(X_own, S_in: Sequence[Optional[np.ndarray]], W, p: int, r: int, m: int) -> np.ndarray:
+    """One-rank view of Alg. 1 with granularity ``m``: ``S_in[i]`` is the slice delivered for hop ``i``."""
+    blocks = [None] * (m * p)
+    for j in range(m * p):
+        i, s = divmod(j, m)
+        src = _f64(X_own) if i == 0 else _f64(S_in[i])
+        blocks[subslice_index_ag(p, m, r, j)] = gemm(split_rows(src, m)[s], W)
+    return np.concatenate(blocks, axis=0)
+
+
+def dp_rank_m(bucket, R: Sequence[Optional[np.ndarray]], p: int, r: int, m: int) -> np.ndarray:
+    out = _f64(bucket).copy()
+    c = out.shape[0] // (m * p)
+    for j in range(m, m * p):
+        i, s = divmod(j, m)
+        k = subslice_index_rs(p, m, r, j)
+        out[k * c:(k + 1) * c] = add(_f64(R[i])[s * c:(s + 1) * c], out[k * c:(k + 1) * c])
+    return out

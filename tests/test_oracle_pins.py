@@ -486,3 +486,84 @@ def test_pairwise_dp_rank():
     mask = np.ones(p * c, dtype=bool)
     mask[r * c:(r + 1) * c] = False
     assert np.array_equal(out[mask], g[r][mask])
+
+
+# ----------------------------------------------------------------------------
+# slicing granularity m > 1 (Sec. 3.2)
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("p,m", [(1, 3), (2, 2), (3, 2), (4, 1), (4, 3), (8, 2)])
+def test_granularity_index_invariants(p, m):
+    S = m * p
+    for r in range(p):
+        rs = [oracle.subslice_index_rs(p, m, r, j) for j in range(S)]
+        ag = [oracle.subslice_index_ag(p, m, r, j) for j in range(S)]
+        assert sorted(rs) == list(range(S)) and sorted(ag) == list(range(S))
+        assert rs[-m:] == [r * m + s for s in range(m)], "own sub-slices are computed in the last hop"
+        assert ag[:m] == [r * m + s for s in range(m)], "own sub-slices are computed in the first hop"
+        nxt = oracle.send_rank(p, r)
+        for j in range(S - m):            # what r handles at sub-step j, its successor handles one hop later
+            assert oracle.subslice_index_rs(p, m, nxt, j + m) == rs[j]
+            assert oracle.subslice_index_ag(p, m, nxt, j + m) == ag[j]
+        if m == 1:
+            assert rs == [oracle.slice_index_rs(p, r, i) for i in range(p)]
+            assert ag == [oracle.slice_index_ag(p, r, i) for i in range(p)]
+
+
+@pytest.mark.parametrize("p,m,mc,n,k", [(2, 2, 4, 3, 5), (3, 2, 2, 5, 2), (4, 3, 6, 7, 6), (8, 2, 2, 5, 3), (1, 4, 8, 3, 2)])
+@pytest.mark.parametrize("integer", [True, False])
+def test_granularity_exactness(p, m, mc, n, k, integer):
+    rng = np.random.default_rng(900 * p + m + (7 if integer else 0))
+    g = _rand_problem(rng, p, mc, n, k, integer)
+    A = [g(p * mc, k) for _ in range(p)]
+    W = [g(k, n) for _ in range(p)]
+    want = oracle.rs_definition(A, W)
+    got, received, sent = oracle.fuse_rs_lockstep_m(A, W, m)
+    base, _, base_sent = oracle.fuse_rs_lockstep(A, W)
+    for r in range(p):
+        # rows are independent, so cutting a slice into m row blocks changes no value at all
+        assert np.array_equal(got[r], base[r])
+        if integer:
+            assert np.array_equal(got[r], want[r])
+        else:
+            np.testing.assert_allclose(got[r], want[r], rtol=0, atol=1e-12 * max(1.0, np.abs(want[r]).max()))
+        for i in range(p - 1):
+            joined = np.concatenate([sent[r][i * m + s] for s in range(m)], axis=0)
+            assert np.array_equal(joined, base_sent[r][i])
+        assert all(sent[r][j] is None for j in range((p - 1) * m, p * m)), "nothing is sent in the last hop"
+        assert all(received[r][j] is None for j in range(m)), "nothing is received in the first hop"
+        # one-rank view fed with what the lock-step run delivered
+        R = [None] + [np.concatenate([received[r][i * m + s] for s in range(m)], axis=0) for i in range(1, p)]
+        outs = oracle.rs_rank_steps_m(A[r], W[r], R, p, r, m)
+        for j in range(m * p):
+            ref = sent[r][j] if j < (p - 1) * m else got[r][(j % m) * (mc // m):(j % m + 1) * (mc // m)]
+            assert np.array_equal(outs[j], ref)
+    # all-gather side
+    X = [g(mc, k) for _ in range(p)]
+    Wc = [g(k, n) for _ in range(p)]
+    wantg = oracle.ag_definition(X, Wc)
+    gotg, held = oracle.fuse_ag_lockstep_m(X, Wc, m)
+    baseg, _ = oracle.fuse_ag_lockstep(X, Wc)
+    for r in range(p):
+        assert np.array_equal(gotg[r], baseg[r])
+        if integer:
+            assert np.array_equal(gotg[r], wantg[r])
+        S_in = [None] + [np.concatenate([held[r][i * m + s] for s in range(m)], axis=0) for i in range(1, p)]
+        assert np.array_equal(oracle.ag_rank_m(X[r], S_in, Wc[r], p, r, m), gotg[r])
+        for i in range(p):          # the slice in hand at hop i is rank (r - i)'s input
+            joined = np.concatenate([held[r][i * m + s] for s in range(m)], axis=0)
+            assert np.array_equal(joined, X[(r - i) % p])
+
+
+def test_granularity_dp_rank():
+    p, m, c, r = 4, 2, 6, 1
+    rng = np.random.default_rng(31)
+    g = [rng.integers(-50, 51, size=p * c).astype(np.float64) for _ in range(p)]
+    O, received, _ = oracle.fuse_rs_lockstep_m(g, [None] * p, m, compute=lambda x, _w: np.asarray(x, dtype=np.float64).copy())
+    want = oracle.dp_definition(g)
+    for q in range(p):
+        assert np.array_equal(O[q], want[q])
+    R = [None] + [np.concatenate([received[r][i * m + s] for s in range(m)]) for i in range(1, p)]
+    out = oracle.dp_rank_m(g[r], R, p, r, m)
+    assert np.array_equal(out[r * c:(r + 1) * c], want[r])
+    assert np.array_equal(out, oracle.dp_rank(g[r], R, p, r)), "granularity changes no value of the gradient path"
