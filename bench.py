@@ -92,8 +92,7 @@ def main() -> int:
     # how the emulated deliveries are enqueued: hipMemcpyAsync on the copy stream ordered by events
     # (eager or as a captured graph), or carried by extra workgroups of the step kernels (one stream)
     MODES = (("streams", 0), ("graph", cf.CF_GRAPH), ("fused-copy", cf.CF_FUSED_COPY),
-             ("fused-copy+graph", cf.CF_FUSED_COPY | cf.CF_GRAPH), ("device-wait", cf.CF_DEVICE_WAIT),
-             ("device-wait+graph", cf.CF_DEVICE_WAIT | cf.CF_GRAPH))
+             ("fused-copy+graph", cf.CF_FUSED_COPY | cf.CF_GRAPH), ("device-wait", cf.CF_DEVICE_WAIT))
 
     if args.modes:
         keep = set(args.modes.split(","))

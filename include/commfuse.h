@@ -78,14 +78,30 @@ typedef struct {
                           sums, B_in, B_out and the reduce-scatter result are
                           always fp32                                            */
     int32_t w_layout;  /* cf_wlayout                                             */
-    int32_t reserved;  /* must be 0                                              */
+    int32_t m;         /* slicing granularity (Sec. 3.2): the sequence is cut into m*p
+                          slices, i.e. every ring hop into m sub-steps; 0 or 1 = the
+                          paper's default m = 1.  m must divide m_chunk.  See below. */
 } cf_layer_desc;
+
+/* Slicing granularity m > 1.  The paper fixes m = 1 and prints no indices for m > 1;
+ * reading taken: the ring and its p hops are unchanged, and the slice l handled at hop
+ * i is cut into m row blocks that are computed, aggregated and sent on one after the
+ * other.  `step` then counts SUB-STEPS j in [0, m*p): hop i = j / m, block s = j % m,
+ * sub-slice c = l*m + s of the m*p (rows [c*m_chunk/m, (c+1)*m_chunk/m) of the
+ * sequence).  Every per-step tensor (recv, out, the slice in hand, the slots of
+ * cf_buffers) then has m_chunk/m rows, "step == 0" conditions become "hop == 0", and
+ * a delivery for sub-step j is what the neighbour produced at sub-step j - m.
+ * The pairwise kinds need m = 1. */
 
 /* Slice index l of step i: Alg. 2 "l = (r - i - 1 + N) mod N" for CF_KIND_RS and
  * CF_KIND_DP, Alg. 1 "l = (r - i + N) mod N" for CF_KIND_AG; for the pairwise kinds
  * the partner of round i+1 while i < p-1 and the rank's own slice at i = p-1.
  * Host-only arithmetic.  Returns a negative cf_status on bad arguments. */
 int commfuse_chunk_index(int kind, int p, int rank, int step);
+
+/* The same for slicing granularity m >= 1: sub-slice index c in [0, m*p) of sub-step
+ * `step` in [0, m*p) (ring kinds only). */
+int commfuse_subslice_index(int kind, int p, int m, int rank, int step);
 
 /* Pairwise bidirectional schedule (Appendix A(a)): the reduce-scatter's p(p-1) sends
  * are p-1 rounds of p/2 simultaneous two-way exchanges, each partial going straight
@@ -162,6 +178,9 @@ cf_status commfuse_ag_step(const cf_layer_desc *desc, int step, const void *shar
  *     bucket[l*chunk_elems : (l+1)*chunk_elems] += recv      (step in [1, p))
  * step 0 computes nothing (its slice is only sent) and enqueues nothing.
  *   bucket fp32 [p*chunk_elems], updated in place;  recv fp32 [chunk_elems].
+ *   (Granularity m > 1 changes nothing for an elementwise sum but the size of the
+ *   pieces: call with p*m "ranks' worth" of pieces through commfuse_run_schedule, which
+ *   honours desc->m for this kind too.)
  *   chunk_elems may be any non-negative number and the pointers need only be
  *   4-byte aligned; the 16-byte vector kernel runs when both the slice start
  *   and recv are 16-byte aligned (a scalar kernel handles the rest).
@@ -178,7 +197,10 @@ cf_status commfuse_dp_pair_step(int p, int rank, int step, float *bucket, int64_
 
 /* Buffers of a whole emulated rank step.  HOST struct holding DEVICE pointers.
  * Peer traffic is emulated: what rank r-1 would deliver for step i (i = 1..p-1)
- * sits in peer_stage[i-1] and is copied into slot[i % 2] on the copy stream. */
+ * sits in peer_stage[i-1] and is copied into slot[i % 2] on the copy stream.
+ * With granularity m > 1, peer_stage[i-1] / peer_sink[i] still hold one whole hop (the
+ * m blocks stacked by rows); block s of hop i is delivered for sub-step j = i*m + s into
+ * slot[j % 2] (m_chunk/m rows are used of each slot and send slot). */
 typedef struct {
     const void *A_or_own_shard;   /* RS: A [p*m_chunk x k]; AG: X^r [m_chunk x k]; DP: unused */
     const void *W;                /* weight shard (unused for DP)                             */
@@ -214,7 +236,11 @@ enum {
                             operand load for AG, before the B_in add for RS, as in
                             Alg. 2 where the transfer is needed by the add only).  The
                             wait is a bounded spin: on time-out the kernel finishes
-                            with invalid results and commfuse_device_status() reports it */
+                            with invalid results and commfuse_device_status() reports it.
+                            The two streams must be able to progress independently, and
+                            the mode cannot be combined with CF_GRAPH: a graph holds no
+                            edge from a flag write to the kernel polling that flag, so a
+                            replay may queue the writer behind the waiting kernel          */
 };
 
 /* A whole rank step: the p iterations of Alg. 1 (CF_KIND_AG) or Alg. 2

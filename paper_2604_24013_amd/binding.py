@@ -25,7 +25,7 @@ KINDS = {"rs": CF_KIND_RS, "ag": CF_KIND_AG, "dp": CF_KIND_DP, "rs_pair": CF_KIN
 DTYPES = {"bf16": CF_BF16, "f32": CF_F32}
 
 EXPORTS = [
-    "commfuse_chunk_index", "commfuse_pair_partner", "commfuse_rs_pair_step", "commfuse_rs_pair_last_step", "commfuse_dp_pair_step", "commfuse_rs_step", "commfuse_ag_step", "commfuse_dp_reduce_step",
+    "commfuse_chunk_index", "commfuse_subslice_index", "commfuse_pair_partner", "commfuse_rs_pair_step", "commfuse_rs_pair_last_step", "commfuse_dp_pair_step", "commfuse_rs_step", "commfuse_ag_step", "commfuse_dp_reduce_step",
     "commfuse_run_schedule", "commfuse_last_error", "commfuse_workspace_bytes", "commfuse_set_workspace",
     "commfuse_device_status",
     "commfuse_destroy_cache", "commfuse_version",
@@ -38,7 +38,7 @@ class LayerDesc(ctypes.Structure):
         ("m_chunk", ctypes.c_int64), ("n", ctypes.c_int64), ("k", ctypes.c_int64),
         ("lda", ctypes.c_int64), ("ldw", ctypes.c_int64), ("ldo", ctypes.c_int64),
         ("in_dtype", ctypes.c_int32), ("out_dtype", ctypes.c_int32),
-        ("w_layout", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("w_layout", ctypes.c_int32), ("m", ctypes.c_int32),
     ]
 
 
@@ -80,6 +80,8 @@ def load():
     lib.commfuse_ag_step.restype = i32
     lib.commfuse_dp_reduce_step.argtypes = [i32, i32, i32, vp, i64, vp, vp]
     lib.commfuse_dp_reduce_step.restype = i32
+    lib.commfuse_subslice_index.argtypes = [i32, i32, i32, i32, i32]
+    lib.commfuse_subslice_index.restype = i32
     lib.commfuse_pair_partner.argtypes = [i32, i32, i32]
     lib.commfuse_pair_partner.restype = i32
     lib.commfuse_rs_pair_step.argtypes = [ctypes.POINTER(LayerDesc), i32, vp, vp, vp, vp, vp, vp]
@@ -133,14 +135,14 @@ def _stream(s) -> Optional[int]:
 
 
 def layer_desc(p: int, rank: int, m_chunk: int, n: int, k: int, in_dtype="bf16", out_dtype="f32",
-               w_layout: int = CF_W_KN, lda: int = 0, ldw: int = 0, ldo: int = 0) -> LayerDesc:
+               w_layout: int = CF_W_KN, lda: int = 0, ldw: int = 0, ldo: int = 0, m: int = 0) -> LayerDesc:
     d = LayerDesc()
     d.p, d.rank, d.m_chunk, d.n, d.k = p, rank, m_chunk, n, k
     d.lda, d.ldw, d.ldo = lda, ldw, ldo
     d.in_dtype = DTYPES[in_dtype] if isinstance(in_dtype, str) else in_dtype
     d.out_dtype = DTYPES[out_dtype] if isinstance(out_dtype, str) else out_dtype
     d.w_layout = w_layout
-    d.reserved = 0
+    d.m = m
     return d
 
 
@@ -150,6 +152,13 @@ def version() -> int:
 
 def chunk_index(kind: int, p: int, rank: int, step: int) -> int:
     v = load().commfuse_chunk_index(kind, p, rank, step)
+    if v < 0:
+        raise CommFuseError(v, last_error())
+    return v
+
+
+def subslice_index(kind: int, p: int, m: int, rank: int, step: int) -> int:
+    v = load().commfuse_subslice_index(kind, p, m, rank, step)
     if v < 0:
         raise CommFuseError(v, last_error())
     return v

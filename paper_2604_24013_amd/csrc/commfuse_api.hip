@@ -74,7 +74,9 @@ Workspace g_ws;
 
 struct Resolved {      // descriptor with defaults filled in
     int p, rank;
-    int64_t mc, n, k, lda, ldw, ldo;
+    int m;             // slicing granularity: sub-steps per ring hop
+    int64_t mc;        // rows one (sub-)step works on: m_chunk / m
+    int64_t n, k, lda, ldw, ldo;
     bool bf16_in, bf16_out, w_kn;
 };
 
@@ -96,12 +98,17 @@ cf_status resolve(const cf_layer_desc *d, int kind, Resolved *out)
     if (d->m_chunk < 0 || d->n < 0 || d->k < 0)
         return fail(CF_ERR_INVALID_ARG, "negative size (m_chunk=%lld n=%lld k=%lld)", (long long)d->m_chunk,
                     (long long)d->n, (long long)d->k);
-    if (d->reserved != 0)
-        return fail(CF_ERR_INVALID_ARG, "reserved field must be 0");
+    if (d->m < 0 || d->m > 4096)
+        return fail(CF_ERR_INVALID_ARG, "slicing granularity m = %d not in [0, 4096]", d->m);
     Resolved r;
     r.p = d->p;
     r.rank = d->rank;
-    r.mc = d->m_chunk;
+    r.m = d->m > 1 ? d->m : 1;
+    if (r.m > 1 && is_pair_kind(kind))
+        return fail(CF_ERR_UNSUPPORTED, "the pairwise kinds need slicing granularity m = 1");
+    if (d->m_chunk % r.m != 0)
+        return fail(CF_ERR_INVALID_ARG, "m = %d must divide m_chunk = %lld", r.m, (long long)d->m_chunk);
+    r.mc = d->m_chunk / r.m;
     r.n = d->n;
     r.k = d->k;
     if (is_dp_kind(kind)) {
@@ -134,7 +141,7 @@ cf_status resolve(const cf_layer_desc *d, int kind, Resolved *out)
     if (r.k % mult || r.n % mult || r.lda % mult || r.ldw % mult || r.ldo % mult)
         return fail(CF_ERR_MISALIGNED, "k, n and row strides must be multiples of %lld elements", (long long)mult);
     const int64_t lim = INT_MAX / 2;
-    if (r.mc * r.p > lim || r.n > lim || r.k > lim)
+    if (d->m_chunk * r.p > lim || r.n > lim || r.k > lim)
         return fail(CF_ERR_INVALID_ARG, "size exceeds the 32-bit index range of the kernels");
     *out = r;
     return CF_OK;
@@ -147,6 +154,9 @@ int chunk_index(int kind, int p, int rank, int step)
         return ((rank - step) % p + p) % p;
     return ((rank - step - 1) % p + p) % p;
 }
+
+// Granularity m: sub-step j = hop*m + s handles sub-slice l(hop)*m + s.
+int subslice_index(int kind, int p, int m, int rank, int j) { return chunk_index(kind, p, rank, j / m) * m + j % m; }
 
 // Appendix A(a): partner of `rank` in round t of the pairwise schedule (p even, t in [1, p-1]).
 int pair_partner(int p, int rank, int t)
@@ -173,8 +183,8 @@ cf_status check_pair_p(int p)
 
 cf_status check_step(const Resolved &r, int step)
 {
-    if (step < 0 || step >= r.p)
-        return fail(CF_ERR_INVALID_ARG, "step = %d not in [0, %d)", step, r.p);
+    if (step < 0 || step >= r.p * r.m)
+        return fail(CF_ERR_INVALID_ARG, "step = %d not in [0, %d)", step, r.p * r.m);
     return CF_OK;
 }
 
@@ -266,15 +276,15 @@ cf_status rs_step_impl(const Resolved &r, int step, const void *A, const void *W
         return st;
     if (A == nullptr || W == nullptr || out == nullptr)
         return fail(CF_ERR_NULL_PTR, "A, W and out must not be NULL");
-    if (step == 0 && recv != nullptr)
-        return fail(CF_ERR_NULL_PTR, "recv must be NULL at step 0 (nothing has been received yet)");
-    if (step > 0 && recv == nullptr)
+    if (step < r.m && recv != nullptr)
+        return fail(CF_ERR_NULL_PTR, "recv must be NULL in the first hop (nothing has been received yet)");
+    if (step >= r.m && recv == nullptr)
         return fail(CF_ERR_NULL_PTR, "recv must not be NULL at step %d", step);
     if (recv == out)
         return fail(CF_ERR_INVALID_ARG, "out may not alias recv");
     if (!aligned16(A) || !aligned16(W) || !aligned16(out) || !aligned16(recv))
         return fail(CF_ERR_MISALIGNED, "tensor pointers must be 16-byte aligned");
-    const int l = chunk_index(CF_KIND_RS, r.p, r.rank, step);
+    const int l = subslice_index(CF_KIND_RS, r.p, r.m, r.rank, step);
     const char *a_rows = static_cast<const char *>(A) + (size_t)l * r.mc * r.lda * in_elem(r);
     return launch_gemm(r, a_rows, W, recv, out, s, job);
 }
@@ -288,29 +298,30 @@ cf_status ag_step_impl(const Resolved &r, int step, const void *shard, const voi
         return fail(CF_ERR_NULL_PTR, "shard, W and O must not be NULL");
     if (!aligned16(shard) || !aligned16(W) || !aligned16(O))
         return fail(CF_ERR_MISALIGNED, "tensor pointers must be 16-byte aligned");
-    const int l = chunk_index(CF_KIND_AG, r.p, r.rank, step);
+    const int l = subslice_index(CF_KIND_AG, r.p, r.m, r.rank, step);
     char *o_rows = static_cast<char *>(O) + (size_t)l * r.mc * r.ldo * (r.bf16_out ? 2 : 4);
     return launch_gemm(r, shard, W, nullptr, o_rows, s, job);
 }
 
+// chunk_elems: elements per (sub-)step; m: sub-steps per hop
 cf_status dp_step_impl(int p, int rank, int step, float *bucket, int64_t chunk_elems, const float *recv,
-                       hipStream_t s)
+                       hipStream_t s, int m = 1)
 {
     if (p < 1)
         return fail(CF_ERR_INVALID_ARG, "p = %d must be >= 1", p);
     if (rank < 0 || rank >= p)
         return fail(CF_ERR_INVALID_ARG, "rank = %d not in [0, %d)", rank, p);
-    if (step < 0 || step >= p)
-        return fail(CF_ERR_INVALID_ARG, "step = %d not in [0, %d)", step, p);
+    if (step < 0 || step >= p * m)
+        return fail(CF_ERR_INVALID_ARG, "step = %d not in [0, %d)", step, p * m);
     if (chunk_elems < 0)
         return fail(CF_ERR_INVALID_ARG, "chunk_elems < 0");
-    if (step == 0 || chunk_elems == 0)
-        return CF_OK;   // the slice of step 0 is only sent: nothing to add
+    if (step < m || chunk_elems == 0)
+        return CF_OK;   // the slices of the first hop are only sent: nothing to add
     if (bucket == nullptr || recv == nullptr)
         return fail(CF_ERR_NULL_PTR, "bucket and recv must not be NULL at step %d", step);
     if ((reinterpret_cast<uintptr_t>(bucket) | reinterpret_cast<uintptr_t>(recv)) & 3u)
         return fail(CF_ERR_MISALIGNED, "fp32 pointers must be 4-byte aligned");
-    const int l = chunk_index(CF_KIND_DP, p, rank, step);
+    const int l = subslice_index(CF_KIND_DP, p, m, rank, step);
     hipError_t e = cf::launch_dp_reduce(bucket + (int64_t)l * chunk_elems, recv, chunk_elems, s,
                                         num_cu_of_current_device());
     if (e != hipSuccess)
@@ -464,12 +475,13 @@ cf_status get_events(size_t count, std::vector<hipEvent_t> *out)
     return CF_OK;
 }
 
-// Enqueues the p iterations on the two streams (see commfuse_run_schedule in the header).
+// Enqueues the S = m*p (sub-)steps on the two streams (see commfuse_run_schedule in the header).
+// Sub-step j belongs to hop j / m; hop 0 receives nothing and the last hop sends nothing.
 cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hipStream_t cs, hipStream_t xs_in,
                            uint32_t flags)
 {
-    const int p = r.p;
-    // CF_FUSED_COPY: the delivery for step i+1 rides in the launch of step i; one stream, no events.
+    const int p = r.p, m = r.m, S = r.p * r.m;
+    // CF_FUSED_COPY: the delivery for step j+1 rides in the launch of step j; one stream, no events.
     const bool fused = (flags & CF_FUSED_COPY) != 0 && !(flags & (CF_NO_COPY | CF_NO_COMPUTE));
     // CF_DEVICE_WAIT: the compute stream never waits for the copy stream between steps; each delivery
     // is followed by a flag write, and the step kernel that needs it waits for the flag on the device.
@@ -488,27 +500,32 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
     const bool do_compute = !(flags & CF_NO_COMPUTE);
     const bool poison = (flags & CF_POISON) != 0;
 
-    const bool pair = is_pair_kind(kind);
+    const bool pair = is_pair_kind(kind);                                                // (m == 1 for these)
     const bool keep_all = kind == CF_KIND_RS_PAIR && b->recv_each != nullptr && p > 1;   // deferred aggregation
-    size_t slot_bytes;
+    size_t slot_bytes;                               // one (sub-)step's delivery
     if (is_rs_kind(kind))
         slot_bytes = (size_t)r.mc * r.n * sizeof(float);
     else if (kind == CF_KIND_AG)
         slot_bytes = (size_t)r.mc * r.k * in_elem(r);
     else
         slot_bytes = (size_t)r.mc * sizeof(float);
+    auto receives = [&](int j) { return j >= m && j < S; };          // sub-step j consumes a delivery
+    auto sends = [&](int j) { return j >= 0 && j < S - m; };         // sub-step j produces something to send
+    // block (j % m) of the hop buffer that holds hop (j / m)'s m blocks stacked by rows
+    auto stage_of = [&](int j) { return static_cast<const char *>(b->peer_stage[j / m - 1]) + (size_t)(j % m) * slot_bytes; };
+    auto sink_of = [&](int j) { return static_cast<char *>(b->peer_sink[j / m]) + (size_t)(j % m) * slot_bytes; };
 
-    // event layout: [0] start, [1] end, ready[i] = 2+i, done[i] = 2+p+i, sunk[i] = 2+2p+i
+    // event layout: [0] start, [1] end, ready[j] = 2+j, done[j] = 2+S+j, sunk[j] = 2+2S+j
     std::vector<hipEvent_t> ev;
-    if (cf_status st = get_events(2 + 3 * (size_t)p, &ev))
+    if (cf_status st = get_events(2 + 3 * (size_t)S, &ev))
         return st;
     hipEvent_t ev_start = ev[0], ev_end = ev[1];
-    auto ready = [&](int i) { return ev[2 + i]; };
-    auto done = [&](int i) { return ev[2 + p + i]; };
-    auto sunk = [&](int i) { return ev[2 + 2 * p + i]; };
+    auto ready = [&](int j) { return ev[2 + j]; };
+    auto done = [&](int j) { return ev[2 + S + j]; };
+    auto sunk = [&](int j) { return ev[2 + 2 * S + j]; };
 
     if (dwait) {                                     // all delivery flags down before any copy raises one
-        hipError_t e = cf::launch_set_words(dw_flags, p, 0u, cs);
+        hipError_t e = cf::launch_set_words(dw_flags, S, 0u, cs);
         if (e != hipSuccess)
             return fail_hip(e, "flag reset");
     }
@@ -517,16 +534,16 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
         CF_HIP(hipStreamWaitEvent(xs, ev_start, 0));
     }
 
-    // what rank r-1 delivers for step i+1 lands in slot[(i+1) % 2]
-    auto deliver = [&](int i) -> cf_status {
-        if (!(i + 1 < p && do_copy) || fused)
+    // what rank r-1 delivers for sub-step j+1 lands in slot[(j+1) % 2]
+    auto deliver = [&](int j) -> cf_status {
+        if (!(receives(j + 1) && do_copy) || fused)
             return CF_OK;
         // pairwise reduce-scatter: every arrival is kept (recv_each), or the first one initialises the
         // accumulator, which is O itself
-        void *dst = keep_all ? b->recv_each[i] : (kind == CF_KIND_RS_PAIR && i == 0) ? b->O : b->slot[(i + 1) & 1];
-        // the slot was last read by the kernel of step i-1 (steps >= 1 read a slot)
-        if (!serial && do_compute && i - 1 >= 1 && !keep_all)
-            CF_HIP(hipStreamWaitEvent(xs, done(i - 1), 0));
+        void *dst = keep_all ? b->recv_each[j] : (kind == CF_KIND_RS_PAIR && j == 0) ? b->O : b->slot[(j + 1) & 1];
+        // the slot was last read by the kernel of sub-step j-1 (if that one read a slot at all)
+        if (!serial && do_compute && receives(j - 1) && !keep_all)
+            CF_HIP(hipStreamWaitEvent(xs, done(j - 1), 0));
         if (slot_bytes == 0)
             return CF_OK;
         if (poison) {
@@ -534,103 +551,107 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
             if (e != hipSuccess)
                 return fail_hip(e, "poison fill");
         }
-        CF_HIP(hipMemcpyAsync(dst, b->peer_stage[i], slot_bytes, hipMemcpyDeviceToDevice, xs));
+        CF_HIP(hipMemcpyAsync(dst, stage_of(j + 1), slot_bytes, hipMemcpyDeviceToDevice, xs));
         if (dwait && !serial) {
-            hipError_t e = cf::launch_set_words(dw_flags + (i + 1), 1, 1u, xs);   // after the copy, same stream
+            hipError_t e = cf::launch_set_words(dw_flags + (j + 1), 1, 1u, xs);   // after the copy, same stream
             if (e != hipSuccess)
                 return fail_hip(e, "flag write");
         }
         if (!serial)
-            CF_HIP(hipEventRecord(ready(i + 1), xs));
+            CF_HIP(hipEventRecord(ready(j + 1), xs));
         return CF_OK;
     };
 
-    auto kernel = [&](int i) -> cf_status {
+    auto kernel = [&](int j) -> cf_status {
         if (!do_compute)
             return CF_OK;
-        if (!serial && do_copy && i > 0 && !dwait && (!keep_all || i == p - 1))
-            CF_HIP(hipStreamWaitEvent(cs, ready(i), 0));   // deliveries are in order on the copy stream
+        const bool last = j == S - 1;
+        if (!serial && do_copy && receives(j) && !dwait && (!keep_all || last))
+            CF_HIP(hipStreamWaitEvent(cs, ready(j), 0));   // deliveries are in order on the copy stream
         cf_status st = CF_OK;
         CopyJob job;
-        if (dwait && !serial && i > 0) {           // the kernel itself waits for the delivery of step i
-            job.wait_flag = dw_flags + i;
+        if (dwait && !serial && receives(j)) {     // the kernel itself waits for the delivery of sub-step j
+            job.wait_flag = dw_flags + j;
             job.status = dw_status;
             job.wait_at_start = kind == CF_KIND_AG;  // the slice is an operand; B_in is needed by the add only
         }
-        if (fused && i + 1 < p) {                  // what the neighbour delivers for step i+1
-            job.src = b->peer_stage[i];
-            job.dst = b->slot[(i + 1) & 1];
+        if (fused && receives(j + 1)) {            // what the neighbour delivers for sub-step j+1
+            job.src = stage_of(j + 1);
+            job.dst = b->slot[(j + 1) & 1];
             job.bytes = slot_bytes;
         }
+        // B_out slot (j % 2) was last sent at sub-step j-2
+        const bool wait_sunk = !serial && do_copy && b->peer_sink != nullptr && sends(j) && sends(j - 2);
         if (kind == CF_KIND_RS) {
-            if (!serial && do_copy && b->peer_sink != nullptr && i >= 2 && i < p - 1)
-                CF_HIP(hipStreamWaitEvent(cs, sunk(i - 2), 0));   // B_out slot still being sent
-            const float *recv = i > 0 ? static_cast<const float *>(b->slot[i & 1]) : nullptr;
-            float *out = i < p - 1 ? b->send_slot[i & 1] : static_cast<float *>(b->O);
-            st = rs_step_impl(r, i, b->A_or_own_shard, b->W, recv, out, cs, &job);
+            if (wait_sunk)
+                CF_HIP(hipStreamWaitEvent(cs, sunk(j - 2), 0));
+            const float *recv = receives(j) ? static_cast<const float *>(b->slot[j & 1]) : nullptr;
+            float *out = sends(j) ? b->send_slot[j & 1] : static_cast<float *>(b->O) + (size_t)(j % m) * r.mc * r.ldo;
+            st = rs_step_impl(r, j, b->A_or_own_shard, b->W, recv, out, cs, &job);
         } else if (kind == CF_KIND_AG) {
-            const void *shard = i > 0 ? b->slot[i & 1] : b->A_or_own_shard;
-            st = ag_step_impl(r, i, shard, b->W, b->O, cs, &job);
+            const void *shard = receives(j) ? b->slot[j & 1]
+                                            : static_cast<const char *>(b->A_or_own_shard) + (size_t)(j % m) * slot_bytes;
+            st = ag_step_impl(r, j, shard, b->W, b->O, cs, &job);
         } else if (kind == CF_KIND_RS_PAIR) {
-            if (!serial && do_copy && b->peer_sink != nullptr && i >= 2 && i < p - 1)
-                CF_HIP(hipStreamWaitEvent(cs, sunk(i - 2), 0));   // B_out slot still being sent
+            if (wait_sunk)
+                CF_HIP(hipStreamWaitEvent(cs, sunk(j - 2), 0));
             float *acc = static_cast<float *>(b->O);
-            const float *recv = i == 0 ? nullptr : (i == 1 ? acc : static_cast<const float *>(b->slot[i & 1]));
-            float *out = i < p - 1 ? b->send_slot[i & 1] : acc;
+            const float *recv = j == 0 ? nullptr : (j == 1 ? acc : static_cast<const float *>(b->slot[j & 1]));
+            float *out = !last ? b->send_slot[j & 1] : acc;
             if (!keep_all)
-                st = rs_pair_step_impl(r, i, b->A_or_own_shard, b->W, recv, acc, out, cs);
-            else if (i < p - 1)
-                st = rs_pair_step_impl(r, i, b->A_or_own_shard, b->W, nullptr, nullptr, out, cs);
+                st = rs_pair_step_impl(r, j, b->A_or_own_shard, b->W, recv, acc, out, cs);
+            else if (!last)
+                st = rs_pair_step_impl(r, j, b->A_or_own_shard, b->W, nullptr, nullptr, out, cs);
             else
                 st = rs_pair_last_step_impl(r, b->A_or_own_shard, b->W,
                                             reinterpret_cast<const float *const *>(b->recv_each), acc, cs);
         } else if (kind == CF_KIND_DP_PAIR) {
-            st = dp_pair_step_impl(p, r.rank, i, static_cast<float *>(b->O), r.mc,
-                                   i > 0 ? static_cast<const float *>(b->slot[i & 1]) : nullptr, cs);
+            st = dp_pair_step_impl(p, r.rank, j, static_cast<float *>(b->O), r.mc,
+                                   j > 0 ? static_cast<const float *>(b->slot[j & 1]) : nullptr, cs);
         } else {
-            st = dp_step_impl(p, r.rank, i, static_cast<float *>(b->O), r.mc,
-                              i > 0 ? static_cast<const float *>(b->slot[i & 1]) : nullptr, cs);
+            st = dp_step_impl(p, r.rank, j, static_cast<float *>(b->O), r.mc,
+                              receives(j) ? static_cast<const float *>(b->slot[j & 1]) : nullptr, cs, m);
         }
         if (st != CF_OK)
             return st;
         if (!serial)
-            CF_HIP(hipEventRecord(done(i), cs));
+            CF_HIP(hipEventRecord(done(j), cs));
         return CF_OK;
     };
 
-    // emulated send of step i: B_out (RS), the slice in hand (AG), slice l (DP)
-    auto send = [&](int i) -> cf_status {
-        if (!(b->peer_sink != nullptr && i < p - 1 && do_copy))
+    // emulated send of sub-step j: B_out (RS), the slice in hand (AG), the local slice (DP)
+    auto send = [&](int j) -> cf_status {
+        if (!(b->peer_sink != nullptr && sends(j) && do_copy))
             return CF_OK;
         const void *src;
-        size_t bytes = slot_bytes;
         if (is_rs_kind(kind)) {
-            src = b->send_slot[i & 1];
+            src = b->send_slot[j & 1];
         } else if (kind == CF_KIND_AG) {
-            src = i > 0 ? b->slot[i & 1] : b->A_or_own_shard;
+            src = receives(j) ? b->slot[j & 1]
+                              : static_cast<const char *>(b->A_or_own_shard) + (size_t)(j % m) * slot_bytes;
         } else {
-            const int l = pair ? pair_slice(p, r.rank, i) : chunk_index(CF_KIND_DP, p, r.rank, i);
+            const int l = pair ? pair_slice(p, r.rank, j) : subslice_index(CF_KIND_DP, p, m, r.rank, j);
             src = static_cast<const float *>(b->O) + (int64_t)l * r.mc;
         }
-        if (bytes == 0)
+        if (slot_bytes == 0)
             return CF_OK;
         if (!serial && do_compute && kind != CF_KIND_AG)
-            CF_HIP(hipStreamWaitEvent(xs, done(i), 0));
+            CF_HIP(hipStreamWaitEvent(xs, done(j), 0));
         // (all-gather: the slice in hand was delivered on this same stream, so it is already ordered)
-        CF_HIP(hipMemcpyAsync(b->peer_sink[i], src, bytes, hipMemcpyDeviceToDevice, xs));
+        CF_HIP(hipMemcpyAsync(sink_of(j), src, slot_bytes, hipMemcpyDeviceToDevice, xs));
         if (!serial)
-            CF_HIP(hipEventRecord(sunk(i), xs));
+            CF_HIP(hipEventRecord(sunk(j), xs));
         return CF_OK;
     };
 
-    for (int i = 0; i < p; ++i) {
+    for (int j = 0; j < S; ++j) {
         cf_status st;
         if (serial) {
-            if ((st = kernel(i)) || (st = send(i)) || (st = deliver(i)))
+            if ((st = kernel(j)) || (st = send(j)) || (st = deliver(j)))
                 return st;
         } else {
-            // the delivery for step i+1 is in flight while the kernel of step i runs
-            if ((st = deliver(i)) || (st = kernel(i)) || (st = send(i)))
+            // the delivery for sub-step j+1 is in flight while the kernel of sub-step j runs
+            if ((st = deliver(j)) || (st = kernel(j)) || (st = send(j)))
                 return st;
         }
     }
@@ -717,6 +738,15 @@ int commfuse_chunk_index(int kind, int p, int rank, int step)
     return chunk_index(kind, p, rank, step);
 }
 
+int commfuse_subslice_index(int kind, int p, int m, int rank, int step)
+{
+    if (kind != CF_KIND_RS && kind != CF_KIND_AG && kind != CF_KIND_DP)
+        return fail(CF_ERR_INVALID_ARG, "kind %d (ring kinds only)", kind);
+    if (p < 1 || m < 1 || m > 4096 || rank < 0 || rank >= p || step < 0 || step >= p * m)
+        return fail(CF_ERR_INVALID_ARG, "need p >= 1, m in [1, 4096], rank in [0, p), step in [0, m*p)");
+    return subslice_index(kind, p, m, rank, step);
+}
+
 int commfuse_pair_partner(int p, int rank, int round)
 {
     if (p < 2 || (p & 1))
@@ -793,7 +823,11 @@ cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_bu
     if (flags & CF_DEVICE_WAIT) {
         if (flags & CF_FUSED_COPY)
             return fail(CF_ERR_UNSUPPORTED, "CF_DEVICE_WAIT and CF_FUSED_COPY exclude each other");
-        if (kind == CF_KIND_DP || !step_can_carry_copy(r) || r.p > WS_MAX_FLAGS)
+        // A captured graph has no edge between a flag write and the kernel that polls the flag, so a replay
+        // may queue the writer behind the waiting kernel; two live streams cannot be ordered that way.
+        if (flags & CF_GRAPH)
+            return fail(CF_ERR_UNSUPPORTED, "CF_DEVICE_WAIT cannot be captured into a graph (CF_GRAPH)");
+        if (kind == CF_KIND_DP || !step_can_carry_copy(r) || r.p * r.m > WS_MAX_FLAGS)
             return fail(CF_ERR_UNSUPPORTED, "CF_DEVICE_WAIT needs the bf16 chunk-GEMM kernels (kind RS or AG, bf16 operands)");
     }
     if (flags & CF_FUSED_COPY) {
@@ -846,7 +880,7 @@ cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_bu
     if (exec == nullptr) {
         // events must exist before capture starts (creation is not a capturable operation)
         std::vector<hipEvent_t> tmp;
-        if (cf_status st = get_events(2 + 3 * (size_t)r.p, &tmp))
+        if (cf_status st = get_events(2 + 3 * (size_t)r.p * r.m, &tmp))
             return st;
         CF_HIP(hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal));
         cf_status st = enqueue_schedule(r, kind, bufs, cs, xs, flags & ~(uint32_t)CF_GRAPH);

@@ -48,9 +48,9 @@ def w_to_dev(W: np.ndarray, dtype: str, w_layout: int) -> torch.Tensor:
 class RsRun:
     """One GEMM + reduce-scatter rank step on the device."""
 
-    def __init__(self, w: inputs.Workload, data: dict, rank: int, w_layout=cf.CF_W_KN, with_sink=False):
-        self.w, self.rank = w, rank
-        self.desc = desc_of(w, rank, w_layout)
+    def __init__(self, w: inputs.Workload, data: dict, rank: int, w_layout=cf.CF_W_KN, with_sink=False, m=1):
+        self.w, self.rank, self.m = w, rank, m
+        self.desc = desc_of(w, rank, w_layout, m=m)
         self.A = to_dev(data["A"], w.dtype)
         self.W = w_to_dev(data["W"], w.dtype, w_layout)
         self.stage = [to_dev(r, "f32") for r in data["R"][1:]]
@@ -66,10 +66,12 @@ class RsRun:
     def run_steps(self):
         """Calls commfuse_rs_step once per step with the staged partial sums as B_in; returns every step's output."""
         outs = []
-        for i in range(self.w.p):
-            out = torch.full((self.w.m_chunk, self.w.n), float("nan"), dtype=torch.float32, device=DEV)
-            recv = self.stage[i - 1] if i > 0 else None
-            cf.rs_step(self.desc, i, self.A, self.W, recv, out, None)
+        m, ms = self.m, self.w.m_chunk // self.m
+        for j in range(self.w.p * m):                    # sub-step j: hop j // m, row block j % m
+            i, s = divmod(j, m)
+            out = torch.full((ms, self.w.n), float("nan"), dtype=torch.float32, device=DEV)
+            recv = self.stage[i - 1][s * ms:(s + 1) * ms] if i > 0 else None
+            cf.rs_step(self.desc, j, self.A, self.W, recv, out, None)
             outs.append(out)
         torch.cuda.synchronize()
         return [to_host_f64(o) for o in outs]
@@ -82,9 +84,9 @@ class RsRun:
 class AgRun:
     """One all-gather + GEMM rank step on the device."""
 
-    def __init__(self, w: inputs.Workload, data: dict, rank: int, w_layout=cf.CF_W_KN, with_sink=False):
-        self.w, self.rank = w, rank
-        self.desc = desc_of(w, rank, w_layout)
+    def __init__(self, w: inputs.Workload, data: dict, rank: int, w_layout=cf.CF_W_KN, with_sink=False, m=1):
+        self.w, self.rank, self.m = w, rank, m
+        self.desc = desc_of(w, rank, w_layout, m=m)
         self.X = to_dev(data["X"], w.dtype)
         self.W = w_to_dev(data["W"], w.dtype, w_layout)
         self.stage = [to_dev(s, w.dtype) for s in data["S"][1:]]
@@ -99,9 +101,11 @@ class AgRun:
         self.xs = torch.cuda.Stream()
 
     def run_steps(self):
-        for i in range(self.w.p):
-            shard = self.X if i == 0 else self.stage[i - 1]
-            cf.ag_step(self.desc, i, shard, self.W, self.O, None)
+        m, ms = self.m, self.w.m_chunk // self.m
+        for j in range(self.w.p * m):
+            i, s = divmod(j, m)
+            shard = (self.X if i == 0 else self.stage[i - 1])[s * ms:(s + 1) * ms]
+            cf.ag_step(self.desc, j, shard, self.W, self.O, None)
         torch.cuda.synchronize()
         return to_host_f64(self.O)
 
@@ -113,9 +117,9 @@ class AgRun:
 class DpRun:
     """The gradient reduce-scatter rank step on the device."""
 
-    def __init__(self, w: inputs.Workload, data: dict, rank: int, with_sink=False):
-        self.w, self.rank = w, rank
-        self.desc = cf.layer_desc(w.p, rank, w.m_chunk, 0, 0, "f32", "f32")
+    def __init__(self, w: inputs.Workload, data: dict, rank: int, with_sink=False, m=1):
+        self.w, self.rank, self.m = w, rank, m
+        self.desc = cf.layer_desc(w.p, rank, w.m_chunk, 0, 0, "f32", "f32", m=m)
         self.bucket = to_dev(data["bucket"], "f32")
         self.stage = [to_dev(r, "f32") for r in data["R"][1:]]
         mk = lambda: torch.empty((w.m_chunk,), dtype=torch.float32, device=DEV)

@@ -272,7 +272,7 @@ def test_schedule_modes_agree_rs():
     rank = 3
     ref = _oracle_rs(w, data, rank)
     for flags in (0, cf.CF_SERIAL, cf.CF_POISON, cf.CF_POISON | cf.CF_SERIAL, cf.CF_GRAPH, cf.CF_FUSED_COPY,
-                  cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_DEVICE_WAIT, cf.CF_DEVICE_WAIT | cf.CF_GRAPH,
+                  cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_DEVICE_WAIT,
                   cf.CF_DEVICE_WAIT | cf.CF_POISON):
         run = H.RsRun(w, data, rank, with_sink=True)
         run.O.fill_(float("nan"))
@@ -296,7 +296,7 @@ def test_schedule_modes_agree_ag():
     rank = 5
     ref = _oracle_ag(w, data, rank)
     for flags in (0, cf.CF_SERIAL, cf.CF_POISON, cf.CF_GRAPH, cf.CF_FUSED_COPY, cf.CF_FUSED_COPY | cf.CF_GRAPH,
-                  cf.CF_DEVICE_WAIT, cf.CF_DEVICE_WAIT | cf.CF_GRAPH, cf.CF_DEVICE_WAIT | cf.CF_POISON):
+                  cf.CF_DEVICE_WAIT, cf.CF_DEVICE_WAIT | cf.CF_POISON):
         run = H.AgRun(w, data, rank, with_sink=True)
         with H.Workspace(run.desc, cf.CF_KIND_AG):
             run.run_schedule(flags)
@@ -308,6 +308,16 @@ def test_schedule_modes_agree_ag():
         assert np.array_equal(H.to_host_f64(run.sink[0]), inputs.as_f64(data["X"], "bf16"))
         for i in range(1, w.p - 1):
             assert np.array_equal(H.to_host_f64(run.sink[i]), inputs.as_f64(data["S"][i], "bf16"))
+
+
+def test_device_wait_cannot_be_captured():
+    """A graph holds no edge from a flag write to the kernel that polls the flag: the combination is refused."""
+    w = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=2, m_chunk=64, n=64, k=64)
+    run = H.AgRun(w, inputs.make_ag(w), 0)
+    with H.Workspace(run.desc, cf.CF_KIND_AG):
+        with pytest.raises(cf.CommFuseError) as ei:
+            run.run_schedule(cf.CF_DEVICE_WAIT | cf.CF_GRAPH)
+    assert ei.value.status == cf.CF_ERR_UNSUPPORTED
 
 
 def test_device_wait_times_out_instead_of_hanging():
@@ -365,7 +375,7 @@ def _sample_rows(mc, rng, extra=6):
     return sorted(fixed)
 
 
-@pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_DEVICE_WAIT | cf.CF_GRAPH, cf.CF_DEVICE_WAIT])
+@pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_GRAPH, cf.CF_DEVICE_WAIT])
 @pytest.mark.parametrize("name", ["c2_rs_7b", "c4_rs_70b_down"])
 def test_full_size_rs(name, flags):
     w = inputs.CONFIGS[name]
@@ -391,7 +401,7 @@ def test_full_size_rs(name, flags):
         assert e <= TOL_BF16 and e <= TIGHT_BF16, f"step {i}: {e:.3e}"
 
 
-@pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_DEVICE_WAIT | cf.CF_GRAPH, cf.CF_DEVICE_WAIT])
+@pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_GRAPH, cf.CF_DEVICE_WAIT])
 @pytest.mark.parametrize("name", ["c3_ag_7b", "c4_ag_70b_up"])
 def test_full_size_ag(name, flags):
     w = inputs.CONFIGS[name]
