@@ -81,7 +81,7 @@ def main() -> int:
         out = {}
         for name, fl in (("overlapped", 0), ("compute_only", cf.CF_NO_COPY), ("copy_only", cf.CF_NO_COMPUTE)):
             best = None
-            for mode, extra in MODES if (fl == 0 and kind in (cf.CF_KIND_RS, cf.CF_KIND_AG)) else MODES[:2]:
+            for mode, extra in MODES if (fl == 0 and kind in (cf.CF_KIND_RS, cf.CF_KIND_AG)) else BASIC:
                 t = time_calls(lambda: cf.run_schedule(run.desc, kind, run.bufs, run.cs, run.xs, fl | extra),
                                run.cs, steps, warmup)
                 if best is None or t < best[0]:
@@ -91,9 +91,13 @@ def main() -> int:
 
     # how the emulated deliveries are enqueued: hipMemcpyAsync on the copy stream ordered by events
     # (eager or as a captured graph), or carried by extra workgroups of the step kernels (one stream)
+    # or not overlapped at all (one stream, each delivery after the kernel before it: the copies then run
+    # at full speed and disturb no GEMM -- a reference point for what the overlap buys)
     MODES = (("streams", 0), ("graph", cf.CF_GRAPH), ("fused-copy", cf.CF_FUSED_COPY),
-             ("fused-copy+graph", cf.CF_FUSED_COPY | cf.CF_GRAPH), ("device-wait", cf.CF_DEVICE_WAIT))
+             ("fused-copy+graph", cf.CF_FUSED_COPY | cf.CF_GRAPH), ("device-wait", cf.CF_DEVICE_WAIT),
+             ("serial", cf.CF_SERIAL), ("serial+graph", cf.CF_SERIAL | cf.CF_GRAPH))
 
+    BASIC = tuple(m for m in MODES if m[0] in ("streams", "graph", "serial", "serial+graph"))   # work for every kind and flag
     if args.modes:
         keep = set(args.modes.split(","))
         MODES = tuple(m for m in MODES[:2]) + tuple(m for m in MODES[2:] if m[0] in keep) if not keep & {"streams", "graph"} \
@@ -124,11 +128,14 @@ def main() -> int:
         cf.run_schedule(rs.desc, cf.CF_KIND_RS, rs.bufs, rs.cs, rs.xs, flags)
 
     pair_t = {}
+    pair_modes = {}
     for name, fl in (("overlapped", 0), ("compute_only", cf.CF_NO_COPY), ("copy_only", cf.CF_NO_COMPUTE)):
         best = None
-        for mode, extra in MODES if fl == 0 else MODES[:2]:
+        for mode, extra in MODES if fl == 0 else BASIC:
             t = time_calls(lambda: pair(fl | extra), ag.cs, K, W)
             log(f"  pair {name} [{mode}]: {t*1e3:.1f} us")
+            if fl == 0:
+                pair_modes[mode] = round(t * 1e3, 1)
             if best is None or t < best[0]:
                 best = (t, mode)
         pair_t[name] = best
@@ -194,6 +201,26 @@ def main() -> int:
             del run
             torch.cuda.empty_cache()
 
+    # ---------------- slicing granularity m = 2 (two sub-steps per ring hop) ----------------
+    granularity = {}
+    if not args.only_pair:
+        for name, Run, make, kind in (("c4_rs_70b_down", H.RsRun, inputs.make_rs, cf.CF_KIND_RS),
+                                      ("c4_ag_70b_up", H.AgRun, inputs.make_ag, cf.CF_KIND_AG)):
+            w = inputs.CONFIGS[name]
+            data = make(w)
+            entry = {}
+            for m in (1, 2):
+                run = Run(w, data, 0, m=m)
+                t = schedule_times(run, kind, max(K, 50), W)
+                entry[f"m{m}"] = {"tflops": round(w.flops / (t["overlapped"][0] * 1e-3) / 1e12, 1),
+                                  "us_per_rank_step": round(t["overlapped"][0] * 1e3, 1), "mode": t["overlapped"][1],
+                                  "overlap_eff": round(overlap_eff(t), 3),
+                                  "us_compute_only": round(t["compute_only"][0] * 1e3, 1)}
+                del run
+                torch.cuda.empty_cache()
+            granularity[name] = entry
+            log("granularity", name, entry)
+
     # ---------------- gradient reduce-scatter step, 1e9 fp32 elements ----------------
     dp = None
     if not (args.skip_dp or args.only_pair):
@@ -252,12 +279,12 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "Llama-70B-shape MLP pair rank step, p=8: AG-GEMM up [8x(1024x8192)]x[8192x3584] -> bf16 H, "
                                "GEMM-RS down [8x(1024x3584)]x[3584x8192] + fp32 partials; emulated ring on one GPU",
-                   "p": 8, "rank": 0, "mode": pair_t["overlapped"][1]},
+                   "p": 8, "rank": 0, "mode": pair_t["overlapped"][1], "us_per_step_by_mode": pair_modes},
         "frac_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
         "overlap_eff": round(max(pair_t["compute_only"][0], pair_t["copy_only"][0]) / ms_step, 3),
         "ms_compute_only": round(pair_t["compute_only"][0], 4), "ms_copy_only": round(pair_t["copy_only"][0], 4),
         "roofline": roofline, "cpu_baseline": cpu, "dp_reduce": dp, "other_configs": others,
-        "pairwise_schedule": pairwise,
+        "pairwise_schedule": pairwise, "slicing_granularity": granularity,
     }
     print(json.dumps(line), flush=True)
     return 0

@@ -17,6 +17,7 @@ struct GemmParams {
     static constexpr int MAX_RECV_MORE = 15;
     const float *recv_more[MAX_RECV_MORE] = {};
     int n_recv_more = 0;
+    int pf_lead = 16;    // B_in prefetch: k-tiles before the end of the k loop at which it is issued (0 = off)
     void *out;
     int64_t lda, ldw, ldo;
     int M, N, K;

@@ -406,6 +406,34 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
 
     bf16x8_t af0[TM], wf0[TN], af1[TM], wf1[TN];
 
+    // B_in prefetch (one workgroup per CU, fp32 output, no k-split): the epilogue's loads of the received
+    // partial are issued pf_lead k-tiles before the end of the k loop and land in registers under the remaining
+    // MFMAs, so that the epilogue only adds and stores.
+    constexpr bool PF = !SPREAD && NS >= 3 && !OUT_BF16;
+    constexpr int PFR = TM * TN * 4;                  // 16-byte loads per lane
+    static_assert(!PF || (NS - 2) * LPT + PFR < 64, "vmcnt range");
+    const unsigned r_bytes = (unsigned)(((int64_t)(M - 1) * P.ldo + N) * 4);
+    __amdgpu_buffer_rsrc_t r_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(P.recv), 0, P.recv != nullptr ? (int)r_bytes : 0, 0x00020000);
+    const int pf_at = nk - 1 - P.pf_lead;             // iteration after whose tile loads the prefetch is issued
+    const bool pf_on = PF && P.recv != nullptr && splits == 1 && P.n_recv_more == 0 && P.pf_lead > 0 && pf_at >= 0;
+    f32x4_t pre[PF ? TM : 1][PF ? TN : 1][4];
+    auto prefetch_recv = [&]() {
+#pragma unroll
+        for (int i = 0; i < (PF ? TM : 0); ++i) {
+            const int m = m0 + wm * WTM + i * 32 + (lane & 31);
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = n0 + wn * WTN + j * 32 + g * 8 + (lane >> 5) * 4;
+                    const unsigned e = (m < M && n < N) ? (unsigned)((int64_t)m * P.ldo + n) : OOB;
+                    pre[i][j][g] = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
+                        r_rsrc, e == OOB ? (int)OOB : (int)(e * 4), 0, 0));
+                }
+        }
+    };
+
     if constexpr (SPREAD) {
         // Prologue: tiles 0 .. NS-2 and the first LH loads of tile NS-1 are requested (tile t lives in
         // stage t mod NS); tile 0 is awaited and its first fragments fetched.
@@ -475,9 +503,20 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             phase_b(af0, wf0, true, cur, 1, af1, wf1, rpm1{});
             phase_b(af1, wf1, true, cur, 2, af0, wf0, rpm1{});
             phase_b(af0, wf0, true, cur, 3, af1, wf1, rpm2{});   // reads early: complete at the barrier
-            wait_vmcnt<(NS - 2) * LPT>();    // tile kt+1 complete, NS-2 later tiles may be in flight
+            // tile kt+1 complete, NS-2 later tiles may be in flight -- and, in the NS-1 iterations after the
+            // B_in prefetch went out behind tile pf_at+NS, those loads too (loads return in issue order)
+            if (PF && pf_on && kt > pf_at && kt < pf_at + NS)
+                wait_vmcnt<(NS - 2) * LPT + PFR>();
+            else
+                wait_vmcnt<(NS - 2) * LPT>();
             __syncthreads();                 // tile kt is read by all, tile kt+1 is published
             issue_range(kt + NS, cur, c0{}, cLPT{});
+            if constexpr (PF) {
+                if (pf_on && kt == pf_at) {
+                    wait_delivery();
+                    prefetch_recv();
+                }
+            }
             __builtin_amdgcn_sched_barrier(0);
             phase_b(af1, wf1, true, nxt, 0, af0, wf0, rpm1{});
             cur = nxt;
@@ -561,12 +600,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     constexpr unsigned o_elem = OUT_BF16 ? 2 : 4;
     const unsigned o_bytes = (unsigned)(((int64_t)(M - 1) * P.ldo + N) * o_elem);
     __amdgpu_buffer_rsrc_t o_rsrc = __builtin_amdgcn_make_buffer_rsrc(P.out, 0, (int)o_bytes, 0x00020000);
-    const unsigned r_bytes = (unsigned)(((int64_t)(M - 1) * P.ldo + N) * 4);
     const bool has_recv = P.recv != nullptr;
-    if (!P.wait_at_start)
+    if (!P.wait_at_start && !pf_on)
         wait_delivery();                             // B_in has travelled under the main loop
-    __amdgpu_buffer_rsrc_t r_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(P.recv), 0, has_recv ? (int)r_bytes : 0, 0x00020000);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int m = m0 + wm * WTM + i * 32 + (lane & 31);
@@ -579,7 +615,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 const int n = n0 + wn * WTN + j * 32 + g * 8 + (lane >> 5) * 4;
                 eoff[j][g] = (m < M && n < N) ? (unsigned)((int64_t)m * P.ldo + n) : OOB;
             }
-        if (has_recv) {
+        if (PF && pf_on) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    rv[j][g] = pre[PF ? i : 0][PF ? j : 0][g];
+        } else if (has_recv) {
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -664,6 +706,8 @@ bool gemm_bf16_dl_supported(const GemmParams &p, bool w_kn)
 hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16, hipStream_t s, TileChoice t)
 {
     GemmParams p = p_in;
+    if (const char *e = getenv("COMMFUSE_PREFETCH"))   // tuning override: lead of the B_in prefetch in k-tiles, 0 = off
+        p.pf_lead = atoi(e) < 0 ? 0 : atoi(e);
     p.splits = t.splitk < 1 ? 1 : t.splitk;
     const int nk_all = (p.K + BK - 1) / BK;
     if (p.splits > nk_all)
