@@ -564,3 +564,97 @@ def dp_rank_m(bucket, R: Sequence[Optional[np.ndarray]], p: int, r: int, m: int)
         k = subslice_index_rs(p, m, r, j)
         out[k * c:(k + 1) * c] = add(_f64(R[i])[s * c:(s + 1) * c], out[k * c:(k + 1) * c])
     return out
+
+
+# ---------------------------------------------------------------------------
+# Backward pass of the two TPSP layers
+# ---------------------------------------------------------------------------
+# The paper states that TPSP involves reduce-scatter and all-gather in the forward AND the backward
+# pass (Sec. 1) and prints no backward algorithm.  Reading taken: the textbook gradients of the two
+# layers, each collective of which is decomposed by the same two loops:
+#   all-gather layer   Y^r = AG(X) W^r :  dX^r = RS_r( G^r (W^r)^T )      -> Alg. 2 with W^T
+#                                         dW^r = AG(X)^T G^r              -> Alg. 1's loop, the slice in hand
+#                                                                            multiplied (transposed) into dW
+#   reduce-scatter layer Y^r = RS_r(A^q W^q): dA^r = AG(G) (W^r)^T        -> Alg. 1 with W^T
+#                                         dW^r = (A^r)^T AG(G)            -> Alg. 1's loop over the arriving G
+# with G^r = dL/dY^r.  The weight gradient is a sum over the sequence slices; it is accumulated in the
+# order in which Alg. 1 meets them (l = (r - i) mod N).
+
+def ag_layer_forward(X_list, W_list):
+    return ag_definition(X_list, W_list)
+
+
+def rs_layer_forward(A_list, W_list):
+    return rs_definition(A_list, W_list)
+
+
+def ag_layer_backward_definition(X_list, W_list, G_list):
+    """Gradients of the all-gather layer, dense: returns ``(dX, dW)`` per rank."""
+    N = len(X_list)
+    X_full = np.concatenate([_f64(x) for x in X_list], axis=0)
+    dX_full = None
+    for r in range(N):
+        term = gemm(_f64(G_list[r]), np.ascontiguousarray(_f64(W_list[r]).T))
+        dX_full = term if dX_full is None else add(dX_full, term)
+    dX = split_rows(dX_full, N)
+    dW = [gemm(np.ascontiguousarray(X_full.T), _f64(G_list[r])) for r in range(N)]
+    return dX, dW
+
+
+def rs_layer_backward_definition(A_list, W_list, G_list):
+    """Gradients of the reduce-scatter layer, dense: returns ``(dA, dW)`` per rank."""
+    N = len(A_list)
+    G_full = np.concatenate([_f64(g) for g in G_list], axis=0)
+    dA = [gemm(G_full, np.ascontiguousarray(_f64(W_list[r]).T)) for r in range(N)]
+    dW = [gemm(np.ascontiguousarray(_f64(A_list[r]).T), G_full) for r in range(N)]
+    return dA, dW
+
+
+def fuse_ag_layer_backward(X_list, W_list, G_list):
+    """The same gradients through the decomposed loops, all ranks in lock-step."""
+    N = len(X_list)
+    dX, _, _ = fuse_rs_lockstep(G_list, [np.ascontiguousarray(_f64(w).T) for w in W_list])
+    # weight gradient: Alg. 1's loop; the compute on the slice in hand adds its contribution to dW
+    _, held = fuse_ag_lockstep(X_list, [None] * N, compute=lambda x, _w: x)
+    dW = []
+    for r in range(N):
+        G_s = split_rows(_f64(G_list[r]), N)
+        acc = None
+        for i in range(N):
+            l = slice_index_ag(N, r, i)
+            term = gemm(np.ascontiguousarray(_f64(held[r][i]).T), G_s[l])
+            acc = term if acc is None else add(acc, term)
+        dW.append(acc)
+    return dX, dW
+
+
+def fuse_rs_layer_backward(A_list, W_list, G_list):
+    N = len(A_list)
+    dA, held = fuse_ag_lockstep(G_list, [np.ascontiguousarray(_f64(w).T) for w in W_list])
+    dW = []
+    for r in range(N):
+        A_s = split_rows(_f64(A_list[r]), N)
+        acc = None
+        for i in range(N):
+            l = slice_index_ag(N, r, i)
+            term = gemm(np.ascontiguousarray(A_s[l].T), _f64(held[r][i]))
+            acc = term if acc is None else add(acc, term)
+        dW.append(acc)
+    return dA, dW
+
+
+def wgrad_rank_steps(moving: Sequence[np.ndarray], local, p: int, r: int, moving_is_left: bool) -> List[np.ndarray]:
+    """One-rank view of the weight-gradient loop.  ``moving[i]`` is the slice in hand at step ``i``
+    (own slice first, then the deliveries); ``local`` is the rank's full ``[p*m_chunk x .]`` operand.
+    ``moving_is_left``: dW += moving^T local[l]  (all-gather layer), else dW += local[l]^T moving
+    (reduce-scatter layer).  Returns dW after every step."""
+    L_s = split_rows(_f64(local), p)
+    outs, acc = [], None
+    for i in range(p):
+        l = slice_index_ag(p, r, i)
+        mv = _f64(moving[i])
+        left, right = (mv, L_s[l]) if moving_is_left else (L_s[l], mv)
+        term = gemm(np.ascontiguousarray(left.T), right)
+        acc = term if acc is None else add(acc, term)
+        outs.append(acc)
+    return outs

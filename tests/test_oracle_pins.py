@@ -567,3 +567,77 @@ def test_granularity_dp_rank():
     out = oracle.dp_rank_m(g[r], R, p, r, m)
     assert np.array_equal(out[r * c:(r + 1) * c], want[r])
     assert np.array_equal(out, oracle.dp_rank(g[r], R, p, r)), "granularity changes no value of the gradient path"
+
+
+# ----------------------------------------------------------------------------
+# backward pass: gradients against central finite differences of the forward definition
+# ----------------------------------------------------------------------------
+
+def _fd_grad(f, x, eps=1e-6):
+    """Central finite differences of the scalar function f at x (flat loop; tiny inputs only)."""
+    g = np.zeros_like(x)
+    flat, gf = x.reshape(-1), g.reshape(-1)
+    for idx in range(flat.size):
+        old = flat[idx]
+        flat[idx] = old + eps
+        up = f()
+        flat[idx] = old - eps
+        dn = f()
+        flat[idx] = old
+        gf[idx] = (up - dn) / (2 * eps)
+    return g
+
+
+@pytest.mark.parametrize("p,mc,n,k", [(2, 2, 3, 2), (3, 1, 2, 3), (4, 2, 2, 2)])
+def test_backward_matches_finite_differences(p, mc, n, k):
+    rng = np.random.default_rng(70 + p)
+    # all-gather layer: X^r [mc x k], W^r [k x n], Y^r [p*mc x n]
+    X = [rng.standard_normal((mc, k)) for _ in range(p)]
+    W = [rng.standard_normal((k, n)) for _ in range(p)]
+    C = [rng.standard_normal((p * mc, n)) for _ in range(p)]          # dL/dY^r for L = sum <Y^r, C^r>
+    loss = lambda: sum(float(np.sum(y * c)) for y, c in zip(oracle.ag_layer_forward(X, W), C))
+    dX, dW = oracle.ag_layer_backward_definition(X, W, C)
+    fX, fW = oracle.fuse_ag_layer_backward(X, W, C)
+    for r in range(p):
+        np.testing.assert_allclose(dX[r], _fd_grad(loss, X[r]), rtol=0, atol=1e-6)
+        np.testing.assert_allclose(dW[r], _fd_grad(loss, W[r]), rtol=0, atol=1e-6)
+        np.testing.assert_allclose(fX[r], dX[r], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(fW[r], dW[r], rtol=0, atol=1e-12)
+    # reduce-scatter layer: A^r [p*mc x k], W^r [k x n], Y^r [mc x n]
+    A = [rng.standard_normal((p * mc, k)) for _ in range(p)]
+    C = [rng.standard_normal((mc, n)) for _ in range(p)]
+    loss = lambda: sum(float(np.sum(y * c)) for y, c in zip(oracle.rs_layer_forward(A, W), C))
+    dA, dW = oracle.rs_layer_backward_definition(A, W, C)
+    fA, fW = oracle.fuse_rs_layer_backward(A, W, C)
+    for r in range(p):
+        np.testing.assert_allclose(dA[r], _fd_grad(loss, A[r]), rtol=0, atol=1e-6)
+        np.testing.assert_allclose(dW[r], _fd_grad(loss, W[r]), rtol=0, atol=1e-6)
+        np.testing.assert_allclose(fA[r], dA[r], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(fW[r], dW[r], rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("p", [1, 2, 4, 8])
+def test_backward_fused_is_exact_on_integers(p):
+    mc, n, k = 3, 4, 5
+    rng = np.random.default_rng(80 + p)
+    g = lambda *s: rng.integers(-4, 5, size=s).astype(np.float64)
+    X, W, G = [g(mc, k) for _ in range(p)], [g(k, n) for _ in range(p)], [g(p * mc, n) for _ in range(p)]
+    dX, dW = oracle.ag_layer_backward_definition(X, W, G)
+    fX, fW = oracle.fuse_ag_layer_backward(X, W, G)
+    Xf = np.concatenate(X)
+    for r in range(p):
+        assert np.array_equal(fX[r], dX[r]) and np.array_equal(fW[r], dW[r])
+        assert np.array_equal(dW[r], Xf.T @ G[r])                     # against the library product
+        assert np.array_equal(dX[r], sum(G[q] @ W[q].T for q in range(p))[r * mc:(r + 1) * mc])
+        # one-rank view of the weight-gradient loop, fed what Alg. 1 hands the rank
+        moving = [X[(r - i) % p] for i in range(p)]
+        assert np.array_equal(oracle.wgrad_rank_steps(moving, G[r], p, r, True)[-1], dW[r])
+    A, G2 = [g(p * mc, k) for _ in range(p)], [g(mc, n) for _ in range(p)]
+    dA, dW = oracle.rs_layer_backward_definition(A, W, G2)
+    fA, fW = oracle.fuse_rs_layer_backward(A, W, G2)
+    Gf = np.concatenate(G2)
+    for r in range(p):
+        assert np.array_equal(fA[r], dA[r]) and np.array_equal(fW[r], dW[r])
+        assert np.array_equal(dW[r], A[r].T @ Gf) and np.array_equal(dA[r], Gf @ W[r].T)
+        moving = [G2[(r - i) % p] for i in range(p)]
+        assert np.array_equal(oracle.wgrad_rank_steps(moving, A[r], p, r, False)[-1], dW[r])
