@@ -52,7 +52,9 @@ typedef enum {
     CF_KIND_AG = 1,       /* FuseAllGather on the ring (Alg. 1)                                   */
     CF_KIND_DP = 2,       /* gradient reduce on the ring (Alg. 2, identity compute)               */
     CF_KIND_RS_PAIR = 3,  /* FuseReduceScatter, pairwise bidirectional schedule (Appendix A(a))   */
-    CF_KIND_DP_PAIR = 4   /* gradient reduce, pairwise bidirectional schedule                     */
+    CF_KIND_DP_PAIR = 4,  /* gradient reduce, pairwise bidirectional schedule                     */
+    CF_KIND_WGRAD_X = 5,  /* weight gradient of the all-gather layer: the [m x k] operand travels  */
+    CF_KIND_WGRAD_G = 6   /* weight gradient of the reduce-scatter layer: the [m x n] one travels  */
 } cf_kind;
 
 /* Memory order of the weight shard W^r.
@@ -187,6 +189,29 @@ cf_status commfuse_ag_step(const cf_layer_desc *desc, int step, const void *shar
  */
 cf_status commfuse_dp_reduce_step(int p, int rank, int step, float *bucket, int64_t chunk_elems,
                                   const float *recv, void *hip_stream);
+
+/* Backward pass.  The paper names reduce-scatter and all-gather in the backward pass
+ * of TPSP (Sec. 1) without printing an algorithm; the gradients of the two layers
+ * decompose with the same two loops:
+ *   all-gather layer  Y^r = AG(X) W^r:   dX^r = RS_r(G^r (W^r)^T) is commfuse_rs_step on
+ *     A = G^r with the weight pointer unchanged and the OTHER w_layout (W^r stored
+ *     [k x n] is (W^r)^T stored [n' x k'] with n' = k, k' = n);
+ *   reduce-scatter layer Y^r = RS_r(A^q W^q):  dA^r = AG(G) (W^r)^T is commfuse_ag_step
+ *     in the same way;
+ *   both weight gradients are sums over the sequence slices, accumulated in the order in
+ *   which Alg. 1's loop meets them -- one call of commfuse_wgrad_step per iteration:
+ *       dW (+)= left^T @ right          (accumulates iff step > 0)
+ *     left  [m_chunk x k] bf16, row stride lda;  right [m_chunk x n] bf16, row stride ldw
+ *     dW    [k x n] fp32, row stride ldo, updated in place
+ *     desc: p, rank, m_chunk (rows contracted per step), k, n as above; in_dtype must be
+ *     CF_BF16 (CF_ERR_UNSUPPORTED otherwise, and for operands of 2 GiB or more);
+ *     w_layout and out_dtype are ignored.  The caller passes the slice in hand and
+ *     rows l = (r - step) mod p of its local operand (commfuse_chunk_index(CF_KIND_AG)).
+ * In cf_buffers for CF_KIND_WGRAD_X / CF_KIND_WGRAD_G: A_or_own_shard = the rank's own
+ * slice of the travelling operand, W = its full local operand [p*m_chunk x .] (the
+ * other factor), O = dW, peer_stage / slot / peer_sink as for CF_KIND_AG. */
+cf_status commfuse_wgrad_step(const cf_layer_desc *desc, int step, const void *left, const void *right,
+                              float *dW, void *hip_stream);
 
 /* Gradient path under the pairwise schedule: every round's arrival is a peer's copy
  * of THIS rank's slice, so for step in [1, p)

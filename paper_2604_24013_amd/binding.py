@@ -17,15 +17,16 @@ LIB_PATH = os.path.join(HERE, "libcommfuse.so")
 CF_OK = 0
 CF_ERR_INVALID_ARG, CF_ERR_NULL_PTR, CF_ERR_UNSUPPORTED, CF_ERR_MISALIGNED, CF_ERR_HIP = -1, -2, -3, -4, -5
 CF_BF16, CF_F32 = 0, 1
-CF_KIND_RS, CF_KIND_AG, CF_KIND_DP, CF_KIND_RS_PAIR, CF_KIND_DP_PAIR = 0, 1, 2, 3, 4
+CF_KIND_RS, CF_KIND_AG, CF_KIND_DP, CF_KIND_RS_PAIR, CF_KIND_DP_PAIR, CF_KIND_WGRAD_X, CF_KIND_WGRAD_G = 0, 1, 2, 3, 4, 5, 6
 CF_W_KN, CF_W_NK = 0, 1
 CF_NO_COPY, CF_NO_COMPUTE, CF_SERIAL, CF_POISON, CF_GRAPH, CF_FUSED_COPY, CF_DEVICE_WAIT = 1, 2, 4, 8, 16, 32, 64
 
-KINDS = {"rs": CF_KIND_RS, "ag": CF_KIND_AG, "dp": CF_KIND_DP, "rs_pair": CF_KIND_RS_PAIR, "dp_pair": CF_KIND_DP_PAIR}
+KINDS = {"rs": CF_KIND_RS, "ag": CF_KIND_AG, "dp": CF_KIND_DP, "rs_pair": CF_KIND_RS_PAIR, "dp_pair": CF_KIND_DP_PAIR,
+         "wgrad_x": CF_KIND_WGRAD_X, "wgrad_g": CF_KIND_WGRAD_G}
 DTYPES = {"bf16": CF_BF16, "f32": CF_F32}
 
 EXPORTS = [
-    "commfuse_chunk_index", "commfuse_subslice_index", "commfuse_pair_partner", "commfuse_rs_pair_step", "commfuse_rs_pair_last_step", "commfuse_dp_pair_step", "commfuse_rs_step", "commfuse_ag_step", "commfuse_dp_reduce_step",
+    "commfuse_chunk_index", "commfuse_subslice_index", "commfuse_pair_partner", "commfuse_rs_pair_step", "commfuse_rs_pair_last_step", "commfuse_dp_pair_step", "commfuse_wgrad_step", "commfuse_rs_step", "commfuse_ag_step", "commfuse_dp_reduce_step",
     "commfuse_run_schedule", "commfuse_last_error", "commfuse_workspace_bytes", "commfuse_set_workspace",
     "commfuse_device_status",
     "commfuse_destroy_cache", "commfuse_version",
@@ -88,6 +89,8 @@ def load():
     lib.commfuse_rs_pair_step.restype = i32
     lib.commfuse_rs_pair_last_step.argtypes = [ctypes.POINTER(LayerDesc), vp, vp, ctypes.POINTER(ctypes.c_void_p), vp, vp]
     lib.commfuse_rs_pair_last_step.restype = i32
+    lib.commfuse_wgrad_step.argtypes = [ctypes.POINTER(LayerDesc), i32, vp, vp, vp, vp]
+    lib.commfuse_wgrad_step.restype = i32
     lib.commfuse_dp_pair_step.argtypes = [i32, i32, i32, vp, i64, vp, vp]
     lib.commfuse_dp_pair_step.restype = i32
     lib.commfuse_run_schedule.argtypes = [ctypes.POINTER(LayerDesc), i32, ctypes.POINTER(Buffers), vp, vp, ctypes.c_uint32]
@@ -181,6 +184,10 @@ def rs_pair_last_step(desc: LayerDesc, A, W, recv_each: Sequence, out, stream=No
     table = (ctypes.c_void_p * max(n, 1))(*[_ptr(t) for t in recv_each])
     arg = ctypes.cast(table, ctypes.POINTER(ctypes.c_void_p)) if n else None
     _check(load().commfuse_rs_pair_last_step(ctypes.byref(desc), _ptr(A), _ptr(W), arg, _ptr(out), _stream(stream)))
+
+
+def wgrad_step(desc: LayerDesc, step: int, left, right, dW, stream=None) -> None:
+    _check(load().commfuse_wgrad_step(ctypes.byref(desc), step, _ptr(left), _ptr(right), _ptr(dW), _stream(stream)))
 
 
 def dp_pair_step(p: int, rank: int, step: int, bucket, chunk_elems: int, recv, stream=None) -> None:

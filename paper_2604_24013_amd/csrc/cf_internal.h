@@ -8,7 +8,10 @@ namespace cf {
 
 // One chunk GEMM: out[M x N] = A[M x K] * W (+ recv), fp32 accumulation.
 // A points at the first row of the slice; W is [K x N] (w_kn) or [N x K].
+// With a_t the left operand is given transposed, as [K x M] with row stride lda (the weight-gradient
+// contraction over tokens: both operands then have the contraction index as their row index).
 struct GemmParams {
+    bool a_t = false;    // direct-to-LDS bf16 kernel, w_kn, fp32 output only
     const void *A;
     const void *W;
     const float *recv;   // nullable: B_in of Alg. 2

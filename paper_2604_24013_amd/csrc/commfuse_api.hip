@@ -83,7 +83,8 @@ struct Resolved {      // descriptor with defaults filled in
 bool is_pair_kind(int kind) { return kind == CF_KIND_RS_PAIR || kind == CF_KIND_DP_PAIR; }
 bool is_dp_kind(int kind) { return kind == CF_KIND_DP || kind == CF_KIND_DP_PAIR; }
 bool is_rs_kind(int kind) { return kind == CF_KIND_RS || kind == CF_KIND_RS_PAIR; }
-bool known_kind(int kind) { return kind >= CF_KIND_RS && kind <= CF_KIND_DP_PAIR; }
+bool known_kind(int kind) { return kind >= CF_KIND_RS && kind <= CF_KIND_WGRAD_G; }
+bool is_wgrad_kind(int kind) { return kind == CF_KIND_WGRAD_X || kind == CF_KIND_WGRAD_G; }
 
 size_t in_elem(const Resolved &r) { return r.bf16_in ? 2 : 4; }
 
@@ -122,13 +123,13 @@ cf_status resolve(const cf_layer_desc *d, int kind, Resolved *out)
         return fail(CF_ERR_UNSUPPORTED, "in_dtype %d", d->in_dtype);
     if (d->out_dtype != CF_BF16 && d->out_dtype != CF_F32)
         return fail(CF_ERR_UNSUPPORTED, "out_dtype %d", d->out_dtype);
-    if (d->w_layout != CF_W_KN && d->w_layout != CF_W_NK)
+    if (d->w_layout != CF_W_KN && d->w_layout != CF_W_NK && !is_wgrad_kind(kind))
         return fail(CF_ERR_UNSUPPORTED, "w_layout %d", d->w_layout);
     r.bf16_in = d->in_dtype == CF_BF16;
     r.bf16_out = (kind == CF_KIND_AG) && d->out_dtype == CF_BF16;
     if (r.bf16_out && !r.bf16_in)
         return fail(CF_ERR_UNSUPPORTED, "bf16 output needs bf16 operands");
-    r.w_kn = d->w_layout == CF_W_KN;
+    r.w_kn = is_wgrad_kind(kind) || d->w_layout == CF_W_KN;   // both weight-gradient operands are [rows x .]
     if (d->lda < 0 || d->ldw < 0 || d->ldo < 0)
         return fail(CF_ERR_INVALID_ARG, "negative row stride");
     r.lda = d->lda ? d->lda : r.k;
@@ -225,6 +226,14 @@ void fill_shape(cf::GemmParams &gp, const Resolved &r)
     gp.M = (int)r.mc;
     gp.N = (int)r.n;
     gp.K = (int)r.k;
+}
+
+bool wgrad_can_carry_copy(const Resolved &r)
+{
+    if (!r.bf16_in || r.mc <= 0 || r.n <= 0 || r.k <= 0)
+        return false;
+    const int64_t lim = (int64_t)1 << 31;
+    return r.mc * r.lda * 2 < lim && r.mc * r.ldw * 2 < lim && r.k * r.ldo * 4 < lim;
 }
 
 cf_status launch_gemm(const Resolved &r, const void *A_rows, const void *W, const float *recv, void *out,
@@ -326,6 +335,71 @@ cf_status dp_step_impl(int p, int rank, int step, float *bucket, int64_t chunk_e
                                         num_cu_of_current_device());
     if (e != hipSuccess)
         return fail_hip(e, "gradient reduce launch");
+    return CF_OK;
+}
+
+// dW (+)= left^T right: the chunk GEMM with the contraction over the m_chunk rows of both operands.
+cf_status wgrad_step_impl(const Resolved &r, int step, const void *left, const void *right, float *dW, hipStream_t s,
+                          const CopyJob *job = nullptr)
+{
+    if (cf_status st = check_step(r, step))
+        return st;
+    if (left == nullptr || right == nullptr || dW == nullptr)
+        return fail(CF_ERR_NULL_PTR, "left, right and dW must not be NULL");
+    if (!aligned16(left) || !aligned16(right) || !aligned16(dW))
+        return fail(CF_ERR_MISALIGNED, "tensor pointers must be 16-byte aligned");
+    if (!r.bf16_in)
+        return fail(CF_ERR_UNSUPPORTED, "the weight-gradient step takes bf16 operands");
+    if (r.k == 0 || r.n == 0)
+        return CF_OK;
+    cf::GemmParams gp;
+    gp.a_t = true;
+    gp.A = left;
+    gp.W = right;
+    gp.recv = step > 0 ? dW : nullptr;             // in place: every element is read, then written, by one lane
+    gp.out = dW;
+    gp.lda = r.lda;
+    gp.ldw = r.ldw;
+    gp.ldo = r.ldo;
+    gp.M = (int)r.k;                               // rows of dW
+    gp.N = (int)r.n;
+    gp.K = (int)r.mc;                              // contraction: the slice's rows
+    if (gp.K == 0) {                               // nothing to contract: the gradient of an empty slice is zero
+        if (step == 0)
+            for (int64_t row = 0; row < r.k; ++row) {
+                hipError_t e = cf::launch_set_words(reinterpret_cast<unsigned *>(dW + row * r.ldo), (int)r.n, 0u, s);
+                if (e != hipSuccess)
+                    return fail_hip(e, "zero fill");
+            }
+        return CF_OK;
+    }
+    if (!cf::gemm_bf16_takes_recv_list(gp, true))
+        return fail(CF_ERR_UNSUPPORTED, "the weight-gradient step needs operands below 2 GiB (direct-to-LDS kernel)");
+    {
+        std::lock_guard<std::mutex> lk(g_ws_mu);
+        if (g_ws.ptr != nullptr && g_ws.bytes > WS_COUNTER_BYTES) {
+            gp.counters = static_cast<unsigned *>(g_ws.ptr);
+            gp.ws = reinterpret_cast<float *>(static_cast<char *>(g_ws.ptr) + WS_COUNTER_BYTES);
+            gp.ws_bytes = g_ws.bytes - WS_COUNTER_BYTES;
+            gp.max_tiles = (int)(WS_TILE_COUNTER_BYTES / sizeof(unsigned));
+        }
+    }
+    const int ncu = num_cu_of_current_device();
+    if (job != nullptr && job->wait_flag != nullptr) {
+        gp.wait_flag = job->wait_flag;
+        gp.status = job->status;
+        gp.spin_limit = spin_limit();
+        gp.wait_at_start = true;
+    }
+    if (job != nullptr && job->bytes > 0) {
+        gp.cp_src = job->src;
+        gp.cp_dst = job->dst;
+        gp.cp_bytes = job->bytes;
+        gp.cp_wgs = ncu / 4;
+    }
+    hipError_t e = cf::launch_gemm_bf16(gp, true, false, s, ncu);
+    if (e != hipSuccess)
+        return fail_hip(e, "weight-gradient GEMM launch");
     return CF_OK;
 }
 
@@ -505,8 +579,10 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
     size_t slot_bytes;                               // one (sub-)step's delivery
     if (is_rs_kind(kind))
         slot_bytes = (size_t)r.mc * r.n * sizeof(float);
-    else if (kind == CF_KIND_AG)
+    else if (kind == CF_KIND_AG || kind == CF_KIND_WGRAD_X)
         slot_bytes = (size_t)r.mc * r.k * in_elem(r);
+    else if (kind == CF_KIND_WGRAD_G)
+        slot_bytes = (size_t)r.mc * r.n * in_elem(r);
     else
         slot_bytes = (size_t)r.mc * sizeof(float);
     auto receives = [&](int j) { return j >= m && j < S; };          // sub-step j consumes a delivery
@@ -573,7 +649,7 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
         if (dwait && !serial && receives(j)) {     // the kernel itself waits for the delivery of sub-step j
             job.wait_flag = dw_flags + j;
             job.status = dw_status;
-            job.wait_at_start = kind == CF_KIND_AG;  // the slice is an operand; B_in is needed by the add only
+            job.wait_at_start = kind != CF_KIND_RS;  // the slice is an operand; B_in is needed by the add only
         }
         if (fused && receives(j + 1)) {            // what the neighbour delivers for sub-step j+1
             job.src = stage_of(j + 1);
@@ -592,6 +668,14 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
             const void *shard = receives(j) ? b->slot[j & 1]
                                             : static_cast<const char *>(b->A_or_own_shard) + (size_t)(j % m) * slot_bytes;
             st = ag_step_impl(r, j, shard, b->W, b->O, cs, &job);
+        } else if (is_wgrad_kind(kind)) {
+            const void *hand = receives(j) ? b->slot[j & 1]
+                                           : static_cast<const char *>(b->A_or_own_shard) + (size_t)(j % m) * slot_bytes;
+            const int c = subslice_index(CF_KIND_AG, p, m, r.rank, j);
+            const size_t local_row = (size_t)(kind == CF_KIND_WGRAD_X ? r.ldw : r.lda) * in_elem(r);
+            const void *local = static_cast<const char *>(b->W) + (size_t)c * r.mc * local_row;
+            st = kind == CF_KIND_WGRAD_X ? wgrad_step_impl(r, j, hand, local, static_cast<float *>(b->O), cs, &job)
+                                         : wgrad_step_impl(r, j, local, hand, static_cast<float *>(b->O), cs, &job);
         } else if (kind == CF_KIND_RS_PAIR) {
             if (wait_sunk)
                 CF_HIP(hipStreamWaitEvent(cs, sunk(j - 2), 0));
@@ -626,7 +710,7 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
         const void *src;
         if (is_rs_kind(kind)) {
             src = b->send_slot[j & 1];
-        } else if (kind == CF_KIND_AG) {
+        } else if (kind == CF_KIND_AG || is_wgrad_kind(kind)) {
             src = receives(j) ? b->slot[j & 1]
                               : static_cast<const char *>(b->A_or_own_shard) + (size_t)(j % m) * slot_bytes;
         } else {
@@ -635,7 +719,7 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
         }
         if (slot_bytes == 0)
             return CF_OK;
-        if (!serial && do_compute && kind != CF_KIND_AG)
+        if (!serial && do_compute && kind != CF_KIND_AG && !is_wgrad_kind(kind))
             CF_HIP(hipStreamWaitEvent(xs, done(j), 0));
         // (all-gather: the slice in hand was delivered on this same stream, so it is already ordered)
         CF_HIP(hipMemcpyAsync(sink_of(j), src, slot_bytes, hipMemcpyDeviceToDevice, xs));
@@ -704,8 +788,10 @@ cf_status check_buffers(const Resolved &r, int kind, const cf_buffers *b, uint32
     if (!is_dp_kind(kind)) {
         if (r.ldo != r.n)
             return fail(CF_ERR_UNSUPPORTED, "run_schedule needs packed partial sums / outputs (ldo == n)");
-        if (kind == CF_KIND_AG && r.lda != r.k)
+        if ((kind == CF_KIND_AG || kind == CF_KIND_WGRAD_X) && r.lda != r.k)
             return fail(CF_ERR_UNSUPPORTED, "run_schedule needs packed slices (lda == k)");
+        if (kind == CF_KIND_WGRAD_G && r.ldw != r.n)
+            return fail(CF_ERR_UNSUPPORTED, "run_schedule needs packed slices (ldw == n)");
     }
     return CF_OK;
 }
@@ -774,6 +860,15 @@ cf_status commfuse_rs_pair_last_step(const cf_layer_desc *desc, const void *A, c
     return rs_pair_last_step_impl(r, A, W, recv_each, out, static_cast<hipStream_t>(hip_stream));
 }
 
+cf_status commfuse_wgrad_step(const cf_layer_desc *desc, int step, const void *left, const void *right, float *dW,
+                              void *hip_stream)
+{
+    Resolved r;
+    if (cf_status st = resolve(desc, CF_KIND_WGRAD_X, &r))
+        return st;
+    return wgrad_step_impl(r, step, left, right, dW, static_cast<hipStream_t>(hip_stream));
+}
+
 cf_status commfuse_dp_pair_step(int p, int rank, int step, float *bucket, int64_t chunk_elems, const float *recv,
                                 void *hip_stream)
 {
@@ -827,13 +922,14 @@ cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_bu
         // may queue the writer behind the waiting kernel; two live streams cannot be ordered that way.
         if (flags & CF_GRAPH)
             return fail(CF_ERR_UNSUPPORTED, "CF_DEVICE_WAIT cannot be captured into a graph (CF_GRAPH)");
-        if (kind == CF_KIND_DP || !step_can_carry_copy(r) || r.p * r.m > WS_MAX_FLAGS)
+        if (is_dp_kind(kind) || !(is_wgrad_kind(kind) ? wgrad_can_carry_copy(r) : step_can_carry_copy(r)) ||
+            r.p * r.m > WS_MAX_FLAGS)
             return fail(CF_ERR_UNSUPPORTED, "CF_DEVICE_WAIT needs the bf16 chunk-GEMM kernels (kind RS or AG, bf16 operands)");
     }
     if (flags & CF_FUSED_COPY) {
         if (flags & CF_POISON)
             return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY cannot be combined with CF_POISON");
-        if (kind == CF_KIND_DP || !step_can_carry_copy(r))
+        if (is_dp_kind(kind) || !(is_wgrad_kind(kind) ? wgrad_can_carry_copy(r) : step_can_carry_copy(r)))
             return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY needs the bf16 chunk-GEMM kernels (kind RS or AG, bf16 operands)");
     }
     if (cf_status st = check_buffers(r, kind, bufs, flags))
@@ -908,6 +1004,11 @@ cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_bu
 size_t commfuse_workspace_bytes(const cf_layer_desc *desc, int kind)
 {
     Resolved r;
+    if (is_wgrad_kind(kind)) {                     // k-splits of a [k x n] gradient tile
+        if (resolve(desc, kind, &r) != CF_OK || !r.bf16_in)
+            return 0;
+        return WS_COUNTER_BYTES + (size_t)WS_MAX_SPLITS * (size_t)r.k * (size_t)r.n * sizeof(float);
+    }
     if (kind != CF_KIND_RS && kind != CF_KIND_AG && kind != CF_KIND_RS_PAIR)
         return 0;                                  // the gradient path needs none
     if (resolve(desc, kind, &r) != CF_OK || !r.bf16_in)

@@ -338,7 +338,7 @@ hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipSt
     const bool staged = staged_kernel_forced();
     if (!staged && gemm_bf16_dl_supported(p, w_kn))
         return launch_gemm_bf16_dl(p, w_kn, out_bf16, s, t);
-    if (p.n_recv_more != 0)
+    if (p.n_recv_more != 0 || p.a_t)
         return hipErrorInvalidValue;                 // callers ask gemm_bf16_takes_recv_list first
     if (t.bm == 256 && t.bn == 256) return launch_cfg<256, 256, 2, 4>(p, w_kn, out_bf16, s);
     if (t.bm == 256 && t.bn == 128) return launch_cfg<256, 128, 4, 2>(p, w_kn, out_bf16, s);

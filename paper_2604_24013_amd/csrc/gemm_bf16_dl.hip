@@ -130,9 +130,12 @@ __device__ __forceinline__ int xcd_remap(int pid, int total)
     return xcd * q + (xcd < rem ? xcd : rem) + idx;
 }
 
-template <int BM, int BN, int WGM, int WGN, int NS, bool SPREAD, bool W_KN, bool OUT_BF16>
+// A_T: the left operand is stored [K x M] (see GemmParams::a_t); its tile then lives in LDS like a
+// [k x n] weight tile and is read with the transposing LDS read as well.
+template <int BM, int BN, int WGM, int WGN, int NS, bool SPREAD, bool W_KN, bool OUT_BF16, bool A_T = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams P, int tiles_m, int tiles_n)
 {
+    static_assert(!A_T || (W_KN && !OUT_BF16), "the transposed left operand comes with [k x n] weights and fp32 output");
     constexpr int NW = WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -144,6 +147,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     static_assert(NS >= 2 && NS <= 4 && NS * STAGE <= 160 * 1024, "LDS budget");
     static_assert(KS == 4, "the slice schedule below is written for four slices per stage");
     constexpr int W_ROWB = BN * 2;                   // bytes of one k-row of a [k x n] weight tile
+    constexpr int A_ROWB = BM * 2;                   // bytes of one k-row of a [k x m] left-operand tile
 
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NS * STAGE];
 
@@ -209,7 +213,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         wait_delivery();
 
     // Buffer resources; all byte extents are below 2^31 (host-checked).
-    const unsigned a_bytes = (unsigned)(((int64_t)(M - 1) * P.lda + K) * 2);
+    const unsigned a_bytes = (unsigned)((A_T ? ((int64_t)(K - 1) * P.lda + M) : ((int64_t)(M - 1) * P.lda + K)) * 2);
     const unsigned w_bytes = (unsigned)((W_KN ? ((int64_t)(K - 1) * P.ldw + N) : ((int64_t)(N - 1) * P.ldw + K)) * 2);
     const i32x4_t a_rsrc = make_rsrc(P.A, a_bytes);
     const i32x4_t w_rsrc = make_rsrc(P.W, w_bytes);
@@ -222,11 +226,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
 #pragma unroll
     for (int j = 0; j < A_LD; ++j) {
         const int pos = (j * NW + wave) * 1024 + lane * 16;
-        int row, kc;
-        unswz_row(pos, row, kc);
-        const int gm = m0 + row;
-        a_k[j] = kc * 8;
-        a_off[j] = gm < M ? (unsigned)(((int64_t)gm * P.lda + kc * 8) * 2) : OOB;
+        if constexpr (A_T) {
+            const int k = pos / A_ROWB, inrow = pos % A_ROWB;
+            const int q = (inrow >> 6) ^ (k & 3);
+            const int gm = m0 + q * 32 + ((inrow >> 4) & 3) * 8;
+            a_k[j] = k;
+            a_off[j] = gm < M ? (unsigned)(((int64_t)k * P.lda + gm) * 2) : OOB;
+        } else {
+            int row, kc;
+            unswz_row(pos, row, kc);
+            const int gm = m0 + row;
+            a_k[j] = kc * 8;
+            a_off[j] = gm < M ? (unsigned)(((int64_t)gm * P.lda + kc * 8) * 2) : OOB;
+        }
     }
 #pragma unroll
     for (int j = 0; j < B_LD; ++j) {
@@ -246,6 +258,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         }
     }
     const int w_kstep = W_KN ? (int)(P.ldw * 2) : 2;   // bytes per unit of k along W
+    const int a_kstep = A_T ? (int)(P.lda * 2) : 2;    // ... and along the left operand
 
     // Direct load number `idx` (0 .. LPT-1: the A wave-loads, then the W wave-loads) of local k-tile
     // kt into `stage`.  A tile beyond the end of this split's k range is requested all the same, with
@@ -258,7 +271,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         const bool full = kt < nk && (k0 + BK) <= K;     // uniform: the common case needs no per-lane test
         if (full) {
             if constexpr (idx < A_LD)
-                direct_load_16(a_rsrc, a_off[idx], k0 * 2, sa + idx * NW * 1024);
+                direct_load_16(a_rsrc, a_off[idx], k0 * a_kstep, sa + idx * NW * 1024);
             else
                 direct_load_16(w_rsrc, b_off[idx - A_LD], k0 * w_kstep, sa + A_BYTES + (idx - A_LD) * NW * 1024);
         } else {
@@ -267,7 +280,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             const int ks0 = none ? 0 : k0;
             if constexpr (idx < A_LD) {
                 const unsigned off = (k0 + a_k[idx]) >= klim ? OOB : a_off[idx];
-                direct_load_16(a_rsrc, off, ks0 * 2, sa + idx * NW * 1024);
+                direct_load_16(a_rsrc, off, ks0 * a_kstep, sa + idx * NW * 1024);
             } else {
                 constexpr int j = idx - A_LD;
                 const unsigned off = (k0 + b_k[j]) >= klim ? OOB : b_off[j];
@@ -284,7 +297,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
 #pragma unroll
             for (int idx = lo; idx < hi; ++idx) {
                 if (idx < A_LD)
-                    direct_load_16(a_rsrc, a_off[idx < A_LD ? idx : 0], k0 * 2, sa + idx * NW * 1024);
+                    direct_load_16(a_rsrc, a_off[idx < A_LD ? idx : 0], k0 * a_kstep, sa + idx * NW * 1024);
                 else
                     direct_load_16(w_rsrc, b_off[idx >= A_LD ? idx - A_LD : 0], k0 * w_kstep,
                                    sa + A_BYTES + (idx - A_LD) * NW * 1024);
@@ -315,6 +328,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // 16-wide k-slice ks is reached by XOR-ing (ks << 5) into the offset of slice 0.
     const int frow = lane & 31, fkc = lane >> 5;
     const int a_addr = swz_row(wm * WTM + frow, fkc);
+    int a_addr_t[A_T ? TM : 1];
+    if constexpr (A_T) {
+        const int blk = lane >> 4, i16 = lane & 15;
+        const int kl = (blk >> 1) * 8 + (i16 >> 2);
+        const int ml = wm * WTM + (blk & 1) * 16 + (i16 & 3) * 4;        // row of tile i = 0
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int q = ((ml >> 5) + i) ^ (kl & 3);
+            a_addr_t[i] = kl * A_ROWB + (q << 6) + (ml & 31) * 2;
+        }
+    } else {
+        a_addr_t[0] = 0;
+    }
     int w_addr[W_KN ? TN : 1];
     if constexpr (W_KN) {
         const int blk = lane >> 4, i16 = lane & 15;
@@ -332,8 +358,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     auto read_frags = [&](int stage, int ks, bf16x8_t (&af)[TM], bf16x8_t (&wf)[TN]) {
         const unsigned char *st = smem + stage * STAGE;
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-            af[i] = *reinterpret_cast<const bf16x8_t *>(st + (a_addr ^ (ks << 5)) + i * 32 * 128);
+        for (int i = 0; i < TM; ++i) {
+            if constexpr (A_T) {
+                const unsigned char *pa = st + a_addr_t[i] + ks * 16 * A_ROWB;
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) s16x4_t *)(pa));
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) s16x4_t *)(pa + 4 * A_ROWB));
+                const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                af[i] = __builtin_bit_cast(bf16x8_t, both);
+            } else {
+                af[i] = *reinterpret_cast<const bf16x8_t *>(st + (a_addr ^ (ks << 5)) + i * 32 * 128);
+            }
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             if constexpr (W_KN) {
@@ -362,7 +399,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // first segment; after each segment one direct load of a later k-tile may be issued (load slots
     // LO .. LO+NSEG-1 of tile kt_l into stage_l), so that the wave never queues a burst of loads
     // behind which its MFMAs would wait.
-    constexpr int NREAD = TM + (W_KN ? 2 * TN : TN);
+    constexpr int NREAD = (A_T ? 2 * TM : TM) + (W_KN ? 2 * TN : TN);
     constexpr int NMFMA = TM * TN;
     constexpr int NSEG = NMFMA < 4 ? NMFMA : 4;
     constexpr int MPS = NMFMA / NSEG;                       // MFMAs per segment
@@ -677,7 +714,11 @@ hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t
 {
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     const dim3 grid(tiles_m * tiles_n * p.splits + p.cp_wgs), block(64 * WGM * WGN);
-    if (w_kn) {
+    if (p.a_t) {
+        if (!w_kn || out_bf16)
+            return hipErrorInvalidValue;
+        hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
+    } else if (w_kn) {
         if (out_bf16)
             hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, true>), grid, block, 0, s, p, tiles_m, tiles_n);
         else
@@ -697,7 +738,7 @@ bool gemm_bf16_dl_supported(const GemmParams &p, bool w_kn)
 {
     // byte extents of operands and outputs must stay below 2^31 (32-bit buffer offsets, OOB marker above them)
     const int64_t lim = (int64_t)1 << 31;
-    const int64_t a_bytes = ((int64_t)p.M * p.lda) * 2;
+    const int64_t a_bytes = ((int64_t)(p.a_t ? p.K : p.M) * p.lda) * 2;
     const int64_t w_bytes = ((int64_t)(w_kn ? p.K : p.N) * p.ldw) * 2;
     const int64_t o_bytes = ((int64_t)p.M * p.ldo) * 4;
     return p.M > 0 && p.N > 0 && p.K > 0 && a_bytes < lim && w_bytes < lim && o_bytes < lim;

@@ -217,3 +217,45 @@ class DpPairRun(DpRun):
     def run_schedule(self, flags=0):
         cf.run_schedule(self.desc, cf.CF_KIND_DP_PAIR, self.bufs, self.cs, self.xs, flags)
         self.cs.synchronize()
+
+
+class WgradRun:
+    """The weight-gradient loop of one layer on the device.  ``moving[i]`` (host arrays) is the slice in
+    hand at step ``i`` (own slice first, then the deliveries), ``local`` the rank's full operand.
+    ``moving_is_left``: all-gather layer (dW += moving^T local[l]), else reduce-scatter layer."""
+
+    def __init__(self, p, rank, m_chunk, k, n, moving, local, moving_is_left, with_sink=False, m=1):
+        self.p, self.rank, self.m, self.mc, self.k, self.n = p, rank, m, m_chunk, k, n
+        self.left_moves = moving_is_left
+        self.kind = cf.CF_KIND_WGRAD_X if moving_is_left else cf.CF_KIND_WGRAD_G
+        self.desc = cf.layer_desc(p, rank, m_chunk, n, k, "bf16", "f32", m=m)
+        self.own = to_dev(moving[0], "bf16")
+        self.stage = [to_dev(s, "bf16") for s in moving[1:]]
+        self.local = to_dev(local, "bf16")
+        width = k if moving_is_left else n
+        mk = lambda: torch.empty((m_chunk, width), dtype=torch.bfloat16, device=DEV)
+        self.slot = [mk(), mk()]
+        self.dW = torch.full((k, n), float("nan"), dtype=torch.float32, device=DEV)
+        self.sink = [mk() for _ in range(p - 1)] if with_sink else None
+        self.bufs = cf.make_buffers(self.own, self.local, self.dW, self.stage, self.slot, (None, None), self.sink)
+        self.cs = torch.cuda.Stream()
+        self.xs = torch.cuda.Stream()
+
+    def run_steps(self):
+        """One commfuse_wgrad_step per (sub-)step; returns dW after every one of them."""
+        outs = []
+        m, ms = self.m, self.mc // self.m
+        for j in range(self.p * m):
+            i, s = divmod(j, m)
+            hand = (self.own if i == 0 else self.stage[i - 1])[s * ms:(s + 1) * ms]
+            c = cf.subslice_index(cf.CF_KIND_AG, self.p, m, self.rank, j)
+            loc = self.local[c * ms:(c + 1) * ms]
+            left, right = (hand, loc) if self.left_moves else (loc, hand)
+            cf.wgrad_step(self.desc, j, left, right, self.dW, None)
+            torch.cuda.synchronize()
+            outs.append(to_host_f64(self.dW))
+        return outs
+
+    def run_schedule(self, flags=0):
+        cf.run_schedule(self.desc, self.kind, self.bufs, self.cs, self.xs, flags)
+        self.cs.synchronize()
