@@ -221,6 +221,57 @@ def main() -> int:
             granularity[name] = entry
             log("granularity", name, entry)
 
+    # ---------------- backward pass of the 70B pair: two data gradients, two weight gradients ----------------
+    backward = {}
+    if not args.only_pair:
+        rng = np.random.default_rng(inputs.BASE_SEED + 77)
+        def bf16_dev(shape, sigma):
+            return H.to_dev(inputs.f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32) * sigma), "bf16")
+        p8, mc8, d_model, d_ff = up.p, up.m_chunk, up.k, up.n           # 8, 1024, 8192, 3584
+        cs, xs = torch.cuda.Stream(), torch.cuda.Stream()
+        def timed(desc, kind, bufs):
+            best = None
+            for mode, extra in BASIC:
+                t = time_calls(lambda: cf.run_schedule(desc, kind, bufs, cs, xs, extra), cs, max(K, 30), W)
+                if best is None or t < best[0]:
+                    best = (t, mode)
+            return best
+        flops = 2.0 * p8 * mc8 * d_model * d_ff
+        mk32 = lambda r, c: torch.empty((r, c), dtype=torch.float32, device=H.DEV)
+        # up-projection layer (all-gather layer, W [d_model x d_ff]): dX = RS(G W^T), dW = AG(X)^T G
+        G_up = bf16_dev((p8 * mc8, d_ff), 1.0)
+        W_up = bf16_dev((d_model, d_ff), 0.01)
+        stage32 = [mk32(mc8, d_model).normal_() for _ in range(p8 - 1)]
+        bufs = cf.make_buffers(G_up, W_up, mk32(mc8, d_model), stage32, [mk32(mc8, d_model) for _ in range(2)],
+                               [mk32(mc8, d_model) for _ in range(2)])
+        t = timed(cf.layer_desc(p8, 0, mc8, d_model, d_ff, "bf16", "f32", cf.CF_W_NK), cf.CF_KIND_RS, bufs)
+        backward["up_dgrad_rs"] = {"us": round(t[0] * 1e3, 1), "tflops": round(flops / (t[0] * 1e-3) / 1e12, 1), "mode": t[1]}
+        X_own = bf16_dev((mc8, d_model), 1.0)
+        stage16 = [bf16_dev((mc8, d_model), 1.0) for _ in range(p8 - 1)]
+        mk16 = lambda r, c: torch.empty((r, c), dtype=torch.bfloat16, device=H.DEV)
+        dW_up = mk32(d_model, d_ff)
+        bufs = cf.make_buffers(X_own, G_up, dW_up, stage16, [mk16(mc8, d_model) for _ in range(2)])
+        t = timed(cf.layer_desc(p8, 0, mc8, d_ff, d_model, "bf16", "f32"), cf.CF_KIND_WGRAD_X, bufs)
+        backward["up_wgrad"] = {"us": round(t[0] * 1e3, 1), "tflops": round(flops / (t[0] * 1e-3) / 1e12, 1), "mode": t[1]}
+        del G_up, stage32, stage16, bufs, dW_up
+        torch.cuda.empty_cache()
+        # down-projection layer (reduce-scatter layer, W [d_ff x d_model]): dA = AG(G) W^T, dW = A^T AG(G)
+        W_dn = bf16_dev((d_ff, d_model), 0.01)
+        G_own = bf16_dev((mc8, d_model), 1.0)
+        stage16 = [bf16_dev((mc8, d_model), 1.0) for _ in range(p8 - 1)]
+        bufs = cf.make_buffers(G_own, W_dn, mk32(p8 * mc8, d_ff), stage16, [mk16(mc8, d_model) for _ in range(2)])
+        t = timed(cf.layer_desc(p8, 0, mc8, d_ff, d_model, "bf16", "f32", cf.CF_W_NK), cf.CF_KIND_AG, bufs)
+        backward["down_dgrad_ag"] = {"us": round(t[0] * 1e3, 1), "tflops": round(flops / (t[0] * 1e-3) / 1e12, 1), "mode": t[1]}
+        A_loc = bf16_dev((p8 * mc8, d_ff), 1.0)
+        bufs = cf.make_buffers(G_own, A_loc, mk32(d_ff, d_model), stage16, [mk16(mc8, d_model) for _ in range(2)])
+        t = timed(cf.layer_desc(p8, 0, mc8, d_model, d_ff, "bf16", "f32"), cf.CF_KIND_WGRAD_G, bufs)
+        backward["down_wgrad"] = {"us": round(t[0] * 1e3, 1), "tflops": round(flops / (t[0] * 1e-3) / 1e12, 1), "mode": t[1]}
+        total = sum(v["us"] for v in backward.values())
+        backward["all_four_rank_steps"] = {"us": round(total, 1), "tflops": round(4 * flops / (total * 1e-6) / 1e12, 1)}
+        log("backward", backward)
+        del A_loc, stage16, bufs, W_dn, W_up
+        torch.cuda.empty_cache()
+
     # ---------------- gradient reduce-scatter step, 1e9 fp32 elements ----------------
     dp = None
     if not (args.skip_dp or args.only_pair):
@@ -284,7 +335,7 @@ def main() -> int:
         "overlap_eff": round(max(pair_t["compute_only"][0], pair_t["copy_only"][0]) / ms_step, 3),
         "ms_compute_only": round(pair_t["compute_only"][0], 4), "ms_copy_only": round(pair_t["copy_only"][0], 4),
         "roofline": roofline, "cpu_baseline": cpu, "dp_reduce": dp, "other_configs": others,
-        "pairwise_schedule": pairwise, "slicing_granularity": granularity,
+        "pairwise_schedule": pairwise, "slicing_granularity": granularity, "backward_pass": backward,
     }
     print(json.dumps(line), flush=True)
     return 0
