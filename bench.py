@@ -116,11 +116,13 @@ def main() -> int:
     # ---------------- headline: 70B MLP pair ----------------
     up, dn = inputs.CONFIGS["c4_ag_70b_up"], inputs.CONFIGS["c4_rs_70b_down"]
     log("generating 70B-shape inputs ...")
-    ag = H.AgRun(up, inputs.make_ag(up), 0)
+    # every hop's delivery has a landing buffer of its own (cf_buffers.recv_each): nothing is reused inside a
+    # rank step, so the copy stream never waits for a kernel
+    ag = H.AgRun(up, inputs.make_ag(up), 0, each=True)
     ddn = inputs.make_rs(dn)
-    rs = H.RsRun(dn, ddn, 0)
+    rs = H.RsRun(dn, ddn, 0, each=True)
     rs.A = ag.O                                   # H is handed over on the device, in bf16
-    rs.bufs = cf.make_buffers(rs.A, rs.W, rs.O, rs.stage, rs.slot, rs.send, None)
+    rs.bufs = cf.make_buffers(rs.A, rs.W, rs.O, rs.stage, rs.slot, rs.send, None, rs.each)
     rs.cs, rs.xs = ag.cs, ag.xs                   # one compute stream, one copy stream for the pair
 
     def pair(flags):
@@ -169,7 +171,7 @@ def main() -> int:
         for name, Run, make, kind in (("c2_rs_7b", H.RsRun, inputs.make_rs, cf.CF_KIND_RS),
                                       ("c3_ag_7b", H.AgRun, inputs.make_ag, cf.CF_KIND_AG)):
             w = inputs.CONFIGS[name]
-            run = Run(w, make(w), 0)
+            run = Run(w, make(w), 0, each=True)
             t = schedule_times(run, kind, max(K, 100), W)
             others[name] = {"tflops": round(w.flops / (t["overlapped"][0] * 1e-3) / 1e12, 1),
                             "frac_mfma_peak": round(w.flops / (t["overlapped"][0] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),

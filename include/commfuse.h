@@ -237,11 +237,16 @@ typedef struct {
     void *const *peer_sink;       /* optional host array of p-1 device pointers receiving the
                                      emulated sends of steps 0..p-2 (RS: B_out, AG: the slice
                                      in hand, DP: slice l); NULL = sends are not copied        */
-    void *const *recv_each;       /* CF_KIND_RS_PAIR only, optional (NULL otherwise): host array
-                                     of p-1 device buffers [m_chunk x n] fp32, one per round.
-                                     When set, round t's delivery lands in recv_each[t-1], no
-                                     step accumulates, and the last step adds them all in its
-                                     epilogue (commfuse_rs_pair_last_step); slot[] is unused    */
+    void *const *recv_each;       /* optional (NULL = use slot[]): host array of p-1 device
+                                     buffers shaped like slot[], one per hop / round; slot[] is
+                                     then unused.  Ring kinds (RS, AG, weight gradient): hop i's
+                                     delivery lands in recv_each[i-1]; no buffer is reused inside
+                                     the call, so no delivery waits for a kernel, and with
+                                     CF_DEVICE_WAIT and no peer_sink the compute stream carries
+                                     nothing but the step kernels.  CF_KIND_RS_PAIR: round t's
+                                     delivery lands in recv_each[t-1], no step accumulates, and
+                                     the last step adds them all in its epilogue
+                                     (commfuse_rs_pair_last_step).  Not for the bucket kinds.    */
 } cf_buffers;
 
 enum {

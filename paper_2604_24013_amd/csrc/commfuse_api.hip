@@ -576,6 +576,9 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
 
     const bool pair = is_pair_kind(kind);                                                // (m == 1 for these)
     const bool keep_all = kind == CF_KIND_RS_PAIR && b->recv_each != nullptr && p > 1;   // deferred aggregation
+    // ring kinds with a landing buffer per hop: no buffer is reused within the call, so no delivery ever waits
+    // for a kernel, and (with CF_DEVICE_WAIT and no sinks) nothing but kernels is enqueued on the compute stream
+    const bool each = !pair && !is_dp_kind(kind) && b->recv_each != nullptr && p > 1;
     size_t slot_bytes;                               // one (sub-)step's delivery
     if (is_rs_kind(kind))
         slot_bytes = (size_t)r.mc * r.n * sizeof(float);
@@ -590,6 +593,11 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
     // block (j % m) of the hop buffer that holds hop (j / m)'s m blocks stacked by rows
     auto stage_of = [&](int j) { return static_cast<const char *>(b->peer_stage[j / m - 1]) + (size_t)(j % m) * slot_bytes; };
     auto sink_of = [&](int j) { return static_cast<char *>(b->peer_sink[j / m]) + (size_t)(j % m) * slot_bytes; };
+    // where the delivery of sub-step j lands / is read from
+    auto landing = [&](int j) -> void * {
+        return each ? static_cast<char *>(b->recv_each[j / m - 1]) + (size_t)(j % m) * slot_bytes : b->slot[j & 1];
+    };
+    const bool need_done = !each || (b->peer_sink != nullptr && do_copy && !(kind == CF_KIND_AG || is_wgrad_kind(kind)));
 
     // event layout: [0] start, [1] end, ready[j] = 2+j, done[j] = 2+S+j, sunk[j] = 2+2S+j
     std::vector<hipEvent_t> ev;
@@ -616,9 +624,9 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
             return CF_OK;
         // pairwise reduce-scatter: every arrival is kept (recv_each), or the first one initialises the
         // accumulator, which is O itself
-        void *dst = keep_all ? b->recv_each[j] : (kind == CF_KIND_RS_PAIR && j == 0) ? b->O : b->slot[(j + 1) & 1];
+        void *dst = keep_all ? b->recv_each[j] : (kind == CF_KIND_RS_PAIR && j == 0) ? b->O : landing(j + 1);
         // the slot was last read by the kernel of sub-step j-1 (if that one read a slot at all)
-        if (!serial && do_compute && receives(j - 1) && !keep_all)
+        if (!serial && do_compute && receives(j - 1) && !keep_all && !each)
             CF_HIP(hipStreamWaitEvent(xs, done(j - 1), 0));
         if (slot_bytes == 0)
             return CF_OK;
@@ -653,7 +661,7 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
         }
         if (fused && receives(j + 1)) {            // what the neighbour delivers for sub-step j+1
             job.src = stage_of(j + 1);
-            job.dst = b->slot[(j + 1) & 1];
+            job.dst = landing(j + 1);
             job.bytes = slot_bytes;
         }
         // B_out slot (j % 2) was last sent at sub-step j-2
@@ -661,15 +669,15 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
         if (kind == CF_KIND_RS) {
             if (wait_sunk)
                 CF_HIP(hipStreamWaitEvent(cs, sunk(j - 2), 0));
-            const float *recv = receives(j) ? static_cast<const float *>(b->slot[j & 1]) : nullptr;
+            const float *recv = receives(j) ? static_cast<const float *>(landing(j)) : nullptr;
             float *out = sends(j) ? b->send_slot[j & 1] : static_cast<float *>(b->O) + (size_t)(j % m) * r.mc * r.ldo;
             st = rs_step_impl(r, j, b->A_or_own_shard, b->W, recv, out, cs, &job);
         } else if (kind == CF_KIND_AG) {
-            const void *shard = receives(j) ? b->slot[j & 1]
+            const void *shard = receives(j) ? landing(j)
                                             : static_cast<const char *>(b->A_or_own_shard) + (size_t)(j % m) * slot_bytes;
             st = ag_step_impl(r, j, shard, b->W, b->O, cs, &job);
         } else if (is_wgrad_kind(kind)) {
-            const void *hand = receives(j) ? b->slot[j & 1]
+            const void *hand = receives(j) ? landing(j)
                                            : static_cast<const char *>(b->A_or_own_shard) + (size_t)(j % m) * slot_bytes;
             const int c = subslice_index(CF_KIND_AG, p, m, r.rank, j);
             const size_t local_row = (size_t)(kind == CF_KIND_WGRAD_X ? r.ldw : r.lda) * in_elem(r);
@@ -698,7 +706,7 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
         }
         if (st != CF_OK)
             return st;
-        if (!serial)
+        if (!serial && need_done)
             CF_HIP(hipEventRecord(done(j), cs));
         return CF_OK;
     };
@@ -711,7 +719,7 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
         if (is_rs_kind(kind)) {
             src = b->send_slot[j & 1];
         } else if (kind == CF_KIND_AG || is_wgrad_kind(kind)) {
-            src = receives(j) ? b->slot[j & 1]
+            src = receives(j) ? landing(j)
                               : static_cast<const char *>(b->A_or_own_shard) + (size_t)(j % m) * slot_bytes;
         } else {
             const int l = pair ? pair_slice(p, r.rank, j) : subslice_index(CF_KIND_DP, p, m, r.rank, j);
@@ -754,9 +762,9 @@ cf_status check_buffers(const Resolved &r, int kind, const cf_buffers *b, uint32
         return fail(CF_ERR_NULL_PTR, "buffers->O is NULL");
     if (!is_dp_kind(kind) && (b->A_or_own_shard == nullptr || b->W == nullptr))
         return fail(CF_ERR_NULL_PTR, "buffers->A_or_own_shard / W is NULL");
-    if (b->recv_each != nullptr && kind != CF_KIND_RS_PAIR)
-        return fail(CF_ERR_INVALID_ARG, "buffers->recv_each is for CF_KIND_RS_PAIR only");
-    const bool keep_all = kind == CF_KIND_RS_PAIR && b->recv_each != nullptr;
+    if (b->recv_each != nullptr && is_dp_kind(kind))
+        return fail(CF_ERR_INVALID_ARG, "buffers->recv_each is not used by the gradient-bucket kinds");
+    const bool keep_all = b->recv_each != nullptr;
     if (r.p > 1) {
         if (keep_all) {
             for (int i = 0; i < r.p - 1; ++i)

@@ -48,7 +48,7 @@ def w_to_dev(W: np.ndarray, dtype: str, w_layout: int) -> torch.Tensor:
 class RsRun:
     """One GEMM + reduce-scatter rank step on the device."""
 
-    def __init__(self, w: inputs.Workload, data: dict, rank: int, w_layout=cf.CF_W_KN, with_sink=False, m=1):
+    def __init__(self, w: inputs.Workload, data: dict, rank: int, w_layout=cf.CF_W_KN, with_sink=False, m=1, each=False):
         self.w, self.rank, self.m = w, rank, m
         self.desc = desc_of(w, rank, w_layout, m=m)
         self.A = to_dev(data["A"], w.dtype)
@@ -59,7 +59,8 @@ class RsRun:
         self.send = [mk(), mk()]
         self.O = mk()
         self.sink = [mk() for _ in range(w.p - 1)] if with_sink else None
-        self.bufs = cf.make_buffers(self.A, self.W, self.O, self.stage, self.slot, self.send, self.sink)
+        self.each = [mk() for _ in range(w.p - 1)] if each else None     # one landing buffer per hop
+        self.bufs = cf.make_buffers(self.A, self.W, self.O, self.stage, self.slot, self.send, self.sink, self.each)
         self.cs = torch.cuda.Stream()
         self.xs = torch.cuda.Stream()
 
@@ -84,7 +85,7 @@ class RsRun:
 class AgRun:
     """One all-gather + GEMM rank step on the device."""
 
-    def __init__(self, w: inputs.Workload, data: dict, rank: int, w_layout=cf.CF_W_KN, with_sink=False, m=1):
+    def __init__(self, w: inputs.Workload, data: dict, rank: int, w_layout=cf.CF_W_KN, with_sink=False, m=1, each=False):
         self.w, self.rank, self.m = w, rank, m
         self.desc = desc_of(w, rank, w_layout, m=m)
         self.X = to_dev(data["X"], w.dtype)
@@ -96,7 +97,8 @@ class AgRun:
         self.slot = [mk(), mk()]
         self.O = torch.full((w.p * w.m_chunk, w.n), float("nan"), dtype=odt, device=DEV)
         self.sink = [mk() for _ in range(w.p - 1)] if with_sink else None
-        self.bufs = cf.make_buffers(self.X, self.W, self.O, self.stage, self.slot, (None, None), self.sink)
+        self.each = [mk() for _ in range(w.p - 1)] if each else None
+        self.bufs = cf.make_buffers(self.X, self.W, self.O, self.stage, self.slot, (None, None), self.sink, self.each)
         self.cs = torch.cuda.Stream()
         self.xs = torch.cuda.Stream()
 
@@ -167,7 +169,6 @@ class RsPairRun(RsRun):
 
     def __init__(self, w, data, rank, w_layout=cf.CF_W_KN, with_sink=False, keep_all=False):
         super().__init__(w, data, rank, w_layout, with_sink)
-        self.each = None
         if keep_all:
             self.each = [torch.full((w.m_chunk, w.n), float("nan"), dtype=torch.float32, device=DEV) for _ in range(w.p - 1)]
             self.bufs = cf.make_buffers(self.A, self.W, self.O, self.stage, (None, None), self.send, self.sink, self.each)
@@ -224,7 +225,7 @@ class WgradRun:
     hand at step ``i`` (own slice first, then the deliveries), ``local`` the rank's full operand.
     ``moving_is_left``: all-gather layer (dW += moving^T local[l]), else reduce-scatter layer."""
 
-    def __init__(self, p, rank, m_chunk, k, n, moving, local, moving_is_left, with_sink=False, m=1):
+    def __init__(self, p, rank, m_chunk, k, n, moving, local, moving_is_left, with_sink=False, m=1, each=False):
         self.p, self.rank, self.m, self.mc, self.k, self.n = p, rank, m, m_chunk, k, n
         self.left_moves = moving_is_left
         self.kind = cf.CF_KIND_WGRAD_X if moving_is_left else cf.CF_KIND_WGRAD_G
@@ -237,7 +238,8 @@ class WgradRun:
         self.slot = [mk(), mk()]
         self.dW = torch.full((k, n), float("nan"), dtype=torch.float32, device=DEV)
         self.sink = [mk() for _ in range(p - 1)] if with_sink else None
-        self.bufs = cf.make_buffers(self.own, self.local, self.dW, self.stage, self.slot, (None, None), self.sink)
+        self.each = [mk() for _ in range(p - 1)] if each else None
+        self.bufs = cf.make_buffers(self.own, self.local, self.dW, self.stage, self.slot, (None, None), self.sink, self.each)
         self.cs = torch.cuda.Stream()
         self.xs = torch.cuda.Stream()
 

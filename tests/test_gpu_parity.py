@@ -310,6 +310,39 @@ def test_schedule_modes_agree_ag():
             assert np.array_equal(H.to_host_f64(run.sink[i]), inputs.as_f64(data["S"][i], "bf16"))
 
 
+@pytest.mark.parametrize("m", [1, 2])
+def test_landing_buffer_per_hop(m):
+    """cf_buffers.recv_each for the ring kinds: every hop's delivery has a buffer of its own (slot[] unused)."""
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=8, m_chunk=264, n=520, k=328)
+    data = inputs.make_rs(w, salt=15)
+    rank = 6
+    ref = _oracle_rs(w, data, rank)
+    wa = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=8, m_chunk=136, n=264, k=520)
+    da = inputs.make_ag(wa, salt=16)
+    refa = _oracle_ag(wa, da, rank)
+    for flags in (0, cf.CF_SERIAL, cf.CF_POISON, cf.CF_GRAPH, cf.CF_FUSED_COPY, cf.CF_FUSED_COPY | cf.CF_GRAPH,
+                  cf.CF_DEVICE_WAIT, cf.CF_DEVICE_WAIT | cf.CF_POISON):
+        for sink in (False, True):
+            run = H.RsRun(w, data, rank, with_sink=sink, m=m, each=True)
+            run.bufs.slot[0] = run.bufs.slot[1] = None           # must not be touched
+            run.O.fill_(float("nan"))
+            with H.Workspace(run.desc, cf.CF_KIND_RS):
+                run.run_schedule(flags)
+                run.run_schedule(flags)                          # back to back: the landing buffers are reused across calls
+                cf.device_status(run.cs)
+            assert H.rel_err(H.to_host_f64(run.O), ref[-1]) <= TIGHT_BF16, f"flags {flags}"
+            for i in range(w.p - 1):
+                assert np.array_equal(H.to_host_f64(run.each[i]), data["R"][i + 1].astype(np.float64))
+                if sink:
+                    assert H.rel_err(H.to_host_f64(run.sink[i]), ref[i]) <= TIGHT_BF16, f"flags {flags} sink {i}"
+            ag = H.AgRun(wa, da, rank, with_sink=sink, m=m, each=True)
+            ag.bufs.slot[0] = ag.bufs.slot[1] = None
+            with H.Workspace(ag.desc, cf.CF_KIND_AG):
+                ag.run_schedule(flags)
+                cf.device_status(ag.cs)
+            assert H.rel_err(H.to_host_f64(ag.O), refa) <= TIGHT_BF16, f"flags {flags}"
+
+
 def test_device_wait_cannot_be_captured():
     """A graph holds no edge from a flag write to the kernel that polls the flag: the combination is refused."""
     w = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=2, m_chunk=64, n=64, k=64)
