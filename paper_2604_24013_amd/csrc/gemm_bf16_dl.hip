@@ -194,7 +194,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
 
     // Device-side wait for an emulated delivery: one lane polls the flag with device-coherent loads,
     // sleeping between polls, for at most spin_limit polls (every wave reaches the barrier either way).
-    auto wait_delivery = [&]() {
+    // The delivery was written by another kernel while this one was already running, possibly through
+    // the L2 of another XCD: the caches this kernel reads through may hold older contents of those
+    // addresses.  So what follows the wait is either an agent-scope acquire (operand loads: L1 and the
+    // non-local L2 lines are invalidated once per workgroup) or loads with the device-coherent cache
+    // policy (the B_in loads of the epilogue, which are read once anyway).
+    auto wait_delivery = [&](bool acquire) {
         if (P.wait_flag != nullptr) {
             if (tid == 0) {
                 unsigned n = 0;
@@ -207,10 +212,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 }
             }
             __syncthreads();
+            if (acquire)
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         }
     };
     if (P.wait_at_start)
-        wait_delivery();
+        wait_delivery(true);
 
     // Buffer resources; all byte extents are below 2^31 (host-checked).
     const unsigned a_bytes = (unsigned)((A_T ? ((int64_t)(K - 1) * P.lda + M) : ((int64_t)(M - 1) * P.lda + K)) * 2);
@@ -455,7 +462,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     const int pf_at = nk - 1 - P.pf_lead;             // iteration after whose tile loads the prefetch is issued
     const bool pf_on = PF && P.recv != nullptr && splits == 1 && P.n_recv_more == 0 && P.pf_lead > 0 && pf_at >= 0;
     f32x4_t pre[PF ? TM : 1][PF ? TN : 1][4];
-    auto prefetch_recv = [&]() {
+    constexpr int COHERENT_LD = 1 | 16;               // buffer cache-policy bits sc0 | sc1
+    auto prefetch_recv = [&](auto aux_tag) {
+        constexpr int AUX = decltype(aux_tag)::value;
 #pragma unroll
         for (int i = 0; i < (PF ? TM : 0); ++i) {
             const int m = m0 + wm * WTM + i * 32 + (lane & 31);
@@ -466,7 +475,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                     const int n = n0 + wn * WTN + j * 32 + g * 8 + (lane >> 5) * 4;
                     const unsigned e = (m < M && n < N) ? (unsigned)((int64_t)m * P.ldo + n) : OOB;
                     pre[i][j][g] = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
-                        r_rsrc, e == OOB ? (int)OOB : (int)(e * 4), 0, 0));
+                        r_rsrc, e == OOB ? (int)OOB : (int)(e * 4), 0, AUX));
                 }
         }
     };
@@ -550,8 +559,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             issue_range(kt + NS, cur, c0{}, cLPT{});
             if constexpr (PF) {
                 if (pf_on && kt == pf_at) {
-                    wait_delivery();
-                    prefetch_recv();
+                    wait_delivery(false);
+                    if (P.wait_flag != nullptr)
+                        prefetch_recv(std::integral_constant<int, COHERENT_LD>{});
+                    else
+                        prefetch_recv(std::integral_constant<int, 0>{});
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -639,7 +651,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     __amdgpu_buffer_rsrc_t o_rsrc = __builtin_amdgcn_make_buffer_rsrc(P.out, 0, (int)o_bytes, 0x00020000);
     const bool has_recv = P.recv != nullptr;
     if (!P.wait_at_start && !pf_on)
-        wait_delivery();                             // B_in has travelled under the main loop
+        wait_delivery(false);                        // B_in has travelled under the main loop
+    const bool recv_coherent = P.wait_flag != nullptr && !P.wait_at_start;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int m = m0 + wm * WTM + i * 32 + (lane & 31);
@@ -662,9 +675,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int g = 0; g < 4; ++g)
-                    rv[j][g] = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
-                        r_rsrc, eoff[j][g] == OOB ? (int)OOB : (int)(eoff[j][g] * 4), 0, 0));
+                for (int g = 0; g < 4; ++g) {
+                    const int boff = eoff[j][g] == OOB ? (int)OOB : (int)(eoff[j][g] * 4);
+                    rv[j][g] = __builtin_bit_cast(f32x4_t, recv_coherent
+                                   ? __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, boff, 0, COHERENT_LD)
+                                   : __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, boff, 0, 0));
+                }
             // further received partials, summed in index order: one batch of independent loads per buffer
             for (int b = 0; b < P.n_recv_more; ++b) {
                 __amdgpu_buffer_rsrc_t m_rsrc = __builtin_amdgcn_make_buffer_rsrc(

@@ -343,6 +343,36 @@ def test_landing_buffer_per_hop(m):
             assert H.rel_err(H.to_host_f64(ag.O), refa) <= TIGHT_BF16, f"flags {flags}"
 
 
+def test_device_wait_sees_fresh_data_every_time():
+    """The step kernel is already running when its delivery is written (by another kernel, possibly through
+    another XCD's L2).  Each round delivers DIFFERENT data into the same buffers, with a NaN fill before
+    the copy: a kernel that read through a stale cache line would produce the previous round's sum or NaN."""
+    w = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=4, m_chunk=256, n=264, k=520)
+    wr = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=4, m_chunk=256, n=520, k=264)
+    rank = 2
+    runs = []
+    for salt in (31, 32, 33):
+        da, dr = inputs.make_ag(w, salt=salt), inputs.make_rs(wr, salt=salt)
+        runs.append((da, _oracle_ag(w, da, rank), dr, _oracle_rs(wr, dr, rank)))
+    ag = H.AgRun(w, runs[0][0], rank, each=True)
+    rs = H.RsRun(wr, runs[0][2], rank, each=True)
+    with H.Workspace(rs.desc, cf.CF_KIND_RS):
+        for rnd in range(6):
+            da, refa, dr, refr = runs[rnd % 3]
+            for t, src in zip(ag.stage, da["S"][1:]):
+                t.copy_(H.to_dev(src, w.dtype))
+            for t, src in zip(rs.stage, dr["R"][1:]):
+                t.copy_(H.to_dev(src, "f32"))
+            ag.X.copy_(H.to_dev(da["X"], w.dtype)); ag.W.copy_(H.to_dev(da["W"], w.dtype))
+            rs.A.copy_(H.to_dev(dr["A"], wr.dtype)); rs.W.copy_(H.to_dev(dr["W"], wr.dtype))
+            torch.cuda.synchronize()
+            ag.run_schedule(cf.CF_DEVICE_WAIT | cf.CF_POISON)
+            rs.run_schedule(cf.CF_DEVICE_WAIT | cf.CF_POISON)
+            cf.device_status(rs.cs)
+            assert H.rel_err(H.to_host_f64(ag.O), refa) <= TIGHT_BF16, f"round {rnd}"
+            assert H.rel_err(H.to_host_f64(rs.O), refr[-1]) <= TIGHT_BF16, f"round {rnd}"
+
+
 def test_device_wait_cannot_be_captured():
     """A graph holds no edge from a flag write to the kernel that polls the flag: the combination is refused."""
     w = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=2, m_chunk=64, n=64, k=64)
