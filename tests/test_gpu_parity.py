@@ -219,6 +219,49 @@ def test_integer_inputs_are_bit_exact(dtype, layout):
             assert np.array_equal(outs[i], ref[i]), f"rank {rank} step {i}"
 
 
+@pytest.mark.parametrize("layout", [cf.CF_W_KN, cf.CF_W_NK])
+@pytest.mark.parametrize("shape", [(3, 200, 264, 168), (4, 72, 136, 1376), (2, 264, 520, 328)])
+def test_register_staged_kernel(shape, layout):
+    """The fallback kernel for operands of 2 GiB and more (global -> registers -> LDS), forced on small shapes."""
+    p, mc, n, k = shape
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=p, m_chunk=mc, n=n, k=k)
+    data = inputs.make_rs(w, salt=17)
+    ref = _oracle_rs(w, data, 1)
+    wa = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=p, m_chunk=mc, n=n, k=k, out_dtype="bf16")
+    da = inputs.make_ag(wa, salt=17)
+    refa = _oracle_ag(wa, da, 1)
+    os.environ["COMMFUSE_KERNEL"] = "staged"
+    try:
+        outs = H.RsRun(w, data, 1, layout).run_steps()
+        O = H.AgRun(wa, da, 1, layout).run_steps()
+    finally:
+        os.environ.pop("COMMFUSE_KERNEL", None)
+    for i in range(p):
+        assert H.rel_err(outs[i], ref[i]) <= TIGHT_BF16, f"step {i}"
+    assert H.rel_err(O, refa) <= TIGHT_BF16_OUT
+
+
+def test_slice_of_two_gib_takes_the_fallback_kernel():
+    """Maximum sizes: a slice whose byte extent reaches 2^31 cannot use 32-bit buffer offsets; the step still
+    runs (register-staged kernel) and the rows at both ends and around the 2 GiB / 32-bit-index marks are right."""
+    p, mc, n, k = 1, 131072, 8, 8192                      # the slice is 131072 x 8192 bf16 = 2 GiB exactly
+    blk = 4096
+    wb = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=1, m_chunk=blk, n=n, k=k)
+    data = inputs.make_rs(wb, salt=18)                    # one seeded block of rows, repeated to fill the slice
+    A = H.to_dev(data["A"], "bf16").repeat(mc // blk, 1)
+    assert A.numel() * 2 == 1 << 31
+    W = H.to_dev(data["W"], "bf16")
+    out = torch.full((mc, n), float("nan"), dtype=torch.float32, device=H.DEV)
+    cf.rs_step(cf.layer_desc(p, 0, mc, n, k), 0, A, W, None, out, None)
+    torch.cuda.synchronize()
+    got = H.to_host_f64(out)
+    assert not np.isnan(got).any()
+    ref_blk = oracle.gemm(inputs.as_f64(data["A"], "bf16"), inputs.as_f64(data["W"], "bf16"))
+    for r0 in (0, 65536 - blk, 65536, mc - blk):          # first, either side of the middle, last block
+        assert H.rel_err(got[r0:r0 + blk], ref_blk) <= TIGHT_BF16, f"rows from {r0}"
+    assert np.array_equal(got[:blk], got[mc - blk:]), "the same rows give the same bits wherever they sit"
+
+
 def test_row_strides_are_honoured():
     p, mc, n, k = 2, 96, 72, 136
     lda, ldw, ldo = k + 24, n + 8, n + 16
