@@ -658,3 +658,93 @@ def wgrad_rank_steps(moving: Sequence[np.ndarray], local, p: int, r: int, moving
         acc = term if acc is None else add(acc, term)
         outs.append(acc)
     return outs
+
+
+# ---------------------------------------------------------------------------
+# FuseReduceScatter with query-split attention (Alg. 4, Sec. 4.3)
+# ---------------------------------------------------------------------------
+# compute_partial_output of Alg. 2 becomes: attention of ONE query slice against the rank's full keys
+# and values (the rank holds a/T heads over the whole sequence), then the row-shard output projection.
+# Readings: Alg. 4 writes Softmax(Q K^T) with no scaling and no mask; a scale factor is an argument
+# here (1/sqrt(D_h) in the tests, 1 gives the printed form), and no mask is applied, as printed.
+# Tensors: Q, K, V [B, h, S, D_h] (h = local heads); a slice is rows [l*S/N, (l+1)*S/N) of the sequence
+# of every batch element; its tokens are ordered (b, s) and its features (head, d), so that
+# O~ [B*S/N x h*D_h] is the left operand of the projection W_o^r [h*D_h x D].
+# The attention output is rounded to bf16 before the projection when ``round_attn`` is set (the GPU
+# path hands it to the bf16 GEMM), as the up-projection output of the MLP pair is.
+
+def softmax_rows(x: np.ndarray) -> np.ndarray:
+    x = _f64(x)
+    e = np.exp(x - np.max(x, axis=-1, keepdims=True))
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def attention_slice(Q, K, V, l: int, N: int, scale: float) -> np.ndarray:
+    """Attention output of query slice ``l`` of ``N``: ``[B*S/N x h*D_h]``, tokens (b, s), features (head, d)."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    B, h, S, Dh = Q.shape
+    c = S // N
+    out = np.zeros((B, c, h, Dh))
+    for b in range(B):
+        for a in range(h):
+            q = Q[b, a, l * c:(l + 1) * c, :]
+            scores = gemm(q, np.ascontiguousarray(K[b, a].T))
+            w = softmax_rows(scores * scale)
+            out[b, :, a, :] = gemm(w, V[b, a])
+    return out.reshape(B * c, h * Dh)
+
+
+def attn_rs_definition(Q_list, K_list, V_list, Wo_list, scale: float, round_attn: bool = False):
+    """Dense definition: every rank runs full attention over its heads and projects; the partial outputs
+    are reduce-scattered along the sequence.  Returns the per-rank results ``[B*S/N x D]`` (tokens (b, s))."""
+    N = len(Q_list)
+    per_rank_slices = []
+    for r in range(N):
+        parts = []
+        for l in range(N):
+            o = attention_slice(Q_list[r], K_list[r], V_list[r], l, N, scale)
+            if round_attn:
+                o = round_to_bf16(o)
+            parts.append(gemm(o, Wo_list[r]))
+        per_rank_slices.append(parts)
+    return reduce_scatter(per_rank_slices)
+
+
+def fuse_attn_rs_lockstep(Q_list, K_list, V_list, Wo_list, scale: float, round_attn: bool = False):
+    """Alg. 4 by all ranks in lock-step: Alg. 2 whose compute is attention of slice ``l`` then the projection."""
+    N = len(Q_list)
+    B_in = [None] * N
+    O = [None] * N
+    received = [[None] * N for _ in range(N)]
+    sent = [[None] * N for _ in range(N)]
+    for i in range(N):
+        in_flight = [None] * N
+        for r in range(N):
+            l = slice_index_rs(N, r, i)
+            o = attention_slice(Q_list[r], K_list[r], V_list[r], l, N, scale)
+            if round_attn:
+                o = round_to_bf16(o)
+            O[r] = gemm(o, Wo_list[r])
+            if i > 0:
+                received[r][i] = B_in[r]
+                O[r] = add(B_in[r], O[r])
+            if i < N - 1:
+                sent[r][i] = O[r].copy()
+                in_flight[send_rank(N, r)] = sent[r][i]
+        B_in = in_flight
+    return O, received, sent
+
+
+def attn_rs_rank_steps(Q, K, V, Wo, R: Sequence[Optional[np.ndarray]], p: int, r: int, scale: float,
+                       round_attn: bool = True) -> List[np.ndarray]:
+    """One-rank view of Alg. 4: the output of every step, ``R[i]`` being what the neighbour delivers for step i."""
+    outs = []
+    for i in range(p):
+        o = attention_slice(Q, K, V, slice_index_rs(p, r, i), p, scale)
+        if round_attn:
+            o = round_to_bf16(o)
+        out = gemm(o, Wo)
+        if i > 0:
+            out = add(_f64(R[i]), out)
+        outs.append(out)
+    return outs

@@ -641,3 +641,77 @@ def test_backward_fused_is_exact_on_integers(p):
         assert np.array_equal(dW[r], A[r].T @ Gf) and np.array_equal(dA[r], Gf @ W[r].T)
         moving = [G2[(r - i) % p] for i in range(p)]
         assert np.array_equal(oracle.wgrad_rank_steps(moving, A[r], p, r, False)[-1], dW[r])
+
+
+# ----------------------------------------------------------------------------
+# query-split attention (Alg. 4)
+# ----------------------------------------------------------------------------
+
+def _brute_attention(Q, K, V, scale):
+    """Pure-Python loops: softmax(Q K^T * scale) V for [S x Dh] operands."""
+    import math
+    S, Dh = len(Q), len(Q[0])
+    out = [[0.0] * Dh for _ in range(S)]
+    for i in range(S):
+        logits = [scale * sum(Q[i][d] * K[j][d] for d in range(Dh)) for j in range(len(K))]
+        m = max(logits)
+        e = [math.exp(x - m) for x in logits]
+        z = sum(e)
+        for d in range(Dh):
+            out[i][d] = sum(e[j] / z * V[j][d] for j in range(len(K)))
+    return out
+
+
+def test_attention_slice_against_brute_force_and_closed_forms():
+    rng = np.random.default_rng(200)
+    B, h, S, Dh, N = 2, 3, 8, 4, 4
+    Q, K, V = (rng.standard_normal((B, h, S, Dh)) for _ in range(3))
+    scale = 1.0 / np.sqrt(Dh)
+    for l in range(N):
+        got = oracle.attention_slice(Q, K, V, l, N, scale)
+        c = S // N
+        assert got.shape == (B * c, h * Dh)
+        for b in range(B):
+            for a in range(h):
+                want = _brute_attention(Q[b, a, l * c:(l + 1) * c].tolist(), K[b, a].tolist(), V[b, a].tolist(), scale)
+                np.testing.assert_allclose(got[b * c:(b + 1) * c, a * Dh:(a + 1) * Dh], np.array(want), rtol=0, atol=1e-12)
+    # zero queries: every key weighs 1/S, the output is the mean of V
+    got = oracle.attention_slice(np.zeros_like(Q), K, V, 0, 1, scale)
+    np.testing.assert_allclose(got.reshape(B, S, h, Dh), np.broadcast_to(V.mean(axis=2)[:, None], (B, S, h, Dh)), atol=1e-12)
+    # one key far more similar than the rest: the output is that key's value row
+    Kh = np.zeros((1, 1, S, Dh)); Kh[0, 0, 5] = 1.0
+    Qh = np.full((1, 1, S, Dh), 50.0)
+    got = oracle.attention_slice(Qh, Kh, V[:1, :1], 0, 1, 1.0)
+    np.testing.assert_allclose(got, np.broadcast_to(V[0, 0, 5], (S, Dh)), atol=1e-9)
+    # keys and values permuted together: nothing changes; the scale matters (a dropped scale is caught)
+    perm = rng.permutation(S)
+    a0 = oracle.attention_slice(Q, K, V, 1, 2, scale)
+    np.testing.assert_allclose(oracle.attention_slice(Q, K[:, :, perm], V[:, :, perm], 1, 2, scale), a0, atol=1e-12)
+    assert np.abs(oracle.attention_slice(Q, K, V, 1, 2, 1.0) - a0).max() > 1e-3
+    w = oracle.softmax_rows(rng.standard_normal((5, 7)) * 30)
+    np.testing.assert_allclose(w.sum(axis=1), 1.0, atol=1e-12)
+
+
+@pytest.mark.parametrize("p", [1, 2, 4])
+def test_query_split_attention_exactness(p):
+    """Alg. 4 decomposed == every rank's full attention + projection, reduce-scattered == the unsharded layer."""
+    rng = np.random.default_rng(210 + p)
+    B, h, S, Dh, D = 2, 2, 8, 4, 6
+    scale = 0.5
+    Q, K, V = ([rng.standard_normal((B, h, S, Dh)) for _ in range(p)] for _ in range(3))
+    Wo = [rng.standard_normal((h * Dh, D)) for _ in range(p)]
+    want = oracle.attn_rs_definition(Q, K, V, Wo, scale)
+    got, received, sent = oracle.fuse_attn_rs_lockstep(Q, K, V, Wo, scale)
+    # the unsharded layer: all p*h heads on one device, one projection with the stacked W_o
+    Qa, Ka, Va = (np.concatenate(x, axis=1) for x in (Q, K, V))
+    full = oracle.attention_slice(Qa, Ka, Va, 0, 1, scale) @ np.concatenate(Wo, axis=0)          # tokens (b, s)
+    c = S // p
+    for r in range(p):
+        np.testing.assert_allclose(got[r], want[r], rtol=0, atol=1e-12)
+        rows = [b * S + r * c + s for b in range(B) for s in range(c)]
+        np.testing.assert_allclose(got[r], full[rows], rtol=0, atol=1e-11)
+        outs = oracle.attn_rs_rank_steps(Q[r], K[r], V[r], Wo[r], received[r], p, r, scale, round_attn=False)
+        for i in range(p - 1):
+            np.testing.assert_allclose(outs[i], sent[r][i], rtol=0, atol=1e-12)
+        np.testing.assert_allclose(outs[p - 1], got[r], rtol=0, atol=1e-12)
+        assert sent[r][p - 1] is None and received[r][0] is None
