@@ -292,6 +292,58 @@ enum {
 cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_buffers *bufs,
                                 void *compute_stream, void *copy_stream, uint32_t flags);
 
+/* Query-split attention (Alg. 4, Sec. 4.3): FuseReduceScatter whose compute_partial_output
+ * is the attention of ONE query slice against the rank's full keys and values, followed by
+ * the row-shard output projection W_o^r; aggregation and staging for sending as in Alg. 2.
+ * The rank holds `heads` = a/T attention heads over the whole sequence.
+ *   Q, K, V   [batch, heads, seq, head_dim] bf16, contiguous (Alg. 4 "Input" line)
+ *   slice l   = queries [l*seq/p, (l+1)*seq/p) of every batch element; its seq/p * batch
+ *               tokens are ordered (batch element, position), its features (head, d)
+ *   attn_out  [batch*seq/p x heads*head_dim] bf16, caller-owned scratch: the attention
+ *               output of the slice, rounded to bf16, the left operand of the projection
+ *   Wo        [heads*head_dim x n] (CF_W_KN) or its transpose (CF_W_NK), bf16
+ *   recv/out  [batch*seq/p x n] fp32, as for commfuse_rs_step
+ * Readings: Alg. 4 prints Softmax(Q K^T) with neither scale nor mask: `scale` multiplies
+ * the scores (1/sqrt(head_dim) is the usual choice, 1 the printed form) and no mask is
+ * applied.  The softmax runs in fp32; the probabilities are rounded to bf16 for the
+ * product with V (the row sum is taken over the rounded values).  head_dim must be 128
+ * and p must divide seq (CF_ERR_UNSUPPORTED / CF_ERR_INVALID_ARG otherwise). */
+typedef struct {
+    int32_t p, rank;
+    int32_t batch, heads, seq, head_dim;
+    int64_t n;          /* output features D of W_o^r                                  */
+    int64_t ldw;        /* row stride of Wo (0 = packed)                               */
+    int64_t ldo;        /* row stride of partial sums and outputs (0 = n)              */
+    int32_t w_layout;   /* cf_wlayout of Wo                                            */
+    float scale;        /* factor on Q K^T before the softmax                          */
+} cf_attn_desc;
+
+/* The attention of query slice `slice` alone (the first half of a step). */
+cf_status commfuse_attn_slice(const cf_attn_desc *desc, int slice, const void *Q, const void *K, const void *V,
+                              void *attn_out, void *hip_stream);
+
+/* One iteration i of Alg. 4: attention of slice l = (r - i - 1) mod p into attn_out, then
+ *     out = attn_out @ Wo (+ recv if step > 0)       (two kernels on `hip_stream`) */
+cf_status commfuse_attn_rs_step(const cf_attn_desc *desc, int step, const void *Q, const void *K, const void *V,
+                                const void *Wo, const float *recv, float *out, void *attn_out, void *hip_stream);
+
+/* Buffers of a whole emulated rank step of Alg. 4 (HOST struct, DEVICE pointers); the
+ * delivery / sending fields mean what they mean in cf_buffers for CF_KIND_RS. */
+typedef struct {
+    const void *Q, *K, *V, *Wo;
+    void *attn_out;
+    float *O;                       /* O^r [batch*seq/p x n] fp32 */
+    const void *const *peer_stage;
+    void *slot[2];
+    float *send_slot[2];
+    void *const *peer_sink;
+    void *const *recv_each;
+} cf_attn_buffers;
+
+/* A whole rank step of Alg. 4 with the overlap and the flags of commfuse_run_schedule. */
+cf_status commfuse_run_attn_schedule(const cf_attn_desc *desc, const cf_attn_buffers *bufs, void *compute_stream,
+                                     void *copy_stream, uint32_t flags);
+
 /* Synchronises `hip_stream` and reports whether any step kernel since the last call gave up a
  * CF_DEVICE_WAIT wait (CF_ERR_HIP; the status word in the workspace is cleared).  CF_OK if none did
  * or no workspace is registered.  This is the one entry point that synchronises. */

@@ -26,7 +26,8 @@ KINDS = {"rs": CF_KIND_RS, "ag": CF_KIND_AG, "dp": CF_KIND_DP, "rs_pair": CF_KIN
 DTYPES = {"bf16": CF_BF16, "f32": CF_F32}
 
 EXPORTS = [
-    "commfuse_chunk_index", "commfuse_subslice_index", "commfuse_pair_partner", "commfuse_rs_pair_step", "commfuse_rs_pair_last_step", "commfuse_dp_pair_step", "commfuse_wgrad_step", "commfuse_rs_step", "commfuse_ag_step", "commfuse_dp_reduce_step",
+    "commfuse_chunk_index", "commfuse_subslice_index", "commfuse_pair_partner", "commfuse_rs_pair_step", "commfuse_rs_pair_last_step", "commfuse_dp_pair_step", "commfuse_wgrad_step", "commfuse_attn_slice", "commfuse_attn_rs_step",
+    "commfuse_run_attn_schedule", "commfuse_rs_step", "commfuse_ag_step", "commfuse_dp_reduce_step",
     "commfuse_run_schedule", "commfuse_last_error", "commfuse_workspace_bytes", "commfuse_set_workspace",
     "commfuse_device_status",
     "commfuse_destroy_cache", "commfuse_version",
@@ -46,6 +47,26 @@ class LayerDesc(ctypes.Structure):
 class Buffers(ctypes.Structure):
     _fields_ = [
         ("A_or_own_shard", ctypes.c_void_p), ("W", ctypes.c_void_p), ("O", ctypes.c_void_p),
+        ("peer_stage", ctypes.POINTER(ctypes.c_void_p)),
+        ("slot", ctypes.c_void_p * 2), ("send_slot", ctypes.c_void_p * 2),
+        ("peer_sink", ctypes.POINTER(ctypes.c_void_p)),
+        ("recv_each", ctypes.POINTER(ctypes.c_void_p)),
+    ]
+
+
+class AttnDesc(ctypes.Structure):
+    _fields_ = [
+        ("p", ctypes.c_int32), ("rank", ctypes.c_int32),
+        ("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("seq", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("n", ctypes.c_int64), ("ldw", ctypes.c_int64), ("ldo", ctypes.c_int64),
+        ("w_layout", ctypes.c_int32), ("scale", ctypes.c_float),
+    ]
+
+
+class AttnBuffers(ctypes.Structure):
+    _fields_ = [
+        ("Q", ctypes.c_void_p), ("K", ctypes.c_void_p), ("V", ctypes.c_void_p), ("Wo", ctypes.c_void_p),
+        ("attn_out", ctypes.c_void_p), ("O", ctypes.c_void_p),
         ("peer_stage", ctypes.POINTER(ctypes.c_void_p)),
         ("slot", ctypes.c_void_p * 2), ("send_slot", ctypes.c_void_p * 2),
         ("peer_sink", ctypes.POINTER(ctypes.c_void_p)),
@@ -91,6 +112,12 @@ def load():
     lib.commfuse_rs_pair_last_step.restype = i32
     lib.commfuse_wgrad_step.argtypes = [ctypes.POINTER(LayerDesc), i32, vp, vp, vp, vp]
     lib.commfuse_wgrad_step.restype = i32
+    lib.commfuse_attn_slice.argtypes = [ctypes.POINTER(AttnDesc), i32, vp, vp, vp, vp, vp]
+    lib.commfuse_attn_slice.restype = i32
+    lib.commfuse_attn_rs_step.argtypes = [ctypes.POINTER(AttnDesc), i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.commfuse_attn_rs_step.restype = i32
+    lib.commfuse_run_attn_schedule.argtypes = [ctypes.POINTER(AttnDesc), ctypes.POINTER(AttnBuffers), vp, vp, ctypes.c_uint32]
+    lib.commfuse_run_attn_schedule.restype = i32
     lib.commfuse_dp_pair_step.argtypes = [i32, i32, i32, vp, i64, vp, vp]
     lib.commfuse_dp_pair_step.restype = i32
     lib.commfuse_run_schedule.argtypes = [ctypes.POINTER(LayerDesc), i32, ctypes.POINTER(Buffers), vp, vp, ctypes.c_uint32]
@@ -188,6 +215,46 @@ def rs_pair_last_step(desc: LayerDesc, A, W, recv_each: Sequence, out, stream=No
 
 def wgrad_step(desc: LayerDesc, step: int, left, right, dW, stream=None) -> None:
     _check(load().commfuse_wgrad_step(ctypes.byref(desc), step, _ptr(left), _ptr(right), _ptr(dW), _stream(stream)))
+
+
+def attn_desc(p: int, rank: int, batch: int, heads: int, seq: int, head_dim: int, n: int, scale: float,
+              w_layout: int = CF_W_KN, ldw: int = 0, ldo: int = 0) -> AttnDesc:
+    d = AttnDesc()
+    d.p, d.rank, d.batch, d.heads, d.seq, d.head_dim = p, rank, batch, heads, seq, head_dim
+    d.n, d.ldw, d.ldo, d.w_layout, d.scale = n, ldw, ldo, w_layout, scale
+    return d
+
+
+def attn_slice(desc: AttnDesc, slice_: int, Q, K, V, attn_out, stream=None) -> None:
+    _check(load().commfuse_attn_slice(ctypes.byref(desc), slice_, _ptr(Q), _ptr(K), _ptr(V), _ptr(attn_out), _stream(stream)))
+
+
+def attn_rs_step(desc: AttnDesc, step: int, Q, K, V, Wo, recv, out, attn_out, stream=None) -> None:
+    _check(load().commfuse_attn_rs_step(ctypes.byref(desc), step, _ptr(Q), _ptr(K), _ptr(V), _ptr(Wo), _ptr(recv),
+                                        _ptr(out), _ptr(attn_out), _stream(stream)))
+
+
+def _table(seq_):
+    if seq_ is None or not len(seq_):
+        return None, None
+    t = (ctypes.c_void_p * len(seq_))(*[_ptr(x) for x in seq_])
+    return ctypes.cast(t, ctypes.POINTER(ctypes.c_void_p)), t
+
+
+def make_attn_buffers(Q, K, V, Wo, attn_out, O, peer_stage, slot, send_slot, peer_sink=None, recv_each=None) -> AttnBuffers:
+    b = AttnBuffers()
+    b.Q, b.K, b.V, b.Wo, b.attn_out, b.O = _ptr(Q), _ptr(K), _ptr(V), _ptr(Wo), _ptr(attn_out), _ptr(O)
+    b.peer_stage, b._k0 = _table(peer_stage)
+    b.slot[0], b.slot[1] = _ptr(slot[0]), _ptr(slot[1])
+    b.send_slot[0], b.send_slot[1] = _ptr(send_slot[0]), _ptr(send_slot[1])
+    b.peer_sink, b._k1 = _table(peer_sink)
+    b.recv_each, b._k2 = _table(recv_each)
+    return b
+
+
+def run_attn_schedule(desc: AttnDesc, bufs: AttnBuffers, compute_stream, copy_stream, flags: int = 0) -> None:
+    _check(load().commfuse_run_attn_schedule(ctypes.byref(desc), ctypes.byref(bufs), _stream(compute_stream),
+                                             _stream(copy_stream), flags))
 
 
 def dp_pair_step(p: int, rank: int, step: int, bucket, chunk_elems: int, recv, stream=None) -> None:

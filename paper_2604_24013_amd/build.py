@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcommfuse.so")
-SOURCES = ["commfuse_api.hip", "gemm_bf16.hip", "gemm_bf16_dl.hip", "gemm_f32.hip", "dp_reduce.hip"]
+SOURCES = ["commfuse_api.hip", "gemm_bf16.hip", "gemm_bf16_dl.hip", "gemm_f32.hip", "dp_reduce.hip", "attn_slice.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # keep the compiler from forming packed-fp32 VALU instructions

@@ -1,0 +1,318 @@
+// Attention of one query slice against the rank's full keys and values (Alg. 4: scores = Q_s[l] K^T,
+// Softmax, times V), bf16 operands, fp32 accumulation and fp32 online softmax, for gfx950.
+//
+// One workgroup = 4 waves = 4 * 32 * QT queries of one (batch element, head); it walks over the keys in
+// tiles of 64.  Per tile and wave:
+//   S^T = K Q^T      v_mfma_f32_32x32x16_bf16 with the key tile as the MFMA "A" operand and the wave's
+//                    queries (kept in registers for the whole walk) as "B": a lane then owns ONE query
+//                    (lane & 31) and 16 of every 32 keys, so the softmax statistics of a query live in two
+//                    lanes (lane, lane ^ 32) and need one cross-lane exchange per tile;
+//   online softmax   m' = max(m, max S), P = exp2(S - m'), l = l * exp2(m - m') + sum P, O *= exp2(m - m');
+//   O^T += V^T P^T   the probabilities, rounded to bf16, are already in the register layout of an MFMA "B"
+//                    operand if the 16 contraction slots of a slice are taken to mean the keys the lane
+//                    holds (a fixed permutation of the slice's keys); the V tile stays [key x d] in LDS and
+//                    its transposed fragments are fetched with the transposing LDS read at the row offsets
+//                    of that same permutation.  No data moves between lanes, no P tile goes through LDS.
+// K and V tiles go global -> LDS directly (buffer_load ... lds), double-buffered; a key row of 256 bytes has
+// its sixteen 16-byte chunks XOR-ed with (key & 15) so that the fragment reads of 16 consecutive keys hit 16
+// different bank groups; the V tile uses the [k x n] weight-tile layout of the chunk GEMM.
+// Keys beyond the sequence read as zero through the buffer bounds check and are masked to -inf; query rows
+// beyond the slice are computed on zeros and not stored.
+#include "cf_internal.h"
+
+#include <cmath>
+#include <cstdlib>
+#include <type_traits>
+
+namespace cf {
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef int i32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr unsigned OOB = 0x80000000u;
+constexpr int DH = 128;                  // head dimension this kernel is written for
+constexpr int BKV = 64;                  // keys per tile
+constexpr int ROWB = DH * 2;             // bytes of one key / value row
+constexpr int TILE_BYTES = BKV * ROWB;   // 16 KiB
+
+__device__ __forceinline__ i32x4_t make_rsrc(const void *base, unsigned bytes)
+{
+    const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+    i32x4_t r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(a & 0xFFFFFFFFull));
+    r[1] = __builtin_amdgcn_readfirstlane((int)((a >> 32) & 0xFFFFull));
+    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+    r[3] = 0x00020000;
+    return r;
+}
+
+// Wave-wide 16-byte-per-lane load from global memory straight into LDS (lane L lands at lds_addr + 16 L).
+__device__ __forceinline__ void direct_load_16(i32x4_t rsrc, unsigned voffset, int soffset, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\t"
+                 "buffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
+                 : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
+}
+
+// QT: 32-query tiles per wave (1 or 2).
+template <int QT>
+__global__ __launch_bounds__(256) void attn_slice_kernel(AttnParams P)
+{
+    constexpr int WQ = 32 * QT;          // queries per wave
+    constexpr int BQ = 4 * WQ;           // queries per workgroup
+    constexpr int KT = BKV / 32;         // 32-key MFMA tiles per key tile
+    constexpr int DS = DH / 16;          // 16-wide d slices (contraction of S^T)
+    constexpr int DT = DH / 32;          // 32-wide d tiles (rows of O^T)
+    constexpr int LOADS = 2 * TILE_BYTES / 1024 / 4;   // wave-loads per wave per key tile (K and V)
+
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * 2 * TILE_BYTES];   // [buffer][K | V]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lq = lane & 31, lh = lane >> 5;
+
+    const int qblocks = (P.c + BQ - 1) / BQ;
+    const int qb = blockIdx.x % qblocks;
+    const int head = (blockIdx.x / qblocks) % P.heads;
+    const int b = blockIdx.x / (qblocks * P.heads);
+    const int S = P.S;
+
+    const size_t mat = (size_t)S * DH;                               // elements of one (b, head) matrix
+    const __bf16 *Qm = static_cast<const __bf16 *>(P.Q) + ((size_t)b * P.heads + head) * mat;
+    const __bf16 *Km = static_cast<const __bf16 *>(P.K) + ((size_t)b * P.heads + head) * mat;
+    const __bf16 *Vm = static_cast<const __bf16 *>(P.V) + ((size_t)b * P.heads + head) * mat;
+    const i32x4_t k_rsrc = make_rsrc(Km, (unsigned)(mat * 2));
+    const i32x4_t v_rsrc = make_rsrc(Vm, (unsigned)(mat * 2));
+    const unsigned lds_base = __builtin_amdgcn_readfirstlane(
+        (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)smem);
+
+    // The wave's queries as MFMA "B" fragments: lane (lq, lh) holds d = 16 ks + 8 lh + 0..7 of query lq.
+    const int q_in_slice = qb * BQ + wave * WQ;                      // first query of this wave in the slice
+    bf16x8_t qf[QT][DS];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+        const int qi = q_in_slice + t * 32 + lq;
+        const bool ok = qi < P.c;
+        const __bf16 *qrow = Qm + (size_t)(P.l * P.c + (ok ? qi : 0)) * DH;
+#pragma unroll
+        for (int ks = 0; ks < DS; ++ks) {
+            bf16x8_t v = *reinterpret_cast<const bf16x8_t *>(qrow + ks * 16 + lh * 8);
+            if (!ok)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    v[e] = (__bf16)0.0f;
+            qf[t][ks] = v;
+        }
+    }
+
+    // Direct loads of key tile `kt` into buffer `buf`: wave-load j covers 4 rows of 256 bytes.
+    // K: the lane at LDS chunk position cp of row r fetches global chunk cp ^ (r & 15).
+    // V: [k x n] weight-tile layout: the 64-byte groups of a row are XOR-ed with (row & 3).
+    unsigned k_off[LOADS / 2], v_off[LOADS / 2];
+#pragma unroll
+    for (int j = 0; j < LOADS / 2; ++j) {
+        const int row = (j * 4 + wave) * 4 + (lane >> 4);            // key row inside the tile
+        const int cp = lane & 15;
+        k_off[j] = (unsigned)(row * ROWB + ((cp ^ (row & 15)) << 4));
+        const int inrow = cp << 4;
+        const int q = (inrow >> 6) ^ (row & 3);
+        v_off[j] = (unsigned)(row * ROWB + (q << 6) + (inrow & 63));
+    }
+    auto issue_tile = [&](int kt, int buf) {
+        const int key0 = kt * BKV;
+        const unsigned sa = lds_base + buf * 2 * TILE_BYTES + wave * 1024;
+#pragma unroll
+        for (int j = 0; j < LOADS / 2; ++j) {
+            const int row = (j * 4 + wave) * 4 + (lane >> 4);
+            const bool in = key0 + row < S;                          // rows beyond the sequence read as zero
+            direct_load_16(k_rsrc, in ? k_off[j] : OOB, key0 * ROWB, sa + j * 4096);
+            direct_load_16(v_rsrc, in ? v_off[j] : OOB, key0 * ROWB, sa + TILE_BYTES + j * 4096);
+        }
+    };
+
+    // Fragment addresses inside a buffer.
+    // K as "A" operand: lane (key = lq, lh) reads chunk (2 ks + lh) of its key row, swizzled.
+    // V^T as "A" operand: transposing reads; lane (blk = lane >> 4, i16 = lane & 15); the two reads of a
+    // slice start at key rows 4 lh + (i16 >> 2) and 8 more (the permutation the probabilities come in).
+    const int blk = lane >> 4, i16 = lane & 15;
+    const int v_kl = 4 * (blk >> 1) + (i16 >> 2);
+    const int v_nl = (blk & 1) * 16 + (i16 & 3) * 4;
+    int v_addr[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+        v_addr[t] = TILE_BYTES + v_kl * ROWB + (((t) ^ (v_kl & 3)) << 6) + v_nl * 2;
+
+    f32x16_t oacc[QT][DT];
+    float m_run[QT], l_run[QT];
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+        m_run[t] = -INFINITY;
+        l_run[t] = 0.0f;
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                oacc[t][d][e] = 0.0f;
+    }
+    const float sl2 = P.scale * 1.4426950408889634f;                 // scores are kept in units of log2(e)
+
+    const int nkt = (S + BKV - 1) / BKV;
+    issue_tile(0, 0);
+    wait_vmcnt<0>();
+    __syncthreads();
+
+    for (int kt = 0; kt < nkt; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nkt)
+            issue_tile(kt + 1, buf ^ 1);                             // that buffer was released by the last barrier
+        const unsigned char *st = smem + buf * 2 * TILE_BYTES;
+
+        // S^T = K Q^T
+        f32x16_t sacc[QT][KT];
+#pragma unroll
+        for (int t = 0; t < QT; ++t)
+#pragma unroll
+            for (int j = 0; j < KT; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    sacc[t][j][e] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < DS; ++ks) {
+#pragma unroll
+            for (int j = 0; j < KT; ++j) {
+                const int row = j * 32 + lq;
+                const bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(st + row * ROWB + (((2 * ks + lh) ^ (row & 15)) << 4));
+#pragma unroll
+                for (int t = 0; t < QT; ++t)
+                    sacc[t][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t][ks], sacc[t][j], 0, 0, 0);
+            }
+        }
+
+        // online softmax; register 4g+e of key tile j is key 32 j + 8 g + 4 lh + e
+        bf16x8_t pf[QT][KT][2];                                      // "B" fragments of the two 16-key slices of a tile
+#pragma unroll
+        for (int t = 0; t < QT; ++t) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < KT; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = kt * BKV + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                    const float s = key < S ? sacc[t][j][r] * sl2 : -INFINITY;
+                    sacc[t][j][r] = s;
+                    mx = fmaxf(mx, s);
+                }
+            mx = fmaxf(mx, __shfl_xor(mx, 32));                      // the query's other half lives in lane ^ 32
+            const float m_new = fmaxf(m_run[t], mx);                 // finite: every tile holds at least one key
+            const float alpha = exp2f(m_run[t] - m_new);
+            float sum = 0.0f;
+#pragma unroll
+            for (int j = 0; j < KT; ++j)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    bf16x8_t f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float p = exp2f(sacc[t][j][8 * s2 + e] - m_new);
+                        const __bf16 pb = (__bf16)p;
+                        f[e] = pb;
+                        sum += (float)pb;                            // the sum of what is actually multiplied
+                    }
+                    pf[t][j][s2] = f;
+                }
+            l_run[t] = l_run[t] * alpha + sum;
+            m_run[t] = m_new;
+#pragma unroll
+            for (int d = 0; d < DT; ++d)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    oacc[t][d][e] *= alpha;
+        }
+
+        // O^T += V^T P^T
+#pragma unroll
+        for (int j = 0; j < KT; ++j)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const int krow = (j * 32 + s2 * 16) * ROWB;
+#pragma unroll
+                for (int d = 0; d < DT; ++d) {
+                    const unsigned char *pv = st + v_addr[d] + krow;
+                    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) s16x4_t *)(pv));
+                    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (__attribute__((address_space(3))) s16x4_t *)(pv + 8 * ROWB));
+                    const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+#pragma unroll
+                    for (int t = 0; t < QT; ++t)
+                        oacc[t][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t][j][s2], oacc[t][d], 0, 0, 0);
+                }
+            }
+
+        wait_vmcnt<0>();                                             // the next tile has landed
+        __syncthreads();                                             // ... for every wave, and this one is read by all
+    }
+
+    // O = O^T / l, rounded to bf16, written as [token x (head, d)]: the left operand of the output projection.
+    __bf16 *out = static_cast<__bf16 *>(P.out);
+#pragma unroll
+    for (int t = 0; t < QT; ++t) {
+        const float l_tot = l_run[t] + __shfl_xor(l_run[t], 32);
+        const float inv = 1.0f / l_tot;
+        const int qi = q_in_slice + t * 32 + lq;
+        if (qi < P.c) {
+            __bf16 *orow = out + ((size_t)b * P.c + qi) * P.ldo + (size_t)head * DH;
+#pragma unroll
+            for (int d = 0; d < DT; ++d)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x4_t h;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        h[e] = (__bf16)(oacc[t][d][4 * g + e] * inv);
+                    *reinterpret_cast<u32x2_t *>(orow + d * 32 + 8 * g + 4 * lh) = __builtin_bit_cast(u32x2_t, h);
+                }
+        }
+    }
+}
+
+}  // namespace
+
+bool attn_slice_supported(const AttnParams &p)
+{
+    return p.head_dim == DH && p.S > 0 && p.c > 0 && p.heads > 0 && p.batch > 0 &&
+           (int64_t)p.S * DH * 2 < ((int64_t)1 << 31);
+}
+
+hipError_t launch_attn_slice(const AttnParams &p, hipStream_t s)
+{
+    int qt = p.c >= 1024 ? 2 : 1;                     // small slices: more, smaller workgroups
+    if (const char *e = getenv("COMMFUSE_ATTN_QT"))   // tuning override: 32-query tiles per wave
+        qt = atoi(e) == 2 ? 2 : 1;
+    const int bq = 4 * 32 * qt;
+    const int qblocks = (p.c + bq - 1) / bq;
+    const dim3 grid(qblocks * p.heads * p.batch), block(256);
+    if (qt == 2)
+        hipLaunchKernelGGL(attn_slice_kernel<2>, grid, block, 0, s, p);
+    else
+        hipLaunchKernelGGL(attn_slice_kernel<1>, grid, block, 0, s, p);
+    return hipGetLastError();
+}
+
+}  // namespace cf

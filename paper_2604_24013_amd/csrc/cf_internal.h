@@ -45,6 +45,18 @@ struct GemmParams {
     int cp_wgs = 0;
 };
 
+// Attention of one query slice (Alg. 4): out[(b, s) x (head, d)] = softmax(scale * Q_l K^T) V per (b, head).
+// Q, K, V are [batch, heads, S, head_dim] bf16, contiguous; out is bf16 with row stride ldo elements.
+struct AttnParams {
+    const void *Q, *K, *V;
+    void *out;
+    int batch, heads, S, head_dim;
+    int c;               // queries of the slice per batch element (S / N)
+    int l;               // slice index: queries [l*c, (l+1)*c)
+    int64_t ldo;
+    float scale;
+};
+
 struct TileChoice {
     int bm, bn;          // workgroup tile
     int splitk;          // k-splits per output tile (1 = none)
@@ -62,6 +74,9 @@ bool gemm_bf16_takes_recv_list(const GemmParams &p, bool w_kn);
 bool gemm_bf16_dl_supported(const GemmParams &p, bool w_kn);
 hipError_t launch_gemm_bf16_dl(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, TileChoice t);
 hipError_t launch_gemm_f32(const GemmParams &p, bool w_kn, hipStream_t s, int num_cu);
+
+bool attn_slice_supported(const AttnParams &p);
+hipError_t launch_attn_slice(const AttnParams &p, hipStream_t s);
 
 // dst[e] += src[e], e in [0, n)
 hipError_t launch_dp_reduce(float *dst, const float *src, int64_t n, hipStream_t s, int num_cu);

@@ -549,10 +549,26 @@ cf_status get_events(size_t count, std::vector<hipEvent_t> *out)
     return CF_OK;
 }
 
+// Query-split attention (Alg. 4) in front of every reduce-scatter step: the attention of the step's query
+// slice is written to `attn_out`, which is then the chunk GEMM's left operand.
+struct AttnCtx {
+    cf::AttnParams ap;     // Q, K, V, out, geometry; `l` is filled in per step
+};
+
+cf_status launch_attention(const AttnCtx &ctx, int l, hipStream_t s)
+{
+    cf::AttnParams ap = ctx.ap;
+    ap.l = l;
+    hipError_t e = cf::launch_attn_slice(ap, s);
+    if (e != hipSuccess)
+        return fail_hip(e, "attention launch");
+    return CF_OK;
+}
+
 // Enqueues the S = m*p (sub-)steps on the two streams (see commfuse_run_schedule in the header).
 // Sub-step j belongs to hop j / m; hop 0 receives nothing and the last hop sends nothing.
 cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hipStream_t cs, hipStream_t xs_in,
-                           uint32_t flags)
+                           uint32_t flags, const AttnCtx *attn = nullptr)
 {
     const int p = r.p, m = r.m, S = r.p * r.m;
     // CF_FUSED_COPY: the delivery for step j+1 rides in the launch of step j; one stream, no events.
@@ -671,7 +687,13 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
                 CF_HIP(hipStreamWaitEvent(cs, sunk(j - 2), 0));
             const float *recv = receives(j) ? static_cast<const float *>(landing(j)) : nullptr;
             float *out = sends(j) ? b->send_slot[j & 1] : static_cast<float *>(b->O) + (size_t)(j % m) * r.mc * r.ldo;
-            st = rs_step_impl(r, j, b->A_or_own_shard, b->W, recv, out, cs, &job);
+            if (attn != nullptr) {                 // Alg. 4: attention of slice l, then the projection of its output
+                st = launch_attention(*attn, chunk_index(CF_KIND_RS, p, r.rank, j), cs);
+                if (st == CF_OK)
+                    st = launch_gemm(r, attn->ap.out, b->W, recv, out, cs, &job);
+            } else {
+                st = rs_step_impl(r, j, b->A_or_own_shard, b->W, recv, out, cs, &job);
+            }
         } else if (kind == CF_KIND_AG) {
             const void *shard = receives(j) ? landing(j)
                                             : static_cast<const char *>(b->A_or_own_shard) + (size_t)(j % m) * slot_bytes;
@@ -810,6 +832,160 @@ void append_bytes(std::vector<unsigned char> &v, const void *p, size_t n)
     v.insert(v.end(), c, c + n);
 }
 
+// Flag checks, buffer checks and (CF_GRAPH) capture-once / replay shared by the schedule entry points.
+// `key` arrives holding what identifies the descriptor; the rest of the argument set is appended here.
+cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *bufs, hipStream_t cs, hipStream_t xs,
+                              uint32_t flags, const AttnCtx *attn, std::vector<unsigned char> &key)
+{
+    if (flags & ~(uint32_t)(CF_NO_COPY | CF_NO_COMPUTE | CF_SERIAL | CF_POISON | CF_GRAPH | CF_FUSED_COPY | CF_DEVICE_WAIT))
+        return fail(CF_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
+    if (is_pair_kind(kind)) {
+        if (cf_status st = check_pair_p(r.p))
+            return st;
+        if (flags & (CF_FUSED_COPY | CF_DEVICE_WAIT))
+            return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY / CF_DEVICE_WAIT are not available for the pairwise kinds");
+    }
+    if (flags & CF_DEVICE_WAIT) {
+        if (flags & CF_FUSED_COPY)
+            return fail(CF_ERR_UNSUPPORTED, "CF_DEVICE_WAIT and CF_FUSED_COPY exclude each other");
+        // A captured graph has no edge between a flag write and the kernel that polls the flag, so a replay
+        // may queue the writer behind the waiting kernel; two live streams cannot be ordered that way.
+        if (flags & CF_GRAPH)
+            return fail(CF_ERR_UNSUPPORTED, "CF_DEVICE_WAIT cannot be captured into a graph (CF_GRAPH)");
+        if (is_dp_kind(kind) || !(is_wgrad_kind(kind) ? wgrad_can_carry_copy(r) : step_can_carry_copy(r)) ||
+            r.p * r.m > WS_MAX_FLAGS)
+            return fail(CF_ERR_UNSUPPORTED, "CF_DEVICE_WAIT needs the bf16 chunk-GEMM kernels (kind RS or AG, bf16 operands)");
+    }
+    if (flags & CF_FUSED_COPY) {
+        if (flags & CF_POISON)
+            return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY cannot be combined with CF_POISON");
+        if (is_dp_kind(kind) || !(is_wgrad_kind(kind) ? wgrad_can_carry_copy(r) : step_can_carry_copy(r)))
+            return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY needs the bf16 chunk-GEMM kernels (kind RS or AG, bf16 operands)");
+    }
+    if (cf_status st = check_buffers(r, kind, bufs, flags))
+        return st;
+    if (!(flags & CF_GRAPH))
+        return enqueue_schedule(r, kind, bufs, cs, xs, flags, attn);
+
+    // CF_GRAPH: the same enqueue sequence, captured once per distinct argument set.
+    if (cs == nullptr || (xs == nullptr && !(flags & CF_SERIAL)))
+        return fail(CF_ERR_INVALID_ARG, "CF_GRAPH needs explicit (non-default) streams");
+    append_bytes(key, &kind, sizeof(kind));
+    append_bytes(key, &flags, sizeof(flags));
+    append_bytes(key, &cs, sizeof(cs));
+    append_bytes(key, &xs, sizeof(xs));
+    append_bytes(key, &bufs->A_or_own_shard, sizeof(void *));
+    append_bytes(key, &bufs->W, sizeof(void *));
+    append_bytes(key, &bufs->O, sizeof(void *));
+    append_bytes(key, bufs->slot, sizeof(bufs->slot));
+    append_bytes(key, bufs->send_slot, sizeof(bufs->send_slot));
+    if (attn != nullptr) {
+        append_bytes(key, &attn->ap.Q, sizeof(void *));
+        append_bytes(key, &attn->ap.K, sizeof(void *));
+        append_bytes(key, &attn->ap.V, sizeof(void *));
+        append_bytes(key, &attn->ap.out, sizeof(void *));
+    }
+    {   // the registered workspace is baked into the captured kernels (split-K partials, delivery flags)
+        std::lock_guard<std::mutex> lk(g_ws_mu);
+        append_bytes(key, &g_ws.ptr, sizeof(g_ws.ptr));
+        append_bytes(key, &g_ws.bytes, sizeof(g_ws.bytes));
+    }
+    for (int i = 0; i < r.p - 1; ++i) {
+        const void *st = bufs->peer_stage ? bufs->peer_stage[i] : nullptr;
+        const void *sk = bufs->peer_sink ? bufs->peer_sink[i] : nullptr;
+        const void *re = bufs->recv_each ? bufs->recv_each[i] : nullptr;
+        append_bytes(key, &st, sizeof(st));
+        append_bytes(key, &sk, sizeof(sk));
+        append_bytes(key, &re, sizeof(re));
+    }
+    hipGraphExec_t exec = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        for (const GraphEntry &g : g_graphs)
+            if (g.key == key)
+                exec = g.exec;
+    }
+    if (exec == nullptr) {
+        // events must exist before capture starts (creation is not a capturable operation)
+        std::vector<hipEvent_t> tmp;
+        if (cf_status st = get_events(2 + 3 * (size_t)r.p * r.m, &tmp))
+            return st;
+        CF_HIP(hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal));
+        cf_status st = enqueue_schedule(r, kind, bufs, cs, xs, flags & ~(uint32_t)CF_GRAPH, attn);
+        hipGraph_t graph = nullptr;
+        hipError_t e = hipStreamEndCapture(cs, &graph);
+        if (st != CF_OK) {
+            if (graph)
+                (void)hipGraphDestroy(graph);
+            return st;
+        }
+        if (e != hipSuccess)
+            return fail_hip(e, "hipStreamEndCapture");
+        e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+        if (e != hipSuccess) {
+            (void)hipGraphDestroy(graph);
+            return fail_hip(e, "hipGraphInstantiate");
+        }
+        std::lock_guard<std::mutex> lk(g_mu);
+        g_graphs.push_back(GraphEntry{key, graph, exec});
+    }
+    CF_HIP(hipGraphLaunch(exec, cs));
+    return CF_OK;
+}
+
+// cf_attn_desc -> the reduce-scatter layer it projects into, and the attention geometry.
+cf_status resolve_attn(const cf_attn_desc *d, Resolved *out, cf::AttnParams *ap)
+{
+    if (d == nullptr)
+        return fail(CF_ERR_NULL_PTR, "descriptor is NULL");
+    if (d->p < 1 || d->rank < 0 || d->rank >= d->p)
+        return fail(CF_ERR_INVALID_ARG, "need p >= 1 and rank in [0, p)");
+    if (d->batch < 1 || d->heads < 1 || d->seq < 1 || d->n < 0)
+        return fail(CF_ERR_INVALID_ARG, "batch, heads and seq must be positive, n non-negative");
+    if (d->seq % d->p != 0)
+        return fail(CF_ERR_INVALID_ARG, "p = %d must divide the sequence length %d", d->p, d->seq);
+    if (d->head_dim != 128)
+        return fail(CF_ERR_UNSUPPORTED, "head_dim %d: the attention kernel is written for 128", d->head_dim);
+    if (!(d->scale > 0.0f) || !(d->scale < 1e30f))
+        return fail(CF_ERR_INVALID_ARG, "scale must be a positive finite number");
+    cf_layer_desc ld;
+    memset(&ld, 0, sizeof(ld));
+    ld.p = d->p;
+    ld.rank = d->rank;
+    ld.m_chunk = (int64_t)d->batch * (d->seq / d->p);
+    ld.n = d->n;
+    ld.k = (int64_t)d->heads * d->head_dim;
+    ld.ldw = d->ldw;
+    ld.ldo = d->ldo;
+    ld.in_dtype = CF_BF16;
+    ld.out_dtype = CF_F32;
+    ld.w_layout = d->w_layout;
+    if (cf_status st = resolve(&ld, CF_KIND_RS, out))
+        return st;
+    ap->Q = ap->K = ap->V = nullptr;
+    ap->out = nullptr;
+    ap->batch = d->batch;
+    ap->heads = d->heads;
+    ap->S = d->seq;
+    ap->head_dim = d->head_dim;
+    ap->c = d->seq / d->p;
+    ap->l = 0;
+    ap->ldo = out->k;                              // attention output rows are the projection's packed left operand
+    ap->scale = d->scale;
+    if (!cf::attn_slice_supported(*ap))
+        return fail(CF_ERR_UNSUPPORTED, "a (batch, head) matrix of K or V must stay below 2 GiB");
+    return CF_OK;
+}
+
+cf_status check_attn_ptrs(const void *Q, const void *K, const void *V, const void *attn_out)
+{
+    if (Q == nullptr || K == nullptr || V == nullptr || attn_out == nullptr)
+        return fail(CF_ERR_NULL_PTR, "Q, K, V and attn_out must not be NULL");
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(attn_out))
+        return fail(CF_ERR_MISALIGNED, "tensor pointers must be 16-byte aligned");
+    return CF_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -912,101 +1088,97 @@ cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_bu
 {
     if (!known_kind(kind))
         return fail(CF_ERR_INVALID_ARG, "kind %d", kind);
-    if (flags & ~(uint32_t)(CF_NO_COPY | CF_NO_COMPUTE | CF_SERIAL | CF_POISON | CF_GRAPH | CF_FUSED_COPY | CF_DEVICE_WAIT))
-        return fail(CF_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
     Resolved r;
     if (cf_status st = resolve(desc, kind, &r))
         return st;
-    if (is_pair_kind(kind)) {
-        if (cf_status st = check_pair_p(r.p))
-            return st;
-        if (flags & (CF_FUSED_COPY | CF_DEVICE_WAIT))
-            return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY / CF_DEVICE_WAIT are not available for the pairwise kinds");
-    }
-    if (flags & CF_DEVICE_WAIT) {
-        if (flags & CF_FUSED_COPY)
-            return fail(CF_ERR_UNSUPPORTED, "CF_DEVICE_WAIT and CF_FUSED_COPY exclude each other");
-        // A captured graph has no edge between a flag write and the kernel that polls the flag, so a replay
-        // may queue the writer behind the waiting kernel; two live streams cannot be ordered that way.
-        if (flags & CF_GRAPH)
-            return fail(CF_ERR_UNSUPPORTED, "CF_DEVICE_WAIT cannot be captured into a graph (CF_GRAPH)");
-        if (is_dp_kind(kind) || !(is_wgrad_kind(kind) ? wgrad_can_carry_copy(r) : step_can_carry_copy(r)) ||
-            r.p * r.m > WS_MAX_FLAGS)
-            return fail(CF_ERR_UNSUPPORTED, "CF_DEVICE_WAIT needs the bf16 chunk-GEMM kernels (kind RS or AG, bf16 operands)");
-    }
-    if (flags & CF_FUSED_COPY) {
-        if (flags & CF_POISON)
-            return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY cannot be combined with CF_POISON");
-        if (is_dp_kind(kind) || !(is_wgrad_kind(kind) ? wgrad_can_carry_copy(r) : step_can_carry_copy(r)))
-            return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY needs the bf16 chunk-GEMM kernels (kind RS or AG, bf16 operands)");
-    }
-    if (cf_status st = check_buffers(r, kind, bufs, flags))
-        return st;
-    hipStream_t cs = static_cast<hipStream_t>(compute_stream);
-    hipStream_t xs = static_cast<hipStream_t>(copy_stream);
-    if (!(flags & CF_GRAPH))
-        return enqueue_schedule(r, kind, bufs, cs, xs, flags);
-
-    // CF_GRAPH: the same enqueue sequence, captured once per distinct argument set.
-    if (cs == nullptr || (xs == nullptr && !(flags & CF_SERIAL)))
-        return fail(CF_ERR_INVALID_ARG, "CF_GRAPH needs explicit (non-default) streams");
     std::vector<unsigned char> key;
     append_bytes(key, desc, sizeof(*desc));
-    append_bytes(key, &kind, sizeof(kind));
-    append_bytes(key, &flags, sizeof(flags));
-    append_bytes(key, &cs, sizeof(cs));
-    append_bytes(key, &xs, sizeof(xs));
-    append_bytes(key, &bufs->A_or_own_shard, sizeof(void *));
-    append_bytes(key, &bufs->W, sizeof(void *));
-    append_bytes(key, &bufs->O, sizeof(void *));
-    append_bytes(key, bufs->slot, sizeof(bufs->slot));
-    append_bytes(key, bufs->send_slot, sizeof(bufs->send_slot));
-    {   // the registered workspace is baked into the captured kernels (split-K partials, delivery flags)
-        std::lock_guard<std::mutex> lk(g_ws_mu);
-        append_bytes(key, &g_ws.ptr, sizeof(g_ws.ptr));
-        append_bytes(key, &g_ws.bytes, sizeof(g_ws.bytes));
-    }
-    for (int i = 0; i < r.p - 1; ++i) {
-        const void *st = bufs->peer_stage ? bufs->peer_stage[i] : nullptr;
-        const void *sk = bufs->peer_sink ? bufs->peer_sink[i] : nullptr;
-        const void *re = bufs->recv_each ? bufs->recv_each[i] : nullptr;
-        append_bytes(key, &st, sizeof(st));
-        append_bytes(key, &sk, sizeof(sk));
-        append_bytes(key, &re, sizeof(re));
-    }
-    hipGraphExec_t exec = nullptr;
-    {
-        std::lock_guard<std::mutex> lk(g_mu);
-        for (const GraphEntry &g : g_graphs)
-            if (g.key == key)
-                exec = g.exec;
-    }
-    if (exec == nullptr) {
-        // events must exist before capture starts (creation is not a capturable operation)
-        std::vector<hipEvent_t> tmp;
-        if (cf_status st = get_events(2 + 3 * (size_t)r.p * r.m, &tmp))
-            return st;
-        CF_HIP(hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal));
-        cf_status st = enqueue_schedule(r, kind, bufs, cs, xs, flags & ~(uint32_t)CF_GRAPH);
-        hipGraph_t graph = nullptr;
-        hipError_t e = hipStreamEndCapture(cs, &graph);
-        if (st != CF_OK) {
-            if (graph)
-                (void)hipGraphDestroy(graph);
-            return st;
-        }
-        if (e != hipSuccess)
-            return fail_hip(e, "hipStreamEndCapture");
-        e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
-        if (e != hipSuccess) {
-            (void)hipGraphDestroy(graph);
-            return fail_hip(e, "hipGraphInstantiate");
-        }
-        std::lock_guard<std::mutex> lk(g_mu);
-        g_graphs.push_back(GraphEntry{key, graph, exec});
-    }
-    CF_HIP(hipGraphLaunch(exec, cs));
-    return CF_OK;
+    return run_schedule_common(r, kind, bufs, static_cast<hipStream_t>(compute_stream),
+                               static_cast<hipStream_t>(copy_stream), flags, nullptr, key);
+}
+
+cf_status commfuse_attn_slice(const cf_attn_desc *desc, int slice, const void *Q, const void *K, const void *V,
+                              void *attn_out, void *hip_stream)
+{
+    Resolved r;
+    AttnCtx ctx;
+    if (cf_status st = resolve_attn(desc, &r, &ctx.ap))
+        return st;
+    if (slice < 0 || slice >= r.p)
+        return fail(CF_ERR_INVALID_ARG, "slice = %d not in [0, %d)", slice, r.p);
+    if (cf_status st = check_attn_ptrs(Q, K, V, attn_out))
+        return st;
+    ctx.ap.Q = Q;
+    ctx.ap.K = K;
+    ctx.ap.V = V;
+    ctx.ap.out = attn_out;
+    return launch_attention(ctx, slice, static_cast<hipStream_t>(hip_stream));
+}
+
+cf_status commfuse_attn_rs_step(const cf_attn_desc *desc, int step, const void *Q, const void *K, const void *V,
+                                const void *Wo, const float *recv, float *out, void *attn_out, void *hip_stream)
+{
+    Resolved r;
+    AttnCtx ctx;
+    if (cf_status st = resolve_attn(desc, &r, &ctx.ap))
+        return st;
+    if (cf_status st = check_step(r, step))
+        return st;
+    if (cf_status st = check_attn_ptrs(Q, K, V, attn_out))
+        return st;
+    if (Wo == nullptr || out == nullptr)
+        return fail(CF_ERR_NULL_PTR, "Wo and out must not be NULL");
+    if (step == 0 && recv != nullptr)
+        return fail(CF_ERR_NULL_PTR, "recv must be NULL at step 0 (nothing has been received yet)");
+    if (step > 0 && recv == nullptr)
+        return fail(CF_ERR_NULL_PTR, "recv must not be NULL at step %d", step);
+    if (recv == out)
+        return fail(CF_ERR_INVALID_ARG, "out may not alias recv");
+    if (!aligned16(Wo) || !aligned16(out) || !aligned16(recv))
+        return fail(CF_ERR_MISALIGNED, "tensor pointers must be 16-byte aligned");
+    ctx.ap.Q = Q;
+    ctx.ap.K = K;
+    ctx.ap.V = V;
+    ctx.ap.out = attn_out;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (cf_status st = launch_attention(ctx, chunk_index(CF_KIND_RS, r.p, r.rank, step), s))
+        return st;
+    return launch_gemm(r, attn_out, Wo, recv, out, s);
+}
+
+cf_status commfuse_run_attn_schedule(const cf_attn_desc *desc, const cf_attn_buffers *ab, void *compute_stream,
+                                     void *copy_stream, uint32_t flags)
+{
+    Resolved r;
+    AttnCtx ctx;
+    if (cf_status st = resolve_attn(desc, &r, &ctx.ap))
+        return st;
+    if (ab == nullptr)
+        return fail(CF_ERR_NULL_PTR, "buffers is NULL");
+    if (cf_status st = check_attn_ptrs(ab->Q, ab->K, ab->V, ab->attn_out))
+        return st;
+    ctx.ap.Q = ab->Q;
+    ctx.ap.K = ab->K;
+    ctx.ap.V = ab->V;
+    ctx.ap.out = ab->attn_out;
+    cf_buffers b;
+    memset(&b, 0, sizeof(b));
+    b.A_or_own_shard = ab->attn_out;
+    b.W = ab->Wo;
+    b.O = ab->O;
+    b.peer_stage = ab->peer_stage;
+    b.slot[0] = ab->slot[0];
+    b.slot[1] = ab->slot[1];
+    b.send_slot[0] = ab->send_slot[0];
+    b.send_slot[1] = ab->send_slot[1];
+    b.peer_sink = ab->peer_sink;
+    b.recv_each = ab->recv_each;
+    std::vector<unsigned char> key;
+    append_bytes(key, desc, sizeof(*desc));
+    const char tag[8] = "attn";
+    append_bytes(key, tag, sizeof(tag));
+    return run_schedule_common(r, CF_KIND_RS, &b, static_cast<hipStream_t>(compute_stream),
+                               static_cast<hipStream_t>(copy_stream), flags, &ctx, key);
 }
 
 size_t commfuse_workspace_bytes(const cf_layer_desc *desc, int kind)
