@@ -274,6 +274,41 @@ def main() -> int:
         del A_loc, stage16, bufs, W_dn, W_up
         torch.cuda.empty_cache()
 
+    # ---------------- query-split attention FuseRS (Alg. 4), 70B shape: 8 of 64 heads per rank ----------------
+    attention = {}
+    if not args.only_pair:
+        rng = np.random.default_rng(inputs.BASE_SEED + 78)
+        pa, Ba, ha, Sa, Da = 8, 1, 8, 8192, 8192
+        mca = Ba * Sa // pa
+        def bf16_dev(shape, sigma):
+            return H.to_dev(inputs.f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32) * sigma), "bf16")
+        Qa, Ka, Va = (bf16_dev((Ba, ha, Sa, 128), 1.0) for _ in range(3))
+        Woa = bf16_dev((ha * 128, Da), 0.01)
+        adesc = cf.attn_desc(pa, 0, Ba, ha, Sa, 128, Da, 1.0 / 128 ** 0.5)
+        attn_out = torch.empty((mca, ha * 128), dtype=torch.bfloat16, device=H.DEV)
+        mk32 = lambda: torch.empty((mca, Da), dtype=torch.float32, device=H.DEV)
+        stage_a = [mk32().normal_() for _ in range(pa - 1)]
+        abufs = cf.make_attn_buffers(Qa, Ka, Va, Woa, attn_out, mk32(), stage_a, [mk32(), mk32()], [mk32(), mk32()],
+                                     None, [mk32() for _ in range(pa - 1)])
+        cs, xs = torch.cuda.Stream(), torch.cuda.Stream()
+        t_attn = time_calls(lambda: cf.attn_slice(adesc, 1, Qa, Ka, Va, attn_out, cs), cs, 50, W)
+        fl_attn = 4.0 * Ba * ha * (Sa // pa) * Sa * 128
+        fl_proj = 2.0 * mca * Da * ha * 128
+        best = None
+        for mode, extra in MODES:
+            t = time_calls(lambda: cf.run_attn_schedule(adesc, abufs, cs, xs, extra), cs, max(K, 30), W)
+            if best is None or t < best[0]:
+                best = (t, mode)
+        attention = {"attention_kernel_us": round(t_attn * 1e3, 1),
+                     "attention_kernel_tflops": round(fl_attn / (t_attn * 1e-3) / 1e12, 1),
+                     "frac_mfma_peak_attention_kernel": round(fl_attn / (t_attn * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                     "rank_step_us": round(best[0] * 1e3, 1), "mode": best[1],
+                     "rank_step_tflops": round(pa * (fl_attn + fl_proj) / (best[0] * 1e-3) / 1e12, 1),
+                     "shape": "p=8, 8 of 64 heads per rank, head_dim 128, seq 8192, batch 1, W_o [1024 x 8192]"}
+        log("attention", attention)
+        del Qa, Ka, Va, Woa, abufs, stage_a
+        torch.cuda.empty_cache()
+
     # ---------------- gradient reduce-scatter step, 1e9 fp32 elements ----------------
     dp = None
     if not (args.skip_dp or args.only_pair):
@@ -339,7 +374,7 @@ def main() -> int:
         "overlap_eff": round(max(pair_t["compute_only"][0], pair_t["copy_only"][0]) / ms_step, 3),
         "ms_compute_only": round(pair_t["compute_only"][0], 4), "ms_copy_only": round(pair_t["copy_only"][0], 4),
         "roofline": roofline, "cpu_baseline": cpu, "dp_reduce": dp, "other_configs": others,
-        "pairwise_schedule": pairwise, "slicing_granularity": granularity, "backward_pass": backward,
+        "pairwise_schedule": pairwise, "slicing_granularity": granularity, "backward_pass": backward, "query_split_attention": attention,
     }
     print(json.dumps(line), flush=True)
     return 0

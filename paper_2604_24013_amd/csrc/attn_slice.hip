@@ -292,6 +292,213 @@ __global__ __launch_bounds__(256) void attn_slice_kernel(AttnParams P)
     }
 }
 
+// Variant for slices with few queries (the per-step grids of Alg. 4 are small: seq/p queries per head): one
+// workgroup = 32 queries of one (batch element, head); its four waves split the KEYS -- wave w takes the
+// 32-key tiles w, w+4, w+8, ... -- each with its own double-buffered K/V landing zone in LDS (no barrier in
+// the walk), and the four partial results (m, l, unnormalised O) are merged through LDS at the end.
+__global__ __launch_bounds__(256) void attn_slice_ksplit_kernel(AttnParams P)
+{
+    constexpr int BK = 32;                   // keys per tile
+    constexpr int TB = BK * ROWB;            // 8 KiB: one K (or V) tile
+    constexpr int DS = DH / 16, DT = DH / 32;
+    constexpr int WAVE_LDS = 4 * TB;         // [buffer][K | V]
+
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[4 * WAVE_LDS];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lq = lane & 31, lh = lane >> 5;
+
+    const int qtiles = (P.c + 31) / 32;
+    const int head = blockIdx.x % P.heads;   // neighbouring workgroups (one per XCD in turn) take different heads:
+    const int qt = (blockIdx.x / P.heads) % qtiles;   // with 8 heads, each XCD's L2 serves one head's K and V
+    const int b = blockIdx.x / (P.heads * qtiles);
+    const int S = P.S;
+
+    const size_t mat = (size_t)S * DH;
+    const __bf16 *Qm = static_cast<const __bf16 *>(P.Q) + ((size_t)b * P.heads + head) * mat;
+    const __bf16 *Km = static_cast<const __bf16 *>(P.K) + ((size_t)b * P.heads + head) * mat;
+    const __bf16 *Vm = static_cast<const __bf16 *>(P.V) + ((size_t)b * P.heads + head) * mat;
+    const i32x4_t k_rsrc = make_rsrc(Km, (unsigned)(mat * 2));
+    const i32x4_t v_rsrc = make_rsrc(Vm, (unsigned)(mat * 2));
+    const unsigned lds_base = __builtin_amdgcn_readfirstlane(
+        (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)smem) + wave * WAVE_LDS;
+    unsigned char *my = smem + wave * WAVE_LDS;
+
+    const int qi = qt * 32 + lq;
+    const bool q_ok = qi < P.c;
+    bf16x8_t qf[DS];
+    {
+        const __bf16 *qrow = Qm + (size_t)(P.l * P.c + (q_ok ? qi : 0)) * DH;
+#pragma unroll
+        for (int ks = 0; ks < DS; ++ks) {
+            bf16x8_t v = *reinterpret_cast<const bf16x8_t *>(qrow + ks * 16 + lh * 8);
+            if (!q_ok)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    v[e] = (__bf16)0.0f;
+            qf[ks] = v;
+        }
+    }
+
+    // wave-load j (1 KiB) covers rows 4j .. 4j+3 of the tile; layouts as in the kernel above
+    unsigned k_off[8], v_off[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int row = j * 4 + (lane >> 4);
+        const int cp = lane & 15;
+        k_off[j] = (unsigned)(row * ROWB + ((cp ^ (row & 15)) << 4));
+        const int inrow = cp << 4;
+        v_off[j] = (unsigned)(row * ROWB + (((inrow >> 6) ^ (row & 3)) << 6) + (inrow & 63));
+    }
+    auto issue_tile = [&](int kt, int buf) {
+        const int key0 = kt * BK;
+        const unsigned sa = lds_base + buf * 2 * TB;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const bool in = key0 + j * 4 + (lane >> 4) < S;
+            direct_load_16(k_rsrc, in ? k_off[j] : OOB, key0 * ROWB, sa + j * 1024);
+            direct_load_16(v_rsrc, in ? v_off[j] : OOB, key0 * ROWB, sa + TB + j * 1024);
+        }
+    };
+
+    const int blk = lane >> 4, i16 = lane & 15;
+    const int v_kl = 4 * (blk >> 1) + (i16 >> 2);
+    const int v_nl = (blk & 1) * 16 + (i16 & 3) * 4;
+    int v_addr[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+        v_addr[t] = TB + v_kl * ROWB + ((t ^ (v_kl & 3)) << 6) + v_nl * 2;
+
+    f32x16_t oacc[DT];
+#pragma unroll
+    for (int d = 0; d < DT; ++d)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            oacc[d][e] = 0.0f;
+    float m_run = -INFINITY, l_run = 0.0f;
+    const float sl2 = P.scale * 1.4426950408889634f;
+
+    const int nkt = (S + BK - 1) / BK;
+    int buf = 0;
+    if (wave < nkt)
+        issue_tile(wave, 0);
+    for (int kt = wave; kt < nkt; kt += 4) {
+        wait_vmcnt<0>();                                             // tile kt has landed (this wave's own loads)
+        if (kt + 4 < nkt)
+            issue_tile(kt + 4, buf ^ 1);                             // its last readers' MFMAs were issued long ago
+        const unsigned char *st = my + buf * 2 * TB;
+
+        f32x16_t sacc;
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            sacc[e] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < DS; ++ks) {
+            const bf16x8_t kf = *reinterpret_cast<const bf16x8_t *>(st + lq * ROWB + (((2 * ks + lh) ^ (lq & 15)) << 4));
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sacc, 0, 0, 0);
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int key = kt * BK + 8 * (r >> 2) + 4 * lh + (r & 3);
+            const float sv = key < S ? sacc[r] * sl2 : -INFINITY;
+            sacc[r] = sv;
+            mx = fmaxf(mx, sv);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = exp2f(m_run - m_new);
+        float sum = 0.0f;
+        bf16x8_t pf[2];
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const __bf16 pb = (__bf16)exp2f(sacc[8 * s2 + e] - m_new);
+                pf[s2][e] = pb;
+                sum += (float)pb;
+            }
+        l_run = l_run * alpha + sum;
+        m_run = m_new;
+        if (__any(alpha != 1.0f)) {                                  // the running maximum settles after a few tiles
+#pragma unroll
+            for (int d = 0; d < DT; ++d)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    oacc[d][e] *= alpha;
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+            for (int d = 0; d < DT; ++d) {
+                const unsigned char *pv = st + v_addr[d] + s2 * 16 * ROWB;
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) s16x4_t *)(pv));
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) s16x4_t *)(pv + 8 * ROWB));
+                const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+                oacc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s2], oacc[d], 0, 0, 0);
+            }
+        buf ^= 1;
+    }
+    wait_vmcnt<0>();
+    __syncthreads();                                                 // every wave is done with its tiles
+
+    // Merge the four partial results: lane L of every wave owns the same (query, d) positions.
+    float *mo = reinterpret_cast<float *>(smem);                     // [wave][lane][64] unnormalised O
+    float *ms = reinterpret_cast<float *>(smem + 4 * 64 * 64 * 4);   // [wave][lane][2]   m, l (both half-lanes summed)
+    const float l_pair = l_run + __shfl_xor(l_run, 32);
+    if (wave > 0) {
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                mo[(wave * 64 + lane) * 64 + d * 16 + e] = oacc[d][e];
+        ms[(wave * 64 + lane) * 2 + 0] = m_run;
+        ms[(wave * 64 + lane) * 2 + 1] = l_pair;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        float m_all = m_run;
+#pragma unroll
+        for (int w = 1; w < 4; ++w)
+            m_all = fmaxf(m_all, ms[(w * 64 + lane) * 2 + 0]);
+        const float f0 = exp2f(m_run - m_all);                       // wave 0 always has a tile: m_all is finite
+        float l_all = l_pair * f0;
+#pragma unroll
+        for (int d = 0; d < DT; ++d)
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                oacc[d][e] *= f0;
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const float fw = exp2f(ms[(w * 64 + lane) * 2 + 0] - m_all);   // 0 for a wave that saw no key
+            l_all += ms[(w * 64 + lane) * 2 + 1] * fw;
+#pragma unroll
+            for (int d = 0; d < DT; ++d)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    oacc[d][e] += mo[(w * 64 + lane) * 64 + d * 16 + e] * fw;
+        }
+        if (q_ok) {
+            const float inv = 1.0f / l_all;
+            __bf16 *orow = static_cast<__bf16 *>(P.out) + ((size_t)b * P.c + qi) * P.ldo + (size_t)head * DH;
+#pragma unroll
+            for (int d = 0; d < DT; ++d)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x4_t h;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        h[e] = (__bf16)(oacc[d][4 * g + e] * inv);
+                    *reinterpret_cast<u32x2_t *>(orow + d * 32 + 8 * g + 4 * lh) = __builtin_bit_cast(u32x2_t, h);
+                }
+        }
+    }
+}
+
 }  // namespace
 
 bool attn_slice_supported(const AttnParams &p)
@@ -300,11 +507,22 @@ bool attn_slice_supported(const AttnParams &p)
            (int64_t)p.S * DH * 2 < ((int64_t)1 << 31);
 }
 
-hipError_t launch_attn_slice(const AttnParams &p, hipStream_t s)
+hipError_t launch_attn_slice(const AttnParams &p, hipStream_t s, int num_cu)
 {
-    int qt = p.c >= 1024 ? 2 : 1;                     // small slices: more, smaller workgroups
-    if (const char *e = getenv("COMMFUSE_ATTN_QT"))   // tuning override: 32-query tiles per wave
-        qt = atoi(e) == 2 ? 2 : 1;
+    // 128 queries per workgroup (key tiles shared by four waves) when that fills the chip, else 32 queries
+    // per workgroup with the keys split over its waves
+    int qt = 1;
+    bool ksplit = (int64_t)((p.c + 127) / 128) * p.heads * p.batch * 4 < (int64_t)num_cu * 3;
+    if (const char *e = getenv("COMMFUSE_ATTN_QT")) { // tuning override: 32-query tiles per wave, 0 = key split
+        qt = atoi(e);
+        ksplit = qt == 0;
+        qt = qt == 2 ? 2 : 1;
+    }
+    if (ksplit) {
+        const dim3 grid(((p.c + 31) / 32) * p.heads * p.batch), block(256);
+        hipLaunchKernelGGL(attn_slice_ksplit_kernel, grid, block, 0, s, p);
+        return hipGetLastError();
+    }
     const int bq = 4 * 32 * qt;
     const int qblocks = (p.c + bq - 1) / bq;
     const dim3 grid(qblocks * p.heads * p.batch), block(256);

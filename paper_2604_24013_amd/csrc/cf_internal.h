@@ -76,7 +76,7 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p, bool w_kn, bool out_bf16, hi
 hipError_t launch_gemm_f32(const GemmParams &p, bool w_kn, hipStream_t s, int num_cu);
 
 bool attn_slice_supported(const AttnParams &p);
-hipError_t launch_attn_slice(const AttnParams &p, hipStream_t s);
+hipError_t launch_attn_slice(const AttnParams &p, hipStream_t s, int num_cu);
 
 // dst[e] += src[e], e in [0, n)
 hipError_t launch_dp_reduce(float *dst, const float *src, int64_t n, hipStream_t s, int num_cu);

@@ -559,7 +559,7 @@ cf_status launch_attention(const AttnCtx &ctx, int l, hipStream_t s)
 {
     cf::AttnParams ap = ctx.ap;
     ap.l = l;
-    hipError_t e = cf::launch_attn_slice(ap, s);
+    hipError_t e = cf::launch_attn_slice(ap, s, num_cu_of_current_device());
     if (e != hipSuccess)
         return fail_hip(e, "attention launch");
     return CF_OK;

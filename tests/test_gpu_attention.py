@@ -59,7 +59,7 @@ ATTN_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("qt", ["1", "2"])
+@pytest.mark.parametrize("qt", ["0", "1", "2"])        # 0: keys split over the waves
 @pytest.mark.parametrize("shape", ATTN_SHAPES)
 def test_attention_slice(shape, qt):
     p, B, h, S = shape
