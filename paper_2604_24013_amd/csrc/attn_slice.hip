@@ -69,16 +69,18 @@ __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
 }
 
-// QT: 32-query tiles per wave (1 or 2).
-template <int QT>
-__global__ __launch_bounds__(256) void attn_slice_kernel(AttnParams P)
+// QT: 32-query tiles per wave (1 or 2); NW: waves per workgroup (4, or 8 = two per SIMD, so that one wave's
+// softmax arithmetic runs under the other's MFMAs).
+template <int QT, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_slice_kernel(AttnParams P)
 {
+    constexpr int NT = 64 * NW;          // threads per workgroup
     constexpr int WQ = 32 * QT;          // queries per wave
-    constexpr int BQ = 4 * WQ;           // queries per workgroup
+    constexpr int BQ = NW * WQ;          // queries per workgroup
     constexpr int KT = BKV / 32;         // 32-key MFMA tiles per key tile
     constexpr int DS = DH / 16;          // 16-wide d slices (contraction of S^T)
     constexpr int DT = DH / 32;          // 32-wide d tiles (rows of O^T)
-    constexpr int LOADS = 2 * TILE_BYTES / 1024 / 4;   // wave-loads per wave per key tile (K and V)
+    constexpr int LOADS = 2 * TILE_BYTES / 1024 / NW;  // wave-loads per wave per key tile (K and V)
 
     __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * 2 * TILE_BYTES];   // [buffer][K | V]
 
@@ -88,9 +90,12 @@ __global__ __launch_bounds__(256) void attn_slice_kernel(AttnParams P)
     const int lq = lane & 31, lh = lane >> 5;
 
     const int qblocks = (P.c + BQ - 1) / BQ;
-    const int qb = blockIdx.x % qblocks;
-    const int head = (blockIdx.x / qblocks) % P.heads;
-    const int b = blockIdx.x / (qblocks * P.heads);
+    const int KSP = P.ksplit;                                        // workgroups sharing a query block
+    const int split = blockIdx.x % KSP;
+    const int group = blockIdx.x / KSP;                              // (batch element, head, query block)
+    const int qb = group % qblocks;
+    const int head = (group / qblocks) % P.heads;
+    const int b = group / (qblocks * P.heads);
     const int S = P.S;
 
     const size_t mat = (size_t)S * DH;                               // elements of one (b, head) matrix
@@ -127,7 +132,7 @@ __global__ __launch_bounds__(256) void attn_slice_kernel(AttnParams P)
     unsigned k_off[LOADS / 2], v_off[LOADS / 2];
 #pragma unroll
     for (int j = 0; j < LOADS / 2; ++j) {
-        const int row = (j * 4 + wave) * 4 + (lane >> 4);            // key row inside the tile
+        const int row = (j * NW + wave) * 4 + (lane >> 4);           // key row inside the tile
         const int cp = lane & 15;
         k_off[j] = (unsigned)(row * ROWB + ((cp ^ (row & 15)) << 4));
         const int inrow = cp << 4;
@@ -139,10 +144,10 @@ __global__ __launch_bounds__(256) void attn_slice_kernel(AttnParams P)
         const unsigned sa = lds_base + buf * 2 * TILE_BYTES + wave * 1024;
 #pragma unroll
         for (int j = 0; j < LOADS / 2; ++j) {
-            const int row = (j * 4 + wave) * 4 + (lane >> 4);
+            const int row = (j * NW + wave) * 4 + (lane >> 4);
             const bool in = key0 + row < S;                          // rows beyond the sequence read as zero
-            direct_load_16(k_rsrc, in ? k_off[j] : OOB, key0 * ROWB, sa + j * 4096);
-            direct_load_16(v_rsrc, in ? v_off[j] : OOB, key0 * ROWB, sa + TILE_BYTES + j * 4096);
+            direct_load_16(k_rsrc, in ? k_off[j] : OOB, key0 * ROWB, sa + j * NW * 1024);
+            direct_load_16(v_rsrc, in ? v_off[j] : OOB, key0 * ROWB, sa + TILE_BYTES + j * NW * 1024);
         }
     };
 
@@ -172,12 +177,14 @@ __global__ __launch_bounds__(256) void attn_slice_kernel(AttnParams P)
     }
     const float sl2 = P.scale * 1.4426950408889634f;                 // scores are kept in units of log2(e)
 
-    const int nkt = (S + BKV - 1) / BKV;
-    issue_tile(0, 0);
+    const int nkt_all = (S + BKV - 1) / BKV;
+    const int kt0 = (int)(((long long)nkt_all * split) / KSP);       // this workgroup's key tiles: [kt0, nkt)
+    const int nkt = (int)(((long long)nkt_all * (split + 1)) / KSP);
+    issue_tile(kt0, kt0 & 1);
     wait_vmcnt<0>();
     __syncthreads();
 
-    for (int kt = 0; kt < nkt; ++kt) {
+    for (int kt = kt0; kt < nkt; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < nkt)
             issue_tile(kt + 1, buf ^ 1);                             // that buffer was released by the last barrier
@@ -267,6 +274,81 @@ __global__ __launch_bounds__(256) void attn_slice_kernel(AttnParams P)
 
         wait_vmcnt<0>();                                             // the next tile has landed
         __syncthreads();                                             // ... for every wave, and this one is read by all
+    }
+
+    // Key split across workgroups: park (m, l, O) in the workspace, thread-major so that every access is a
+    // coalesced 4 bytes per lane; the workgroup that arrives last merges all splits (its own included) in
+    // split order.  Cross-XCD visibility as in the chunk GEMM's k-split: device-coherent cache policy on
+    // exactly these accesses, relaxed agent-scope atomics on the counter.
+    if (KSP > 1) {
+        constexpr int COHERENT = 1 | 16;
+        constexpr int NV = QT * DT * 16 + 2 * QT;                    // floats per thread
+        const size_t part = (size_t)NV * NT;
+        auto part_rsrc = [&](int sp) {
+            return __builtin_amdgcn_make_buffer_rsrc(P.ws + ((size_t)group * KSP + sp) * part, 0, (int)(part * 4), 0x00020000);
+        };
+        {
+            __amdgpu_buffer_rsrc_t rs = part_rsrc(split);
+#pragma unroll
+            for (int t = 0; t < QT; ++t) {
+#pragma unroll
+                for (int d = 0; d < DT; ++d)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        // (through a plain VGPR: storing the accumulator elements straight from their AGPRs
+                        // came out of this compiler as sixteen stores of element 0)
+                        float v = oacc[t][d][e];
+                        asm volatile("" : "+v"(v));
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), rs,
+                                                              (((t * DT + d) * 16 + e) * NT + tid) * 4, 0, COHERENT);
+                    }
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, m_run[t]), rs,
+                                                      ((QT * DT * 16 + 2 * t) * NT + tid) * 4, 0, COHERENT);
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, l_run[t]), rs,
+                                                      ((QT * DT * 16 + 2 * t + 1) * NT + tid) * 4, 0, COHERENT);
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        unsigned *arrived = reinterpret_cast<unsigned *>(smem);       // the key tiles are no longer read
+        if (tid == 0)
+            *arrived = __hip_atomic_fetch_add(&P.counters[group], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (*arrived != (unsigned)(KSP - 1))
+            return;
+        if (tid == 0)
+            __hip_atomic_store(&P.counters[group], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int t = 0; t < QT; ++t) {
+            float m_all = -INFINITY;
+            for (int sp = 0; sp < KSP; ++sp) {
+                __amdgpu_buffer_rsrc_t rs = part_rsrc(sp);
+                m_all = fmaxf(m_all, __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                         rs, ((QT * DT * 16 + 2 * t) * NT + tid) * 4, 0, COHERENT)));
+            }
+            float l_all = 0.0f;
+#pragma unroll
+            for (int d = 0; d < DT; ++d)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    oacc[t][d][e] = 0.0f;
+            for (int sp = 0; sp < KSP; ++sp) {
+                __amdgpu_buffer_rsrc_t rs = part_rsrc(sp);
+                const float m_s = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                    rs, ((QT * DT * 16 + 2 * t) * NT + tid) * 4, 0, COHERENT));
+                const float l_s = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                    rs, ((QT * DT * 16 + 2 * t + 1) * NT + tid) * 4, 0, COHERENT));
+                const float f = exp2f(m_s - m_all);                  // every split holds at least one key tile
+                l_all += l_s * f;
+#pragma unroll
+                for (int d = 0; d < DT; ++d)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        oacc[t][d][e] += f * __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                                 rs, (((t * DT + d) * 16 + e) * NT + tid) * 4, 0, COHERENT));
+            }
+            l_run[t] = l_all;
+        }
     }
 
     // O = O^T / l, rounded to bf16, written as [token x (head, d)]: the left operand of the output projection.
@@ -507,29 +589,51 @@ bool attn_slice_supported(const AttnParams &p)
            (int64_t)p.S * DH * 2 < ((int64_t)1 << 31);
 }
 
-hipError_t launch_attn_slice(const AttnParams &p, hipStream_t s, int num_cu)
+hipError_t launch_attn_slice(const AttnParams &p_in, hipStream_t s, int num_cu)
 {
-    // 128 queries per workgroup (key tiles shared by four waves) when that fills the chip, else 32 queries
-    // per workgroup with the keys split over its waves
-    int qt = 1;
-    bool ksplit = (int64_t)((p.c + 127) / 128) * p.heads * p.batch * 4 < (int64_t)num_cu * 3;
-    if (const char *e = getenv("COMMFUSE_ATTN_QT")) { // tuning override: 32-query tiles per wave, 0 = key split
-        qt = atoi(e);
-        ksplit = qt == 0;
-        qt = qt == 2 ? 2 : 1;
+    // One workgroup = NW waves of 32 queries sharing the key tiles.  Slices with few queries (the per-step grids
+    // of Alg. 4 are small) leave most of the chip idle that way: then the keys are split as well -- over
+    // several workgroups per query block if a workspace is registered, else over the waves of 32-query
+    // workgroups.
+    AttnParams p = p_in;
+    int qt = 1, nw = 8, ksp = 0;
+    bool wave_split = false;
+    if (const char *e = getenv("COMMFUSE_ATTN_WAVES"))   // tuning override: waves per workgroup, 4 or 8
+        nw = atoi(e) == 8 ? 8 : 4;
+    if (const char *e = getenv("COMMFUSE_ATTN_KSPLIT"))  // tuning override: workgroups per query block
+        ksp = atoi(e);
+    if (const char *e = getenv("COMMFUSE_ATTN_QT")) {    // tuning override: 32-query tiles per wave; 0 = keys over waves
+        const int v = atoi(e);
+        wave_split = v == 0;
+        qt = v == 2 ? 2 : 1;
+        if (qt == 2)
+            nw = 4;
     }
-    if (ksplit) {
+    const int bq = nw * 32 * qt;
+    const int64_t groups = (int64_t)((p.c + bq - 1) / bq) * p.heads * p.batch;
+    const bool small_grid = groups * 4 < (int64_t)num_cu * 3;
+    p.ksplit = 1;
+    if (!wave_split && qt == 1 && (small_grid || ksp > 1) && p.ws != nullptr && p.counters != nullptr) {
+        const int nkt = (p.S + BKV - 1) / BKV;
+        int k = ksp > 0 ? ksp : (int)((num_cu + groups - 1) / groups);   // one workgroup per compute unit
+        k = k > 16 ? 16 : k;
+        k = k > nkt ? nkt : k;
+        const size_t need = (size_t)groups * k * (64 + 2) * (64 * nw) * sizeof(float);
+        if (k > 1 && need <= p.ws_bytes && groups <= p.max_groups)
+            p.ksplit = k;
+    }
+    if (wave_split || (small_grid && p.ksplit == 1 && qt == 1 && getenv("COMMFUSE_ATTN_QT") == nullptr)) {
         const dim3 grid(((p.c + 31) / 32) * p.heads * p.batch), block(256);
         hipLaunchKernelGGL(attn_slice_ksplit_kernel, grid, block, 0, s, p);
         return hipGetLastError();
     }
-    const int bq = 4 * 32 * qt;
-    const int qblocks = (p.c + bq - 1) / bq;
-    const dim3 grid(qblocks * p.heads * p.batch), block(256);
+    const dim3 grid((unsigned)(groups * p.ksplit)), block(64 * nw);
     if (qt == 2)
-        hipLaunchKernelGGL(attn_slice_kernel<2>, grid, block, 0, s, p);
+        hipLaunchKernelGGL((attn_slice_kernel<2, 4>), grid, block, 0, s, p);
+    else if (nw == 8)
+        hipLaunchKernelGGL((attn_slice_kernel<1, 8>), grid, block, 0, s, p);
     else
-        hipLaunchKernelGGL(attn_slice_kernel<1>, grid, block, 0, s, p);
+        hipLaunchKernelGGL((attn_slice_kernel<1, 4>), grid, block, 0, s, p);
     return hipGetLastError();
 }
 

@@ -55,6 +55,13 @@ struct AttnParams {
     int l;               // slice index: queries [l*c, (l+1)*c)
     int64_t ldo;
     float scale;
+    // key split across workgroups (the 128-query kernel): the key tiles are divided over `ksplit` workgroups per
+    // query block, which park (m, l, unnormalised O) in the workspace; the last one to finish merges them
+    int ksplit = 1;
+    float *ws = nullptr;
+    unsigned *counters = nullptr;
+    size_t ws_bytes = 0;
+    int max_groups = 0;
 };
 
 struct TileChoice {

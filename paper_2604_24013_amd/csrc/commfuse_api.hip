@@ -559,6 +559,15 @@ cf_status launch_attention(const AttnCtx &ctx, int l, hipStream_t s)
 {
     cf::AttnParams ap = ctx.ap;
     ap.l = l;
+    {
+        std::lock_guard<std::mutex> lk(g_ws_mu);
+        if (g_ws.ptr != nullptr && g_ws.bytes > WS_COUNTER_BYTES) {
+            ap.counters = static_cast<unsigned *>(g_ws.ptr);
+            ap.ws = reinterpret_cast<float *>(static_cast<char *>(g_ws.ptr) + WS_COUNTER_BYTES);
+            ap.ws_bytes = g_ws.bytes - WS_COUNTER_BYTES;
+            ap.max_groups = (int)(WS_TILE_COUNTER_BYTES / sizeof(unsigned));
+        }
+    }
     hipError_t e = cf::launch_attn_slice(ap, s, num_cu_of_current_device());
     if (e != hipSuccess)
         return fail_hip(e, "attention launch");

@@ -83,6 +83,40 @@ def test_attention_slice(shape, qt):
         os.environ.pop("COMMFUSE_ATTN_QT", None)
 
 
+@pytest.mark.parametrize("waves", ["4", "8"])
+@pytest.mark.parametrize("ksplit", ["2", "3", "16"])
+@pytest.mark.parametrize("shape", ATTN_SHAPES)
+def test_attention_slice_keys_split_over_workgroups(shape, ksplit, waves):
+    """With a workspace registered the key tiles of a query block are divided over several workgroups whose
+    partial (m, l, O) are merged by the one that finishes last."""
+    p, B, h, S = shape
+    dev, host, _ = _problem(330 + S, p, B, h, S, 64)
+    scale = 1.0 / np.sqrt(128.0)
+    Qd, Kd, Vd = (H.to_dev(x, "bf16") for x in dev[:3])
+    desc = cf.attn_desc(p, 0, B, h, S, 128, 64, scale)
+    c = S // p
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device=H.DEV)
+    cf.set_workspace(ws)
+    torch.cuda.synchronize()
+    os.environ["COMMFUSE_ATTN_KSPLIT"] = ksplit
+    os.environ["COMMFUSE_ATTN_WAVES"] = waves
+    try:
+        for l in sorted({0, p - 1}):
+            out = torch.full((B * c, h * 128), float("nan"), dtype=torch.bfloat16, device=H.DEV)
+            for _ in range(2):                                    # twice: the arrival counters are left at zero
+                cf.attn_slice(desc, l, Qd, Kd, Vd, out, None)
+            torch.cuda.synchronize()
+            got = H.to_host_f64(out)
+            ref = oracle.attention_slice(host[0], host[1], host[2], l, p, scale)
+            assert not np.isnan(got).any()
+            assert H.rel_err(got, ref) <= TOL_ATTN, f"slice {l}"
+    finally:
+        os.environ.pop("COMMFUSE_ATTN_KSPLIT", None)
+        os.environ.pop("COMMFUSE_ATTN_WAVES", None)
+        torch.cuda.synchronize()
+        cf.set_workspace(None)
+
+
 def test_attention_peaked_and_flat_softmax():
     """Large logits (one key dominates: the output is that key's value row, exactly representable) and zero
     queries (uniform weights: the output is the mean of V)."""
