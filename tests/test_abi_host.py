@@ -41,6 +41,42 @@ def test_struct_layout_matches_header():
     assert ctypes.sizeof(cf.Buffers) == 10 * ctypes.sizeof(ctypes.c_void_p)
 
 
+def test_attention_struct_layout_matches_header():
+    # cf_attn_desc: 6 x int32, 3 x int64, int32 + float = 56 bytes; cf_attn_buffers: 13 pointers
+    assert ctypes.sizeof(cf.AttnDesc) == 56
+    assert cf.AttnDesc.n.offset == 24 and cf.AttnDesc.w_layout.offset == 48 and cf.AttnDesc.scale.offset == 52
+    assert ctypes.sizeof(cf.AttnBuffers) == 13 * ctypes.sizeof(ctypes.c_void_p)
+
+
+def test_backward_granularity_and_attention_bad_arguments(lib):
+    A, B, C, D = 0x1000, 0x2000, 0x3000, 0x4000            # fake, aligned, never dereferenced
+    # weight gradient
+    assert _status(cf.wgrad_step, cf.layer_desc(2, 0, 64, 64, 64, "f32", "f32"), 0, A, B, C)[0] == cf.CF_ERR_UNSUPPORTED
+    assert _status(cf.wgrad_step, cf.layer_desc(2, 0, 64, 64, 64), 2, A, B, C)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.wgrad_step, cf.layer_desc(2, 0, 64, 64, 64), 0, None, B, C)[0] == cf.CF_ERR_NULL_PTR
+    assert _status(cf.wgrad_step, cf.layer_desc(2, 0, 64, 64, 64), 0, A + 8, B, C)[0] == cf.CF_ERR_MISALIGNED
+    # slicing granularity
+    assert _status(cf.rs_step, cf.layer_desc(2, 0, 30, 64, 64, m=4), 0, A, B, None, D)[0] == cf.CF_ERR_INVALID_ARG
+    d = cf.layer_desc(2, 0, 32, 64, 64, m=2)
+    assert _status(cf.rs_step, d, 4, A, B, C, D)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.rs_step, d, 1, A, B, C, D)[0] == cf.CF_ERR_NULL_PTR          # the first hop receives nothing
+    assert _status(cf.rs_step, d, 2, A, B, None, D)[0] == cf.CF_ERR_NULL_PTR
+    assert _status(cf.rs_pair_step, d, 0, A, B, None, None, D)[0] == cf.CF_ERR_UNSUPPORTED
+    assert [cf.subslice_index(cf.CF_KIND_RS, 4, 2, 1, j) for j in range(8)] == [0, 1, 6, 7, 4, 5, 2, 3]
+    assert _status(cf.subslice_index, cf.CF_KIND_RS_PAIR, 4, 2, 1, 0)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.subslice_index, cf.CF_KIND_RS, 4, 0, 1, 0)[0] == cf.CF_ERR_INVALID_ARG
+    # attention
+    ok = cf.attn_desc(2, 0, 1, 1, 128, 128, 64, 0.1)
+    assert _status(cf.attn_slice, cf.attn_desc(2, 0, 1, 1, 128, 64, 64, 0.1), 0, A, B, C, D)[0] == cf.CF_ERR_UNSUPPORTED
+    assert _status(cf.attn_slice, cf.attn_desc(3, 0, 1, 1, 128, 128, 64, 0.1), 0, A, B, C, D)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.attn_slice, ok, 2, A, B, C, D)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.attn_slice, ok, 0, A, None, C, D)[0] == cf.CF_ERR_NULL_PTR
+    assert _status(cf.attn_slice, cf.attn_desc(2, 0, 1, 1, 128, 128, 64, 0.0), 0, A, B, C, D)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.attn_rs_step, ok, 0, A, B, C, D, 0x5000, 0x6000, 0x7000)[0] == cf.CF_ERR_NULL_PTR   # recv at step 0
+    assert _status(cf.attn_rs_step, ok, 1, A, B, C, D, None, 0x6000, 0x7000)[0] == cf.CF_ERR_NULL_PTR
+    assert _status(cf.attn_rs_step, ok, 1, A, B, C, D, 0x6000, 0x6000, 0x7000)[0] == cf.CF_ERR_INVALID_ARG
+
+
 def test_version(lib):
     assert cf.version() >= 100
 
