@@ -259,6 +259,18 @@ enum {
                             extra workgroups of step i's kernel launch instead of a
                             hipMemcpyAsync on copy_stream: one stream, no events
                             (copy_stream is unused; not with CF_POISON)               */
+    CF_PERSISTENT = 128u,/* bf16 CF_KIND_RS / CF_KIND_AG only, at most 16 (sub-)steps: ONE kernel launch
+                            runs all steps of the rank step.  Its work items (step, output tile) are
+                            dealt out step-major to a grid that fills the chip once; tiles of different
+                            steps run side by side (the chunk GEMMs do not depend on each other -- only
+                            the add of B_in / the arrival of the slice does), nothing is launched or
+                            drained between steps, and because a step no longer has to fill the chip
+                            alone the tiles can be larger.  Needs cf_buffers.recv_each (every hop's
+                            delivery stays where it landed) and no peer_sink.  With copies overlapped
+                            the kernel waits for each delivery's flag on the device as under
+                            CF_DEVICE_WAIT (workspace needed; not with CF_GRAPH); with CF_SERIAL all
+                            deliveries are enqueued before the kernel and no flags are involved.
+                            Not with CF_FUSED_COPY / CF_DEVICE_WAIT.                                   */
     CF_DEVICE_WAIT = 64u /* bf16 RS / AG only, needs a registered workspace: the compute
                             stream does not wait for the copy stream between steps;
                             each delivery is followed by a flag write and the step

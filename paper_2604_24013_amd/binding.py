@@ -20,6 +20,7 @@ CF_BF16, CF_F32 = 0, 1
 CF_KIND_RS, CF_KIND_AG, CF_KIND_DP, CF_KIND_RS_PAIR, CF_KIND_DP_PAIR, CF_KIND_WGRAD_X, CF_KIND_WGRAD_G = 0, 1, 2, 3, 4, 5, 6
 CF_W_KN, CF_W_NK = 0, 1
 CF_NO_COPY, CF_NO_COMPUTE, CF_SERIAL, CF_POISON, CF_GRAPH, CF_FUSED_COPY, CF_DEVICE_WAIT = 1, 2, 4, 8, 16, 32, 64
+CF_PERSISTENT = 128
 
 KINDS = {"rs": CF_KIND_RS, "ag": CF_KIND_AG, "dp": CF_KIND_DP, "rs_pair": CF_KIND_RS_PAIR, "dp_pair": CF_KIND_DP_PAIR,
          "wgrad_x": CF_KIND_WGRAD_X, "wgrad_g": CF_KIND_WGRAD_G}

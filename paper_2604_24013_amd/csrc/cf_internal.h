@@ -39,6 +39,16 @@ struct GemmParams {
     unsigned *status = nullptr;
     unsigned spin_limit = 0;
     bool wait_at_start = false;   // true: before the first operand load; false: before the B_in loads
+    // persistent mode (direct-to-LDS bf16 kernel only): n_steps > 0 makes one launch run that many chunk GEMMs
+    // of the same shape, step s with its own left operand, B_in, output and delivery flag (each nullable as
+    // above); A, recv, out and wait_flag are then ignored
+    static constexpr int MAX_STEPS = 16;
+    int n_steps = 0;
+    int num_cu = 256;
+    const void *A_step[MAX_STEPS] = {};
+    const float *recv_step[MAX_STEPS] = {};
+    void *out_step[MAX_STEPS] = {};
+    const unsigned *flag_step[MAX_STEPS] = {};
     const void *cp_src = nullptr;
     void *cp_dst = nullptr;
     size_t cp_bytes = 0;

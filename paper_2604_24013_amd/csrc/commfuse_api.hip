@@ -785,6 +785,99 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
     return CF_OK;
 }
 
+// CF_PERSISTENT: all (sub-)steps of a reduce-scatter or all-gather rank step in ONE launch of the chunk-GEMM
+// kernel (its work-item loop), the deliveries either all before it (serial) or beside it on the copy stream,
+// each followed by a flag write that the kernel polls.
+cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, hipStream_t cs, hipStream_t xs_in,
+                             uint32_t flags)
+{
+    const int p = r.p, m = r.m, S = r.p * r.m;
+    const bool do_copy = !(flags & CF_NO_COPY) && p > 1;
+    const bool do_compute = !(flags & CF_NO_COMPUTE);
+    const bool serial = (flags & CF_SERIAL) != 0 || xs_in == cs || !do_copy || !do_compute;
+    hipStream_t xs = serial ? cs : xs_in;
+    const bool poison = (flags & CF_POISON) != 0;
+    const size_t slot_bytes = kind == CF_KIND_RS ? (size_t)r.mc * r.n * sizeof(float) : (size_t)r.mc * r.k * in_elem(r);
+    auto receives = [&](int j) { return j >= m && j < S; };
+    auto sends = [&](int j) { return j >= 0 && j < S - m; };
+    auto landing = [&](int j) -> void * {
+        return static_cast<char *>(b->recv_each[j / m - 1]) + (size_t)(j % m) * slot_bytes;
+    };
+    unsigned *dw_flags = nullptr, *dw_status = nullptr;
+    if (!serial) {
+        std::lock_guard<std::mutex> lk(g_ws_mu);
+        if (g_ws.ptr == nullptr || g_ws.bytes < WS_COUNTER_BYTES)
+            return fail(CF_ERR_INVALID_ARG, "CF_PERSISTENT with overlapped copies needs a registered workspace");
+        dw_flags = reinterpret_cast<unsigned *>(static_cast<char *>(g_ws.ptr) + WS_FLAG_OFFSET);
+        dw_status = reinterpret_cast<unsigned *>(static_cast<char *>(g_ws.ptr) + WS_STATUS_OFFSET);
+    }
+    std::vector<hipEvent_t> ev;
+    if (cf_status st = get_events(2, &ev))
+        return st;
+    if (!serial) {
+        hipError_t e = cf::launch_set_words(dw_flags, S, 0u, cs);
+        if (e != hipSuccess)
+            return fail_hip(e, "flag reset");
+        CF_HIP(hipEventRecord(ev[0], cs));
+        CF_HIP(hipStreamWaitEvent(xs, ev[0], 0));
+    }
+    if (do_copy) {
+        for (int j = m; j < S; ++j) {
+            if (slot_bytes == 0)
+                break;
+            void *dst = landing(j);
+            if (poison) {
+                hipError_t e = cf::launch_fill_ff(dst, slot_bytes, xs);
+                if (e != hipSuccess)
+                    return fail_hip(e, "poison fill");
+            }
+            const char *src = static_cast<const char *>(b->peer_stage[j / m - 1]) + (size_t)(j % m) * slot_bytes;
+            CF_HIP(hipMemcpyAsync(dst, src, slot_bytes, hipMemcpyDeviceToDevice, xs));
+            if (!serial) {
+                hipError_t e = cf::launch_set_words(dw_flags + j, 1, 1u, xs);
+                if (e != hipSuccess)
+                    return fail_hip(e, "flag write");
+            }
+        }
+    }
+    if (do_compute && r.mc > 0 && r.n > 0) {
+        cf::GemmParams gp;
+        gp.W = b->W;
+        fill_shape(gp, r);
+        gp.n_steps = S;
+        gp.num_cu = num_cu_of_current_device();
+        gp.wait_at_start = kind == CF_KIND_AG;
+        gp.status = dw_status;
+        gp.spin_limit = spin_limit();
+        for (int j = 0; j < S; ++j) {
+            const int c = subslice_index(kind, p, m, r.rank, j);
+            if (kind == CF_KIND_RS) {
+                gp.A_step[j] = static_cast<const char *>(b->A_or_own_shard) + (size_t)c * r.mc * r.lda * in_elem(r);
+                gp.recv_step[j] = receives(j) ? static_cast<const float *>(landing(j)) : nullptr;
+                gp.out_step[j] = sends(j) ? static_cast<void *>(b->send_slot[j & 1])
+                                          : static_cast<void *>(static_cast<float *>(b->O) + (size_t)(j % m) * r.mc * r.ldo);
+            } else {
+                gp.A_step[j] = receives(j) ? landing(j)
+                                           : static_cast<const char *>(b->A_or_own_shard) + (size_t)(j % m) * slot_bytes;
+                gp.recv_step[j] = nullptr;
+                gp.out_step[j] = static_cast<char *>(b->O) + (size_t)c * r.mc * r.ldo * (r.bf16_out ? 2 : 4);
+            }
+            gp.flag_step[j] = (!serial && receives(j)) ? dw_flags + j : nullptr;
+        }
+        if (r.k == 0) {
+            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT needs k > 0");
+        }
+        hipError_t e = cf::launch_gemm_bf16(gp, r.w_kn, r.bf16_out, cs, gp.num_cu);
+        if (e != hipSuccess)
+            return fail_hip(e, "persistent rank-step launch");
+    }
+    if (!serial) {
+        CF_HIP(hipEventRecord(ev[1], xs));
+        CF_HIP(hipStreamWaitEvent(cs, ev[1], 0));
+    }
+    return CF_OK;
+}
+
 cf_status check_buffers(const Resolved &r, int kind, const cf_buffers *b, uint32_t flags)
 {
     if (b == nullptr)
@@ -846,7 +939,8 @@ void append_bytes(std::vector<unsigned char> &v, const void *p, size_t n)
 cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *bufs, hipStream_t cs, hipStream_t xs,
                               uint32_t flags, const AttnCtx *attn, std::vector<unsigned char> &key)
 {
-    if (flags & ~(uint32_t)(CF_NO_COPY | CF_NO_COMPUTE | CF_SERIAL | CF_POISON | CF_GRAPH | CF_FUSED_COPY | CF_DEVICE_WAIT))
+    if (flags & ~(uint32_t)(CF_NO_COPY | CF_NO_COMPUTE | CF_SERIAL | CF_POISON | CF_GRAPH | CF_FUSED_COPY | CF_DEVICE_WAIT |
+                            CF_PERSISTENT))
         return fail(CF_ERR_INVALID_ARG, "unknown flag bits 0x%x", flags);
     if (is_pair_kind(kind)) {
         if (cf_status st = check_pair_p(r.p))
@@ -871,10 +965,26 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
         if (is_dp_kind(kind) || !(is_wgrad_kind(kind) ? wgrad_can_carry_copy(r) : step_can_carry_copy(r)))
             return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY needs the bf16 chunk-GEMM kernels (kind RS or AG, bf16 operands)");
     }
+    if (flags & CF_PERSISTENT) {
+        if (flags & (CF_FUSED_COPY | CF_DEVICE_WAIT))
+            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT excludes CF_FUSED_COPY and CF_DEVICE_WAIT");
+        if ((kind != CF_KIND_RS && kind != CF_KIND_AG) || attn != nullptr || !step_can_carry_copy(r) ||
+            r.p * r.m > cf::GemmParams::MAX_STEPS)
+            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT needs kind RS or AG, bf16 operands and at most %d (sub-)steps",
+                        cf::GemmParams::MAX_STEPS);
+        if (bufs != nullptr && bufs->peer_sink != nullptr)
+            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT cannot feed peer_sink (nothing signals a finished step)");
+        if (bufs != nullptr && r.p > 1 && bufs->recv_each == nullptr)
+            return fail(CF_ERR_INVALID_ARG, "CF_PERSISTENT needs buffers->recv_each (a landing buffer per hop)");
+        const bool flags_needed = !(flags & (CF_SERIAL | CF_NO_COPY | CF_NO_COMPUTE)) && xs != cs && r.p > 1;
+        if (flags_needed && (flags & CF_GRAPH))
+            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT with overlapped copies polls delivery flags: not with CF_GRAPH");
+    }
     if (cf_status st = check_buffers(r, kind, bufs, flags))
         return st;
     if (!(flags & CF_GRAPH))
-        return enqueue_schedule(r, kind, bufs, cs, xs, flags, attn);
+        return (flags & CF_PERSISTENT) ? enqueue_persistent(r, kind, bufs, cs, xs, flags)
+                                       : enqueue_schedule(r, kind, bufs, cs, xs, flags, attn);
 
     // CF_GRAPH: the same enqueue sequence, captured once per distinct argument set.
     if (cs == nullptr || (xs == nullptr && !(flags & CF_SERIAL)))
@@ -920,7 +1030,9 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
         if (cf_status st = get_events(2 + 3 * (size_t)r.p * r.m, &tmp))
             return st;
         CF_HIP(hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal));
-        cf_status st = enqueue_schedule(r, kind, bufs, cs, xs, flags & ~(uint32_t)CF_GRAPH, attn);
+        const uint32_t fl = flags & ~(uint32_t)CF_GRAPH;
+        cf_status st = (fl & CF_PERSISTENT) ? enqueue_persistent(r, kind, bufs, cs, xs, fl)
+                                            : enqueue_schedule(r, kind, bufs, cs, xs, fl, attn);
         hipGraph_t graph = nullptr;
         hipError_t e = hipStreamEndCapture(cs, &graph);
         if (st != CF_OK) {

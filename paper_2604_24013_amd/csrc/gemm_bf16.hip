@@ -321,6 +321,25 @@ hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipSt
     if (p.M <= 0 || p.N <= 0)
         return hipSuccess;
     TileChoice t = choose_tile_bf16(p.M, p.N, p.K, num_cu);
+    if (p.n_steps > 0) {
+        // Persistent rank step: n_steps * tiles work items share one grid, so a step need not fill the chip
+        // alone.  Cost of a tile shape = rounds over the chip x tile area x its measured cost per flop
+        // (per-k-tile time of a full grid: 256x256 1.00, 256x128 1.15, 128x128 1.30, relative).
+        const struct { int bm, bn; double cost; } cand[3] = {{256, 256, 1.00}, {256, 128, 1.15}, {128, 128, 1.30}};
+        double best = 0.0;
+        for (int c = 0; c < 3; ++c) {
+            const int64_t items = (int64_t)((p.M + cand[c].bm - 1) / cand[c].bm) * ((p.N + cand[c].bn - 1) / cand[c].bn) * p.n_steps;
+            const int64_t rounds = (items + num_cu - 1) / num_cu;
+            const double cost = (double)rounds * cand[c].bm * cand[c].bn * cand[c].cost;
+            if (c == 0 || cost < best) {
+                best = cost;
+                t.bm = cand[c].bm;
+                t.bn = cand[c].bn;
+            }
+        }
+        t.splitk = 1;
+        t.deep = true;                               // 128x128: one workgroup per CU, four stages
+    }
     if (const char *e = getenv("COMMFUSE_TILE")) {   // tuning override: "256x256", "256x128", "128x128"
         int bm = 0, bn = 0;
         if (sscanf(e, "%dx%d", &bm, &bn) == 2) {
@@ -338,7 +357,7 @@ hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipSt
     const bool staged = staged_kernel_forced();
     if (!staged && gemm_bf16_dl_supported(p, w_kn))
         return launch_gemm_bf16_dl(p, w_kn, out_bf16, s, t);
-    if (p.n_recv_more != 0 || p.a_t)
+    if (p.n_recv_more != 0 || p.a_t || p.n_steps > 0)
         return hipErrorInvalidValue;                 // callers ask gemm_bf16_takes_recv_list first
     if (t.bm == 256 && t.bn == 256) return launch_cfg<256, 256, 2, 4>(p, w_kn, out_bf16, s);
     if (t.bm == 256 && t.bn == 128) return launch_cfg<256, 128, 4, 2>(p, w_kn, out_bf16, s);

@@ -132,7 +132,9 @@ __device__ __forceinline__ int xcd_remap(int pid, int total)
 
 // A_T: the left operand is stored [K x M] (see GemmParams::a_t); its tile then lives in LDS like a
 // [k x n] weight tile and is read with the transposing LDS read as well.
-template <int BM, int BN, int WGM, int WGN, int NS, bool SPREAD, bool W_KN, bool OUT_BF16, bool A_T = false>
+// PERSIST: one launch runs all steps of a rank step (GemmParams::n_steps, see the work-item loop below).
+template <int BM, int BN, int WGM, int WGN, int NS, bool SPREAD, bool W_KN, bool OUT_BF16, bool A_T = false,
+          bool PERSIST = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams P, int tiles_m, int tiles_n)
 {
     static_assert(!A_T || (W_KN && !OUT_BF16), "the transposed left operand comes with [k x n] weights and fp32 output");
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // neighbour sends while this step computes): a streaming copy that shares the launch with the GEMM,
     // so that no second stream, event or inter-queue wait sits between two step kernels.
     const int gemm_wgs = tiles_m * tiles_n * P.splits;
-    if ((int)blockIdx.x >= gemm_wgs) {
+    if (!PERSIST && (int)blockIdx.x >= gemm_wgs) {
         const u32x4_t *src = static_cast<const u32x4_t *>(P.cp_src);
         u32x4_t *dst = static_cast<u32x4_t *>(P.cp_dst);
         const size_t n16 = P.cp_bytes / 16;
@@ -181,9 +183,25 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         return;
     }
 
+    // Persistent mode (GemmParams::n_steps > 0): one launch runs ALL steps of a rank step.  The work items
+    // (step, output tile) are dealt out round robin, step-major, to the workgroups of a grid that fills the
+    // chip once; a workgroup goes on to its next item as soon as it is done with the last one, so tiles of
+    // different steps run side by side (the chunk GEMMs of Alg. 1 / Alg. 2 do not depend on each other; only
+    // the add of B_in / the arrival of the slice does, which the per-step delivery flag guards) and nothing
+    // is launched, drained or refilled between steps.  Every workgroup's loop is finite: the kernel exits.
+    const int tiles_per_step = tiles_m * tiles_n * P.splits;
+    const int n_items = PERSIST ? tiles_per_step * P.n_steps : 0;
+    int item = blockIdx.x;
+    do {
+    const int step_i = PERSIST ? item / tiles_per_step : 0;
+    const void *const cA = PERSIST ? P.A_step[step_i] : P.A;
+    const float *const cRecv = PERSIST ? P.recv_step[step_i] : P.recv;
+    void *const cOut = PERSIST ? P.out_step[step_i] : P.out;
+    const unsigned *const cFlag = PERSIST ? P.flag_step[step_i] : P.wait_flag;
+
     // Work item = (output tile, k-split); the splits of a tile are neighbours in the remapped order.
     const int splits = P.splits;
-    const int work = xcd_remap(blockIdx.x, tiles_m * tiles_n * splits);
+    const int work = xcd_remap(PERSIST ? item % tiles_per_step : (int)blockIdx.x, tiles_per_step);
     const int tile = work / splits, split = work % splits;
     const int m0 = (tile % tiles_m) * BM;
     const int n0 = (tile / tiles_m) * BN;
@@ -200,10 +218,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // non-local L2 lines are invalidated once per workgroup) or loads with the device-coherent cache
     // policy (the B_in loads of the epilogue, which are read once anyway).
     auto wait_delivery = [&](bool acquire) {
-        if (P.wait_flag != nullptr) {
+        if (cFlag != nullptr) {
             if (tid == 0) {
                 unsigned n = 0;
-                while (__hip_atomic_load(P.wait_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == 0u) {
+                while (__hip_atomic_load(cFlag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) == 0u) {
                     if (++n >= P.spin_limit) {
                         __hip_atomic_fetch_or(P.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
                         break;
@@ -222,7 +240,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // Buffer resources; all byte extents are below 2^31 (host-checked).
     const unsigned a_bytes = (unsigned)((A_T ? ((int64_t)(K - 1) * P.lda + M) : ((int64_t)(M - 1) * P.lda + K)) * 2);
     const unsigned w_bytes = (unsigned)((W_KN ? ((int64_t)(K - 1) * P.ldw + N) : ((int64_t)(N - 1) * P.ldw + K)) * 2);
-    const i32x4_t a_rsrc = make_rsrc(P.A, a_bytes);
+    const i32x4_t a_rsrc = make_rsrc(cA, a_bytes);
     const i32x4_t w_rsrc = make_rsrc(P.W, w_bytes);
     const unsigned lds_base = __builtin_amdgcn_readfirstlane(
         (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)smem);
@@ -458,9 +476,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     static_assert(!PF || (NS - 2) * LPT + PFR < 64, "vmcnt range");
     const unsigned r_bytes = (unsigned)(((int64_t)(M - 1) * P.ldo + N) * 4);
     __amdgpu_buffer_rsrc_t r_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<float *>(P.recv), 0, P.recv != nullptr ? (int)r_bytes : 0, 0x00020000);
+        const_cast<float *>(cRecv), 0, cRecv != nullptr ? (int)r_bytes : 0, 0x00020000);
     const int pf_at = nk - 1 - P.pf_lead;             // iteration after whose tile loads the prefetch is issued
-    const bool pf_on = PF && P.recv != nullptr && splits == 1 && P.n_recv_more == 0 && P.pf_lead > 0 && pf_at >= 0;
+    const bool pf_on = PF && cRecv != nullptr && splits == 1 && P.n_recv_more == 0 && P.pf_lead > 0 && pf_at >= 0;
     f32x4_t pre[PF ? TM : 1][PF ? TN : 1][4];
     constexpr int COHERENT_LD = 1 | 16;               // buffer cache-policy bits sc0 | sc1
     auto prefetch_recv = [&](auto aux_tag) {
@@ -560,7 +578,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             if constexpr (PF) {
                 if (pf_on && kt == pf_at) {
                     wait_delivery(false);
-                    if (P.wait_flag != nullptr)
+                    if (cFlag != nullptr)
                         prefetch_recv(std::integral_constant<int, COHERENT_LD>{});
                     else
                         prefetch_recv(std::integral_constant<int, 0>{});
@@ -610,11 +628,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         }
         __builtin_amdgcn_s_waitcnt(0);           // this wave's partial stores are acknowledged
         __syncthreads();                         // ... and every wave's
-        __shared__ unsigned arrived;
+        unsigned *arrived = reinterpret_cast<unsigned *>(smem);   // the stages are no longer read by anyone
         if (tid == 0)
-            arrived = __hip_atomic_fetch_add(&P.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *arrived = __hip_atomic_fetch_add(&P.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
-        if (arrived != (unsigned)(splits - 1))
+        if (*arrived != (unsigned)(splits - 1))
             return;                              // not the last to finish: done
         if (tid == 0)                            // leave the counter ready for the next launch
             __hip_atomic_store(&P.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -648,11 +666,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // and its store is dropped.
     constexpr unsigned o_elem = OUT_BF16 ? 2 : 4;
     const unsigned o_bytes = (unsigned)(((int64_t)(M - 1) * P.ldo + N) * o_elem);
-    __amdgpu_buffer_rsrc_t o_rsrc = __builtin_amdgcn_make_buffer_rsrc(P.out, 0, (int)o_bytes, 0x00020000);
-    const bool has_recv = P.recv != nullptr;
+    __amdgpu_buffer_rsrc_t o_rsrc = __builtin_amdgcn_make_buffer_rsrc(cOut, 0, (int)o_bytes, 0x00020000);
+    const bool has_recv = cRecv != nullptr;
     if (!P.wait_at_start && !pf_on)
         wait_delivery(false);                        // B_in has travelled under the main loop
-    const bool recv_coherent = P.wait_flag != nullptr && !P.wait_at_start;
+    const bool recv_coherent = cFlag != nullptr && !P.wait_at_start;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int m = m0 + wm * WTM + i * 32 + (lane & 31);
@@ -723,13 +741,39 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 }
             }
     }
+    if constexpr (PERSIST)
+        __syncthreads();                             // every wave is done with the LDS stages
+    item += gridDim.x;
+    } while (PERSIST && item < n_items);             // next work item
 }
 
 template <int BM, int BN, int WGM, int WGN, int NS, bool SPREAD>
 hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s)
 {
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    const dim3 grid(tiles_m * tiles_n * p.splits + p.cp_wgs), block(64 * WGM * WGN);
+    int wgs = tiles_m * tiles_n * p.splits + p.cp_wgs;
+    if (p.n_steps > 0) {                             // persistent: a grid that fills the chip once
+        constexpr int per_cu = (NS * (BM + BN) * 64 * 2 <= 80 * 1024) ? 2 : 1;
+        const int items = tiles_m * tiles_n * p.n_steps;
+        wgs = items < p.num_cu * per_cu ? items : p.num_cu * per_cu;
+    }
+    const dim3 grid(wgs), block(64 * WGM * WGN);
+    if (p.n_steps > 0) {                             // persistent rank step: fp32 or bf16 output, either weight order
+        if (p.a_t)
+            return hipErrorInvalidValue;
+        if (w_kn) {
+            if (out_bf16)
+                hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, true, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
+            else
+                hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, false, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
+        } else {
+            if (out_bf16)
+                hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, false, true, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
+            else
+                hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, false, false, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
+        }
+        return hipGetLastError();
+    }
     if (p.a_t) {
         if (!w_kn || out_bf16)
             return hipErrorInvalidValue;
@@ -770,6 +814,11 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
     if (p.splits > nk_all)
         p.splits = nk_all;
     const int64_t tiles = (int64_t)((p.M + t.bm - 1) / t.bm) * ((p.N + t.bn - 1) / t.bn);
+    if (p.n_steps > 0) {
+        p.splits = 1;
+        p.cp_wgs = 0;
+        p.cp_bytes = 0;
+    }
     if (p.splits > 1 && (p.ws == nullptr || p.counters == nullptr ||
                          (size_t)p.splits * p.M * p.N * sizeof(float) > p.ws_bytes || tiles > p.max_tiles ||
                          (int64_t)p.M * p.N * 4 >= ((int64_t)1 << 31)))

@@ -416,6 +416,67 @@ def test_device_wait_sees_fresh_data_every_time():
             assert H.rel_err(H.to_host_f64(rs.O), refr[-1]) <= TIGHT_BF16, f"round {rnd}"
 
 
+@pytest.mark.parametrize("tile", [None, "256x256", "256x128", "128x128"])
+@pytest.mark.parametrize("m", [1, 2])
+def test_persistent_rank_step(m, tile):
+    """CF_PERSISTENT: all steps in one launch; work items (step, tile) round robin over one chip-filling grid."""
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=8, m_chunk=264, n=520, k=328)
+    data = inputs.make_rs(w, salt=19)
+    rank = 5
+    ref = _oracle_rs(w, data, rank)
+    wa = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=8, m_chunk=136, n=264, k=520, out_dtype="bf16")
+    da = inputs.make_ag(wa, salt=20)
+    refa = _oracle_ag(wa, da, rank)
+    _tile_env(tile)
+    try:
+        for flags in (cf.CF_PERSISTENT, cf.CF_PERSISTENT | cf.CF_SERIAL, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_GRAPH,
+                      cf.CF_PERSISTENT | cf.CF_POISON, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_POISON):
+            for layout in (cf.CF_W_KN, cf.CF_W_NK):
+                run = H.RsRun(w, data, rank, layout, m=m, each=True)
+                run.O.fill_(float("nan"))
+                with H.Workspace(run.desc, cf.CF_KIND_RS):
+                    run.run_schedule(flags)
+                    run.run_schedule(flags)
+                    cf.device_status(run.cs)
+                e = H.rel_err(H.to_host_f64(run.O), ref[-1])
+                assert e <= TIGHT_BF16, f"flags {flags} layout {layout}: {e:.3e}"
+                ag = H.AgRun(wa, da, rank, layout, m=m, each=True)
+                with H.Workspace(ag.desc, cf.CF_KIND_AG):
+                    ag.run_schedule(flags)
+                    cf.device_status(ag.cs)
+                o = H.to_host_f64(ag.O)
+                assert not np.isnan(o).any(), f"flags {flags}"
+                assert H.rel_err(o, refa) <= TIGHT_BF16_OUT, f"flags {flags} layout {layout}"
+    finally:
+        _tile_env(None)
+    # compute-only on whatever the landing buffers hold after a full run; copy-only delivers everything
+    run = H.RsRun(w, data, rank, each=True)
+    run.run_schedule(cf.CF_PERSISTENT | cf.CF_NO_COMPUTE)
+    for i in range(w.p - 1):
+        assert np.array_equal(H.to_host_f64(run.each[i]), data["R"][i + 1].astype(np.float64))
+    run.run_schedule(cf.CF_PERSISTENT | cf.CF_NO_COPY)
+    assert H.rel_err(H.to_host_f64(run.O), ref[-1]) <= TIGHT_BF16
+
+
+def test_persistent_needs_what_it_needs():
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=4, m_chunk=64, n=64, k=64)
+    data = inputs.make_rs(w)
+    for kw, flags, status in (({}, cf.CF_PERSISTENT, cf.CF_ERR_INVALID_ARG),                       # no recv_each
+                              ({"each": True, "with_sink": True}, cf.CF_PERSISTENT, cf.CF_ERR_UNSUPPORTED),
+                              ({"each": True}, cf.CF_PERSISTENT | cf.CF_GRAPH, cf.CF_ERR_UNSUPPORTED),   # flags + graph
+                              ({"each": True}, cf.CF_PERSISTENT | cf.CF_FUSED_COPY, cf.CF_ERR_UNSUPPORTED),
+                              ({"each": True}, cf.CF_PERSISTENT, cf.CF_ERR_INVALID_ARG)):                # no workspace
+        run = H.RsRun(w, data, 0, **kw)
+        with pytest.raises(cf.CommFuseError) as ei:
+            run.run_schedule(flags)
+        assert ei.value.status == status, (kw, flags)
+    wf = inputs.scaled(inputs.CONFIGS["c1_rs_f32"], p=2)
+    run = H.RsRun(wf, inputs.make_rs(wf), 0, each=True)
+    with pytest.raises(cf.CommFuseError) as ei:
+        run.run_schedule(cf.CF_PERSISTENT | cf.CF_SERIAL)                                          # fp32 operands
+    assert ei.value.status == cf.CF_ERR_UNSUPPORTED
+
+
 def test_device_wait_cannot_be_captured():
     """A graph holds no edge from a flag write to the kernel that polls the flag: the combination is refused."""
     w = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=2, m_chunk=64, n=64, k=64)
