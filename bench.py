@@ -81,7 +81,11 @@ def main() -> int:
         out = {}
         for name, fl in (("overlapped", 0), ("compute_only", cf.CF_NO_COPY), ("copy_only", cf.CF_NO_COMPUTE)):
             best = None
-            for mode, extra in MODES if (fl == 0 and kind in (cf.CF_KIND_RS, cf.CF_KIND_AG)) else BASIC:
+            for mode, extra in MODES if (kind in (cf.CF_KIND_RS, cf.CF_KIND_AG) and (fl == 0 or "persistent" in mode or mode in BASIC_NAMES)) else BASIC:
+                if fl != 0 and (extra & (cf.CF_FUSED_COPY | cf.CF_DEVICE_WAIT)):
+                    continue
+                if (extra & cf.CF_PERSISTENT) and getattr(run, "each", None) is None:
+                    continue                              # needs a landing buffer per hop
                 t = time_calls(lambda: cf.run_schedule(run.desc, kind, run.bufs, run.cs, run.xs, fl | extra),
                                run.cs, steps, warmup)
                 if best is None or t < best[0]:
@@ -92,12 +96,16 @@ def main() -> int:
     # how the emulated deliveries are enqueued: hipMemcpyAsync on the copy stream ordered by events
     # (eager or as a captured graph), or carried by extra workgroups of the step kernels (one stream)
     # or not overlapped at all (one stream, each delivery after the kernel before it: the copies then run
-    # at full speed and disturb no GEMM -- a reference point for what the overlap buys)
+    # at full speed and disturb no GEMM -- a reference point for what the overlap buys); "persistent": all
+    # steps of a rank step in one kernel launch, the deliveries enqueued before it
     MODES = (("streams", 0), ("graph", cf.CF_GRAPH), ("fused-copy", cf.CF_FUSED_COPY),
              ("fused-copy+graph", cf.CF_FUSED_COPY | cf.CF_GRAPH), ("device-wait", cf.CF_DEVICE_WAIT),
-             ("serial", cf.CF_SERIAL), ("serial+graph", cf.CF_SERIAL | cf.CF_GRAPH))
+             ("serial", cf.CF_SERIAL), ("serial+graph", cf.CF_SERIAL | cf.CF_GRAPH),
+             ("persistent", cf.CF_PERSISTENT | cf.CF_SERIAL),
+             ("persistent+graph", cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_GRAPH))
 
-    BASIC = tuple(m for m in MODES if m[0] in ("streams", "graph", "serial", "serial+graph"))   # work for every kind and flag
+    BASIC_NAMES = ("streams", "graph", "serial", "serial+graph")
+    BASIC = tuple(m for m in MODES if m[0] in BASIC_NAMES)   # work for every kind and flag
     if args.modes:
         keep = set(args.modes.split(","))
         MODES = tuple(m for m in MODES[:2]) + tuple(m for m in MODES[2:] if m[0] in keep) if not keep & {"streams", "graph"} \
@@ -133,7 +141,9 @@ def main() -> int:
     pair_modes = {}
     for name, fl in (("overlapped", 0), ("compute_only", cf.CF_NO_COPY), ("copy_only", cf.CF_NO_COMPUTE)):
         best = None
-        for mode, extra in MODES if fl == 0 else BASIC:
+        for mode, extra in MODES:
+            if fl != 0 and (extra & (cf.CF_FUSED_COPY | cf.CF_DEVICE_WAIT)):
+                continue
             t = time_calls(lambda: pair(fl | extra), ag.cs, K, W)
             log(f"  pair {name} [{mode}]: {t*1e3:.1f} us")
             if fl == 0:
@@ -296,6 +306,8 @@ def main() -> int:
         fl_proj = 2.0 * mca * Da * ha * 128
         best = None
         for mode, extra in MODES:
+            if extra & cf.CF_PERSISTENT:
+                continue                                  # the attention steps are two kernels each
             t = time_calls(lambda: cf.run_attn_schedule(adesc, abufs, cs, xs, extra), cs, max(K, 30), W)
             if best is None or t < best[0]:
                 best = (t, mode)

@@ -266,10 +266,12 @@ enum {
                             the add of B_in / the arrival of the slice does), nothing is launched or
                             drained between steps, and because a step no longer has to fill the chip
                             alone the tiles can be larger.  Needs cf_buffers.recv_each (every hop's
-                            delivery stays where it landed) and no peer_sink.  With copies overlapped
-                            the kernel waits for each delivery's flag on the device as under
-                            CF_DEVICE_WAIT (workspace needed; not with CF_GRAPH); with CF_SERIAL all
-                            deliveries are enqueued before the kernel and no flags are involved.
+                            delivery stays where it landed), no peer_sink, and CF_SERIAL: the
+                            deliveries are enqueued before the kernel on the compute stream -- a
+                            kernel that holds its compute units for the whole rank step starves
+                            concurrent blit copies.  (The kernel can also wait for per-step delivery
+                            flags on the device; on a real ring, where a delivery is a remote DMA
+                            write that needs no compute unit here, that is how it would overlap.)
                             Not with CF_FUSED_COPY / CF_DEVICE_WAIT.                                   */
     CF_DEVICE_WAIT = 64u /* bf16 RS / AG only, needs a registered workspace: the compute
                             stream does not wait for the copy stream between steps;

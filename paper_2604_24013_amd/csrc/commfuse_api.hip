@@ -786,16 +786,12 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
 }
 
 // CF_PERSISTENT: all (sub-)steps of a reduce-scatter or all-gather rank step in ONE launch of the chunk-GEMM
-// kernel (its work-item loop), the deliveries either all before it (serial) or beside it on the copy stream,
-// each followed by a flag write that the kernel polls.
-cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, hipStream_t cs, hipStream_t xs_in,
-                             uint32_t flags)
+// kernel (its work-item loop); the deliveries are enqueued before it on the same stream.
+cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, hipStream_t cs, uint32_t flags)
 {
     const int p = r.p, m = r.m, S = r.p * r.m;
     const bool do_copy = !(flags & CF_NO_COPY) && p > 1;
     const bool do_compute = !(flags & CF_NO_COMPUTE);
-    const bool serial = (flags & CF_SERIAL) != 0 || xs_in == cs || !do_copy || !do_compute;
-    hipStream_t xs = serial ? cs : xs_in;
     const bool poison = (flags & CF_POISON) != 0;
     const size_t slot_bytes = kind == CF_KIND_RS ? (size_t)r.mc * r.n * sizeof(float) : (size_t)r.mc * r.k * in_elem(r);
     auto receives = [&](int j) { return j >= m && j < S; };
@@ -803,52 +799,26 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
     auto landing = [&](int j) -> void * {
         return static_cast<char *>(b->recv_each[j / m - 1]) + (size_t)(j % m) * slot_bytes;
     };
-    unsigned *dw_flags = nullptr, *dw_status = nullptr;
-    if (!serial) {
-        std::lock_guard<std::mutex> lk(g_ws_mu);
-        if (g_ws.ptr == nullptr || g_ws.bytes < WS_COUNTER_BYTES)
-            return fail(CF_ERR_INVALID_ARG, "CF_PERSISTENT with overlapped copies needs a registered workspace");
-        dw_flags = reinterpret_cast<unsigned *>(static_cast<char *>(g_ws.ptr) + WS_FLAG_OFFSET);
-        dw_status = reinterpret_cast<unsigned *>(static_cast<char *>(g_ws.ptr) + WS_STATUS_OFFSET);
-    }
-    std::vector<hipEvent_t> ev;
-    if (cf_status st = get_events(2, &ev))
-        return st;
-    if (!serial) {
-        hipError_t e = cf::launch_set_words(dw_flags, S, 0u, cs);
-        if (e != hipSuccess)
-            return fail_hip(e, "flag reset");
-        CF_HIP(hipEventRecord(ev[0], cs));
-        CF_HIP(hipStreamWaitEvent(xs, ev[0], 0));
-    }
-    if (do_copy) {
+    if (do_copy && slot_bytes > 0) {
         for (int j = m; j < S; ++j) {
-            if (slot_bytes == 0)
-                break;
             void *dst = landing(j);
             if (poison) {
-                hipError_t e = cf::launch_fill_ff(dst, slot_bytes, xs);
+                hipError_t e = cf::launch_fill_ff(dst, slot_bytes, cs);
                 if (e != hipSuccess)
                     return fail_hip(e, "poison fill");
             }
             const char *src = static_cast<const char *>(b->peer_stage[j / m - 1]) + (size_t)(j % m) * slot_bytes;
-            CF_HIP(hipMemcpyAsync(dst, src, slot_bytes, hipMemcpyDeviceToDevice, xs));
-            if (!serial) {
-                hipError_t e = cf::launch_set_words(dw_flags + j, 1, 1u, xs);
-                if (e != hipSuccess)
-                    return fail_hip(e, "flag write");
-            }
+            CF_HIP(hipMemcpyAsync(dst, src, slot_bytes, hipMemcpyDeviceToDevice, cs));
         }
     }
     if (do_compute && r.mc > 0 && r.n > 0) {
+        if (r.k == 0)
+            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT needs k > 0");
         cf::GemmParams gp;
         gp.W = b->W;
         fill_shape(gp, r);
         gp.n_steps = S;
         gp.num_cu = num_cu_of_current_device();
-        gp.wait_at_start = kind == CF_KIND_AG;
-        gp.status = dw_status;
-        gp.spin_limit = spin_limit();
         for (int j = 0; j < S; ++j) {
             const int c = subslice_index(kind, p, m, r.rank, j);
             if (kind == CF_KIND_RS) {
@@ -862,18 +832,11 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
                 gp.recv_step[j] = nullptr;
                 gp.out_step[j] = static_cast<char *>(b->O) + (size_t)c * r.mc * r.ldo * (r.bf16_out ? 2 : 4);
             }
-            gp.flag_step[j] = (!serial && receives(j)) ? dw_flags + j : nullptr;
-        }
-        if (r.k == 0) {
-            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT needs k > 0");
+            gp.flag_step[j] = nullptr;               // everything was delivered before the launch
         }
         hipError_t e = cf::launch_gemm_bf16(gp, r.w_kn, r.bf16_out, cs, gp.num_cu);
         if (e != hipSuccess)
             return fail_hip(e, "persistent rank-step launch");
-    }
-    if (!serial) {
-        CF_HIP(hipEventRecord(ev[1], xs));
-        CF_HIP(hipStreamWaitEvent(cs, ev[1], 0));
     }
     return CF_OK;
 }
@@ -976,14 +939,16 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
             return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT cannot feed peer_sink (nothing signals a finished step)");
         if (bufs != nullptr && r.p > 1 && bufs->recv_each == nullptr)
             return fail(CF_ERR_INVALID_ARG, "CF_PERSISTENT needs buffers->recv_each (a landing buffer per hop)");
-        const bool flags_needed = !(flags & (CF_SERIAL | CF_NO_COPY | CF_NO_COMPUTE)) && xs != cs && r.p > 1;
-        if (flags_needed && (flags & CF_GRAPH))
-            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT with overlapped copies polls delivery flags: not with CF_GRAPH");
+        // A kernel that holds its compute units for a whole rank step starves the blit kernels of concurrent
+        // deliveries (its workgroups can take every register of a CU; measured: the copies then crawl on the
+        // few CUs left over and the kernel's bounded waits time out).  So the deliveries are enqueued before it.
+        if (!(flags & (CF_SERIAL | CF_NO_COPY | CF_NO_COMPUTE)) && xs != cs && r.p > 1)
+            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT needs CF_SERIAL (the deliveries are enqueued before the kernel)");
     }
     if (cf_status st = check_buffers(r, kind, bufs, flags))
         return st;
     if (!(flags & CF_GRAPH))
-        return (flags & CF_PERSISTENT) ? enqueue_persistent(r, kind, bufs, cs, xs, flags)
+        return (flags & CF_PERSISTENT) ? enqueue_persistent(r, kind, bufs, cs, flags)
                                        : enqueue_schedule(r, kind, bufs, cs, xs, flags, attn);
 
     // CF_GRAPH: the same enqueue sequence, captured once per distinct argument set.
@@ -1031,7 +996,7 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
             return st;
         CF_HIP(hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal));
         const uint32_t fl = flags & ~(uint32_t)CF_GRAPH;
-        cf_status st = (fl & CF_PERSISTENT) ? enqueue_persistent(r, kind, bufs, cs, xs, fl)
+        cf_status st = (fl & CF_PERSISTENT) ? enqueue_persistent(r, kind, bufs, cs, fl)
                                             : enqueue_schedule(r, kind, bufs, cs, xs, fl, attn);
         hipGraph_t graph = nullptr;
         hipError_t e = hipStreamEndCapture(cs, &graph);

@@ -429,8 +429,8 @@ def test_persistent_rank_step(m, tile):
     refa = _oracle_ag(wa, da, rank)
     _tile_env(tile)
     try:
-        for flags in (cf.CF_PERSISTENT, cf.CF_PERSISTENT | cf.CF_SERIAL, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_GRAPH,
-                      cf.CF_PERSISTENT | cf.CF_POISON, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_POISON):
+        for flags in (cf.CF_PERSISTENT | cf.CF_SERIAL, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_GRAPH,
+                      cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_POISON):
             for layout in (cf.CF_W_KN, cf.CF_W_NK):
                 run = H.RsRun(w, data, rank, layout, m=m, each=True)
                 run.O.fill_(float("nan"))
@@ -461,11 +461,11 @@ def test_persistent_rank_step(m, tile):
 def test_persistent_needs_what_it_needs():
     w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=4, m_chunk=64, n=64, k=64)
     data = inputs.make_rs(w)
-    for kw, flags, status in (({}, cf.CF_PERSISTENT, cf.CF_ERR_INVALID_ARG),                       # no recv_each
-                              ({"each": True, "with_sink": True}, cf.CF_PERSISTENT, cf.CF_ERR_UNSUPPORTED),
-                              ({"each": True}, cf.CF_PERSISTENT | cf.CF_GRAPH, cf.CF_ERR_UNSUPPORTED),   # flags + graph
-                              ({"each": True}, cf.CF_PERSISTENT | cf.CF_FUSED_COPY, cf.CF_ERR_UNSUPPORTED),
-                              ({"each": True}, cf.CF_PERSISTENT, cf.CF_ERR_INVALID_ARG)):                # no workspace
+    PS = cf.CF_PERSISTENT | cf.CF_SERIAL
+    for kw, flags, status in (({}, PS, cf.CF_ERR_INVALID_ARG),                                     # no recv_each
+                              ({"each": True, "with_sink": True}, PS, cf.CF_ERR_UNSUPPORTED),
+                              ({"each": True}, cf.CF_PERSISTENT, cf.CF_ERR_UNSUPPORTED),           # overlapped copies
+                              ({"each": True}, PS | cf.CF_FUSED_COPY, cf.CF_ERR_UNSUPPORTED)):
         run = H.RsRun(w, data, 0, **kw)
         with pytest.raises(cf.CommFuseError) as ei:
             run.run_schedule(flags)
