@@ -26,6 +26,8 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+SETTLE_S = 0.06               # untimed load before every timed region (see time_calls)
+TRAFFIC_DOWN_RANK_STEP = 1444.6e6   # measured, see the roofline object
 
 
 def log(*a):
@@ -61,9 +63,16 @@ def main() -> int:
     K, W = args.steps, args.warmup
 
     def time_calls(fn, stream, steps, warmup):
-        """Average milliseconds of fn() over `steps` back-to-back calls, HIP events on `stream`."""
-        for _ in range(warmup):
+        """Average milliseconds of fn() over `steps` back-to-back calls, HIP events on `stream`.
+        Untimed calls first: `warmup` of them, and as many more as it takes to keep the GPU busy for
+        SETTLE_S seconds (after an idle stretch -- input generation on the host -- the shader clock
+        takes some tens of milliseconds of load to settle; shorter warm-ups time the ramp)."""
+        t0, n = time.perf_counter(), 0
+        while n < warmup or time.perf_counter() - t0 < SETTLE_S:
             fn()
+            n += 1
+            if n % 4 == 0:
+                stream.synchronize()
         stream.synchronize()
         torch.cuda.synchronize()
         e0 = torch.cuda.Event(enable_timing=True)
@@ -156,22 +165,31 @@ def main() -> int:
     ms_step = pair_t["overlapped"][0]
     value = flops_pair / (ms_step * 1e-3) / 1e12
 
-    # dominant kernel: the fused down-projection chunk GEMM (B_in add + B_out store), launched alone
-    recv = rs.stage[0]
-    out = rs.send[0]
-    t_kernel = time_calls(lambda: cf.rs_step(rs.desc, 1, rs.A, rs.W, recv, out, ag.cs), ag.cs, max(K, 50), W)
-    flops_kernel = 2.0 * dn.m_chunk * dn.n * dn.k
-    ach = flops_kernel / (t_kernel * 1e-3) / 1e12
-    t_kernel_up = time_calls(lambda: cf.ag_step(ag.desc, 1, ag.stage[0], ag.W, ag.O, ag.cs), ag.cs, max(K, 50), W)
-    roofline = {"bound": "mfma", "kernel": "gemm_bf16_dl_kernel (down-projection chunk GEMM, fused B_in add)",
+    # dominant kernel: the down-projection rank-step kernel (one persistent launch = the eight chunk GEMMs
+    # of the rank step with their B_in adds and B_out / O stores), launched alone: CF_NO_COPY enqueues nothing else
+    PS = cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_NO_COPY
+    t_kernel = time_calls(lambda: cf.run_schedule(rs.desc, cf.CF_KIND_RS, rs.bufs, rs.cs, rs.xs, PS), ag.cs, max(K, 50), W)
+    ach = dn.flops / (t_kernel * 1e-3) / 1e12
+    t_kernel_up = time_calls(lambda: cf.run_schedule(ag.desc, cf.CF_KIND_AG, ag.bufs, ag.cs, ag.xs, PS), ag.cs, max(K, 50), W)
+    # the same GEMMs as one kernel per step (what every mode but "persistent" launches), step 1 alone
+    t_chunk = time_calls(lambda: cf.rs_step(rs.desc, 1, rs.A, rs.W, rs.stage[0], rs.send[0], ag.cs), ag.cs, max(K, 50), W)
+    t_chunk_up = time_calls(lambda: cf.ag_step(ag.desc, 1, ag.stage[0], ag.W, ag.O, ag.cs), ag.cs, max(K, 50), W)
+    chunk_flops = 2.0 * dn.m_chunk * dn.n * dn.k
+    roofline = {"bound": "mfma",
+                "kernel": "gemm_bf16_dl_kernel<256,256,...,persistent> (down-projection rank step: 8 chunk GEMMs, fused B_in adds)",
                 "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                # HBM bytes per launch from rocprofv3 counters (profiles/gemm_bf16_dl_kernel_70b_pair_counters.md):
-                # FETCH_SIZE x 2.00 (scale from a plain 256 MiB copy) + WRITE_SIZE; algorithmic bytes are 133.2e6
-                "traffic": 183.9e6, "algorithmic_bytes": 133.2e6,
+                # bytes through the L2s' memory side per launch from rocprofv3 counters
+                # (profiles/gemm_bf16_dl_kernel_70b_pair_counters.md): FETCH_SIZE x 2.00 (scale from a plain
+                # 256 MiB copy) + WRITE_SIZE; algorithmic bytes: A 58.7 + W 58.7 + B_in 7 x 33.55 + B_out/O 8 x 33.55 MB
+                "traffic": TRAFFIC_DOWN_RANK_STEP, "algorithmic_bytes": 620.7e6,
                 "us_per_launch": round(t_kernel * 1e3, 2),
-                "up_projection_kernel_tflops": round(2.0 * up.m_chunk * up.n * up.k / (t_kernel_up * 1e-3) / 1e12, 1)}
-    log(f"chunk GEMM down {t_kernel*1e3:.1f} us = {ach:.0f} TFLOP/s; up {t_kernel_up*1e3:.1f} us")
+                "up_projection_rank_step_kernel": {"us_per_launch": round(t_kernel_up * 1e3, 2),
+                                                   "tflops": round(up.flops / (t_kernel_up * 1e-3) / 1e12, 1)},
+                "one_kernel_per_step": {"down_us": round(t_chunk * 1e3, 2), "down_tflops": round(chunk_flops / (t_chunk * 1e-3) / 1e12, 1),
+                                        "up_us": round(t_chunk_up * 1e3, 2), "up_tflops": round(chunk_flops / (t_chunk_up * 1e-3) / 1e12, 1)}}
+    log(f"rank-step kernel down {t_kernel*1e3:.1f} us = {ach:.0f} TFLOP/s, up {t_kernel_up*1e3:.1f} us; "
+        f"chunk GEMM down {t_chunk*1e3:.1f} us, up {t_chunk_up*1e3:.1f} us")
     del ag, rs, ddn
     torch.cuda.empty_cache()
 
@@ -222,7 +240,7 @@ def main() -> int:
             data = make(w)
             entry = {}
             for m in (1, 2):
-                run = Run(w, data, 0, m=m)
+                run = Run(w, data, 0, m=m, each=True)
                 t = schedule_times(run, kind, max(K, 50), W)
                 entry[f"m{m}"] = {"tflops": round(w.flops / (t["overlapped"][0] * 1e-3) / 1e12, 1),
                                   "us_per_rank_step": round(t["overlapped"][0] * 1e3, 1), "mode": t["overlapped"][1],

@@ -225,7 +225,11 @@ cf_status commfuse_dp_pair_step(int p, int rank, int step, float *bucket, int64_
  * sits in peer_stage[i-1] and is copied into slot[i % 2] on the copy stream.
  * With granularity m > 1, peer_stage[i-1] / peer_sink[i] still hold one whole hop (the
  * m blocks stacked by rows); block s of hop i is delivered for sub-step j = i*m + s into
- * slot[j % 2] (m_chunk/m rows are used of each slot and send slot). */
+ * slot[j % 2] (m_chunk/m rows are used of each slot and send slot).
+ * Slices and partial sums keep the descriptor's row strides everywhere (slices of the
+ * all-gather path: lda, of the weight-gradient path: lda / ldw, partial sums: ldo), in
+ * peer_stage, slot, send_slot, peer_sink and recv_each alike; a delivery copies a row
+ * block with its padding.  The pairwise kinds need packed partial sums (ldo == n). */
 typedef struct {
     const void *A_or_own_shard;   /* RS: A [p*m_chunk x k]; AG: X^r [m_chunk x k]; DP: unused */
     const void *W;                /* weight shard (unused for DP)                             */

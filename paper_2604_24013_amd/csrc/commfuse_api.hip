@@ -605,12 +605,12 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
     // for a kernel, and (with CF_DEVICE_WAIT and no sinks) nothing but kernels is enqueued on the compute stream
     const bool each = !pair && !is_dp_kind(kind) && b->recv_each != nullptr && p > 1;
     size_t slot_bytes;                               // one (sub-)step's delivery
-    if (is_rs_kind(kind))
-        slot_bytes = (size_t)r.mc * r.n * sizeof(float);
+    if (is_rs_kind(kind))                            // row blocks travel with their row stride, padding included
+        slot_bytes = (size_t)r.mc * r.ldo * sizeof(float);
     else if (kind == CF_KIND_AG || kind == CF_KIND_WGRAD_X)
-        slot_bytes = (size_t)r.mc * r.k * in_elem(r);
+        slot_bytes = (size_t)r.mc * r.lda * in_elem(r);
     else if (kind == CF_KIND_WGRAD_G)
-        slot_bytes = (size_t)r.mc * r.n * in_elem(r);
+        slot_bytes = (size_t)r.mc * r.ldw * in_elem(r);
     else
         slot_bytes = (size_t)r.mc * sizeof(float);
     auto receives = [&](int j) { return j >= m && j < S; };          // sub-step j consumes a delivery
@@ -793,7 +793,7 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
     const bool do_copy = !(flags & CF_NO_COPY) && p > 1;
     const bool do_compute = !(flags & CF_NO_COMPUTE);
     const bool poison = (flags & CF_POISON) != 0;
-    const size_t slot_bytes = kind == CF_KIND_RS ? (size_t)r.mc * r.n * sizeof(float) : (size_t)r.mc * r.k * in_elem(r);
+    const size_t slot_bytes = kind == CF_KIND_RS ? (size_t)r.mc * r.ldo * sizeof(float) : (size_t)r.mc * r.lda * in_elem(r);
     auto receives = [&](int j) { return j >= m && j < S; };
     auto sends = [&](int j) { return j >= 0 && j < S - m; };
     auto landing = [&](int j) -> void * {
@@ -880,14 +880,8 @@ cf_status check_buffers(const Resolved &r, int kind, const cf_buffers *b, uint32
                 return fail(CF_ERR_INVALID_ARG, "the two send slots must be distinct buffers");
         }
     }
-    if (!is_dp_kind(kind)) {
-        if (r.ldo != r.n)
-            return fail(CF_ERR_UNSUPPORTED, "run_schedule needs packed partial sums / outputs (ldo == n)");
-        if ((kind == CF_KIND_AG || kind == CF_KIND_WGRAD_X) && r.lda != r.k)
-            return fail(CF_ERR_UNSUPPORTED, "run_schedule needs packed slices (lda == k)");
-        if (kind == CF_KIND_WGRAD_G && r.ldw != r.n)
-            return fail(CF_ERR_UNSUPPORTED, "run_schedule needs packed slices (ldw == n)");
-    }
+    if (is_pair_kind(kind) && !is_dp_kind(kind) && r.ldo != r.n)
+        return fail(CF_ERR_UNSUPPORTED, "the pairwise schedule needs packed partial sums (ldo == n)");
     return CF_OK;
 }
 

@@ -153,10 +153,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
 
     __shared__ __attribute__((aligned(1024))) unsigned char smem[NS * STAGE];
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave % WGM, wn = wave / WGM;
+    const int tid0 = threadIdx.x;
 
     // Workgroups beyond the GEMM's own grid carry the emulated delivery of the NEXT step (what the ring
     // neighbour sends while this step computes): a streaming copy that shares the launch with the GEMM,
@@ -167,7 +164,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         u32x4_t *dst = static_cast<u32x4_t *>(P.cp_dst);
         const size_t n16 = P.cp_bytes / 16;
         const size_t stride = (size_t)P.cp_wgs * (64 * NW);
-        size_t i = (size_t)((int)blockIdx.x - gemm_wgs) * (64 * NW) + tid;
+        size_t i = (size_t)((int)blockIdx.x - gemm_wgs) * (64 * NW) + tid0;
         for (; i + 3 * stride < n16; i += 4 * stride) {
             const u32x4_t v0 = __builtin_nontemporal_load(&src[i]);
             const u32x4_t v1 = __builtin_nontemporal_load(&src[i + stride]);
@@ -193,6 +190,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     const int n_items = PERSIST ? tiles_per_step * P.n_steps : 0;
     int item = blockIdx.x;
     do {
+    // Lane and wave indices are taken anew for every work item: what is derived from them then lives
+    // from its first use in this item, not across the whole loop.
+    int tid = tid0;
+    if constexpr (PERSIST)
+        asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave % WGM, wn = wave / WGM;
     const int step_i = PERSIST ? item / tiles_per_step : 0;
     const void *const cA = PERSIST ? P.A_step[step_i] : P.A;
     const float *const cRecv = PERSIST ? P.recv_step[step_i] : P.recv;

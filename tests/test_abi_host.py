@@ -196,7 +196,7 @@ def test_schedule_argument_checks(lib):
     bad = cf.make_buffers(0x100, 0x200, 0x300, [0x1000, None, 0x3000], (0x400, 0x500), (0x600, 0x700))
     assert _status(cf.run_schedule, d, cf.CF_KIND_RS, bad, None, None, 0)[0] == cf.CF_ERR_NULL_PTR
     strided = cf.layer_desc(4, 0, 16, 32, 64, ldo=40)
-    assert _status(cf.run_schedule, strided, cf.CF_KIND_RS, ok, None, None, 0)[0] == cf.CF_ERR_UNSUPPORTED
+    assert _status(cf.run_schedule, strided, cf.CF_KIND_RS_PAIR, ok, None, None, 0)[0] == cf.CF_ERR_UNSUPPORTED
     assert _status(cf.run_schedule, d, cf.CF_KIND_RS, ok, None, None, cf.CF_GRAPH)[0] == cf.CF_ERR_INVALID_ARG
     assert _status(cf.run_schedule, d, cf.CF_KIND_RS, ok, None, None, cf.CF_FUSED_COPY | cf.CF_POISON)[0] == cf.CF_ERR_UNSUPPORTED
     assert _status(cf.run_schedule, cf.layer_desc(4, 0, 16, 32, 64, "f32"), cf.CF_KIND_RS, ok, None, None, cf.CF_FUSED_COPY)[0] == cf.CF_ERR_UNSUPPORTED

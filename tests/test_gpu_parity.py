@@ -458,6 +458,65 @@ def test_persistent_rank_step(m, tile):
     assert H.rel_err(H.to_host_f64(run.O), ref[-1]) <= TIGHT_BF16
 
 
+def _padded(t, rows, cols, ld, fill):
+    """Device copy of a [rows x cols] tensor with row stride ld; the padding holds `fill`."""
+    o = torch.full((rows, ld), fill, dtype=t.dtype, device=H.DEV)
+    o[:, :cols] = t.reshape(rows, cols)
+    return o
+
+
+@pytest.mark.parametrize("m", [1, 2])
+def test_run_schedule_padded_row_strides(m):
+    """Slices and partial sums with padded rows (lda > k, ldw > n, ldo > n): every buffer of the schedule
+    keeps the descriptor's strides, a delivery moves a row block with its padding; what sits in the padding
+    (huge values here) reaches no result."""
+    rank = 2
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=4, m_chunk=264, n=520, k=328)
+    data = inputs.make_rs(w, salt=23)
+    ref = _oracle_rs(w, data, rank)
+    lda, ldw, ldo = w.k + 8, w.n + 24, w.n + 16
+    base = H.RsRun(w, data, rank, m=m, each=True)
+    pad32 = lambda t: _padded(t, w.m_chunk, w.n, ldo, 1e30)
+    mk32 = lambda: torch.full((w.m_chunk, ldo), 1e30, dtype=torch.float32, device=H.DEV)
+    A = _padded(base.A, w.p * w.m_chunk, w.k, lda, 1e30)
+    W = _padded(base.W, w.k, w.n, ldw, 1e30)
+    stage = [pad32(t) for t in base.stage]
+    desc = cf.layer_desc(w.p, rank, w.m_chunk, w.n, w.k, w.dtype, w.out_dtype, cf.CF_W_KN, lda=lda, ldw=ldw, ldo=ldo, m=m)
+    for flags, each in ((0, False), (cf.CF_SERIAL, False), (cf.CF_GRAPH, True), (cf.CF_FUSED_COPY, False),
+                        (cf.CF_DEVICE_WAIT | cf.CF_POISON, True), (cf.CF_PERSISTENT | cf.CF_SERIAL, True)):
+        O = mk32()
+        keep = ([mk32(), mk32()], [mk32(), mk32()], [mk32() for _ in range(w.p - 1)])
+        bufs = cf.make_buffers(A, W, O, stage, keep[0], keep[1], None, keep[2] if each else None)
+        with H.Workspace(desc, cf.CF_KIND_RS):
+            cf.run_schedule(desc, cf.CF_KIND_RS, bufs, base.cs, base.xs, flags)
+            base.cs.synchronize()
+            cf.device_status(base.cs)
+        got = H.to_host_f64(O)
+        assert H.rel_err(got[:, :w.n], ref[-1]) <= TIGHT_BF16, f"flags {flags}"
+        assert np.all(got[:, w.n:] == np.float64(np.float32(1e30))), f"flags {flags}: padding of O was written"
+    wa = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=4, m_chunk=136, n=264, k=520, out_dtype="bf16")
+    da = inputs.make_ag(wa, salt=24)
+    refa = _oracle_ag(wa, da, rank)
+    lda, ldw, ldo = wa.k + 8, wa.n + 8, wa.n + 24
+    ab = H.AgRun(wa, da, rank, m=m, each=True)
+    pad16 = lambda t: _padded(t, wa.m_chunk, wa.k, lda, 1e30)
+    mk16 = lambda: torch.full((wa.m_chunk, lda), 1e30, dtype=torch.bfloat16, device=H.DEV)
+    W = _padded(ab.W, wa.k, wa.n, ldw, 1e30)
+    desc = cf.layer_desc(wa.p, rank, wa.m_chunk, wa.n, wa.k, wa.dtype, wa.out_dtype, cf.CF_W_KN, lda=lda, ldw=ldw, ldo=ldo, m=m)
+    for flags, each in ((0, False), (cf.CF_SERIAL | cf.CF_GRAPH, False), (cf.CF_FUSED_COPY, True),
+                        (cf.CF_DEVICE_WAIT | cf.CF_POISON, True), (cf.CF_PERSISTENT | cf.CF_SERIAL, True)):
+        O = torch.full((wa.p * wa.m_chunk, ldo), 3.0, dtype=torch.bfloat16, device=H.DEV)
+        keep = (pad16(ab.X), [pad16(t) for t in ab.stage], [mk16(), mk16()], [mk16() for _ in range(wa.p - 1)])
+        bufs = cf.make_buffers(keep[0], W, O, keep[1], keep[2], (None, None), None, keep[3] if each else None)
+        with H.Workspace(desc, cf.CF_KIND_AG):
+            cf.run_schedule(desc, cf.CF_KIND_AG, bufs, ab.cs, ab.xs, flags)
+            ab.cs.synchronize()
+            cf.device_status(ab.cs)
+        got = H.to_host_f64(O)
+        assert H.rel_err(got[:, :wa.n], refa) <= TIGHT_BF16_OUT, f"flags {flags}"
+        assert np.all(got[:, wa.n:] == 3.0), f"flags {flags}: padding of O was written"
+
+
 def test_persistent_needs_what_it_needs():
     w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=4, m_chunk=64, n=64, k=64)
     data = inputs.make_rs(w)
