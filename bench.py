@@ -259,9 +259,9 @@ def main() -> int:
             return H.to_dev(inputs.f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32) * sigma), "bf16")
         p8, mc8, d_model, d_ff = up.p, up.m_chunk, up.k, up.n           # 8, 1024, 8192, 3584
         cs, xs = torch.cuda.Stream(), torch.cuda.Stream()
-        def timed(desc, kind, bufs):
+        def timed(desc, kind, bufs, modes=BASIC):
             best = None
-            for mode, extra in BASIC:
+            for mode, extra in modes:
                 t = time_calls(lambda: cf.run_schedule(desc, kind, bufs, cs, xs, extra), cs, max(K, 30), W)
                 if best is None or t < best[0]:
                     best = (t, mode)
@@ -272,34 +272,46 @@ def main() -> int:
         G_up = bf16_dev((p8 * mc8, d_ff), 1.0)
         W_up = bf16_dev((d_model, d_ff), 0.01)
         stage32 = [mk32(mc8, d_model).normal_() for _ in range(p8 - 1)]
-        bufs = cf.make_buffers(G_up, W_up, mk32(mc8, d_model), stage32, [mk32(mc8, d_model) for _ in range(2)],
-                               [mk32(mc8, d_model) for _ in range(2)])
-        t = timed(cf.layer_desc(p8, 0, mc8, d_model, d_ff, "bf16", "f32", cf.CF_W_NK), cf.CF_KIND_RS, bufs)
+        PERS = tuple(m for m in MODES if m[0] in BASIC_NAMES or "persistent" in m[0])
+        each32 = [mk32(mc8, d_model) for _ in range(p8 - 1)]
+        keep = [mk32(mc8, d_model), [mk32(mc8, d_model) for _ in range(2)], [mk32(mc8, d_model) for _ in range(2)]]
+        bufs = cf.make_buffers(G_up, W_up, keep[0], stage32, keep[1], keep[2], None, each32)   # (the tensors must outlive bufs)
+        t = timed(cf.layer_desc(p8, 0, mc8, d_model, d_ff, "bf16", "f32", cf.CF_W_NK), cf.CF_KIND_RS, bufs, PERS)
         backward["up_dgrad_rs"] = {"us": round(t[0] * 1e3, 1), "tflops": round(flops / (t[0] * 1e-3) / 1e12, 1), "mode": t[1]}
-        X_own = bf16_dev((mc8, d_model), 1.0)
+        # the arriving slices land in ONE gathered buffer (own slice in row block rank = 0, hop i in row block
+        # (rank - i) mod p): with CF_PERSISTENT the eight chunk GEMMs are then one GEMM over all its rows
         stage16 = [bf16_dev((mc8, d_model), 1.0) for _ in range(p8 - 1)]
         mk16 = lambda r, c: torch.empty((r, c), dtype=torch.bfloat16, device=H.DEV)
+        gathered = mk16(p8 * mc8, d_model)
+        blk = lambda c: gathered[c * mc8:(c + 1) * mc8]
+        blk(0).copy_(bf16_dev((mc8, d_model), 1.0))
+        land = [blk((0 - i) % p8) for i in range(1, p8)]
         dW_up = mk32(d_model, d_ff)
-        bufs = cf.make_buffers(X_own, G_up, dW_up, stage16, [mk16(mc8, d_model) for _ in range(2)])
-        t = timed(cf.layer_desc(p8, 0, mc8, d_ff, d_model, "bf16", "f32"), cf.CF_KIND_WGRAD_X, bufs)
+        slots16 = [mk16(mc8, d_model) for _ in range(2)]
+        bufs = cf.make_buffers(blk(0), G_up, dW_up, stage16, slots16, (None, None), None, land)
+        t = timed(cf.layer_desc(p8, 0, mc8, d_ff, d_model, "bf16", "f32"), cf.CF_KIND_WGRAD_X, bufs, PERS)
         backward["up_wgrad"] = {"us": round(t[0] * 1e3, 1), "tflops": round(flops / (t[0] * 1e-3) / 1e12, 1), "mode": t[1]}
-        del G_up, stage32, stage16, bufs, dW_up
+        del G_up, stage32, stage16, bufs, dW_up, each32, keep
         torch.cuda.empty_cache()
         # down-projection layer (reduce-scatter layer, W [d_ff x d_model]): dA = AG(G) W^T, dW = A^T AG(G)
         W_dn = bf16_dev((d_ff, d_model), 0.01)
         G_own = bf16_dev((mc8, d_model), 1.0)
         stage16 = [bf16_dev((mc8, d_model), 1.0) for _ in range(p8 - 1)]
-        bufs = cf.make_buffers(G_own, W_dn, mk32(p8 * mc8, d_ff), stage16, [mk16(mc8, d_model) for _ in range(2)])
-        t = timed(cf.layer_desc(p8, 0, mc8, d_ff, d_model, "bf16", "f32", cf.CF_W_NK), cf.CF_KIND_AG, bufs)
+        each16 = [mk16(mc8, d_model) for _ in range(p8 - 1)]
+        keep = [mk32(p8 * mc8, d_ff)]
+        bufs = cf.make_buffers(G_own, W_dn, keep[0], stage16, slots16, (None, None), None, each16)
+        t = timed(cf.layer_desc(p8, 0, mc8, d_ff, d_model, "bf16", "f32", cf.CF_W_NK), cf.CF_KIND_AG, bufs, PERS)
         backward["down_dgrad_ag"] = {"us": round(t[0] * 1e3, 1), "tflops": round(flops / (t[0] * 1e-3) / 1e12, 1), "mode": t[1]}
         A_loc = bf16_dev((p8 * mc8, d_ff), 1.0)
-        bufs = cf.make_buffers(G_own, A_loc, mk32(d_ff, d_model), stage16, [mk16(mc8, d_model) for _ in range(2)])
-        t = timed(cf.layer_desc(p8, 0, mc8, d_model, d_ff, "bf16", "f32"), cf.CF_KIND_WGRAD_G, bufs)
+        blk(0).copy_(G_own)
+        keep = [mk32(d_ff, d_model)]
+        bufs = cf.make_buffers(blk(0), A_loc, keep[0], stage16, slots16, (None, None), None, land)
+        t = timed(cf.layer_desc(p8, 0, mc8, d_model, d_ff, "bf16", "f32"), cf.CF_KIND_WGRAD_G, bufs, PERS)
         backward["down_wgrad"] = {"us": round(t[0] * 1e3, 1), "tflops": round(flops / (t[0] * 1e-3) / 1e12, 1), "mode": t[1]}
         total = sum(v["us"] for v in backward.values())
         backward["all_four_rank_steps"] = {"us": round(total, 1), "tflops": round(4 * flops / (total * 1e-6) / 1e12, 1)}
         log("backward", backward)
-        del A_loc, stage16, bufs, W_dn, W_up
+        del A_loc, stage16, bufs, W_dn, W_up, gathered, land, keep, slots16, each16
         torch.cuda.empty_cache()
 
     # ---------------- query-split attention FuseRS (Alg. 4), 70B shape: 8 of 64 heads per rank ----------------
@@ -316,8 +328,8 @@ def main() -> int:
         attn_out = torch.empty((mca, ha * 128), dtype=torch.bfloat16, device=H.DEV)
         mk32 = lambda: torch.empty((mca, Da), dtype=torch.float32, device=H.DEV)
         stage_a = [mk32().normal_() for _ in range(pa - 1)]
-        abufs = cf.make_attn_buffers(Qa, Ka, Va, Woa, attn_out, mk32(), stage_a, [mk32(), mk32()], [mk32(), mk32()],
-                                     None, [mk32() for _ in range(pa - 1)])
+        keep = [mk32(), [mk32(), mk32()], [mk32(), mk32()], [mk32() for _ in range(pa - 1)]]
+        abufs = cf.make_attn_buffers(Qa, Ka, Va, Woa, attn_out, keep[0], stage_a, keep[1], keep[2], None, keep[3])
         cs, xs = torch.cuda.Stream(), torch.cuda.Stream()
         t_attn = time_calls(lambda: cf.attn_slice(adesc, 1, Qa, Ka, Va, attn_out, cs), cs, 50, W)
         fl_attn = 4.0 * Ba * ha * (Sa // pa) * Sa * 128
@@ -336,7 +348,7 @@ def main() -> int:
                      "rank_step_tflops": round(pa * (fl_attn + fl_proj) / (best[0] * 1e-3) / 1e12, 1),
                      "shape": "p=8, 8 of 64 heads per rank, head_dim 128, seq 8192, batch 1, W_o [1024 x 8192]"}
         log("attention", attention)
-        del Qa, Ka, Va, Woa, abufs, stage_a
+        del Qa, Ka, Va, Woa, abufs, stage_a, keep
         torch.cuda.empty_cache()
 
     # ---------------- gradient reduce-scatter step, 1e9 fp32 elements ----------------

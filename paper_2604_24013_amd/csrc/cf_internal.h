@@ -45,6 +45,7 @@ struct GemmParams {
     static constexpr int MAX_STEPS = 16;
     int n_steps = 0;
     int num_cu = 256;
+    bool xcd_steps = false;  // persistent mode: XCD x runs steps x, x+8, ... whole (set by the launcher)
     const void *A_step[MAX_STEPS] = {};
     const float *recv_step[MAX_STEPS] = {};
     void *out_step[MAX_STEPS] = {};

@@ -793,7 +793,23 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
     const bool do_copy = !(flags & CF_NO_COPY) && p > 1;
     const bool do_compute = !(flags & CF_NO_COMPUTE);
     const bool poison = (flags & CF_POISON) != 0;
-    const size_t slot_bytes = kind == CF_KIND_RS ? (size_t)r.mc * r.ldo * sizeof(float) : (size_t)r.mc * r.lda * in_elem(r);
+    const size_t slot_bytes = kind == CF_KIND_RS       ? (size_t)r.mc * r.ldo * sizeof(float)
+                              : kind == CF_KIND_WGRAD_G ? (size_t)r.mc * r.ldw * in_elem(r)
+                                                        : (size_t)r.mc * r.lda * in_elem(r);
+    // Weight gradient: the moving operand must sit in "gathered" order -- one [p*m_chunk x width] buffer, the
+    // own slice in row block `rank`, hop i's landing buffer in row block (rank - i) mod p, the row block the
+    // local operand pairs it with.  The p chunk GEMMs dW += slice^T local_slice are then ONE GEMM with the
+    // contraction over all p*m_chunk rows: dW is written once instead of read and written p times.
+    uintptr_t gathered = 0;
+    if (is_wgrad_kind(kind)) {
+        const size_t hop_bytes = slot_bytes * m;
+        gathered = reinterpret_cast<uintptr_t>(b->A_or_own_shard) - (uintptr_t)r.rank * hop_bytes;
+        for (int i = 1; i < p; ++i)
+            if (reinterpret_cast<uintptr_t>(b->recv_each[i - 1]) != gathered + (uintptr_t)chunk_index(CF_KIND_AG, p, r.rank, i) * hop_bytes)
+                return fail(CF_ERR_UNSUPPORTED,
+                            "CF_PERSISTENT for the weight gradient needs the gathered layout: recv_each[%d] must be row block "
+                            "%d of the buffer whose row block %d is the own slice", i - 1, chunk_index(CF_KIND_AG, p, r.rank, i), r.rank);
+    }
     auto receives = [&](int j) { return j >= m && j < S; };
     auto sends = [&](int j) { return j >= 0 && j < S - m; };
     auto landing = [&](int j) -> void * {
@@ -810,6 +826,14 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
             const char *src = static_cast<const char *>(b->peer_stage[j / m - 1]) + (size_t)(j % m) * slot_bytes;
             CF_HIP(hipMemcpyAsync(dst, src, slot_bytes, hipMemcpyDeviceToDevice, cs));
         }
+    }
+    if (do_compute && is_wgrad_kind(kind)) {
+        Resolved all = r;
+        all.m = 1;
+        all.mc = r.mc * S;                           // all rows of the gathered and the local operand
+        const void *moving = reinterpret_cast<const void *>(gathered);
+        return kind == CF_KIND_WGRAD_X ? wgrad_step_impl(all, 0, moving, b->W, static_cast<float *>(b->O), cs)
+                                       : wgrad_step_impl(all, 0, b->W, moving, static_cast<float *>(b->O), cs);
     }
     if (do_compute && r.mc > 0 && r.n > 0) {
         if (r.k == 0)
@@ -925,9 +949,11 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
     if (flags & CF_PERSISTENT) {
         if (flags & (CF_FUSED_COPY | CF_DEVICE_WAIT))
             return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT excludes CF_FUSED_COPY and CF_DEVICE_WAIT");
-        if ((kind != CF_KIND_RS && kind != CF_KIND_AG) || attn != nullptr || !step_can_carry_copy(r) ||
-            r.p * r.m > cf::GemmParams::MAX_STEPS)
-            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT needs kind RS or AG, bf16 operands and at most %d (sub-)steps",
+        const bool ok_kind = is_wgrad_kind(kind) ? wgrad_can_carry_copy(r)
+                                                 : (kind == CF_KIND_RS || kind == CF_KIND_AG) && step_can_carry_copy(r);
+        if (!ok_kind || attn != nullptr || r.p * r.m > cf::GemmParams::MAX_STEPS)
+            return fail(CF_ERR_UNSUPPORTED,
+                        "CF_PERSISTENT needs kind RS, AG or a weight-gradient kind, bf16 operands and at most %d (sub-)steps",
                         cf::GemmParams::MAX_STEPS);
         if (bufs != nullptr && bufs->peer_sink != nullptr)
             return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT cannot feed peer_sink (nothing signals a finished step)");

@@ -187,8 +187,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // the add of B_in / the arrival of the slice does, which the per-step delivery flag guards) and nothing
     // is launched, drained or refilled between steps.  Every workgroup's loop is finite: the kernel exits.
     const int tiles_per_step = tiles_m * tiles_n * P.splits;
-    const int n_items = PERSIST ? tiles_per_step * P.n_steps : 0;
-    int item = blockIdx.x;
+    // XCD-per-step mapping (GemmParams::xcd_steps): XCD x (workgroups x, x+8, ...) runs the steps x, x+8, ...
+    // whole, so a step's own operand (A of the step) passes through one L2 only, instead of through all
+    // eight when every XCD holds a band of every step's tiles.
+    const bool by_xcd = PERSIST && P.xcd_steps;
+    const int item_stride = by_xcd ? (int)(gridDim.x >> 3) : (int)gridDim.x;
+    const int n_items = PERSIST ? tiles_per_step * (by_xcd ? P.n_steps >> 3 : P.n_steps) : 0;
+    int item = by_xcd ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;
     do {
     // Lane and wave indices are taken anew for every work item: what is derived from them then lives
     // from its first use in this item, not across the whole loop.
@@ -198,7 +203,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WGM, wn = wave / WGM;
-    const int step_i = PERSIST ? item / tiles_per_step : 0;
+    const int step_i = PERSIST ? (by_xcd ? (int)(blockIdx.x & 7) + 8 * (item / tiles_per_step) : item / tiles_per_step) : 0;
     const void *const cA = PERSIST ? P.A_step[step_i] : P.A;
     const float *const cRecv = PERSIST ? P.recv_step[step_i] : P.recv;
     void *const cOut = PERSIST ? P.out_step[step_i] : P.out;
@@ -206,7 +211,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
 
     // Work item = (output tile, k-split); the splits of a tile are neighbours in the remapped order.
     const int splits = P.splits;
-    const int work = xcd_remap(PERSIST ? item % tiles_per_step : (int)blockIdx.x, tiles_per_step);
+    const int work = by_xcd ? item % tiles_per_step
+                            : xcd_remap(PERSIST ? item % tiles_per_step : (int)blockIdx.x, tiles_per_step);
     const int tile = work / splits, split = work % splits;
     const int m0 = (tile % tiles_m) * BM;
     const int n0 = (tile / tiles_m) * BN;
@@ -748,7 +754,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     }
     if constexpr (PERSIST)
         __syncthreads();                             // every wave is done with the LDS stages
-    item += gridDim.x;
+    item += item_stride;
     } while (PERSIST && item < n_items);             // next work item
 }
 
@@ -761,6 +767,9 @@ hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t
         constexpr int per_cu = (NS * (BM + BN) * 64 * 2 <= 80 * 1024) ? 2 : 1;
         const int items = tiles_m * tiles_n * p.n_steps;
         wgs = items < p.num_cu * per_cu ? items : p.num_cu * per_cu;
+        if (p.xcd_steps)                             // whole octets of workgroups: the same number per XCD
+            wgs = (tiles_m * tiles_n * (p.n_steps / 8) < p.num_cu * per_cu / 8 ? tiles_m * tiles_n * (p.n_steps / 8)
+                                                                              : p.num_cu * per_cu / 8) * 8;
     }
     const dim3 grid(wgs), block(64 * WGM * WGN);
     if (p.n_steps > 0) {                             // persistent rank step: fp32 or bf16 output, either weight order
@@ -823,6 +832,8 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
         p.splits = 1;
         p.cp_wgs = 0;
         p.cp_bytes = 0;
+        const char *e = getenv("COMMFUSE_XCD_STEPS");  // tuning override: 0 = every XCD takes a band of every step
+        p.xcd_steps = p.n_steps % 8 == 0 && p.num_cu % 8 == 0 && !(e != nullptr && atoi(e) == 0);
     }
     if (p.splits > 1 && (p.ws == nullptr || p.counters == nullptr ||
                          (size_t)p.splits * p.M * p.N * sizeof(float) > p.ws_bytes || tiles > p.max_tiles ||

@@ -225,7 +225,8 @@ class WgradRun:
     hand at step ``i`` (own slice first, then the deliveries), ``local`` the rank's full operand.
     ``moving_is_left``: all-gather layer (dW += moving^T local[l]), else reduce-scatter layer."""
 
-    def __init__(self, p, rank, m_chunk, k, n, moving, local, moving_is_left, with_sink=False, m=1, each=False):
+    def __init__(self, p, rank, m_chunk, k, n, moving, local, moving_is_left, with_sink=False, m=1, each=False,
+                 gathered=False):
         self.p, self.rank, self.m, self.mc, self.k, self.n = p, rank, m, m_chunk, k, n
         self.left_moves = moving_is_left
         self.kind = cf.CF_KIND_WGRAD_X if moving_is_left else cf.CF_KIND_WGRAD_G
@@ -239,6 +240,13 @@ class WgradRun:
         self.dW = torch.full((k, n), float("nan"), dtype=torch.float32, device=DEV)
         self.sink = [mk() for _ in range(p - 1)] if with_sink else None
         self.each = [mk() for _ in range(p - 1)] if each else None
+        if gathered:
+            # one [p*m_chunk x width] buffer: the own slice in row block `rank`, hop i lands in row block (rank - i) mod p
+            self.gathered = torch.full((p * m_chunk, width), float("nan"), dtype=torch.bfloat16, device=DEV)
+            blk = lambda c: self.gathered[c * m_chunk:(c + 1) * m_chunk]
+            blk(rank).copy_(self.own)
+            self.own = blk(rank)
+            self.each = [blk((rank - i) % p) for i in range(1, p)]
         self.bufs = cf.make_buffers(self.own, self.local, self.dW, self.stage, self.slot, (None, None), self.sink, self.each)
         self.cs = torch.cuda.Stream()
         self.xs = torch.cuda.Stream()

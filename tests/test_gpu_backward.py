@@ -130,6 +130,44 @@ def test_wgrad_reduced(shape, left_moves, tile):
                 assert np.array_equal(H.to_host_f64(run.sink[i]), mv[i][1]), f"flags {flags} hop {i}"
 
 
+@pytest.mark.parametrize("m", [1, 2])
+@pytest.mark.parametrize("left_moves", [True, False])
+@pytest.mark.parametrize("shape", [(4, 72, 136, 200), (8, 128, 264, 136), (2, 264, 64, 328)])
+def test_wgrad_persistent_is_one_gemm_over_the_gathered_operand(shape, left_moves, m):
+    """CF_PERSISTENT for the weight gradient: the landing buffers form one gathered buffer, and the p chunk
+    GEMMs become one GEMM over all its rows (other summation order: a tolerance, bit-exact on integers)."""
+    p, mc, k, n = shape
+    rng = np.random.default_rng(140 + p + (1 if left_moves else 0))
+    width_mv, width_loc = (k, n) if left_moves else (n, k)
+    PS = cf.CF_PERSISTENT | cf.CF_SERIAL
+    for integer in (False, True):
+        mv = [_bf16(rng, (mc, width_mv), 0.5, integer) for _ in range(p)]
+        loc_b, loc = _bf16(rng, (p * mc, width_loc), 0.5, integer)
+        for rank in (0, p - 1, p // 2):
+            ref = oracle.wgrad_rank_steps([x[1] for x in mv], loc, p, rank, left_moves)[-1]
+            run = H.WgradRun(p, rank, mc, k, n, [x[0] for x in mv], loc_b, left_moves, m=m, gathered=True)
+            with H.Workspace(run.desc, run.kind):
+                for flags in (PS, PS | cf.CF_GRAPH, PS | cf.CF_POISON, 0, cf.CF_DEVICE_WAIT):   # the layout serves every mode
+                    run.dW.fill_(float("nan"))
+                    run.run_schedule(flags)
+                    run.run_schedule(flags)
+                    cf.device_status(run.cs)
+                    got = H.to_host_f64(run.dW)
+                    if integer:
+                        assert np.array_equal(got, ref), f"rank {rank} flags {flags}"
+                    else:
+                        assert H.rel_err(got, ref) <= TIGHT_BF16, f"rank {rank} flags {flags}"
+            # every hop landed in its row block
+            for i in range(1, p):
+                c = (rank - i) % p
+                assert np.array_equal(H.to_host_f64(run.gathered[c * mc:(c + 1) * mc]), mv[i][1])
+    # separate landing buffers are not the gathered layout
+    run = H.WgradRun(p, 0, mc, k, n, [x[0] for x in mv], loc_b, left_moves, each=True)
+    with pytest.raises(cf.CommFuseError) as ei:
+        run.run_schedule(PS)
+    assert ei.value.status == cf.CF_ERR_UNSUPPORTED
+
+
 def test_wgrad_integer_inputs_are_bit_exact_and_granularity_changes_nothing_but_the_order():
     p, mc, k, n = 4, 128, 136, 264
     rng = np.random.default_rng(111)
