@@ -263,8 +263,8 @@ enum {
                             extra workgroups of step i's kernel launch instead of a
                             hipMemcpyAsync on copy_stream: one stream, no events
                             (copy_stream is unused; not with CF_POISON)               */
-    CF_PERSISTENT = 128u,/* bf16 CF_KIND_RS / CF_KIND_AG only, at most 16 (sub-)steps: ONE kernel launch
-                            runs all steps of the rank step.  Its work items (step, output tile) are
+    CF_PERSISTENT = 128u,/* bf16 CF_KIND_RS / CF_KIND_AG / CF_KIND_WGRAD_*, at most 16 (sub-)steps: ONE kernel
+                            launch runs all steps of the rank step.  Its work items (step, output tile) are
                             dealt out step-major to a grid that fills the chip once; tiles of different
                             steps run side by side (the chunk GEMMs do not depend on each other -- only
                             the add of B_in / the arrival of the slice does), nothing is launched or
@@ -276,6 +276,13 @@ enum {
                             concurrent blit copies.  (The kernel can also wait for per-step delivery
                             flags on the device; on a real ring, where a delivery is a remote DMA
                             write that needs no compute unit here, that is how it would overlap.)
+                            Weight-gradient kinds: recv_each must be in GATHERED order -- with
+                            blk = m_chunk rows of the moving operand, the own slice is row block `rank`
+                            of one buffer and recv_each[i-1] its row block (rank - i) mod p (the block
+                            the local operand pairs hop i with); else CF_ERR_UNSUPPORTED.  The p chunk
+                            GEMMs dW += slice^T local_slice are then one GEMM whose contraction runs
+                            over all p*m_chunk rows: dW is written once, not read and written p times
+                            (the sum runs in row-block order, not in step order).
                             Not with CF_FUSED_COPY / CF_DEVICE_WAIT.                                   */
     CF_DEVICE_WAIT = 64u /* bf16 RS / AG only, needs a registered workspace: the compute
                             stream does not wait for the copy stream between steps;
