@@ -601,20 +601,24 @@ def _sample_rows(mc, rng, extra=6):
     return sorted(fixed)
 
 
-@pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_GRAPH, cf.CF_DEVICE_WAIT])
+PERSISTENT_SERIAL = cf.CF_PERSISTENT | cf.CF_SERIAL       # the mode the benchmark's best times come from
+
+
+@pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_GRAPH, cf.CF_DEVICE_WAIT, PERSISTENT_SERIAL])
 @pytest.mark.parametrize("name", ["c2_rs_7b", "c4_rs_70b_down"])
 def test_full_size_rs(name, flags):
     w = inputs.CONFIGS[name]
     data = inputs.make_rs(w)
     rank = 0
-    run = H.RsRun(w, data, rank, with_sink=True)
+    persistent = bool(flags & cf.CF_PERSISTENT)      # no sinks there: only the last step's output stays
+    run = H.RsRun(w, data, rank, each=True) if persistent else H.RsRun(w, data, rank, with_sink=True)
     with H.Workspace(run.desc, cf.CF_KIND_RS):          # as the benchmark runs it
         run.run_schedule(flags)
         cf.device_status(run.cs)
     A64 = None
     W64 = inputs.as_f64(data["W"], w.dtype)
     rng = np.random.default_rng(1)
-    for i in range(w.p):
+    for i in range(w.p - 1 if persistent else 0, w.p):
         l = (rank - i - 1) % w.p
         rows = _sample_rows(w.m_chunk, rng)
         Arows = inputs.as_f64(data["A"][[l * w.m_chunk + r for r in rows]], w.dtype)
@@ -627,13 +631,13 @@ def test_full_size_rs(name, flags):
         assert e <= TOL_BF16 and e <= TIGHT_BF16, f"step {i}: {e:.3e}"
 
 
-@pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_GRAPH, cf.CF_DEVICE_WAIT])
+@pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_GRAPH, cf.CF_DEVICE_WAIT, PERSISTENT_SERIAL])
 @pytest.mark.parametrize("name", ["c3_ag_7b", "c4_ag_70b_up"])
 def test_full_size_ag(name, flags):
     w = inputs.CONFIGS[name]
     data = inputs.make_ag(w)
     rank = 0
-    run = H.AgRun(w, data, rank)
+    run = H.AgRun(w, data, rank, each=bool(flags & cf.CF_PERSISTENT))
     with H.Workspace(run.desc, cf.CF_KIND_AG):          # as the benchmark runs it (the 7B shape splits k)
         run.run_schedule(flags)
         cf.device_status(run.cs)
@@ -651,18 +655,22 @@ def test_full_size_ag(name, flags):
         assert e <= gate and e <= tight, f"step {i}: {e:.3e}"
 
 
-def test_full_size_pair_70b():
-    """AG-GEMM (up) writes H in bf16; GEMM-RS (down) consumes it.  No activation between."""
+@pytest.mark.parametrize("flags", [0, PERSISTENT_SERIAL])
+def test_full_size_pair_70b(flags):
+    """AG-GEMM (up) writes H in bf16; GEMM-RS (down) consumes it.  No activation between.  Set up as the
+    benchmark sets it up (a landing buffer per hop, one compute stream for both layers)."""
     up, dn = inputs.CONFIGS["c4_ag_70b_up"], inputs.CONFIGS["c4_rs_70b_down"]
     dup, ddn = inputs.make_ag(up), inputs.make_rs(dn)
     rank = 0
-    ag = H.AgRun(up, dup, rank)
-    ag.run_schedule(0)
-    ddn_dev = dict(ddn)
-    rs = H.RsRun(dn, ddn, rank)
+    ag = H.AgRun(up, dup, rank, each=True)
+    rs = H.RsRun(dn, ddn, rank, each=True)
     rs.A = ag.O                                            # hand H over on the device
-    rs.bufs = cf.make_buffers(rs.A, rs.W, rs.O, rs.stage, rs.slot, rs.send, None)
-    rs.run_schedule(0)
+    rs.bufs = cf.make_buffers(rs.A, rs.W, rs.O, rs.stage, rs.slot, rs.send, None, rs.each)
+    rs.cs, rs.xs = ag.cs, ag.xs
+    for _ in range(2):                                     # back to back, as in the timed loop
+        cf.run_schedule(ag.desc, cf.CF_KIND_AG, ag.bufs, ag.cs, ag.xs, flags)
+        cf.run_schedule(rs.desc, cf.CF_KIND_RS, rs.bufs, rs.cs, rs.xs, flags)
+    rs.cs.synchronize()
     got = H.to_host_f64(rs.O)
     # oracle on sampled rows of the final slice (slice `rank`, computed last)
     rng = np.random.default_rng(3)
