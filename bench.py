@@ -90,7 +90,9 @@ def main() -> int:
         out = {}
         for name, fl in (("overlapped", 0), ("compute_only", cf.CF_NO_COPY), ("copy_only", cf.CF_NO_COMPUTE)):
             best = None
-            for mode, extra in MODES if (kind in (cf.CF_KIND_RS, cf.CF_KIND_AG) and (fl == 0 or "persistent" in mode or mode in BASIC_NAMES)) else BASIC:
+            pers_pair = kind == cf.CF_KIND_RS_PAIR and getattr(run, "each", None) is not None
+            for mode, extra in MODES if (kind in (cf.CF_KIND_RS, cf.CF_KIND_AG) and (fl == 0 or "persistent" in mode or mode in BASIC_NAMES)) \
+                    else (BASIC + tuple(m for m in MODES if "persistent" in m[0]) if pers_pair else BASIC):
                 if fl != 0 and (extra & (cf.CF_FUSED_COPY | cf.CF_DEVICE_WAIT)):
                     continue
                 if (extra & cf.CF_PERSISTENT) and getattr(run, "each", None) is None:

@@ -263,7 +263,7 @@ enum {
                             extra workgroups of step i's kernel launch instead of a
                             hipMemcpyAsync on copy_stream: one stream, no events
                             (copy_stream is unused; not with CF_POISON)               */
-    CF_PERSISTENT = 128u,/* bf16 CF_KIND_RS / CF_KIND_AG / CF_KIND_WGRAD_*, at most 16 (sub-)steps: ONE kernel
+    CF_PERSISTENT = 128u,/* bf16 CF_KIND_RS / CF_KIND_AG / CF_KIND_RS_PAIR / CF_KIND_WGRAD_*, at most 16 (sub-)steps: ONE kernel
                             launch runs all steps of the rank step.  Its work items (step, output tile) are
                             dealt out step-major to a grid that fills the chip once; tiles of different
                             steps run side by side (the chunk GEMMs do not depend on each other -- only
@@ -276,6 +276,8 @@ enum {
                             concurrent blit copies.  (The kernel can also wait for per-step delivery
                             flags on the device; on a real ring, where a delivery is a remote DMA
                             write that needs no compute unit here, that is how it would overlap.)
+                            CF_KIND_RS_PAIR: every arrival is kept (recv_each) and the last step adds
+                            them all, as commfuse_rs_pair_last_step does.
                             Weight-gradient kinds: recv_each must be in GATHERED order -- with
                             blk = m_chunk rows of the moving operand, the own slice is row block `rank`
                             of one buffer and recv_each[i-1] its row block (rank - i) mod p (the block

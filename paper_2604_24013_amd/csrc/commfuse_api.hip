@@ -793,7 +793,7 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
     const bool do_copy = !(flags & CF_NO_COPY) && p > 1;
     const bool do_compute = !(flags & CF_NO_COMPUTE);
     const bool poison = (flags & CF_POISON) != 0;
-    const size_t slot_bytes = kind == CF_KIND_RS       ? (size_t)r.mc * r.ldo * sizeof(float)
+    const size_t slot_bytes = is_rs_kind(kind)         ? (size_t)r.mc * r.ldo * sizeof(float)
                               : kind == CF_KIND_WGRAD_G ? (size_t)r.mc * r.ldw * in_elem(r)
                                                         : (size_t)r.mc * r.lda * in_elem(r);
     // Weight gradient: the moving operand must sit in "gathered" order -- one [p*m_chunk x width] buffer, the
@@ -844,6 +844,20 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
         gp.n_steps = S;
         gp.num_cu = num_cu_of_current_device();
         for (int j = 0; j < S; ++j) {
+            if (kind == CF_KIND_RS_PAIR) {
+                // Appendix A(a) with deferred aggregation: steps 0..p-2 are plain chunk GEMMs for the partners'
+                // slices, the last step adds every arrival to the product for the own slice (m = 1 here)
+                const bool last = j == p - 1;
+                gp.A_step[j] = static_cast<const char *>(b->A_or_own_shard) +
+                               (size_t)pair_slice(p, r.rank, j) * r.mc * r.lda * in_elem(r);
+                gp.recv_step[j] = last && p > 1 ? static_cast<const float *>(b->recv_each[0]) : nullptr;
+                gp.out_step[j] = last ? b->O : static_cast<void *>(b->send_slot[j & 1]);
+                gp.flag_step[j] = nullptr;
+                if (last)
+                    for (int t = 1; t < p - 1; ++t)
+                        gp.recv_more[gp.n_recv_more++] = static_cast<const float *>(b->recv_each[t]);
+                continue;
+            }
             const int c = subslice_index(kind, p, m, r.rank, j);
             if (kind == CF_KIND_RS) {
                 gp.A_step[j] = static_cast<const char *>(b->A_or_own_shard) + (size_t)c * r.mc * r.lda * in_elem(r);
@@ -950,10 +964,11 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
         if (flags & (CF_FUSED_COPY | CF_DEVICE_WAIT))
             return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT excludes CF_FUSED_COPY and CF_DEVICE_WAIT");
         const bool ok_kind = is_wgrad_kind(kind) ? wgrad_can_carry_copy(r)
-                                                 : (kind == CF_KIND_RS || kind == CF_KIND_AG) && step_can_carry_copy(r);
+                                                 : (kind == CF_KIND_RS || kind == CF_KIND_AG || kind == CF_KIND_RS_PAIR) &&
+                                                       step_can_carry_copy(r) && r.p - 2 <= cf::GemmParams::MAX_RECV_MORE;
         if (!ok_kind || attn != nullptr || r.p * r.m > cf::GemmParams::MAX_STEPS)
             return fail(CF_ERR_UNSUPPORTED,
-                        "CF_PERSISTENT needs kind RS, AG or a weight-gradient kind, bf16 operands and at most %d (sub-)steps",
+                        "CF_PERSISTENT needs kind RS, AG, RS_PAIR or a weight-gradient kind, bf16 operands and at most %d (sub-)steps",
                         cf::GemmParams::MAX_STEPS);
         if (bufs != nullptr && bufs->peer_sink != nullptr)
             return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT cannot feed peer_sink (nothing signals a finished step)");

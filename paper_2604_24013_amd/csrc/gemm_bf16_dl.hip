@@ -208,6 +208,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     const float *const cRecv = PERSIST ? P.recv_step[step_i] : P.recv;
     void *const cOut = PERSIST ? P.out_step[step_i] : P.out;
     const unsigned *const cFlag = PERSIST ? P.flag_step[step_i] : P.wait_flag;
+    // further received partials (GemmParams::recv_more): in a persistent launch they belong to the last step only
+    const int n_more = (!PERSIST || step_i == P.n_steps - 1) ? P.n_recv_more : 0;
 
     // Work item = (output tile, k-split); the splits of a tile are neighbours in the remapped order.
     const int splits = P.splits;
@@ -489,7 +491,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     __amdgpu_buffer_rsrc_t r_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(cRecv), 0, cRecv != nullptr ? (int)r_bytes : 0, 0x00020000);
     const int pf_at = nk - 1 - P.pf_lead;             // iteration after whose tile loads the prefetch is issued
-    const bool pf_on = PF && cRecv != nullptr && splits == 1 && P.n_recv_more == 0 && P.pf_lead > 0 && pf_at >= 0;
+    const bool pf_on = PF && cRecv != nullptr && splits == 1 && n_more == 0 && P.pf_lead > 0 && pf_at >= 0;
     f32x4_t pre[PF ? TM : 1][PF ? TN : 1][4];
     constexpr int COHERENT_LD = 1 | 16;               // buffer cache-policy bits sc0 | sc1
     auto prefetch_recv = [&](auto aux_tag) {
@@ -711,7 +713,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                                    : __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, boff, 0, 0));
                 }
             // further received partials, summed in index order: one batch of independent loads per buffer
-            for (int b = 0; b < P.n_recv_more; ++b) {
+            for (int b = 0; b < n_more; ++b) {
                 __amdgpu_buffer_rsrc_t m_rsrc = __builtin_amdgcn_make_buffer_rsrc(
                     const_cast<float *>(P.recv_more[b]), 0, (int)r_bytes, 0x00020000);
                 f32x4_t tv[TN][4];
@@ -833,7 +835,9 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
         p.cp_wgs = 0;
         p.cp_bytes = 0;
         const char *e = getenv("COMMFUSE_XCD_STEPS");  // tuning override: 0 = every XCD takes a band of every step
-        p.xcd_steps = p.n_steps % 8 == 0 && p.num_cu % 8 == 0 && !(e != nullptr && atoi(e) == 0);
+        // (not when one step carries the sum of several received partials: that step's epilogue is heavy and
+        // would fall on one XCD)
+        p.xcd_steps = p.n_steps % 8 == 0 && p.num_cu % 8 == 0 && p.n_recv_more == 0 && !(e != nullptr && atoi(e) == 0);
     }
     if (p.splits > 1 && (p.ws == nullptr || p.counters == nullptr ||
                          (size_t)p.splits * p.M * p.N * sizeof(float) > p.ws_bytes || tiles > p.max_tiles ||

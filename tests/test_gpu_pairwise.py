@@ -77,6 +77,15 @@ def test_rs_pair_reduced(shape, layout, dtype):
                 assert np.array_equal(H.to_host_f64(r_.O), outs[-1]), f"rank {rank} flags {flags}"
                 for i in range(p - 1):
                     assert np.array_equal(H.to_host_f64(r_.sink[i]), outs[i]), f"rank {rank} flags {flags} sink {i}"
+        if dtype == "bf16":
+            # all steps in one launch: the same GEMMs and the same additions in the same order
+            pers = H.RsPairRun(w, data, rank, layout, keep_all=True)
+            PS = cf.CF_PERSISTENT | cf.CF_SERIAL
+            for flags in (PS, PS | cf.CF_GRAPH, PS | cf.CF_POISON):
+                pers.O.fill_(float("nan"))
+                pers.run_schedule(flags)
+                pers.run_schedule(flags)
+                assert np.array_equal(H.to_host_f64(pers.O), outs[-1]), f"rank {rank} flags {flags} (persistent)"
 
 
 def test_rs_pair_deferred_with_the_staged_kernel():
@@ -163,18 +172,21 @@ def _sample_rows(mc, rng, extra=6):
 
 
 @pytest.mark.parametrize("keep_all", [False, True])
-@pytest.mark.parametrize("flags", [0, cf.CF_GRAPH])
+@pytest.mark.parametrize("flags", [0, cf.CF_GRAPH, cf.CF_PERSISTENT | cf.CF_SERIAL])
 @pytest.mark.parametrize("name", ["c2_rs_7b", "c4_rs_70b_down"])
 def test_full_size_rs_pair(name, flags, keep_all):
     w = inputs.CONFIGS[name]
     data = inputs.make_rs(w, salt=12)
     rank = 5
-    run = H.RsPairRun(w, data, rank, with_sink=True, keep_all=keep_all)
+    persistent = bool(flags & cf.CF_PERSISTENT)      # deferred aggregation only, no sinks: the last output stays
+    if persistent and not keep_all:
+        pytest.skip("the persistent launch keeps every arrival (recv_each)")
+    run = H.RsPairRun(w, data, rank, with_sink=not persistent, keep_all=keep_all)
     with H.Workspace(run.desc, cf.CF_KIND_RS_PAIR):       # as the benchmark runs it
         run.run_schedule(flags)
     W64 = inputs.as_f64(data["W"], w.dtype)
     rng = np.random.default_rng(2)
-    for i in range(w.p):
+    for i in range(w.p - 1 if persistent else 0, w.p):
         l = oracle.slice_index_pair(w.p, rank, i)
         rows = _sample_rows(w.m_chunk, rng)
         Arows = inputs.as_f64(data["A"][[l * w.m_chunk + r for r in rows]], w.dtype)
