@@ -327,7 +327,7 @@ def main() -> int:
         Qa, Ka, Va = (bf16_dev((Ba, ha, Sa, 128), 1.0) for _ in range(3))
         Woa = bf16_dev((ha * 128, Da), 0.01)
         adesc = cf.attn_desc(pa, 0, Ba, ha, Sa, 128, Da, 1.0 / 128 ** 0.5)
-        attn_out = torch.empty((mca, ha * 128), dtype=torch.bfloat16, device=H.DEV)
+        attn_out = torch.empty((pa * mca, ha * 128), dtype=torch.bfloat16, device=H.DEV)   # all p slices (persistent mode)
         mk32 = lambda: torch.empty((mca, Da), dtype=torch.float32, device=H.DEV)
         stage_a = [mk32().normal_() for _ in range(pa - 1)]
         keep = [mk32(), [mk32(), mk32()], [mk32(), mk32()], [mk32() for _ in range(pa - 1)]]
@@ -338,8 +338,6 @@ def main() -> int:
         fl_proj = 2.0 * mca * Da * ha * 128
         best = None
         for mode, extra in MODES:
-            if extra & cf.CF_PERSISTENT:
-                continue                                  # the attention steps are two kernels each
             t = time_calls(lambda: cf.run_attn_schedule(adesc, abufs, cs, xs, extra), cs, max(K, 30), W)
             if best is None or t < best[0]:
                 best = (t, mode)

@@ -358,7 +358,9 @@ cf_status commfuse_attn_rs_step(const cf_attn_desc *desc, int step, const void *
  * delivery / sending fields mean what they mean in cf_buffers for CF_KIND_RS. */
 typedef struct {
     const void *Q, *K, *V, *Wo;
-    void *attn_out;
+    void *attn_out;                 /* one slice's attention output [batch*seq/p x heads*head_dim] bf16; with
+                                       CF_PERSISTENT p times that: the outputs of all p slices, slice l in row
+                                       block l                                                               */
     float *O;                       /* O^r [batch*seq/p x n] fp32 */
     const void *const *peer_stage;
     void *slot[2];
@@ -367,7 +369,10 @@ typedef struct {
     void *const *recv_each;
 } cf_attn_buffers;
 
-/* A whole rank step of Alg. 4 with the overlap and the flags of commfuse_run_schedule. */
+/* A whole rank step of Alg. 4 with the overlap and the flags of commfuse_run_schedule.
+ * CF_PERSISTENT (with CF_SERIAL and recv_each, m = 1): the deliveries, then the attention of ALL p query slices
+ * in one launch (a slice's attention depends on nothing that travels; the grid then fills the chip without a
+ * key split), then the projections with their B_in adds as one persistent launch over attn_out. */
 cf_status commfuse_run_attn_schedule(const cf_attn_desc *desc, const cf_attn_buffers *bufs, void *compute_stream,
                                      void *copy_stream, uint32_t flags);
 

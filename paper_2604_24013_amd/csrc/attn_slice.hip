@@ -92,10 +92,11 @@ __global__ __launch_bounds__(64 * NW) void attn_slice_kernel(AttnParams P)
     const int qblocks = (P.c + BQ - 1) / BQ;
     const int KSP = P.ksplit;                                        // workgroups sharing a query block
     const int split = blockIdx.x % KSP;
-    const int group = blockIdx.x / KSP;                              // (batch element, head, query block)
+    const int group = blockIdx.x / KSP;                              // (slice, batch element, head, query block)
     const int qb = group % qblocks;
     const int head = (group / qblocks) % P.heads;
-    const int b = group / (qblocks * P.heads);
+    const int b = (group / (qblocks * P.heads)) % P.batch;
+    const int slice = P.l + group / (qblocks * P.heads * P.batch);
     const int S = P.S;
 
     const size_t mat = (size_t)S * DH;                               // elements of one (b, head) matrix
@@ -114,7 +115,7 @@ __global__ __launch_bounds__(64 * NW) void attn_slice_kernel(AttnParams P)
     for (int t = 0; t < QT; ++t) {
         const int qi = q_in_slice + t * 32 + lq;
         const bool ok = qi < P.c;
-        const __bf16 *qrow = Qm + (size_t)(P.l * P.c + (ok ? qi : 0)) * DH;
+        const __bf16 *qrow = Qm + (size_t)(slice * P.c + (ok ? qi : 0)) * DH;
 #pragma unroll
         for (int ks = 0; ks < DS; ++ks) {
             bf16x8_t v = *reinterpret_cast<const bf16x8_t *>(qrow + ks * 16 + lh * 8);
@@ -163,12 +164,19 @@ __global__ __launch_bounds__(64 * NW) void attn_slice_kernel(AttnParams P)
     for (int t = 0; t < DT; ++t)
         v_addr[t] = TILE_BYTES + v_kl * ROWB + (((t) ^ (v_kl & 3)) << 6) + v_nl * 2;
 
-    f32x16_t oacc[QT][DT];
+    f32x16_t oacc[QT][DT], lacc[QT];     // lacc: every element of a lane is the row sum l of the lane's query
     float m_run[QT], l_run[QT];
+    bf16x8_t ones;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        ones[e] = (__bf16)1.0f;
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
         m_run[t] = -INFINITY;
         l_run[t] = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            lacc[t][e] = 0.0f;
 #pragma unroll
         for (int d = 0; d < DT; ++d)
 #pragma unroll
@@ -211,48 +219,70 @@ __global__ __launch_bounds__(64 * NW) void attn_slice_kernel(AttnParams P)
             }
         }
 
-        // online softmax; register 4g+e of key tile j is key 32 j + 8 g + 4 lh + e
+        // Online softmax; register 4g+e of key tile j is key 32 j + 8 g + 4 lh + e.  The vector ALU is the
+        // busiest unit of this loop, so its work per score is kept to a max, one fused multiply-add, one exp2 and
+        // half a packed conversion:
+        //  * keys beyond the sequence are masked in the one tile that can hold them only;
+        //  * the exponentials are taken against a running reference m that is raised only when the tile's
+        //    maximum exceeds it by more than 2^RAISE (probabilities then stay below 2^RAISE: no overflow, the
+        //    same relative precision in bf16), so the rescaling of the accumulators is rare and sits in a
+        //    wave-uniform branch;
+        //  * the row sums l come out of the matrix pipe: one more MFMA per 16-key slice with an all-ones "A"
+        //    operand adds up exactly the rounded probabilities that multiply V (every row of its result is the
+        //    sum over the slice's keys, both lanes of a query get the whole sum).
+        constexpr float RAISE = 8.0f;
         bf16x8_t pf[QT][KT][2];                                      // "B" fragments of the two 16-key slices of a tile
+        const bool partial = (kt + 1) * BKV > S;                     // uniform
 #pragma unroll
         for (int t = 0; t < QT; ++t) {
+            if (partial) {
+                float ninf = -INFINITY;
+                asm volatile("" : "+v"(ninf));                       // (keeps this a branch: not 32 selects in every tile)
+#pragma unroll
+                for (int j = 0; j < KT; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = kt * BKV + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                        if (key >= S)
+                            sacc[t][j][r] = ninf;
+                    }
+            }
             float mx = -INFINITY;
 #pragma unroll
             for (int j = 0; j < KT; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = kt * BKV + j * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                    const float s = key < S ? sacc[t][j][r] * sl2 : -INFINITY;
-                    sacc[t][j][r] = s;
-                    mx = fmaxf(mx, s);
-                }
+                for (int r = 0; r < 16; ++r)
+                    mx = fmaxf(mx, sacc[t][j][r]);
             mx = fmaxf(mx, __shfl_xor(mx, 32));                      // the query's other half lives in lane ^ 32
-            const float m_new = fmaxf(m_run[t], mx);                 // finite: every tile holds at least one key
-            const float alpha = exp2f(m_run[t] - m_new);
-            float sum = 0.0f;
+            const float mxs = mx * sl2;                              // scale > 0: the maximum of the scaled scores
+            if (__builtin_amdgcn_ballot_w64(mxs > m_run[t] + RAISE) != 0) {   // finite: every tile holds a key
+                const float m_new = fmaxf(m_run[t], mxs);
+                float alpha = exp2f(m_run[t] - m_new);               // 0 on the first tile (m_run = -inf)
+                asm volatile("" : "+v"(alpha));                      // (keeps this a branch, as above)
+                m_run[t] = m_new;
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    lacc[t][e] *= alpha;
+#pragma unroll
+                for (int d = 0; d < DT; ++d)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e)
+                        oacc[t][d][e] *= alpha;
+            }
+            const float nm = -m_run[t];
 #pragma unroll
             for (int j = 0; j < KT; ++j)
 #pragma unroll
                 for (int s2 = 0; s2 < 2; ++s2) {
                     bf16x8_t f;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float p = exp2f(sacc[t][j][8 * s2 + e] - m_new);
-                        const __bf16 pb = (__bf16)p;
-                        f[e] = pb;
-                        sum += (float)pb;                            // the sum of what is actually multiplied
-                    }
+                    for (int e = 0; e < 8; ++e)
+                        f[e] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(sacc[t][j][8 * s2 + e], sl2, nm));   // bare v_exp_f32: arguments below -126 give 0
                     pf[t][j][s2] = f;
                 }
-            l_run[t] = l_run[t] * alpha + sum;
-            m_run[t] = m_new;
-#pragma unroll
-            for (int d = 0; d < DT; ++d)
-#pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    oacc[t][d][e] *= alpha;
         }
 
-        // O^T += V^T P^T
+        // O^T += V^T P^T, l += 1^T P^T
 #pragma unroll
         for (int j = 0; j < KT; ++j)
 #pragma unroll
@@ -270,11 +300,18 @@ __global__ __launch_bounds__(64 * NW) void attn_slice_kernel(AttnParams P)
                     for (int t = 0; t < QT; ++t)
                         oacc[t][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t][j][s2], oacc[t][d], 0, 0, 0);
                 }
+#pragma unroll
+                for (int t = 0; t < QT; ++t)
+                    lacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, pf[t][j][s2], lacc[t], 0, 0, 0);
             }
 
         wait_vmcnt<0>();                                             // the next tile has landed
         __syncthreads();                                             // ... for every wave, and this one is read by all
     }
+
+#pragma unroll
+    for (int t = 0; t < QT; ++t)
+        l_run[t] = lacc[t][0];                                       // the whole row sum, in both lanes of the query
 
     // Key split across workgroups: park (m, l, O) in the workspace, thread-major so that every access is a
     // coalesced 4 bytes per lane; the workgroup that arrives last merges all splits (its own included) in
@@ -332,31 +369,44 @@ __global__ __launch_bounds__(64 * NW) void attn_slice_kernel(AttnParams P)
 #pragma unroll
                 for (int e = 0; e < 16; ++e)
                     oacc[t][d][e] = 0.0f;
-            for (int sp = 0; sp < KSP; ++sp) {
-                __amdgpu_buffer_rsrc_t rs = part_rsrc(sp);
-                const float m_s = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                    rs, ((QT * DT * 16 + 2 * t) * NT + tid) * 4, 0, COHERENT));
-                const float l_s = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                    rs, ((QT * DT * 16 + 2 * t + 1) * NT + tid) * 4, 0, COHERENT));
-                const float f = exp2f(m_s - m_all);                  // every split holds at least one key tile
-                l_all += l_s * f;
+            // two splits per round: their loads (2 x 66 per lane) are in flight together, the sums stay in split order
+            for (int sp = 0; sp < KSP; sp += 2) {
+                const bool two = sp + 1 < KSP;
+                __amdgpu_buffer_rsrc_t rs0 = part_rsrc(sp), rs1 = part_rsrc(two ? sp + 1 : sp);
+                auto ld = [&](__amdgpu_buffer_rsrc_t rs, int idx) {
+                    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, (idx * NT + tid) * 4, 0, COHERENT));
+                };
+                const float m0 = ld(rs0, QT * DT * 16 + 2 * t), l0 = ld(rs0, QT * DT * 16 + 2 * t + 1);
+                const float m1 = ld(rs1, QT * DT * 16 + 2 * t), l1 = ld(rs1, QT * DT * 16 + 2 * t + 1);
+                float v0[DT][16], v1[DT][16];
 #pragma unroll
                 for (int d = 0; d < DT; ++d)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        oacc[t][d][e] += f * __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                                 rs, (((t * DT + d) * 16 + e) * NT + tid) * 4, 0, COHERENT));
+                    for (int e = 0; e < 16; ++e) {
+                        v0[d][e] = ld(rs0, (t * DT + d) * 16 + e);
+                        v1[d][e] = ld(rs1, (t * DT + d) * 16 + e);
+                    }
+                const float f0 = exp2f(m0 - m_all);                  // every split holds at least one key tile
+                const float f1 = two ? exp2f(m1 - m_all) : 0.0f;
+                l_all += l0 * f0;
+                l_all += l1 * f1;
+#pragma unroll
+                for (int d = 0; d < DT; ++d)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        oacc[t][d][e] += f0 * v0[d][e];
+                        oacc[t][d][e] += f1 * v1[d][e];
+                    }
             }
             l_run[t] = l_all;
         }
     }
 
     // O = O^T / l, rounded to bf16, written as [token x (head, d)]: the left operand of the output projection.
-    __bf16 *out = static_cast<__bf16 *>(P.out);
+    __bf16 *out = static_cast<__bf16 *>(P.out) + (size_t)(slice - P.l) * P.out_slice_stride;
 #pragma unroll
     for (int t = 0; t < QT; ++t) {
-        const float l_tot = l_run[t] + __shfl_xor(l_run[t], 32);
-        const float inv = 1.0f / l_tot;
+        const float inv = 1.0f / l_run[t];
         const int qi = q_in_slice + t * 32 + lq;
         if (qi < P.c) {
             __bf16 *orow = out + ((size_t)b * P.c + qi) * P.ldo + (size_t)head * DH;
@@ -609,8 +659,12 @@ hipError_t launch_attn_slice(const AttnParams &p_in, hipStream_t s, int num_cu)
         if (qt == 2)
             nw = 4;
     }
+    if (p.n_slices < 1)
+        p.n_slices = 1;
+    if (p.n_slices > 1)
+        wave_split = false;                            // several slices per launch: the query-block kernel only
     const int bq = nw * 32 * qt;
-    const int64_t groups = (int64_t)((p.c + bq - 1) / bq) * p.heads * p.batch;
+    const int64_t groups = (int64_t)((p.c + bq - 1) / bq) * p.heads * p.batch * p.n_slices;
     const bool small_grid = groups * 4 < (int64_t)num_cu * 3;
     p.ksplit = 1;
     if (!wave_split && qt == 1 && (small_grid || ksp > 1) && p.ws != nullptr && p.counters != nullptr) {
@@ -622,7 +676,7 @@ hipError_t launch_attn_slice(const AttnParams &p_in, hipStream_t s, int num_cu)
         if (k > 1 && need <= p.ws_bytes && groups <= p.max_groups)
             p.ksplit = k;
     }
-    if (wave_split || (small_grid && p.ksplit == 1 && qt == 1 && getenv("COMMFUSE_ATTN_QT") == nullptr)) {
+    if (wave_split || (small_grid && p.ksplit == 1 && qt == 1 && p.n_slices == 1 && getenv("COMMFUSE_ATTN_QT") == nullptr)) {
         const dim3 grid(((p.c + 31) / 32) * p.heads * p.batch), block(256);
         hipLaunchKernelGGL(attn_slice_ksplit_kernel, grid, block, 0, s, p);
         return hipGetLastError();

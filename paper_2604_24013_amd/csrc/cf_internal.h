@@ -66,6 +66,10 @@ struct AttnParams {
     int l;               // slice index: queries [l*c, (l+1)*c)
     int64_t ldo;
     float scale;
+    // several slices in one launch (the 128/256-query kernel only): slices l, l+1, ..., l+n_slices-1, the output
+    // of slice l+i starting out_slice_stride elements after that of slice l+i-1
+    int n_slices = 1;
+    int64_t out_slice_stride = 0;
     // key split across workgroups (the 128-query kernel): the key tiles are divided over `ksplit` workgroups per
     // query block, which park (m, l, unnormalised O) in the workspace; the last one to finish merges them
     int ksplit = 1;

@@ -555,10 +555,13 @@ struct AttnCtx {
     cf::AttnParams ap;     // Q, K, V, out, geometry; `l` is filled in per step
 };
 
-cf_status launch_attention(const AttnCtx &ctx, int l, hipStream_t s)
+// n_slices > 1: slices l .. l+n_slices-1 in one launch, their outputs one after the other in ctx.ap.out
+cf_status launch_attention(const AttnCtx &ctx, int l, hipStream_t s, int n_slices = 1)
 {
     cf::AttnParams ap = ctx.ap;
     ap.l = l;
+    ap.n_slices = n_slices;
+    ap.out_slice_stride = (int64_t)ap.batch * ap.c * ap.ldo;
     {
         std::lock_guard<std::mutex> lk(g_ws_mu);
         if (g_ws.ptr != nullptr && g_ws.bytes > WS_COUNTER_BYTES) {
@@ -787,7 +790,8 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
 
 // CF_PERSISTENT: all (sub-)steps of a reduce-scatter or all-gather rank step in ONE launch of the chunk-GEMM
 // kernel (its work-item loop); the deliveries are enqueued before it on the same stream.
-cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, hipStream_t cs, uint32_t flags)
+cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, hipStream_t cs, uint32_t flags,
+                             const AttnCtx *attn = nullptr)
 {
     const int p = r.p, m = r.m, S = r.p * r.m;
     const bool do_copy = !(flags & CF_NO_COPY) && p > 1;
@@ -835,6 +839,12 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
         return kind == CF_KIND_WGRAD_X ? wgrad_step_impl(all, 0, moving, b->W, static_cast<float *>(b->O), cs)
                                        : wgrad_step_impl(all, 0, b->W, moving, static_cast<float *>(b->O), cs);
     }
+    // Alg. 4: the attention of a slice depends on nothing that travels, so the attention of ALL p query slices
+    // is one launch with a chip-filling grid (no key split, no merge); its output [p slices x B*S/p x heads*D_h]
+    // is then the left operand of the persistent projection + reduce-scatter kernel, slice by slice.
+    if (do_compute && attn != nullptr && r.mc > 0)
+        if (cf_status st = launch_attention(*attn, 0, cs, p))
+            return st;
     if (do_compute && r.mc > 0 && r.n > 0) {
         if (r.k == 0)
             return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT needs k > 0");
@@ -963,10 +973,12 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
     if (flags & CF_PERSISTENT) {
         if (flags & (CF_FUSED_COPY | CF_DEVICE_WAIT))
             return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT excludes CF_FUSED_COPY and CF_DEVICE_WAIT");
+        if (attn != nullptr && r.m != 1)
+            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT with the attention layer needs m = 1");
         const bool ok_kind = is_wgrad_kind(kind) ? wgrad_can_carry_copy(r)
                                                  : (kind == CF_KIND_RS || kind == CF_KIND_AG || kind == CF_KIND_RS_PAIR) &&
                                                        step_can_carry_copy(r) && r.p - 2 <= cf::GemmParams::MAX_RECV_MORE;
-        if (!ok_kind || attn != nullptr || r.p * r.m > cf::GemmParams::MAX_STEPS)
+        if (!ok_kind || r.p * r.m > cf::GemmParams::MAX_STEPS)
             return fail(CF_ERR_UNSUPPORTED,
                         "CF_PERSISTENT needs kind RS, AG, RS_PAIR or a weight-gradient kind, bf16 operands and at most %d (sub-)steps",
                         cf::GemmParams::MAX_STEPS);
@@ -983,7 +995,7 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
     if (cf_status st = check_buffers(r, kind, bufs, flags))
         return st;
     if (!(flags & CF_GRAPH))
-        return (flags & CF_PERSISTENT) ? enqueue_persistent(r, kind, bufs, cs, flags)
+        return (flags & CF_PERSISTENT) ? enqueue_persistent(r, kind, bufs, cs, flags, attn)
                                        : enqueue_schedule(r, kind, bufs, cs, xs, flags, attn);
 
     // CF_GRAPH: the same enqueue sequence, captured once per distinct argument set.
@@ -1031,7 +1043,7 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
             return st;
         CF_HIP(hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal));
         const uint32_t fl = flags & ~(uint32_t)CF_GRAPH;
-        cf_status st = (fl & CF_PERSISTENT) ? enqueue_persistent(r, kind, bufs, cs, fl)
+        cf_status st = (fl & CF_PERSISTENT) ? enqueue_persistent(r, kind, bufs, cs, fl, attn)
                                             : enqueue_schedule(r, kind, bufs, cs, xs, fl, attn);
         hipGraph_t graph = nullptr;
         hipError_t e = hipStreamEndCapture(cs, &graph);

@@ -184,6 +184,23 @@ def test_attn_rs_steps_and_schedule(shape, layout):
                 assert e <= TOL_STEP, f"flags {flags}: {e:.3e}"
                 for i in range(p - 1):
                     assert H.rel_err(H.to_host_f64(sink[i]), ref[i]) <= TOL_STEP, f"flags {flags} sink {i}"
+        # all steps in two launches: the attention of all p slices, then the persistent projection + reduce-scatter
+        attn_all = torch.full((p * mc, h * 128), float("nan"), dtype=torch.bfloat16, device=H.DEV)
+        bufs = cf.make_attn_buffers(Qd, Kd, Vd, Wd, attn_all, O, stage, slot, send, None, each)
+        PS = cf.CF_PERSISTENT | cf.CF_SERIAL
+        for flags in (PS, PS | cf.CF_GRAPH, PS | cf.CF_POISON):
+            O.fill_(float("nan"))
+            cf.run_attn_schedule(desc, bufs, cs, xs, flags)
+            cf.run_attn_schedule(desc, bufs, cs, xs, flags)
+            cs.synchronize()
+            e = H.rel_err(H.to_host_f64(O), ref[-1])
+            assert e <= TOL_STEP, f"persistent flags {flags}: {e:.3e}"
+        # the attention outputs themselves: slice l in row block l
+        for l in (0, p - 1):
+            one = torch.empty((mc, h * 128), dtype=torch.bfloat16, device=H.DEV)
+            cf.attn_slice(desc, l, Qd, Kd, Vd, one, None)
+            torch.cuda.synchronize()
+            assert H.rel_err(H.to_host_f64(attn_all[l * mc:(l + 1) * mc]), H.to_host_f64(one)) <= 2.0 ** -7
     finally:
         torch.cuda.synchronize()
         cf.set_workspace(None)
