@@ -436,6 +436,9 @@ def test_persistent_rank_step(m, tile):
                 run.O.fill_(float("nan"))
                 with H.Workspace(run.desc, cf.CF_KIND_RS):
                     run.run_schedule(flags)
+                    for t in run.each:                     # a step that does not wait for its delivery reads NaN
+                        t.fill_(float("nan"))
+                    torch.cuda.synchronize()
                     run.run_schedule(flags)
                     cf.device_status(run.cs)
                 e = H.rel_err(H.to_host_f64(run.O), ref[-1])
@@ -667,10 +670,15 @@ def test_full_size_pair_70b(flags):
     rs.A = ag.O                                            # hand H over on the device
     rs.bufs = cf.make_buffers(rs.A, rs.W, rs.O, rs.stage, rs.slot, rs.send, None, rs.each)
     rs.cs, rs.xs = ag.cs, ag.xs
-    for _ in range(2):                                     # back to back, as in the timed loop
-        cf.run_schedule(ag.desc, cf.CF_KIND_AG, ag.bufs, ag.cs, ag.xs, flags)
-        cf.run_schedule(rs.desc, cf.CF_KIND_RS, rs.bufs, rs.cs, rs.xs, flags)
-    rs.cs.synchronize()
+    with H.Workspace(rs.desc, cf.CF_KIND_RS):
+        for _ in range(2):                                 # back to back, as in the timed loop
+            for t in ag.each + rs.each:                    # a step that does not wait for its delivery reads NaN
+                t.fill_(float("nan"))
+            torch.cuda.synchronize()
+            cf.run_schedule(ag.desc, cf.CF_KIND_AG, ag.bufs, ag.cs, ag.xs, flags)
+            cf.run_schedule(rs.desc, cf.CF_KIND_RS, rs.bufs, rs.cs, rs.xs, flags)
+        rs.cs.synchronize()
+        cf.device_status(rs.cs)
     got = H.to_host_f64(rs.O)
     # oracle on sampled rows of the final slice (slice `rank`, computed last)
     rng = np.random.default_rng(3)
