@@ -788,8 +788,12 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
     return CF_OK;
 }
 
-// CF_PERSISTENT: all (sub-)steps of a reduce-scatter or all-gather rank step in ONE launch of the chunk-GEMM
-// kernel (its work-item loop); the deliveries are enqueued before it on the same stream.
+// CF_PERSISTENT: all (sub-)steps of a rank step in ONE launch of the chunk-GEMM kernel (its work-item loop) --
+// reduce-scatter, all-gather, pairwise reduce-scatter with deferred aggregation, the projection of the attention
+// layer (after one attention launch for all slices) -- or, for the weight gradient, as one GEMM over the gathered
+// operand; the deliveries are enqueued before it on the same stream.  The steps of one launch run side by side:
+// the send slots, which consecutive steps share, end up with unspecified contents (nothing reads them here:
+// this mode takes no peer_sink).
 cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, hipStream_t cs, uint32_t flags,
                              const AttnCtx *attn = nullptr)
 {
