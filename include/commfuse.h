@@ -270,7 +270,9 @@ enum {
                             the add of B_in / the arrival of the slice does), nothing is launched or
                             drained between steps, and because a step no longer has to fill the chip
                             alone the tiles can be larger.  Needs cf_buffers.recv_each (every hop's
-                            delivery stays where it landed), no peer_sink, and CF_SERIAL: the
+                            delivery stays where it landed), no peer_sink (the send slots, which
+                            steps that now run side by side share, are left with unspecified
+                            contents), and CF_SERIAL: the
                             deliveries are enqueued before the kernel on the compute stream -- a
                             kernel that holds its compute units for the whole rank step starves
                             concurrent blit copies.  (The kernel can also wait for per-step delivery
