@@ -192,6 +192,41 @@ def main() -> int:
                                         "up_us": round(t_chunk_up * 1e3, 2), "up_tflops": round(chunk_flops / (t_chunk_up * 1e-3) / 1e12, 1)}}
     log(f"rank-step kernel down {t_kernel*1e3:.1f} us = {ach:.0f} TFLOP/s, up {t_kernel_up*1e3:.1f} us; "
         f"chunk GEMM down {t_chunk*1e3:.1f} us, up {t_chunk_up*1e3:.1f} us")
+    # comparator, same kernels: the layer pair WITHOUT the fusion ("vanilla": the collective, then / after the whole GEMM).
+    # up: all-gather first, then the GEMM over all 8192 rows -- which is what the persistent arrangement does anyway;
+    # down: the GEMM over all 8192 rows into a full fp32 partial (the same persistent kernel, no B_in adds), then the
+    # reduce-scatter: seven deliveries, each added to its slice in a pass of its own (the gradient kernel).
+    # One stream, nothing overlaps: what the paper's method starts from.
+    vanilla = None
+    if not args.only_pair:
+        H_all = ag.O                                              # [8192 x 3584] bf16, written by the up-projection
+        Y_all = torch.empty((dn.p * dn.m_chunk, dn.n), dtype=torch.float32, device=H.DEV)
+        slot32 = torch.empty((dn.m_chunk, dn.n), dtype=torch.float32, device=H.DEV)
+        blk = lambda c: H_all[c * dn.m_chunk:(c + 1) * dn.m_chunk]
+        rows = [blk((0 - i) % dn.p) for i in range(1, dn.p)]      # slice of step i where Alg. 1 expects it: no copies needed
+        d_whole = cf.layer_desc(dn.p, 0, dn.m_chunk, dn.n, dn.k, "bf16", "f32")
+        b_whole = cf.make_buffers(blk(0), rs.W, Y_all, rows, (None, None), (None, None), None, rows)
+        chunk_elems = dn.m_chunk * dn.n
+        PS_ = cf.CF_PERSISTENT | cf.CF_SERIAL
+
+        def vanilla_up():
+            cf.run_schedule(ag.desc, cf.CF_KIND_AG, ag.bufs, ag.cs, ag.xs, PS_)
+
+        def vanilla_down():
+            cf.run_schedule(d_whole, cf.CF_KIND_AG, b_whole, ag.cs, ag.xs, PS_ | cf.CF_NO_COPY)
+            for i in range(1, dn.p):
+                with torch.cuda.stream(ag.cs):
+                    slot32.copy_(rs.stage[i - 1], non_blocking=True)
+                cf.dp_reduce_step(dn.p, 0, i, Y_all, chunk_elems, slot32, ag.cs)
+
+        t_vu = time_calls(vanilla_up, ag.cs, K, W)
+        t_vd = time_calls(vanilla_down, ag.cs, K, W)
+        t_vp = time_calls(lambda: (vanilla_up(), vanilla_down()), ag.cs, K, W)
+        vanilla = {"us_up_gather_then_gemm": round(t_vu * 1e3, 1), "us_down_gemm_then_reduce_scatter": round(t_vd * 1e3, 1),
+                   "us_pair": round(t_vp * 1e3, 1), "tflops_pair": round(flops_pair / (t_vp * 1e-3) / 1e12, 1),
+                   "vanilla_over_fused": round(t_vp / ms_step, 3)}
+        log("vanilla", vanilla)
+        del Y_all, slot32, b_whole, rows
     del ag, rs, ddn
     torch.cuda.empty_cache()
 
@@ -416,6 +451,7 @@ def main() -> int:
         "overlap_eff": round(max(pair_t["compute_only"][0], pair_t["copy_only"][0]) / ms_step, 3),
         "ms_compute_only": round(pair_t["compute_only"][0], 4), "ms_copy_only": round(pair_t["copy_only"][0], 4),
         "roofline": roofline, "cpu_baseline": cpu, "dp_reduce": dp, "other_configs": others,
+        "vanilla_comparator": vanilla,
         "pairwise_schedule": pairwise, "slicing_granularity": granularity, "backward_pass": backward, "query_split_attention": attention,
     }
     print(json.dumps(line), flush=True)
