@@ -102,6 +102,10 @@ hipError_t launch_attn_slice(const AttnParams &p, hipStream_t s, int num_cu);
 
 // dst[e] += src[e], e in [0, n)
 hipError_t launch_dp_reduce(float *dst, const float *src, int64_t n, hipStream_t s, int num_cu);
+// n (<= 16) copies of `bytes` bytes each in one launch; copy_batch_takes says whether the arguments qualify
+// (16-byte aligned pointers, bytes a multiple of 16), else the caller copies one by one
+bool copy_batch_takes(const void *const *src, void *const *dst, int n, size_t bytes);
+hipError_t launch_copy_batch(const void *const *src, void *const *dst, int n, size_t bytes, hipStream_t s);
 
 // Writes `value` to each of dst[0..count) with device-coherent stores (flags polled by other kernels).
 hipError_t launch_set_words(unsigned *dst, int count, unsigned value, hipStream_t s);

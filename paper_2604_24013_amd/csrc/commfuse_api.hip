@@ -824,6 +824,15 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
         return static_cast<char *>(b->recv_each[j / m - 1]) + (size_t)(j % m) * slot_bytes;
     };
     if (do_copy && slot_bytes > 0) {
+        // all deliveries of the rank step are due now: one batched copy launch where the buffers allow it
+        // (at most 16 hops of 16-byte-aligned whole hop buffers), else one hipMemcpyAsync per (sub-)step
+        const void *srcs[cf::GemmParams::MAX_STEPS];
+        void *dsts[cf::GemmParams::MAX_STEPS];
+        for (int i = 1; i < p; ++i) {
+            srcs[i - 1] = b->peer_stage[i - 1];
+            dsts[i - 1] = b->recv_each[i - 1];
+        }
+        const bool batched = cf::copy_batch_takes(srcs, dsts, p - 1, slot_bytes * m);
         for (int j = m; j < S; ++j) {
             void *dst = landing(j);
             if (poison) {
@@ -832,7 +841,13 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
                     return fail_hip(e, "poison fill");
             }
             const char *src = static_cast<const char *>(b->peer_stage[j / m - 1]) + (size_t)(j % m) * slot_bytes;
-            CF_HIP(hipMemcpyAsync(dst, src, slot_bytes, hipMemcpyDeviceToDevice, cs));
+            if (!batched)
+                CF_HIP(hipMemcpyAsync(dst, src, slot_bytes, hipMemcpyDeviceToDevice, cs));
+        }
+        if (batched) {
+            hipError_t e = cf::launch_copy_batch(srcs, dsts, p - 1, slot_bytes * m, cs);
+            if (e != hipSuccess)
+                return fail_hip(e, "delivery copy launch");
         }
     }
     if (do_compute && is_wgrad_kind(kind)) {

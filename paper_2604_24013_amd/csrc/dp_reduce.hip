@@ -43,6 +43,32 @@ __global__ __launch_bounds__(DP_THREADS) void dp_reduce_scalar_kernel(float *__r
         dst[i] = src[i] + dst[i];
 }
 
+// Several equally long device-to-device copies in ONE launch (the deliveries of a whole rank step when they are
+// all enqueued in front of the persistent kernel): workgroup b moves chunk b % per_buf of buffer b / per_buf,
+// 16 bytes per lane and access, four independent vectors in flight, non-temporal both ways like the reduce above.
+struct CopyBatch {
+    static constexpr int MAX = 16;
+    const void *src[MAX];
+    void *dst[MAX];
+};
+
+__global__ __launch_bounds__(DP_THREADS) void copy_batch_kernel(CopyBatch cb, int64_t n16, int per_buf)
+{
+    const int buf = blockIdx.x / per_buf, chunk = blockIdx.x % per_buf;
+    const f32x4_t *__restrict__ src = static_cast<const f32x4_t *>(cb.src[buf]);
+    f32x4_t *__restrict__ dst = static_cast<f32x4_t *>(cb.dst[buf]);
+    const int64_t base = (int64_t)chunk * DP_THREADS * DP_UNROLL + threadIdx.x;
+    f32x4_t v[DP_UNROLL];
+#pragma unroll
+    for (int u = 0; u < DP_UNROLL; ++u)
+        if (base + u * DP_THREADS < n16)
+            v[u] = __builtin_nontemporal_load(&src[base + u * DP_THREADS]);
+#pragma unroll
+    for (int u = 0; u < DP_UNROLL; ++u)
+        if (base + u * DP_THREADS < n16)
+            __builtin_nontemporal_store(v[u], &dst[base + u * DP_THREADS]);
+}
+
 __global__ __launch_bounds__(64) void set_words_kernel(unsigned *dst, int count, unsigned value)
 {
     for (int i = threadIdx.x; i < count; i += 64)
@@ -87,6 +113,32 @@ hipError_t launch_dp_reduce(float *dst, const float *src, int64_t n, hipStream_t
         return hipGetLastError();
     }
     return hipSuccess;
+}
+
+bool copy_batch_takes(const void *const *src, void *const *dst, int n, size_t bytes)
+{
+    if (n < 1 || n > CopyBatch::MAX || bytes == 0 || bytes % 16 != 0)
+        return false;
+    const int64_t per_buf = (int64_t)((bytes / 16 + (size_t)DP_THREADS * DP_UNROLL - 1) / ((size_t)DP_THREADS * DP_UNROLL));
+    if (per_buf * n >= ((int64_t)1 << 31))
+        return false;
+    for (int i = 0; i < n; ++i)
+        if (((reinterpret_cast<uintptr_t>(src[i]) | reinterpret_cast<uintptr_t>(dst[i])) & 15u) != 0)
+            return false;
+    return true;
+}
+
+hipError_t launch_copy_batch(const void *const *src, void *const *dst, int n, size_t bytes, hipStream_t s)
+{
+    CopyBatch cb = {};
+    for (int i = 0; i < n; ++i) {
+        cb.src[i] = src[i];
+        cb.dst[i] = dst[i];
+    }
+    const int64_t n16 = (int64_t)(bytes / 16);
+    const int per_buf = (int)((n16 + (int64_t)DP_THREADS * DP_UNROLL - 1) / ((int64_t)DP_THREADS * DP_UNROLL));
+    hipLaunchKernelGGL(copy_batch_kernel, dim3((unsigned)(per_buf * n)), dim3(DP_THREADS), 0, s, cb, n16, per_buf);
+    return hipGetLastError();
 }
 
 hipError_t launch_set_words(unsigned *dst, int count, unsigned value, hipStream_t s)
