@@ -201,7 +201,6 @@ def main() -> int:
     if not args.only_pair:
         H_all = ag.O                                              # [8192 x 3584] bf16, written by the up-projection
         Y_all = torch.empty((dn.p * dn.m_chunk, dn.n), dtype=torch.float32, device=H.DEV)
-        slot32 = torch.empty((dn.m_chunk, dn.n), dtype=torch.float32, device=H.DEV)
         blk = lambda c: H_all[c * dn.m_chunk:(c + 1) * dn.m_chunk]
         rows = [blk((0 - i) % dn.p) for i in range(1, dn.p)]      # slice of step i where Alg. 1 expects it: no copies needed
         d_whole = cf.layer_desc(dn.p, 0, dn.m_chunk, dn.n, dn.k, "bf16", "f32")
@@ -214,10 +213,9 @@ def main() -> int:
 
         def vanilla_down():
             cf.run_schedule(d_whole, cf.CF_KIND_AG, b_whole, ag.cs, ag.xs, PS_ | cf.CF_NO_COPY)
+            cf.run_schedule(rs.desc, cf.CF_KIND_RS, rs.bufs, rs.cs, rs.xs, PS_ | cf.CF_NO_COMPUTE)   # the seven deliveries
             for i in range(1, dn.p):
-                with torch.cuda.stream(ag.cs):
-                    slot32.copy_(rs.stage[i - 1], non_blocking=True)
-                cf.dp_reduce_step(dn.p, 0, i, Y_all, chunk_elems, slot32, ag.cs)
+                cf.dp_reduce_step(dn.p, 0, i, Y_all, chunk_elems, rs.each[i - 1], ag.cs)
 
         t_vu = time_calls(vanilla_up, ag.cs, K, W)
         t_vd = time_calls(vanilla_down, ag.cs, K, W)
@@ -226,7 +224,7 @@ def main() -> int:
                    "us_pair": round(t_vp * 1e3, 1), "tflops_pair": round(flops_pair / (t_vp * 1e-3) / 1e12, 1),
                    "vanilla_over_fused": round(t_vp / ms_step, 3)}
         log("vanilla", vanilla)
-        del Y_all, slot32, b_whole, rows
+        del Y_all, b_whole, rows
     del ag, rs, ddn
     torch.cuda.empty_cache()
 
