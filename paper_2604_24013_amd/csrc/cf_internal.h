@@ -45,6 +45,7 @@ struct GemmParams {
     static constexpr int MAX_STEPS = 16;
     int n_steps = 0;
     int num_cu = 256;
+    bool k_rotate = false;   // persistent mode: XCD x starts its k loops x/8 of the way into the k range (set by the launcher)
     bool xcd_steps = false;  // persistent mode: XCD x runs steps x, x+8, ... whole (set by the launcher)
     const void *A_step[MAX_STEPS] = {};
     const float *recv_step[MAX_STEPS] = {};

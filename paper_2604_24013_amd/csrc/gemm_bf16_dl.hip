@@ -302,9 +302,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // kt into `stage`.  A tile beyond the end of this split's k range is requested all the same, with
     // every lane out of range (it reads zeros and moves no data), so that the number of loads per
     // tile -- and with it every vmcnt below -- is the same in every iteration.
+    // Persistent mode: the workgroups of XCD x walk the k range starting x/8 of the way in and wrap around, so
+    // that the eight XCDs -- which all read the same weight tiles, and would ask for the same lines at the same
+    // moment -- are spread over the k range (measured: 1 % of the pair's rank step).  The sum over k is taken in
+    // that rotated order: deterministic for a given launch, last-bit different between XCDs.
+    const int rot = (PERSIST && P.k_rotate) ? (int)(((blockIdx.x & 7) * nk_all) >> 3) : 0;
+    auto ktile = [&](int kt) {                           // global k-tile of this item's local k-tile kt
+        const int kk = ktb + kt + rot;
+        return kk >= nk_all ? kk - nk_all : kk;
+    };
     auto issue_load = [&](int kt, int stage, auto idx_tag) {
         constexpr int idx = decltype(idx_tag)::value;
-        const int k0 = (ktb + kt) * BK;
+        const int k0 = ktile(kt) * BK;
         const unsigned sa = lds_base + stage * STAGE + wave * 1024;
         const bool full = kt < nk && (k0 + BK) <= K;     // uniform: the common case needs no per-lane test
         if (full) {
@@ -329,7 +338,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     auto issue_range = [&](int kt, int stage, auto lo_tag, auto hi_tag) {   // loads [lo, hi) of a tile
         constexpr int lo = decltype(lo_tag)::value, hi = decltype(hi_tag)::value;
         static_assert(hi - lo <= 8, "at most eight direct loads per tile and wave");
-        const int k0 = (ktb + kt) * BK;
+        const int k0 = ktile(kt) * BK;
         const unsigned sa = lds_base + stage * STAGE + wave * 1024;
         if (kt < nk && (k0 + BK) <= K) {                 // uniform: the common case, no per-lane test
 #pragma unroll
@@ -834,10 +843,12 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
         p.splits = 1;
         p.cp_wgs = 0;
         p.cp_bytes = 0;
+        const char *rk = getenv("COMMFUSE_K_ROTATE");   // tuning override: 0 = every XCD walks k from 0
         const char *e = getenv("COMMFUSE_XCD_STEPS");  // tuning override: 0 = every XCD takes a band of every step
         // (not when one step carries the sum of several received partials: that step's epilogue is heavy and
         // would fall on one XCD)
         p.xcd_steps = p.n_steps % 8 == 0 && p.num_cu % 8 == 0 && p.n_recv_more == 0 && !(e != nullptr && atoi(e) == 0);
+        p.k_rotate = p.xcd_steps && !(rk != nullptr && atoi(rk) == 0);   // (measured with whole steps per XCD only)
     }
     if (p.splits > 1 && (p.ws == nullptr || p.counters == nullptr ||
                          (size_t)p.splits * p.M * p.N * sizeof(float) > p.ws_bytes || tiles > p.max_tiles ||

@@ -461,6 +461,39 @@ def test_persistent_rank_step(m, tile):
     assert H.rel_err(H.to_host_f64(run.O), ref[-1]) <= TIGHT_BF16
 
 
+@pytest.mark.parametrize("kind", ["rs", "ag"])
+def test_persistent_k_rotation(kind):
+    """The persistent launch lets the workgroups of XCD x start their k loops x/8 of the way into the k range
+    (wrapping around; the ragged last k-tile then falls in mid-loop).  With the rotation and without it the
+    rank step must match the oracle; the two differ at most in last bits (another order of the same sum)."""
+    rank = 6
+    flags = cf.CF_PERSISTENT | cf.CF_SERIAL
+    outs = {}
+    try:
+        for rot in ("1", "0"):
+            os.environ["COMMFUSE_K_ROTATE"] = rot
+            if kind == "rs":
+                w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=8, m_chunk=264, n=520, k=1096)
+                data = inputs.make_rs(w, salt=43)
+                ref = _oracle_rs(w, data, rank)[-1]
+                run = H.RsRun(w, data, rank, each=True)
+                tol = TIGHT_BF16
+            else:
+                w = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=8, m_chunk=136, n=264, k=1096)
+                data = inputs.make_ag(w, salt=44)
+                ref = _oracle_ag(w, data, rank)
+                run = H.AgRun(w, data, rank, each=True)
+                tol = TIGHT_BF16
+            run.O.fill_(float("nan"))
+            run.run_schedule(flags)
+            outs[rot] = H.to_host_f64(run.O)
+            e = H.rel_err(outs[rot], ref)
+            assert e <= tol, f"rotate {rot}: {e:.3e}"
+        assert H.rel_err(outs["1"], outs["0"]) <= 1e-5
+    finally:
+        os.environ.pop("COMMFUSE_K_ROTATE", None)
+
+
 def _padded(t, rows, cols, ld, fill):
     """Device copy of a [rows x cols] tensor with row stride ld; the padding holds `fill`."""
     o = torch.full((rows, ld), fill, dtype=t.dtype, device=H.DEV)
