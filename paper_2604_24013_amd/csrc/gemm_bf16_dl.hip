@@ -146,12 +146,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     constexpr int B_LD = (B_BYTES / 1024) / NW;
     constexpr int LPT = A_LD + B_LD;                // direct loads per wave per k-tile
     static_assert(A_LD >= 1 && B_LD >= 1 && (A_BYTES / 1024) % NW == 0 && (B_BYTES / 1024) % NW == 0, "tile vs waves");
-    static_assert(NS >= 2 && NS <= 4 && NS * STAGE <= 160 * 1024, "LDS budget");
+    // LDS: NSA stages of the left-operand tile, then NS stages of the weight tile.  The 256x256 tile (SPREAD)
+    // fills the 160 KiB with THREE left-operand stages and two weight stages: its weight loads go out first
+    // after the barrier that frees their stage and its left-operand loads one k-tile further ahead (see the
+    // steady state below), which lengthens the time every load has to arrive.
+    constexpr int NSA = SPREAD ? NS + 1 : NS;
+    constexpr int W_BASE = NSA * A_BYTES;
+    static_assert(NS >= 2 && NS <= 4 && NSA * A_BYTES + NS * B_BYTES <= 160 * 1024, "LDS budget");
     static_assert(KS == 4, "the slice schedule below is written for four slices per stage");
     constexpr int W_ROWB = BN * 2;                   // bytes of one k-row of a [k x n] weight tile
     constexpr int A_ROWB = BM * 2;                   // bytes of one k-row of a [k x m] left-operand tile
 
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[NS * STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[NSA * A_BYTES + NS * B_BYTES];
 
     const int tid0 = threadIdx.x;
 
@@ -311,16 +317,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         const int kk = ktb + kt + rot;
         return kk >= nk_all ? kk - nk_all : kk;
     };
-    auto issue_load = [&](int kt, int stage, auto idx_tag) {
+    auto issue_load = [&](int kt, int stage_a, int stage_w, auto idx_tag) {
         constexpr int idx = decltype(idx_tag)::value;
         const int k0 = ktile(kt) * BK;
-        const unsigned sa = lds_base + stage * STAGE + wave * 1024;
+        const unsigned sa = lds_base + stage_a * A_BYTES + wave * 1024;
+        const unsigned sw = lds_base + W_BASE + stage_w * B_BYTES + wave * 1024;
         const bool full = kt < nk && (k0 + BK) <= K;     // uniform: the common case needs no per-lane test
         if (full) {
             if constexpr (idx < A_LD)
                 direct_load_16(a_rsrc, a_off[idx], k0 * a_kstep, sa + idx * NW * 1024);
             else
-                direct_load_16(w_rsrc, b_off[idx - A_LD], k0 * w_kstep, sa + A_BYTES + (idx - A_LD) * NW * 1024);
+                direct_load_16(w_rsrc, b_off[idx - A_LD], k0 * w_kstep, sw + (idx - A_LD) * NW * 1024);
         } else {
             const bool none = kt >= nk;
             const int klim = none ? -1 : K;              // chunks at k >= klim read as zero
@@ -331,15 +338,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             } else {
                 constexpr int j = idx - A_LD;
                 const unsigned off = (k0 + b_k[j]) >= klim ? OOB : b_off[j];
-                direct_load_16(w_rsrc, off, ks0 * w_kstep, sa + A_BYTES + j * NW * 1024);
+                direct_load_16(w_rsrc, off, ks0 * w_kstep, sw + j * NW * 1024);
             }
         }
     };
-    auto issue_range = [&](int kt, int stage, auto lo_tag, auto hi_tag) {   // loads [lo, hi) of a tile
+    auto issue_range = [&](int kt, int stage_a, int stage_w, auto lo_tag, auto hi_tag) {   // loads [lo, hi) of a tile
         constexpr int lo = decltype(lo_tag)::value, hi = decltype(hi_tag)::value;
         static_assert(hi - lo <= 8, "at most eight direct loads per tile and wave");
         const int k0 = ktile(kt) * BK;
-        const unsigned sa = lds_base + stage * STAGE + wave * 1024;
+        const unsigned sa = lds_base + stage_a * A_BYTES + wave * 1024;
+        const unsigned sw = lds_base + W_BASE + stage_w * B_BYTES + wave * 1024;
         if (kt < nk && (k0 + BK) <= K) {                 // uniform: the common case, no per-lane test
 #pragma unroll
             for (int idx = lo; idx < hi; ++idx) {
@@ -347,17 +355,17 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                     direct_load_16(a_rsrc, a_off[idx < A_LD ? idx : 0], k0 * a_kstep, sa + idx * NW * 1024);
                 else
                     direct_load_16(w_rsrc, b_off[idx >= A_LD ? idx - A_LD : 0], k0 * w_kstep,
-                                   sa + A_BYTES + (idx - A_LD) * NW * 1024);
+                                   sw + (idx - A_LD) * NW * 1024);
             }
         } else {
-            if constexpr (lo + 0 < hi) issue_load(kt, stage, std::integral_constant<int, lo + 0>{});
-            if constexpr (lo + 1 < hi) issue_load(kt, stage, std::integral_constant<int, lo + 1>{});
-            if constexpr (lo + 2 < hi) issue_load(kt, stage, std::integral_constant<int, lo + 2>{});
-            if constexpr (lo + 3 < hi) issue_load(kt, stage, std::integral_constant<int, lo + 3>{});
-            if constexpr (lo + 4 < hi) issue_load(kt, stage, std::integral_constant<int, lo + 4>{});
-            if constexpr (lo + 5 < hi) issue_load(kt, stage, std::integral_constant<int, lo + 5>{});
-            if constexpr (lo + 6 < hi) issue_load(kt, stage, std::integral_constant<int, lo + 6>{});
-            if constexpr (lo + 7 < hi) issue_load(kt, stage, std::integral_constant<int, lo + 7>{});
+            if constexpr (lo + 0 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 0>{});
+            if constexpr (lo + 1 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 1>{});
+            if constexpr (lo + 2 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 2>{});
+            if constexpr (lo + 3 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 3>{});
+            if constexpr (lo + 4 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 4>{});
+            if constexpr (lo + 5 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 5>{});
+            if constexpr (lo + 6 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 6>{});
+            if constexpr (lo + 7 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 7>{});
         }
     };
 
@@ -396,14 +404,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int q = ((nl >> 5) + j) ^ (kl & 3);
-            w_addr[j] = A_BYTES + kl * W_ROWB + (q << 6) + (nl & 31) * 2;
+            w_addr[j] = W_BASE + kl * W_ROWB + (q << 6) + (nl & 31) * 2;
         }
     } else {
-        w_addr[0] = A_BYTES + swz_row(wn * WTN + frow, fkc);
+        w_addr[0] = W_BASE + swz_row(wn * WTN + frow, fkc);
     }
 
-    auto read_frags = [&](int stage, int ks, bf16x8_t (&af)[TM], bf16x8_t (&wf)[TN]) {
-        const unsigned char *st = smem + stage * STAGE;
+    auto read_frags = [&](int stage_a, int stage_w, int ks, bf16x8_t (&af)[TM], bf16x8_t (&wf)[TN]) {
+        const unsigned char *st = smem + stage_a * A_BYTES;
+        const unsigned char *stw = smem + stage_w * B_BYTES;     // (w_addr holds the weight region's base)
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             if constexpr (A_T) {
@@ -421,7 +430,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             if constexpr (W_KN) {
-                const unsigned char *pw = st + w_addr[j] + ks * 16 * W_ROWB;
+                const unsigned char *pw = stw + w_addr[j] + ks * 16 * W_ROWB;
                 const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                     (__attribute__((address_space(3))) s16x4_t *)(pw));
                 const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -429,7 +438,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 wf[j] = __builtin_bit_cast(bf16x8_t, both);
             } else {
-                wf[j] = *reinterpret_cast<const bf16x8_t *>(st + (w_addr[0] ^ (ks << 5)) + j * 32 * 128);
+                wf[j] = *reinterpret_cast<const bf16x8_t *>(stw + (w_addr[0] ^ (ks << 5)) + j * 32 * 128);
             }
         }
     };
@@ -458,29 +467,29 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         for (int q = seg * MPS; q < (seg + 1) * MPS; ++q)
             acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[q % TN], af[q / TN], acc[q / TN][q % TN], 0, 0, 0);
     };
-    auto phase = [&](const bf16x8_t (&afc)[TM], const bf16x8_t (&wfc)[TN], bool do_read, int stage_n, int ks_n,
-                     bf16x8_t (&afn)[TM], bf16x8_t (&wfn)[TN], int kt_l, int stage_l, auto lo_tag, auto n_tag) {
+    auto phase = [&](const bf16x8_t (&afc)[TM], const bf16x8_t (&wfc)[TN], bool do_read, int sa_n, int sw_n, int ks_n,
+                     bf16x8_t (&afn)[TM], bf16x8_t (&wfn)[TN], int kt_l, int sa_l, int sw_l, auto lo_tag, auto n_tag) {
         constexpr int LO = decltype(lo_tag)::value, NL = decltype(n_tag)::value;   // load slots of this phase
         if (do_read)
-            read_frags(stage_n, ks_n, afn, wfn);
+            read_frags(sa_n, sw_n, ks_n, afn, wfn);
         mfma_seg(afc, wfc, std::integral_constant<int, 0>{});
         interleave_mfma_reads<NREAD, (NREAD + MPS - 1) / MPS>();
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (NL > 0) issue_load(kt_l, stage_l, std::integral_constant<int, LO>{});
+        if constexpr (NL > 0) issue_load(kt_l, sa_l, sw_l, std::integral_constant<int, LO>{});
         if constexpr (NSEG > 1) {
             mfma_seg(afc, wfc, std::integral_constant<int, 1>{});
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (NL > 1) issue_load(kt_l, stage_l, std::integral_constant<int, LO + 1>{});
+            if constexpr (NL > 1) issue_load(kt_l, sa_l, sw_l, std::integral_constant<int, LO + 1>{});
         }
         if constexpr (NSEG > 2) {
             mfma_seg(afc, wfc, std::integral_constant<int, 2>{});
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (NL > 2) issue_load(kt_l, stage_l, std::integral_constant<int, LO + 2>{});
+            if constexpr (NL > 2) issue_load(kt_l, sa_l, sw_l, std::integral_constant<int, LO + 2>{});
         }
         if constexpr (NSEG > 3) {
             mfma_seg(afc, wfc, std::integral_constant<int, 3>{});
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (NL > 3) issue_load(kt_l, stage_l, std::integral_constant<int, LO + 3>{});
+            if constexpr (NL > 3) issue_load(kt_l, sa_l, sw_l, std::integral_constant<int, LO + 3>{});
         }
     };
     using c0 = std::integral_constant<int, 0>;
@@ -521,40 +530,48 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     };
 
     if constexpr (SPREAD) {
-        // Prologue: tiles 0 .. NS-2 and the first LH loads of tile NS-1 are requested (tile t lives in
-        // stage t mod NS); tile 0 is awaited and its first fragments fetched.
+        // The left-operand tile has NS+1 stages, the weight tile NS (tile t lives in stages t mod (NS+1) and
+        // t mod NS).  Loads return in issue order, so what is issued first must be what is needed first:
+        //   prologue: tiles 0 .. NS-1 whole, in tile order; tile 0 is awaited, its first fragments fetched
+        //   steady state, tile kt:
+        //     slice 0: + the left-operand loads of tile kt+NS, into the stage tile kt-1 vacated
+        //     slice 1, slice 2
+        //     wait: tile kt+1 complete -- the loads of NS-2 later whole tiles and the left-operand loads
+        //           just issued may be in flight; barrier: tile kt has been read by all
+        //     slice 3: + the weight loads of tile kt+NS, into the stage tile kt vacated
+        // A weight load thus has 1 to 1.25 k-tiles of MFMA time to arrive and a left-operand load 1.75 to 2
+        // (with NS = 2; both NS-2 more otherwise).
+        static_assert(A_LD == LH && LPT - LH == B_LD, "one load slot per MFMA segment and operand");
+        using cALD = std::integral_constant<int, A_LD>;
     #pragma unroll
-        for (int t = 0; t < NS - 1; ++t)
-            issue_range(t, t, c0{}, cLPT{});
-        issue_range(NS - 1, NS - 1, c0{}, cLH{});
-        wait_vmcnt<(NS - 2) * LPT + LH>();
+        for (int t = 0; t < NS; ++t)
+            issue_range(t, t, t, c0{}, cLPT{});
+        wait_vmcnt<(NS - 1) * LPT>();
         __syncthreads();
-        read_frags(0, 0, af0, wf0);
+        read_frags(0, 0, 0, af0, wf0);
         __builtin_amdgcn_sched_barrier(0);
 
-        // Steady state, tile kt in stage `cur`:
-        //   slice 0: + the remaining loads of tile kt-1+NS (its first LH went out in the previous slice 3)
-        //   slice 1, slice 2
-        //   wait: tile kt+1 complete, NS-2 later tiles may be in flight; barrier: tile kt is read by all
-        //   slice 3: + the first LH loads of tile kt+NS, into the stage tile kt vacated
-        int cur = 0, prev = NS - 1;                      // stage of tile kt / of tile kt-1 (= of tile kt-1+NS)
+        int cur_a = 0, cur_w = 0;                        // stages of tile kt
+        int prev_a = NSA - 1;                            // left-operand stage of tile kt-1 (= of tile kt+NS)
         for (int kt = 0; kt + 1 < nk; ++kt) {
-            const int nxt = (cur + 1 == NS) ? 0 : cur + 1;
-            phase(af0, wf0, true, cur, 1, af1, wf1, kt - 1 + NS, prev, cLH{}, cLR{});
-            phase(af1, wf1, true, cur, 2, af0, wf0, 0, 0, c0{}, c0{});
-            phase(af0, wf0, true, cur, 3, af1, wf1, 0, 0, c0{}, c0{});
-            wait_vmcnt<(NS - 2) * LPT>();
+            const int nxt_a = (cur_a + 1 == NSA) ? 0 : cur_a + 1;
+            const int nxt_w = (cur_w + 1 == NS) ? 0 : cur_w + 1;
+            phase(af0, wf0, true, cur_a, cur_w, 1, af1, wf1, kt + NS, prev_a, 0, c0{}, cALD{});
+            phase(af1, wf1, true, cur_a, cur_w, 2, af0, wf0, 0, 0, 0, c0{}, c0{});
+            phase(af0, wf0, true, cur_a, cur_w, 3, af1, wf1, 0, 0, 0, c0{}, c0{});
+            wait_vmcnt<(NS - 2) * LPT + A_LD>();
             __syncthreads();
             __builtin_amdgcn_sched_barrier(0);
-            phase(af1, wf1, true, nxt, 0, af0, wf0, kt + NS, cur, c0{}, cLH{});
-            prev = cur;
-            cur = nxt;
+            phase(af1, wf1, true, nxt_a, nxt_w, 0, af0, wf0, kt + NS, 0, cur_w, cALD{}, cLR{});
+            prev_a = cur_a;
+            cur_a = nxt_a;
+            cur_w = nxt_w;
         }
         if (nk > 0) {                                    // last tile: nothing follows it
-            phase(af0, wf0, true, cur, 1, af1, wf1, 0, 0, c0{}, c0{});
-            phase(af1, wf1, true, cur, 2, af0, wf0, 0, 0, c0{}, c0{});
-            phase(af0, wf0, true, cur, 3, af1, wf1, 0, 0, c0{}, c0{});
-            phase(af1, wf1, false, 0, 0, af0, wf0, 0, 0, c0{}, c0{});
+            phase(af0, wf0, true, cur_a, cur_w, 1, af1, wf1, 0, 0, 0, c0{}, c0{});
+            phase(af1, wf1, true, cur_a, cur_w, 2, af0, wf0, 0, 0, 0, c0{}, c0{});
+            phase(af0, wf0, true, cur_a, cur_w, 3, af1, wf1, 0, 0, 0, c0{}, c0{});
+            phase(af1, wf1, false, 0, 0, 0, af0, wf0, 0, 0, 0, c0{}, c0{});
         }
 
     } else {
@@ -565,7 +582,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                            bf16x8_t (&afn)[TM], bf16x8_t (&wfn)[TN], auto rpm_tag) {
             constexpr int RPM = decltype(rpm_tag)::value;
             if (do_read)
-                read_frags(stage_n, ks_n, afn, wfn);
+                read_frags(stage_n, stage_n, ks_n, afn, wfn);
 #pragma unroll
             for (int q = 0; q < NMFMA; ++q)
                 acc[q / TN][q % TN] =
@@ -578,10 +595,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         using rpm2 = std::integral_constant<int, 2 * RPM_N>;    // reads packed into its first half
 #pragma unroll
         for (int t = 0; t < NS; ++t)
-            issue_range(t, t, c0{}, cLPT{});
+            issue_range(t, t, t, c0{}, cLPT{});
         wait_vmcnt<(NS - 1) * LPT>();
         __syncthreads();
-        read_frags(0, 0, af0, wf0);
+        read_frags(0, 0, 0, af0, wf0);
         __builtin_amdgcn_sched_barrier(0);
         int cur = 0;
         for (int kt = 0; kt + 1 < nk; ++kt) {
@@ -596,7 +613,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             else
                 wait_vmcnt<(NS - 2) * LPT>();
             __syncthreads();                 // tile kt is read by all, tile kt+1 is published
-            issue_range(kt + NS, cur, c0{}, cLPT{});
+            issue_range(kt + NS, cur, cur, c0{}, cLPT{});
             if constexpr (PF) {
                 if (pf_on && kt == pf_at) {
                     wait_delivery(false);
