@@ -396,6 +396,17 @@ def main() -> int:
         t_k = time_calls(lambda: cf.dp_reduce_step(w5.p, 0, 1, run.bucket, c, run.stage[0], run.cs), run.cs, 50, 5)
         gbs = 12.0 * c / (t_k * 1e-3) / 1e9
         t = schedule_times(run, cf.CF_KIND_DP, 10, 2)
+        # CF_PERSISTENT: a landing buffer per hop, the seven deliveries as one batched copy, then the seven adds
+        pers = H.DpRun.__new__(H.DpRun)
+        pers.__dict__.update(run.__dict__)
+        pers.each = [torch.empty((c,), dtype=torch.float32, device=H.DEV) for _ in range(w5.p - 1)]
+        pers.bufs = cf.make_buffers(None, None, run.bucket, run.stage, run.slot, (None, None), None, pers.each)
+        for name, fl in (("overlapped", 0), ("copy_only", cf.CF_NO_COMPUTE)):
+            for mode, extra in (m_ for m_ in MODES if "persistent" in m_[0]):
+                tp = time_calls(lambda: cf.run_schedule(pers.desc, cf.CF_KIND_DP, pers.bufs, pers.cs, pers.xs, fl | extra),
+                                pers.cs, 10, 2)
+                if tp < t[name][0]:
+                    t[name] = (tp, mode)
         steps_with_add = w5.p - 1
         dp = {"kernel_GBps": round(gbs, 1), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4),
               "us_per_reduce_kernel": round(t_k * 1e3, 1), "bytes_per_elem": 12,
@@ -405,7 +416,7 @@ def main() -> int:
               "overlap_eff": round(overlap_eff(t), 3),
               "us_compute_only": round(t["compute_only"][0] * 1e3, 1), "us_copy_only": round(t["copy_only"][0] * 1e3, 1)}
         log("dp", dp)
-        del run
+        del run, pers
         torch.cuda.empty_cache()
 
     cf.device_status(None)                            # no step kernel gave up a device-side wait

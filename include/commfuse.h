@@ -250,7 +250,8 @@ typedef struct {
                                      nothing but the step kernels.  CF_KIND_RS_PAIR: round t's
                                      delivery lands in recv_each[t-1], no step accumulates, and
                                      the last step adds them all in its epilogue
-                                     (commfuse_rs_pair_last_step).  Not for the bucket kinds.    */
+                                     (commfuse_rs_pair_last_step).  Bucket kinds (CF_KIND_DP,
+                                     CF_KIND_DP_PAIR): with CF_PERSISTENT only.                  */
 } cf_buffers;
 
 enum {
@@ -263,7 +264,8 @@ enum {
                             extra workgroups of step i's kernel launch instead of a
                             hipMemcpyAsync on copy_stream: one stream, no events
                             (copy_stream is unused; not with CF_POISON)               */
-    CF_PERSISTENT = 128u,/* bf16 CF_KIND_RS / CF_KIND_AG / CF_KIND_RS_PAIR / CF_KIND_WGRAD_*, at most 16 (sub-)steps: ONE kernel
+    CF_PERSISTENT = 128u,/* bf16 CF_KIND_RS / CF_KIND_AG / CF_KIND_RS_PAIR / CF_KIND_WGRAD_* (and the fp32 bucket kinds, see
+                            the end), at most 16 (sub-)steps: ONE kernel
                             launch runs all steps of the rank step.  Its work items (step, output tile) are
                             dealt out step-major to a grid that fills the chip once; tiles of different
                             steps run side by side (the chunk GEMMs do not depend on each other -- only
@@ -287,6 +289,9 @@ enum {
                             GEMMs dW += slice^T local_slice are then one GEMM whose contraction runs
                             over all p*m_chunk rows: dW is written once, not read and written p times
                             (the sum runs in row-block order, not in step order).
+                            Bucket kinds (CF_KIND_DP, CF_KIND_DP_PAIR; fp32): there is no GEMM to fuse
+                            into; the flag buys the deliveries of all hops as ONE batched copy launch
+                            into recv_each, followed by the same add kernels in the same order.
                             Not with CF_FUSED_COPY / CF_DEVICE_WAIT.                                   */
     CF_DEVICE_WAIT = 64u /* bf16 RS / AG only, needs a registered workspace: the compute
                             stream does not wait for the copy stream between steps;

@@ -801,7 +801,8 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
     const bool do_copy = !(flags & CF_NO_COPY) && p > 1;
     const bool do_compute = !(flags & CF_NO_COMPUTE);
     const bool poison = (flags & CF_POISON) != 0;
-    const size_t slot_bytes = is_rs_kind(kind)         ? (size_t)r.mc * r.ldo * sizeof(float)
+    const size_t slot_bytes = is_dp_kind(kind)         ? (size_t)r.mc * sizeof(float)
+                              : is_rs_kind(kind)       ? (size_t)r.mc * r.ldo * sizeof(float)
                               : kind == CF_KIND_WGRAD_G ? (size_t)r.mc * r.ldw * in_elem(r)
                                                         : (size_t)r.mc * r.lda * in_elem(r);
     // Weight gradient: the moving operand must sit in "gathered" order -- one [p*m_chunk x width] buffer, the
@@ -850,6 +851,22 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
                 return fail_hip(e, "delivery copy launch");
         }
     }
+    // Gradient bucket: nothing to fuse into -- the adds of a rank step, each on the landing buffer of its own hop
+    // (ring: every hop's slice is a different one, Alg. 2 with the identity; pairwise: all arrivals are summed
+    // into the own slice in round order), behind the one batched delivery
+    if (do_compute && is_dp_kind(kind)) {
+        float *bucket = static_cast<float *>(b->O);
+        for (int j = m; j < S; ++j) {
+            const float *recv = static_cast<const float *>(landing(j));
+            cf_status st = kind == CF_KIND_DP_PAIR ? dp_pair_step_impl(p, r.rank, j, bucket, r.mc, recv, cs)
+                                                   : dp_step_impl(p, r.rank, j, bucket, r.mc, recv, cs, m);
+            if (st != CF_OK)
+                return st;
+        }
+        return CF_OK;
+    }
+    if (is_dp_kind(kind))
+        return CF_OK;
     if (do_compute && is_wgrad_kind(kind)) {
         Resolved all = r;
         all.m = 1;
@@ -916,8 +933,8 @@ cf_status check_buffers(const Resolved &r, int kind, const cf_buffers *b, uint32
         return fail(CF_ERR_NULL_PTR, "buffers->O is NULL");
     if (!is_dp_kind(kind) && (b->A_or_own_shard == nullptr || b->W == nullptr))
         return fail(CF_ERR_NULL_PTR, "buffers->A_or_own_shard / W is NULL");
-    if (b->recv_each != nullptr && is_dp_kind(kind))
-        return fail(CF_ERR_INVALID_ARG, "buffers->recv_each is not used by the gradient-bucket kinds");
+    if (b->recv_each != nullptr && is_dp_kind(kind) && !(flags & CF_PERSISTENT))
+        return fail(CF_ERR_INVALID_ARG, "buffers->recv_each is used by the gradient-bucket kinds with CF_PERSISTENT only");
     const bool keep_all = b->recv_each != nullptr;
     if (r.p > 1) {
         if (keep_all) {
@@ -994,12 +1011,14 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
             return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT excludes CF_FUSED_COPY and CF_DEVICE_WAIT");
         if (attn != nullptr && r.m != 1)
             return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT with the attention layer needs m = 1");
-        const bool ok_kind = is_wgrad_kind(kind) ? wgrad_can_carry_copy(r)
-                                                 : (kind == CF_KIND_RS || kind == CF_KIND_AG || kind == CF_KIND_RS_PAIR) &&
-                                                       step_can_carry_copy(r) && r.p - 2 <= cf::GemmParams::MAX_RECV_MORE;
+        const bool ok_kind = is_dp_kind(kind)      ? true
+                             : is_wgrad_kind(kind) ? wgrad_can_carry_copy(r)
+                                                   : (kind == CF_KIND_RS || kind == CF_KIND_AG || kind == CF_KIND_RS_PAIR) &&
+                                                         step_can_carry_copy(r) && r.p - 2 <= cf::GemmParams::MAX_RECV_MORE;
         if (!ok_kind || r.p * r.m > cf::GemmParams::MAX_STEPS)
             return fail(CF_ERR_UNSUPPORTED,
-                        "CF_PERSISTENT needs kind RS, AG, RS_PAIR or a weight-gradient kind, bf16 operands and at most %d (sub-)steps",
+                        "CF_PERSISTENT needs bf16 operands (kinds RS, AG, RS_PAIR, weight gradient; the gradient-bucket kinds take "
+                        "fp32) and at most %d (sub-)steps",
                         cf::GemmParams::MAX_STEPS);
         if (bufs != nullptr && bufs->peer_sink != nullptr)
             return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT cannot feed peer_sink (nothing signals a finished step)");

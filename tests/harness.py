@@ -119,7 +119,7 @@ class AgRun:
 class DpRun:
     """The gradient reduce-scatter rank step on the device."""
 
-    def __init__(self, w: inputs.Workload, data: dict, rank: int, with_sink=False, m=1):
+    def __init__(self, w: inputs.Workload, data: dict, rank: int, with_sink=False, m=1, each=False):
         self.w, self.rank, self.m = w, rank, m
         self.desc = cf.layer_desc(w.p, rank, w.m_chunk, 0, 0, "f32", "f32", m=m)
         self.bucket = to_dev(data["bucket"], "f32")
@@ -127,7 +127,8 @@ class DpRun:
         mk = lambda: torch.empty((w.m_chunk,), dtype=torch.float32, device=DEV)
         self.slot = [mk(), mk()]
         self.sink = [mk() for _ in range(w.p - 1)] if with_sink else None
-        self.bufs = cf.make_buffers(None, None, self.bucket, self.stage, self.slot, (None, None), self.sink)
+        self.each = [mk() for _ in range(w.p - 1)] if each else None      # a landing buffer per hop (CF_PERSISTENT)
+        self.bufs = cf.make_buffers(None, None, self.bucket, self.stage, self.slot, (None, None), self.sink, self.each)
         self.cs = torch.cuda.Stream()
         self.xs = torch.cuda.Stream()
 

@@ -158,6 +158,11 @@ def test_dp_granularity(p, m, c):
         for i in range(p - 1):
             l = (rank - i - 1) % p
             assert np.array_equal(H.to_host_f64(run.sink[i]), want32[l * c:(l + 1) * c]), f"flags {flags} hop {i}"
+    pers = H.DpRun(w, data, rank, m=m, each=True)                 # the m sub-slices of a hop stacked in its landing buffer
+    for t in pers.each:
+        t.fill_(float("nan"))
+    pers.run_schedule(cf.CF_PERSISTENT | cf.CF_SERIAL)
+    assert np.array_equal(H.to_host_f64(pers.bucket), want32)
 
 
 def test_granularity_bad_arguments():

@@ -157,12 +157,21 @@ def test_dp_pair_reduced(p, c):
     for i in range(p - 1):
         l = oracle.slice_index_pair(p, rank, i)
         assert np.array_equal(H.to_host_f64(run.sink[i]), data["bucket"][l * c:(l + 1) * c].astype(np.float64))
+    # CF_PERSISTENT: all rounds' deliveries as one batched copy into a buffer per round, then the adds in round order
+    pers = H.DpPairRun(w, data, rank, each=True)
+    for t in pers.each:
+        t.fill_(float("nan"))
+    pers.run_schedule(cf.CF_PERSISTENT | cf.CF_SERIAL)
+    assert np.array_equal(H.to_host_f64(pers.bucket), ref)
     # normally distributed gradients: p-1 fp32 additions in round order
     data = inputs.make_dp(w, salt=9)
     ref = oracle.dp_pair_rank(data["bucket"], data["R"], p, rank)
     got = H.DpPairRun(w, data, rank).run_steps()
     scale = max(1.0, float(np.abs(ref).max()))
     assert np.max(np.abs(got - ref)) <= (p - 1) * 2.0 ** -24 * scale * 2
+    pers = H.DpPairRun(w, data, rank, each=True)
+    pers.run_schedule(cf.CF_PERSISTENT | cf.CF_SERIAL)
+    assert np.array_equal(H.to_host_f64(pers.bucket), got)       # the same adds in the same order
 
 
 def _sample_rows(mc, rng, extra=6):

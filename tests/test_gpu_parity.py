@@ -303,6 +303,21 @@ def test_dp_reduced(p, c):
     for i in range(p - 1):
         l = (rank - i - 1) % p
         assert np.array_equal(H.to_host_f64(run.sink[i]), want32[l * c:(l + 1) * c])
+    # CF_PERSISTENT: every hop lands in a buffer of its own, all deliveries as one batched copy (slices whose
+    # byte size is no multiple of 16: one copy per hop), then the same adds
+    run = H.DpRun(w, data, rank, each=True)
+    for flags in (cf.CF_PERSISTENT | cf.CF_SERIAL, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_GRAPH,
+                  cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_GRAPH):
+        run.bucket.copy_(H.to_dev(data["bucket"], "f32"))
+        for t in run.each:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        run.run_schedule(flags)
+        assert np.array_equal(H.to_host_f64(run.bucket), want32), f"flags {flags}"
+    if p > 1:
+        with pytest.raises(cf.CommFuseError) as ei:              # a landing buffer per hop is a CF_PERSISTENT matter here
+            run.run_schedule(cf.CF_SERIAL)
+        assert ei.value.status == cf.CF_ERR_INVALID_ARG
 
 
 # ----------------------------------------------------------------------------
