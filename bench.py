@@ -407,6 +407,11 @@ def main() -> int:
                                 pers.cs, 10, 2)
                 if tp < t[name][0]:
                     t[name] = (tp, mode)
+        # pairwise schedule on the same bucket: seven arrivals for the own slice, summed in one pass (36 B per element)
+        t_pw = min(time_calls(lambda: cf.run_schedule(pers.desc, cf.CF_KIND_DP_PAIR, pers.bufs, pers.cs, pers.xs, extra),
+                              pers.cs, 10, 2) for mode, extra in MODES if "persistent" in mode)
+        t_pw_c = time_calls(lambda: cf.run_schedule(pers.desc, cf.CF_KIND_DP_PAIR, pers.bufs, pers.cs, pers.xs,
+                                                    cf.CF_PERSISTENT | cf.CF_NO_COPY), pers.cs, 10, 2)
         steps_with_add = w5.p - 1
         dp = {"kernel_GBps": round(gbs, 1), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4),
               "us_per_reduce_kernel": round(t_k * 1e3, 1), "bytes_per_elem": 12,
@@ -414,7 +419,9 @@ def main() -> int:
               "rank_step_GBps_algorithmic": round(12.0 * c * steps_with_add / (t["overlapped"][0] * 1e-3) / 1e9, 1),
               "rank_step_GBps_with_copies": round(20.0 * c * steps_with_add / (t["overlapped"][0] * 1e-3) / 1e9, 1),
               "overlap_eff": round(overlap_eff(t), 3),
-              "us_compute_only": round(t["compute_only"][0] * 1e3, 1), "us_copy_only": round(t["copy_only"][0] * 1e3, 1)}
+              "us_compute_only": round(t["compute_only"][0] * 1e3, 1), "us_copy_only": round(t["copy_only"][0] * 1e3, 1),
+              "pairwise_rank_step_us": round(t_pw * 1e3, 1), "pairwise_us_compute_only": round(t_pw_c * 1e3, 1),
+              "pairwise_add_GBps": round(4.0 * (w5.p + 1) * c / (t_pw_c * 1e-3) / 1e9, 1)}
         log("dp", dp)
         del run, pers
         torch.cuda.empty_cache()

@@ -854,6 +854,19 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
     // Gradient bucket: nothing to fuse into -- the adds of a rank step, each on the landing buffer of its own hop
     // (ring: every hop's slice is a different one, Alg. 2 with the identity; pairwise: all arrivals are summed
     // into the own slice in round order), behind the one batched delivery
+    if (do_compute && kind == CF_KIND_DP_PAIR && p > 1 && r.mc > 0) {
+        // every round's arrival goes into the own slice: one pass that reads them all (same order of additions)
+        const float *srcs[cf::GemmParams::MAX_STEPS];
+        for (int j = 1; j < p; ++j)
+            srcs[j - 1] = static_cast<const float *>(landing(j));
+        if (cf_status st = check_pair_p(p))
+            return st;
+        hipError_t e = cf::launch_dp_reduce_multi(static_cast<float *>(b->O) + (int64_t)r.rank * r.mc, srcs, p - 1, r.mc, cs,
+                                                  num_cu_of_current_device());
+        if (e != hipSuccess)
+            return fail_hip(e, "gradient reduce launch");
+        return CF_OK;
+    }
     if (do_compute && is_dp_kind(kind)) {
         float *bucket = static_cast<float *>(b->O);
         for (int j = m; j < S; ++j) {

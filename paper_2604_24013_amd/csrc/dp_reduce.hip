@@ -43,6 +43,49 @@ __global__ __launch_bounds__(DP_THREADS) void dp_reduce_scalar_kernel(float *__r
         dst[i] = src[i] + dst[i];
 }
 
+// dst <- (((dst + src[0]) + src[1]) + ...) in ONE pass: the pairwise gradient reduce, where every round's arrival
+// is added to the same slice.  4 (n + 2) bytes per element instead of 12 n for n separate passes; the additions
+// are taken in the order of the separate passes, so the result is the same bit for bit.
+struct AddBatch {
+    static constexpr int MAX = 15;
+    const float *src[MAX];
+};
+
+__global__ __launch_bounds__(DP_THREADS) void dp_reduce_multi_kernel(f32x4_t *__restrict__ dst, AddBatch ab, int n_src,
+                                                                    int64_t n4)
+{
+    constexpr int U = 2;                             // vectors per lane: (n_src + 1) * U loads in flight
+    const int64_t base = (int64_t)blockIdx.x * DP_THREADS * U + threadIdx.x;
+    f32x4_t a[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (base + u * DP_THREADS < n4)
+            a[u] = __builtin_nontemporal_load(&dst[base + u * DP_THREADS]);
+    for (int s = 0; s < n_src; ++s) {
+        const f32x4_t *__restrict__ src = reinterpret_cast<const f32x4_t *>(ab.src[s]);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (base + u * DP_THREADS < n4)
+                a[u] = __builtin_nontemporal_load(&src[base + u * DP_THREADS]) + a[u];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (base + u * DP_THREADS < n4)
+            __builtin_nontemporal_store(a[u], &dst[base + u * DP_THREADS]);
+}
+
+__global__ __launch_bounds__(DP_THREADS) void dp_reduce_multi_scalar_kernel(float *__restrict__ dst, AddBatch ab, int n_src,
+                                                                           int64_t first, int64_t n)
+{
+    const int64_t stride = (int64_t)gridDim.x * DP_THREADS;
+    for (int64_t i = first + (int64_t)blockIdx.x * DP_THREADS + threadIdx.x; i < n; i += stride) {
+        float a = dst[i];
+        for (int s = 0; s < n_src; ++s)
+            a = ab.src[s][i] + a;
+        dst[i] = a;
+    }
+}
+
 // Several equally long device-to-device copies in ONE launch (the deliveries of a whole rank step when they are
 // all enqueued in front of the persistent kernel): workgroup b moves chunk b % per_buf of buffer b / per_buf,
 // 16 bytes per lane and access, four independent vectors in flight, non-temporal both ways like the reduce above.
@@ -110,6 +153,43 @@ hipError_t launch_dp_reduce(float *dst, const float *src, int64_t n, hipStream_t
         const int64_t cap = (int64_t)num_cu * 8;
         const int blocks = (int)(want < cap ? want : cap);
         hipLaunchKernelGGL(dp_reduce_scalar_kernel, dim3(blocks), dim3(DP_THREADS), 0, s, dst + done, src + done, rest);
+        return hipGetLastError();
+    }
+    return hipSuccess;
+}
+
+hipError_t launch_dp_reduce_multi(float *dst, const float *const *src, int n_src, int64_t n, hipStream_t s, int num_cu)
+{
+    if (n <= 0 || n_src <= 0)
+        return hipSuccess;
+    uintptr_t bits = reinterpret_cast<uintptr_t>(dst);
+    for (int i = 0; i < n_src; ++i)
+        bits |= reinterpret_cast<uintptr_t>(src[i]);
+    if (n_src > AddBatch::MAX || (bits & 15u) != 0) {        // one pass per source: the same additions in the same order
+        for (int i = 0; i < n_src; ++i) {
+            hipError_t e = launch_dp_reduce(dst, src[i], n, s, num_cu);
+            if (e != hipSuccess)
+                return e;
+        }
+        return hipSuccess;
+    }
+    AddBatch ab = {};
+    for (int i = 0; i < n_src; ++i)
+        ab.src[i] = src[i];
+    const int64_t n4 = n / 4;
+    if (n4 > 0) {
+        const int64_t per_wg = (int64_t)DP_THREADS * 2;
+        const int64_t want = (n4 + per_wg - 1) / per_wg;
+        if (want >= ((int64_t)1 << 31))
+            return hipErrorInvalidValue;
+        hipLaunchKernelGGL(dp_reduce_multi_kernel, dim3((unsigned)want), dim3(DP_THREADS), 0, s,
+                           reinterpret_cast<f32x4_t *>(dst), ab, n_src, n4);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess)
+            return e;
+    }
+    if (n4 * 4 < n) {
+        hipLaunchKernelGGL(dp_reduce_multi_scalar_kernel, dim3(1), dim3(DP_THREADS), 0, s, dst, ab, n_src, n4 * 4, n);
         return hipGetLastError();
     }
     return hipSuccess;

@@ -739,12 +739,16 @@ def test_full_size_pair_70b(flags):
     assert e <= TOL_BF16, f"{e:.3e}"
 
 
-def test_full_size_dp():
+@pytest.mark.parametrize("flags", [0, PERSISTENT_SERIAL])
+def test_full_size_dp(flags):
     w = inputs.CONFIGS["c5_dp"]
     data = inputs.make_dp(w)
     rank = 0
-    run = H.DpRun(w, data, rank)
-    run.run_schedule(0)
+    run = H.DpRun(w, data, rank, each=bool(flags & cf.CF_PERSISTENT))
+    if run.each:
+        for t in run.each:
+            t.fill_(float("nan"))
+    run.run_schedule(flags)
     c = w.m_chunk
     touched = {(rank - i - 1) % w.p: i for i in range(1, w.p)}
     for l in range(w.p):
