@@ -289,6 +289,10 @@ enum {
                             GEMMs dW += slice^T local_slice are then one GEMM whose contraction runs
                             over all p*m_chunk rows: dW is written once, not read and written p times
                             (the sum runs in row-block order, not in step order).
+                            Results are deterministic for a given launch, but not bit-identical to the
+                            one-kernel-per-step modes: with eight or sixteen (sub-)steps the workgroups of
+                            each XCD start their k loops at a different k-tile and wrap around, so the fp32
+                            sum over k is taken in a rotated order.
                             Bucket kinds (CF_KIND_DP, CF_KIND_DP_PAIR; fp32): there is no GEMM to fuse
                             into; the flag buys the deliveries of all hops as ONE batched copy launch
                             into recv_each, followed by the same add kernels in the same order.
