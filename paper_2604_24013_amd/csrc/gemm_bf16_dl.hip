@@ -317,11 +317,23 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         const int kk = ktb + kt + rot;
         return kk >= nk_all ? kk - nk_all : kk;
     };
-    auto issue_load = [&](int kt, int stage_a, int stage_w, auto idx_tag) {
+    // With WHOLE_K (K a multiple of the k-tile: no k tail anywhere) the load is issued without any test: a
+    // branch after every MFMA segment of the main loop costs more than it looks (measured: 4 - 6 % of the launch,
+    // and a select on the offset still 1 %).  A tile beyond the end of the range is then fetched for real -- the
+    // k-tile index wraps around (ktile), so it is a tile of the matrix -- into a stage that nobody reads.
+    auto issue_load = [&](int kt, int stage_a, int stage_w, auto idx_tag, auto whole_k_tag) {
         constexpr int idx = decltype(idx_tag)::value;
+        constexpr bool WHOLE_K = decltype(whole_k_tag)::value;
         const int k0 = ktile(kt) * BK;
         const unsigned sa = lds_base + stage_a * A_BYTES + wave * 1024;
         const unsigned sw = lds_base + W_BASE + stage_w * B_BYTES + wave * 1024;
+        if constexpr (WHOLE_K) {
+            if constexpr (idx < A_LD)
+                direct_load_16(a_rsrc, a_off[idx], k0 * a_kstep, sa + idx * NW * 1024);
+            else
+                direct_load_16(w_rsrc, b_off[idx - A_LD], k0 * w_kstep, sw + (idx - A_LD) * NW * 1024);
+            return;
+        }
         const bool full = kt < nk && (k0 + BK) <= K;     // uniform: the common case needs no per-lane test
         if (full) {
             if constexpr (idx < A_LD)
@@ -358,14 +370,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                                    sw + (idx - A_LD) * NW * 1024);
             }
         } else {
-            if constexpr (lo + 0 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 0>{});
-            if constexpr (lo + 1 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 1>{});
-            if constexpr (lo + 2 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 2>{});
-            if constexpr (lo + 3 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 3>{});
-            if constexpr (lo + 4 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 4>{});
-            if constexpr (lo + 5 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 5>{});
-            if constexpr (lo + 6 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 6>{});
-            if constexpr (lo + 7 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 7>{});
+            if constexpr (lo + 0 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 0>{}, std::false_type{});
+            if constexpr (lo + 1 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 1>{}, std::false_type{});
+            if constexpr (lo + 2 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 2>{}, std::false_type{});
+            if constexpr (lo + 3 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 3>{}, std::false_type{});
+            if constexpr (lo + 4 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 4>{}, std::false_type{});
+            if constexpr (lo + 5 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 5>{}, std::false_type{});
+            if constexpr (lo + 6 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 6>{}, std::false_type{});
+            if constexpr (lo + 7 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 7>{}, std::false_type{});
         }
     };
 
@@ -468,28 +480,29 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             acc[q / TN][q % TN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[q % TN], af[q / TN], acc[q / TN][q % TN], 0, 0, 0);
     };
     auto phase = [&](const bf16x8_t (&afc)[TM], const bf16x8_t (&wfc)[TN], bool do_read, int sa_n, int sw_n, int ks_n,
-                     bf16x8_t (&afn)[TM], bf16x8_t (&wfn)[TN], int kt_l, int sa_l, int sw_l, auto lo_tag, auto n_tag) {
+                     bf16x8_t (&afn)[TM], bf16x8_t (&wfn)[TN], int kt_l, int sa_l, int sw_l, auto lo_tag, auto n_tag,
+                     auto whole_k_tag) {
         constexpr int LO = decltype(lo_tag)::value, NL = decltype(n_tag)::value;   // load slots of this phase
         if (do_read)
             read_frags(sa_n, sw_n, ks_n, afn, wfn);
         mfma_seg(afc, wfc, std::integral_constant<int, 0>{});
         interleave_mfma_reads<NREAD, (NREAD + MPS - 1) / MPS>();
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (NL > 0) issue_load(kt_l, sa_l, sw_l, std::integral_constant<int, LO>{});
+        if constexpr (NL > 0) issue_load(kt_l, sa_l, sw_l, std::integral_constant<int, LO>{}, whole_k_tag);
         if constexpr (NSEG > 1) {
             mfma_seg(afc, wfc, std::integral_constant<int, 1>{});
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (NL > 1) issue_load(kt_l, sa_l, sw_l, std::integral_constant<int, LO + 1>{});
+            if constexpr (NL > 1) issue_load(kt_l, sa_l, sw_l, std::integral_constant<int, LO + 1>{}, whole_k_tag);
         }
         if constexpr (NSEG > 2) {
             mfma_seg(afc, wfc, std::integral_constant<int, 2>{});
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (NL > 2) issue_load(kt_l, sa_l, sw_l, std::integral_constant<int, LO + 2>{});
+            if constexpr (NL > 2) issue_load(kt_l, sa_l, sw_l, std::integral_constant<int, LO + 2>{}, whole_k_tag);
         }
         if constexpr (NSEG > 3) {
             mfma_seg(afc, wfc, std::integral_constant<int, 3>{});
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (NL > 3) issue_load(kt_l, sa_l, sw_l, std::integral_constant<int, LO + 3>{});
+            if constexpr (NL > 3) issue_load(kt_l, sa_l, sw_l, std::integral_constant<int, LO + 3>{}, whole_k_tag);
         }
     };
     using c0 = std::integral_constant<int, 0>;
@@ -551,28 +564,35 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         read_frags(0, 0, 0, af0, wf0);
         __builtin_amdgcn_sched_barrier(0);
 
-        int cur_a = 0, cur_w = 0;                        // stages of tile kt
-        int prev_a = NSA - 1;                            // left-operand stage of tile kt-1 (= of tile kt+NS)
-        for (int kt = 0; kt + 1 < nk; ++kt) {
-            const int nxt_a = (cur_a + 1 == NSA) ? 0 : cur_a + 1;
-            const int nxt_w = (cur_w + 1 == NS) ? 0 : cur_w + 1;
-            phase(af0, wf0, true, cur_a, cur_w, 1, af1, wf1, kt + NS, prev_a, 0, c0{}, cALD{});
-            phase(af1, wf1, true, cur_a, cur_w, 2, af0, wf0, 0, 0, 0, c0{}, c0{});
-            phase(af0, wf0, true, cur_a, cur_w, 3, af1, wf1, 0, 0, 0, c0{}, c0{});
-            wait_vmcnt<(NS - 2) * LPT + A_LD>();
-            __syncthreads();
-            __builtin_amdgcn_sched_barrier(0);
-            phase(af1, wf1, true, nxt_a, nxt_w, 0, af0, wf0, kt + NS, 0, cur_w, cALD{}, cLR{});
-            prev_a = cur_a;
-            cur_a = nxt_a;
-            cur_w = nxt_w;
-        }
-        if (nk > 0) {                                    // last tile: nothing follows it
-            phase(af0, wf0, true, cur_a, cur_w, 1, af1, wf1, 0, 0, 0, c0{}, c0{});
-            phase(af1, wf1, true, cur_a, cur_w, 2, af0, wf0, 0, 0, 0, c0{}, c0{});
-            phase(af0, wf0, true, cur_a, cur_w, 3, af1, wf1, 0, 0, 0, c0{}, c0{});
-            phase(af1, wf1, false, 0, 0, 0, af0, wf0, 0, 0, 0, c0{}, c0{});
-        }
+        // the steady state, once per kind of k range (see issue_load)
+        auto steady = [&](auto wk) {
+            int cur_a = 0, cur_w = 0;                        // stages of tile kt
+            int prev_a = NSA - 1;                            // left-operand stage of tile kt-1 (= of tile kt+NS)
+            for (int kt = 0; kt + 1 < nk; ++kt) {
+                const int nxt_a = (cur_a + 1 == NSA) ? 0 : cur_a + 1;
+                const int nxt_w = (cur_w + 1 == NS) ? 0 : cur_w + 1;
+                phase(af0, wf0, true, cur_a, cur_w, 1, af1, wf1, kt + NS, prev_a, 0, c0{}, cALD{}, wk);
+                phase(af1, wf1, true, cur_a, cur_w, 2, af0, wf0, 0, 0, 0, c0{}, c0{}, wk);
+                phase(af0, wf0, true, cur_a, cur_w, 3, af1, wf1, 0, 0, 0, c0{}, c0{}, wk);
+                wait_vmcnt<(NS - 2) * LPT + A_LD>();
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+                phase(af1, wf1, true, nxt_a, nxt_w, 0, af0, wf0, kt + NS, 0, cur_w, cALD{}, cLR{}, wk);
+                prev_a = cur_a;
+                cur_a = nxt_a;
+                cur_w = nxt_w;
+            }
+            if (nk > 0) {                                    // last tile: nothing follows it
+                phase(af0, wf0, true, cur_a, cur_w, 1, af1, wf1, 0, 0, 0, c0{}, c0{}, wk);
+                phase(af1, wf1, true, cur_a, cur_w, 2, af0, wf0, 0, 0, 0, c0{}, c0{}, wk);
+                phase(af0, wf0, true, cur_a, cur_w, 3, af1, wf1, 0, 0, 0, c0{}, c0{}, wk);
+                phase(af1, wf1, false, 0, 0, 0, af0, wf0, 0, 0, 0, c0{}, c0{}, wk);
+            }
+        };
+        if (K % BK == 0)
+            steady(std::true_type{});
+        else
+            steady(std::false_type{});
 
     } else {
         // Variant for the small tiles (few MFMAs per slice): a tile's loads go out together right

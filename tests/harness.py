@@ -78,6 +78,7 @@ class RsRun:
         return [to_host_f64(o) for o in outs]
 
     def run_schedule(self, flags=0):
+        torch.cuda.synchronize()     # what the test enqueued on other streams (fills, uploads) comes first
         cf.run_schedule(self.desc, cf.CF_KIND_RS, self.bufs, self.cs, self.xs, flags)
         self.cs.synchronize()
 
@@ -112,6 +113,7 @@ class AgRun:
         return to_host_f64(self.O)
 
     def run_schedule(self, flags=0):
+        torch.cuda.synchronize()     # what the test enqueued on other streams (fills, uploads) comes first
         cf.run_schedule(self.desc, cf.CF_KIND_AG, self.bufs, self.cs, self.xs, flags)
         self.cs.synchronize()
 
@@ -140,6 +142,7 @@ class DpRun:
         return to_host_f64(self.bucket)
 
     def run_schedule(self, flags=0):
+        torch.cuda.synchronize()     # what the test enqueued on other streams (fills, uploads) comes first
         cf.run_schedule(self.desc, cf.CF_KIND_DP, self.bufs, self.cs, self.xs, flags)
         self.cs.synchronize()
 
@@ -202,6 +205,7 @@ class RsPairRun(RsRun):
         return [to_host_f64(o) for o in outs]
 
     def run_schedule(self, flags=0):
+        torch.cuda.synchronize()     # what the test enqueued on other streams (fills, uploads) comes first
         cf.run_schedule(self.desc, cf.CF_KIND_RS_PAIR, self.bufs, self.cs, self.xs, flags)
         self.cs.synchronize()
 
@@ -217,6 +221,7 @@ class DpPairRun(DpRun):
         return to_host_f64(self.bucket)
 
     def run_schedule(self, flags=0):
+        torch.cuda.synchronize()     # what the test enqueued on other streams (fills, uploads) comes first
         cf.run_schedule(self.desc, cf.CF_KIND_DP_PAIR, self.bufs, self.cs, self.xs, flags)
         self.cs.synchronize()
 
@@ -268,5 +273,6 @@ class WgradRun:
         return outs
 
     def run_schedule(self, flags=0):
+        torch.cuda.synchronize()     # what the test enqueued on other streams (fills, uploads) comes first
         cf.run_schedule(self.desc, self.kind, self.bufs, self.cs, self.xs, flags)
         self.cs.synchronize()

@@ -178,6 +178,7 @@ def test_attn_rs_steps_and_schedule(shape, layout):
             bufs = cf.make_attn_buffers(Qd, Kd, Vd, Wd, attn_out, O, stage, slot, send, sink, each if use_each else None)
             for flags in (0, cf.CF_SERIAL, cf.CF_POISON, cf.CF_GRAPH, cf.CF_FUSED_COPY, cf.CF_DEVICE_WAIT):
                 O.fill_(float("nan"))
+                torch.cuda.synchronize()                     # the fill runs on another stream than the schedule
                 cf.run_attn_schedule(desc, bufs, cs, xs, flags)
                 cf.device_status(cs)
                 e = H.rel_err(H.to_host_f64(O), ref[-1])
@@ -190,6 +191,7 @@ def test_attn_rs_steps_and_schedule(shape, layout):
         PS = cf.CF_PERSISTENT | cf.CF_SERIAL
         for flags in (PS, PS | cf.CF_GRAPH, PS | cf.CF_POISON):
             O.fill_(float("nan"))
+            torch.cuda.synchronize()
             cf.run_attn_schedule(desc, bufs, cs, xs, flags)
             cf.run_attn_schedule(desc, bufs, cs, xs, flags)
             cs.synchronize()

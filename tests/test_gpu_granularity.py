@@ -161,6 +161,7 @@ def test_dp_granularity(p, m, c):
     pers = H.DpRun(w, data, rank, m=m, each=True)                 # the m sub-slices of a hop stacked in its landing buffer
     for t in pers.each:
         t.fill_(float("nan"))
+    torch.cuda.synchronize()                         # the fills run on another stream than the schedule
     pers.run_schedule(cf.CF_PERSISTENT | cf.CF_SERIAL)
     assert np.array_equal(H.to_host_f64(pers.bucket), want32)
 

@@ -161,6 +161,7 @@ def test_dp_pair_reduced(p, c):
     pers = H.DpPairRun(w, data, rank, each=True)
     for t in pers.each:
         t.fill_(float("nan"))
+    torch.cuda.synchronize()                         # the fills run on another stream than the schedule
     pers.run_schedule(cf.CF_PERSISTENT | cf.CF_SERIAL)
     assert np.array_equal(H.to_host_f64(pers.bucket), ref)
     # normally distributed gradients: p-1 fp32 additions in round order

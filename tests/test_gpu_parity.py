@@ -748,6 +748,7 @@ def test_full_size_dp(flags):
     if run.each:
         for t in run.each:
             t.fill_(float("nan"))
+        torch.cuda.synchronize()                     # the fills run on another stream than the schedule
     run.run_schedule(flags)
     c = w.m_chunk
     touched = {(rank - i - 1) % w.p: i for i in range(1, w.p)}
