@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 SETTLE_S = 0.06               # untimed load before every timed region (see time_calls)
-TRAFFIC_DOWN_RANK_STEP = 1230.7e6   # measured, see the roofline object
+TRAFFIC_DOWN_RANK_STEP = 1253.4e6   # measured, see the roofline object
 
 
 def log(*a):
