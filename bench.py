@@ -56,7 +56,7 @@ def main() -> int:
 
     from paper_2604_24013_amd import binding as cf
     from paper_2604_24013_amd import inputs
-    from tests import harness as H
+    from paper_2604_24013_amd import emulated_rank as H
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     cf.load()
@@ -141,7 +141,7 @@ def main() -> int:
     ddn = inputs.make_rs(dn)
     rs = H.RsRun(dn, ddn, 0, each=True)
     rs.A = ag.O                                   # H is handed over on the device, in bf16
-    rs.bufs = cf.make_buffers(rs.A, rs.W, rs.O, rs.stage, rs.slot, rs.send, None, rs.each)
+    rs.bufs = cf.make_buffers(rs.A, rs.W, rs.O, rs.stage, rs.slot, rs.send, None, rs.each, rs.send_each)
     rs.cs, rs.xs = ag.cs, ag.xs                   # one compute stream, one copy stream for the pair
 
     def pair(flags):
@@ -309,8 +309,9 @@ def main() -> int:
         stage32 = [mk32(mc8, d_model).normal_() for _ in range(p8 - 1)]
         PERS = tuple(m for m in MODES if m[0] in BASIC_NAMES or "persistent" in m[0])
         each32 = [mk32(mc8, d_model) for _ in range(p8 - 1)]
-        keep = [mk32(mc8, d_model), [mk32(mc8, d_model) for _ in range(2)], [mk32(mc8, d_model) for _ in range(2)]]
-        bufs = cf.make_buffers(G_up, W_up, keep[0], stage32, keep[1], keep[2], None, each32)   # (the tensors must outlive bufs)
+        keep = [mk32(mc8, d_model), [mk32(mc8, d_model) for _ in range(2)], [mk32(mc8, d_model) for _ in range(2)],
+                [mk32(mc8, d_model) for _ in range(p8 - 1)]]
+        bufs = cf.make_buffers(G_up, W_up, keep[0], stage32, keep[1], keep[2], None, each32, keep[3])   # (the tensors must outlive bufs)
         t = timed(cf.layer_desc(p8, 0, mc8, d_model, d_ff, "bf16", "f32", cf.CF_W_NK), cf.CF_KIND_RS, bufs, PERS)
         backward["up_dgrad_rs"] = {"us": round(t[0] * 1e3, 1), "tflops": round(flops / (t[0] * 1e-3) / 1e12, 1), "mode": t[1]}
         # the arriving slices land in ONE gathered buffer (own slice in row block rank = 0, hop i in row block
@@ -363,8 +364,8 @@ def main() -> int:
         attn_out = torch.empty((pa * mca, ha * 128), dtype=torch.bfloat16, device=H.DEV)   # all p slices (persistent mode)
         mk32 = lambda: torch.empty((mca, Da), dtype=torch.float32, device=H.DEV)
         stage_a = [mk32().normal_() for _ in range(pa - 1)]
-        keep = [mk32(), [mk32(), mk32()], [mk32(), mk32()], [mk32() for _ in range(pa - 1)]]
-        abufs = cf.make_attn_buffers(Qa, Ka, Va, Woa, attn_out, keep[0], stage_a, keep[1], keep[2], None, keep[3])
+        keep = [mk32(), [mk32(), mk32()], [mk32(), mk32()], [mk32() for _ in range(pa - 1)], [mk32() for _ in range(pa - 1)]]
+        abufs = cf.make_attn_buffers(Qa, Ka, Va, Woa, attn_out, keep[0], stage_a, keep[1], keep[2], None, keep[3], keep[4])
         cs, xs = torch.cuda.Stream(), torch.cuda.Stream()
         t_attn = time_calls(lambda: cf.attn_slice(adesc, 1, Qa, Ka, Va, attn_out, cs), cs, 50, W)
         fl_attn = 4.0 * Ba * ha * (Sa // pa) * Sa * 128

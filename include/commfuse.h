@@ -252,6 +252,17 @@ typedef struct {
                                      the last step adds them all in its epilogue
                                      (commfuse_rs_pair_last_step).  Bucket kinds (CF_KIND_DP,
                                      CF_KIND_DP_PAIR): with CF_PERSISTENT only.                  */
+    float *const *send_each;      /* reduce-scatter kinds, optional (NULL = use send_slot[]): host
+                                     array of p-1 device buffers [m_chunk x n] fp32, row stride ldo,
+                                     one per sending step: the B_out of step i < p-1 (Alg. 2
+                                     "B_out <- O"; with m > 1 the m blocks of hop i stacked by rows)
+                                     is stored to send_each[i] and stays there, send_slot[] is then
+                                     unused, and peer_sink[i], if given, is copied from it.  No
+                                     send buffer is reused inside the call, so no step waits for an
+                                     earlier send to drain.  Required with CF_PERSISTENT when
+                                     p > 1: the steps of that launch run side by side and each
+                                     needs a B_out of its own.  None may alias O or a landing
+                                     buffer.                                                      */
 } cf_buffers;
 
 enum {
@@ -272,9 +283,10 @@ enum {
                             the add of B_in / the arrival of the slice does), nothing is launched or
                             drained between steps, and because a step no longer has to fill the chip
                             alone the tiles can be larger.  Needs cf_buffers.recv_each (every hop's
-                            delivery stays where it landed), no peer_sink (the send slots, which
-                            steps that now run side by side share, are left with unspecified
-                            contents), and CF_SERIAL: the
+                            delivery stays where it landed), for the reduce-scatter kinds
+                            cf_buffers.send_each (every step stores the B_out of Alg. 2 into a
+                            buffer of its own; peer_sink, if given, is copied from those after the
+                            launch), and CF_SERIAL: the
                             deliveries are enqueued before the kernel on the compute stream -- a
                             kernel that holds its compute units for the whole rank step starves
                             concurrent blit copies.  (The kernel can also wait for per-step delivery
@@ -378,6 +390,7 @@ typedef struct {
     float *send_slot[2];
     void *const *peer_sink;
     void *const *recv_each;
+    float *const *send_each;
 } cf_attn_buffers;
 
 /* A whole rank step of Alg. 4 with the overlap and the flags of commfuse_run_schedule.

@@ -52,6 +52,7 @@ class Buffers(ctypes.Structure):
         ("slot", ctypes.c_void_p * 2), ("send_slot", ctypes.c_void_p * 2),
         ("peer_sink", ctypes.POINTER(ctypes.c_void_p)),
         ("recv_each", ctypes.POINTER(ctypes.c_void_p)),
+        ("send_each", ctypes.POINTER(ctypes.c_void_p)),
     ]
 
 
@@ -72,6 +73,7 @@ class AttnBuffers(ctypes.Structure):
         ("slot", ctypes.c_void_p * 2), ("send_slot", ctypes.c_void_p * 2),
         ("peer_sink", ctypes.POINTER(ctypes.c_void_p)),
         ("recv_each", ctypes.POINTER(ctypes.c_void_p)),
+        ("send_each", ctypes.POINTER(ctypes.c_void_p)),
     ]
 
 
@@ -242,7 +244,8 @@ def _table(seq_):
     return ctypes.cast(t, ctypes.POINTER(ctypes.c_void_p)), t
 
 
-def make_attn_buffers(Q, K, V, Wo, attn_out, O, peer_stage, slot, send_slot, peer_sink=None, recv_each=None) -> AttnBuffers:
+def make_attn_buffers(Q, K, V, Wo, attn_out, O, peer_stage, slot, send_slot, peer_sink=None, recv_each=None,
+                      send_each=None) -> AttnBuffers:
     b = AttnBuffers()
     b.Q, b.K, b.V, b.Wo, b.attn_out, b.O = _ptr(Q), _ptr(K), _ptr(V), _ptr(Wo), _ptr(attn_out), _ptr(O)
     b.peer_stage, b._k0 = _table(peer_stage)
@@ -250,6 +253,7 @@ def make_attn_buffers(Q, K, V, Wo, attn_out, O, peer_stage, slot, send_slot, pee
     b.send_slot[0], b.send_slot[1] = _ptr(send_slot[0]), _ptr(send_slot[1])
     b.peer_sink, b._k1 = _table(peer_sink)
     b.recv_each, b._k2 = _table(recv_each)
+    b.send_each, b._k3 = _table(send_each)
     return b
 
 
@@ -275,7 +279,8 @@ def dp_reduce_step(p: int, rank: int, step: int, bucket, chunk_elems: int, recv,
 
 
 def make_buffers(A_or_own_shard, W, O, peer_stage: Sequence, slot: Sequence, send_slot: Sequence = (None, None),
-                 peer_sink: Optional[Sequence] = None, recv_each: Optional[Sequence] = None) -> Buffers:
+                 peer_sink: Optional[Sequence] = None, recv_each: Optional[Sequence] = None,
+                 send_each: Optional[Sequence] = None) -> Buffers:
     """Fills a ``cf_buffers``.  The returned object keeps the pointer tables alive;
     the caller keeps the tensors alive."""
     b = Buffers()
@@ -298,6 +303,7 @@ def make_buffers(A_or_own_shard, W, O, peer_stage: Sequence, slot: Sequence, sen
         b._each_keepalive = each
     else:
         b.recv_each = None
+    b.send_each, b._send_each_keepalive = _table(send_each)
     return b
 
 

@@ -626,6 +626,11 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
         return each ? static_cast<char *>(b->recv_each[j / m - 1]) + (size_t)(j % m) * slot_bytes : b->slot[j & 1];
     };
     const bool need_done = !each || (b->peer_sink != nullptr && do_copy && !(kind == CF_KIND_AG || is_wgrad_kind(kind)));
+    // B_out of sub-step j (Alg. 2 "B_out <- O"): a buffer of its own per sending hop (send_each), else the
+    // two alternating send slots
+    auto send_buf = [&](int j) -> float * {
+        return b->send_each != nullptr ? b->send_each[j / m] + (size_t)(j % m) * r.mc * r.ldo : b->send_slot[j & 1];
+    };
 
     // event layout: [0] start, [1] end, ready[j] = 2+j, done[j] = 2+S+j, sunk[j] = 2+2S+j
     std::vector<hipEvent_t> ev;
@@ -692,13 +697,14 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
             job.dst = landing(j + 1);
             job.bytes = slot_bytes;
         }
-        // B_out slot (j % 2) was last sent at sub-step j-2
-        const bool wait_sunk = !serial && do_copy && b->peer_sink != nullptr && sends(j) && sends(j - 2);
+        // B_out slot (j % 2) was last sent at sub-step j-2 (a send buffer per hop is never reused)
+        const bool wait_sunk = !serial && do_copy && b->peer_sink != nullptr && sends(j) && sends(j - 2) &&
+                               b->send_each == nullptr;
         if (kind == CF_KIND_RS) {
             if (wait_sunk)
                 CF_HIP(hipStreamWaitEvent(cs, sunk(j - 2), 0));
             const float *recv = receives(j) ? static_cast<const float *>(landing(j)) : nullptr;
-            float *out = sends(j) ? b->send_slot[j & 1] : static_cast<float *>(b->O) + (size_t)(j % m) * r.mc * r.ldo;
+            float *out = sends(j) ? send_buf(j) : static_cast<float *>(b->O) + (size_t)(j % m) * r.mc * r.ldo;
             if (attn != nullptr) {                 // Alg. 4: attention of slice l, then the projection of its output
                 st = launch_attention(*attn, chunk_index(CF_KIND_RS, p, r.rank, j), cs);
                 if (st == CF_OK)
@@ -723,7 +729,7 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
                 CF_HIP(hipStreamWaitEvent(cs, sunk(j - 2), 0));
             float *acc = static_cast<float *>(b->O);
             const float *recv = j == 0 ? nullptr : (j == 1 ? acc : static_cast<const float *>(b->slot[j & 1]));
-            float *out = !last ? b->send_slot[j & 1] : acc;
+            float *out = !last ? send_buf(j) : acc;
             if (!keep_all)
                 st = rs_pair_step_impl(r, j, b->A_or_own_shard, b->W, recv, acc, out, cs);
             else if (!last)
@@ -751,7 +757,7 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
             return CF_OK;
         const void *src;
         if (is_rs_kind(kind)) {
-            src = b->send_slot[j & 1];
+            src = send_buf(j);
         } else if (kind == CF_KIND_AG || is_wgrad_kind(kind)) {
             src = receives(j) ? landing(j)
                               : static_cast<const char *>(b->A_or_own_shard) + (size_t)(j % m) * slot_bytes;
@@ -791,9 +797,9 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
 // CF_PERSISTENT: all (sub-)steps of a rank step in ONE launch of the chunk-GEMM kernel (its work-item loop) --
 // reduce-scatter, all-gather, pairwise reduce-scatter with deferred aggregation, the projection of the attention
 // layer (after one attention launch for all slices) -- or, for the weight gradient, as one GEMM over the gathered
-// operand; the deliveries are enqueued before it on the same stream.  The steps of one launch run side by side:
-// the send slots, which consecutive steps share, end up with unspecified contents (nothing reads them here:
-// this mode takes no peer_sink).
+// operand; the deliveries are enqueued before it on the same stream.  The steps of one launch run side by side,
+// so every sending step of a reduce-scatter kind stores its B_out into a buffer of its own (cf_buffers.send_each);
+// the emulated sends into peer_sink, if any, are copied from those after the launch.
 cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, hipStream_t cs, uint32_t flags,
                              const AttnCtx *attn = nullptr)
 {
@@ -885,8 +891,9 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
         all.m = 1;
         all.mc = r.mc * S;                           // all rows of the gathered and the local operand
         const void *moving = reinterpret_cast<const void *>(gathered);
-        return kind == CF_KIND_WGRAD_X ? wgrad_step_impl(all, 0, moving, b->W, static_cast<float *>(b->O), cs)
-                                       : wgrad_step_impl(all, 0, b->W, moving, static_cast<float *>(b->O), cs);
+        if (cf_status st = kind == CF_KIND_WGRAD_X ? wgrad_step_impl(all, 0, moving, b->W, static_cast<float *>(b->O), cs)
+                                                   : wgrad_step_impl(all, 0, b->W, moving, static_cast<float *>(b->O), cs))
+            return st;
     }
     // Alg. 4: the attention of a slice depends on nothing that travels, so the attention of ALL p query slices
     // is one launch with a chip-filling grid (no key split, no merge); its output [p slices x B*S/p x heads*D_h]
@@ -894,7 +901,7 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
     if (do_compute && attn != nullptr && r.mc > 0)
         if (cf_status st = launch_attention(*attn, 0, cs, p))
             return st;
-    if (do_compute && r.mc > 0 && r.n > 0) {
+    if (do_compute && !is_wgrad_kind(kind) && r.mc > 0 && r.n > 0) {
         if (r.k == 0)
             return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT needs k > 0");
         cf::GemmParams gp;
@@ -910,7 +917,7 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
                 gp.A_step[j] = static_cast<const char *>(b->A_or_own_shard) +
                                (size_t)pair_slice(p, r.rank, j) * r.mc * r.lda * in_elem(r);
                 gp.recv_step[j] = last && p > 1 ? static_cast<const float *>(b->recv_each[0]) : nullptr;
-                gp.out_step[j] = last ? b->O : static_cast<void *>(b->send_slot[j & 1]);
+                gp.out_step[j] = last ? b->O : static_cast<void *>(b->send_each[j]);
                 gp.flag_step[j] = nullptr;
                 if (last)
                     for (int t = 1; t < p - 1; ++t)
@@ -921,7 +928,7 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
             if (kind == CF_KIND_RS) {
                 gp.A_step[j] = static_cast<const char *>(b->A_or_own_shard) + (size_t)c * r.mc * r.lda * in_elem(r);
                 gp.recv_step[j] = receives(j) ? static_cast<const float *>(landing(j)) : nullptr;
-                gp.out_step[j] = sends(j) ? static_cast<void *>(b->send_slot[j & 1])
+                gp.out_step[j] = sends(j) ? static_cast<void *>(b->send_each[j / m] + (size_t)(j % m) * r.mc * r.ldo)
                                           : static_cast<void *>(static_cast<float *>(b->O) + (size_t)(j % m) * r.mc * r.ldo);
             } else {
                 gp.A_step[j] = receives(j) ? landing(j)
@@ -934,6 +941,25 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
         hipError_t e = cf::launch_gemm_bf16(gp, r.w_kn, r.bf16_out, cs, gp.num_cu);
         if (e != hipSuccess)
             return fail_hip(e, "persistent rank-step launch");
+    }
+    // emulated sends (Alg. 2 "p2p_send(B_out)", Alg. 1 "p2p_send(B_out)" of the slice in hand): hop i < p-1 into
+    // peer_sink[i], all hops as one batched copy where the buffers allow it
+    if (b->peer_sink != nullptr && do_copy && slot_bytes > 0) {
+        const void *srcs[cf::GemmParams::MAX_STEPS];
+        void *dsts[cf::GemmParams::MAX_STEPS];
+        for (int i = 0; i < p - 1; ++i) {
+            srcs[i] = is_rs_kind(kind) ? static_cast<const void *>(b->send_each[i])
+                                       : (i == 0 ? b->A_or_own_shard : static_cast<const void *>(b->recv_each[i - 1]));
+            dsts[i] = b->peer_sink[i];
+        }
+        if (cf::copy_batch_takes(srcs, dsts, p - 1, slot_bytes * m)) {
+            hipError_t e = cf::launch_copy_batch(srcs, dsts, p - 1, slot_bytes * m, cs);
+            if (e != hipSuccess)
+                return fail_hip(e, "send copy launch");
+        } else {
+            for (int i = 0; i < p - 1; ++i)
+                CF_HIP(hipMemcpyAsync(dsts[i], srcs[i], slot_bytes * m, hipMemcpyDeviceToDevice, cs));
+        }
     }
     return CF_OK;
 }
@@ -970,7 +996,20 @@ cf_status check_buffers(const Resolved &r, int kind, const cf_buffers *b, uint32
                     return fail(CF_ERR_NULL_PTR, "peer_sink[%d] is NULL", i);
             }
         }
-        if (is_rs_kind(kind)) {
+        if (is_rs_kind(kind) && b->send_each != nullptr) {
+            for (int i = 0; i < r.p - 1; ++i) {
+                if (b->send_each[i] == nullptr || b->send_each[i] == b->O)
+                    return fail(CF_ERR_NULL_PTR, "send_each[%d] is NULL or aliases O", i);
+                if (!aligned16(b->send_each[i]))
+                    return fail(CF_ERR_MISALIGNED, "send_each[%d] must be 16-byte aligned", i);
+                for (int q = 0; q < r.p - 1; ++q)
+                    if ((q < i && b->send_each[q] == b->send_each[i]) ||
+                        (keep_all && b->recv_each[q] == static_cast<void *>(b->send_each[i])))
+                        return fail(CF_ERR_INVALID_ARG, "send_each[%d] aliases another send or landing buffer", i);
+            }
+        } else if (is_rs_kind(kind)) {
+            if (flags & CF_PERSISTENT)
+                return fail(CF_ERR_INVALID_ARG, "CF_PERSISTENT needs buffers->send_each (a B_out buffer per sending step)");
             if (b->send_slot[0] == nullptr || b->send_slot[1] == nullptr)
                 return fail(CF_ERR_NULL_PTR, "buffers->send_slot[0..1] must be set for the reduce-scatter path");
             if (b->send_slot[0] == b->send_slot[1])
@@ -1033,8 +1072,8 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
                         "CF_PERSISTENT needs bf16 operands (kinds RS, AG, RS_PAIR, weight gradient; the gradient-bucket kinds take "
                         "fp32) and at most %d (sub-)steps",
                         cf::GemmParams::MAX_STEPS);
-        if (bufs != nullptr && bufs->peer_sink != nullptr)
-            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT cannot feed peer_sink (nothing signals a finished step)");
+        if (bufs != nullptr && bufs->peer_sink != nullptr && is_dp_kind(kind))
+            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT does not feed peer_sink for the gradient-bucket kinds");
         if (bufs != nullptr && r.p > 1 && bufs->recv_each == nullptr)
             return fail(CF_ERR_INVALID_ARG, "CF_PERSISTENT needs buffers->recv_each (a landing buffer per hop)");
         // A kernel that holds its compute units for a whole rank step starves the blit kernels of concurrent
@@ -1076,9 +1115,11 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
         const void *st = bufs->peer_stage ? bufs->peer_stage[i] : nullptr;
         const void *sk = bufs->peer_sink ? bufs->peer_sink[i] : nullptr;
         const void *re = bufs->recv_each ? bufs->recv_each[i] : nullptr;
+        const void *se = bufs->send_each ? bufs->send_each[i] : nullptr;
         append_bytes(key, &st, sizeof(st));
         append_bytes(key, &sk, sizeof(sk));
         append_bytes(key, &re, sizeof(re));
+        append_bytes(key, &se, sizeof(se));
     }
     hipGraphExec_t exec = nullptr;
     {
@@ -1357,6 +1398,7 @@ cf_status commfuse_run_attn_schedule(const cf_attn_desc *desc, const cf_attn_buf
     b.send_slot[1] = ab->send_slot[1];
     b.peer_sink = ab->peer_sink;
     b.recv_each = ab->recv_each;
+    b.send_each = ab->send_each;
     std::vector<unsigned char> key;
     append_bytes(key, desc, sizeof(*desc));
     const char tag[8] = "attn";

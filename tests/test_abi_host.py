@@ -35,17 +35,17 @@ def test_header_functions_are_exported(lib):
 
 
 def test_struct_layout_matches_header():
-    # cf_layer_desc: 2 x int32, 6 x int64, 4 x int32 = 72 bytes; cf_buffers: 9 pointers
+    # cf_layer_desc: 2 x int32, 6 x int64, 4 x int32 = 72 bytes; cf_buffers: 11 pointers
     assert ctypes.sizeof(cf.LayerDesc) == 72
     assert cf.LayerDesc.m_chunk.offset == 8 and cf.LayerDesc.in_dtype.offset == 56
-    assert ctypes.sizeof(cf.Buffers) == 10 * ctypes.sizeof(ctypes.c_void_p)
+    assert ctypes.sizeof(cf.Buffers) == 11 * ctypes.sizeof(ctypes.c_void_p)
 
 
 def test_attention_struct_layout_matches_header():
-    # cf_attn_desc: 6 x int32, 3 x int64, int32 + float = 56 bytes; cf_attn_buffers: 13 pointers
+    # cf_attn_desc: 6 x int32, 3 x int64, int32 + float = 56 bytes; cf_attn_buffers: 14 pointers
     assert ctypes.sizeof(cf.AttnDesc) == 56
     assert cf.AttnDesc.n.offset == 24 and cf.AttnDesc.w_layout.offset == 48 and cf.AttnDesc.scale.offset == 52
-    assert ctypes.sizeof(cf.AttnBuffers) == 13 * ctypes.sizeof(ctypes.c_void_p)
+    assert ctypes.sizeof(cf.AttnBuffers) == 14 * ctypes.sizeof(ctypes.c_void_p)
 
 
 def test_backward_granularity_and_attention_bad_arguments(lib):
@@ -195,6 +195,16 @@ def test_schedule_argument_checks(lib):
     assert _status(cf.run_schedule, d, cf.CF_KIND_RS, bad, None, None, 0)[0] == cf.CF_ERR_NULL_PTR
     bad = cf.make_buffers(0x100, 0x200, 0x300, [0x1000, None, 0x3000], (0x400, 0x500), (0x600, 0x700))
     assert _status(cf.run_schedule, d, cf.CF_KIND_RS, bad, None, None, 0)[0] == cf.CF_ERR_NULL_PTR
+    # a B_out buffer per sending step: every entry set, aligned, distinct from O, the landing buffers and each other
+    each = [0x4000, 0x5000, 0x6000]
+    se = lambda tab, **kw: cf.make_buffers(0x100, 0x200, 0x300, t, (0x400, 0x500), (None, None), None, kw.get("each"), tab)
+    PS = cf.CF_PERSISTENT | cf.CF_SERIAL
+    assert _status(cf.run_schedule, d, cf.CF_KIND_RS, se([0x7000, None, 0x9000]), None, None, 0)[0] == cf.CF_ERR_NULL_PTR
+    assert _status(cf.run_schedule, d, cf.CF_KIND_RS, se([0x7000, 0x300, 0x9000]), None, None, 0)[0] == cf.CF_ERR_NULL_PTR
+    assert _status(cf.run_schedule, d, cf.CF_KIND_RS, se([0x7000, 0x8008, 0x9000]), None, None, 0)[0] == cf.CF_ERR_MISALIGNED
+    assert _status(cf.run_schedule, d, cf.CF_KIND_RS, se([0x7000, 0x8000, 0x7000]), None, None, 0)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.run_schedule, d, cf.CF_KIND_RS, se([0x7000, 0x5000, 0x9000], each=each), None, None, PS)[0] == cf.CF_ERR_INVALID_ARG
+    assert _status(cf.run_schedule, d, cf.CF_KIND_RS, se(None, each=each), None, None, PS)[0] == cf.CF_ERR_INVALID_ARG
     strided = cf.layer_desc(4, 0, 16, 32, 64, ldo=40)
     assert _status(cf.run_schedule, strided, cf.CF_KIND_RS_PAIR, ok, None, None, 0)[0] == cf.CF_ERR_UNSUPPORTED
     assert _status(cf.run_schedule, d, cf.CF_KIND_RS, ok, None, None, cf.CF_GRAPH)[0] == cf.CF_ERR_INVALID_ARG

@@ -187,16 +187,22 @@ def test_attn_rs_steps_and_schedule(shape, layout):
                     assert H.rel_err(H.to_host_f64(sink[i]), ref[i]) <= TOL_STEP, f"flags {flags} sink {i}"
         # all steps in two launches: the attention of all p slices, then the persistent projection + reduce-scatter
         attn_all = torch.full((p * mc, h * 128), float("nan"), dtype=torch.bfloat16, device=H.DEV)
-        bufs = cf.make_attn_buffers(Qd, Kd, Vd, Wd, attn_all, O, stage, slot, send, None, each)
+        send_each = [mk() for _ in range(p - 1)]
+        bufs = cf.make_attn_buffers(Qd, Kd, Vd, Wd, attn_all, O, stage, slot, send, None, each, send_each)
         PS = cf.CF_PERSISTENT | cf.CF_SERIAL
         for flags in (PS, PS | cf.CF_GRAPH, PS | cf.CF_POISON):
             O.fill_(float("nan"))
+            for t in send_each:
+                t.fill_(float("nan"))
             torch.cuda.synchronize()
             cf.run_attn_schedule(desc, bufs, cs, xs, flags)
             cf.run_attn_schedule(desc, bufs, cs, xs, flags)
             cs.synchronize()
             e = H.rel_err(H.to_host_f64(O), ref[-1])
             assert e <= TOL_STEP, f"persistent flags {flags}: {e:.3e}"
+            for i in range(p - 1):                       # every step's B_out
+                e = H.rel_err(H.to_host_f64(send_each[i]), ref[i])
+                assert e <= TOL_STEP, f"persistent flags {flags} B_out of step {i}: {e:.3e}"
         # the attention outputs themselves: slice l in row block l
         for l in (0, p - 1):
             one = torch.empty((mc, h * 128), dtype=torch.bfloat16, device=H.DEV)

@@ -83,9 +83,14 @@ def test_rs_pair_reduced(shape, layout, dtype):
             PS = cf.CF_PERSISTENT | cf.CF_SERIAL
             for flags in (PS, PS | cf.CF_GRAPH, PS | cf.CF_POISON):
                 pers.O.fill_(float("nan"))
+                for t in pers.send_each:
+                    t.fill_(float("nan"))
                 pers.run_schedule(flags)
                 pers.run_schedule(flags)
                 assert np.array_equal(H.to_host_f64(pers.O), outs[-1]), f"rank {rank} flags {flags} (persistent)"
+                for i in range(p - 1):               # the partial every step sends to its partner
+                    assert np.array_equal(H.to_host_f64(pers.send_each[i]), outs[i]), \
+                        f"rank {rank} flags {flags} (persistent) B_out of step {i}"
 
 
 def test_rs_pair_deferred_with_the_staged_kernel():
@@ -175,42 +180,44 @@ def test_dp_pair_reduced(p, c):
     assert np.array_equal(H.to_host_f64(pers.bucket), got)       # the same adds in the same order
 
 
-def _sample_rows(mc, rng, extra=6):
-    fixed = {0, 1, mc - 1, mc // 2, min(255, mc - 1), min(256, mc - 1), min(127, mc - 1), min(128, mc - 1)}
-    fixed |= set(int(x) for x in rng.integers(0, mc, size=extra))
-    return sorted(fixed)
+_full_refs = {}
+
+
+def _full_ref(name, rank):
+    """Seeded inputs and the oracle's outputs of every step of a full-size configuration (computed once)."""
+    if (name, rank) not in _full_refs:
+        w = inputs.CONFIGS[name]
+        data = inputs.make_rs(w, salt=12)
+        ref = oracle.rs_pair_rank_steps(inputs.as_f64(data["A"], w.dtype), inputs.as_f64(data["W"], w.dtype),
+                                        [None] + [r.astype(np.float64) for r in data["R"][1:]], w.p, rank)
+        _full_refs[(name, rank)] = (data, ref)
+    return _full_refs[(name, rank)]
 
 
 @pytest.mark.parametrize("keep_all", [False, True])
 @pytest.mark.parametrize("flags", [0, cf.CF_GRAPH, cf.CF_PERSISTENT | cf.CF_SERIAL])
 @pytest.mark.parametrize("name", ["c2_rs_7b", "c4_rs_70b_down"])
 def test_full_size_rs_pair(name, flags, keep_all):
+    """Full benchmark sizes; every element of every step's output (the partials sent to the partners, then the
+    reduced own slice) against the oracle."""
     w = inputs.CONFIGS[name]
-    data = inputs.make_rs(w, salt=12)
     rank = 5
-    persistent = bool(flags & cf.CF_PERSISTENT)      # deferred aggregation only, no sinks: the last output stays
+    persistent = bool(flags & cf.CF_PERSISTENT)      # deferred aggregation only; every B_out in a buffer of its own
     if persistent and not keep_all:
         pytest.skip("the persistent launch keeps every arrival (recv_each)")
-    run = H.RsPairRun(w, data, rank, with_sink=not persistent, keep_all=keep_all)
+    data, ref = _full_ref(name, rank)
+    run = H.RsPairRun(w, data, rank, with_sink=True, keep_all=keep_all)
+    for t in run.sink + [run.O]:
+        t.fill_(float("nan"))
     with H.Workspace(run.desc, cf.CF_KIND_RS_PAIR):       # as the benchmark runs it
         run.run_schedule(flags)
-    W64 = inputs.as_f64(data["W"], w.dtype)
-    rng = np.random.default_rng(2)
-    for i in range(w.p - 1 if persistent else 0, w.p):
-        l = oracle.slice_index_pair(w.p, rank, i)
-        rows = _sample_rows(w.m_chunk, rng)
-        Arows = inputs.as_f64(data["A"][[l * w.m_chunk + r for r in rows]], w.dtype)
-        ref = oracle.gemm(Arows, W64)
-        if i == w.p - 1:
-            acc = None
-            for t in range(1, w.p):
-                got_t = data["R"][t][rows].astype(np.float64)
-                acc = got_t if acc is None else oracle.add(acc, got_t)
-            ref = oracle.add(acc, ref)
-        got_full = H.to_host_f64(run.sink[i] if i < w.p - 1 else run.O)
-        assert not np.isnan(got_full).any()
-        e = H.rel_err(got_full[rows], ref)
+    for i in range(w.p):
+        got = H.to_host_f64(run.sink[i] if i < w.p - 1 else run.O)
+        assert not np.isnan(got).any(), f"step {i}"
+        e = H.rel_err(got, ref[i])
         assert e <= TOL_BF16 and e <= TIGHT_BF16, f"step {i}: {e:.3e}"
+        if persistent and i < w.p - 1:
+            assert torch.equal(run.sink[i], run.send_each[i])
 
 
 def test_pair_rejects_what_it_cannot_do():
