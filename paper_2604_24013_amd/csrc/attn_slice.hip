@@ -648,14 +648,14 @@ hipError_t launch_attn_slice(const AttnParams &p_in, hipStream_t s, int num_cu)
     AttnParams p = p_in;
     int qt = 1, nw = 8, ksp = 0;
     bool wave_split = false;
-    if (const char *e = getenv("COMMFUSE_ATTN_WAVES"))   // tuning override: waves per workgroup, 4 or 8
-        nw = atoi(e) == 8 ? 8 : 4;
-    if (const char *e = getenv("COMMFUSE_ATTN_KSPLIT"))  // tuning override: workgroups per query block
-        ksp = atoi(e);
-    if (const char *e = getenv("COMMFUSE_ATTN_QT")) {    // tuning override: 32-query tiles per wave; 0 = keys over waves
-        const int v = atoi(e);
-        wave_split = v == 0;
-        qt = v == 2 ? 2 : 1;
+    const Tuning tn = tuning();                          // overrides
+    if (tn.attn_waves)                                   // waves per workgroup, 4 or 8
+        nw = tn.attn_waves;
+    if (tn.attn_ksplit)                                  // workgroups per query block
+        ksp = tn.attn_ksplit;
+    if (tn.attn_qt >= 0) {                               // 32-query tiles per wave; 0 = keys over waves
+        wave_split = tn.attn_qt == 0;
+        qt = tn.attn_qt == 2 ? 2 : 1;
         if (qt == 2)
             nw = 4;
     }
@@ -676,7 +676,7 @@ hipError_t launch_attn_slice(const AttnParams &p_in, hipStream_t s, int num_cu)
         if (k > 1 && need <= p.ws_bytes && groups <= p.max_groups)
             p.ksplit = k;
     }
-    if (wave_split || (small_grid && p.ksplit == 1 && qt == 1 && p.n_slices == 1 && getenv("COMMFUSE_ATTN_QT") == nullptr)) {
+    if (wave_split || (small_grid && p.ksplit == 1 && qt == 1 && p.n_slices == 1 && tn.attn_qt < 0)) {
         const dim3 grid(((p.c + 31) / 32) * p.heads * p.batch), block(256);
         hipLaunchKernelGGL(attn_slice_ksplit_kernel, grid, block, 0, s, p);
         return hipGetLastError();

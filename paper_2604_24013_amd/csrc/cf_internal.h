@@ -80,6 +80,28 @@ struct AttnParams {
     int max_groups = 0;
 };
 
+// Tuning overrides (environment variables COMMFUSE_*; tests use them to force every code path).  They are read
+// ONCE, at the first call into the library -- unless COMMFUSE_TUNING_LIVE is set to a non-zero value at that
+// moment, in which case every call of tuning() reads the environment again (test mode).  A field keeps its
+// "unset" value when its variable is absent.  The struct is plain data: it is part of the key under which a
+// captured graph is cached, because the choices are baked into the captured launches.
+struct Tuning {
+    int tile_bm = 0, tile_bn = 0;   // COMMFUSE_TILE = "256x256" | "256x128" | "128x128"   (0 = unset)
+    int deep = -1;                  // COMMFUSE_DEEP = 0 | 1                               (-1 = unset)
+    int splitk = 0;                 // COMMFUSE_SPLITK = 1..8                              (0 = unset)
+    int staged = 0;                 // COMMFUSE_KERNEL = "staged"
+    int prefetch = -1;              // COMMFUSE_PREFETCH = lead of the B_in prefetch in k-tiles (-1 = unset)
+    int xcd_steps = -1;             // COMMFUSE_XCD_STEPS = 0 | 1                          (-1 = unset)
+    int k_rotate = -1;              // COMMFUSE_K_ROTATE = 0 | 1                           (-1 = unset)
+    int stream_recv = -1;           // COMMFUSE_STREAM_RECV = 0 | 1                        (-1 = unset)
+    int tile_f32_bm = 0;            // COMMFUSE_TILE_F32 = "128x128" | "64x64"             (0 = unset)
+    unsigned spin_limit = 0;        // COMMFUSE_SPIN_LIMIT                                 (0 = unset)
+    int attn_qt = -1;               // COMMFUSE_ATTN_QT = 0 | 1 | 2                        (-1 = unset)
+    int attn_waves = 0;             // COMMFUSE_ATTN_WAVES = 4 | 8                         (0 = unset)
+    int attn_ksplit = 0;            // COMMFUSE_ATTN_KSPLIT                                (0 = unset)
+};
+Tuning tuning();
+
 struct TileChoice {
     int bm, bn;          // workgroup tile
     int splitk;          // k-splits per output tile (1 = none)

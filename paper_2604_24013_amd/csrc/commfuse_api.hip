@@ -201,12 +201,8 @@ struct CopyJob {
 
 unsigned spin_limit()
 {
-    if (const char *e = getenv("COMMFUSE_SPIN_LIMIT")) {   // tests force a time-out with a tiny limit
-        const long v = atol(e);
-        if (v > 0)
-            return (unsigned)v;
-    }
-    return 400000u;                                        // about a second of polling
+    const unsigned v = cf::tuning().spin_limit;            // tests force a time-out with a tiny limit
+    return v > 0 ? v : 400000u;                            // default: about a second of polling
 }
 
 // True if a step of this layer runs the kernel that can carry a delivery (direct-to-LDS bf16 kernel).
@@ -1106,6 +1102,10 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
         append_bytes(key, &attn->ap.V, sizeof(void *));
         append_bytes(key, &attn->ap.out, sizeof(void *));
     }
+    {   // so are the tuning overrides (tile shape, k-split, work-item order, spin limit, ...)
+        const cf::Tuning tn = cf::tuning();
+        append_bytes(key, &tn, sizeof(tn));
+    }
     {   // the registered workspace is baked into the captured kernels (split-K partials, delivery flags)
         std::lock_guard<std::mutex> lk(g_ws_mu);
         append_bytes(key, &g_ws.ptr, sizeof(g_ws.ptr));
@@ -1212,6 +1212,65 @@ cf_status check_attn_ptrs(const void *Q, const void *K, const void *V, const voi
 }
 
 }  // namespace
+
+namespace cf {
+
+static Tuning read_tuning_from_environment()
+{
+    Tuning t;
+    memset(&t, 0, sizeof(t));                      // (padding too: the struct is hashed byte-wise into graph keys)
+    t.deep = t.prefetch = t.xcd_steps = t.k_rotate = t.stream_recv = t.attn_qt = -1;
+    int bm = 0, bn = 0;
+    if (const char *e = getenv("COMMFUSE_TILE"))
+        if (sscanf(e, "%dx%d", &bm, &bn) == 2) {
+            t.tile_bm = bm;
+            t.tile_bn = bn;
+        }
+    if (const char *e = getenv("COMMFUSE_DEEP"))
+        t.deep = atoi(e) != 0;
+    if (const char *e = getenv("COMMFUSE_SPLITK")) {
+        const int sk = atoi(e);
+        if (sk >= 1 && sk <= 8)
+            t.splitk = sk;
+    }
+    if (const char *e = getenv("COMMFUSE_KERNEL"))
+        t.staged = strcmp(e, "staged") == 0;
+    if (const char *e = getenv("COMMFUSE_PREFETCH"))
+        t.prefetch = atoi(e) < 0 ? 0 : atoi(e);
+    if (const char *e = getenv("COMMFUSE_XCD_STEPS"))
+        t.xcd_steps = atoi(e) != 0;
+    if (const char *e = getenv("COMMFUSE_K_ROTATE"))
+        t.k_rotate = atoi(e) != 0;
+    if (const char *e = getenv("COMMFUSE_STREAM_RECV"))
+        t.stream_recv = atoi(e) != 0;
+    if (const char *e = getenv("COMMFUSE_TILE_F32"))
+        if (sscanf(e, "%dx%d", &bm, &bn) == 2)
+            t.tile_f32_bm = bm;
+    if (const char *e = getenv("COMMFUSE_SPIN_LIMIT")) {
+        const long v = atol(e);
+        if (v > 0)
+            t.spin_limit = (unsigned)v;
+    }
+    if (const char *e = getenv("COMMFUSE_ATTN_QT"))
+        t.attn_qt = atoi(e);
+    if (const char *e = getenv("COMMFUSE_ATTN_WAVES"))
+        t.attn_waves = atoi(e) == 8 ? 8 : 4;
+    if (const char *e = getenv("COMMFUSE_ATTN_KSPLIT"))
+        t.attn_ksplit = atoi(e);
+    return t;
+}
+
+Tuning tuning()
+{
+    static const bool live = [] {
+        const char *e = getenv("COMMFUSE_TUNING_LIVE");
+        return e != nullptr && atoi(e) != 0;
+    }();
+    static const Tuning once = read_tuning_from_environment();
+    return live ? read_tuning_from_environment() : once;
+}
+
+}  // namespace cf
 
 extern "C" {
 

@@ -307,8 +307,7 @@ TileChoice choose_tile_bf16(int M, int N, int K, int num_cu)
 
 static bool staged_kernel_forced()                   // "staged": the register-staged kernel of this file
 {
-    const char *e = getenv("COMMFUSE_KERNEL");
-    return e != nullptr && strcmp(e, "staged") == 0;
+    return tuning().staged != 0;
 }
 
 bool gemm_bf16_takes_recv_list(const GemmParams &p, bool w_kn)
@@ -340,20 +339,15 @@ hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipSt
         t.splitk = 1;
         t.deep = true;                               // 128x128: one workgroup per CU, four stages
     }
-    if (const char *e = getenv("COMMFUSE_TILE")) {   // tuning override: "256x256", "256x128", "128x128"
-        int bm = 0, bn = 0;
-        if (sscanf(e, "%dx%d", &bm, &bn) == 2) {
-            t.bm = bm;
-            t.bn = bn;
-        }
+    const Tuning tn = tuning();                      // overrides: tile shape, stages, k-splits per output tile
+    if (tn.tile_bm > 0) {
+        t.bm = tn.tile_bm;
+        t.bn = tn.tile_bn;
     }
-    if (const char *e = getenv("COMMFUSE_DEEP"))      // tuning override: 128x128 with four LDS stages
-        t.deep = atoi(e) != 0;
-    if (const char *e = getenv("COMMFUSE_SPLITK")) {  // tuning override: k-splits per output tile
-        const int sk = atoi(e);
-        if (sk >= 1 && sk <= 8)
-            t.splitk = sk;
-    }
+    if (tn.deep >= 0)
+        t.deep = tn.deep != 0;
+    if (tn.splitk >= 1)
+        t.splitk = tn.splitk;
     const bool staged = staged_kernel_forced();
     if (!staged && gemm_bf16_dl_supported(p, w_kn))
         return launch_gemm_bf16_dl(p, w_kn, out_bf16, s, t);

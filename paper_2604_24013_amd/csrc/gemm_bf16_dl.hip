@@ -869,8 +869,9 @@ bool gemm_bf16_dl_supported(const GemmParams &p, bool w_kn)
 hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16, hipStream_t s, TileChoice t)
 {
     GemmParams p = p_in;
-    if (const char *e = getenv("COMMFUSE_PREFETCH"))   // tuning override: lead of the B_in prefetch in k-tiles, 0 = off
-        p.pf_lead = atoi(e) < 0 ? 0 : atoi(e);
+    const Tuning tn = tuning();
+    if (tn.prefetch >= 0)                              // override: lead of the B_in prefetch in k-tiles, 0 = off
+        p.pf_lead = tn.prefetch;
     p.splits = t.splitk < 1 ? 1 : t.splitk;
     const int nk_all = (p.K + BK - 1) / BK;
     if (p.splits > nk_all)
@@ -880,12 +881,11 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
         p.splits = 1;
         p.cp_wgs = 0;
         p.cp_bytes = 0;
-        const char *rk = getenv("COMMFUSE_K_ROTATE");   // tuning override: 0 = every XCD walks k from 0
-        const char *e = getenv("COMMFUSE_XCD_STEPS");  // tuning override: 0 = every XCD takes a band of every step
-        // (not when one step carries the sum of several received partials: that step's epilogue is heavy and
-        // would fall on one XCD)
-        p.xcd_steps = p.n_steps % 8 == 0 && p.num_cu % 8 == 0 && p.n_recv_more == 0 && !(e != nullptr && atoi(e) == 0);
-        p.k_rotate = p.xcd_steps && !(rk != nullptr && atoi(rk) == 0);   // (measured with whole steps per XCD only)
+        // overrides: xcd_steps 0 = every XCD takes a band of every step; k_rotate 0 = every XCD walks k from 0
+        // (whole steps per XCD not when one step carries the sum of several received partials: that step's
+        // epilogue is heavy and would fall on one XCD)
+        p.xcd_steps = p.n_steps % 8 == 0 && p.num_cu % 8 == 0 && p.n_recv_more == 0 && tn.xcd_steps != 0;
+        p.k_rotate = p.xcd_steps && tn.k_rotate != 0;   // (measured with whole steps per XCD only)
     }
     if (p.splits > 1 && (p.ws == nullptr || p.counters == nullptr ||
                          (size_t)p.splits * p.M * p.N * sizeof(float) > p.ws_bytes || tiles > p.max_tiles ||

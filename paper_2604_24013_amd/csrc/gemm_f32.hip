@@ -185,11 +185,8 @@ hipError_t launch_gemm_f32(const GemmParams &p, bool w_kn, hipStream_t s, int nu
         return hipSuccess;
     const int big = ((p.M + 127) / 128) * ((p.N + 127) / 128);
     bool use_big = big >= num_cu;
-    if (const char *e = getenv("COMMFUSE_TILE_F32")) {   // tuning override: "128x128" or "64x64"
-        int bm = 0, bn = 0;
-        if (sscanf(e, "%dx%d", &bm, &bn) == 2)
-            use_big = bm >= 128;
-    }
+    if (const int bm = tuning().tile_f32_bm)             // override: "128x128" or "64x64"
+        use_big = bm >= 128;
     if (use_big)
         return launch_cfg<128, 128>(p, w_kn, s);
     return launch_cfg<64, 64>(p, w_kn, s);

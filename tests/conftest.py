@@ -9,6 +9,10 @@ if ROOT not in sys.path:
 
 GOLDEN = os.path.join(ROOT, "tests", "golden")
 
+# The library reads its COMMFUSE_* tuning overrides once, at its first call; the tests switch them between
+# calls (to force every tile shape and code path), so they ask for the environment to be read on every call.
+os.environ.setdefault("COMMFUSE_TUNING_LIVE", "1")
+
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")

@@ -214,6 +214,66 @@ def test_attn_rs_steps_and_schedule(shape, layout):
         cf.set_workspace(None)
 
 
+def test_attention_at_the_benchmarked_shape():
+    """The shape the benchmark times (p = 8, 8 of 64 heads on the rank, sequence 8192, head_dim 128, batch 1,
+    output width 8192, inputs drawn as the benchmark draws them), launched the three ways it launches it: one
+    slice with the keys split over workgroups (workspace registered), all p slices in one launch, and the
+    persistent rank step.  Every element is compared: all 128 features of every (head, query) of every slice,
+    every step's B_out and O^r (the oracle needs a few seconds for the whole layer)."""
+    p, B, h, S, n = 8, 1, 8, 8192, 8192
+    rng = np.random.default_rng(inputs.BASE_SEED + 78)
+    bits = lambda shape, sigma: inputs.f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32) * sigma)
+    Qb, Kb, Vb = (bits((B, h, S, 128), 1.0) for _ in range(3))
+    Wb = bits((h * 128, n), 0.01)
+    f64 = lambda b: inputs.bf16_bits_to_f32(b).astype(np.float64)
+    Q, K, V, W = f64(Qb), f64(Kb), f64(Vb), f64(Wb)
+    mc = B * S // p
+    R = [None] + [rng.standard_normal((mc, n)).astype(np.float32) for _ in range(p - 1)]
+    scale = 1.0 / np.sqrt(128.0)
+    rank = 0
+    attn_ref = [oracle.attention_slice(Q, K, V, l, p, scale) for l in range(p)]
+    ref = []
+    for i in range(p):                                   # Alg. 4 step by step (the attention of a slice computed once)
+        out = oracle.gemm(oracle.round_to_bf16(attn_ref[oracle.slice_index_rs(p, rank, i)]), W)
+        ref.append(out if i == 0 else oracle.add(R[i].astype(np.float64), out))
+    Qd, Kd, Vd, Wd = (H.to_dev(x, "bf16") for x in (Qb, Kb, Vb, Wb))
+    desc = cf.attn_desc(p, rank, B, h, S, 128, n, scale)
+    mk = lambda: torch.full((mc, n), float("nan"), dtype=torch.float32, device=H.DEV)
+    O, slot, send = mk(), [mk(), mk()], [mk(), mk()]
+    each, send_each = [mk() for _ in range(p - 1)], [mk() for _ in range(p - 1)]
+    stage = [H.to_dev(r, "f32") for r in R[1:]]
+    attn_all = torch.full((p * mc, h * 128), float("nan"), dtype=torch.bfloat16, device=H.DEV)
+    ws = torch.empty(max(cf.workspace_bytes(cf.layer_desc(p, rank, mc, n, h * 128), cf.CF_KIND_RS), 64 << 20),
+                     dtype=torch.uint8, device=H.DEV)
+    cf.set_workspace(ws)                                  # as the benchmark runs it: the single-slice launch splits the keys
+    torch.cuda.synchronize()
+    cs, xs = torch.cuda.Stream(), torch.cuda.Stream()
+    try:
+        for l in (1, p - 1):                              # single-slice launches (slice 1 is the one the benchmark times)
+            one = torch.full((mc, h * 128), float("nan"), dtype=torch.bfloat16, device=H.DEV)
+            cf.attn_slice(desc, l, Qd, Kd, Vd, one, cs)
+            cs.synchronize()
+            got = H.to_host_f64(one)
+            assert not np.isnan(got).any()
+            e = H.rel_err(got, attn_ref[l])
+            assert e <= TOL_ATTN, f"single-slice launch, slice {l}: {e:.3e}"
+        bufs = cf.make_attn_buffers(Qd, Kd, Vd, Wd, attn_all, O, stage, slot, send, None, each, send_each)
+        cf.run_attn_schedule(desc, bufs, cs, xs, cf.CF_PERSISTENT | cf.CF_SERIAL)
+        cs.synchronize()
+        cf.device_status(cs)
+        got = H.to_host_f64(attn_all)                     # the all-slices launch: slice l in row block l
+        assert not np.isnan(got).any()
+        for l in range(p):
+            e = H.rel_err(got[l * mc:(l + 1) * mc], attn_ref[l])
+            assert e <= TOL_ATTN, f"all-slices launch, slice {l}: {e:.3e}"
+        for i in range(p):                                # the persistent projection + reduce-scatter over it
+            e = H.rel_err(H.to_host_f64(send_each[i] if i < p - 1 else O), ref[i])
+            assert e <= TOL_BF16 and e <= TOL_STEP, f"step {i}: {e:.3e}"
+    finally:
+        torch.cuda.synchronize()
+        cf.set_workspace(None)
+
+
 def test_attention_bad_arguments():
     t = torch.zeros(1 << 16, dtype=torch.bfloat16, device=H.DEV)
     ok = cf.attn_desc(2, 0, 1, 1, 128, 128, 64, 0.1)
