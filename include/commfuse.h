@@ -129,6 +129,25 @@ int commfuse_pair_partner(int p, int rank, int round);
 cf_status commfuse_rs_step(const cf_layer_desc *desc, int step, const void *A, const void *W,
                            const float *recv, float *out, void *hip_stream);
 
+/* commfuse_rs_step for callers that cannot allocate device memory and have no workspace to register: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and the same result as commfuse_rs_step; the split-K scratch (arrival counters and fp32 partial
+ * tiles) is a file-scope device array inside the library instead of the workspace registered with
+ * commfuse_set_workspace, which this call ignores.  The call allocates nothing: no hipMalloc, no hipFree, no
+ * allocating library routine.
+ *   Limit: (m_chunk / m) * n <= 2,097,152 elements per step (8 k-splits of such a step's fp32 output fill the
+ *     64 MiB of partial tiles; 64 KiB of counters beside them); larger steps get CF_ERR_INVALID_ARG and
+ *     nothing is enqueued.  Every GPU the library is used on holds its own 64 MiB + 64 KiB array from the
+ *     moment the library's code is loaded there until the process ends.
+ *   First call on a device: looks up the device address of that GPU's array once (with that device current)
+ *     and zeroes the arrival counters with a small fill kernel on `hip_stream`; make that first call outside
+ *     graph capture.  The kernels leave the counters at zero, and the partial tiles are written before they
+ *     are read, so nothing else needs clearing between calls.
+ *   All calls on one GPU share that GPU's array: two calls whose kernels overlap in time on one GPU (different
+ *     streams, or one stream of a graph with parallel branches) race.  Calls on one stream are safe. */
+cf_status commfuse_rs_step_noalloc(const cf_layer_desc *desc, int step, const void *A, const void *W,
+                                   const float *recv, float *out, void *hip_stream);
+
 /* One iteration i of the pairwise schedule (Appendix A(a)), p even or 1.  The
  * partials that travel first are computed first and the rank's own slice last, as
  * in Alg. 2, so nothing is left to send after the last compute:

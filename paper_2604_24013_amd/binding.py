@@ -28,7 +28,7 @@ DTYPES = {"bf16": CF_BF16, "f32": CF_F32}
 
 EXPORTS = [
     "commfuse_chunk_index", "commfuse_subslice_index", "commfuse_pair_partner", "commfuse_rs_pair_step", "commfuse_rs_pair_last_step", "commfuse_dp_pair_step", "commfuse_wgrad_step", "commfuse_attn_slice", "commfuse_attn_rs_step",
-    "commfuse_run_attn_schedule", "commfuse_rs_step", "commfuse_ag_step", "commfuse_dp_reduce_step",
+    "commfuse_run_attn_schedule", "commfuse_rs_step", "commfuse_rs_step_noalloc", "commfuse_ag_step", "commfuse_dp_reduce_step",
     "commfuse_run_schedule", "commfuse_last_error", "commfuse_workspace_bytes", "commfuse_set_workspace",
     "commfuse_device_status",
     "commfuse_destroy_cache", "commfuse_version",
@@ -101,6 +101,8 @@ def load():
     lib.commfuse_chunk_index.restype = i32
     lib.commfuse_rs_step.argtypes = [ctypes.POINTER(LayerDesc), i32, vp, vp, vp, vp, vp]
     lib.commfuse_rs_step.restype = i32
+    lib.commfuse_rs_step_noalloc.argtypes = [ctypes.POINTER(LayerDesc), i32, vp, vp, vp, vp, vp]
+    lib.commfuse_rs_step_noalloc.restype = i32
     lib.commfuse_ag_step.argtypes = [ctypes.POINTER(LayerDesc), i32, vp, vp, vp, vp]
     lib.commfuse_ag_step.restype = i32
     lib.commfuse_dp_reduce_step.argtypes = [i32, i32, i32, vp, i64, vp, vp]
@@ -268,6 +270,11 @@ def dp_pair_step(p: int, rank: int, step: int, bucket, chunk_elems: int, recv, s
 
 def rs_step(desc: LayerDesc, step: int, A, W, recv, out, stream=None) -> None:
     _check(load().commfuse_rs_step(ctypes.byref(desc), step, _ptr(A), _ptr(W), _ptr(recv), _ptr(out), _stream(stream)))
+
+
+def rs_step_noalloc(desc: LayerDesc, step: int, A, W, recv, out, stream=None) -> None:
+    _check(load().commfuse_rs_step_noalloc(ctypes.byref(desc), step, _ptr(A), _ptr(W), _ptr(recv), _ptr(out),
+                                           _stream(stream)))
 
 
 def ag_step(desc: LayerDesc, step: int, shard, W, O, stream=None) -> None:

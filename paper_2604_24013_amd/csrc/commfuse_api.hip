@@ -72,6 +72,15 @@ struct Workspace {
 std::mutex g_ws_mu;
 Workspace g_ws;
 
+// Scratch of commfuse_rs_step_noalloc: the same layout as a registered workspace (arrival counters, then fp32
+// partial tiles), but owned by the library, in device memory that exists from the moment the code object is
+// loaded.  Every GPU the library runs on holds its own copy of the array until the process ends.  In host
+// code the array's name only stands for the symbol; the device address is looked up once per device
+// (static_scratch_of_current_device) and everything below uses that pointer.
+constexpr size_t STATIC_PARTIAL_BYTES = (size_t)64 << 20;                       // 8 k-splits of 2^21 fp32 elements
+constexpr size_t STATIC_SCRATCH_BYTES = WS_COUNTER_BYTES + STATIC_PARTIAL_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
 struct Resolved {      // descriptor with defaults filled in
     int p, rank;
     int m;             // slicing granularity: sub-steps per ring hop
@@ -234,7 +243,7 @@ bool wgrad_can_carry_copy(const Resolved &r)
 
 cf_status launch_gemm(const Resolved &r, const void *A_rows, const void *W, const float *recv, void *out,
                       hipStream_t s, const CopyJob *job = nullptr, const float *const *recv_more = nullptr,
-                      int n_recv_more = 0)
+                      int n_recv_more = 0, const Workspace *ws_instead = nullptr)
 {
     cf::GemmParams gp;
     for (int b = 0; b < n_recv_more; ++b)
@@ -247,10 +256,11 @@ cf_status launch_gemm(const Resolved &r, const void *A_rows, const void *W, cons
     fill_shape(gp, r);
     {
         std::lock_guard<std::mutex> lk(g_ws_mu);
-        if (g_ws.ptr != nullptr && g_ws.bytes > WS_COUNTER_BYTES) {
-            gp.counters = static_cast<unsigned *>(g_ws.ptr);
-            gp.ws = reinterpret_cast<float *>(static_cast<char *>(g_ws.ptr) + WS_COUNTER_BYTES);
-            gp.ws_bytes = g_ws.bytes - WS_COUNTER_BYTES;
+        const Workspace ws = ws_instead != nullptr ? *ws_instead : g_ws;   // (the library's own scratch, or the registered one)
+        if (ws.ptr != nullptr && ws.bytes > WS_COUNTER_BYTES) {
+            gp.counters = static_cast<unsigned *>(ws.ptr);
+            gp.ws = reinterpret_cast<float *>(static_cast<char *>(ws.ptr) + WS_COUNTER_BYTES);
+            gp.ws_bytes = ws.bytes - WS_COUNTER_BYTES;
             gp.max_tiles = (int)(WS_TILE_COUNTER_BYTES / sizeof(unsigned));
         }
     }
@@ -275,7 +285,7 @@ cf_status launch_gemm(const Resolved &r, const void *A_rows, const void *W, cons
 }
 
 cf_status rs_step_impl(const Resolved &r, int step, const void *A, const void *W, const float *recv, float *out,
-                       hipStream_t s, const CopyJob *job = nullptr)
+                       hipStream_t s, const CopyJob *job = nullptr, const Workspace *ws_instead = nullptr)
 {
     if (cf_status st = check_step(r, step))
         return st;
@@ -291,7 +301,7 @@ cf_status rs_step_impl(const Resolved &r, int step, const void *A, const void *W
         return fail(CF_ERR_MISALIGNED, "tensor pointers must be 16-byte aligned");
     const int l = subslice_index(CF_KIND_RS, r.p, r.m, r.rank, step);
     const char *a_rows = static_cast<const char *>(A) + (size_t)l * r.mc * r.lda * in_elem(r);
-    return launch_gemm(r, a_rows, W, recv, out, s, job);
+    return launch_gemm(r, a_rows, W, recv, out, s, job, nullptr, 0, ws_instead);
 }
 
 cf_status ag_step_impl(const Resolved &r, int step, const void *shard, const void *W, void *O, hipStream_t s,
@@ -515,6 +525,33 @@ cf_status dp_pair_step_impl(int p, int rank, int step, float *bucket, int64_t ch
     if ((reinterpret_cast<uintptr_t>(bucket) | reinterpret_cast<uintptr_t>(recv)) & 3u)
         return fail(CF_ERR_MISALIGNED, "fp32 pointers must be 4-byte aligned");
     return accumulate(bucket + (int64_t)rank * chunk_elems, recv, chunk_elems, s);
+}
+
+// Device address of this GPU's copy of `scratch`.  Looked up once per device with that device current (the
+// first call on a device also zeroes the arrival counters with a small fill kernel on `s`; the kernels leave
+// them at zero afterwards).  Later calls only read the table: no HIP call that could allocate.
+cf_status static_scratch_of_current_device(hipStream_t s, Workspace *out)
+{
+    static std::mutex mu;
+    static void *ptr_of[64];
+    int dev = 0;
+    CF_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64)
+        return fail(CF_ERR_UNSUPPORTED, "device ordinal %d beyond the table of per-device scratch pointers", dev);
+    std::lock_guard<std::mutex> lk(mu);
+    if (ptr_of[dev] == nullptr) {
+        void *ptr = nullptr;
+        CF_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (ptr == nullptr)
+            return fail(CF_ERR_HIP, "hipGetSymbolAddress returned a null device address for the static scratch");
+        hipError_t e = cf::launch_set_words(static_cast<unsigned *>(ptr), (int)(WS_COUNTER_BYTES / sizeof(unsigned)), 0u, s);
+        if (e != hipSuccess)
+            return fail_hip(e, "clearing the arrival counters of the static scratch");
+        ptr_of[dev] = ptr;
+    }
+    out->ptr = ptr_of[dev];
+    out->bytes = STATIC_SCRATCH_BYTES;
+    return CF_OK;
 }
 
 // ---------------------------------------------------------------------------
@@ -1350,6 +1387,25 @@ cf_status commfuse_rs_step(const cf_layer_desc *desc, int step, const void *A, c
     if (cf_status st = resolve(desc, CF_KIND_RS, &r))
         return st;
     return rs_step_impl(r, step, A, W, recv, out, static_cast<hipStream_t>(hip_stream));
+}
+
+cf_status commfuse_rs_step_noalloc(const cf_layer_desc *desc, int step, const void *A, const void *W,
+                                   const float *recv, float *out, void *hip_stream)
+{
+    Resolved r;
+    if (cf_status st = resolve(desc, CF_KIND_RS, &r))
+        return st;
+    // the largest step whose k-split partials fit the library's scratch for every split choice
+    if ((size_t)r.mc * (size_t)r.n * sizeof(float) * WS_MAX_SPLITS > STATIC_PARTIAL_BYTES)
+        return fail(CF_ERR_INVALID_ARG,
+                    "commfuse_rs_step_noalloc: a step output of %lld x %lld fp32 elements exceeds the static scratch "
+                    "(at most %zu elements per step); use commfuse_rs_step with a registered workspace",
+                    (long long)r.mc, (long long)r.n, STATIC_PARTIAL_BYTES / sizeof(float) / WS_MAX_SPLITS);
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    Workspace own;
+    if (cf_status st = static_scratch_of_current_device(s, &own))
+        return st;
+    return rs_step_impl(r, step, A, W, recv, out, s, nullptr, &own);
 }
 
 cf_status commfuse_ag_step(const cf_layer_desc *desc, int step, const void *shard, const void *W, void *O,
