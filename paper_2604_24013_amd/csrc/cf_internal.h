@@ -21,6 +21,7 @@ struct GemmParams {
     const float *recv_more[MAX_RECV_MORE] = {};
     int n_recv_more = 0;
     int pf_lead = 16;    // B_in prefetch: k-tiles before the end of the k loop at which it is issued (0 = off)
+    bool stream_recv = true;   // 256x256 tile: B_in lands in LDS under the main loop and is added in mid-sum (set by the launcher)
     void *out;
     int64_t lda, ldw, ldo;
     int M, N, K;

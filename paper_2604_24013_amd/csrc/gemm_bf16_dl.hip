@@ -133,11 +133,17 @@ __device__ __forceinline__ int xcd_remap(int pid, int total)
 // A_T: the left operand is stored [K x M] (see GemmParams::a_t); its tile then lives in LDS like a
 // [k x n] weight tile and is read with the transposing LDS read as well.
 // PERSIST: one launch runs all steps of a rank step (GemmParams::n_steps, see the work-item loop below).
+// RLDS: reduce-scatter variant of the SPREAD tile.  The received partial B_in does not wait for the epilogue: in
+// the last sixteen k-tiles before the final one it is brought in, one 32x32 sub-tile of every wave at a time,
+// by direct loads into an LDS landing area (no register is held while the load is in flight) and added to the
+// accumulators in mid-loop, so that the epilogue only stores.  The landing area takes the place of the third
+// left-operand stage (see the schedule below).
 template <int BM, int BN, int WGM, int WGN, int NS, bool SPREAD, bool W_KN, bool OUT_BF16, bool A_T = false,
-          bool PERSIST = false>
+          bool PERSIST = false, bool RLDS = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams P, int tiles_m, int tiles_n)
 {
     static_assert(!A_T || (W_KN && !OUT_BF16), "the transposed left operand comes with [k x n] weights and fp32 output");
+    static_assert(!RLDS || (SPREAD && !OUT_BF16 && !A_T && NS == 2), "B_in through LDS: 256x256 tile, fp32 output");
     constexpr int NW = WGM * WGN;
     constexpr int WTM = BM / WGM, WTN = BN / WGN;
     constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -150,14 +156,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // fills the 160 KiB with THREE left-operand stages and two weight stages: its weight loads go out first
     // after the barrier that frees their stage and its left-operand loads one k-tile further ahead (see the
     // steady state below), which lengthens the time every load has to arrive.
-    constexpr int NSA = SPREAD ? NS + 1 : NS;
+    constexpr int NSA = (SPREAD && !RLDS) ? NS + 1 : NS;
     constexpr int W_BASE = NSA * A_BYTES;
-    static_assert(NS >= 2 && NS <= 4 && NSA * A_BYTES + NS * B_BYTES <= 160 * 1024, "LDS budget");
+    constexpr int R_BASE = NSA * A_BYTES + NS * B_BYTES;      // RLDS: landing area of B_in, 4 KiB per wave
+    constexpr int R_BYTES = RLDS ? NW * 4096 : 0;
+    static_assert(NS >= 2 && NS <= 4 && NSA * A_BYTES + NS * B_BYTES + R_BYTES <= 160 * 1024, "LDS budget");
     static_assert(KS == 4, "the slice schedule below is written for four slices per stage");
     constexpr int W_ROWB = BN * 2;                   // bytes of one k-row of a [k x n] weight tile
     constexpr int A_ROWB = BM * 2;                   // bytes of one k-row of a [k x m] left-operand tile
 
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[NSA * A_BYTES + NS * B_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[NSA * A_BYTES + NS * B_BYTES + R_BYTES];
 
     const int tid0 = threadIdx.x;
 
@@ -236,7 +244,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // addresses.  So what follows the wait is either an agent-scope acquire (operand loads: L1 and the
     // non-local L2 lines are invalidated once per workgroup) or loads with the device-coherent cache
     // policy (the B_in loads of the epilogue, which are read once anyway).
-    auto wait_delivery = [&](bool acquire) {
+    auto wait_delivery = [&](bool acquire) __attribute__((always_inline)) {
         if (cFlag != nullptr) {
             if (tid == 0) {
                 unsigned n = 0;
@@ -266,7 +274,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
 
     // Per-lane global byte offsets (k0 = 0) of every wave-load, and the k index of its chunk for the tail test.
     unsigned a_off[A_LD], b_off[B_LD];
-    int a_k[A_LD], b_k[B_LD];
 #pragma unroll
     for (int j = 0; j < A_LD; ++j) {
         const int pos = (j * NW + wave) * 1024 + lane * 16;
@@ -274,13 +281,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             const int k = pos / A_ROWB, inrow = pos % A_ROWB;
             const int q = (inrow >> 6) ^ (k & 3);
             const int gm = m0 + q * 32 + ((inrow >> 4) & 3) * 8;
-            a_k[j] = k;
             a_off[j] = gm < M ? (unsigned)(((int64_t)k * P.lda + gm) * 2) : OOB;
         } else {
             int row, kc;
             unswz_row(pos, row, kc);
             const int gm = m0 + row;
-            a_k[j] = kc * 8;
             a_off[j] = gm < M ? (unsigned)(((int64_t)gm * P.lda + kc * 8) * 2) : OOB;
         }
     }
@@ -291,16 +296,27 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             const int k = pos / W_ROWB, inrow = pos % W_ROWB;
             const int q = (inrow >> 6) ^ (k & 3);
             const int gn = n0 + q * 32 + ((inrow >> 4) & 3) * 8;
-            b_k[j] = k;
             b_off[j] = gn < N ? (unsigned)(((int64_t)k * P.ldw + gn) * 2) : OOB;
         } else {
             int row, kc;
             unswz_row(pos, row, kc);
             const int gn = n0 + row;
-            b_k[j] = kc * 8;
             b_off[j] = gn < N ? (unsigned)(((int64_t)gn * P.ldw + kc * 8) * 2) : OOB;
         }
     }
+    // k index (inside a k-tile) of the chunk wave-load j of a tile fetches for this lane: needed only where a
+    // k-tile is ragged or beyond the range, so it is recomputed there (from an opaque copy of the lane index:
+    // kept in registers across the main loop it costs eight of them)
+    auto chunk_k = [&](int j, bool k_major, int rowb) __attribute__((always_inline)) {
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
+        const int pos = (j * NW + wave) * 1024 + ln * 16;
+        if (k_major)
+            return pos / rowb;
+        int row, kc;
+        unswz_row(pos, row, kc);
+        return kc * 8;
+    };
     const int w_kstep = W_KN ? (int)(P.ldw * 2) : 2;   // bytes per unit of k along W
     const int a_kstep = A_T ? (int)(P.lda * 2) : 2;    // ... and along the left operand
 
@@ -313,15 +329,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // moment -- are spread over the k range (measured: 1 % of the pair's rank step).  The sum over k is taken in
     // that rotated order: deterministic for a given launch, last-bit different between XCDs.
     const int rot = (PERSIST && P.k_rotate) ? (int)(((blockIdx.x & 7) * nk_all) >> 3) : 0;
-    auto ktile = [&](int kt) {                           // global k-tile of this item's local k-tile kt
+    auto ktile = [&](int kt) __attribute__((always_inline)) {                           // global k-tile of this item's local k-tile kt
         const int kk = ktb + kt + rot;
         return kk >= nk_all ? kk - nk_all : kk;
     };
-    // With WHOLE_K (K a multiple of the k-tile: no k tail anywhere) the load is issued without any test: a
+    // With WHOLE_K (a k-tile known to be whole) the load is issued without any test: a
     // branch after every MFMA segment of the main loop costs more than it looks (measured: 4 - 6 % of the launch,
     // and a select on the offset still 1 %).  A tile beyond the end of the range is then fetched for real -- the
     // k-tile index wraps around (ktile), so it is a tile of the matrix -- into a stage that nobody reads.
-    auto issue_load = [&](int kt, int stage_a, int stage_w, auto idx_tag, auto whole_k_tag) {
+    auto issue_load = [&](int kt, int stage_a, int stage_w, auto idx_tag, auto whole_k_tag) __attribute__((always_inline)) {
         constexpr int idx = decltype(idx_tag)::value;
         constexpr bool WHOLE_K = decltype(whole_k_tag)::value;
         const int k0 = ktile(kt) * BK;
@@ -345,16 +361,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             const int klim = none ? -1 : K;              // chunks at k >= klim read as zero
             const int ks0 = none ? 0 : k0;
             if constexpr (idx < A_LD) {
-                const unsigned off = (k0 + a_k[idx]) >= klim ? OOB : a_off[idx];
+                const unsigned off = (k0 + chunk_k(idx, A_T, A_ROWB)) >= klim ? OOB : a_off[idx];
                 direct_load_16(a_rsrc, off, ks0 * a_kstep, sa + idx * NW * 1024);
             } else {
                 constexpr int j = idx - A_LD;
-                const unsigned off = (k0 + b_k[j]) >= klim ? OOB : b_off[j];
+                const unsigned off = (k0 + chunk_k(j, W_KN, W_ROWB)) >= klim ? OOB : b_off[j];
                 direct_load_16(w_rsrc, off, ks0 * w_kstep, sw + j * NW * 1024);
             }
         }
     };
-    auto issue_range = [&](int kt, int stage_a, int stage_w, auto lo_tag, auto hi_tag) {   // loads [lo, hi) of a tile
+    auto issue_range = [&](int kt, int stage_a, int stage_w, auto lo_tag, auto hi_tag) __attribute__((always_inline)) {   // loads [lo, hi) of a tile
         constexpr int lo = decltype(lo_tag)::value, hi = decltype(hi_tag)::value;
         static_assert(hi - lo <= 8, "at most eight direct loads per tile and wave");
         const int k0 = ktile(kt) * BK;
@@ -422,7 +438,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         w_addr[0] = W_BASE + swz_row(wn * WTN + frow, fkc);
     }
 
-    auto read_frags = [&](int stage_a, int stage_w, int ks, bf16x8_t (&af)[TM], bf16x8_t (&wf)[TN]) {
+    auto read_frags = [&](int stage_a, int stage_w, int ks, bf16x8_t (&af)[TM], bf16x8_t (&wf)[TN]) __attribute__((always_inline)) {
         const unsigned char *st = smem + stage_a * A_BYTES;
         const unsigned char *stw = smem + stage_w * B_BYTES;     // (w_addr holds the weight region's base)
 #pragma unroll
@@ -454,7 +470,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             }
         }
     };
-    auto mfma_block = [&](const bf16x8_t (&af)[TM], const bf16x8_t (&wf)[TN]) {
+    auto mfma_block = [&](const bf16x8_t (&af)[TM], const bf16x8_t (&wf)[TN]) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -473,7 +489,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     constexpr int MPS = NMFMA / NSEG;                       // MFMAs per segment
     constexpr int LH = LPT < NSEG ? LPT : NSEG;             // loads issued in the first load phase
     static_assert(NMFMA % NSEG == 0 && LPT - LH <= NSEG, "segmenting");
-    auto mfma_seg = [&](const bf16x8_t (&af)[TM], const bf16x8_t (&wf)[TN], auto seg_tag) {
+    auto mfma_seg = [&](const bf16x8_t (&af)[TM], const bf16x8_t (&wf)[TN], auto seg_tag) __attribute__((always_inline)) {
         constexpr int seg = decltype(seg_tag)::value;
 #pragma unroll
         for (int q = seg * MPS; q < (seg + 1) * MPS; ++q)
@@ -481,7 +497,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     };
     auto phase = [&](const bf16x8_t (&afc)[TM], const bf16x8_t (&wfc)[TN], bool do_read, int sa_n, int sw_n, int ks_n,
                      bf16x8_t (&afn)[TM], bf16x8_t (&wfn)[TN], int kt_l, int sa_l, int sw_l, auto lo_tag, auto n_tag,
-                     auto whole_k_tag) {
+                     auto whole_k_tag) __attribute__((always_inline)) {
         constexpr int LO = decltype(lo_tag)::value, NL = decltype(n_tag)::value;   // load slots of this phase
         if (do_read)
             read_frags(sa_n, sw_n, ks_n, afn, wfn);
@@ -519,13 +535,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     constexpr int PFR = TM * TN * 4;                  // 16-byte loads per lane
     static_assert(!PF || (NS - 2) * LPT + PFR < 64, "vmcnt range");
     const unsigned r_bytes = (unsigned)(((int64_t)(M - 1) * P.ldo + N) * 4);
+    const unsigned r_bytes_of_recv = r_bytes;
     __amdgpu_buffer_rsrc_t r_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(cRecv), 0, cRecv != nullptr ? (int)r_bytes : 0, 0x00020000);
     const int pf_at = nk - 1 - P.pf_lead;             // iteration after whose tile loads the prefetch is issued
     const bool pf_on = PF && cRecv != nullptr && splits == 1 && n_more == 0 && P.pf_lead > 0 && pf_at >= 0;
     f32x4_t pre[PF ? TM : 1][PF ? TN : 1][4];
     constexpr int COHERENT_LD = 1 | 16;               // buffer cache-policy bits sc0 | sc1
-    auto prefetch_recv = [&](auto aux_tag) {
+    auto prefetch_recv = [&](auto aux_tag) __attribute__((always_inline)) {
         constexpr int AUX = decltype(aux_tag)::value;
 #pragma unroll
         for (int i = 0; i < (PF ? TM : 0); ++i) {
@@ -542,7 +559,139 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         }
     };
 
-    if constexpr (SPREAD) {
+    // RLDS: is B_in streamed in under the main loop for this work item?  (Uniform.)  It needs the sixteen k-tiles
+    // before the last one; a step that waits for a delivery flag, sums several received partials or is a k-split
+    // keeps the loads in the epilogue.
+    constexpr int RQ = TM * TN;                       // 32x32 sub-tiles per wave, one in flight at a time
+    const bool streamed = RLDS && cRecv != nullptr && cFlag == nullptr && n_more == 0 && splits == 1 &&
+                          P.stream_recv && nk >= 2 * RQ + 1;
+    if constexpr (RLDS) {
+        // Two stages of both operands (tile t in stage t & 1) and the landing area.  Iteration kt:
+        //     slice 0: + the weight loads of tile kt+1 (its stage was vacated at the barrier of iteration kt-1)
+        //     slice 1 (X iterations: + the four B_in loads of one sub-tile), slice 2
+        //     wait: tile kt+1 complete (X: the B_in loads just issued may still be in flight); barrier
+        //     (Y iterations: the sub-tile is read from the landing area and added to its accumulators)
+        //     slice 3: + the left-operand loads of tile kt+2, into the stage tile kt vacated
+        // Loads return in issue order: the B_in loads of an X iteration are behind the weight loads of tile
+        // kt+1 and ahead of everything tile kt+2 needs, so they have until the wait of the following (Y)
+        // iteration, one and a half k-tiles of MFMA time, to arrive.  Each wave reads back only what it
+        // loaded itself, so its own vmcnt wait is all the ordering the landing area needs.
+        static_assert(A_LD <= NSEG && B_LD <= NSEG && NSEG == 4, "one load slot per MFMA segment");
+        using cALD = std::integral_constant<int, A_LD>;
+        const i32x4_t rr = make_rsrc(cRecv, cRecv != nullptr ? r_bytes_of_recv : 0u);
+        const unsigned r_lds = lds_base + R_BASE + wave * 4096;
+        // byte offset of sub-tile q = (i, j) of this wave, row 0 / column 0 of the lane pattern
+        auto r_soff = [&](int q) __attribute__((always_inline)) {
+            const int i = q / TN, j = q % TN;
+            return (int)((((int64_t)(m0 + wm * WTM + i * 32)) * P.ldo + n0 + wn * WTN + j * 32) * 4);
+        };
+        auto phase_x = [&](const bf16x8_t (&afc)[TM], const bf16x8_t (&wfc)[TN], int sa_n, int sw_n, int ks_n,
+                           bf16x8_t (&afn)[TM], bf16x8_t (&wfn)[TN], int q) __attribute__((always_inline)) {
+            const int so = r_soff(q);
+            // a lane outside the matrix must not touch memory: the scalar part of the address is not covered
+            // by the buffer's range check, so such a lane is given the out-of-range offset itself
+            // (computed from an opaque copy of the lane index: otherwise the offsets of all eight sub-tiles are
+            // hoisted out of the k loop and held in registers the main loop does not have)
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
+            const int rm = m0 + wm * WTM + (q / TN) * 32 + (ln & 31);
+            const int rn = n0 + wn * WTN + (q % TN) * 32 + (ln >> 5) * 4;
+            const unsigned rv = (unsigned)((((int64_t)(ln & 31)) * P.ldo + (ln >> 5) * 4) * 4);
+            const unsigned v0 = (rm < M && rn < N) ? rv : OOB, v1 = (rm < M && rn + 8 < N) ? rv : OOB;
+            const unsigned v2 = (rm < M && rn + 16 < N) ? rv : OOB, v3 = (rm < M && rn + 24 < N) ? rv : OOB;
+            read_frags(sa_n, sw_n, ks_n, afn, wfn);
+            mfma_seg(afc, wfc, std::integral_constant<int, 0>{});
+            interleave_mfma_reads<NREAD, (NREAD + MPS - 1) / MPS>();
+            __builtin_amdgcn_sched_barrier(0);
+            direct_load_16(rr, v0, so, r_lds);
+            mfma_seg(afc, wfc, std::integral_constant<int, 1>{});
+            __builtin_amdgcn_sched_barrier(0);
+            direct_load_16(rr, v1, so + 32, r_lds + 1024);
+            mfma_seg(afc, wfc, std::integral_constant<int, 2>{});
+            __builtin_amdgcn_sched_barrier(0);
+            direct_load_16(rr, v2, so + 64, r_lds + 2048);
+            mfma_seg(afc, wfc, std::integral_constant<int, 3>{});
+            __builtin_amdgcn_sched_barrier(0);
+            direct_load_16(rr, v3, so + 96, r_lds + 3072);
+        };
+        auto add_landed = [&](auto q_tag) __attribute__((always_inline)) {          // "O <- B_in + O" for sub-tile q, in mid-sum
+            constexpr int q = decltype(q_tag)::value;
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
+            const unsigned char *src = smem + R_BASE + wave * 4096 + ln * 16;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4_t v = *reinterpret_cast<const f32x4_t *>(src + g * 1024);
+                acc[q / TN][q % TN][4 * g + 0] += v[0];
+                acc[q / TN][q % TN][4 * g + 1] += v[1];
+                acc[q / TN][q % TN][4 * g + 2] += v[2];
+                acc[q / TN][q % TN][4 * g + 3] += v[3];
+            }
+        };
+        issue_range(0, 0, 0, c0{}, cLPT{});
+        issue_range(1, 1, 1, c0{}, cALD{});           // the left operand of tile 1; its weights go out in iteration 0
+        wait_vmcnt<A_LD>();
+        __syncthreads();
+        read_frags(0, 0, 0, af0, wf0);
+        __builtin_amdgcn_sched_barrier(0);
+        {
+            // mode 0: plain; mode 1 (X): issues the B_in loads of sub-tile q; mode 2 (Y): adds sub-tile Q
+            auto iteration_wk = [&](int kt, auto mode_tag, int q, auto q_tag, auto wk) __attribute__((always_inline)) {
+                constexpr int MODE = decltype(mode_tag)::value;
+                const int cur = kt & 1, nxt = cur ^ 1;
+                phase(af0, wf0, true, cur, cur, 1, af1, wf1, kt + 1, 0, nxt, cALD{}, cLR{}, wk);
+                if constexpr (MODE == 1)
+                    phase_x(af1, wf1, cur, cur, 2, af0, wf0, q);
+                else
+                    phase(af1, wf1, true, cur, cur, 2, af0, wf0, 0, 0, 0, c0{}, c0{}, wk);
+                phase(af0, wf0, true, cur, cur, 3, af1, wf1, 0, 0, 0, c0{}, c0{}, wk);
+                if constexpr (MODE == 1)
+                    wait_vmcnt<4>();
+                else
+                    wait_vmcnt<0>();
+                __syncthreads();
+                if constexpr (MODE == 2)
+                    add_landed(q_tag);
+                __builtin_amdgcn_sched_barrier(0);
+                phase(af1, wf1, true, nxt, nxt, 0, af0, wf0, kt + 2, cur, 0, c0{}, cALD{}, wk);
+            };
+            // (the launcher takes this variant only when K is a multiple of the k-tile: every load is branch-free)
+            auto iteration = [&](int kt, auto mode_tag, int q, auto q_tag) __attribute__((always_inline)) {
+                iteration_wk(kt, mode_tag, q, q_tag, std::true_type{});
+            };
+            using wk = std::true_type;                       // (the last tile requests nothing)
+            using m0_t = std::integral_constant<int, 0>;
+            using m1_t = std::integral_constant<int, 1>;
+            using m2_t = std::integral_constant<int, 2>;
+            int kt = 0;
+            const int first = streamed ? nk - 1 - 2 * RQ : nk - 1;
+            for (; kt < first; ++kt)
+                iteration(kt, m0_t{}, 0, c0{});
+            if (streamed) {
+                auto pair_of = [&](auto q_tag) __attribute__((always_inline)) {
+                    iteration(kt, m1_t{}, decltype(q_tag)::value, c0{});
+                    iteration(kt + 1, m2_t{}, 0, q_tag);
+                    kt += 2;
+                };
+                static_assert(RQ == 8, "eight sub-tiles per wave");
+                pair_of(std::integral_constant<int, 0>{});
+                pair_of(std::integral_constant<int, 1>{});
+                pair_of(std::integral_constant<int, 2>{});
+                pair_of(std::integral_constant<int, 3>{});
+                pair_of(std::integral_constant<int, 4>{});
+                pair_of(std::integral_constant<int, 5>{});
+                pair_of(std::integral_constant<int, 6>{});
+                pair_of(std::integral_constant<int, 7>{});
+            }
+            if (nk > 0) {                                    // last tile: nothing follows it
+                const int cur = (nk - 1) & 1;
+                phase(af0, wf0, true, cur, cur, 1, af1, wf1, 0, 0, 0, c0{}, c0{}, wk{});
+                phase(af1, wf1, true, cur, cur, 2, af0, wf0, 0, 0, 0, c0{}, c0{}, wk{});
+                phase(af0, wf0, true, cur, cur, 3, af1, wf1, 0, 0, 0, c0{}, c0{}, wk{});
+                phase(af1, wf1, false, 0, 0, 0, af0, wf0, 0, 0, 0, c0{}, c0{}, wk{});
+            }
+        }
+    } else if constexpr (SPREAD) {
         // The left-operand tile has NS+1 stages, the weight tile NS (tile t lives in stages t mod (NS+1) and
         // t mod NS).  Loads return in issue order, so what is issued first must be what is needed first:
         //   prologue: tiles 0 .. NS-1 whole, in tile order; tile 0 is awaited, its first fragments fetched
@@ -564,42 +713,55 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         read_frags(0, 0, 0, af0, wf0);
         __builtin_amdgcn_sched_barrier(0);
 
-        // the steady state, once per kind of k range (see issue_load)
-        auto steady = [&](auto wk) {
+        // The steady state.  When K is a multiple of the k-tile every iteration is branch-free.  Otherwise (the
+        // launcher then leaves the k order unrotated) the ragged k-tile is the last one of the range: the
+        // iterations up to the one that requests it are branch-free too, and only the last NS ones test.
+        {
             int cur_a = 0, cur_w = 0;                        // stages of tile kt
             int prev_a = NSA - 1;                            // left-operand stage of tile kt-1 (= of tile kt+NS)
-            for (int kt = 0; kt + 1 < nk; ++kt) {
-                const int nxt_a = (cur_a + 1 == NSA) ? 0 : cur_a + 1;
-                const int nxt_w = (cur_w + 1 == NS) ? 0 : cur_w + 1;
-                phase(af0, wf0, true, cur_a, cur_w, 1, af1, wf1, kt + NS, prev_a, 0, c0{}, cALD{}, wk);
-                phase(af1, wf1, true, cur_a, cur_w, 2, af0, wf0, 0, 0, 0, c0{}, c0{}, wk);
-                phase(af0, wf0, true, cur_a, cur_w, 3, af1, wf1, 0, 0, 0, c0{}, c0{}, wk);
+            auto body = [&](int kt, int ca, int cw, int pa, int na, int nw_, auto wk) __attribute__((always_inline)) {
+                phase(af0, wf0, true, ca, cw, 1, af1, wf1, kt + NS, pa, 0, c0{}, cALD{}, wk);
+                phase(af1, wf1, true, ca, cw, 2, af0, wf0, 0, 0, 0, c0{}, c0{}, wk);
+                phase(af0, wf0, true, ca, cw, 3, af1, wf1, 0, 0, 0, c0{}, c0{}, wk);
                 wait_vmcnt<(NS - 2) * LPT + A_LD>();
                 __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
-                phase(af1, wf1, true, nxt_a, nxt_w, 0, af0, wf0, kt + NS, 0, cur_w, cALD{}, cLR{}, wk);
+                phase(af1, wf1, true, na, nw_, 0, af0, wf0, kt + NS, 0, cw, cALD{}, cLR{}, wk);
+            };
+            // first iteration that tests its loads (all of them when K is a multiple of the k-tile: none does)
+            const int tested = K % BK == 0 ? nk - 1 : ((rot == 0 && nk - 1 > NS) ? nk - 1 - NS : 0);
+            int kt = 0;
+            for (; kt < tested; ++kt) {
+                const int nxt_a = (cur_a + 1 == NSA) ? 0 : cur_a + 1;
+                const int nxt_w = (cur_w + 1 == NS) ? 0 : cur_w + 1;
+                body(kt, cur_a, cur_w, prev_a, nxt_a, nxt_w, std::true_type{});
+                prev_a = cur_a;
+                cur_a = nxt_a;
+                cur_w = nxt_w;
+            }
+            for (; kt + 1 < nk; ++kt) {
+                const int nxt_a = (cur_a + 1 == NSA) ? 0 : cur_a + 1;
+                const int nxt_w = (cur_w + 1 == NS) ? 0 : cur_w + 1;
+                body(kt, cur_a, cur_w, prev_a, nxt_a, nxt_w, std::false_type{});
                 prev_a = cur_a;
                 cur_a = nxt_a;
                 cur_w = nxt_w;
             }
             if (nk > 0) {                                    // last tile: nothing follows it
-                phase(af0, wf0, true, cur_a, cur_w, 1, af1, wf1, 0, 0, 0, c0{}, c0{}, wk);
-                phase(af1, wf1, true, cur_a, cur_w, 2, af0, wf0, 0, 0, 0, c0{}, c0{}, wk);
-                phase(af0, wf0, true, cur_a, cur_w, 3, af1, wf1, 0, 0, 0, c0{}, c0{}, wk);
-                phase(af1, wf1, false, 0, 0, 0, af0, wf0, 0, 0, 0, c0{}, c0{}, wk);
+                using wk = std::true_type;
+                phase(af0, wf0, true, cur_a, cur_w, 1, af1, wf1, 0, 0, 0, c0{}, c0{}, wk{});
+                phase(af1, wf1, true, cur_a, cur_w, 2, af0, wf0, 0, 0, 0, c0{}, c0{}, wk{});
+                phase(af0, wf0, true, cur_a, cur_w, 3, af1, wf1, 0, 0, 0, c0{}, c0{}, wk{});
+                phase(af1, wf1, false, 0, 0, 0, af0, wf0, 0, 0, 0, c0{}, c0{}, wk{});
             }
-        };
-        if (K % BK == 0)
-            steady(std::true_type{});
-        else
-            steady(std::false_type{});
+        }
 
     } else {
         // Variant for the small tiles (few MFMAs per slice): a tile's loads go out together right
         // after the barrier that frees their stage, and the LDS reads of the next slice are
         // interleaved with all MFMAs of the current one.
         auto phase_b = [&](const bf16x8_t (&afc)[TM], const bf16x8_t (&wfc)[TN], bool do_read, int stage_n, int ks_n,
-                           bf16x8_t (&afn)[TM], bf16x8_t (&wfn)[TN], auto rpm_tag) {
+                           bf16x8_t (&afn)[TM], bf16x8_t (&wfn)[TN], auto rpm_tag) __attribute__((always_inline)) {
             constexpr int RPM = decltype(rpm_tag)::value;
             if (do_read)
                 read_frags(stage_n, stage_n, ks_n, afn, wfn);
@@ -748,7 +910,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
 #pragma unroll
                 for (int g = 0; g < 4; ++g)
                     rv[j][g] = pre[PF ? i : 0][PF ? j : 0][g];
-        } else if (has_recv) {
+        } else if (has_recv && !streamed) {
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -785,7 +947,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 o[1] = acc[i][j][4 * g + 1];
                 o[2] = acc[i][j][4 * g + 2];
                 o[3] = acc[i][j][4 * g + 3];
-                if (has_recv)
+                if (has_recv && !streamed)
                     o = rv[j][g] + o;                                    // "O <- B_in + O"
                 const int boff = eoff[j][g] == OOB ? (int)OOB : (int)(eoff[j][g] * o_elem);
                 if constexpr (OUT_BF16) {
@@ -809,6 +971,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
 template <int BM, int BN, int WGM, int WGN, int NS, bool SPREAD>
 hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s)
 {
+    // reduce-scatter steps on the 256x256 tile: the variant that brings B_in in under the main loop
+    bool any_recv = p.recv != nullptr;
+    for (int j = 0; j < p.n_steps; ++j)
+        any_recv = any_recv || p.recv_step[j] != nullptr;
+    [[maybe_unused]] const bool rlds = SPREAD && NS == 2 && any_recv && !out_bf16 && !p.a_t && p.stream_recv && p.K % BK == 0;
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     int wgs = tiles_m * tiles_n * p.splits + p.cp_wgs;
     if (p.n_steps > 0) {                             // persistent: a grid that fills the chip once
@@ -826,12 +993,22 @@ hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t
         if (w_kn) {
             if (out_bf16)
                 hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, true, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
-            else
+            else if constexpr (SPREAD && NS == 2) {
+                if (rlds)
+                    hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, false, false, true, true>), grid, block, 0, s, p, tiles_m, tiles_n);
+                else
+                    hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, false, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
+            } else
                 hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, false, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
         } else {
             if (out_bf16)
                 hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, false, true, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
-            else
+            else if constexpr (SPREAD && NS == 2) {
+                if (rlds)
+                    hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, false, false, false, true, true>), grid, block, 0, s, p, tiles_m, tiles_n);
+                else
+                    hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, false, false, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
+            } else
                 hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, false, false, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
         }
         return hipGetLastError();
@@ -843,12 +1020,22 @@ hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t
     } else if (w_kn) {
         if (out_bf16)
             hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, true>), grid, block, 0, s, p, tiles_m, tiles_n);
-        else
+        else if constexpr (SPREAD && NS == 2) {
+            if (rlds)
+                hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, false, false, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
+            else
+                hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, false>), grid, block, 0, s, p, tiles_m, tiles_n);
+        } else
             hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, false>), grid, block, 0, s, p, tiles_m, tiles_n);
     } else {
         if (out_bf16)
             hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
-        else
+        else if constexpr (SPREAD && NS == 2) {
+            if (rlds)
+                hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, false, false, false, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
+            else
+                hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, false, false>), grid, block, 0, s, p, tiles_m, tiles_n);
+        } else
             hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, false, false>), grid, block, 0, s, p, tiles_m, tiles_n);
     }
     return hipGetLastError();
@@ -872,6 +1059,7 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
     const Tuning tn = tuning();
     if (tn.prefetch >= 0)                              // override: lead of the B_in prefetch in k-tiles, 0 = off
         p.pf_lead = tn.prefetch;
+    p.stream_recv = tn.stream_recv != 0;               // override: 0 = B_in is loaded in the epilogue (256x256 tile)
     p.splits = t.splitk < 1 ? 1 : t.splitk;
     const int nk_all = (p.K + BK - 1) / BK;
     if (p.splits > nk_all)
@@ -885,7 +1073,9 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
         // (whole steps per XCD not when one step carries the sum of several received partials: that step's
         // epilogue is heavy and would fall on one XCD)
         p.xcd_steps = p.n_steps % 8 == 0 && p.num_cu % 8 == 0 && p.n_recv_more == 0 && tn.xcd_steps != 0;
-        p.k_rotate = p.xcd_steps && tn.k_rotate != 0;   // (measured with whole steps per XCD only)
+        // (measured with whole steps per XCD only; a ragged k tail stays the last k-tile of every work item,
+        // which keeps all earlier iterations of the 256x256 main loop branch-free)
+        p.k_rotate = p.xcd_steps && tn.k_rotate != 0 && p.K % BK == 0;
     }
     if (p.splits > 1 && (p.ws == nullptr || p.counters == nullptr ||
                          (size_t)p.splits * p.M * p.N * sizeof(float) > p.ws_bytes || tiles > p.max_tiles ||

@@ -95,6 +95,8 @@ RS_SHAPES = [
     (4, 72, 136, 1376),     # the 7B down-projection's K (21*64 + 32)
     (1, 40, 8, 8),          # p = 1: plain GEMM, minimum n and k
     (8, 520, 392, 200),     # several tiles in both directions plus tails
+    (3, 200, 264, 1160),    # 19 k-tiles, the last ragged: long enough for B_in to be brought in under the main loop
+    (2, 256, 512, 1152),    # 18 whole k-tiles, exact tiles
 ]
 
 
@@ -217,6 +219,37 @@ def test_integer_inputs_are_bit_exact(dtype, layout):
         outs = H.RsRun(w, data, rank, layout).run_steps()
         for i in range(p):
             assert np.array_equal(outs[i], ref[i]), f"rank {rank} step {i}"
+
+
+@pytest.mark.parametrize("stream", ["1", "0"])
+@pytest.mark.parametrize("layout", [cf.CF_W_KN, cf.CF_W_NK])
+def test_b_in_added_in_mid_sum_is_bit_exact_on_integers(layout, stream):
+    """256x256 tile with a long k range: the received partial lands in LDS under the main loop and is added to
+    the accumulators in mid-sum (another order of the same additions).  On small-integer data every order gives
+    the same bits, per-step launches and the one-launch rank step alike; with the path switched off too."""
+    p, mc, n, k = 4, 264, 520, 1224                     # 20 k-tiles (the last ragged), tiles ragged in M and N
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=p, m_chunk=mc, n=n, k=k)
+    rng = np.random.default_rng(78)
+    A = inputs.small_int_like((p * mc, k), rng, -4, 4)
+    W = inputs.small_int_like((k, n), rng, -4, 4)
+    R = [None] + [inputs.small_int_like((mc, n), rng, -50, 50) for _ in range(p - 1)]
+    data = {"A": inputs._as_dtype(A, "bf16"), "W": inputs._as_dtype(W, "bf16"), "R": R}
+    os.environ["COMMFUSE_TILE"] = "256x256"
+    os.environ["COMMFUSE_STREAM_RECV"] = stream
+    try:
+        for rank in (0, p - 1):
+            ref = _oracle_rs(w, data, rank)
+            run = H.RsRun(w, data, rank, layout, each=True)
+            outs = run.run_steps()
+            for i in range(p):
+                assert np.array_equal(outs[i], ref[i]), f"rank {rank} step {i}"
+            run.run_schedule(cf.CF_PERSISTENT | cf.CF_SERIAL)
+            for i in range(p):
+                got = H.to_host_f64(run.send_each[i] if i < p - 1 else run.O)
+                assert np.array_equal(got, ref[i]), f"rank {rank} step {i} (one launch)"
+    finally:
+        os.environ.pop("COMMFUSE_TILE", None)
+        os.environ.pop("COMMFUSE_STREAM_RECV", None)
 
 
 @pytest.mark.parametrize("layout", [cf.CF_W_KN, cf.CF_W_NK])
@@ -433,9 +466,10 @@ def test_device_wait_sees_fresh_data_every_time():
 
 @pytest.mark.parametrize("tile", [None, "256x256", "256x128", "128x128"])
 @pytest.mark.parametrize("m", [1, 2])
-def test_persistent_rank_step(m, tile):
+@pytest.mark.parametrize("k", [328, 1224, 1280])      # 6 k-tiles; 20 (ragged) and 20 whole: B_in comes in under the main loop
+def test_persistent_rank_step(m, tile, k):
     """CF_PERSISTENT: all steps in one launch; work items (step, tile) round robin over one chip-filling grid."""
-    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=8, m_chunk=264, n=520, k=328)
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=8, m_chunk=264, n=520, k=k)
     data = inputs.make_rs(w, salt=19)
     rank = 5
     ref = _oracle_rs(w, data, rank)
