@@ -42,6 +42,10 @@ def main() -> int:
     ap.add_argument("--skip-dp", action="store_true", help="leave out the 1e9-element gradient bucket")
     ap.add_argument("--skip-cpu", action="store_true", help="leave out the CPU-oracle baseline")
     ap.add_argument("--only-pair", action="store_true", help="time the headline workload only")
+    ap.add_argument("--sections", default="", help="comma-separated subset of the secondary measurements to run "
+                    "(7b, pairwise, granularity, backward, attention, dp); default: all.  With --skip-pair the headline "
+                    "workload is left out and the JSON line carries only what was measured (profiling runs)")
+    ap.add_argument("--skip-pair", action="store_true", help="leave the headline workload out (profiling runs of one section)")
     ap.add_argument("--modes", default="", help="comma-separated subset of the schedule modes to time (default: all)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (known bytes, for scaling hardware counters)")
@@ -61,6 +65,13 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     cf.load()
     K, W = args.steps, args.warmup
+    ALL_SECTIONS = ("7b", "pairwise", "granularity", "backward", "attention", "dp")
+    sections = set(args.sections.split(",")) if args.sections else set(ALL_SECTIONS)
+    if args.only_pair:
+        sections = set()
+    if args.skip_dp:
+        sections.discard("dp")
+    assert sections <= set(ALL_SECTIONS), f"unknown section in {sorted(sections)}"
 
     def time_calls(fn, stream, steps, warmup):
         """Average milliseconds of fn() over `steps` back-to-back calls, HIP events on `stream`.
@@ -86,8 +97,9 @@ def main() -> int:
         return e0.elapsed_time(e1) / steps
 
     def schedule_times(run, kind, steps, warmup):
-        """Rank-step time overlapped / compute-only / copy-only, best of eager and graph replay."""
-        out = {}
+        """Rank-step time overlapped / compute-only / copy-only: the best mode of each, and every mode's own
+        three times under "by_mode" (the overlap figures compare a mode with ITS compute-only and copy-only times)."""
+        out = {"by_mode": {}}
         for name, fl in (("overlapped", 0), ("compute_only", cf.CF_NO_COPY), ("copy_only", cf.CF_NO_COMPUTE)):
             best = None
             pers_pair = kind == cf.CF_KIND_RS_PAIR and getattr(run, "each", None) is not None
@@ -99,6 +111,7 @@ def main() -> int:
                     continue                              # needs a landing buffer per hop
                 t = time_calls(lambda: cf.run_schedule(run.desc, kind, run.bufs, run.cs, run.xs, fl | extra),
                                run.cs, steps, warmup)
+                out["by_mode"].setdefault(mode, {})[name] = t
                 if best is None or t < best[0]:
                     best = (t, mode)
             out[name] = best
@@ -122,8 +135,32 @@ def main() -> int:
         MODES = tuple(m for m in MODES[:2]) + tuple(m for m in MODES[2:] if m[0] in keep) if not keep & {"streams", "graph"} \
             else tuple(m for m in MODES if m[0] in keep)
 
+    def overlap_of(step, compute, copy):
+        """Overlap efficiency max(compute, copy) / step and hidden fraction (compute + copy - step) / copy of ONE
+        mode: all three times are that mode's own.  A mode that enqueues the deliveries in front of the kernels
+        (serial, persistent) hides nothing: its hidden fraction is ~0 whatever its efficiency figure says."""
+        return {"overlap_eff": round(max(compute, copy) / step, 3),
+                "hidden_fraction": round((compute + copy - step) / copy, 3) if copy > 0 else None}
+
     def overlap_eff(t):
-        return max(t["compute_only"][0], t["copy_only"][0]) / t["overlapped"][0]
+        """Overlap figures of the mode whose step time is reported (its own compute-only / copy-only times;
+        the fused-copy and device-wait modes have no such variants and take the stream mode's)."""
+        m = t["by_mode"].get(t["overlapped"][1], {})
+        ref = t["by_mode"].get("streams", {})
+        comp = m.get("compute_only", ref.get("compute_only", t["compute_only"][0]))
+        cpy = m.get("copy_only", ref.get("copy_only", t["copy_only"][0]))
+        return overlap_of(t["overlapped"][0], comp, cpy)
+
+    def overlap_by_mode(t):
+        out = {}
+        ref = t["by_mode"].get("streams", {})
+        for mode, v in t["by_mode"].items():
+            if "overlapped" in v:
+                comp = v.get("compute_only", ref.get("compute_only"))
+                cpy = v.get("copy_only", ref.get("copy_only"))
+                if comp and cpy:
+                    out[mode] = dict(us_per_step=round(v["overlapped"] * 1e3, 1), **overlap_of(v["overlapped"], comp, cpy))
+        return out
 
     # split-K workspace for the layers whose per-step grids are small (sized for the largest layer here)
     ws_bytes = max(cf.workspace_bytes(H.desc_of(inputs.CONFIGS[n], 0), cf.CF_KIND_AG if inputs.CONFIGS[n].kind == "ag" else cf.CF_KIND_RS)
@@ -134,103 +171,105 @@ def main() -> int:
 
     # ---------------- headline: 70B MLP pair ----------------
     up, dn = inputs.CONFIGS["c4_ag_70b_up"], inputs.CONFIGS["c4_rs_70b_down"]
-    log("generating 70B-shape inputs ...")
-    # every hop's delivery has a landing buffer of its own (cf_buffers.recv_each): nothing is reused inside a
-    # rank step, so the copy stream never waits for a kernel
-    ag = H.AgRun(up, inputs.make_ag(up), 0, each=True)
-    ddn = inputs.make_rs(dn)
-    rs = H.RsRun(dn, ddn, 0, each=True)
-    rs.A = ag.O                                   # H is handed over on the device, in bf16
-    rs.bufs = cf.make_buffers(rs.A, rs.W, rs.O, rs.stage, rs.slot, rs.send, None, rs.each, rs.send_each)
-    rs.cs, rs.xs = ag.cs, ag.xs                   # one compute stream, one copy stream for the pair
-
-    def pair(flags):
-        cf.run_schedule(ag.desc, cf.CF_KIND_AG, ag.bufs, ag.cs, ag.xs, flags)
-        cf.run_schedule(rs.desc, cf.CF_KIND_RS, rs.bufs, rs.cs, rs.xs, flags)
-
-    pair_t = {}
-    pair_modes = {}
-    for name, fl in (("overlapped", 0), ("compute_only", cf.CF_NO_COPY), ("copy_only", cf.CF_NO_COMPUTE)):
-        best = None
-        for mode, extra in MODES:
-            if fl != 0 and (extra & (cf.CF_FUSED_COPY | cf.CF_DEVICE_WAIT)):
-                continue
-            t = time_calls(lambda: pair(fl | extra), ag.cs, K, W)
-            log(f"  pair {name} [{mode}]: {t*1e3:.1f} us")
-            if fl == 0:
-                pair_modes[mode] = round(t * 1e3, 1)
-            if best is None or t < best[0]:
-                best = (t, mode)
-        pair_t[name] = best
-        log(f"pair {name}: {best[0]*1e3:.1f} us ({best[1]})")
     flops_pair = up.flops + dn.flops
-    ms_step = pair_t["overlapped"][0]
-    value = flops_pair / (ms_step * 1e-3) / 1e12
+    value = ms_step = None
+    roofline = vanilla = None
+    pair_t, pair_modes, pair_overlap, pair_by_mode = {}, {}, {}, {}
+    if not args.skip_pair:
+        log("generating 70B-shape inputs ...")
+        # every hop's delivery has a landing buffer of its own (cf_buffers.recv_each): nothing is reused inside a
+        # rank step, so the copy stream never waits for a kernel
+        ag = H.AgRun(up, inputs.make_ag(up), 0, each=True)
+        ddn = inputs.make_rs(dn)
+        rs = H.RsRun(dn, ddn, 0, each=True)
+        rs.A = ag.O                                   # H is handed over on the device, in bf16
+        rs.bufs = cf.make_buffers(rs.A, rs.W, rs.O, rs.stage, rs.slot, rs.send, None, rs.each, rs.send_each)
+        rs.cs, rs.xs = ag.cs, ag.xs                   # one compute stream, one copy stream for the pair
 
-    # dominant kernel: the down-projection rank-step kernel (one persistent launch = the eight chunk GEMMs
-    # of the rank step with their B_in adds and B_out / O stores), launched alone: CF_NO_COPY enqueues nothing else
-    PS = cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_NO_COPY
-    t_kernel = time_calls(lambda: cf.run_schedule(rs.desc, cf.CF_KIND_RS, rs.bufs, rs.cs, rs.xs, PS), ag.cs, max(K, 50), W)
-    ach = dn.flops / (t_kernel * 1e-3) / 1e12
-    t_kernel_up = time_calls(lambda: cf.run_schedule(ag.desc, cf.CF_KIND_AG, ag.bufs, ag.cs, ag.xs, PS), ag.cs, max(K, 50), W)
-    # the same GEMMs as one kernel per step (what every mode but "persistent" launches), step 1 alone
-    t_chunk = time_calls(lambda: cf.rs_step(rs.desc, 1, rs.A, rs.W, rs.stage[0], rs.send[0], ag.cs), ag.cs, max(K, 50), W)
-    t_chunk_up = time_calls(lambda: cf.ag_step(ag.desc, 1, ag.stage[0], ag.W, ag.O, ag.cs), ag.cs, max(K, 50), W)
-    chunk_flops = 2.0 * dn.m_chunk * dn.n * dn.k
-    roofline = {"bound": "mfma",
-                "kernel": "gemm_bf16_dl_kernel<256,256,...,persistent> (down-projection rank step: 8 chunk GEMMs, fused B_in adds)",
-                "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                # bytes through the L2s' memory side per launch from rocprofv3 counters
-                # (profiles/gemm_bf16_dl_kernel_70b_pair_counters.md): FETCH_SIZE x 2.00 (scale from a plain
-                # 256 MiB copy) + WRITE_SIZE; algorithmic bytes: A 58.7 + W 58.7 + B_in 7 x 33.55 + B_out/O 8 x 33.55 MB
-                "traffic": TRAFFIC_DOWN_RANK_STEP, "algorithmic_bytes": 620.7e6,
-                "us_per_launch": round(t_kernel * 1e3, 2),
-                "up_projection_rank_step_kernel": {"us_per_launch": round(t_kernel_up * 1e3, 2),
-                                                   "tflops": round(up.flops / (t_kernel_up * 1e-3) / 1e12, 1)},
-                "one_kernel_per_step": {"down_us": round(t_chunk * 1e3, 2), "down_tflops": round(chunk_flops / (t_chunk * 1e-3) / 1e12, 1),
-                                        "up_us": round(t_chunk_up * 1e3, 2), "up_tflops": round(chunk_flops / (t_chunk_up * 1e-3) / 1e12, 1)}}
-    log(f"rank-step kernel down {t_kernel*1e3:.1f} us = {ach:.0f} TFLOP/s, up {t_kernel_up*1e3:.1f} us; "
-        f"chunk GEMM down {t_chunk*1e3:.1f} us, up {t_chunk_up*1e3:.1f} us")
-    # comparator, same kernels: the layer pair WITHOUT the fusion ("vanilla": the collective, then / after the whole GEMM).
-    # up: all-gather first, then the GEMM over all 8192 rows -- which is what the persistent arrangement does anyway;
-    # down: the GEMM over all 8192 rows into a full fp32 partial (the same persistent kernel, no B_in adds), then the
-    # reduce-scatter: seven deliveries, each added to its slice in a pass of its own (the gradient kernel).
-    # One stream, nothing overlaps: what the paper's method starts from.
-    vanilla = None
-    if not args.only_pair:
-        H_all = ag.O                                              # [8192 x 3584] bf16, written by the up-projection
-        Y_all = torch.empty((dn.p * dn.m_chunk, dn.n), dtype=torch.float32, device=H.DEV)
-        blk = lambda c: H_all[c * dn.m_chunk:(c + 1) * dn.m_chunk]
-        rows = [blk((0 - i) % dn.p) for i in range(1, dn.p)]      # slice of step i where Alg. 1 expects it: no copies needed
-        d_whole = cf.layer_desc(dn.p, 0, dn.m_chunk, dn.n, dn.k, "bf16", "f32")
-        b_whole = cf.make_buffers(blk(0), rs.W, Y_all, rows, (None, None), (None, None), None, rows)
-        chunk_elems = dn.m_chunk * dn.n
-        PS_ = cf.CF_PERSISTENT | cf.CF_SERIAL
+        def pair(flags):
+            cf.run_schedule(ag.desc, cf.CF_KIND_AG, ag.bufs, ag.cs, ag.xs, flags)
+            cf.run_schedule(rs.desc, cf.CF_KIND_RS, rs.bufs, rs.cs, rs.xs, flags)
 
-        def vanilla_up():
-            cf.run_schedule(ag.desc, cf.CF_KIND_AG, ag.bufs, ag.cs, ag.xs, PS_)
+        for name, fl in (("overlapped", 0), ("compute_only", cf.CF_NO_COPY), ("copy_only", cf.CF_NO_COMPUTE)):
+            best = None
+            for mode, extra in MODES:
+                if fl != 0 and (extra & (cf.CF_FUSED_COPY | cf.CF_DEVICE_WAIT)):
+                    continue
+                t = time_calls(lambda: pair(fl | extra), ag.cs, K, W)
+                log(f"  pair {name} [{mode}]: {t*1e3:.1f} us")
+                pair_by_mode.setdefault(mode, {})[name] = t
+                if fl == 0:
+                    pair_modes[mode] = round(t * 1e3, 1)
+                if best is None or t < best[0]:
+                    best = (t, mode)
+            pair_t[name] = best
+            log(f"pair {name}: {best[0]*1e3:.1f} us ({best[1]})")
+        ms_step = pair_t["overlapped"][0]
+        value = flops_pair / (ms_step * 1e-3) / 1e12
 
-        def vanilla_down():
-            cf.run_schedule(d_whole, cf.CF_KIND_AG, b_whole, ag.cs, ag.xs, PS_ | cf.CF_NO_COPY)
-            cf.run_schedule(rs.desc, cf.CF_KIND_RS, rs.bufs, rs.cs, rs.xs, PS_ | cf.CF_NO_COMPUTE)   # the seven deliveries
-            for i in range(1, dn.p):
-                cf.dp_reduce_step(dn.p, 0, i, Y_all, chunk_elems, rs.each[i - 1], ag.cs)
+        # dominant kernel: the down-projection rank-step kernel (one persistent launch = the eight chunk GEMMs
+        # of the rank step with their B_in adds and B_out / O stores), launched alone: CF_NO_COPY enqueues nothing else
+        PS = cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_NO_COPY
+        t_kernel = time_calls(lambda: cf.run_schedule(rs.desc, cf.CF_KIND_RS, rs.bufs, rs.cs, rs.xs, PS), ag.cs, max(K, 50), W)
+        ach = dn.flops / (t_kernel * 1e-3) / 1e12
+        t_kernel_up = time_calls(lambda: cf.run_schedule(ag.desc, cf.CF_KIND_AG, ag.bufs, ag.cs, ag.xs, PS), ag.cs, max(K, 50), W)
+        # the same GEMMs as one kernel per step (what every mode but "persistent" launches), step 1 alone
+        t_chunk = time_calls(lambda: cf.rs_step(rs.desc, 1, rs.A, rs.W, rs.stage[0], rs.send[0], ag.cs), ag.cs, max(K, 50), W)
+        t_chunk_up = time_calls(lambda: cf.ag_step(ag.desc, 1, ag.stage[0], ag.W, ag.O, ag.cs), ag.cs, max(K, 50), W)
+        chunk_flops = 2.0 * dn.m_chunk * dn.n * dn.k
+        roofline = {"bound": "mfma",
+                    "kernel": "gemm_bf16_dl_kernel<256,256,...,persistent> (down-projection rank step: 8 chunk GEMMs, fused B_in adds)",
+                    "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                    # bytes through the L2s' memory side per launch from rocprofv3 counters
+                    # (profiles/gemm_bf16_dl_kernel_70b_pair_counters.md): FETCH_SIZE x 2.00 (scale from a plain
+                    # 256 MiB copy) + WRITE_SIZE; algorithmic bytes: A 58.7 + W 58.7 + B_in 7 x 33.55 + B_out/O 8 x 33.55 MB
+                    "traffic": TRAFFIC_DOWN_RANK_STEP, "algorithmic_bytes": 620.7e6,
+                    "us_per_launch": round(t_kernel * 1e3, 2),
+                    "up_projection_rank_step_kernel": {"us_per_launch": round(t_kernel_up * 1e3, 2),
+                                                       "tflops": round(up.flops / (t_kernel_up * 1e-3) / 1e12, 1)},
+                    "one_kernel_per_step": {"down_us": round(t_chunk * 1e3, 2), "down_tflops": round(chunk_flops / (t_chunk * 1e-3) / 1e12, 1),
+                                            "up_us": round(t_chunk_up * 1e3, 2), "up_tflops": round(chunk_flops / (t_chunk_up * 1e-3) / 1e12, 1)}}
+        log(f"rank-step kernel down {t_kernel*1e3:.1f} us = {ach:.0f} TFLOP/s, up {t_kernel_up*1e3:.1f} us; "
+            f"chunk GEMM down {t_chunk*1e3:.1f} us, up {t_chunk_up*1e3:.1f} us")
+        # comparator, same kernels: the layer pair WITHOUT the fusion ("vanilla": the collective, then / after the whole GEMM).
+        # up: all-gather first, then the GEMM over all 8192 rows -- which is what the persistent arrangement does anyway;
+        # down: the GEMM over all 8192 rows into a full fp32 partial (the same persistent kernel, no B_in adds), then the
+        # reduce-scatter: seven deliveries, each added to its slice in a pass of its own (the gradient kernel).
+        # One stream, nothing overlaps: what the paper's method starts from.
+        if sections:
+            H_all = ag.O                                              # [8192 x 3584] bf16, written by the up-projection
+            Y_all = torch.empty((dn.p * dn.m_chunk, dn.n), dtype=torch.float32, device=H.DEV)
+            blk = lambda c: H_all[c * dn.m_chunk:(c + 1) * dn.m_chunk]
+            rows = [blk((0 - i) % dn.p) for i in range(1, dn.p)]      # slice of step i where Alg. 1 expects it: no copies needed
+            d_whole = cf.layer_desc(dn.p, 0, dn.m_chunk, dn.n, dn.k, "bf16", "f32")
+            b_whole = cf.make_buffers(blk(0), rs.W, Y_all, rows, (None, None), (None, None), None, rows)
+            chunk_elems = dn.m_chunk * dn.n
+            PS_ = cf.CF_PERSISTENT | cf.CF_SERIAL
 
-        t_vu = time_calls(vanilla_up, ag.cs, K, W)
-        t_vd = time_calls(vanilla_down, ag.cs, K, W)
-        t_vp = time_calls(lambda: (vanilla_up(), vanilla_down()), ag.cs, K, W)
-        vanilla = {"us_up_gather_then_gemm": round(t_vu * 1e3, 1), "us_down_gemm_then_reduce_scatter": round(t_vd * 1e3, 1),
-                   "us_pair": round(t_vp * 1e3, 1), "tflops_pair": round(flops_pair / (t_vp * 1e-3) / 1e12, 1),
-                   "vanilla_over_fused": round(t_vp / ms_step, 3)}
-        log("vanilla", vanilla)
-        del Y_all, b_whole, rows
-    del ag, rs, ddn
-    torch.cuda.empty_cache()
+            def vanilla_up():
+                cf.run_schedule(ag.desc, cf.CF_KIND_AG, ag.bufs, ag.cs, ag.xs, PS_)
+
+            def vanilla_down():
+                cf.run_schedule(d_whole, cf.CF_KIND_AG, b_whole, ag.cs, ag.xs, PS_ | cf.CF_NO_COPY)
+                cf.run_schedule(rs.desc, cf.CF_KIND_RS, rs.bufs, rs.cs, rs.xs, PS_ | cf.CF_NO_COMPUTE)   # the seven deliveries
+                for i in range(1, dn.p):
+                    cf.dp_reduce_step(dn.p, 0, i, Y_all, chunk_elems, rs.each[i - 1], ag.cs)
+
+            t_vu = time_calls(vanilla_up, ag.cs, K, W)
+            t_vd = time_calls(vanilla_down, ag.cs, K, W)
+            t_vp = time_calls(lambda: (vanilla_up(), vanilla_down()), ag.cs, K, W)
+            vanilla = {"us_up_gather_then_gemm": round(t_vu * 1e3, 1), "us_down_gemm_then_reduce_scatter": round(t_vd * 1e3, 1),
+                       "us_pair": round(t_vp * 1e3, 1), "tflops_pair": round(flops_pair / (t_vp * 1e-3) / 1e12, 1),
+                       "vanilla_over_fused": round(t_vp / ms_step, 3)}
+            log("vanilla", vanilla)
+            del Y_all, b_whole, rows
+        del ag, rs, ddn
+        torch.cuda.empty_cache()
 
     # ---------------- the two 7B-shape rank steps ----------------
     others = {}
-    if not args.only_pair:
+    if "7b" in sections:
         for name, Run, make, kind in (("c2_rs_7b", H.RsRun, inputs.make_rs, cf.CF_KIND_RS),
                                       ("c3_ag_7b", H.AgRun, inputs.make_ag, cf.CF_KIND_AG)):
             w = inputs.CONFIGS[name]
@@ -239,16 +278,18 @@ def main() -> int:
             others[name] = {"tflops": round(w.flops / (t["overlapped"][0] * 1e-3) / 1e12, 1),
                             "frac_mfma_peak": round(w.flops / (t["overlapped"][0] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
                             "us_per_rank_step": round(t["overlapped"][0] * 1e3, 1), "mode": t["overlapped"][1],
-                            "overlap_eff": round(overlap_eff(t), 3),
+                            **overlap_eff(t),
                             "us_compute_only": round(t["compute_only"][0] * 1e3, 1),
-                            "us_copy_only": round(t["copy_only"][0] * 1e3, 1)}
+                            "us_copy_only": round(t["copy_only"][0] * 1e3, 1),
+                            "tflops_compute_only": round(w.flops / (t["compute_only"][0] * 1e-3) / 1e12, 1),
+                            "overlap_by_mode": overlap_by_mode(t)}
             log(name, others[name])
             del run
             torch.cuda.empty_cache()
 
     # ---------------- GEMM + reduce-scatter under the pairwise bidirectional schedule ----------------
     pairwise = {}
-    if not args.only_pair:
+    if "pairwise" in sections:
         for name in ("c2_rs_7b", "c4_rs_70b_down"):
             w = inputs.CONFIGS[name]
             data = inputs.make_rs(w)
@@ -259,7 +300,7 @@ def main() -> int:
             t = schedule_times(run, cf.CF_KIND_RS_PAIR, max(K, 50), W)
             pairwise[name] = {"us_per_rank_step_incremental_aggregation": round(t_inc["overlapped"][0] * 1e3, 1),"tflops": round(w.flops / (t["overlapped"][0] * 1e-3) / 1e12, 1),
                               "us_per_rank_step": round(t["overlapped"][0] * 1e3, 1), "mode": t["overlapped"][1],
-                              "overlap_eff": round(overlap_eff(t), 3),
+                              **overlap_eff(t),
                               "us_compute_only": round(t["compute_only"][0] * 1e3, 1),
                               "us_copy_only": round(t["copy_only"][0] * 1e3, 1)}
             log("pairwise", name, pairwise[name])
@@ -268,7 +309,7 @@ def main() -> int:
 
     # ---------------- slicing granularity m = 2 (two sub-steps per ring hop) ----------------
     granularity = {}
-    if not args.only_pair:
+    if "granularity" in sections:
         for name, Run, make, kind in (("c4_rs_70b_down", H.RsRun, inputs.make_rs, cf.CF_KIND_RS),
                                       ("c4_ag_70b_up", H.AgRun, inputs.make_ag, cf.CF_KIND_AG)):
             w = inputs.CONFIGS[name]
@@ -279,7 +320,7 @@ def main() -> int:
                 t = schedule_times(run, kind, max(K, 50), W)
                 entry[f"m{m}"] = {"tflops": round(w.flops / (t["overlapped"][0] * 1e-3) / 1e12, 1),
                                   "us_per_rank_step": round(t["overlapped"][0] * 1e3, 1), "mode": t["overlapped"][1],
-                                  "overlap_eff": round(overlap_eff(t), 3),
+                                  **overlap_eff(t),
                                   "us_compute_only": round(t["compute_only"][0] * 1e3, 1)}
                 del run
                 torch.cuda.empty_cache()
@@ -288,7 +329,7 @@ def main() -> int:
 
     # ---------------- backward pass of the 70B pair: two data gradients, two weight gradients ----------------
     backward = {}
-    if not args.only_pair:
+    if "backward" in sections:
         rng = np.random.default_rng(inputs.BASE_SEED + 77)
         def bf16_dev(shape, sigma):
             return H.to_dev(inputs.f32_to_bf16_bits(rng.standard_normal(shape, dtype=np.float32) * sigma), "bf16")
@@ -352,7 +393,7 @@ def main() -> int:
 
     # ---------------- query-split attention FuseRS (Alg. 4), 70B shape: 8 of 64 heads per rank ----------------
     attention = {}
-    if not args.only_pair:
+    if "attention" in sections:
         rng = np.random.default_rng(inputs.BASE_SEED + 78)
         pa, Ba, ha, Sa, Da = 8, 1, 8, 8192, 8192
         mca = Ba * Sa // pa
@@ -387,7 +428,7 @@ def main() -> int:
 
     # ---------------- gradient reduce-scatter step, 1e9 fp32 elements ----------------
     dp = None
-    if not (args.skip_dp or args.only_pair):
+    if "dp" in sections:
         w5 = inputs.CONFIGS["c5_dp"]
         log("generating the 1e9-element gradient bucket on the host (about half a minute) ...")
         t0 = time.time()
@@ -406,6 +447,7 @@ def main() -> int:
             for mode, extra in (m_ for m_ in MODES if "persistent" in m_[0]):
                 tp = time_calls(lambda: cf.run_schedule(pers.desc, cf.CF_KIND_DP, pers.bufs, pers.cs, pers.xs, fl | extra),
                                 pers.cs, 10, 2)
+                t["by_mode"].setdefault(mode, {})[name] = tp
                 if tp < t[name][0]:
                     t[name] = (tp, mode)
         # pairwise schedule on the same bucket: seven arrivals for the own slice, summed in one pass (36 B per element)
@@ -419,7 +461,7 @@ def main() -> int:
               "rank_step_us": round(t["overlapped"][0] * 1e3, 1), "rank_step_mode": t["overlapped"][1],
               "rank_step_GBps_algorithmic": round(12.0 * c * steps_with_add / (t["overlapped"][0] * 1e-3) / 1e9, 1),
               "rank_step_GBps_with_copies": round(20.0 * c * steps_with_add / (t["overlapped"][0] * 1e-3) / 1e9, 1),
-              "overlap_eff": round(overlap_eff(t), 3),
+              **overlap_eff(t),
               "us_compute_only": round(t["compute_only"][0] * 1e3, 1), "us_copy_only": round(t["copy_only"][0] * 1e3, 1),
               "pairwise_rank_step_us": round(t_pw * 1e3, 1), "pairwise_us_compute_only": round(t_pw_c * 1e3, 1),
               "pairwise_add_GBps": round(4.0 * (w5.p + 1) * c / (t_pw_c * 1e-3) / 1e9, 1)}
@@ -456,6 +498,22 @@ def main() -> int:
         b.copy_(a)                                                   # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
 
+    if args.skip_pair:                                # profiling run of one section: no headline, no contract line
+        print(json.dumps({"sections": sorted(sections), "dp_reduce": dp, "other_configs": others, "pairwise_schedule": pairwise,
+                          "slicing_granularity": granularity, "backward_pass": backward,
+                          "query_split_attention": attention}), flush=True)
+        return 0
+    # overlap figures: every mode against ITS OWN compute-only and copy-only times (the fused-copy and
+    # device-wait modes have no such variants and take the stream mode's)
+    ref = pair_by_mode.get("streams", {})
+    for mode, v in pair_by_mode.items():
+        comp, cpy = v.get("compute_only", ref.get("compute_only")), v.get("copy_only", ref.get("copy_only"))
+        if "overlapped" in v and comp and cpy:
+            pair_overlap[mode] = dict(us_per_step=round(v["overlapped"] * 1e3, 1), **overlap_of(v["overlapped"], comp, cpy))
+    head_mode = pair_t["overlapped"][1]
+    head = pair_by_mode[head_mode]
+    head_comp = head.get("compute_only", pair_t["compute_only"][0])
+    head_copy = head.get("copy_only", pair_t["copy_only"][0])
     line = {
         "metric": "rank-step TFLOP/s (% bf16 MFMA peak) + overlap efficiency; grad-reduce GB/s",
         "value": round(value, 1), "unit": "TFLOP/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -463,10 +521,15 @@ def main() -> int:
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "Llama-70B-shape MLP pair rank step, p=8: AG-GEMM up [8x(1024x8192)]x[8192x3584] -> bf16 H, "
                                "GEMM-RS down [8x(1024x3584)]x[3584x8192] + fp32 partials; emulated ring on one GPU",
-                   "p": 8, "rank": 0, "mode": pair_t["overlapped"][1], "us_per_step_by_mode": pair_modes},
+                   "p": 8, "rank": 0, "mode": head_mode, "us_per_step_by_mode": pair_modes,
+                   "mode_note": "persistent = every delivery enqueued in front of ONE kernel per layer (nothing is hidden: "
+                                "hidden_fraction ~ 0); streams / graph / fused-copy / device-wait overlap each delivery with "
+                                "the step kernel before it"},
         "frac_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
-        "overlap_eff": round(max(pair_t["compute_only"][0], pair_t["copy_only"][0]) / ms_step, 3),
-        "ms_compute_only": round(pair_t["compute_only"][0], 4), "ms_copy_only": round(pair_t["copy_only"][0], 4),
+        # of the headline mode, against its own compute-only and copy-only times
+        **overlap_of(ms_step, head_comp, head_copy),
+        "overlap_by_mode": pair_overlap,
+        "ms_compute_only": round(head_comp, 4), "ms_copy_only": round(head_copy, 4),
         "roofline": roofline, "cpu_baseline": cpu, "dp_reduce": dp, "other_configs": others,
         "vanilla_comparator": vanilla,
         "pairwise_schedule": pairwise, "slicing_granularity": granularity, "backward_pass": backward, "query_split_attention": attention,

@@ -372,7 +372,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     };
     auto issue_range = [&](int kt, int stage_a, int stage_w, auto lo_tag, auto hi_tag) __attribute__((always_inline)) {   // loads [lo, hi) of a tile
         constexpr int lo = decltype(lo_tag)::value, hi = decltype(hi_tag)::value;
-        static_assert(hi - lo <= 8, "at most eight direct loads per tile and wave");
+        static_assert(hi - lo <= 12, "at most twelve direct loads per tile and wave");
         const int k0 = ktile(kt) * BK;
         const unsigned sa = lds_base + stage_a * A_BYTES + wave * 1024;
         const unsigned sw = lds_base + W_BASE + stage_w * B_BYTES + wave * 1024;
@@ -394,6 +394,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             if constexpr (lo + 5 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 5>{}, std::false_type{});
             if constexpr (lo + 6 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 6>{}, std::false_type{});
             if constexpr (lo + 7 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 7>{}, std::false_type{});
+            if constexpr (lo + 8 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 8>{}, std::false_type{});
+            if constexpr (lo + 9 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 9>{}, std::false_type{});
+            if constexpr (lo + 10 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 10>{}, std::false_type{});
+            if constexpr (lo + 11 < hi) issue_load(kt, stage_a, stage_w, std::integral_constant<int, lo + 11>{}, std::false_type{});
         }
     };
 
@@ -488,7 +492,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     constexpr int NSEG = NMFMA < 4 ? NMFMA : 4;
     constexpr int MPS = NMFMA / NSEG;                       // MFMAs per segment
     constexpr int LH = LPT < NSEG ? LPT : NSEG;             // loads issued in the first load phase
-    static_assert(NMFMA % NSEG == 0 && LPT - LH <= NSEG, "segmenting");
+    static_assert(NMFMA % NSEG == 0 && (!SPREAD || LPT - LH <= NSEG), "segmenting");
     auto mfma_seg = [&](const bf16x8_t (&af)[TM], const bf16x8_t (&wf)[TN], auto seg_tag) __attribute__((always_inline)) {
         constexpr int seg = decltype(seg_tag)::value;
 #pragma unroll
