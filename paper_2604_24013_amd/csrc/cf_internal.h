@@ -95,6 +95,7 @@ struct Tuning {
     int xcd_steps = -1;             // COMMFUSE_XCD_STEPS = 0 | 1                          (-1 = unset)
     int k_rotate = -1;              // COMMFUSE_K_ROTATE = 0 | 1                           (-1 = unset)
     int stream_recv = -1;           // COMMFUSE_STREAM_RECV = 0 | 1                        (-1 = unset)
+    int persist_wgs = 0;            // COMMFUSE_PERSIST_WGS = cap on the persistent kernel's grid (0 = unset)
     int tile_f32_bm = 0;            // COMMFUSE_TILE_F32 = "128x128" | "64x64"             (0 = unset)
     unsigned spin_limit = 0;        // COMMFUSE_SPIN_LIMIT                                 (0 = unset)
     int attn_qt = -1;               // COMMFUSE_ATTN_QT = 0 | 1 | 2                        (-1 = unset)

@@ -1278,6 +1278,8 @@ static Tuning read_tuning_from_environment()
         t.xcd_steps = atoi(e) != 0;
     if (const char *e = getenv("COMMFUSE_K_ROTATE"))
         t.k_rotate = atoi(e) != 0;
+    if (const char *e = getenv("COMMFUSE_PERSIST_WGS"))
+        t.persist_wgs = atoi(e) > 0 ? atoi(e) : 0;
     if (const char *e = getenv("COMMFUSE_STREAM_RECV"))
         t.stream_recv = atoi(e) != 0;
     if (const char *e = getenv("COMMFUSE_TILE_F32"))

@@ -567,8 +567,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // before the last one; a step that waits for a delivery flag, sums several received partials or is a k-split
     // keeps the loads in the epilogue.
     constexpr int RQ = TM * TN;                       // 32x32 sub-tiles per wave, one in flight at a time
+    // A ragged k tail (the launcher then leaves the k order unrotated: it is the last k-tile) is requested in the
+    // last two iterations before the final tile; those test their loads and come after the streamed ones.
+    const int tested = (RLDS && K % BK != 0) ? (nk - 1 < 2 ? nk - 1 : 2) : 0;
     const bool streamed = RLDS && cRecv != nullptr && cFlag == nullptr && n_more == 0 && splits == 1 &&
-                          P.stream_recv && nk >= 2 * RQ + 1;
+                          P.stream_recv && nk >= 2 * RQ + 1 + tested && (tested == 0 || rot == 0);
     if constexpr (RLDS) {
         // Two stages of both operands (tile t in stage t & 1) and the landing area.  Iteration kt:
         //     slice 0: + the weight loads of tile kt+1 (its stage was vacated at the barrier of iteration kt-1)
@@ -659,16 +662,16 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 __builtin_amdgcn_sched_barrier(0);
                 phase(af1, wf1, true, nxt, nxt, 0, af0, wf0, kt + 2, cur, 0, c0{}, cALD{}, wk);
             };
-            // (the launcher takes this variant only when K is a multiple of the k-tile: every load is branch-free)
             auto iteration = [&](int kt, auto mode_tag, int q, auto q_tag) __attribute__((always_inline)) {
-                iteration_wk(kt, mode_tag, q, q_tag, std::true_type{});
+                iteration_wk(kt, mode_tag, q, q_tag, std::true_type{});     // branch-free loads
             };
             using wk = std::true_type;                       // (the last tile requests nothing)
             using m0_t = std::integral_constant<int, 0>;
             using m1_t = std::integral_constant<int, 1>;
             using m2_t = std::integral_constant<int, 2>;
             int kt = 0;
-            const int first = streamed ? nk - 1 - 2 * RQ : nk - 1;
+            const int untested = (tested > 0 && rot != 0) ? 0 : nk - 1 - tested;   // iterations with branch-free loads
+            const int first = streamed ? untested - 2 * RQ : untested;
             for (; kt < first; ++kt)
                 iteration(kt, m0_t{}, 0, c0{});
             if (streamed) {
@@ -687,6 +690,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 pair_of(std::integral_constant<int, 6>{});
                 pair_of(std::integral_constant<int, 7>{});
             }
+            for (; kt + 1 < nk; ++kt)                        // the iterations that request the ragged k-tile
+                iteration_wk(kt, m0_t{}, 0, c0{}, std::false_type{});
             if (nk > 0) {                                    // last tile: nothing follows it
                 const int cur = (nk - 1) & 1;
                 phase(af0, wf0, true, cur, cur, 1, af1, wf1, 0, 0, 0, c0{}, c0{}, wk{});
@@ -979,7 +984,7 @@ hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t
     bool any_recv = p.recv != nullptr;
     for (int j = 0; j < p.n_steps; ++j)
         any_recv = any_recv || p.recv_step[j] != nullptr;
-    [[maybe_unused]] const bool rlds = SPREAD && NS == 2 && any_recv && !out_bf16 && !p.a_t && p.stream_recv && p.K % BK == 0;
+    [[maybe_unused]] const bool rlds = SPREAD && NS == 2 && any_recv && !out_bf16 && !p.a_t && p.stream_recv;
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     int wgs = tiles_m * tiles_n * p.splits + p.cp_wgs;
     if (p.n_steps > 0) {                             // persistent: a grid that fills the chip once
@@ -989,6 +994,8 @@ hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t
         if (p.xcd_steps)                             // whole octets of workgroups: the same number per XCD
             wgs = (tiles_m * tiles_n * (p.n_steps / 8) < p.num_cu * per_cu / 8 ? tiles_m * tiles_n * (p.n_steps / 8)
                                                                               : p.num_cu * per_cu / 8) * 8;
+        if (const int cap = tuning().persist_wgs; cap >= 8 && cap < wgs)   // override: leave compute units free
+            wgs = p.xcd_steps ? cap / 8 * 8 : cap;
     }
     const dim3 grid(wgs), block(64 * WGM * WGN);
     if (p.n_steps > 0) {                             // persistent rank step: fp32 or bf16 output, either weight order
