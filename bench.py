@@ -27,7 +27,10 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 SETTLE_S = 0.06               # untimed load before every timed region (see time_calls)
-TRAFFIC_DOWN_RANK_STEP = 1253.4e6   # measured, see the roofline object
+# HBM-side bytes per launch of the dominant kernel from rocprofv3 counters (FETCH_SIZE x 2.00 + WRITE_SIZE): a constant
+# taken from TRAFFIC_SOURCE, not measured in this run -- to be re-derived there whenever that kernel changes
+TRAFFIC_DOWN_RANK_STEP = 1300.8e6
+TRAFFIC_SOURCE = "profiles/gemm_bf16_dl_kernel_70b_pair_counters.md"
 
 
 def log(*a):
@@ -218,13 +221,14 @@ def main() -> int:
         t_chunk_up = time_calls(lambda: cf.ag_step(ag.desc, 1, ag.stage[0], ag.W, ag.O, ag.cs), ag.cs, max(K, 50), W)
         chunk_flops = 2.0 * dn.m_chunk * dn.n * dn.k
         roofline = {"bound": "mfma",
-                    "kernel": "gemm_bf16_dl_kernel<256,256,...,persistent> (down-projection rank step: 8 chunk GEMMs, fused B_in adds)",
+                    "kernel": "gemm_bf16_dl_kernel<256,256,...,persistent,B_in through LDS> (down-projection rank step: 8 chunk GEMMs, "
+                              "fused B_in adds, every step's B_out stored)",
                     "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                    # bytes through the L2s' memory side per launch from rocprofv3 counters
-                    # (profiles/gemm_bf16_dl_kernel_70b_pair_counters.md): FETCH_SIZE x 2.00 (scale from a plain
-                    # 256 MiB copy) + WRITE_SIZE; algorithmic bytes: A 58.7 + W 58.7 + B_in 7 x 33.55 + B_out/O 8 x 33.55 MB
-                    "traffic": TRAFFIC_DOWN_RANK_STEP, "algorithmic_bytes": 620.7e6,
+                    # bytes through the L2s' memory side per launch from rocprofv3 counters: FETCH_SIZE x 2.00 (scale
+                    # from a plain 256 MiB copy) + WRITE_SIZE; algorithmic bytes: A 58.7 + W 58.7 + B_in 7 x 33.55 +
+                    # B_out/O 8 x 33.55 MB
+                    "traffic": TRAFFIC_DOWN_RANK_STEP, "traffic_source": TRAFFIC_SOURCE, "algorithmic_bytes": 620.7e6,
                     "us_per_launch": round(t_kernel * 1e3, 2),
                     "up_projection_rank_step_kernel": {"us_per_launch": round(t_kernel_up * 1e3, 2),
                                                        "tflops": round(up.flops / (t_kernel_up * 1e-3) / 1e12, 1)},

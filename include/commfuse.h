@@ -437,12 +437,17 @@ const char *commfuse_last_error(void);
  *   commfuse_workspace_bytes: size that lets every split choice be used for this
  *     layer (0 if the kind / dtype never splits).  Host-only arithmetic.
  *   commfuse_set_workspace: registers a caller-owned DEVICE buffer (16-byte
- *     aligned) for all later calls on this process, or clears the registration
- *     (NULL / 0).  Its first 64 KiB (arrival counters, delivery flags, a status word)
- *     are zeroed on `hip_stream` (this is the one
+ *     aligned), or clears a registration (NULL / 0).  With hip_stream == NULL the
+ *     buffer serves all later calls of this process; with a stream it serves the
+ *     work enqueued on THAT stream (for commfuse_run_schedule: the compute stream)
+ *     and takes precedence there -- two layers in flight on two streams each
+ *     register a workspace of their own.  The first 64 KiB (arrival counters,
+ *     delivery flags, a status word) are zeroed on `hip_stream` (this is the one
  *     call that enqueues a memset; do not capture it into a graph).  The caller
  *     keeps the buffer alive and unmodified while registered.  Steps that
  *     overlap in time on the GPU must not share a workspace.
+ *     commfuse_device_status(stream) reads the status word of the workspace that
+ *     serves `stream`.
  */
 size_t commfuse_workspace_bytes(const cf_layer_desc *desc, int kind);
 cf_status commfuse_set_workspace(void *device_ptr, size_t bytes, void *hip_stream);

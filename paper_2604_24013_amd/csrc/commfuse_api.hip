@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <map>
 #include <mutex>
 #include <unordered_map>
 #include <vector>
@@ -70,7 +71,20 @@ struct Workspace {
     size_t bytes = 0;
 };
 std::mutex g_ws_mu;
-Workspace g_ws;
+Workspace g_ws;                                              // registered without a stream: serves every stream ...
+std::unordered_map<hipStream_t, Workspace> g_ws_of_stream;   // ... that has no registration of its own
+
+// The workspace the work enqueued on stream `s` uses.
+Workspace workspace_for(hipStream_t s)
+{
+    std::lock_guard<std::mutex> lk(g_ws_mu);
+    if (s != nullptr) {
+        auto it = g_ws_of_stream.find(s);
+        if (it != g_ws_of_stream.end())
+            return it->second;
+    }
+    return g_ws;
+}
 
 // Scratch of commfuse_rs_step_noalloc: the same layout as a registered workspace (arrival counters, then fp32
 // partial tiles), but owned by the library, in device memory that exists from the moment the code object is
@@ -255,8 +269,7 @@ cf_status launch_gemm(const Resolved &r, const void *A_rows, const void *W, cons
     gp.out = out;
     fill_shape(gp, r);
     {
-        std::lock_guard<std::mutex> lk(g_ws_mu);
-        const Workspace ws = ws_instead != nullptr ? *ws_instead : g_ws;   // (the library's own scratch, or the registered one)
+        const Workspace ws = ws_instead != nullptr ? *ws_instead : workspace_for(s);   // (the library's own scratch, or the registered one)
         if (ws.ptr != nullptr && ws.bytes > WS_COUNTER_BYTES) {
             gp.counters = static_cast<unsigned *>(ws.ptr);
             gp.ws = reinterpret_cast<float *>(static_cast<char *>(ws.ptr) + WS_COUNTER_BYTES);
@@ -382,11 +395,11 @@ cf_status wgrad_step_impl(const Resolved &r, int step, const void *left, const v
     if (!cf::gemm_bf16_takes_recv_list(gp, true))
         return fail(CF_ERR_UNSUPPORTED, "the weight-gradient step needs operands below 2 GiB (direct-to-LDS kernel)");
     {
-        std::lock_guard<std::mutex> lk(g_ws_mu);
-        if (g_ws.ptr != nullptr && g_ws.bytes > WS_COUNTER_BYTES) {
-            gp.counters = static_cast<unsigned *>(g_ws.ptr);
-            gp.ws = reinterpret_cast<float *>(static_cast<char *>(g_ws.ptr) + WS_COUNTER_BYTES);
-            gp.ws_bytes = g_ws.bytes - WS_COUNTER_BYTES;
+        const Workspace ws = workspace_for(s);
+        if (ws.ptr != nullptr && ws.bytes > WS_COUNTER_BYTES) {
+            gp.counters = static_cast<unsigned *>(ws.ptr);
+            gp.ws = reinterpret_cast<float *>(static_cast<char *>(ws.ptr) + WS_COUNTER_BYTES);
+            gp.ws_bytes = ws.bytes - WS_COUNTER_BYTES;
             gp.max_tiles = (int)(WS_TILE_COUNTER_BYTES / sizeof(unsigned));
         }
     }
@@ -561,11 +574,13 @@ std::mutex g_mu;
 std::unordered_map<int, std::vector<hipEvent_t>> g_events;   // per device
 
 struct GraphEntry {
-    std::vector<unsigned char> key;
     hipGraph_t graph;
     hipGraphExec_t exec;
 };
-std::vector<GraphEntry> g_graphs;
+// captured rank steps by argument set; at most MAX_GRAPHS are kept (a caller that keeps changing its
+// arguments gets CF_ERR_INVALID_ARG instead of an ever-growing cache: commfuse_destroy_cache empties it)
+constexpr size_t MAX_GRAPHS = 4096;
+std::map<std::vector<unsigned char>, GraphEntry> g_graphs;
 
 cf_status get_events(size_t count, std::vector<hipEvent_t> *out)
 {
@@ -596,11 +611,11 @@ cf_status launch_attention(const AttnCtx &ctx, int l, hipStream_t s, int n_slice
     ap.n_slices = n_slices;
     ap.out_slice_stride = (int64_t)ap.batch * ap.c * ap.ldo;
     {
-        std::lock_guard<std::mutex> lk(g_ws_mu);
-        if (g_ws.ptr != nullptr && g_ws.bytes > WS_COUNTER_BYTES) {
-            ap.counters = static_cast<unsigned *>(g_ws.ptr);
-            ap.ws = reinterpret_cast<float *>(static_cast<char *>(g_ws.ptr) + WS_COUNTER_BYTES);
-            ap.ws_bytes = g_ws.bytes - WS_COUNTER_BYTES;
+        const Workspace ws = workspace_for(s);
+        if (ws.ptr != nullptr && ws.bytes > WS_COUNTER_BYTES) {
+            ap.counters = static_cast<unsigned *>(ws.ptr);
+            ap.ws = reinterpret_cast<float *>(static_cast<char *>(ws.ptr) + WS_COUNTER_BYTES);
+            ap.ws_bytes = ws.bytes - WS_COUNTER_BYTES;
             ap.max_groups = (int)(WS_TILE_COUNTER_BYTES / sizeof(unsigned));
         }
     }
@@ -623,11 +638,11 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
     const bool dwait = (flags & CF_DEVICE_WAIT) != 0 && !(flags & CF_NO_COMPUTE) && !fused;
     unsigned *dw_flags = nullptr, *dw_status = nullptr;
     if (dwait) {
-        std::lock_guard<std::mutex> lk(g_ws_mu);
-        if (g_ws.ptr == nullptr || g_ws.bytes < WS_COUNTER_BYTES)
+        const Workspace ws = workspace_for(cs);
+        if (ws.ptr == nullptr || ws.bytes < WS_COUNTER_BYTES)
             return fail(CF_ERR_INVALID_ARG, "CF_DEVICE_WAIT needs a registered workspace (commfuse_set_workspace)");
-        dw_flags = reinterpret_cast<unsigned *>(static_cast<char *>(g_ws.ptr) + WS_FLAG_OFFSET);
-        dw_status = reinterpret_cast<unsigned *>(static_cast<char *>(g_ws.ptr) + WS_STATUS_OFFSET);
+        dw_flags = reinterpret_cast<unsigned *>(static_cast<char *>(ws.ptr) + WS_FLAG_OFFSET);
+        dw_status = reinterpret_cast<unsigned *>(static_cast<char *>(ws.ptr) + WS_STATUS_OFFSET);
     }
     const bool serial = (flags & CF_SERIAL) != 0 || xs_in == cs || fused;
     hipStream_t xs = serial ? cs : xs_in;
@@ -1144,9 +1159,9 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
         append_bytes(key, &tn, sizeof(tn));
     }
     {   // the registered workspace is baked into the captured kernels (split-K partials, delivery flags)
-        std::lock_guard<std::mutex> lk(g_ws_mu);
-        append_bytes(key, &g_ws.ptr, sizeof(g_ws.ptr));
-        append_bytes(key, &g_ws.bytes, sizeof(g_ws.bytes));
+        const Workspace ws = workspace_for(cs);
+        append_bytes(key, &ws.ptr, sizeof(ws.ptr));
+        append_bytes(key, &ws.bytes, sizeof(ws.bytes));
     }
     for (int i = 0; i < r.p - 1; ++i) {
         const void *st = bufs->peer_stage ? bufs->peer_stage[i] : nullptr;
@@ -1161,9 +1176,12 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
     hipGraphExec_t exec = nullptr;
     {
         std::lock_guard<std::mutex> lk(g_mu);
-        for (const GraphEntry &g : g_graphs)
-            if (g.key == key)
-                exec = g.exec;
+        auto it = g_graphs.find(key);
+        if (it != g_graphs.end())
+            exec = it->second.exec;
+        else if (g_graphs.size() >= MAX_GRAPHS)
+            return fail(CF_ERR_INVALID_ARG, "CF_GRAPH: %zu captured argument sets are cached already; call "
+                                            "commfuse_destroy_cache() to release them", g_graphs.size());
     }
     if (exec == nullptr) {
         // events must exist before capture starts (creation is not a capturable operation)
@@ -1189,7 +1207,7 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
             return fail_hip(e, "hipGraphInstantiate");
         }
         std::lock_guard<std::mutex> lk(g_mu);
-        g_graphs.push_back(GraphEntry{key, graph, exec});
+        g_graphs.emplace(key, GraphEntry{graph, exec});
     }
     CF_HIP(hipGraphLaunch(exec, cs));
     return CF_OK;
@@ -1541,9 +1559,13 @@ size_t commfuse_workspace_bytes(const cf_layer_desc *desc, int kind)
 
 cf_status commfuse_set_workspace(void *device_ptr, size_t bytes, void *hip_stream)
 {
+    hipStream_t key = static_cast<hipStream_t>(hip_stream);
     if (device_ptr == nullptr || bytes == 0) {
         std::lock_guard<std::mutex> lk(g_ws_mu);
-        g_ws = Workspace{};
+        if (key != nullptr)
+            g_ws_of_stream.erase(key);
+        else
+            g_ws = Workspace{};
         return CF_OK;
     }
     if (!aligned16(device_ptr))
@@ -1553,18 +1575,15 @@ cf_status commfuse_set_workspace(void *device_ptr, size_t bytes, void *hip_strea
     // arrival counters start at zero; the kernels leave them at zero
     CF_HIP(hipMemsetAsync(device_ptr, 0, WS_COUNTER_BYTES, static_cast<hipStream_t>(hip_stream)));
     std::lock_guard<std::mutex> lk(g_ws_mu);
-    g_ws.ptr = device_ptr;
-    g_ws.bytes = bytes;
+    Workspace &w = key != nullptr ? g_ws_of_stream[key] : g_ws;
+    w.ptr = device_ptr;
+    w.bytes = bytes;
     return CF_OK;
 }
 
 cf_status commfuse_device_status(void *hip_stream)
 {
-    void *ws = nullptr;
-    {
-        std::lock_guard<std::mutex> lk(g_ws_mu);
-        ws = g_ws.ptr;
-    }
+    void *ws = workspace_for(static_cast<hipStream_t>(hip_stream)).ptr;
     if (ws == nullptr)
         return CF_OK;
     unsigned word = 0;
@@ -1582,9 +1601,9 @@ cf_status commfuse_device_status(void *hip_stream)
 void commfuse_destroy_cache(void)
 {
     std::lock_guard<std::mutex> lk(g_mu);
-    for (GraphEntry &g : g_graphs) {
-        (void)hipGraphExecDestroy(g.exec);
-        (void)hipGraphDestroy(g.graph);
+    for (auto &kv : g_graphs) {
+        (void)hipGraphExecDestroy(kv.second.exec);
+        (void)hipGraphDestroy(kv.second.graph);
     }
     g_graphs.clear();
     for (auto &kv : g_events)

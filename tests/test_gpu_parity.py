@@ -154,6 +154,46 @@ def test_split_k_reduced(layout, tile, splitk):
     assert H.rel_err(got_ag, refa) <= TIGHT_BF16_OUT
 
 
+def test_two_layers_in_flight_split_k_with_a_workspace_per_stream():
+    """A workspace registered for a stream serves the work enqueued on that stream: two rank steps that run side by
+    side on two streams, both with their k ranges split, each park their partial tiles in a workspace of their own."""
+    p, mc, n, k = 4, 264, 520, 2112          # 33 k-tiles
+    runs, refs, wss = [], [], []
+    for salt in (31, 32):
+        w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=p, m_chunk=mc, n=n, k=k)
+        data = inputs.make_rs(w, salt=salt)
+        refs.append(_oracle_rs(w, data, 2))
+        run = H.RsRun(w, data, 2, with_sink=True)
+        ws = torch.full((cf.workspace_bytes(run.desc, cf.CF_KIND_RS),), 0xFF, dtype=torch.uint8, device=H.DEV)
+        torch.cuda.synchronize()                            # the fill first: the registration zeroes the counters on run.cs
+        cf.set_workspace(ws, stream=run.cs)                 # for the work enqueued on this run's compute stream
+        runs.append(run)
+        wss.append(ws)
+    torch.cuda.synchronize()
+    os.environ["COMMFUSE_TILE"] = "128x128"
+    os.environ["COMMFUSE_SPLITK"] = "3"
+    try:
+        for rep in range(3):                                 # enqueue both, then wait: the two rank steps overlap in time
+            for run in runs:
+                cf.run_schedule(run.desc, cf.CF_KIND_RS, run.bufs, run.cs, run.xs, 0)
+        torch.cuda.synchronize()
+        for run in runs:
+            cf.device_status(run.cs)
+    finally:
+        os.environ.pop("COMMFUSE_TILE", None)
+        os.environ.pop("COMMFUSE_SPLITK", None)
+        torch.cuda.synchronize()
+        for run in runs:
+            cf.set_workspace(None, stream=run.cs)
+    for run, ref, ws in zip(runs, refs, wss):
+        for i in range(p):
+            got = H.to_host_f64(run.sink[i] if i < p - 1 else run.O)
+            e = H.rel_err(got, ref[i])
+            assert e <= TIGHT_BF16, f"step {i}: {e:.3e}"
+        # the partial tiles were parked in this run's own workspace (it was all 0xFF bytes before)
+        assert not bool((ws[64 * 1024:64 * 1024 + 4096] == 0xFF).all())
+
+
 AG_SHAPES = [(3, 200, 264, 168), (2, 128, 128, 4096), (4, 72, 136, 1376), (1, 33, 16, 24), (8, 260, 520, 72)]
 
 
