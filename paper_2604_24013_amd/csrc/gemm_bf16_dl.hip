@@ -984,7 +984,14 @@ hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t
     bool any_recv = p.recv != nullptr;
     for (int j = 0; j < p.n_steps; ++j)
         any_recv = any_recv || p.recv_step[j] != nullptr;
-    [[maybe_unused]] const bool rlds = SPREAD && NS == 2 && any_recv && !out_bf16 && !p.a_t && p.stream_recv;
+    // (only where the kernel would stream: a long enough k range, one received partial per step, no delivery flag, no
+    // k-split -- otherwise the variant with three left-operand stages is the faster one)
+    bool any_flag = p.wait_flag != nullptr;
+    for (int j = 0; j < p.n_steps; ++j)
+        any_flag = any_flag || p.flag_step[j] != nullptr;
+    const int nk_all = (p.K + BK - 1) / BK;
+    [[maybe_unused]] const bool rlds = SPREAD && NS == 2 && any_recv && !out_bf16 && !p.a_t && p.stream_recv && !any_flag &&
+                                       p.n_recv_more == 0 && p.splits == 1 && nk_all >= 17 + (p.K % BK != 0 ? 2 : 0);
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     int wgs = tiles_m * tiles_n * p.splits + p.cp_wgs;
     if (p.n_steps > 0) {                             // persistent: a grid that fills the chip once
