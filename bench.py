@@ -29,7 +29,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 SETTLE_S = 0.06               # untimed load before every timed region (see time_calls)
 # HBM-side bytes per launch of the dominant kernel from rocprofv3 counters (FETCH_SIZE x 2.00 + WRITE_SIZE): a constant
 # taken from TRAFFIC_SOURCE, not measured in this run -- to be re-derived there whenever that kernel changes
-TRAFFIC_DOWN_RANK_STEP = 1300.8e6
+TRAFFIC_DOWN_RANK_STEP = 1332.8e6
 TRAFFIC_SOURCE = "profiles/gemm_bf16_dl_kernel_70b_pair_counters.md"
 
 

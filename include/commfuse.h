@@ -447,7 +447,8 @@ const char *commfuse_last_error(void);
  *     keeps the buffer alive and unmodified while registered.  Steps that
  *     overlap in time on the GPU must not share a workspace.
  *     commfuse_device_status(stream) reads the status word of the workspace that
- *     serves `stream`.
+ *     serves `stream`.  Clear a stream's registration before destroying the stream
+ *     (a later stream may get the same handle).
  */
 size_t commfuse_workspace_bytes(const cf_layer_desc *desc, int kind);
 cf_status commfuse_set_workspace(void *device_ptr, size_t bytes, void *hip_stream);
