@@ -107,11 +107,13 @@ def main() -> int:
             best = None
             pers_pair = kind == cf.CF_KIND_RS_PAIR and getattr(run, "each", None) is not None
             for mode, extra in MODES if (kind in (cf.CF_KIND_RS, cf.CF_KIND_AG) and (fl == 0 or "persistent" in mode or mode in BASIC_NAMES)) \
-                    else (BASIC + tuple(m for m in MODES if "persistent" in m[0]) if pers_pair else BASIC):
+                    else (BASIC + tuple(m for m in MODES if "persistent" in m[0] and "carried" not in m[0]) if pers_pair else BASIC):
                 if fl != 0 and (extra & (cf.CF_FUSED_COPY | cf.CF_DEVICE_WAIT)):
                     continue
                 if (extra & cf.CF_PERSISTENT) and getattr(run, "each", None) is None:
                     continue                              # needs a landing buffer per hop
+                if "carried" in mode and kind != cf.CF_KIND_RS:
+                    continue                              # only the reduce-scatter launch can carry its deliveries
                 t = time_calls(lambda: cf.run_schedule(run.desc, kind, run.bufs, run.cs, run.xs, fl | extra),
                                run.cs, steps, warmup)
                 out["by_mode"].setdefault(mode, {})[name] = t
@@ -120,6 +122,8 @@ def main() -> int:
             out[name] = best
         return out
 
+    # "persistent+carried": the persistent mode, and where the launch is a single round (the 7B reduce-scatter) the
+    # kernel's own waves read B_in from the neighbour's buffer under the main loop and store it to the landing buffer
     # how the emulated deliveries are enqueued: hipMemcpyAsync on the copy stream ordered by events
     # (eager or as a captured graph), or carried by extra workgroups of the step kernels (one stream)
     # or not overlapped at all (one stream, each delivery after the kernel before it: the copies then run
@@ -129,7 +133,9 @@ def main() -> int:
              ("fused-copy+graph", cf.CF_FUSED_COPY | cf.CF_GRAPH), ("device-wait", cf.CF_DEVICE_WAIT),
              ("serial", cf.CF_SERIAL), ("serial+graph", cf.CF_SERIAL | cf.CF_GRAPH),
              ("persistent", cf.CF_PERSISTENT | cf.CF_SERIAL),
-             ("persistent+graph", cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_GRAPH))
+             ("persistent+graph", cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_GRAPH),
+             # the one-launch reduce-scatter carries its deliveries itself where that pays (single-round launches)
+             ("persistent+carried", cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY))
 
     BASIC_NAMES = ("streams", "graph", "serial", "serial+graph")
     BASIC = tuple(m for m in MODES if m[0] in BASIC_NAMES)   # work for every kind and flag
@@ -149,15 +155,15 @@ def main() -> int:
         """Overlap figures of the mode whose step time is reported (its own compute-only / copy-only times;
         the fused-copy and device-wait modes have no such variants and take the stream mode's)."""
         m = t["by_mode"].get(t["overlapped"][1], {})
-        ref = t["by_mode"].get("streams", {})
+        ref = t["by_mode"].get("persistent" if "persistent" in t["overlapped"][1] else "streams", {})
         comp = m.get("compute_only", ref.get("compute_only", t["compute_only"][0]))
         cpy = m.get("copy_only", ref.get("copy_only", t["copy_only"][0]))
         return overlap_of(t["overlapped"][0], comp, cpy)
 
     def overlap_by_mode(t):
         out = {}
-        ref = t["by_mode"].get("streams", {})
         for mode, v in t["by_mode"].items():
+            ref = t["by_mode"].get("persistent" if "persistent" in mode else "streams", {})
             if "overlapped" in v:
                 comp = v.get("compute_only", ref.get("compute_only"))
                 cpy = v.get("copy_only", ref.get("copy_only"))
@@ -448,7 +454,7 @@ def main() -> int:
         pers.each = [torch.empty((c,), dtype=torch.float32, device=H.DEV) for _ in range(w5.p - 1)]
         pers.bufs = cf.make_buffers(None, None, run.bucket, run.stage, run.slot, (None, None), None, pers.each)
         for name, fl in (("overlapped", 0), ("copy_only", cf.CF_NO_COMPUTE)):
-            for mode, extra in (m_ for m_ in MODES if "persistent" in m_[0]):
+            for mode, extra in (m_ for m_ in MODES if "persistent" in m_[0] and "carried" not in m_[0]):
                 tp = time_calls(lambda: cf.run_schedule(pers.desc, cf.CF_KIND_DP, pers.bufs, pers.cs, pers.xs, fl | extra),
                                 pers.cs, 10, 2)
                 t["by_mode"].setdefault(mode, {})[name] = tp
@@ -456,7 +462,7 @@ def main() -> int:
                     t[name] = (tp, mode)
         # pairwise schedule on the same bucket: seven arrivals for the own slice, summed in one pass (36 B per element)
         t_pw = min(time_calls(lambda: cf.run_schedule(pers.desc, cf.CF_KIND_DP_PAIR, pers.bufs, pers.cs, pers.xs, extra),
-                              pers.cs, 10, 2) for mode, extra in MODES if "persistent" in mode)
+                              pers.cs, 10, 2) for mode, extra in MODES if "persistent" in mode and "carried" not in mode)
         t_pw_c = time_calls(lambda: cf.run_schedule(pers.desc, cf.CF_KIND_DP_PAIR, pers.bufs, pers.cs, pers.xs,
                                                     cf.CF_PERSISTENT | cf.CF_NO_COPY), pers.cs, 10, 2)
         steps_with_add = w5.p - 1
@@ -509,8 +515,8 @@ def main() -> int:
         return 0
     # overlap figures: every mode against ITS OWN compute-only and copy-only times (the fused-copy and
     # device-wait modes have no such variants and take the stream mode's)
-    ref = pair_by_mode.get("streams", {})
     for mode, v in pair_by_mode.items():
+        ref = pair_by_mode.get("persistent" if "persistent" in mode else "streams", {})
         comp, cpy = v.get("compute_only", ref.get("compute_only")), v.get("copy_only", ref.get("copy_only"))
         if "overlapped" in v and comp and cpy:
             pair_overlap[mode] = dict(us_per_step=round(v["overlapped"] * 1e3, 1), **overlap_of(v["overlapped"], comp, cpy))

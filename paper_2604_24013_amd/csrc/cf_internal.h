@@ -52,6 +52,11 @@ struct GemmParams {
     const float *recv_step[MAX_STEPS] = {};
     void *out_step[MAX_STEPS] = {};
     const unsigned *flag_step[MAX_STEPS] = {};
+    // the delivery carried by the consumer (persistent reduce-scatter launch, 256x256 tile with B_in through LDS):
+    // recv_step[s] then points at what the neighbour sends (its buffer, not this rank's landing buffer), and the
+    // waves that add B_in also store it to land_step[s], the landing buffer -- the emulated transfer happens
+    // inside the kernel, under its main loop.  Null = B_in is already where recv_step[s] points.
+    float *land_step[MAX_STEPS] = {};
     const void *cp_src = nullptr;
     void *cp_dst = nullptr;
     size_t cp_bytes = 0;
@@ -96,6 +101,8 @@ struct Tuning {
     int k_rotate = -1;              // COMMFUSE_K_ROTATE = 0 | 1                           (-1 = unset)
     int stream_recv = -1;           // COMMFUSE_STREAM_RECV = 0 | 1                        (-1 = unset)
     int persist_wgs = 0;            // COMMFUSE_PERSIST_WGS = cap on the persistent kernel's grid (0 = unset)
+    int carry = -1;                 // COMMFUSE_CARRY = 0 | 1: never / wherever possible let the one-launch
+                                    // reduce-scatter carry its deliveries under CF_FUSED_COPY (-1 = unset: by shape)
     int tile_f32_bm = 0;            // COMMFUSE_TILE_F32 = "128x128" | "64x64"             (0 = unset)
     unsigned spin_limit = 0;        // COMMFUSE_SPIN_LIMIT                                 (0 = unset)
     int attn_qt = -1;               // COMMFUSE_ATTN_QT = 0 | 1 | 2                        (-1 = unset)
@@ -117,9 +124,13 @@ TileChoice choose_tile_bf16(int M, int N, int K, int num_cu);
 hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, int num_cu);
 // True if launch_gemm_bf16 would run the kernel that honours GemmParams::recv_more for these operands.
 bool gemm_bf16_takes_recv_list(const GemmParams &p, bool w_kn);
+// True if launch_gemm_bf16 would run this persistent reduce-scatter launch on the kernel that honours
+// GemmParams::land_step (the delivery carried by the consumer) -- for every step that receives.
+bool gemm_bf16_carries_delivery(const GemmParams &p, bool w_kn, bool out_bf16, int num_cu);
 // Direct-to-LDS variant of the bf16 kernel (operand extents below 2^31 bytes).
 bool gemm_bf16_dl_supported(const GemmParams &p, bool w_kn);
 hipError_t launch_gemm_bf16_dl(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, TileChoice t);
+bool gemm_bf16_dl_streams_recv(const GemmParams &p, bool w_kn, bool out_bf16, TileChoice t);
 hipError_t launch_gemm_f32(const GemmParams &p, bool w_kn, hipStream_t s, int num_cu);
 
 bool attn_slice_supported(const AttnParams &p);

@@ -878,7 +878,21 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
     auto landing = [&](int j) -> void * {
         return static_cast<char *>(b->recv_each[j / m - 1]) + (size_t)(j % m) * slot_bytes;
     };
-    if (do_copy && slot_bytes > 0) {
+    auto stage_of = [&](int j) { return static_cast<const char *>(b->peer_stage[j / m - 1]) + (size_t)(j % m) * slot_bytes; };
+    // CF_FUSED_COPY with the one-launch reduce-scatter: the delivery is carried by the consumer.  The waves that
+    // need B_in read it from the neighbour's buffer (peer_stage) under the main loop, add it, and store it to the
+    // landing buffer; no copy is launched.  Only where the launch runs the kernel that brings B_in in through LDS
+    // (256x256 tile, a k range long enough); otherwise the deliveries are enqueued in front as without the flag.
+    bool carried = false;
+    if ((flags & CF_FUSED_COPY) && kind == CF_KIND_RS && attn == nullptr && do_copy && do_compute && slot_bytes > 0 &&
+        r.mc > 0 && r.n > 0 && r.k > 0) {
+        cf::GemmParams probe;
+        probe.W = b->W;
+        fill_shape(probe, r);
+        probe.n_steps = S;
+        carried = cf::gemm_bf16_carries_delivery(probe, r.w_kn, r.bf16_out, num_cu_of_current_device());
+    }
+    if (do_copy && slot_bytes > 0 && !carried) {
         // all deliveries of the rank step are due now: one batched copy launch where the buffers allow it
         // (at most 16 hops of 16-byte-aligned whole hop buffers), else one hipMemcpyAsync per (sub-)step
         const void *srcs[cf::GemmParams::MAX_STEPS];
@@ -976,6 +990,10 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
             if (kind == CF_KIND_RS) {
                 gp.A_step[j] = static_cast<const char *>(b->A_or_own_shard) + (size_t)c * r.mc * r.lda * in_elem(r);
                 gp.recv_step[j] = receives(j) ? static_cast<const float *>(landing(j)) : nullptr;
+                if (carried && receives(j)) {        // read from the neighbour's buffer, land it here
+                    gp.recv_step[j] = reinterpret_cast<const float *>(stage_of(j));
+                    gp.land_step[j] = static_cast<float *>(landing(j));
+                }
                 gp.out_step[j] = sends(j) ? static_cast<void *>(b->send_each[j / m] + (size_t)(j % m) * r.mc * r.ldo)
                                           : static_cast<void *>(static_cast<float *>(b->O) + (size_t)(j % m) * r.mc * r.ldo);
             } else {
@@ -1107,8 +1125,8 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
             return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY needs the bf16 chunk-GEMM kernels (kind RS or AG, bf16 operands)");
     }
     if (flags & CF_PERSISTENT) {
-        if (flags & (CF_FUSED_COPY | CF_DEVICE_WAIT))
-            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT excludes CF_FUSED_COPY and CF_DEVICE_WAIT");
+        if (flags & CF_DEVICE_WAIT)
+            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT excludes CF_DEVICE_WAIT");
         if (attn != nullptr && r.m != 1)
             return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT with the attention layer needs m = 1");
         const bool ok_kind = is_dp_kind(kind)      ? true
@@ -1274,7 +1292,7 @@ static Tuning read_tuning_from_environment()
 {
     Tuning t;
     memset(&t, 0, sizeof(t));                      // (padding too: the struct is hashed byte-wise into graph keys)
-    t.deep = t.prefetch = t.xcd_steps = t.k_rotate = t.stream_recv = t.attn_qt = -1;
+    t.deep = t.prefetch = t.xcd_steps = t.k_rotate = t.stream_recv = t.attn_qt = t.carry = -1;
     int bm = 0, bn = 0;
     if (const char *e = getenv("COMMFUSE_TILE"))
         if (sscanf(e, "%dx%d", &bm, &bn) == 2) {
@@ -1296,6 +1314,8 @@ static Tuning read_tuning_from_environment()
         t.xcd_steps = atoi(e) != 0;
     if (const char *e = getenv("COMMFUSE_K_ROTATE"))
         t.k_rotate = atoi(e) != 0;
+    if (const char *e = getenv("COMMFUSE_CARRY"))
+        t.carry = atoi(e) != 0;
     if (const char *e = getenv("COMMFUSE_PERSIST_WGS"))
         t.persist_wgs = atoi(e) > 0 ? atoi(e) : 0;
     if (const char *e = getenv("COMMFUSE_STREAM_RECV"))

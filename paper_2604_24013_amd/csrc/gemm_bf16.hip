@@ -315,10 +315,9 @@ bool gemm_bf16_takes_recv_list(const GemmParams &p, bool w_kn)
     return p.M > 0 && p.N > 0 && !staged_kernel_forced() && gemm_bf16_dl_supported(p, w_kn);
 }
 
-hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, int num_cu)
+// Tile of a launch: the per-step choice, the persistent rank step's cost model, then the overrides.
+static TileChoice tile_of_launch(const GemmParams &p, int num_cu)
 {
-    if (p.M <= 0 || p.N <= 0)
-        return hipSuccess;
     TileChoice t = choose_tile_bf16(p.M, p.N, p.K, num_cu);
     if (p.n_steps > 0) {
         // Persistent rank step: n_steps * tiles work items share one grid, so a step need not fill the chip
@@ -348,6 +347,35 @@ hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipSt
         t.deep = tn.deep != 0;
     if (tn.splitk >= 1)
         t.splitk = tn.splitk;
+    return t;
+}
+
+bool gemm_bf16_carries_delivery(const GemmParams &p, bool w_kn, bool out_bf16, int num_cu)
+{
+    if (p.M <= 0 || p.N <= 0 || p.n_steps <= 0 || staged_kernel_forced() || !gemm_bf16_dl_supported(p, w_kn))
+        return false;
+    for (int j = 0; j < p.n_steps; ++j)
+        if (p.flag_step[j] != nullptr)
+            return false;                            // a step that waits for a flag keeps its B_in loads in the epilogue
+    const TileChoice t = tile_of_launch(p, num_cu);
+    if (!gemm_bf16_dl_streams_recv(p, w_kn, out_bf16, t))
+        return false;
+    // Where it pays (measured): a launch of ONE round -- nothing else can hide its deliveries, and the memory system
+    // idles under its short main loop (7B down-projection: 81 -> 65 us per rank step).  In a launch of several
+    // rounds at the 70B shape the acknowledgements of the landing stores stall the two-stage operand pipeline
+    // (vmcnt counts loads and stores in one order): 528 us against 510 us with the deliveries copied in front.
+    const Tuning tn = tuning();
+    if (tn.carry >= 0)
+        return tn.carry != 0;
+    const int64_t items = (int64_t)((p.M + t.bm - 1) / t.bm) * ((p.N + t.bn - 1) / t.bn) * p.n_steps;
+    return items <= num_cu;
+}
+
+hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, int num_cu)
+{
+    if (p.M <= 0 || p.N <= 0)
+        return hipSuccess;
+    const TileChoice t = tile_of_launch(p, num_cu);
     const bool staged = staged_kernel_forced();
     if (!staged && gemm_bf16_dl_supported(p, w_kn))
         return launch_gemm_bf16_dl(p, w_kn, out_bf16, s, t);

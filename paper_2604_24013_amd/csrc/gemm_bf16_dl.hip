@@ -134,7 +134,8 @@ __device__ __forceinline__ int xcd_remap(int pid, int total)
 // [k x n] weight tile and is read with the transposing LDS read as well.
 // PERSIST: one launch runs all steps of a rank step (GemmParams::n_steps, see the work-item loop below).
 // RLDS: reduce-scatter variant of the SPREAD tile.  The received partial B_in does not wait for the epilogue: in
-// the last sixteen k-tiles before the final one it is brought in, one 32x32 sub-tile of every wave at a time,
+// sixteen k-tiles near the end of the k loop (the last before the final one; with a ragged K the two iterations that
+// request the ragged k-tile come in between) it is brought in, one 32x32 sub-tile of every wave at a time,
 // by direct loads into an LDS landing area (no register is held while the load is in flight) and added to the
 // accumulators in mid-loop, so that the epilogue only stores.  The landing area takes the place of the third
 // left-operand stage (see the schedule below).
@@ -220,6 +221,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     const int step_i = PERSIST ? (by_xcd ? (int)(blockIdx.x & 7) + 8 * (item / tiles_per_step) : item / tiles_per_step) : 0;
     const void *const cA = PERSIST ? P.A_step[step_i] : P.A;
     const float *const cRecv = PERSIST ? P.recv_step[step_i] : P.recv;
+    float *const cLand = (PERSIST && RLDS) ? P.land_step[step_i] : nullptr;   // where B_in is to land, if this kernel carries it
     void *const cOut = PERSIST ? P.out_step[step_i] : P.out;
     const unsigned *const cFlag = PERSIST ? P.flag_step[step_i] : P.wait_flag;
     // further received partials (GemmParams::recv_more): in a persistent launch they belong to the last step only
@@ -563,9 +565,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         }
     };
 
-    // RLDS: is B_in streamed in under the main loop for this work item?  (Uniform.)  It needs the sixteen k-tiles
-    // before the last one; a step that waits for a delivery flag, sums several received partials or is a k-split
-    // keeps the loads in the epilogue.
+    // RLDS: is B_in streamed in under the main loop for this work item?  (Uniform.)  It needs sixteen k-tiles
+    // before the last one (and before the iterations that test their loads); a step that waits for a delivery
+    // flag, sums several received partials or is a k-split keeps the loads in the epilogue.
     constexpr int RQ = TM * TN;                       // 32x32 sub-tiles per wave, one in flight at a time
     // A ragged k tail (the launcher then leaves the k order unrotated: it is the last k-tile) is requested in the
     // last two iterations before the final tile; those test their loads and come after the streamed ones.
@@ -586,6 +588,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         static_assert(A_LD <= NSEG && B_LD <= NSEG && NSEG == 4, "one load slot per MFMA segment");
         using cALD = std::integral_constant<int, A_LD>;
         const i32x4_t rr = make_rsrc(cRecv, cRecv != nullptr ? r_bytes_of_recv : 0u);
+        __amdgpu_buffer_rsrc_t l_rsrc =
+            __builtin_amdgcn_make_buffer_rsrc(cLand, 0, cLand != nullptr ? (int)r_bytes_of_recv : 0, 0x00020000);
         const unsigned r_lds = lds_base + R_BASE + wave * 4096;
         // byte offset of sub-tile q = (i, j) of this wave, row 0 / column 0 of the lane pattern
         auto r_soff = [&](int q) __attribute__((always_inline)) {
@@ -626,13 +630,27 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             int ln = lane;
             asm volatile("" : "+v"(ln));
             const unsigned char *src = smem + R_BASE + wave * 4096 + ln * 16;
+            f32x4_t v[4];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const f32x4_t v = *reinterpret_cast<const f32x4_t *>(src + g * 1024);
-                acc[q / TN][q % TN][4 * g + 0] += v[0];
-                acc[q / TN][q % TN][4 * g + 1] += v[1];
-                acc[q / TN][q % TN][4 * g + 2] += v[2];
-                acc[q / TN][q % TN][4 * g + 3] += v[3];
+                v[g] = *reinterpret_cast<const f32x4_t *>(src + g * 1024);
+                acc[q / TN][q % TN][4 * g + 0] += v[g][0];
+                acc[q / TN][q % TN][4 * g + 1] += v[g][1];
+                acc[q / TN][q % TN][4 * g + 2] += v[g][2];
+                acc[q / TN][q % TN][4 * g + 3] += v[g][3];
+            }
+            // the delivery carried by the consumer: what just arrived from the neighbour's buffer is also stored to
+            // this rank's landing buffer (a lane outside the matrix is given the out-of-range offset: store dropped)
+            if (cLand != nullptr) {
+                const int rm = m0 + wm * WTM + (q / TN) * 32 + (ln & 31);
+                const int rn = n0 + wn * WTN + (q % TN) * 32 + (ln >> 5) * 4;
+                const unsigned e0 = (unsigned)((int64_t)rm * P.ldo + rn);
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int boff = (rm < M && rn + 8 * g < N) ? (int)((e0 + 8 * g) * 4) : (int)OOB;
+                    // (plain stores: non-temporal or write-through ones measured 10 - 30 % slower here)
+                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, v[g]), l_rsrc, boff, 0, 0);
+                }
             }
         };
         issue_range(0, 0, 0, c0{}, cLPT{});
@@ -928,6 +946,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                     rv[j][g] = __builtin_bit_cast(f32x4_t, recv_coherent
                                    ? __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, boff, 0, COHERENT_LD)
                                    : __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, boff, 0, 0));
+                    if constexpr (PERSIST && RLDS) {
+                        if (cLand != nullptr) {      // (a work item that could not stream still delivers)
+                            __amdgpu_buffer_rsrc_t le_rsrc =
+                                __builtin_amdgcn_make_buffer_rsrc(cLand, 0, (int)r_bytes, 0x00020000);
+                            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, rv[j][g]), le_rsrc, boff, 0, 0);
+                        }
+                    }
                 }
             // further received partials, summed in index order: one batch of independent loads per buffer
             for (int b = 0; b < n_more; ++b) {
@@ -1069,6 +1094,16 @@ bool gemm_bf16_dl_supported(const GemmParams &p, bool w_kn)
     const int64_t w_bytes = ((int64_t)(w_kn ? p.K : p.N) * p.ldw) * 2;
     const int64_t o_bytes = ((int64_t)p.M * p.ldo) * 4;
     return p.M > 0 && p.N > 0 && p.K > 0 && a_bytes < lim && w_bytes < lim && o_bytes < lim;
+}
+
+// Would launch_gemm_bf16_dl take the kernel variant that streams B_in through LDS (and so can carry the delivery)
+// for this persistent launch with tile t?  Mirrors the choice in launch_cfg.
+bool gemm_bf16_dl_streams_recv(const GemmParams &p, bool w_kn, bool out_bf16, TileChoice t)
+{
+    (void)w_kn;
+    const int nk_all = (p.K + BK - 1) / BK;
+    return p.n_steps > 0 && t.bm == 256 && t.bn == 256 && !out_bf16 && !p.a_t && tuning().stream_recv != 0 &&
+           p.n_recv_more == 0 && nk_all >= 17 + (p.K % BK != 0 ? 2 : 0);
 }
 
 hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16, hipStream_t s, TileChoice t)

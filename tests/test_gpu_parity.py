@@ -283,10 +283,15 @@ def test_b_in_added_in_mid_sum_is_bit_exact_on_integers(layout, stream):
             outs = run.run_steps()
             for i in range(p):
                 assert np.array_equal(outs[i], ref[i]), f"rank {rank} step {i}"
-            run.run_schedule(cf.CF_PERSISTENT | cf.CF_SERIAL)
-            for i in range(p):
-                got = H.to_host_f64(run.send_each[i] if i < p - 1 else run.O)
-                assert np.array_equal(got, ref[i]), f"rank {rank} step {i} (one launch)"
+            for fl in (cf.CF_PERSISTENT | cf.CF_SERIAL, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY):
+                for t in run.each + run.send_each + [run.O]:
+                    t.fill_(float("nan"))
+                run.run_schedule(fl)
+                for i in range(p):
+                    got = H.to_host_f64(run.send_each[i] if i < p - 1 else run.O)
+                    assert np.array_equal(got, ref[i]), f"rank {rank} step {i} (one launch, flags {fl})"
+                for i in range(p - 1):               # delivered by the batched copy or by the kernel itself
+                    assert torch.equal(run.each[i], run.stage[i]), f"rank {rank} hop {i + 1} (flags {fl})"
     finally:
         os.environ.pop("COMMFUSE_TILE", None)
         os.environ.pop("COMMFUSE_STREAM_RECV", None)
@@ -518,8 +523,11 @@ def test_persistent_rank_step(m, tile, k):
     refa = _oracle_ag(wa, da, rank)
     _tile_env(tile)
     try:
+        # (with CF_FUSED_COPY the reduce-scatter launch carries its deliveries itself where it brings B_in in through
+        # LDS -- the 256x256 tile with the longer k ranges -- and has them copied in front otherwise: same results)
         for flags in (cf.CF_PERSISTENT | cf.CF_SERIAL, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_GRAPH,
-                      cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_POISON):
+                      cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_POISON, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY,
+                      cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY | cf.CF_GRAPH):
             for layout in (cf.CF_W_KN, cf.CF_W_NK):
                 run = H.RsRun(w, data, rank, layout, m=m, each=True)
                 run.O.fill_(float("nan"))
@@ -535,6 +543,8 @@ def test_persistent_rank_step(m, tile, k):
                 for i in range(w.p - 1):                   # every step's B_out (Alg. 2 "B_out <- O"), hop by hop
                     e = H.rel_err(H.to_host_f64(run.send_each[i]), ref[i])
                     assert e <= TIGHT_BF16, f"flags {flags} layout {layout} B_out of step {i}: {e:.3e}"
+                    # and every delivery arrived: the landing buffer holds what the neighbour sent, bit for bit
+                    assert torch.equal(run.each[i], run.stage[i]), f"flags {flags} layout {layout} delivery of hop {i + 1}"
                 ag = H.AgRun(wa, da, rank, layout, m=m, each=True)
                 with H.Workspace(ag.desc, cf.CF_KIND_AG):
                     ag.run_schedule(flags)
@@ -667,7 +677,7 @@ def test_persistent_needs_what_it_needs():
     PS = cf.CF_PERSISTENT | cf.CF_SERIAL
     for kw, flags, status in (({}, PS, cf.CF_ERR_INVALID_ARG),                                     # no recv_each
                               ({"each": True}, cf.CF_PERSISTENT, cf.CF_ERR_UNSUPPORTED),           # overlapped copies
-                              ({"each": True}, PS | cf.CF_FUSED_COPY, cf.CF_ERR_UNSUPPORTED)):
+                              ({"each": True}, PS | cf.CF_DEVICE_WAIT, cf.CF_ERR_UNSUPPORTED)):
         run = H.RsRun(w, data, 0, **kw)
         with pytest.raises(cf.CommFuseError) as ei:
             run.run_schedule(flags)
@@ -763,7 +773,7 @@ def _full_ref(name, rank):
 
 
 @pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_GRAPH, cf.CF_DEVICE_WAIT, PERSISTENT_SERIAL,
-                                   PERSISTENT_SERIAL | cf.CF_GRAPH])
+                                   PERSISTENT_SERIAL | cf.CF_GRAPH, PERSISTENT_SERIAL | cf.CF_FUSED_COPY])
 @pytest.mark.parametrize("name", ["c2_rs_7b", "c4_rs_70b_down"])
 def test_full_size_rs(name, flags):
     w = inputs.CONFIGS[name]
@@ -771,11 +781,20 @@ def test_full_size_rs(name, flags):
     data, ref = _full_ref(name, rank)
     persistent = bool(flags & cf.CF_PERSISTENT)      # every step's B_out stays in a buffer of its own there
     run = H.RsRun(w, data, rank, each=True) if persistent else H.RsRun(w, data, rank, with_sink=True)
-    for t in (run.send_each if persistent else run.sink) + [run.O]:
+    for t in (run.send_each + run.each if persistent else run.sink) + [run.O]:
         t.fill_(float("nan"))
-    with H.Workspace(run.desc, cf.CF_KIND_RS):          # as the benchmark runs it
-        run.run_schedule(flags)
-        cf.device_status(run.cs)
+    carried = persistent and bool(flags & cf.CF_FUSED_COPY)
+    if carried:                                      # the kernel carries its deliveries at both shapes (by default
+        os.environ["COMMFUSE_CARRY"] = "1"           # only where the launch is a single round: the 7B shape)
+    try:
+        with H.Workspace(run.desc, cf.CF_KIND_RS):      # as the benchmark runs it
+            run.run_schedule(flags)
+            cf.device_status(run.cs)
+    finally:
+        os.environ.pop("COMMFUSE_CARRY", None)
+    if persistent:                                   # every delivery landed (copied in front, or carried by the kernel)
+        for i in range(w.p - 1):
+            assert torch.equal(run.each[i], run.stage[i]), f"delivery of hop {i + 1}"
     for i in range(w.p):
         got = H.to_host_f64((run.send_each if persistent else run.sink)[i] if i < w.p - 1 else run.O)
         assert not np.isnan(got).any(), f"step {i}"
@@ -804,7 +823,7 @@ def test_full_size_ag(name, flags):
         assert e <= gate and e <= tight, f"step {i}: {e:.3e}"
 
 
-@pytest.mark.parametrize("flags", [0, PERSISTENT_SERIAL])
+@pytest.mark.parametrize("flags", [0, PERSISTENT_SERIAL, PERSISTENT_SERIAL | cf.CF_FUSED_COPY])
 def test_full_size_pair_70b(flags):
     """AG-GEMM (up) writes H in bf16; GEMM-RS (down) consumes it.  No activation between.  Set up as the
     benchmark sets it up (a landing buffer per hop, a B_out buffer per step, one compute stream for both
