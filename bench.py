@@ -112,8 +112,6 @@ def main() -> int:
                     continue
                 if (extra & cf.CF_PERSISTENT) and getattr(run, "each", None) is None:
                     continue                              # needs a landing buffer per hop
-                if "carried" in mode and kind != cf.CF_KIND_RS:
-                    continue                              # only the reduce-scatter launch can carry its deliveries
                 t = time_calls(lambda: cf.run_schedule(run.desc, kind, run.bufs, run.cs, run.xs, fl | extra),
                                run.cs, steps, warmup)
                 out["by_mode"].setdefault(mode, {})[name] = t
@@ -122,19 +120,18 @@ def main() -> int:
             out[name] = best
         return out
 
-    # "persistent+carried": the persistent mode, and where the launch is a single round (the 7B reduce-scatter) the
-    # kernel's own waves read B_in from the neighbour's buffer under the main loop and store it to the landing buffer
     # how the emulated deliveries are enqueued: hipMemcpyAsync on the copy stream ordered by events
     # (eager or as a captured graph), or carried by extra workgroups of the step kernels (one stream)
     # or not overlapped at all (one stream, each delivery after the kernel before it: the copies then run
     # at full speed and disturb no GEMM -- a reference point for what the overlap buys); "persistent": all
-    # steps of a rank step in one kernel launch, the deliveries enqueued before it
+    # steps of a rank step in one kernel launch, the deliveries enqueued before it; "persistent+carried": no copy is
+    # enqueued, the kernel's own waves read B_in from the neighbour's buffer under the main loop and store it to the
+    # landing buffer
     MODES = (("streams", 0), ("graph", cf.CF_GRAPH), ("fused-copy", cf.CF_FUSED_COPY),
              ("fused-copy+graph", cf.CF_FUSED_COPY | cf.CF_GRAPH), ("device-wait", cf.CF_DEVICE_WAIT),
              ("serial", cf.CF_SERIAL), ("serial+graph", cf.CF_SERIAL | cf.CF_GRAPH),
              ("persistent", cf.CF_PERSISTENT | cf.CF_SERIAL),
              ("persistent+graph", cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_GRAPH),
-             # the one-launch reduce-scatter carries its deliveries itself where that pays (single-round launches)
              ("persistent+carried", cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY))
 
     BASIC_NAMES = ("streams", "graph", "serial", "serial+graph")

@@ -327,14 +327,18 @@ enum {
                             Bucket kinds (CF_KIND_DP, CF_KIND_DP_PAIR; fp32): there is no GEMM to fuse
                             into; the flag buys the deliveries of all hops as ONE batched copy launch
                             into recv_each, followed by the same add kernels in the same order.
-                            With CF_FUSED_COPY (CF_KIND_RS): the delivery is carried by the consumer -- no copy
-                            is launched; the waves that need B_in read it from the neighbour's buffer
-                            (peer_stage) under their main loop, add it in mid-sum, and store it to the
-                            landing buffer (recv_each), so the emulated transfer runs inside the kernel,
-                            hidden under its compute (a row block lands without its padding).  Where the
-                            launch cannot do that (a tile other than 256x256, a k range under 17 k-tiles
-                            of 64, or 19 with a ragged last one; the other kinds) the flag changes nothing:
-                            the deliveries are enqueued in front.  Not with CF_DEVICE_WAIT.          */
+                            With CF_FUSED_COPY (CF_KIND_RS, CF_KIND_AG): the delivery is carried by the
+                            consumer -- no copy is launched, the emulated transfer runs inside the kernel,
+                            under its main loop.  Reduce-scatter: the waves that need B_in read it from the
+                            neighbour's buffer (peer_stage), add it in mid-sum, and store it to the landing
+                            buffer (recv_each).  All-gather: the kernel takes the gathered slices from the
+                            neighbours' buffers as its left operand, and every k-tile that comes in is
+                            stored on to the landing buffer by one of the workgroups that load it.  (A row
+                            block lands without the padding of its rows.)  Where the launch cannot do that
+                            (reduce-scatter: a tile other than 256x256, a k range under 17 k-tiles of 64,
+                            or 19 with a ragged last one; all-gather: k not a multiple of 64; the other
+                            kinds) the flag changes nothing: the deliveries are enqueued in front.
+                            Not with CF_DEVICE_WAIT.                                                  */
     CF_DEVICE_WAIT = 64u /* bf16 RS / AG only, needs a registered workspace: the compute
                             stream does not wait for the copy stream between steps;
                             each delivery is followed by a flag write and the step

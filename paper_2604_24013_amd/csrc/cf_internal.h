@@ -12,9 +12,9 @@ namespace cf {
 // contraction over tokens: both operands then have the contraction index as their row index).
 struct GemmParams {
     bool a_t = false;    // direct-to-LDS bf16 kernel, w_kn, fp32 output only
-    const void *A;
-    const void *W;
-    const float *recv;   // nullable: B_in of Alg. 2
+    const void *A = nullptr;
+    const void *W = nullptr;
+    const float *recv = nullptr;   // nullable: B_in of Alg. 2
     // further received partials, added after `recv` in index order before the product is added
     // (pairwise schedule with the aggregation deferred to the last step; direct-to-LDS bf16 kernel only)
     static constexpr int MAX_RECV_MORE = 15;
@@ -22,9 +22,9 @@ struct GemmParams {
     int n_recv_more = 0;
     int pf_lead = 16;    // B_in prefetch: k-tiles before the end of the k loop at which it is issued (0 = off)
     bool stream_recv = true;   // 256x256 tile: B_in lands in LDS under the main loop and is added in mid-sum (set by the launcher)
-    void *out;
-    int64_t lda, ldw, ldo;
-    int M, N, K;
+    void *out = nullptr;
+    int64_t lda = 0, ldw = 0, ldo = 0;
+    int M = 0, N = 0, K = 0;
     // split-K workspace (direct-to-LDS bf16 kernel only): partial tiles and per-tile arrival counters
     float *ws = nullptr;
     unsigned *counters = nullptr;
@@ -52,11 +52,13 @@ struct GemmParams {
     const float *recv_step[MAX_STEPS] = {};
     void *out_step[MAX_STEPS] = {};
     const unsigned *flag_step[MAX_STEPS] = {};
-    // the delivery carried by the consumer (persistent reduce-scatter launch, 256x256 tile with B_in through LDS):
-    // recv_step[s] then points at what the neighbour sends (its buffer, not this rank's landing buffer), and the
-    // waves that add B_in also store it to land_step[s], the landing buffer -- the emulated transfer happens
-    // inside the kernel, under its main loop.  Null = B_in is already where recv_step[s] points.
-    float *land_step[MAX_STEPS] = {};
+    // the delivery carried by the consumer (persistent launch).  Reduce-scatter (256x256 tile with B_in through LDS):
+    // recv_step[s] points at what the neighbour sends (its buffer, not this rank's landing buffer), and the
+    // waves that add B_in also store it to land_step[s], the landing buffer.  All-gather: A_step[s] points at the
+    // neighbour's buffer, and every k-tile of the slice that comes in through LDS is stored on to land_step[s]
+    // (same layout as A_step[s]) by one of the workgroups that load it.  Either way the emulated transfer happens
+    // inside the kernel, under its main loop.  Null = the operand is already where recv_step[s] / A_step[s] points.
+    void *land_step[MAX_STEPS] = {};
     const void *cp_src = nullptr;
     void *cp_dst = nullptr;
     size_t cp_bytes = 0;
@@ -101,8 +103,8 @@ struct Tuning {
     int k_rotate = -1;              // COMMFUSE_K_ROTATE = 0 | 1                           (-1 = unset)
     int stream_recv = -1;           // COMMFUSE_STREAM_RECV = 0 | 1                        (-1 = unset)
     int persist_wgs = 0;            // COMMFUSE_PERSIST_WGS = cap on the persistent kernel's grid (0 = unset)
-    int carry = -1;                 // COMMFUSE_CARRY = 0 | 1: never / wherever possible let the one-launch
-                                    // reduce-scatter carry its deliveries under CF_FUSED_COPY (-1 = unset: by shape)
+    int carry = -1;                 // COMMFUSE_CARRY = 0: the one-launch reduce-scatter never carries its deliveries
+                                    // under CF_FUSED_COPY (-1 = unset, 1: wherever the launch streams B_in)
     int tile_f32_bm = 0;            // COMMFUSE_TILE_F32 = "128x128" | "64x64"             (0 = unset)
     unsigned spin_limit = 0;        // COMMFUSE_SPIN_LIMIT                                 (0 = unset)
     int attn_qt = -1;               // COMMFUSE_ATTN_QT = 0 | 1 | 2                        (-1 = unset)
@@ -124,13 +126,15 @@ TileChoice choose_tile_bf16(int M, int N, int K, int num_cu);
 hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, int num_cu);
 // True if launch_gemm_bf16 would run the kernel that honours GemmParams::recv_more for these operands.
 bool gemm_bf16_takes_recv_list(const GemmParams &p, bool w_kn);
-// True if launch_gemm_bf16 would run this persistent reduce-scatter launch on the kernel that honours
-// GemmParams::land_step (the delivery carried by the consumer) -- for every step that receives.
-bool gemm_bf16_carries_delivery(const GemmParams &p, bool w_kn, bool out_bf16, int num_cu);
+// True if launch_gemm_bf16 would run this persistent launch (reduce_scatter: its steps add a received partial;
+// else an all-gather's) on a kernel that honours GemmParams::land_step (the delivery carried by the consumer)
+// for every step that receives.
+bool gemm_bf16_carries_delivery(const GemmParams &p, bool w_kn, bool out_bf16, int num_cu, bool reduce_scatter);
 // Direct-to-LDS variant of the bf16 kernel (operand extents below 2^31 bytes).
 bool gemm_bf16_dl_supported(const GemmParams &p, bool w_kn);
 hipError_t launch_gemm_bf16_dl(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, TileChoice t);
 bool gemm_bf16_dl_streams_recv(const GemmParams &p, bool w_kn, bool out_bf16, TileChoice t);
+bool gemm_bf16_dl_carries_operand(const GemmParams &p);
 hipError_t launch_gemm_f32(const GemmParams &p, bool w_kn, hipStream_t s, int num_cu);
 
 bool attn_slice_supported(const AttnParams &p);

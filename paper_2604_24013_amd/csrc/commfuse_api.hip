@@ -879,18 +879,21 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
         return static_cast<char *>(b->recv_each[j / m - 1]) + (size_t)(j % m) * slot_bytes;
     };
     auto stage_of = [&](int j) { return static_cast<const char *>(b->peer_stage[j / m - 1]) + (size_t)(j % m) * slot_bytes; };
-    // CF_FUSED_COPY with the one-launch reduce-scatter: the delivery is carried by the consumer.  The waves that
-    // need B_in read it from the neighbour's buffer (peer_stage) under the main loop, add it, and store it to the
-    // landing buffer; no copy is launched.  Only where the launch runs the kernel that brings B_in in through LDS
-    // (256x256 tile, a k range long enough); otherwise the deliveries are enqueued in front as without the flag.
+    // CF_FUSED_COPY with the one-launch reduce-scatter or all-gather: the delivery is carried by the consumer, no
+    // copy is launched.  Reduce-scatter: the waves that need B_in read it from the neighbour's buffer (peer_stage)
+    // under the main loop, add it, and store it to the landing buffer; only where the launch runs the kernel that
+    // brings B_in in through LDS (256x256 tile, a k range long enough).  All-gather: the kernel takes its left
+    // operand from the neighbour's buffer, and each k-tile that comes in through LDS is stored on to the landing
+    // buffer by one of the workgroups that load it (k a multiple of the k-tile).  Otherwise the deliveries are
+    // enqueued in front as without the flag.
     bool carried = false;
-    if ((flags & CF_FUSED_COPY) && kind == CF_KIND_RS && attn == nullptr && do_copy && do_compute && slot_bytes > 0 &&
-        r.mc > 0 && r.n > 0 && r.k > 0) {
+    if ((flags & CF_FUSED_COPY) && (kind == CF_KIND_RS || kind == CF_KIND_AG) && attn == nullptr && do_copy && do_compute &&
+        slot_bytes > 0 && r.mc > 0 && r.n > 0 && r.k > 0) {
         cf::GemmParams probe;
         probe.W = b->W;
         fill_shape(probe, r);
         probe.n_steps = S;
-        carried = cf::gemm_bf16_carries_delivery(probe, r.w_kn, r.bf16_out, num_cu_of_current_device());
+        carried = cf::gemm_bf16_carries_delivery(probe, r.w_kn, r.bf16_out, num_cu_of_current_device(), kind == CF_KIND_RS);
     }
     if (do_copy && slot_bytes > 0 && !carried) {
         // all deliveries of the rank step are due now: one batched copy launch where the buffers allow it
@@ -992,13 +995,17 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
                 gp.recv_step[j] = receives(j) ? static_cast<const float *>(landing(j)) : nullptr;
                 if (carried && receives(j)) {        // read from the neighbour's buffer, land it here
                     gp.recv_step[j] = reinterpret_cast<const float *>(stage_of(j));
-                    gp.land_step[j] = static_cast<float *>(landing(j));
+                    gp.land_step[j] = landing(j);
                 }
                 gp.out_step[j] = sends(j) ? static_cast<void *>(b->send_each[j / m] + (size_t)(j % m) * r.mc * r.ldo)
                                           : static_cast<void *>(static_cast<float *>(b->O) + (size_t)(j % m) * r.mc * r.ldo);
             } else {
                 gp.A_step[j] = receives(j) ? landing(j)
                                            : static_cast<const char *>(b->A_or_own_shard) + (size_t)(j % m) * slot_bytes;
+                if (carried && receives(j)) {        // the slice is read from the neighbour's buffer and landed here
+                    gp.A_step[j] = stage_of(j);
+                    gp.land_step[j] = landing(j);
+                }
                 gp.recv_step[j] = nullptr;
                 gp.out_step[j] = static_cast<char *>(b->O) + (size_t)c * r.mc * r.ldo * (r.bf16_out ? 2 : 4);
             }

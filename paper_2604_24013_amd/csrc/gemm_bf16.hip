@@ -350,25 +350,25 @@ static TileChoice tile_of_launch(const GemmParams &p, int num_cu)
     return t;
 }
 
-bool gemm_bf16_carries_delivery(const GemmParams &p, bool w_kn, bool out_bf16, int num_cu)
+bool gemm_bf16_carries_delivery(const GemmParams &p, bool w_kn, bool out_bf16, int num_cu, bool reduce_scatter)
 {
     if (p.M <= 0 || p.N <= 0 || p.n_steps <= 0 || staged_kernel_forced() || !gemm_bf16_dl_supported(p, w_kn))
         return false;
     for (int j = 0; j < p.n_steps; ++j)
         if (p.flag_step[j] != nullptr)
             return false;                            // a step that waits for a flag keeps its B_in loads in the epilogue
-    const TileChoice t = tile_of_launch(p, num_cu);
-    if (!gemm_bf16_dl_streams_recv(p, w_kn, out_bf16, t))
+    if (reduce_scatter) {
+        const TileChoice t = tile_of_launch(p, num_cu);
+        if (!gemm_bf16_dl_streams_recv(p, w_kn, out_bf16, t))
+            return false;
+    } else if (!gemm_bf16_dl_carries_operand(p)) {
         return false;
-    // Where it pays (measured): a launch of ONE round -- nothing else can hide its deliveries, and the memory system
-    // idles under its short main loop (7B down-projection: 81 -> 65 us per rank step).  In a launch of several
-    // rounds at the 70B shape the acknowledgements of the landing stores stall the two-stage operand pipeline
-    // (vmcnt counts loads and stores in one order): 528 us against 510 us with the deliveries copied in front.
+    }
+    // Wherever the launch can, it does (measured, with the landed tiles stored as whole 128-byte lines: 7B
+    // down-projection rank step 76 -> 57 us, 70B 482 -> 470 us against deliveries copied in front of the launch).
+    // COMMFUSE_CARRY=0 keeps the copies in front.
     const Tuning tn = tuning();
-    if (tn.carry >= 0)
-        return tn.carry != 0;
-    const int64_t items = (int64_t)((p.M + t.bm - 1) / t.bm) * ((p.N + t.bn - 1) / t.bn) * p.n_steps;
-    return items <= num_cu;
+    return tn.carry >= 0 ? tn.carry != 0 : true;
 }
 
 hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, int num_cu)

@@ -226,7 +226,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     const int step_i = PERSIST ? (by_xcd ? (int)(blockIdx.x & 7) + 8 * (item / tiles_per_step) : item / tiles_per_step) : 0;
     const void *const cA = PERSIST ? P.A_step[step_i] : P.A;
     const float *const cRecv = PERSIST ? P.recv_step[step_i] : P.recv;
-    float *const cLand = (PERSIST && RLDS) ? P.land_step[step_i] : nullptr;   // where B_in is to land, if this kernel carries it
+    void *const cLand = PERSIST ? P.land_step[step_i] : nullptr;   // where the delivery is to land, if this kernel carries it
     void *const cOut = PERSIST ? P.out_step[step_i] : P.out;
     const unsigned *const cFlag = PERSIST ? P.flag_step[step_i] : P.wait_flag;
     // further received partials (GemmParams::recv_more): in a persistent launch they belong to the last step only
@@ -417,6 +417,26 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             for (int e = 0; e < 16; ++e)
                 acc[i][j][e] = 0.0f;
 
+    // All-gather with the delivery carried by the consumer (GemmParams::land_step): the left operand comes in from the
+    // neighbour's buffer, and each of its k-tiles is stored on to the landing buffer by ONE of the workgroups that
+    // load it: the work item of tile column c takes the local k-tiles c, c + tiles_n, c + 2 tiles_n, ...  (All
+    // items of a step and tile row walk k in the same order: the k rotation comes with whole steps per XCD.)
+    // Every wave stores the 4 KiB it loaded itself -- it reads them back from the stage, whole 128-byte rows per
+    // eight lanes, at the global offsets it fetched them from -- so its own vmcnt wait is all the ordering needed.
+    constexpr bool CARRY_A = PERSIST && !RLDS && !A_T;
+    int carry_at = (CARRY_A && cLand != nullptr && cRecv == nullptr) ? tile / tiles_m : 0x7fffffff;
+    __amdgpu_buffer_rsrc_t la_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(cLand, 0, (CARRY_A && cLand != nullptr) ? (int)a_bytes : 0, 0x00020000);
+    auto carry_tile = [&](int kt, int stage_a) __attribute__((always_inline)) {
+        const int k0 = ktile(kt) * BK;
+#pragma unroll
+        for (int j = 0; j < A_LD; ++j) {
+            const u32x4_t t = *reinterpret_cast<const u32x4_t *>(smem + stage_a * A_BYTES + (j * NW + wave) * 1024 + lane * 16);
+            __builtin_amdgcn_raw_buffer_store_b128(t, la_rsrc, (int)a_off[j], k0 * 2, 0);
+        }
+        carry_at += tiles_n;
+    };
+
     // Fragment addressing (byte offsets inside a stage), fixed for the whole loop.  The swizzle
     // uses row bits 0..3 only, so the 32-row MFMA tiles of a wave differ by constants, and the
     // 16-wide k-slice ks is reached by XOR-ing (ks << 5) into the offset of slice 0.
@@ -594,7 +614,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         using cALD = std::integral_constant<int, A_LD>;
         const i32x4_t rr = make_rsrc(cRecv, cRecv != nullptr ? r_bytes_of_recv : 0u);
         __amdgpu_buffer_rsrc_t l_rsrc =
-            __builtin_amdgcn_make_buffer_rsrc(cLand, 0, cLand != nullptr ? (int)r_bytes_of_recv : 0, 0x00020000);
+            __builtin_amdgcn_make_buffer_rsrc(static_cast<float *>(cLand), 0, cLand != nullptr ? (int)r_bytes_of_recv : 0, 0x00020000);
         const unsigned r_lds = lds_base + R_BASE + wave * 4096;
         // byte offset of sub-tile q = (i, j) of this wave, row 0 / column 0 of the lane pattern
         auto r_soff = [&](int q) __attribute__((always_inline)) {
@@ -761,7 +781,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 phase(af0, wf0, true, ca, cw, 1, af1, wf1, kt + NS, pa, 0, c0{}, cALD{}, wk);
                 phase(af1, wf1, true, ca, cw, 2, af0, wf0, 0, 0, 0, c0{}, c0{}, wk);
                 phase(af0, wf0, true, ca, cw, 3, af1, wf1, 0, 0, 0, c0{}, c0{}, wk);
-                wait_vmcnt<(NS - 2) * LPT + A_LD>();
+                if (CARRY_A && kt == carry_at) {         // tile kt goes on to the landing buffer: its stores are the
+                    carry_tile(kt, ca);                  // youngest requests and need not be awaited here
+                    wait_vmcnt<(NS - 2) * LPT + 2 * A_LD>();
+                } else {
+                    wait_vmcnt<(NS - 2) * LPT + A_LD>();
+                }
                 __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
                 phase(af1, wf1, true, na, nw_, 0, af0, wf0, kt + NS, 0, cw, cALD{}, cLR{}, wk);
@@ -790,6 +815,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 phase(af0, wf0, true, cur_a, cur_w, 1, af1, wf1, 0, 0, 0, c0{}, c0{}, wk{});
                 phase(af1, wf1, true, cur_a, cur_w, 2, af0, wf0, 0, 0, 0, c0{}, c0{}, wk{});
                 phase(af0, wf0, true, cur_a, cur_w, 3, af1, wf1, 0, 0, 0, c0{}, c0{}, wk{});
+                if (CARRY_A && nk - 1 == carry_at)
+                    carry_tile(nk - 1, cur_a);
                 phase(af1, wf1, false, 0, 0, 0, af0, wf0, 0, 0, 0, c0{}, c0{}, wk{});
             }
         }
@@ -828,10 +855,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             phase_b(af0, wf0, true, cur, 3, af1, wf1, rpm2{});   // reads early: complete at the barrier
             // tile kt+1 complete, NS-2 later tiles may be in flight -- and, in the NS-1 iterations after the
             // B_in prefetch went out behind tile pf_at+NS, those loads too (loads return in issue order)
-            if (PF && pf_on && kt > pf_at && kt < pf_at + NS)
+            if (PF && pf_on && kt > pf_at && kt < pf_at + NS) {
                 wait_vmcnt<(NS - 2) * LPT + PFR>();
-            else
+            } else if (CARRY_A && kt == carry_at) {  // tile kt goes on to the landing buffer (stores not awaited here)
+                carry_tile(kt, cur);
+                wait_vmcnt<(NS - 2) * LPT + A_LD>();
+            } else {
                 wait_vmcnt<(NS - 2) * LPT>();
+            }
             __syncthreads();                 // tile kt is read by all, tile kt+1 is published
             issue_range(kt + NS, cur, cur, c0{}, cLPT{});
             if constexpr (PF) {
@@ -851,6 +882,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             phase_b(af0, wf0, true, cur, 1, af1, wf1, rpm1{});
             phase_b(af1, wf1, true, cur, 2, af0, wf0, rpm1{});
             phase_b(af0, wf0, true, cur, 3, af1, wf1, rpm1{});
+            if (CARRY_A && nk - 1 == carry_at)
+                carry_tile(nk - 1, cur);
             phase_b(af1, wf1, false, 0, 0, af0, wf0, rpm1{});
         }
     }
@@ -962,7 +995,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                     if constexpr (PERSIST && RLDS) {
                         if (cLand != nullptr) {      // (a work item that could not stream still delivers)
                             __amdgpu_buffer_rsrc_t le_rsrc =
-                                __builtin_amdgcn_make_buffer_rsrc(cLand, 0, (int)r_bytes, 0x00020000);
+                                __builtin_amdgcn_make_buffer_rsrc(static_cast<float *>(cLand), 0, (int)r_bytes, 0x00020000);
                             __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, rv[j][g]), le_rsrc, boff, 0, 0);
                         }
                     }
@@ -1053,12 +1086,12 @@ template <int BM, int BN, int WGM, int WGN, int NS, bool SPREAD>
 hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s)
 {
     // reduce-scatter steps on the 256x256 tile: the variant that brings B_in in under the main loop
-    bool any_recv = p.recv != nullptr;
+    bool any_recv = p.n_steps == 0 && p.recv != nullptr;     // (a persistent launch ignores recv and wait_flag)
     for (int j = 0; j < p.n_steps; ++j)
         any_recv = any_recv || p.recv_step[j] != nullptr;
     // (only where the kernel would stream: a long enough k range, one received partial per step, no delivery flag, no
     // k-split -- otherwise the variant with three left-operand stages is the faster one)
-    bool any_flag = p.wait_flag != nullptr;
+    bool any_flag = p.n_steps == 0 && p.wait_flag != nullptr;
     for (int j = 0; j < p.n_steps; ++j)
         any_flag = any_flag || p.flag_step[j] != nullptr;
     const int nk_all = (p.K + BK - 1) / BK;
@@ -1153,6 +1186,13 @@ bool gemm_bf16_dl_streams_recv(const GemmParams &p, bool w_kn, bool out_bf16, Ti
            p.n_recv_more == 0 && nk_all >= 17 + (p.K % BK != 0 ? 2 : 0);
 }
 
+// Can a persistent all-gather launch carry its deliveries (GemmParams::land_step with steps that add nothing)?  Every
+// tile shape can; the k-tiles must be whole (a ragged one would be stored beyond the end of its rows).
+bool gemm_bf16_dl_carries_operand(const GemmParams &p)
+{
+    return p.n_steps > 0 && !p.a_t && p.K % BK == 0;
+}
+
 hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16, hipStream_t s, TileChoice t)
 {
     GemmParams p = p_in;
@@ -1166,6 +1206,9 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
         p.splits = nk_all;
     const int64_t tiles = (int64_t)((p.M + t.bm - 1) / t.bm) * ((p.N + t.bn - 1) / t.bn);
     if (p.n_steps > 0) {
+        for (int j = 0; j < p.n_steps; ++j)
+            if (p.land_step[j] != nullptr && p.recv_step[j] == nullptr && !gemm_bf16_dl_carries_operand(p))
+                return hipErrorInvalidValue;          // callers ask gemm_bf16_carries_delivery first
         p.splits = 1;
         p.cp_wgs = 0;
         p.cp_bytes = 0;

@@ -524,7 +524,8 @@ def test_persistent_rank_step(m, tile, k):
     _tile_env(tile)
     try:
         # (with CF_FUSED_COPY the reduce-scatter launch carries its deliveries itself where it brings B_in in through
-        # LDS -- the 256x256 tile with the longer k ranges -- and has them copied in front otherwise: same results)
+        # LDS -- the 256x256 tile with the longer k ranges -- and the all-gather launch where k is whole k-tiles;
+        # they have them copied in front otherwise: same results)
         for flags in (cf.CF_PERSISTENT | cf.CF_SERIAL, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_GRAPH,
                       cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_POISON, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY,
                       cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY | cf.CF_GRAPH):
@@ -572,6 +573,51 @@ def test_persistent_rank_step(m, tile, k):
     for i in range(wa.p - 1):                                # Alg. 1 sends the slice in hand on
         hand = da["X"] if i == 0 else da["S"][i]
         assert np.array_equal(H.to_host_f64(ag.sink[i]), inputs.as_f64(hand, wa.dtype)), f"all-gather sink {i}"
+
+
+@pytest.mark.parametrize("tile", [None, "256x256", "256x128", "128x128"])
+@pytest.mark.parametrize("k", [64, 128, 1280])         # one k-tile (only the last iteration), two, twenty
+def test_all_gather_carries_its_deliveries(tile, k):
+    """CF_PERSISTENT | CF_FUSED_COPY, all-gather: no copy is launched; the kernel reads the gathered slices from the
+    neighbours' buffers and stores every k-tile on to the landing buffer of its hop.  O against Alg. 1's result,
+    the landing buffers bit for bit against what was sent -- for every tile shape, both weight orders, granularity
+    1 and 2, with and without the k rotation, eagerly and as a replayed graph."""
+    flags = cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY
+    rank = 3
+    _tile_env(tile)
+    try:
+        for out_dtype, n in (("bf16", 520), ("f32", 264)):     # ragged tiles in M and N
+            w = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=8, m_chunk=264, n=n, k=k, out_dtype=out_dtype)
+            data = inputs.make_ag(w, salt=61 + k)
+            ref = _oracle_ag(w, data, rank)
+            for layout, m, rot, extra in ((cf.CF_W_KN, 1, "1", 0), (cf.CF_W_NK, 2, "1", cf.CF_GRAPH), (cf.CF_W_KN, 2, "0", 0)):
+                os.environ["COMMFUSE_K_ROTATE"] = rot
+                run = H.AgRun(w, data, rank, layout, m=m, each=True)
+                for rep in range(2):                       # (a graph: captured, then replayed)
+                    run.O.fill_(float("nan"))
+                    for t in run.each:
+                        t.fill_(float("nan"))
+                    run.run_schedule(flags | extra)
+                    cf.device_status(run.cs)
+                    o = H.to_host_f64(run.O)
+                    assert not np.isnan(o).any(), f"{out_dtype} layout {layout} m {m} rot {rot} rep {rep}"
+                    e = H.rel_err(o, ref)
+                    assert e <= (TIGHT_BF16_OUT if out_dtype == "bf16" else TIGHT_BF16), f"{out_dtype} layout {layout} m {m}: {e:.3e}"
+                    for i in range(w.p - 1):
+                        assert torch.equal(run.each[i], run.stage[i]), f"{out_dtype} layout {layout} m {m} rot {rot} rep {rep}: hop {i + 1}"
+        # a ragged k: the kernel cannot carry (whole k-tiles only), the deliveries are copied in front: same results
+        w = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=8, m_chunk=136, n=264, k=k + 8)
+        data = inputs.make_ag(w, salt=62)
+        run = H.AgRun(w, data, rank, each=True)
+        for t in run.each:
+            t.fill_(float("nan"))
+        run.run_schedule(flags)
+        assert H.rel_err(H.to_host_f64(run.O), _oracle_ag(w, data, rank)) <= TIGHT_BF16
+        for i in range(w.p - 1):
+            assert torch.equal(run.each[i], run.stage[i])
+    finally:
+        _tile_env(None)
+        os.environ.pop("COMMFUSE_K_ROTATE", None)
 
 
 @pytest.mark.parametrize("kind", ["rs", "ag"])
@@ -783,15 +829,9 @@ def test_full_size_rs(name, flags):
     run = H.RsRun(w, data, rank, each=True) if persistent else H.RsRun(w, data, rank, with_sink=True)
     for t in (run.send_each + run.each if persistent else run.sink) + [run.O]:
         t.fill_(float("nan"))
-    carried = persistent and bool(flags & cf.CF_FUSED_COPY)
-    if carried:                                      # the kernel carries its deliveries at both shapes (by default
-        os.environ["COMMFUSE_CARRY"] = "1"           # only where the launch is a single round: the 7B shape)
-    try:
-        with H.Workspace(run.desc, cf.CF_KIND_RS):      # as the benchmark runs it
-            run.run_schedule(flags)
-            cf.device_status(run.cs)
-    finally:
-        os.environ.pop("COMMFUSE_CARRY", None)
+    with H.Workspace(run.desc, cf.CF_KIND_RS):          # as the benchmark runs it
+        run.run_schedule(flags)                         # with CF_FUSED_COPY the kernel carries its deliveries at both shapes
+        cf.device_status(run.cs)
     if persistent:                                   # every delivery landed (copied in front, or carried by the kernel)
         for i in range(w.p - 1):
             assert torch.equal(run.each[i], run.stage[i]), f"delivery of hop {i + 1}"
@@ -803,16 +843,22 @@ def test_full_size_rs(name, flags):
 
 
 @pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_GRAPH, cf.CF_DEVICE_WAIT, PERSISTENT_SERIAL,
-                                   PERSISTENT_SERIAL | cf.CF_GRAPH])
+                                   PERSISTENT_SERIAL | cf.CF_GRAPH, PERSISTENT_SERIAL | cf.CF_FUSED_COPY])
 @pytest.mark.parametrize("name", ["c3_ag_7b", "c4_ag_70b_up"])
 def test_full_size_ag(name, flags):
     w = inputs.CONFIGS[name]
     rank = 0
     data, ref = _full_ref(name, rank)
-    run = H.AgRun(w, data, rank, each=bool(flags & cf.CF_PERSISTENT))
+    persistent = bool(flags & cf.CF_PERSISTENT)
+    run = H.AgRun(w, data, rank, each=persistent)
+    for t in run.each or []:
+        t.fill_(float("nan"))
     with H.Workspace(run.desc, cf.CF_KIND_AG):          # as the benchmark runs it (the 7B shape splits k)
-        run.run_schedule(flags)
+        run.run_schedule(flags)                         # with CF_FUSED_COPY the one launch carries its deliveries
         cf.device_status(run.cs)
+    if persistent:                                   # every delivery landed (copied in front, or carried by the kernel)
+        for i in range(w.p - 1):
+            assert torch.equal(run.each[i], run.stage[i]), f"delivery of hop {i + 1}"
     got = H.to_host_f64(run.O)
     assert not np.isnan(got).any()
     gate, tight = _tols(w)
@@ -846,6 +892,9 @@ def test_full_size_pair_70b(flags):
             cf.run_schedule(rs.desc, cf.CF_KIND_RS, rs.bufs, rs.cs, rs.xs, flags)
         rs.cs.synchronize()
         cf.device_status(rs.cs)
+    if flags & cf.CF_PERSISTENT:
+        for i in range(up.p - 1):
+            assert torch.equal(ag.each[i], ag.stage[i]) and torch.equal(rs.each[i], rs.stage[i]), f"delivery of hop {i + 1}"
     # oracle: H = bf16(AG(X) W_up) (Alg. 1), then Alg. 2 on A = H
     H64 = oracle.round_to_bf16(_full_ref("c4_ag_70b_up", rank)[1])
     e = H.rel_err(H.to_host_f64(ag.O), H64)
