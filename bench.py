@@ -451,15 +451,17 @@ def main() -> int:
         pers.each = [torch.empty((c,), dtype=torch.float32, device=H.DEV) for _ in range(w5.p - 1)]
         pers.bufs = cf.make_buffers(None, None, run.bucket, run.stage, run.slot, (None, None), None, pers.each)
         for name, fl in (("overlapped", 0), ("copy_only", cf.CF_NO_COMPUTE)):
-            for mode, extra in (m_ for m_ in MODES if "persistent" in m_[0] and "carried" not in m_[0]):
+            for mode, extra in (m_ for m_ in MODES if "persistent" in m_[0]):
+                if fl != 0 and "carried" in mode:     # (the add kernels land what they read: no copy-only variant)
+                    continue
                 tp = time_calls(lambda: cf.run_schedule(pers.desc, cf.CF_KIND_DP, pers.bufs, pers.cs, pers.xs, fl | extra),
                                 pers.cs, 10, 2)
                 t["by_mode"].setdefault(mode, {})[name] = tp
                 if tp < t[name][0]:
                     t[name] = (tp, mode)
         # pairwise schedule on the same bucket: seven arrivals for the own slice, summed in one pass (36 B per element)
-        t_pw = min(time_calls(lambda: cf.run_schedule(pers.desc, cf.CF_KIND_DP_PAIR, pers.bufs, pers.cs, pers.xs, extra),
-                              pers.cs, 10, 2) for mode, extra in MODES if "persistent" in mode and "carried" not in mode)
+        t_pw, pw_mode = min((time_calls(lambda: cf.run_schedule(pers.desc, cf.CF_KIND_DP_PAIR, pers.bufs, pers.cs, pers.xs, extra),
+                                        pers.cs, 10, 2), mode) for mode, extra in MODES if "persistent" in mode)
         t_pw_c = time_calls(lambda: cf.run_schedule(pers.desc, cf.CF_KIND_DP_PAIR, pers.bufs, pers.cs, pers.xs,
                                                     cf.CF_PERSISTENT | cf.CF_NO_COPY), pers.cs, 10, 2)
         steps_with_add = w5.p - 1
@@ -467,10 +469,15 @@ def main() -> int:
               "us_per_reduce_kernel": round(t_k * 1e3, 1), "bytes_per_elem": 12,
               "rank_step_us": round(t["overlapped"][0] * 1e3, 1), "rank_step_mode": t["overlapped"][1],
               "rank_step_GBps_algorithmic": round(12.0 * c * steps_with_add / (t["overlapped"][0] * 1e-3) / 1e9, 1),
-              "rank_step_GBps_with_copies": round(20.0 * c * steps_with_add / (t["overlapped"][0] * 1e-3) / 1e9, 1),
+              # bytes moved per element and hop: a copy (8) plus the add (12), or 16 where the add kernel reads the
+              # neighbour's buffer and lands what it reads ("persistent+carried")
+              "rank_step_bytes_per_elem_moved": 16 if "carried" in t["overlapped"][1] else 20,
+              "rank_step_GBps_with_copies": round((16.0 if "carried" in t["overlapped"][1] else 20.0) * c * steps_with_add /
+                                                  (t["overlapped"][0] * 1e-3) / 1e9, 1),
+              "rank_step_us_by_mode": {m_: round(v["overlapped"] * 1e3, 1) for m_, v in t["by_mode"].items() if "overlapped" in v},
               **overlap_eff(t),
               "us_compute_only": round(t["compute_only"][0] * 1e3, 1), "us_copy_only": round(t["copy_only"][0] * 1e3, 1),
-              "pairwise_rank_step_us": round(t_pw * 1e3, 1), "pairwise_us_compute_only": round(t_pw_c * 1e3, 1),
+              "pairwise_rank_step_us": round(t_pw * 1e3, 1), "pairwise_rank_step_mode": pw_mode, "pairwise_us_compute_only": round(t_pw_c * 1e3, 1),
               "pairwise_add_GBps": round(4.0 * (w5.p + 1) * c / (t_pw_c * 1e-3) / 1e9, 1)}
         log("dp", dp)
         del run, pers
@@ -530,8 +537,10 @@ def main() -> int:
                                "GEMM-RS down [8x(1024x3584)]x[3584x8192] + fp32 partials; emulated ring on one GPU",
                    "p": 8, "rank": 0, "mode": head_mode, "us_per_step_by_mode": pair_modes,
                    "mode_note": "persistent = every delivery enqueued in front of ONE kernel per layer (nothing is hidden: "
-                                "hidden_fraction ~ 0); streams / graph / fused-copy / device-wait overlap each delivery with "
-                                "the step kernel before it"},
+                                "hidden_fraction ~ 0); persistent+carried = no copy is enqueued, that one kernel reads what the "
+                                "neighbours send from their buffers under its main loop and stores it to this rank's landing "
+                                "buffers; streams / graph / fused-copy / device-wait overlap each delivery with the step kernel "
+                                "before it"},
         "frac_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
         # of the headline mode, against its own compute-only and copy-only times
         **overlap_of(ms_step, head_comp, head_copy),

@@ -290,7 +290,8 @@ enum {
     CF_SERIAL = 4u,      /* one stream, copy i+1 strictly after kernel i: no overlap   */
     CF_POISON = 8u,      /* debug: fill each B_in slot with NaN bytes before its copy  */
     CF_GRAPH = 16u,      /* capture the schedule once into a HIP graph, replay after   */
-    CF_FUSED_COPY = 32u, /* bf16 RS / AG only: the delivery for step i+1 is carried by
+    CF_FUSED_COPY = 32u, /* bf16 RS / AG only (bucket kinds: with CF_PERSISTENT only, see
+                            there): the delivery for step i+1 is carried by
                             extra workgroups of step i's kernel launch instead of a
                             hipMemcpyAsync on copy_stream: one stream, no events
                             (copy_stream is unused; not with CF_POISON)               */
@@ -326,7 +327,10 @@ enum {
                             sum over k is taken in a rotated order.
                             Bucket kinds (CF_KIND_DP, CF_KIND_DP_PAIR; fp32): there is no GEMM to fuse
                             into; the flag buys the deliveries of all hops as ONE batched copy launch
-                            into recv_each, followed by the same add kernels in the same order.
+                            into recv_each, followed by the same add kernels in the same order.  With
+                            CF_FUSED_COPY no copy is launched: the add kernels read the arrivals from
+                            the neighbours' buffers (peer_stage) and store them on to recv_each in the
+                            same pass (same sums, bit for bit).
                             With CF_FUSED_COPY (CF_KIND_RS, CF_KIND_AG): the delivery is carried by the
                             consumer -- no copy is launched, the emulated transfer runs inside the kernel,
                             under its main loop.  Reduce-scatter: the waves that need B_in read it from the

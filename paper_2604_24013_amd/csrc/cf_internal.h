@@ -141,10 +141,12 @@ bool attn_slice_supported(const AttnParams &p);
 hipError_t launch_attn_slice(const AttnParams &p, hipStream_t s, int num_cu);
 
 // dst[e] += src[e], e in [0, n)
-hipError_t launch_dp_reduce(float *dst, const float *src, int64_t n, hipStream_t s, int num_cu);
+// (land: nullable -- what is read from src is also stored there, the delivery carried by the consumer)
+hipError_t launch_dp_reduce(float *dst, const float *src, int64_t n, hipStream_t s, int num_cu, float *land = nullptr);
 // dst <- (((dst + src[0]) + src[1]) + ...) over n elements, one pass when all pointers are 16-byte aligned and
 // n_src <= 15 (else one pass per source: same additions, same order, same bits)
-hipError_t launch_dp_reduce_multi(float *dst, const float *const *src, int n_src, int64_t n, hipStream_t s, int num_cu);
+hipError_t launch_dp_reduce_multi(float *dst, const float *const *src, int n_src, int64_t n, hipStream_t s, int num_cu,
+                                  float *const *land = nullptr);
 // n (<= 16) copies of `bytes` bytes each in one launch; copy_batch_takes says whether the arguments qualify
 // (16-byte aligned pointers, bytes a multiple of 16), else the caller copies one by one
 bool copy_batch_takes(const void *const *src, void *const *dst, int n, size_t bytes);

@@ -333,7 +333,7 @@ cf_status ag_step_impl(const Resolved &r, int step, const void *shard, const voi
 
 // chunk_elems: elements per (sub-)step; m: sub-steps per hop
 cf_status dp_step_impl(int p, int rank, int step, float *bucket, int64_t chunk_elems, const float *recv,
-                       hipStream_t s, int m = 1)
+                       hipStream_t s, int m = 1, float *land = nullptr)
 {
     if (p < 1)
         return fail(CF_ERR_INVALID_ARG, "p = %d must be >= 1", p);
@@ -351,7 +351,7 @@ cf_status dp_step_impl(int p, int rank, int step, float *bucket, int64_t chunk_e
         return fail(CF_ERR_MISALIGNED, "fp32 pointers must be 4-byte aligned");
     const int l = subslice_index(CF_KIND_DP, p, m, rank, step);
     hipError_t e = cf::launch_dp_reduce(bucket + (int64_t)l * chunk_elems, recv, chunk_elems, s,
-                                        num_cu_of_current_device());
+                                        num_cu_of_current_device(), land);
     if (e != hipSuccess)
         return fail_hip(e, "gradient reduce launch");
     return CF_OK;
@@ -895,6 +895,11 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
         probe.n_steps = S;
         carried = cf::gemm_bf16_carries_delivery(probe, r.w_kn, r.bf16_out, num_cu_of_current_device(), kind == CF_KIND_RS);
     }
+    // The gradient bucket with CF_FUSED_COPY: the add kernels read the arrivals from the neighbours' buffers and
+    // store them on to the landing buffers in the same pass (ring: 16 bytes per element instead of a copy's 8 plus
+    // the add's 12; pairwise, p - 1 arrivals in one pass: 8 p instead of 12 p - 4).
+    if ((flags & CF_FUSED_COPY) && is_dp_kind(kind) && do_copy && do_compute && slot_bytes > 0)
+        carried = true;
     if (do_copy && slot_bytes > 0 && !carried) {
         // all deliveries of the rank step are due now: one batched copy launch where the buffers allow it
         // (at most 16 hops of 16-byte-aligned whole hop buffers), else one hipMemcpyAsync per (sub-)step
@@ -928,12 +933,15 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
     if (do_compute && kind == CF_KIND_DP_PAIR && p > 1 && r.mc > 0) {
         // every round's arrival goes into the own slice: one pass that reads them all (same order of additions)
         const float *srcs[cf::GemmParams::MAX_STEPS];
-        for (int j = 1; j < p; ++j)
-            srcs[j - 1] = static_cast<const float *>(landing(j));
+        float *lands[cf::GemmParams::MAX_STEPS];
+        for (int j = 1; j < p; ++j) {
+            srcs[j - 1] = carried ? reinterpret_cast<const float *>(stage_of(j)) : static_cast<const float *>(landing(j));
+            lands[j - 1] = static_cast<float *>(landing(j));
+        }
         if (cf_status st = check_pair_p(p))
             return st;
         hipError_t e = cf::launch_dp_reduce_multi(static_cast<float *>(b->O) + (int64_t)r.rank * r.mc, srcs, p - 1, r.mc, cs,
-                                                  num_cu_of_current_device());
+                                                  num_cu_of_current_device(), carried ? lands : nullptr);
         if (e != hipSuccess)
             return fail_hip(e, "gradient reduce launch");
         return CF_OK;
@@ -941,9 +949,10 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
     if (do_compute && is_dp_kind(kind)) {
         float *bucket = static_cast<float *>(b->O);
         for (int j = m; j < S; ++j) {
-            const float *recv = static_cast<const float *>(landing(j));
+            const float *recv = carried ? reinterpret_cast<const float *>(stage_of(j)) : static_cast<const float *>(landing(j));
             cf_status st = kind == CF_KIND_DP_PAIR ? dp_pair_step_impl(p, r.rank, j, bucket, r.mc, recv, cs)
-                                                   : dp_step_impl(p, r.rank, j, bucket, r.mc, recv, cs, m);
+                                                   : dp_step_impl(p, r.rank, j, bucket, r.mc, recv, cs, m,
+                                                                  carried ? static_cast<float *>(landing(j)) : nullptr);
             if (st != CF_OK)
                 return st;
         }
@@ -1111,8 +1120,10 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
     if (is_pair_kind(kind)) {
         if (cf_status st = check_pair_p(r.p))
             return st;
-        if (flags & (CF_FUSED_COPY | CF_DEVICE_WAIT))
-            return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY / CF_DEVICE_WAIT are not available for the pairwise kinds");
+        const bool dp_one_launch = kind == CF_KIND_DP_PAIR && (flags & CF_PERSISTENT) && !(flags & CF_DEVICE_WAIT);
+        if ((flags & (CF_FUSED_COPY | CF_DEVICE_WAIT)) && !dp_one_launch)
+            return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY / CF_DEVICE_WAIT are not available for the pairwise kinds (but "
+                                            "CF_FUSED_COPY with CF_PERSISTENT for the pairwise gradient bucket)");
     }
     if (flags & CF_DEVICE_WAIT) {
         if (flags & CF_FUSED_COPY)
@@ -1128,8 +1139,10 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
     if (flags & CF_FUSED_COPY) {
         if (flags & CF_POISON)
             return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY cannot be combined with CF_POISON");
-        if (is_dp_kind(kind) || !(is_wgrad_kind(kind) ? wgrad_can_carry_copy(r) : step_can_carry_copy(r)))
-            return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY needs the bf16 chunk-GEMM kernels (kind RS or AG, bf16 operands)");
+        const bool dp_one_launch = is_dp_kind(kind) && (flags & CF_PERSISTENT);   // the add kernels carry the deliveries
+        if (!dp_one_launch && (is_dp_kind(kind) || !(is_wgrad_kind(kind) ? wgrad_can_carry_copy(r) : step_can_carry_copy(r))))
+            return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY needs the bf16 chunk-GEMM kernels (kind RS or AG, bf16 operands), or "
+                                            "CF_PERSISTENT for the gradient-bucket kinds");
     }
     if (flags & CF_PERSISTENT) {
         if (flags & CF_DEVICE_WAIT)

@@ -2,7 +2,9 @@
 // compute_partial_output, i.e. "O <- B_in + O" on one slice of the local fp32
 // gradient bucket, in place.  HBM-bound: 12 bytes per element (read slice, read
 // B_in, write slice).  16-byte accesses, several independent loads in flight
-// per lane, one pass over the slice.
+// per lane, one pass over the slice.  A variant also carries the emulated delivery:
+// B_in is read from the neighbour's buffer and stored on to the landing buffer in the
+// same pass (16 bytes per element instead of a copy's 8 plus the add's 12).
 #include "cf_internal.h"
 
 namespace cf {
@@ -13,10 +15,15 @@ typedef float f32x4_t __attribute__((ext_vector_type(4)));
 constexpr int DP_THREADS = 256;
 constexpr int DP_UNROLL = 4;
 
+// LAND: the delivery carried by the consumer -- src is the neighbour's buffer, and what is read from it is also stored
+// to `land`, this rank's landing buffer: 16 bytes per element (two reads, two writes) where a copy followed by the add
+// moves 20.
+template <bool LAND>
 __global__ __launch_bounds__(DP_THREADS) void dp_reduce_vec_kernel(f32x4_t *__restrict__ dst,
-                                                                  const f32x4_t *__restrict__ src, int64_t n4)
+                                                                  const f32x4_t *__restrict__ src, int64_t n4,
+                                                                  f32x4_t *__restrict__ land)
 {
-    // Every element is touched exactly once: all three streams bypass the caches' retention
+    // Every element is touched exactly once: all streams bypass the caches' retention
     // (non-temporal), which measured ~25% faster than cached accesses on MI355X.
     const int64_t stride = (int64_t)gridDim.x * DP_THREADS;
     int64_t i = (int64_t)blockIdx.x * DP_THREADS + threadIdx.x;
@@ -28,19 +35,31 @@ __global__ __launch_bounds__(DP_THREADS) void dp_reduce_vec_kernel(f32x4_t *__re
             b[u] = __builtin_nontemporal_load(&src[i + u * stride]);
         }
 #pragma unroll
-        for (int u = 0; u < DP_UNROLL; ++u)
+        for (int u = 0; u < DP_UNROLL; ++u) {
             __builtin_nontemporal_store(b[u] + a[u], &dst[i + u * stride]);   // "O <- B_in + O"
+            if constexpr (LAND)
+                __builtin_nontemporal_store(b[u], &land[i + u * stride]);
+        }
     }
-    for (; i < n4; i += stride)
-        __builtin_nontemporal_store(__builtin_nontemporal_load(&src[i]) + __builtin_nontemporal_load(&dst[i]), &dst[i]);
+    for (; i < n4; i += stride) {
+        const f32x4_t b = __builtin_nontemporal_load(&src[i]);
+        __builtin_nontemporal_store(b + __builtin_nontemporal_load(&dst[i]), &dst[i]);
+        if constexpr (LAND)
+            __builtin_nontemporal_store(b, &land[i]);
+    }
 }
 
 __global__ __launch_bounds__(DP_THREADS) void dp_reduce_scalar_kernel(float *__restrict__ dst,
-                                                                     const float *__restrict__ src, int64_t n)
+                                                                     const float *__restrict__ src, int64_t n,
+                                                                     float *__restrict__ land)
 {
     const int64_t stride = (int64_t)gridDim.x * DP_THREADS;
-    for (int64_t i = (int64_t)blockIdx.x * DP_THREADS + threadIdx.x; i < n; i += stride)
-        dst[i] = src[i] + dst[i];
+    for (int64_t i = (int64_t)blockIdx.x * DP_THREADS + threadIdx.x; i < n; i += stride) {
+        const float b = src[i];
+        dst[i] = b + dst[i];
+        if (land != nullptr)
+            land[i] = b;
+    }
 }
 
 // dst <- (((dst + src[0]) + src[1]) + ...) in ONE pass: the pairwise gradient reduce, where every round's arrival
@@ -51,8 +70,10 @@ struct AddBatch {
     const float *src[MAX];
 };
 
+// LAND: as above -- source s is also stored to land[s].
+template <bool LAND>
 __global__ __launch_bounds__(DP_THREADS) void dp_reduce_multi_kernel(f32x4_t *__restrict__ dst, AddBatch ab, int n_src,
-                                                                    int64_t n4)
+                                                                    int64_t n4, AddBatch lb)
 {
     constexpr int U = 2;                             // vectors per lane: (n_src + 1) * U loads in flight
     const int64_t base = (int64_t)blockIdx.x * DP_THREADS * U + threadIdx.x;
@@ -63,10 +84,15 @@ __global__ __launch_bounds__(DP_THREADS) void dp_reduce_multi_kernel(f32x4_t *__
             a[u] = __builtin_nontemporal_load(&dst[base + u * DP_THREADS]);
     for (int s = 0; s < n_src; ++s) {
         const f32x4_t *__restrict__ src = reinterpret_cast<const f32x4_t *>(ab.src[s]);
+        f32x4_t *__restrict__ land = reinterpret_cast<f32x4_t *>(const_cast<float *>(lb.src[s]));
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (base + u * DP_THREADS < n4)
-                a[u] = __builtin_nontemporal_load(&src[base + u * DP_THREADS]) + a[u];
+            if (base + u * DP_THREADS < n4) {
+                const f32x4_t b = __builtin_nontemporal_load(&src[base + u * DP_THREADS]);
+                a[u] = b + a[u];
+                if constexpr (LAND)
+                    __builtin_nontemporal_store(b, &land[base + u * DP_THREADS]);
+            }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
@@ -75,13 +101,17 @@ __global__ __launch_bounds__(DP_THREADS) void dp_reduce_multi_kernel(f32x4_t *__
 }
 
 __global__ __launch_bounds__(DP_THREADS) void dp_reduce_multi_scalar_kernel(float *__restrict__ dst, AddBatch ab, int n_src,
-                                                                           int64_t first, int64_t n)
+                                                                           int64_t first, int64_t n, AddBatch lb, bool land)
 {
     const int64_t stride = (int64_t)gridDim.x * DP_THREADS;
     for (int64_t i = first + (int64_t)blockIdx.x * DP_THREADS + threadIdx.x; i < n; i += stride) {
         float a = dst[i];
-        for (int s = 0; s < n_src; ++s)
-            a = ab.src[s][i] + a;
+        for (int s = 0; s < n_src; ++s) {
+            const float b = ab.src[s][i];
+            a = b + a;
+            if (land)
+                const_cast<float *>(lb.src[s])[i] = b;
+        }
         dst[i] = a;
     }
 }
@@ -127,11 +157,12 @@ __global__ __launch_bounds__(256) void fill_ff_kernel(unsigned *dst, size_t nwor
 
 }  // namespace
 
-hipError_t launch_dp_reduce(float *dst, const float *src, int64_t n, hipStream_t s, int num_cu)
+hipError_t launch_dp_reduce(float *dst, const float *src, int64_t n, hipStream_t s, int num_cu, float *land)
 {
     if (n <= 0)
         return hipSuccess;
-    const bool aligned = ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15u) == 0;
+    const bool aligned = ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src) |
+                           reinterpret_cast<uintptr_t>(land)) & 15u) == 0;
     const int64_t n4 = aligned ? n / 4 : 0;
     if (n4 > 0) {
         // one workgroup per DP_THREADS * DP_UNROLL vectors: a grid that covers the slice once measured
@@ -140,8 +171,12 @@ hipError_t launch_dp_reduce(float *dst, const float *src, int64_t n, hipStream_t
         const int64_t cap = (int64_t)1 << 30;
         (void)num_cu;
         const int blocks = (int)(want < cap ? want : cap);
-        hipLaunchKernelGGL(dp_reduce_vec_kernel, dim3(blocks), dim3(DP_THREADS), 0, s,
-                           reinterpret_cast<f32x4_t *>(dst), reinterpret_cast<const f32x4_t *>(src), n4);
+        if (land != nullptr)
+            hipLaunchKernelGGL(dp_reduce_vec_kernel<true>, dim3(blocks), dim3(DP_THREADS), 0, s, reinterpret_cast<f32x4_t *>(dst),
+                               reinterpret_cast<const f32x4_t *>(src), n4, reinterpret_cast<f32x4_t *>(land));
+        else
+            hipLaunchKernelGGL(dp_reduce_vec_kernel<false>, dim3(blocks), dim3(DP_THREADS), 0, s, reinterpret_cast<f32x4_t *>(dst),
+                               reinterpret_cast<const f32x4_t *>(src), n4, static_cast<f32x4_t *>(nullptr));
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return e;
@@ -152,44 +187,53 @@ hipError_t launch_dp_reduce(float *dst, const float *src, int64_t n, hipStream_t
         int64_t want = (rest + DP_THREADS - 1) / DP_THREADS;
         const int64_t cap = (int64_t)num_cu * 8;
         const int blocks = (int)(want < cap ? want : cap);
-        hipLaunchKernelGGL(dp_reduce_scalar_kernel, dim3(blocks), dim3(DP_THREADS), 0, s, dst + done, src + done, rest);
+        hipLaunchKernelGGL(dp_reduce_scalar_kernel, dim3(blocks), dim3(DP_THREADS), 0, s, dst + done, src + done, rest,
+                           land != nullptr ? land + done : nullptr);
         return hipGetLastError();
     }
     return hipSuccess;
 }
 
-hipError_t launch_dp_reduce_multi(float *dst, const float *const *src, int n_src, int64_t n, hipStream_t s, int num_cu)
+hipError_t launch_dp_reduce_multi(float *dst, const float *const *src, int n_src, int64_t n, hipStream_t s, int num_cu,
+                                  float *const *land)
 {
     if (n <= 0 || n_src <= 0)
         return hipSuccess;
     uintptr_t bits = reinterpret_cast<uintptr_t>(dst);
     for (int i = 0; i < n_src; ++i)
-        bits |= reinterpret_cast<uintptr_t>(src[i]);
+        bits |= reinterpret_cast<uintptr_t>(src[i]) | (land != nullptr ? reinterpret_cast<uintptr_t>(land[i]) : 0);
     if (n_src > AddBatch::MAX || (bits & 15u) != 0) {        // one pass per source: the same additions in the same order
         for (int i = 0; i < n_src; ++i) {
-            hipError_t e = launch_dp_reduce(dst, src[i], n, s, num_cu);
+            hipError_t e = launch_dp_reduce(dst, src[i], n, s, num_cu, land != nullptr ? land[i] : nullptr);
             if (e != hipSuccess)
                 return e;
         }
         return hipSuccess;
     }
-    AddBatch ab = {};
-    for (int i = 0; i < n_src; ++i)
+    AddBatch ab = {}, lb = {};
+    for (int i = 0; i < n_src; ++i) {
         ab.src[i] = src[i];
+        lb.src[i] = land != nullptr ? land[i] : nullptr;
+    }
     const int64_t n4 = n / 4;
     if (n4 > 0) {
         const int64_t per_wg = (int64_t)DP_THREADS * 2;
         const int64_t want = (n4 + per_wg - 1) / per_wg;
         if (want >= ((int64_t)1 << 31))
             return hipErrorInvalidValue;
-        hipLaunchKernelGGL(dp_reduce_multi_kernel, dim3((unsigned)want), dim3(DP_THREADS), 0, s,
-                           reinterpret_cast<f32x4_t *>(dst), ab, n_src, n4);
+        if (land != nullptr)
+            hipLaunchKernelGGL(dp_reduce_multi_kernel<true>, dim3((unsigned)want), dim3(DP_THREADS), 0, s,
+                               reinterpret_cast<f32x4_t *>(dst), ab, n_src, n4, lb);
+        else
+            hipLaunchKernelGGL(dp_reduce_multi_kernel<false>, dim3((unsigned)want), dim3(DP_THREADS), 0, s,
+                               reinterpret_cast<f32x4_t *>(dst), ab, n_src, n4, lb);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess)
             return e;
     }
     if (n4 * 4 < n) {
-        hipLaunchKernelGGL(dp_reduce_multi_scalar_kernel, dim3(1), dim3(DP_THREADS), 0, s, dst, ab, n_src, n4 * 4, n);
+        hipLaunchKernelGGL(dp_reduce_multi_scalar_kernel, dim3(1), dim3(DP_THREADS), 0, s, dst, ab, n_src, n4 * 4, n, lb,
+                           land != nullptr);
         return hipGetLastError();
     }
     return hipSuccess;

@@ -158,12 +158,15 @@ def test_dp_granularity(p, m, c):
         for i in range(p - 1):
             l = (rank - i - 1) % p
             assert np.array_equal(H.to_host_f64(run.sink[i]), want32[l * c:(l + 1) * c]), f"flags {flags} hop {i}"
-    pers = H.DpRun(w, data, rank, m=m, each=True)                 # the m sub-slices of a hop stacked in its landing buffer
-    for t in pers.each:
-        t.fill_(float("nan"))
-    torch.cuda.synchronize()                         # the fills run on another stream than the schedule
-    pers.run_schedule(cf.CF_PERSISTENT | cf.CF_SERIAL)
-    assert np.array_equal(H.to_host_f64(pers.bucket), want32)
+    for flags in (cf.CF_PERSISTENT | cf.CF_SERIAL, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY):
+        pers = H.DpRun(w, data, rank, m=m, each=True)             # the m sub-slices of a hop stacked in its landing buffer
+        for t in pers.each:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()                     # the fills run on another stream than the schedule
+        pers.run_schedule(flags)
+        assert np.array_equal(H.to_host_f64(pers.bucket), want32), f"flags {flags}"
+        for i in range(p - 1):                       # copied in front, or landed by the add kernels themselves
+            assert torch.equal(pers.each[i], pers.stage[i]), f"flags {flags}: delivery of hop {i + 1}"
 
 
 def test_granularity_bad_arguments():

@@ -163,12 +163,16 @@ def test_dp_pair_reduced(p, c):
         l = oracle.slice_index_pair(p, rank, i)
         assert np.array_equal(H.to_host_f64(run.sink[i]), data["bucket"][l * c:(l + 1) * c].astype(np.float64))
     # CF_PERSISTENT: all rounds' deliveries as one batched copy into a buffer per round, then the adds in round order
-    pers = H.DpPairRun(w, data, rank, each=True)
-    for t in pers.each:
-        t.fill_(float("nan"))
-    torch.cuda.synchronize()                         # the fills run on another stream than the schedule
-    pers.run_schedule(cf.CF_PERSISTENT | cf.CF_SERIAL)
-    assert np.array_equal(H.to_host_f64(pers.bucket), ref)
+    # (with CF_FUSED_COPY no copy is launched: the one add pass reads the partners' buffers and lands what it reads)
+    for flags in (cf.CF_PERSISTENT | cf.CF_SERIAL, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY):
+        pers = H.DpPairRun(w, data, rank, each=True)
+        for t in pers.each:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()                     # the fills run on another stream than the schedule
+        pers.run_schedule(flags)
+        assert np.array_equal(H.to_host_f64(pers.bucket), ref), f"flags {flags}"
+        for i in range(p - 1):
+            assert torch.equal(pers.each[i], pers.stage[i]), f"flags {flags}: delivery of round {i + 1}"
     # normally distributed gradients: p-1 fp32 additions in round order
     data = inputs.make_dp(w, salt=9)
     ref = oracle.dp_pair_rank(data["bucket"], data["R"], p, rank)

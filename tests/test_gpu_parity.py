@@ -384,14 +384,18 @@ def test_dp_reduced(p, c):
     # CF_PERSISTENT: every hop lands in a buffer of its own, all deliveries as one batched copy (slices whose
     # byte size is no multiple of 16: one copy per hop), then the same adds
     run = H.DpRun(w, data, rank, each=True)
+    # (with CF_FUSED_COPY no copy is launched: the add kernels read the neighbours' buffers and land what they read)
     for flags in (cf.CF_PERSISTENT | cf.CF_SERIAL, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_GRAPH,
-                  cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_GRAPH):
+                  cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_GRAPH, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY,
+                  cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY | cf.CF_GRAPH):
         run.bucket.copy_(H.to_dev(data["bucket"], "f32"))
         for t in run.each:
             t.fill_(float("nan"))
         torch.cuda.synchronize()
         run.run_schedule(flags)
         assert np.array_equal(H.to_host_f64(run.bucket), want32), f"flags {flags}"
+        for i in range(p - 1):
+            assert torch.equal(run.each[i], run.stage[i]), f"flags {flags}: delivery of hop {i + 1}"
     if p > 1:
         with pytest.raises(cf.CommFuseError) as ei:              # a landing buffer per hop is a CF_PERSISTENT matter here
             run.run_schedule(cf.CF_SERIAL)
@@ -908,7 +912,7 @@ def test_full_size_pair_70b(flags):
         assert e <= TOL_BF16 and e <= 1e-3, f"step {i}: {e:.3e}"
 
 
-@pytest.mark.parametrize("flags", [0, PERSISTENT_SERIAL])
+@pytest.mark.parametrize("flags", [0, PERSISTENT_SERIAL, PERSISTENT_SERIAL | cf.CF_FUSED_COPY])
 def test_full_size_dp(flags):
     w = inputs.CONFIGS["c5_dp"]
     data = inputs.make_dp(w)
@@ -919,6 +923,9 @@ def test_full_size_dp(flags):
             t.fill_(float("nan"))
         torch.cuda.synchronize()                     # the fills run on another stream than the schedule
     run.run_schedule(flags)
+    if run.each:                                     # copied in front, or landed by the add kernels themselves
+        for i in range(w.p - 1):
+            assert torch.equal(run.each[i], run.stage[i]), f"delivery of hop {i + 1}"
     c = w.m_chunk
     touched = {(rank - i - 1) % w.p: i for i in range(1, w.p)}
     for l in range(w.p):
