@@ -339,8 +339,8 @@ enum {
                             neighbours' buffers as its left operand, and every k-tile that comes in is
                             stored on to the landing buffer by one of the workgroups that load it.  (A row
                             block lands without the padding of its rows.)  Where the launch cannot do that
-                            (reduce-scatter: a tile other than 256x256, a k range under 17 k-tiles of 64,
-                            or 19 with a ragged last one; all-gather: k not a multiple of 64; the other
+                            (reduce-scatter: a tile other than 256x256, a k range under 18 k-tiles of 64,
+                            or 20 with a ragged last one; all-gather: k not a multiple of 64; the other
                             kinds) the flag changes nothing: the deliveries are enqueued in front.
                             Not with CF_DEVICE_WAIT.                                                  */
     CF_DEVICE_WAIT = 64u /* bf16 RS / AG only, needs a registered workspace: the compute

@@ -157,15 +157,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // fills the 160 KiB with THREE left-operand stages and two weight stages: its weight loads go out first
     // after the barrier that frees their stage and its left-operand loads one k-tile further ahead (see the
     // steady state below), which lengthens the time every load has to arrive.
-    constexpr int NSA = (SPREAD && !RLDS) ? NS + 1 : NS;
+    constexpr int NSA = SPREAD ? NS + 1 : NS;
     constexpr int W_BASE = NSA * A_BYTES;
-    constexpr int R_BASE = NSA * A_BYTES + NS * B_BYTES;      // RLDS: landing area of B_in, 4 KiB per wave
-    constexpr int R_BYTES = RLDS ? NW * 4096 : 0;
-    // wave-private scratch of the epilogue's stores: the landing area where there is one, else the start of the
-    // stages (after a barrier: every wave is done reading them)
-    constexpr int E_SCR = RLDS ? R_BASE : 0;
-    constexpr int E_SCR_BYTES = RLDS ? 4096 : 4608;
-    static_assert(RLDS || NW * E_SCR_BYTES <= NSA * A_BYTES + NS * B_BYTES, "epilogue scratch inside the stages");
+    constexpr int R_BYTES = 0;
+    // wave-private scratch of the epilogue's stores (4 KiB per wave): a left-operand stage that no load targets any
+    // more -- RLDS: the stage that served as the landing area of B_in (land_stage below); else the third stage of the
+    // 256x256 tile, else the first (after a barrier: every wave is done reading the stages)
+    constexpr int E_SCR_BYTES = 4096;
+    static_assert(NW * E_SCR_BYTES <= A_BYTES || !SPREAD, "epilogue scratch inside one left-operand stage");
+    static_assert(NW * E_SCR_BYTES <= NSA * A_BYTES + NS * B_BYTES, "epilogue scratch inside the stages");
     static_assert(NS >= 2 && NS <= 4 && NSA * A_BYTES + NS * B_BYTES + R_BYTES <= 160 * 1024, "LDS budget");
     static_assert(KS == 4, "the slice schedule below is written for four slices per stage");
     constexpr int W_ROWB = BN * 2;                   // bytes of one k-row of a [k x n] weight tile
@@ -591,165 +591,19 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     };
 
     // RLDS: is B_in streamed in under the main loop for this work item?  (Uniform.)  It needs sixteen k-tiles
-    // before the last one (and before the iterations that test their loads); a step that waits for a delivery
-    // flag, sums several received partials or is a k-split keeps the loads in the epilogue.
+    // before the last one (and before the iterations that test their loads), and one more for the change of
+    // schedule in front of them; a step that waits for a delivery flag, sums several received partials or is a
+    // k-split keeps the loads in the epilogue.
     constexpr int RQ = TM * TN;                       // 32x32 sub-tiles per wave, one in flight at a time
     // A ragged k tail (the launcher then leaves the k order unrotated: it is the last k-tile) is requested in the
     // last two iterations before the final tile; those test their loads and come after the streamed ones.
     const int tested = (RLDS && K % BK != 0) ? (nk - 1 < 2 ? nk - 1 : 2) : 0;
     const bool streamed = RLDS && cRecv != nullptr && cFlag == nullptr && n_more == 0 && splits == 1 &&
-                          P.stream_recv && nk >= 2 * RQ + 1 + tested && (tested == 0 || rot == 0);
-    if constexpr (RLDS) {
-        // Two stages of both operands (tile t in stage t & 1) and the landing area.  Iteration kt:
-        //     slice 0: + the weight loads of tile kt+1 (its stage was vacated at the barrier of iteration kt-1)
-        //     slice 1 (X iterations: + the four B_in loads of one sub-tile), slice 2
-        //     wait: tile kt+1 complete (X: the B_in loads just issued may still be in flight); barrier
-        //     (Y iterations: the sub-tile is read from the landing area and added to its accumulators)
-        //     slice 3: + the left-operand loads of tile kt+2, into the stage tile kt vacated
-        // Loads return in issue order: the B_in loads of an X iteration are behind the weight loads of tile
-        // kt+1 and ahead of everything tile kt+2 needs, so they have until the wait of the following (Y)
-        // iteration, one and a half k-tiles of MFMA time, to arrive.  Each wave reads back only what it
-        // loaded itself, so its own vmcnt wait is all the ordering the landing area needs.
-        static_assert(A_LD <= NSEG && B_LD <= NSEG && NSEG == 4, "one load slot per MFMA segment");
-        using cALD = std::integral_constant<int, A_LD>;
-        const i32x4_t rr = make_rsrc(cRecv, cRecv != nullptr ? r_bytes_of_recv : 0u);
-        __amdgpu_buffer_rsrc_t l_rsrc =
-            __builtin_amdgcn_make_buffer_rsrc(static_cast<float *>(cLand), 0, cLand != nullptr ? (int)r_bytes_of_recv : 0, 0x00020000);
-        const unsigned r_lds = lds_base + R_BASE + wave * 4096;
-        // byte offset of sub-tile q = (i, j) of this wave, row 0 / column 0 of the lane pattern
-        auto r_soff = [&](int q) __attribute__((always_inline)) {
-            const int i = q / TN, j = q % TN;
-            return (int)((((int64_t)(m0 + wm * WTM + i * 32)) * P.ldo + n0 + wn * WTN + j * 32) * 4);
-        };
-        auto phase_x = [&](const bf16x8_t (&afc)[TM], const bf16x8_t (&wfc)[TN], int sa_n, int sw_n, int ks_n,
-                           bf16x8_t (&afn)[TM], bf16x8_t (&wfn)[TN], int q) __attribute__((always_inline)) {
-            const int so = r_soff(q);
-            // a lane outside the matrix must not touch memory: the scalar part of the address is not covered
-            // by the buffer's range check, so such a lane is given the out-of-range offset itself
-            // (computed from an opaque copy of the lane index: otherwise the offsets of all eight sub-tiles are
-            // hoisted out of the k loop and held in registers the main loop does not have)
-            int ln = lane;
-            asm volatile("" : "+v"(ln));
-            const int rm = m0 + wm * WTM + (q / TN) * 32 + (ln & 31);
-            const int rn = n0 + wn * WTN + (q % TN) * 32 + (ln >> 5) * 4;
-            const unsigned rv = (unsigned)((((int64_t)(ln & 31)) * P.ldo + (ln >> 5) * 4) * 4);
-            const unsigned v0 = (rm < M && rn < N) ? rv : OOB, v1 = (rm < M && rn + 8 < N) ? rv : OOB;
-            const unsigned v2 = (rm < M && rn + 16 < N) ? rv : OOB, v3 = (rm < M && rn + 24 < N) ? rv : OOB;
-            read_frags(sa_n, sw_n, ks_n, afn, wfn);
-            mfma_seg(afc, wfc, std::integral_constant<int, 0>{});
-            interleave_mfma_reads<NREAD, (NREAD + MPS - 1) / MPS>();
-            __builtin_amdgcn_sched_barrier(0);
-            direct_load_16(rr, v0, so, r_lds);
-            mfma_seg(afc, wfc, std::integral_constant<int, 1>{});
-            __builtin_amdgcn_sched_barrier(0);
-            direct_load_16(rr, v1, so + 32, r_lds + 1024);
-            mfma_seg(afc, wfc, std::integral_constant<int, 2>{});
-            __builtin_amdgcn_sched_barrier(0);
-            direct_load_16(rr, v2, so + 64, r_lds + 2048);
-            mfma_seg(afc, wfc, std::integral_constant<int, 3>{});
-            __builtin_amdgcn_sched_barrier(0);
-            direct_load_16(rr, v3, so + 96, r_lds + 3072);
-        };
-        auto add_landed = [&](auto q_tag) __attribute__((always_inline)) {          // "O <- B_in + O" for sub-tile q, in mid-sum
-            constexpr int q = decltype(q_tag)::value;
-            int ln = lane;
-            asm volatile("" : "+v"(ln));
-            const unsigned char *src = smem + R_BASE + wave * 4096 + ln * 16;
-            f32x4_t v[4];
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                v[g] = *reinterpret_cast<const f32x4_t *>(src + g * 1024);
-                acc[q / TN][q % TN][4 * g + 0] += v[g][0];
-                acc[q / TN][q % TN][4 * g + 1] += v[g][1];
-                acc[q / TN][q % TN][4 * g + 2] += v[g][2];
-                acc[q / TN][q % TN][4 * g + 3] += v[g][3];
-            }
-            // the delivery carried by the consumer: what just arrived from the neighbour's buffer is also stored to
-            // this rank's landing buffer (a lane outside the matrix is given the out-of-range offset: store dropped)
-            if (cLand != nullptr) {
-                // Whole 128-byte lines per store: the sub-tile is read from the landing area a second time, eight
-                // lanes to a row (chunk c of row r lies in plane c / 2 at lane slot r + 32 (c & 1)), so that one
-                // store instruction writes eight full rows instead of 32-byte pieces of thirty-two.
-                const int c = ln & 7, r8 = ln >> 3;
-                const unsigned char *base = smem + R_BASE + wave * 4096 + (c >> 1) * 1024 + (32 * (c & 1)) * 16;
-                const int rn = n0 + wn * WTN + (q % TN) * 32 + c * 4;
-#pragma unroll
-                for (int s4 = 0; s4 < 4; ++s4) {
-                    const int row = 8 * s4 + r8;
-                    const f32x4_t t = *reinterpret_cast<const f32x4_t *>(base + row * 16);
-                    const int rm = m0 + wm * WTM + (q / TN) * 32 + row;
-                    const int boff = (rm < M && rn < N) ? (int)(((int64_t)rm * P.ldo + rn) * 4) : (int)OOB;
-                    // (plain stores: non-temporal or write-through ones measured 10 - 30 % slower here)
-                    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, t), l_rsrc, boff, 0, 0);
-                }
-            }
-        };
-        issue_range(0, 0, 0, c0{}, cLPT{});
-        issue_range(1, 1, 1, c0{}, cALD{});           // the left operand of tile 1; its weights go out in iteration 0
-        wait_vmcnt<A_LD>();
-        __syncthreads();
-        read_frags(0, 0, 0, af0, wf0);
-        __builtin_amdgcn_sched_barrier(0);
-        {
-            // mode 0: plain; mode 1 (X): issues the B_in loads of sub-tile q; mode 2 (Y): adds sub-tile Q
-            auto iteration_wk = [&](int kt, auto mode_tag, int q, auto q_tag, auto wk) __attribute__((always_inline)) {
-                constexpr int MODE = decltype(mode_tag)::value;
-                const int cur = kt & 1, nxt = cur ^ 1;
-                phase(af0, wf0, true, cur, cur, 1, af1, wf1, kt + 1, 0, nxt, cALD{}, cLR{}, wk);
-                if constexpr (MODE == 1)
-                    phase_x(af1, wf1, cur, cur, 2, af0, wf0, q);
-                else
-                    phase(af1, wf1, true, cur, cur, 2, af0, wf0, 0, 0, 0, c0{}, c0{}, wk);
-                phase(af0, wf0, true, cur, cur, 3, af1, wf1, 0, 0, 0, c0{}, c0{}, wk);
-                if constexpr (MODE == 1)
-                    wait_vmcnt<4>();
-                else
-                    wait_vmcnt<0>();
-                __syncthreads();
-                if constexpr (MODE == 2)
-                    add_landed(q_tag);
-                __builtin_amdgcn_sched_barrier(0);
-                phase(af1, wf1, true, nxt, nxt, 0, af0, wf0, kt + 2, cur, 0, c0{}, cALD{}, wk);
-            };
-            auto iteration = [&](int kt, auto mode_tag, int q, auto q_tag) __attribute__((always_inline)) {
-                iteration_wk(kt, mode_tag, q, q_tag, std::true_type{});     // branch-free loads
-            };
-            using wk = std::true_type;                       // (the last tile requests nothing)
-            using m0_t = std::integral_constant<int, 0>;
-            using m1_t = std::integral_constant<int, 1>;
-            using m2_t = std::integral_constant<int, 2>;
-            int kt = 0;
-            const int untested = (tested > 0 && rot != 0) ? 0 : nk - 1 - tested;   // iterations with branch-free loads
-            const int first = streamed ? untested - 2 * RQ : untested;
-            for (; kt < first; ++kt)
-                iteration(kt, m0_t{}, 0, c0{});
-            if (streamed) {
-                auto pair_of = [&](auto q_tag) __attribute__((always_inline)) {
-                    iteration(kt, m1_t{}, decltype(q_tag)::value, c0{});
-                    iteration(kt + 1, m2_t{}, 0, q_tag);
-                    kt += 2;
-                };
-                static_assert(RQ == 8, "eight sub-tiles per wave");
-                pair_of(std::integral_constant<int, 0>{});
-                pair_of(std::integral_constant<int, 1>{});
-                pair_of(std::integral_constant<int, 2>{});
-                pair_of(std::integral_constant<int, 3>{});
-                pair_of(std::integral_constant<int, 4>{});
-                pair_of(std::integral_constant<int, 5>{});
-                pair_of(std::integral_constant<int, 6>{});
-                pair_of(std::integral_constant<int, 7>{});
-            }
-            for (; kt + 1 < nk; ++kt)                        // the iterations that request the ragged k-tile
-                iteration_wk(kt, m0_t{}, 0, c0{}, std::false_type{});
-            if (nk > 0) {                                    // last tile: nothing follows it
-                const int cur = (nk - 1) & 1;
-                phase(af0, wf0, true, cur, cur, 1, af1, wf1, 0, 0, 0, c0{}, c0{}, wk{});
-                phase(af1, wf1, true, cur, cur, 2, af0, wf0, 0, 0, 0, c0{}, c0{}, wk{});
-                phase(af0, wf0, true, cur, cur, 3, af1, wf1, 0, 0, 0, c0{}, c0{}, wk{});
-                phase(af1, wf1, false, 0, 0, 0, af0, wf0, 0, 0, 0, c0{}, c0{}, wk{});
-            }
-        }
-    } else if constexpr (SPREAD) {
+                          P.stream_recv && nk >= 2 * RQ + 2 + tested && (tested == 0 || rot == 0);
+    // the left-operand stage whose memory serves as the wave-private scratch of the epilogue's stores (and, RLDS, as
+    // the landing area of B_in before)
+    int land_stage = SPREAD ? NSA - 1 : 0;
+    if constexpr (SPREAD) {
         // The left-operand tile has NS+1 stages, the weight tile NS (tile t lives in stages t mod (NS+1) and
         // t mod NS).  Loads return in issue order, so what is issued first must be what is needed first:
         //   prologue: tiles 0 .. NS-1 whole, in tile order; tile 0 is awaited, its first fragments fetched
@@ -774,34 +628,38 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         // The steady state.  When K is a multiple of the k-tile every iteration is branch-free.  Otherwise (the
         // launcher then leaves the k order unrotated) the ragged k-tile is the last one of the range: the
         // iterations up to the one that requests it are branch-free too, and only the last NS ones test.
-        {
-            int cur_a = 0, cur_w = 0;                        // stages of tile kt
-            int prev_a = NSA - 1;                            // left-operand stage of tile kt-1 (= of tile kt+NS)
-            auto body = [&](int kt, int ca, int cw, int pa, int na, int nw_, auto wk) __attribute__((always_inline)) {
-                phase(af0, wf0, true, ca, cw, 1, af1, wf1, kt + NS, pa, 0, c0{}, cALD{}, wk);
-                phase(af1, wf1, true, ca, cw, 2, af0, wf0, 0, 0, 0, c0{}, c0{}, wk);
-                phase(af0, wf0, true, ca, cw, 3, af1, wf1, 0, 0, 0, c0{}, c0{}, wk);
-                if (CARRY_A && kt == carry_at) {         // tile kt goes on to the landing buffer: its stores are the
-                    carry_tile(kt, ca);                  // youngest requests and need not be awaited here
-                    wait_vmcnt<(NS - 2) * LPT + 2 * A_LD>();
-                } else {
-                    wait_vmcnt<(NS - 2) * LPT + A_LD>();
-                }
-                __syncthreads();
-                __builtin_amdgcn_sched_barrier(0);
-                phase(af1, wf1, true, na, nw_, 0, af0, wf0, kt + NS, 0, cw, cALD{}, cLR{}, wk);
-            };
-            // first iteration that tests its loads (all of them when K is a multiple of the k-tile: none does)
-            const int tested = K % BK == 0 ? nk - 1 : ((rot == 0 && nk - 1 > NS) ? nk - 1 - NS : 0);
-            int kt = 0;
-            for (; kt < tested; ++kt) {
-                const int nxt_a = (cur_a + 1 == NSA) ? 0 : cur_a + 1;
-                const int nxt_w = (cur_w + 1 == NS) ? 0 : cur_w + 1;
-                body(kt, cur_a, cur_w, prev_a, nxt_a, nxt_w, std::true_type{});
-                prev_a = cur_a;
-                cur_a = nxt_a;
-                cur_w = nxt_w;
+        int cur_a = 0, cur_w = 0;                        // stages of tile kt
+        int prev_a = NSA - 1;                            // left-operand stage of tile kt-1 (= of tile kt+NS)
+        auto body = [&](int kt, int ca, int cw, int pa, int na, int nw_, auto wk) __attribute__((always_inline)) {
+            phase(af0, wf0, true, ca, cw, 1, af1, wf1, kt + NS, pa, 0, c0{}, cALD{}, wk);
+            phase(af1, wf1, true, ca, cw, 2, af0, wf0, 0, 0, 0, c0{}, c0{}, wk);
+            phase(af0, wf0, true, ca, cw, 3, af1, wf1, 0, 0, 0, c0{}, c0{}, wk);
+            if (CARRY_A && kt == carry_at) {         // tile kt goes on to the landing buffer: its stores are the
+                carry_tile(kt, ca);                  // youngest requests and need not be awaited here
+                wait_vmcnt<(NS - 2) * LPT + 2 * A_LD>();
+            } else {
+                wait_vmcnt<(NS - 2) * LPT + A_LD>();
             }
+            __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+            phase(af1, wf1, true, na, nw_, 0, af0, wf0, kt + NS, 0, cw, cALD{}, cLR{}, wk);
+        };
+        // first iteration that tests its loads (all of them when K is a multiple of the k-tile: none does)
+        const int tested_at = K % BK == 0 ? nk - 1 : ((rot == 0 && nk - 1 > NS) ? nk - 1 - NS : 0);
+        // RLDS, a work item that streams B_in: the three-stage schedule runs up to the k-tile before the sixteen
+        // streamed ones, the two-stage schedule with the landing area (below) takes over there
+        const int change_at = nk - 1 - tested - 2 * RQ - 1;
+        const int plain_end = (RLDS && streamed) ? change_at : tested_at;
+        int kt = 0;
+        for (; kt < plain_end; ++kt) {
+            const int nxt_a = (cur_a + 1 == NSA) ? 0 : cur_a + 1;
+            const int nxt_w = (cur_w + 1 == NS) ? 0 : cur_w + 1;
+            body(kt, cur_a, cur_w, prev_a, nxt_a, nxt_w, std::true_type{});
+            prev_a = cur_a;
+            cur_a = nxt_a;
+            cur_w = nxt_w;
+        }
+        if (!(RLDS && streamed)) {
             for (; kt + 1 < nk; ++kt) {
                 const int nxt_a = (cur_a + 1 == NSA) ? 0 : cur_a + 1;
                 const int nxt_w = (cur_w + 1 == NS) ? 0 : cur_w + 1;
@@ -820,7 +678,153 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 phase(af1, wf1, false, 0, 0, 0, af0, wf0, 0, 0, 0, c0{}, c0{}, wk{});
             }
         }
-
+        if constexpr (RLDS) {
+          if (streamed) {
+            // The streamed part: two stages of both operands and the landing area.  On entry (kt = change_at) tile
+            // kt is complete and all of tile kt+1 is in flight; the left-operand tiles kt and kt+1 keep their
+            // stages, later ones alternate between the two, and the third stage -- tile kt-1 has been read by all
+            // -- becomes the landing area, 4 KiB per wave.  Weight tile t stays in stage t & 1.  Iteration kt:
+            //     slice 0: + the weight loads of tile kt+1 (its stage was vacated at the barrier of iteration kt-1;
+            //              not in the first iteration, where they are in flight already)
+            //     slice 1 (X iterations: + the four B_in loads of one sub-tile), slice 2
+            //     wait: tile kt+1 complete (X: the B_in loads just issued may still be in flight); barrier
+            //     (Y iterations: the sub-tile is read from the landing area and added to its accumulators)
+            //     slice 3: + the left-operand loads of tile kt+2, into the stage tile kt vacated
+            // Loads return in issue order: the B_in loads of an X iteration are behind the weight loads of tile
+            // kt+1 and ahead of everything tile kt+2 needs, so they have until the wait of the following (Y)
+            // iteration, one and a half k-tiles of MFMA time, to arrive.  Each wave reads back only what it
+            // loaded itself, so its own vmcnt wait is all the ordering the landing area needs.
+            static_assert(A_LD <= NSEG && B_LD <= NSEG && NSEG == 4 && NS == 2, "one load slot per MFMA segment");
+            const int nxt_a0 = (cur_a + 1 == NSA) ? 0 : cur_a + 1;
+            const int a_of_parity[2] = {(kt & 1) ? nxt_a0 : cur_a, (kt & 1) ? cur_a : nxt_a0};
+            land_stage = prev_a;                         // (the stage of tile kt-1; kt >= 1 here)
+            const int a_ev = a_of_parity[0], a_od = a_of_parity[1];
+            const i32x4_t rr = make_rsrc(cRecv, r_bytes_of_recv);
+            __amdgpu_buffer_rsrc_t l_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                static_cast<float *>(cLand), 0, cLand != nullptr ? (int)r_bytes_of_recv : 0, 0x00020000);
+            const int land_off = land_stage * A_BYTES + wave * 4096;
+            const unsigned r_lds = lds_base + land_off;
+            // byte offset of sub-tile q = (i, j) of this wave, row 0 / column 0 of the lane pattern
+            auto r_soff = [&](int q) __attribute__((always_inline)) {
+                const int i = q / TN, j = q % TN;
+                return (int)((((int64_t)(m0 + wm * WTM + i * 32)) * P.ldo + n0 + wn * WTN + j * 32) * 4);
+            };
+            auto phase_x = [&](const bf16x8_t (&afc)[TM], const bf16x8_t (&wfc)[TN], int sa_n, int sw_n, int ks_n,
+                               bf16x8_t (&afn)[TM], bf16x8_t (&wfn)[TN], int q) __attribute__((always_inline)) {
+                const int so = r_soff(q);
+                // a lane outside the matrix must not touch memory: the scalar part of the address is not covered
+                // by the buffer's range check, so such a lane is given the out-of-range offset itself
+                // (computed from an opaque copy of the lane index: otherwise the offsets of all eight sub-tiles are
+                // hoisted out of the k loop and held in registers the main loop does not have)
+                int ln = lane;
+                asm volatile("" : "+v"(ln));
+                const int rm = m0 + wm * WTM + (q / TN) * 32 + (ln & 31);
+                const int rn = n0 + wn * WTN + (q % TN) * 32 + (ln >> 5) * 4;
+                const unsigned rv = (unsigned)((((int64_t)(ln & 31)) * P.ldo + (ln >> 5) * 4) * 4);
+                const unsigned v0 = (rm < M && rn < N) ? rv : OOB, v1 = (rm < M && rn + 8 < N) ? rv : OOB;
+                const unsigned v2 = (rm < M && rn + 16 < N) ? rv : OOB, v3 = (rm < M && rn + 24 < N) ? rv : OOB;
+                read_frags(sa_n, sw_n, ks_n, afn, wfn);
+                mfma_seg(afc, wfc, std::integral_constant<int, 0>{});
+                interleave_mfma_reads<NREAD, (NREAD + MPS - 1) / MPS>();
+                __builtin_amdgcn_sched_barrier(0);
+                direct_load_16(rr, v0, so, r_lds);
+                mfma_seg(afc, wfc, std::integral_constant<int, 1>{});
+                __builtin_amdgcn_sched_barrier(0);
+                direct_load_16(rr, v1, so + 32, r_lds + 1024);
+                mfma_seg(afc, wfc, std::integral_constant<int, 2>{});
+                __builtin_amdgcn_sched_barrier(0);
+                direct_load_16(rr, v2, so + 64, r_lds + 2048);
+                mfma_seg(afc, wfc, std::integral_constant<int, 3>{});
+                __builtin_amdgcn_sched_barrier(0);
+                direct_load_16(rr, v3, so + 96, r_lds + 3072);
+            };
+            auto add_landed = [&](auto q_tag) __attribute__((always_inline)) {          // "O <- B_in + O" for sub-tile q, in mid-sum
+                constexpr int q = decltype(q_tag)::value;
+                int ln = lane;
+                asm volatile("" : "+v"(ln));
+                const unsigned char *src = smem + land_off + ln * 16;
+                f32x4_t v[4];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    v[g] = *reinterpret_cast<const f32x4_t *>(src + g * 1024);
+                    acc[q / TN][q % TN][4 * g + 0] += v[g][0];
+                    acc[q / TN][q % TN][4 * g + 1] += v[g][1];
+                    acc[q / TN][q % TN][4 * g + 2] += v[g][2];
+                    acc[q / TN][q % TN][4 * g + 3] += v[g][3];
+                }
+                // the delivery carried by the consumer: what just arrived from the neighbour's buffer is also stored to
+                // this rank's landing buffer (a lane outside the matrix is given the out-of-range offset: store dropped)
+                if (cLand != nullptr) {
+                    // Whole 128-byte lines per store: the sub-tile is read from the landing area a second time, eight
+                    // lanes to a row (chunk c of row r lies in plane c / 2 at lane slot r + 32 (c & 1)), so that one
+                    // store instruction writes eight full rows instead of 32-byte pieces of thirty-two.
+                    const int c = ln & 7, r8 = ln >> 3;
+                    const unsigned char *base = smem + land_off + (c >> 1) * 1024 + (32 * (c & 1)) * 16;
+                    const int rn = n0 + wn * WTN + (q % TN) * 32 + c * 4;
+#pragma unroll
+                    for (int s4 = 0; s4 < 4; ++s4) {
+                        const int row = 8 * s4 + r8;
+                        const f32x4_t t = *reinterpret_cast<const f32x4_t *>(base + row * 16);
+                        const int rm = m0 + wm * WTM + (q / TN) * 32 + row;
+                        const int boff = (rm < M && rn < N) ? (int)(((int64_t)rm * P.ldo + rn) * 4) : (int)OOB;
+                        // (plain stores: non-temporal or write-through ones measured 10 - 30 % slower here)
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, t), l_rsrc, boff, 0, 0);
+                    }
+                }
+            };
+            // mode 0: plain; mode 1 (X): issues the B_in loads of sub-tile q; mode 2 (Y): adds sub-tile Q.
+            // n_w: the number of weight loads slice 0 issues (none in the iteration that takes over)
+            auto iteration_wk = [&](int kt_, auto mode_tag, int q, auto q_tag, auto wk, auto n_w) __attribute__((always_inline)) {
+                constexpr int MODE = decltype(mode_tag)::value;
+                const int cw = kt_ & 1, nw_ = cw ^ 1;
+                const int ca = cw ? a_od : a_ev, na = cw ? a_ev : a_od;
+                phase(af0, wf0, true, ca, cw, 1, af1, wf1, kt_ + 1, 0, nw_, cALD{}, n_w, wk);
+                if constexpr (MODE == 1)
+                    phase_x(af1, wf1, ca, cw, 2, af0, wf0, q);
+                else
+                    phase(af1, wf1, true, ca, cw, 2, af0, wf0, 0, 0, 0, c0{}, c0{}, wk);
+                phase(af0, wf0, true, ca, cw, 3, af1, wf1, 0, 0, 0, c0{}, c0{}, wk);
+                if constexpr (MODE == 1)
+                    wait_vmcnt<4>();
+                else
+                    wait_vmcnt<0>();
+                __syncthreads();
+                if constexpr (MODE == 2)
+                    add_landed(q_tag);
+                __builtin_amdgcn_sched_barrier(0);
+                phase(af1, wf1, true, na, nw_, 0, af0, wf0, kt_ + 2, ca, 0, c0{}, cALD{}, wk);
+            };
+            using m0_t = std::integral_constant<int, 0>;
+            using m1_t = std::integral_constant<int, 1>;
+            using m2_t = std::integral_constant<int, 2>;
+            iteration_wk(kt, m0_t{}, 0, c0{}, std::true_type{}, c0{});       // the iteration that takes over
+            ++kt;
+            auto pair_of = [&](auto q_tag) __attribute__((always_inline)) {
+                iteration_wk(kt, m1_t{}, decltype(q_tag)::value, c0{}, std::true_type{}, cLR{});
+                iteration_wk(kt + 1, m2_t{}, 0, q_tag, std::true_type{}, cLR{});
+                kt += 2;
+            };
+            static_assert(RQ == 8, "eight sub-tiles per wave");
+            pair_of(std::integral_constant<int, 0>{});
+            pair_of(std::integral_constant<int, 1>{});
+            pair_of(std::integral_constant<int, 2>{});
+            pair_of(std::integral_constant<int, 3>{});
+            pair_of(std::integral_constant<int, 4>{});
+            pair_of(std::integral_constant<int, 5>{});
+            pair_of(std::integral_constant<int, 6>{});
+            pair_of(std::integral_constant<int, 7>{});
+            for (; kt + 1 < nk; ++kt)                        // the iterations that request the ragged k-tile
+                iteration_wk(kt, m0_t{}, 0, c0{}, std::false_type{}, cLR{});
+            {                                                // last tile: nothing follows it
+                using wk = std::true_type;
+                const int cw = (nk - 1) & 1, ca = cw ? a_od : a_ev;
+                phase(af0, wf0, true, ca, cw, 1, af1, wf1, 0, 0, 0, c0{}, c0{}, wk{});
+                phase(af1, wf1, true, ca, cw, 2, af0, wf0, 0, 0, 0, c0{}, c0{}, wk{});
+                phase(af0, wf0, true, ca, cw, 3, af1, wf1, 0, 0, 0, c0{}, c0{}, wk{});
+                phase(af1, wf1, false, 0, 0, 0, af0, wf0, 0, 0, 0, c0{}, c0{}, wk{});
+            }
+          }
+        }
     } else {
         // Variant for the small tiles (few MFMAs per slice): a tile's loads go out together right
         // after the barrier that frees their stage, and the LDS reads of the next slice are
@@ -956,8 +960,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // Epilogue.  Accumulator register 4g+e of lane L holds row (L & 31), column 8g + 4(L >> 5) + e
     // of its 32x32 tile.  Bounds-checked buffer accesses: a lane outside the matrix reads zero
     // and its store is dropped.
-    if constexpr (!RLDS)
-        __syncthreads();                             // the stores' scratch lies in the stages: all waves are done with them
+    if (!(RLDS && streamed))
+        __syncthreads();                             // the stores' scratch lies in a stage: all waves are done with them
     constexpr unsigned o_elem = OUT_BF16 ? 2 : 4;
     const unsigned o_bytes = (unsigned)(((int64_t)(M - 1) * P.ldo + N) * o_elem);
     __amdgpu_buffer_rsrc_t o_rsrc = __builtin_amdgcn_make_buffer_rsrc(cOut, 0, (int)o_bytes, 0x00020000);
@@ -1018,10 +1022,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                         rv[j][g] = rv[j][g] + tv[j][g];
             }
         }
-        // The stores go through a wave-private LDS scratch (E_SCR) so that they leave as whole 128-byte lines: the
+        // The stores go through a wave-private LDS scratch so that they leave as whole 128-byte lines: the
         // accumulator layout would store 32-byte (bf16: 16-byte) pieces of thirty-two rows per instruction, which
         // the memory system handles markedly worse (measured: 70B down-projection rank step 438 -> 418 us).
-        unsigned char *const scr = smem + E_SCR + wave * E_SCR_BYTES;
+        unsigned char *const scr = smem + land_stage * A_BYTES + wave * E_SCR_BYTES;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
 #pragma unroll
@@ -1034,14 +1038,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 if (has_recv && !streamed)
                     o = rv[j][g] + o;                                    // "O <- B_in + O"
                 if constexpr (OUT_BF16) {
-                    // row (lane & 31) of the wave tile's row block i: 64-column rows of bf16 (128 bytes), padded
-                    // to 144 so that the rows spread over the banks
+                    // row (lane & 31) of the wave tile's row block i: 64-column rows of bf16 (128 bytes), their
+                    // eight 16-byte chunks XOR-ed with the row so that the rows spread over the banks
                     bf16x4_t h;
                     h[0] = static_cast<__bf16>(o[0]);
                     h[1] = static_cast<__bf16>(o[1]);
                     h[2] = static_cast<__bf16>(o[2]);
                     h[3] = static_cast<__bf16>(o[3]);
-                    *reinterpret_cast<bf16x4_t *>(scr + (lane & 31) * 144 + j * 64 + g * 16 + (lane >> 5) * 8) = h;
+                    *reinterpret_cast<bf16x4_t *>(scr + (lane & 31) * 128 + (((j * 4 + g) ^ (lane & 7)) << 4) + (lane >> 5) * 8) = h;
                 } else {
                     // plane g of the 32x32 sub-tile (i, j) at the lane's slot
                     *reinterpret_cast<f32x4_t *>(scr + g * 1024 + lane * 16) = o;
@@ -1069,7 +1073,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
 #pragma unroll
             for (int s4 = 0; s4 < 4; ++s4) {
                 const int row = 8 * s4 + r8;
-                const u32x4_t t = *reinterpret_cast<const u32x4_t *>(scr + row * 144 + c * 16);
+                const u32x4_t t = *reinterpret_cast<const u32x4_t *>(scr + row * 128 + ((c ^ (row & 7)) << 4));
                 const int sm = m0 + wm * WTM + i * 32 + row;
                 const int so = (sm < M && sn < N) ? (int)(((int64_t)sm * P.ldo + sn) * 2) : (int)OOB;
                 __builtin_amdgcn_raw_buffer_store_b128(t, o_rsrc, so, 0, 0);
@@ -1096,7 +1100,7 @@ hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t
         any_flag = any_flag || p.flag_step[j] != nullptr;
     const int nk_all = (p.K + BK - 1) / BK;
     [[maybe_unused]] const bool rlds = SPREAD && NS == 2 && any_recv && !out_bf16 && !p.a_t && p.stream_recv && !any_flag &&
-                                       p.n_recv_more == 0 && p.splits == 1 && nk_all >= 17 + (p.K % BK != 0 ? 2 : 0);
+                                       p.n_recv_more == 0 && p.splits == 1 && nk_all >= 18 + (p.K % BK != 0 ? 2 : 0);
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     int wgs = tiles_m * tiles_n * p.splits + p.cp_wgs;
     if (p.n_steps > 0) {                             // persistent: a grid that fills the chip once
@@ -1183,7 +1187,7 @@ bool gemm_bf16_dl_streams_recv(const GemmParams &p, bool w_kn, bool out_bf16, Ti
     (void)w_kn;
     const int nk_all = (p.K + BK - 1) / BK;
     return p.n_steps > 0 && t.bm == 256 && t.bn == 256 && !out_bf16 && !p.a_t && tuning().stream_recv != 0 &&
-           p.n_recv_more == 0 && nk_all >= 17 + (p.K % BK != 0 ? 2 : 0);
+           p.n_recv_more == 0 && nk_all >= 18 + (p.K % BK != 0 ? 2 : 0);
 }
 
 // Can a persistent all-gather launch carry its deliveries (GemmParams::land_step with steps that add nothing)?  Every
