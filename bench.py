@@ -49,6 +49,9 @@ def main() -> int:
                     "(7b, pairwise, granularity, backward, attention, dp); default: all.  With --skip-pair the headline "
                     "workload is left out and the JSON line carries only what was measured (profiling runs)")
     ap.add_argument("--skip-pair", action="store_true", help="leave the headline workload out (profiling runs of one section)")
+    ap.add_argument("--skip-kernel-probe", action="store_true",
+                    help="do not time the dominant kernel alone (profiling runs of one schedule mode: the probe launches the "
+                         "same kernel without its deliveries); the line then carries no roofline")
     ap.add_argument("--modes", default="", help="comma-separated subset of the schedule modes to time (default: all)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (known bytes, for scaling hardware counters)")
@@ -216,29 +219,30 @@ def main() -> int:
         # dominant kernel: the down-projection rank-step kernel (one persistent launch = the eight chunk GEMMs
         # of the rank step with their B_in adds and B_out / O stores), launched alone: CF_NO_COPY enqueues nothing else
         PS = cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_NO_COPY
-        t_kernel = time_calls(lambda: cf.run_schedule(rs.desc, cf.CF_KIND_RS, rs.bufs, rs.cs, rs.xs, PS), ag.cs, max(K, 50), W)
-        ach = dn.flops / (t_kernel * 1e-3) / 1e12
-        t_kernel_up = time_calls(lambda: cf.run_schedule(ag.desc, cf.CF_KIND_AG, ag.bufs, ag.cs, ag.xs, PS), ag.cs, max(K, 50), W)
-        # the same GEMMs as one kernel per step (what every mode but "persistent" launches), step 1 alone
-        t_chunk = time_calls(lambda: cf.rs_step(rs.desc, 1, rs.A, rs.W, rs.stage[0], rs.send[0], ag.cs), ag.cs, max(K, 50), W)
-        t_chunk_up = time_calls(lambda: cf.ag_step(ag.desc, 1, ag.stage[0], ag.W, ag.O, ag.cs), ag.cs, max(K, 50), W)
-        chunk_flops = 2.0 * dn.m_chunk * dn.n * dn.k
-        roofline = {"bound": "mfma",
-                    "kernel": "gemm_bf16_dl_kernel<256,256,...,persistent,B_in through LDS> (down-projection rank step: 8 chunk GEMMs, "
-                              "fused B_in adds, every step's B_out stored)",
-                    "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(ach / PEAK_BF16_TFLOPS, 4),
-                    # bytes through the L2s' memory side per launch from rocprofv3 counters: FETCH_SIZE x 2.00 (scale
-                    # from a plain 256 MiB copy) + WRITE_SIZE; algorithmic bytes: A 58.7 + W 58.7 + B_in 7 x 33.55 +
-                    # B_out/O 8 x 33.55 MB
-                    "traffic": TRAFFIC_DOWN_RANK_STEP, "traffic_source": TRAFFIC_SOURCE, "algorithmic_bytes": 620.7e6,
-                    "us_per_launch": round(t_kernel * 1e3, 2),
-                    "up_projection_rank_step_kernel": {"us_per_launch": round(t_kernel_up * 1e3, 2),
-                                                       "tflops": round(up.flops / (t_kernel_up * 1e-3) / 1e12, 1)},
-                    "one_kernel_per_step": {"down_us": round(t_chunk * 1e3, 2), "down_tflops": round(chunk_flops / (t_chunk * 1e-3) / 1e12, 1),
-                                            "up_us": round(t_chunk_up * 1e3, 2), "up_tflops": round(chunk_flops / (t_chunk_up * 1e-3) / 1e12, 1)}}
-        log(f"rank-step kernel down {t_kernel*1e3:.1f} us = {ach:.0f} TFLOP/s, up {t_kernel_up*1e3:.1f} us; "
-            f"chunk GEMM down {t_chunk*1e3:.1f} us, up {t_chunk_up*1e3:.1f} us")
+        if not args.skip_kernel_probe:
+            t_kernel = time_calls(lambda: cf.run_schedule(rs.desc, cf.CF_KIND_RS, rs.bufs, rs.cs, rs.xs, PS), ag.cs, max(K, 50), W)
+            ach = dn.flops / (t_kernel * 1e-3) / 1e12
+            t_kernel_up = time_calls(lambda: cf.run_schedule(ag.desc, cf.CF_KIND_AG, ag.bufs, ag.cs, ag.xs, PS), ag.cs, max(K, 50), W)
+            # the same GEMMs as one kernel per step (what every mode but "persistent" launches), step 1 alone
+            t_chunk = time_calls(lambda: cf.rs_step(rs.desc, 1, rs.A, rs.W, rs.stage[0], rs.send[0], ag.cs), ag.cs, max(K, 50), W)
+            t_chunk_up = time_calls(lambda: cf.ag_step(ag.desc, 1, ag.stage[0], ag.W, ag.O, ag.cs), ag.cs, max(K, 50), W)
+            chunk_flops = 2.0 * dn.m_chunk * dn.n * dn.k
+            roofline = {"bound": "mfma",
+                        "kernel": "gemm_bf16_dl_kernel<256,256,...,persistent,B_in through LDS> (down-projection rank step: 8 chunk GEMMs, "
+                                  "fused B_in adds, every step's B_out stored)",
+                        "achieved": round(ach, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                        # bytes through the L2s' memory side per launch from rocprofv3 counters: FETCH_SIZE x 2.00 (scale
+                        # from a plain 256 MiB copy) + WRITE_SIZE; algorithmic bytes: A 58.7 + W 58.7 + B_in 7 x 33.55 +
+                        # B_out/O 8 x 33.55 MB
+                        "traffic": TRAFFIC_DOWN_RANK_STEP, "traffic_source": TRAFFIC_SOURCE, "algorithmic_bytes": 620.7e6,
+                        "us_per_launch": round(t_kernel * 1e3, 2),
+                        "up_projection_rank_step_kernel": {"us_per_launch": round(t_kernel_up * 1e3, 2),
+                                                           "tflops": round(up.flops / (t_kernel_up * 1e-3) / 1e12, 1)},
+                        "one_kernel_per_step": {"down_us": round(t_chunk * 1e3, 2), "down_tflops": round(chunk_flops / (t_chunk * 1e-3) / 1e12, 1),
+                                                "up_us": round(t_chunk_up * 1e3, 2), "up_tflops": round(chunk_flops / (t_chunk_up * 1e-3) / 1e12, 1)}}
+            log(f"rank-step kernel down {t_kernel*1e3:.1f} us = {ach:.0f} TFLOP/s, up {t_kernel_up*1e3:.1f} us; "
+                f"chunk GEMM down {t_chunk*1e3:.1f} us, up {t_chunk_up*1e3:.1f} us")
         # comparator, same kernels: the layer pair WITHOUT the fusion ("vanilla": the collective, then / after the whole GEMM).
         # up: all-gather first, then the GEMM over all 8192 rows -- which is what the persistent arrangement does anyway;
         # down: the GEMM over all 8192 rows into a full fp32 partial (the same persistent kernel, no B_in adds), then the

@@ -711,18 +711,25 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             };
             auto phase_x = [&](const bf16x8_t (&afc)[TM], const bf16x8_t (&wfc)[TN], int sa_n, int sw_n, int ks_n,
                                bf16x8_t (&afn)[TM], bf16x8_t (&wfn)[TN], int q) __attribute__((always_inline)) {
-                const int so = r_soff(q);
+                const int so = __builtin_amdgcn_readfirstlane(r_soff(q));     // (uniform; kept in a scalar register)
                 // a lane outside the matrix must not touch memory: the scalar part of the address is not covered
                 // by the buffer's range check, so such a lane is given the out-of-range offset itself
                 // (computed from an opaque copy of the lane index: otherwise the offsets of all eight sub-tiles are
                 // hoisted out of the k loop and held in registers the main loop does not have)
                 int ln = lane;
                 asm volatile("" : "+v"(ln));
-                const int rm = m0 + wm * WTM + (q / TN) * 32 + (ln & 31);
-                const int rn = n0 + wn * WTN + (q % TN) * 32 + (ln >> 5) * 4;
-                const unsigned rv = (unsigned)((((int64_t)(ln & 31)) * P.ldo + (ln >> 5) * 4) * 4);
-                const unsigned v0 = (rm < M && rn < N) ? rv : OOB, v1 = (rm < M && rn + 8 < N) ? rv : OOB;
-                const unsigned v2 = (rm < M && rn + 16 < N) ? rv : OOB, v3 = (rm < M && rn + 24 < N) ? rv : OOB;
+                // Plane g of the landing area (load g: columns 8g + 4 (lane >> 5) .. + 3) holds its rows permuted:
+                // the lane fetches row (lane & 31) ^ (2g + (lane >> 5)), so that the eight 16-byte chunks of a row,
+                // which lie 512 bytes apart across the planes, fall into different banks when the rows are read
+                // back eight lanes to a row.
+                const int half = ln >> 5;
+                const int rn = n0 + wn * WTN + (q % TN) * 32 + half * 4;
+                auto off_of = [&](int g) __attribute__((always_inline)) {
+                    const int r = (ln & 31) ^ (2 * g + half);
+                    const int rm = m0 + wm * WTM + (q / TN) * 32 + r;
+                    return (rm < M && rn + 8 * g < N) ? (unsigned)((((int64_t)r) * P.ldo + half * 4) * 4) : OOB;
+                };
+                const unsigned v0 = off_of(0), v1 = off_of(1), v2 = off_of(2), v3 = off_of(3);
                 read_frags(sa_n, sw_n, ks_n, afn, wfn);
                 mfma_seg(afc, wfc, std::integral_constant<int, 0>{});
                 interleave_mfma_reads<NREAD, (NREAD + MPS - 1) / MPS>();
@@ -742,11 +749,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 constexpr int q = decltype(q_tag)::value;
                 int ln = lane;
                 asm volatile("" : "+v"(ln));
-                const unsigned char *src = smem + land_off + ln * 16;
+                const unsigned char *src = smem + land_off + (ln & 32) * 16;
                 f32x4_t v[4];
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    v[g] = *reinterpret_cast<const f32x4_t *>(src + g * 1024);
+                    v[g] = *reinterpret_cast<const f32x4_t *>(src + g * 1024 + (((ln & 31) ^ (2 * g + (ln >> 5))) << 4));
                     acc[q / TN][q % TN][4 * g + 0] += v[g][0];
                     acc[q / TN][q % TN][4 * g + 1] += v[g][1];
                     acc[q / TN][q % TN][4 * g + 2] += v[g][2];
@@ -756,15 +763,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 // this rank's landing buffer (a lane outside the matrix is given the out-of-range offset: store dropped)
                 if (cLand != nullptr) {
                     // Whole 128-byte lines per store: the sub-tile is read from the landing area a second time, eight
-                    // lanes to a row (chunk c of row r lies in plane c / 2 at lane slot r + 32 (c & 1)), so that one
-                    // store instruction writes eight full rows instead of 32-byte pieces of thirty-two.
+                    // lanes to a row (chunk c of row r lies in plane c / 2 at lane slot (r ^ c) + 32 (c & 1)), so that
+                    // one store instruction writes eight full rows instead of 32-byte pieces of thirty-two.
                     const int c = ln & 7, r8 = ln >> 3;
                     const unsigned char *base = smem + land_off + (c >> 1) * 1024 + (32 * (c & 1)) * 16;
                     const int rn = n0 + wn * WTN + (q % TN) * 32 + c * 4;
 #pragma unroll
                     for (int s4 = 0; s4 < 4; ++s4) {
                         const int row = 8 * s4 + r8;
-                        const f32x4_t t = *reinterpret_cast<const f32x4_t *>(base + row * 16);
+                        const f32x4_t t = *reinterpret_cast<const f32x4_t *>(base + ((row ^ c) << 4));
                         const int rm = m0 + wm * WTM + (q / TN) * 32 + row;
                         const int boff = (rm < M && rn < N) ? (int)(((int64_t)rm * P.ldo + rn) * 4) : (int)OOB;
                         // (plain stores: non-temporal or write-through ones measured 10 - 30 % slower here)
@@ -1047,19 +1054,20 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                     h[3] = static_cast<__bf16>(o[3]);
                     *reinterpret_cast<bf16x4_t *>(scr + (lane & 31) * 128 + (((j * 4 + g) ^ (lane & 7)) << 4) + (lane >> 5) * 8) = h;
                 } else {
-                    // plane g of the 32x32 sub-tile (i, j) at the lane's slot
-                    *reinterpret_cast<f32x4_t *>(scr + g * 1024 + lane * 16) = o;
+                    // plane g of the 32x32 sub-tile (i, j), the rows permuted within the plane (row ^ chunk number:
+                    // the chunks of a row lie 512 bytes apart and would all fall into one bank otherwise)
+                    *reinterpret_cast<f32x4_t *>(scr + g * 1024 + (((lane & 32) | ((lane & 31) ^ (2 * g + (lane >> 5)))) << 4)) = o;
                 }
             }
             if constexpr (!OUT_BF16) {
-                // read back eight lanes to a row: chunk c of row r lies in plane c / 2 at lane slot r + 32 (c & 1)
+                // read back eight lanes to a row: chunk c of row r lies in plane c / 2 at lane slot (r ^ c) + 32 (c & 1)
                 const int c = lane & 7, r8 = lane >> 3;
                 const unsigned char *base = scr + (c >> 1) * 1024 + (32 * (c & 1)) * 16;
                 const int sn = n0 + wn * WTN + j * 32 + c * 4;
 #pragma unroll
                 for (int s4 = 0; s4 < 4; ++s4) {
                     const int row = 8 * s4 + r8;
-                    const f32x4_t t = *reinterpret_cast<const f32x4_t *>(base + row * 16);
+                    const f32x4_t t = *reinterpret_cast<const f32x4_t *>(base + ((row ^ c) << 4));
                     const int sm = m0 + wm * WTM + i * 32 + row;
                     const int so = (sm < M && sn < N) ? (int)(((int64_t)sm * P.ldo + sn) * 4) : (int)OOB;
                     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, t), o_rsrc, so, 0, 0);
