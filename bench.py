@@ -29,7 +29,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 SETTLE_S = 0.06               # untimed load before every timed region (see time_calls)
 # HBM-side bytes per launch of the dominant kernel from rocprofv3 counters (FETCH_SIZE x 2.00 + WRITE_SIZE): a constant
 # taken from TRAFFIC_SOURCE, not measured in this run -- to be re-derived there whenever that kernel changes
-TRAFFIC_DOWN_RANK_STEP = 1332.8e6
+TRAFFIC_DOWN_RANK_STEP = 1218.8e6
 TRAFFIC_SOURCE = "profiles/gemm_bf16_dl_kernel_70b_pair_counters.md"
 
 
@@ -46,13 +46,16 @@ def main() -> int:
     ap.add_argument("--skip-cpu", action="store_true", help="leave out the CPU-oracle baseline")
     ap.add_argument("--only-pair", action="store_true", help="time the headline workload only")
     ap.add_argument("--sections", default="", help="comma-separated subset of the secondary measurements to run "
-                    "(7b, pairwise, granularity, backward, attention, dp); default: all.  With --skip-pair the headline "
+                    "(7b, pairwise, granularity, backward, attention, dp; and, on request only, power); default: all.  With --skip-pair the headline "
                     "workload is left out and the JSON line carries only what was measured (profiling runs)")
     ap.add_argument("--skip-pair", action="store_true", help="leave the headline workload out (profiling runs of one section)")
     ap.add_argument("--skip-kernel-probe", action="store_true",
                     help="do not time the dominant kernel alone (profiling runs of one schedule mode: the probe launches the "
                          "same kernel without its deliveries); the line then carries no roofline")
     ap.add_argument("--modes", default="", help="comma-separated subset of the schedule modes to time (default: all)")
+    ap.add_argument("--power-data", default="both", choices=("random", "zero", "both"),
+                    help="operands of the section 'power' (--sections power: the up-projection kernel on random and on "
+                         "all-zero operands, and on grids capped below the chip)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (known bytes, for scaling hardware counters)")
     args = ap.parse_args()
@@ -69,10 +72,14 @@ def main() -> int:
     from paper_2604_24013_amd import emulated_rank as H
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if "power" in args.sections.split(","):          # that probe switches a tuning override between its launches
+        os.environ["COMMFUSE_TUNING_LIVE"] = "1"
     cf.load()
     K, W = args.steps, args.warmup
     ALL_SECTIONS = ("7b", "pairwise", "granularity", "backward", "attention", "dp")
     sections = set(args.sections.split(",")) if args.sections else set(ALL_SECTIONS)
+    power_probe = "power" in sections                # on request only: not one of the default sections
+    sections.discard("power")
     if args.only_pair:
         sections = set()
     if args.skip_dp:
@@ -487,6 +494,44 @@ def main() -> int:
         del run, pers
         torch.cuda.empty_cache()
 
+    # ---------------- what bounds the main loop: the up-projection rank-step kernel under less electrical load ----------------
+    # The same launch (same instructions, same memory traffic) on operands that are all zero toggles far fewer wires in
+    # the matrix pipe; a grid capped below the chip leaves compute units idle.  If the launch were bound by its
+    # instruction schedule or by memory, neither would change the time per unit of work.
+    power = None
+    if power_probe:
+        up_w = inputs.CONFIGS["c4_ag_70b_up"]
+        PSK = cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_NO_COPY
+        d_up = H.desc_of(up_w, 0)
+        mk = lambda *shape: torch.randn(shape, dtype=torch.float32, device=H.DEV).to(torch.bfloat16)
+        Xp = mk(up_w.m_chunk, up_w.k)
+        each_p = [mk(up_w.m_chunk, up_w.k) for _ in range(up_w.p - 1)]
+        slot_p = [torch.empty((up_w.m_chunk, up_w.k), dtype=torch.bfloat16, device=H.DEV) for _ in range(2)]
+        Wp = mk(up_w.k, up_w.n) * 0.02
+        Op = torch.empty((up_w.p * up_w.m_chunk, up_w.n), dtype=torch.bfloat16, device=H.DEV)
+        bufs_p = cf.make_buffers(Xp, Wp, Op, each_p, slot_p, (None, None), None, each_p)
+        cs_p, xs_p = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        launch = lambda: cf.run_schedule(d_up, cf.CF_KIND_AG, bufs_p, cs_p, xs_p, PSK)
+        power = {"kernel": "up-projection rank-step kernel alone (8 x 1024x3584x8192, one persistent launch)", "random_data_us": {}}
+        which = args.power_data
+        if which in ("random", "both"):
+            for wgs in (256, 224, 192, 160, 128):
+                os.environ["COMMFUSE_PERSIST_WGS"] = str(wgs)
+                t = time_calls(launch, cs_p, max(K, 30), W)
+                power["random_data_us"][str(wgs) + "_workgroups"] = round(t * 1e3, 1)
+                log(f"power probe: random data, {wgs} workgroups: {t*1e3:.1f} us = {up_w.flops/(t*1e-3)/1e12:.0f} TFLOP/s")
+            os.environ.pop("COMMFUSE_PERSIST_WGS", None)
+        if which in ("zero", "both"):
+            for t_ in [Xp, Wp] + each_p:
+                t_.zero_()
+            torch.cuda.synchronize()
+            t = time_calls(launch, cs_p, max(K, 30), W)
+            power["zero_data_us"] = {"256_workgroups": round(t * 1e3, 1)}
+            log(f"power probe: all-zero operands, 256 workgroups: {t*1e3:.1f} us = {up_w.flops/(t*1e-3)/1e12:.0f} TFLOP/s")
+        del Xp, each_p, slot_p, Wp, Op, bufs_p
+        torch.cuda.empty_cache()
+
     cf.device_status(None)                            # no step kernel gave up a device-side wait
 
     # ---------------- CPU oracle on a bounded sample of the headline workload ----------------
@@ -517,7 +562,7 @@ def main() -> int:
         torch.cuda.synchronize()
 
     if args.skip_pair:                                # profiling run of one section: no headline, no contract line
-        print(json.dumps({"sections": sorted(sections), "dp_reduce": dp, "other_configs": others, "pairwise_schedule": pairwise,
+        print(json.dumps({"sections": sorted(sections), "power_probe": power, "dp_reduce": dp, "other_configs": others, "pairwise_schedule": pairwise,
                           "slicing_granularity": granularity, "backward_pass": backward,
                           "query_split_attention": attention}), flush=True)
         return 0
@@ -551,7 +596,7 @@ def main() -> int:
         "overlap_by_mode": pair_overlap,
         "ms_compute_only": round(head_comp, 4), "ms_copy_only": round(head_copy, 4),
         "roofline": roofline, "cpu_baseline": cpu, "dp_reduce": dp, "other_configs": others,
-        "vanilla_comparator": vanilla,
+        "vanilla_comparator": vanilla, "power_probe": power,
         "pairwise_schedule": pairwise, "slicing_granularity": granularity, "backward_pass": backward, "query_split_attention": attention,
     }
     print(json.dumps(line), flush=True)
