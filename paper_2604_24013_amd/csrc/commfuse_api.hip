@@ -1334,6 +1334,10 @@ static Tuning read_tuning_from_environment()
         t.xcd_steps = atoi(e) != 0;
     if (const char *e = getenv("COMMFUSE_K_ROTATE"))
         t.k_rotate = atoi(e) != 0;
+    if (const char *e = getenv("COMMFUSE_XCD_BANDS")) {
+        const int v = atoi(e);
+        t.xcd_bands = (v == 1 || v == 2 || v == 4) ? v : 0;
+    }
     if (const char *e = getenv("COMMFUSE_CARRY"))
         t.carry = atoi(e) != 0;
     if (const char *e = getenv("COMMFUSE_PERSIST_WGS"))

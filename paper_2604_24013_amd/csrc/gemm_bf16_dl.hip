@@ -209,8 +209,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     const int tiles_per_step = tiles_m * tiles_n * P.splits;
     // XCD-per-step mapping (GemmParams::xcd_steps): XCD x (workgroups x, x+8, ...) runs the steps x, x+8, ...
     // whole, so a step's own operand (A of the step) passes through one L2 only, instead of through all
-    // eight when every XCD holds a band of every step's tiles.
+    // eight when every XCD holds a band of every step's tiles.  With GemmParams::xcd_bands = NB > 1 the XCDs form
+    // 8 / NB step groups x NB column bands instead: XCD x runs the steps x / NB, x / NB + 8 / NB, ... on the tile
+    // columns of band x % NB only -- fewer weight bands and more left-operand bands per L2, which is less traffic
+    // where a step has few tile rows and many tile columns.
     const bool by_xcd = PERSIST && P.xcd_steps;
+    const int xcd_nb = by_xcd ? P.xcd_bands : 1, xcd_groups = 8 / xcd_nb;
+    const int xcd_grp = (int)(blockIdx.x & 7) / xcd_nb, xcd_band = (int)(blockIdx.x & 7) % xcd_nb;
     const int item_stride = by_xcd ? (int)(gridDim.x >> 3) : (int)gridDim.x;
     const int n_items = PERSIST ? tiles_per_step * (by_xcd ? P.n_steps >> 3 : P.n_steps) : 0;
     int item = by_xcd ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;
@@ -223,7 +228,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave % WGM, wn = wave / WGM;
-    const int step_i = PERSIST ? (by_xcd ? (int)(blockIdx.x & 7) + 8 * (item / tiles_per_step) : item / tiles_per_step) : 0;
+    // the XCD's items: all (step, tile row) pairs of one tile column, then the next column of its band
+    const int rows_x = by_xcd ? (P.n_steps / xcd_groups) * tiles_m : 1;       // (step, tile row) pairs of this XCD
+    const int step_i = PERSIST ? (by_xcd ? xcd_grp + xcd_groups * ((item % rows_x) / tiles_m) : item / tiles_per_step) : 0;
     const void *const cA = PERSIST ? P.A_step[step_i] : P.A;
     const float *const cRecv = PERSIST ? P.recv_step[step_i] : P.recv;
     void *const cLand = PERSIST ? P.land_step[step_i] : nullptr;   // where the delivery is to land, if this kernel carries it
@@ -234,7 +241,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
 
     // Work item = (output tile, k-split); the splits of a tile are neighbours in the remapped order.
     const int splits = P.splits;
-    const int work = by_xcd ? item % tiles_per_step
+    const int work = by_xcd ? (xcd_band * (tiles_n / xcd_nb) + item / rows_x) * tiles_m + (item % rows_x) % tiles_m
                             : xcd_remap(PERSIST ? item % tiles_per_step : (int)blockIdx.x, tiles_per_step);
     const int tile = work / splits, split = work % splits;
     const int m0 = (tile % tiles_m) * BM;
@@ -331,11 +338,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // kt into `stage`.  A tile beyond the end of this split's k range is requested all the same, with
     // every lane out of range (it reads zeros and moves no data), so that the number of loads per
     // tile -- and with it every vmcnt below -- is the same in every iteration.
-    // Persistent mode: the workgroups of XCD x walk the k range starting x/8 of the way in and wrap around, so
-    // that the eight XCDs -- which all read the same weight tiles, and would ask for the same lines at the same
-    // moment -- are spread over the k range (measured: 1 % of the pair's rank step).  The sum over k is taken in
-    // that rotated order: deterministic for a given launch, last-bit different between XCDs.
-    const int rot = (PERSIST && P.k_rotate) ? (int)(((blockIdx.x & 7) * nk_all) >> 3) : 0;
+    // Persistent mode: the workgroups of step group g of G (XCD x of 8 without column bands) walk the k range
+    // starting g/G of the way in and wrap around, so that the XCDs that read the same weight tiles -- and would ask
+    // for the same lines at the same moment -- are spread over the k range (measured: 1 % of the pair's rank step).
+    // The sum over k is taken in that rotated order: deterministic for a given launch, last-bit different between
+    // step groups.
+    const int rot = (PERSIST && P.k_rotate) ? (xcd_grp * nk_all) / xcd_groups : 0;
     auto ktile = [&](int kt) __attribute__((always_inline)) {                           // global k-tile of this item's local k-tile kt
         const int kk = ktb + kt + rot;
         return kk >= nk_all ? kk - nk_all : kk;
@@ -1231,6 +1239,35 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
         // (measured with whole steps per XCD only; a ragged k tail stays the last k-tile of every work item,
         // which keeps all earlier iterations of the 256x256 main loop branch-free)
         p.k_rotate = p.xcd_steps && tn.k_rotate != 0 && p.K % BK == 0;
+        // Step groups x column bands: per k-tile the 32 (or fewer) workgroups of an XCD that run side by side fetch
+        // `a` left-operand bands of bm rows and `b` weight bands of bn columns, a = (step, tile row) pairs of the XCD
+        // (at most its workgroups), b = the columns they spread over; the number of bands NB that makes a bm + b bn
+        // smallest (ties: the fewest bands).  7B down-projection (2 tile rows x 16 tile columns per step): NB = 2,
+        // 12 instead of 18 bands; the 70B shapes stay at NB = 1 (4 x 8 is already the best cut of 32).
+        p.xcd_bands = 1;
+        if (p.xcd_steps) {
+            const int tiles_m = (p.M + t.bm - 1) / t.bm, tiles_n = (p.N + t.bn - 1) / t.bn;
+            const int per_cu = (t.bm == 128 && t.bn == 128 && !t.deep) ? 2 : 1;
+            const int items_x = tiles_m * tiles_n * (p.n_steps / 8);
+            const int wgs_x = items_x < p.num_cu * per_cu / 8 ? items_x : p.num_cu * per_cu / 8;
+            long best = -1;
+            for (int nb = 1; nb <= 4; nb *= 2) {
+                if (tiles_n % nb != 0 || p.n_steps % (8 / nb) != 0)
+                    continue;
+                if (tn.xcd_bands > 0 && nb != tn.xcd_bands)
+                    continue;                          // override: this many bands where the shape allows it
+                const int rows = p.n_steps / (8 / nb) * tiles_m;
+                const int a = rows < wgs_x ? rows : wgs_x;
+                const int cols = tiles_n / nb;
+                int b = (wgs_x + a - 1) / a;
+                b = b < cols ? b : cols;
+                const long cost = (long)a * t.bm + (long)b * t.bn;
+                if (best < 0 || cost < best) {
+                    best = cost;
+                    p.xcd_bands = nb;
+                }
+            }
+        }
     }
     if (p.splits > 1 && (p.ws == nullptr || p.counters == nullptr ||
                          (size_t)p.splits * p.M * p.N * sizeof(float) > p.ws_bytes || tiles > p.max_tiles ||

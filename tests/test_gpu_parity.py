@@ -624,6 +624,45 @@ def test_all_gather_carries_its_deliveries(tile, k):
         os.environ.pop("COMMFUSE_K_ROTATE", None)
 
 
+@pytest.mark.parametrize("bands", ["1", "2", "4"])
+@pytest.mark.parametrize("tile", ["256x256", "256x128", "128x128"])
+def test_persistent_step_groups_and_column_bands(tile, bands):
+    """The one-launch rank step deals its work items to the eight XCDs as 8 / NB step groups x NB bands of tile columns
+    (NB = 1: whole steps per XCD).  Every NB must give every step's output and every delivery, for reduce-scatter and
+    all-gather, with the deliveries copied in front and carried by the kernel, with granularity 1 and 2."""
+    rank = 2
+    os.environ["COMMFUSE_XCD_BANDS"] = bands
+    _tile_env(tile)
+    try:
+        for m in (1, 2):
+            w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=8, m_chunk=264, n=1000, k=1280)   # 4 (8) tile columns, the last ragged
+            data = inputs.make_rs(w, salt=71)
+            ref = _oracle_rs(w, data, rank)
+            wa = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=8, m_chunk=264, n=1000, k=640, out_dtype="bf16")
+            da = inputs.make_ag(wa, salt=72)
+            refa = _oracle_ag(wa, da, rank)
+            for flags in (PERSISTENT_SERIAL, PERSISTENT_SERIAL | cf.CF_FUSED_COPY):
+                run = H.RsRun(w, data, rank, m=m, each=True)
+                for t in run.each + run.send_each + [run.O]:
+                    t.fill_(float("nan"))
+                run.run_schedule(flags)
+                for i in range(w.p):
+                    got = H.to_host_f64(run.send_each[i] if i < w.p - 1 else run.O)
+                    e = H.rel_err(got, ref[i])
+                    assert e <= TIGHT_BF16, f"m {m} flags {flags} step {i}: {e:.3e}"
+                ag = H.AgRun(wa, da, rank, m=m, each=True)
+                for t in ag.each:
+                    t.fill_(float("nan"))
+                ag.run_schedule(flags)
+                o = H.to_host_f64(ag.O)
+                assert not np.isnan(o).any() and H.rel_err(o, refa) <= TIGHT_BF16_OUT, f"m {m} flags {flags}"
+                for i in range(w.p - 1):
+                    assert torch.equal(run.each[i], run.stage[i]) and torch.equal(ag.each[i], ag.stage[i]), f"m {m} flags {flags} hop {i + 1}"
+    finally:
+        os.environ.pop("COMMFUSE_XCD_BANDS", None)
+        _tile_env(None)
+
+
 @pytest.mark.parametrize("kind", ["rs", "ag"])
 def test_persistent_k_rotation(kind):
     """The persistent launch lets the workgroups of XCD x start their k loops x/8 of the way into the k range
