@@ -320,7 +320,8 @@ def main() -> int:
                               "us_per_rank_step": round(t["overlapped"][0] * 1e3, 1), "mode": t["overlapped"][1],
                               **overlap_eff(t),
                               "us_compute_only": round(t["compute_only"][0] * 1e3, 1),
-                              "us_copy_only": round(t["copy_only"][0] * 1e3, 1)}
+                              "us_copy_only": round(t["copy_only"][0] * 1e3, 1),
+                              "us_per_rank_step_by_mode": {m_: round(v["overlapped"] * 1e3, 1) for m_, v in t["by_mode"].items() if "overlapped" in v}}
             log("pairwise", name, pairwise[name])
             del run
             torch.cuda.empty_cache()
