@@ -117,7 +117,7 @@ def main() -> int:
             best = None
             pers_pair = kind == cf.CF_KIND_RS_PAIR and getattr(run, "each", None) is not None
             for mode, extra in MODES if (kind in (cf.CF_KIND_RS, cf.CF_KIND_AG) and (fl == 0 or "persistent" in mode or mode in BASIC_NAMES)) \
-                    else (BASIC + tuple(m for m in MODES if "persistent" in m[0] and "carried" not in m[0]) if pers_pair else BASIC):
+                    else (BASIC + tuple(m for m in MODES if "persistent" in m[0] and "carried" not in m[0] and "groups" not in m[0]) if pers_pair else BASIC):
                 if fl != 0 and (extra & (cf.CF_FUSED_COPY | cf.CF_DEVICE_WAIT)):
                     continue
                 if (extra & cf.CF_PERSISTENT) and getattr(run, "each", None) is None:
@@ -136,13 +136,15 @@ def main() -> int:
     # at full speed and disturb no GEMM -- a reference point for what the overlap buys); "persistent": all
     # steps of a rank step in one kernel launch, the deliveries enqueued before it; "persistent+carried": no copy is
     # enqueued, the kernel's own waves read B_in from the neighbour's buffer under the main loop and store it to the
-    # landing buffer
+    # landing buffer; "persistent-groups": two streams again -- a few launches per layer, each a group of steps that fills
+    # the chip about once, the deliveries of a group on the copy stream under the launches of the groups before it
     MODES = (("streams", 0), ("graph", cf.CF_GRAPH), ("fused-copy", cf.CF_FUSED_COPY),
              ("fused-copy+graph", cf.CF_FUSED_COPY | cf.CF_GRAPH), ("device-wait", cf.CF_DEVICE_WAIT),
              ("serial", cf.CF_SERIAL), ("serial+graph", cf.CF_SERIAL | cf.CF_GRAPH),
              ("persistent", cf.CF_PERSISTENT | cf.CF_SERIAL),
              ("persistent+graph", cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_GRAPH),
-             ("persistent+carried", cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY))
+             ("persistent+carried", cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY),
+             ("persistent-groups", cf.CF_PERSISTENT), ("persistent-groups+graph", cf.CF_PERSISTENT | cf.CF_GRAPH))
 
     BASIC_NAMES = ("streams", "graph", "serial", "serial+graph")
     BASIC = tuple(m for m in MODES if m[0] in BASIC_NAMES)   # work for every kind and flag
@@ -367,7 +369,7 @@ def main() -> int:
         G_up = bf16_dev((p8 * mc8, d_ff), 1.0)
         W_up = bf16_dev((d_model, d_ff), 0.01)
         stage32 = [mk32(mc8, d_model).normal_() for _ in range(p8 - 1)]
-        PERS = tuple(m for m in MODES if m[0] in BASIC_NAMES or "persistent" in m[0])
+        PERS = tuple(m for m in MODES if m[0] in BASIC_NAMES or ("persistent" in m[0] and "groups" not in m[0]))
         each32 = [mk32(mc8, d_model) for _ in range(p8 - 1)]
         keep = [mk32(mc8, d_model), [mk32(mc8, d_model) for _ in range(2)], [mk32(mc8, d_model) for _ in range(2)],
                 [mk32(mc8, d_model) for _ in range(p8 - 1)]]
@@ -432,6 +434,8 @@ def main() -> int:
         fl_proj = 2.0 * mca * Da * ha * 128
         best = None
         for mode, extra in MODES:
+            if "groups" in mode:                         # (the grouped launches exist for the plain RS / AG kinds)
+                continue
             t = time_calls(lambda: cf.run_attn_schedule(adesc, abufs, cs, xs, extra), cs, max(K, 30), W)
             if best is None or t < best[0]:
                 best = (t, mode)
@@ -463,7 +467,7 @@ def main() -> int:
         pers.each = [torch.empty((c,), dtype=torch.float32, device=H.DEV) for _ in range(w5.p - 1)]
         pers.bufs = cf.make_buffers(None, None, run.bucket, run.stage, run.slot, (None, None), None, pers.each)
         for name, fl in (("overlapped", 0), ("copy_only", cf.CF_NO_COMPUTE)):
-            for mode, extra in (m_ for m_ in MODES if "persistent" in m_[0]):
+            for mode, extra in (m_ for m_ in MODES if "persistent" in m_[0] and "groups" not in m_[0]):
                 if fl != 0 and "carried" in mode:     # (the add kernels land what they read: no copy-only variant)
                     continue
                 tp = time_calls(lambda: cf.run_schedule(pers.desc, cf.CF_KIND_DP, pers.bufs, pers.cs, pers.xs, fl | extra),
@@ -473,7 +477,7 @@ def main() -> int:
                     t[name] = (tp, mode)
         # pairwise schedule on the same bucket: seven arrivals for the own slice, summed in one pass (36 B per element)
         t_pw, pw_mode = min((time_calls(lambda: cf.run_schedule(pers.desc, cf.CF_KIND_DP_PAIR, pers.bufs, pers.cs, pers.xs, extra),
-                                        pers.cs, 10, 2), mode) for mode, extra in MODES if "persistent" in mode)
+                                        pers.cs, 10, 2), mode) for mode, extra in MODES if "persistent" in mode and "groups" not in mode)
         t_pw_c = time_calls(lambda: cf.run_schedule(pers.desc, cf.CF_KIND_DP_PAIR, pers.bufs, pers.cs, pers.xs,
                                                     cf.CF_PERSISTENT | cf.CF_NO_COPY), pers.cs, 10, 2)
         steps_with_add = w5.p - 1

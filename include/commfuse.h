@@ -306,11 +306,15 @@ enum {
                             delivery stays where it landed), for the reduce-scatter kinds
                             cf_buffers.send_each (every step stores the B_out of Alg. 2 into a
                             buffer of its own; peer_sink, if given, is copied from those after the
-                            launch), and CF_SERIAL: the
+                            launch).  With CF_SERIAL the
                             deliveries are enqueued before the kernel on the compute stream -- a
                             kernel that holds its compute units for the whole rank step starves
-                            concurrent blit copies.  (The kernel can also wait for per-step delivery
-                            flags on the device; on a real ring, where a delivery is a remote DMA
+                            concurrent blit copies.  Without CF_SERIAL (CF_KIND_RS / CF_KIND_AG only, two
+                            streams; the other kinds need CF_SERIAL): the rank step is a few launches, each a
+                            group of consecutive (sub-)steps that fills the chip about once, and the
+                            deliveries of a group are copied on copy_stream under the launches of the
+                            groups before it, one event per group ordering the two streams.
+                            (The kernel can also wait for per-step delivery flags on the device; on a real ring, where a delivery is a remote DMA
                             write that needs no compute unit here, that is how it would overlap.)
                             CF_KIND_RS_PAIR: every arrival is kept (recv_each) and the last step adds
                             them all, as commfuse_rs_pair_last_step does.

@@ -132,6 +132,9 @@ bool gemm_bf16_takes_recv_list(const GemmParams &p, bool w_kn);
 // else an all-gather's) on a kernel that honours GemmParams::land_step (the delivery carried by the consumer)
 // for every step that receives.
 bool gemm_bf16_carries_delivery(const GemmParams &p, bool w_kn, bool out_bf16, int num_cu, bool reduce_scatter);
+// Steps per launch when a persistent rank step of p.n_steps steps is cut into launches that fill the chip about once
+// each (equal groups; p.n_steps when the whole rank step is one round or less).
+int gemm_bf16_steps_per_launch(const GemmParams &p, bool w_kn, int num_cu);
 // Direct-to-LDS variant of the bf16 kernel (operand extents below 2^31 bytes).
 bool gemm_bf16_dl_supported(const GemmParams &p, bool w_kn);
 hipError_t launch_gemm_bf16_dl(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, TileChoice t);

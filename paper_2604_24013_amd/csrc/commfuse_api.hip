@@ -848,8 +848,8 @@ cf_status enqueue_schedule(const Resolved &r, int kind, const cf_buffers *b, hip
 // operand; the deliveries are enqueued before it on the same stream.  The steps of one launch run side by side,
 // so every sending step of a reduce-scatter kind stores its B_out into a buffer of its own (cf_buffers.send_each);
 // the emulated sends into peer_sink, if any, are copied from those after the launch.
-cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, hipStream_t cs, uint32_t flags,
-                             const AttnCtx *attn = nullptr)
+cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, hipStream_t cs, hipStream_t xs,
+                             uint32_t flags, const AttnCtx *attn = nullptr)
 {
     const int p = r.p, m = r.m, S = r.p * r.m;
     const bool do_copy = !(flags & CF_NO_COPY) && p > 1;
@@ -900,7 +900,58 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
     // the add's 12; pairwise, p - 1 arrivals in one pass: 8 p instead of 12 p - 4).
     if ((flags & CF_FUSED_COPY) && is_dp_kind(kind) && do_copy && do_compute && slot_bytes > 0)
         carried = true;
-    if (do_copy && slot_bytes > 0 && !carried) {
+    // Without CF_SERIAL (reduce-scatter and all-gather on two streams): the rank step as a few launches, each a group
+    // of consecutive (sub-)steps that fills the chip about once, and the deliveries of a group copied on the copy
+    // stream under the launches of the groups before it -- Fig. 1's overlap with a group of steps where the paper has
+    // one step.  One event per group orders the two streams; every hop has its own landing buffer, so the copy
+    // stream never waits for a kernel.
+    int group = S;
+    const bool grouped = !(flags & CF_SERIAL) && xs != cs && (kind == CF_KIND_RS || kind == CF_KIND_AG) && attn == nullptr &&
+                         !carried && p > 1 && slot_bytes > 0 && r.mc > 0 && r.n > 0 && r.k > 0;
+    if (grouped) {
+        cf::GemmParams probe;
+        probe.W = b->W;
+        fill_shape(probe, r);
+        probe.n_steps = S;
+        group = cf::gemm_bf16_steps_per_launch(probe, r.w_kn, num_cu_of_current_device());
+    }
+    const int n_groups = (S + group - 1) / group;
+    std::vector<hipEvent_t> ev;
+    if (grouped) {
+        if (cf_status st = get_events(1 + (size_t)n_groups, &ev))
+            return st;
+        CF_HIP(hipEventRecord(ev[0], cs));               // the copy stream starts behind what the compute stream holds
+        CF_HIP(hipStreamWaitEvent(xs, ev[0], 0));
+    }
+    if (grouped && do_copy) {
+        for (int g = 0; g < n_groups; ++g) {             // the deliveries of group g: one batched copy launch, then its event
+            const void *srcs[cf::GemmParams::MAX_STEPS];
+            void *dsts[cf::GemmParams::MAX_STEPS];
+            int n = 0;
+            for (int j = g * group; j < S && j < (g + 1) * group; ++j)
+                if (receives(j)) {
+                    srcs[n] = stage_of(j);
+                    dsts[n++] = landing(j);
+                    if (poison) {
+                        hipError_t e = cf::launch_fill_ff(landing(j), slot_bytes, xs);
+                        if (e != hipSuccess)
+                            return fail_hip(e, "poison fill");
+                    }
+                }
+            if (n > 0 && cf::copy_batch_takes(srcs, dsts, n, slot_bytes)) {
+                hipError_t e = cf::launch_copy_batch(srcs, dsts, n, slot_bytes, xs);
+                if (e != hipSuccess)
+                    return fail_hip(e, "delivery copy launch");
+            } else {
+                for (int i = 0; i < n; ++i)
+                    CF_HIP(hipMemcpyAsync(dsts[i], srcs[i], slot_bytes, hipMemcpyDeviceToDevice, xs));
+            }
+            CF_HIP(hipEventRecord(ev[1 + g], xs));
+        }
+        if (!do_compute)                                 // copies only: the compute stream still ends behind them
+            CF_HIP(hipStreamWaitEvent(cs, ev[n_groups], 0));
+    }
+    if (do_copy && slot_bytes > 0 && !carried && !grouped) {
         // all deliveries of the rank step are due now: one batched copy launch where the buffers allow it
         // (at most 16 hops of 16-byte-aligned whole hop buffers), else one hipMemcpyAsync per (sub-)step
         const void *srcs[cf::GemmParams::MAX_STEPS];
@@ -978,12 +1029,15 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
     if (do_compute && !is_wgrad_kind(kind) && r.mc > 0 && r.n > 0) {
         if (r.k == 0)
             return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT needs k > 0");
+      for (int g0 = 0; g0 < S; g0 += group) {            // one launch per group of steps (all steps: one group)
+        const int g1 = g0 + group < S ? g0 + group : S;
         cf::GemmParams gp;
         gp.W = b->W;
         fill_shape(gp, r);
-        gp.n_steps = S;
+        gp.n_steps = g1 - g0;
         gp.num_cu = num_cu_of_current_device();
-        for (int j = 0; j < S; ++j) {
+        for (int jj = g0; jj < g1; ++jj) {
+            const int j = jj - g0;                       // the step's place in this launch
             if (kind == CF_KIND_RS_PAIR) {
                 // Appendix A(a) with deferred aggregation: steps 0..p-2 are plain chunk GEMMs for the partners'
                 // slices, the last step adds every arrival to the product for the own slice (m = 1 here)
@@ -998,31 +1052,34 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
                         gp.recv_more[gp.n_recv_more++] = static_cast<const float *>(b->recv_each[t]);
                 continue;
             }
-            const int c = subslice_index(kind, p, m, r.rank, j);
+            const int c = subslice_index(kind, p, m, r.rank, jj);
             if (kind == CF_KIND_RS) {
                 gp.A_step[j] = static_cast<const char *>(b->A_or_own_shard) + (size_t)c * r.mc * r.lda * in_elem(r);
-                gp.recv_step[j] = receives(j) ? static_cast<const float *>(landing(j)) : nullptr;
-                if (carried && receives(j)) {        // read from the neighbour's buffer, land it here
-                    gp.recv_step[j] = reinterpret_cast<const float *>(stage_of(j));
-                    gp.land_step[j] = landing(j);
+                gp.recv_step[j] = receives(jj) ? static_cast<const float *>(landing(jj)) : nullptr;
+                if (carried && receives(jj)) {       // read from the neighbour's buffer, land it here
+                    gp.recv_step[j] = reinterpret_cast<const float *>(stage_of(jj));
+                    gp.land_step[j] = landing(jj);
                 }
-                gp.out_step[j] = sends(j) ? static_cast<void *>(b->send_each[j / m] + (size_t)(j % m) * r.mc * r.ldo)
-                                          : static_cast<void *>(static_cast<float *>(b->O) + (size_t)(j % m) * r.mc * r.ldo);
+                gp.out_step[j] = sends(jj) ? static_cast<void *>(b->send_each[jj / m] + (size_t)(jj % m) * r.mc * r.ldo)
+                                           : static_cast<void *>(static_cast<float *>(b->O) + (size_t)(jj % m) * r.mc * r.ldo);
             } else {
-                gp.A_step[j] = receives(j) ? landing(j)
-                                           : static_cast<const char *>(b->A_or_own_shard) + (size_t)(j % m) * slot_bytes;
-                if (carried && receives(j)) {        // the slice is read from the neighbour's buffer and landed here
-                    gp.A_step[j] = stage_of(j);
-                    gp.land_step[j] = landing(j);
+                gp.A_step[j] = receives(jj) ? landing(jj)
+                                            : static_cast<const char *>(b->A_or_own_shard) + (size_t)(jj % m) * slot_bytes;
+                if (carried && receives(jj)) {       // the slice is read from the neighbour's buffer and landed here
+                    gp.A_step[j] = stage_of(jj);
+                    gp.land_step[j] = landing(jj);
                 }
                 gp.recv_step[j] = nullptr;
                 gp.out_step[j] = static_cast<char *>(b->O) + (size_t)c * r.mc * r.ldo * (r.bf16_out ? 2 : 4);
             }
             gp.flag_step[j] = nullptr;               // everything was delivered before the launch
         }
+        if (grouped && do_copy)                          // this group's deliveries have landed
+            CF_HIP(hipStreamWaitEvent(cs, ev[1 + g0 / group], 0));
         hipError_t e = cf::launch_gemm_bf16(gp, r.w_kn, r.bf16_out, cs, gp.num_cu);
         if (e != hipSuccess)
             return fail_hip(e, "persistent rank-step launch");
+      }
     }
     // emulated sends (Alg. 2 "p2p_send(B_out)", Alg. 1 "p2p_send(B_out)" of the slice in hand): hop i < p-1 into
     // peer_sink[i], all hops as one batched copy where the buffers allow it
@@ -1165,13 +1222,14 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
         // A kernel that holds its compute units for a whole rank step starves the blit kernels of concurrent
         // deliveries (its workgroups can take every register of a CU; measured: the copies then crawl on the
         // few CUs left over and the kernel's bounded waits time out).  So the deliveries are enqueued before it.
-        if (!(flags & (CF_SERIAL | CF_NO_COPY | CF_NO_COMPUTE)) && xs != cs && r.p > 1)
-            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT needs CF_SERIAL (the deliveries are enqueued before the kernel)");
+        if (!(flags & (CF_SERIAL | CF_NO_COPY | CF_NO_COMPUTE)) && xs != cs && r.p > 1 &&
+            !((kind == CF_KIND_RS || kind == CF_KIND_AG) && attn == nullptr))
+            return fail(CF_ERR_UNSUPPORTED, "CF_PERSISTENT needs CF_SERIAL for this kind (the deliveries are enqueued before the kernel)");
     }
     if (cf_status st = check_buffers(r, kind, bufs, flags))
         return st;
     if (!(flags & CF_GRAPH))
-        return (flags & CF_PERSISTENT) ? enqueue_persistent(r, kind, bufs, cs, flags, attn)
+        return (flags & CF_PERSISTENT) ? enqueue_persistent(r, kind, bufs, cs, xs, flags, attn)
                                        : enqueue_schedule(r, kind, bufs, cs, xs, flags, attn);
 
     // CF_GRAPH: the same enqueue sequence, captured once per distinct argument set.
@@ -1228,7 +1286,7 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
             return st;
         CF_HIP(hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal));
         const uint32_t fl = flags & ~(uint32_t)CF_GRAPH;
-        cf_status st = (fl & CF_PERSISTENT) ? enqueue_persistent(r, kind, bufs, cs, fl, attn)
+        cf_status st = (fl & CF_PERSISTENT) ? enqueue_persistent(r, kind, bufs, cs, xs, fl, attn)
                                             : enqueue_schedule(r, kind, bufs, cs, xs, fl, attn);
         hipGraph_t graph = nullptr;
         hipError_t e = hipStreamEndCapture(cs, &graph);

@@ -371,6 +371,20 @@ bool gemm_bf16_carries_delivery(const GemmParams &p, bool w_kn, bool out_bf16, i
     return tn.carry >= 0 ? tn.carry != 0 : true;
 }
 
+int gemm_bf16_steps_per_launch(const GemmParams &p, bool w_kn, int num_cu)
+{
+    if (p.M <= 0 || p.N <= 0 || p.n_steps <= 1 || staged_kernel_forced() || !gemm_bf16_dl_supported(p, w_kn))
+        return p.n_steps > 0 ? p.n_steps : 1;
+    const TileChoice t = tile_of_launch(p, num_cu);
+    const int64_t tiles = (int64_t)((p.M + t.bm - 1) / t.bm) * ((p.N + t.bn - 1) / t.bn);
+    const int64_t wgs = (int64_t)num_cu * ((t.bm == 128 && t.bn == 128 && !t.deep) ? 2 : 1);
+    int64_t per_round = (wgs + tiles - 1) / tiles;       // steps that fill the chip once (rounded up)
+    if (per_round < 1)
+        per_round = 1;
+    const int64_t launches = (p.n_steps + per_round - 1) / per_round;
+    return (int)((p.n_steps + launches - 1) / launches);   // equal groups
+}
+
 hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, int num_cu)
 {
     if (p.M <= 0 || p.N <= 0)

@@ -217,7 +217,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     const int xcd_nb = by_xcd ? P.xcd_bands : 1, xcd_groups = 8 / xcd_nb;
     const int xcd_grp = (int)(blockIdx.x & 7) / xcd_nb, xcd_band = (int)(blockIdx.x & 7) % xcd_nb;
     const int item_stride = by_xcd ? (int)(gridDim.x >> 3) : (int)gridDim.x;
-    const int n_items = PERSIST ? tiles_per_step * (by_xcd ? P.n_steps >> 3 : P.n_steps) : 0;
+    const int n_items = PERSIST ? (by_xcd ? (tiles_per_step * P.n_steps) >> 3 : tiles_per_step * P.n_steps) : 0;
     int item = by_xcd ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;
     do {
     // Lane and wave indices are taken anew for every work item: what is derived from them then lives
@@ -1124,8 +1124,8 @@ hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t
         const int items = tiles_m * tiles_n * p.n_steps;
         wgs = items < p.num_cu * per_cu ? items : p.num_cu * per_cu;
         if (p.xcd_steps)                             // whole octets of workgroups: the same number per XCD
-            wgs = (tiles_m * tiles_n * (p.n_steps / 8) < p.num_cu * per_cu / 8 ? tiles_m * tiles_n * (p.n_steps / 8)
-                                                                              : p.num_cu * per_cu / 8) * 8;
+            wgs = (tiles_m * tiles_n * p.n_steps / 8 < p.num_cu * per_cu / 8 ? tiles_m * tiles_n * p.n_steps / 8
+                                                                            : p.num_cu * per_cu / 8) * 8;
         if (const int cap = tuning().persist_wgs; cap >= 8 && cap < wgs)   // override: leave compute units free
             wgs = p.xcd_steps ? cap / 8 * 8 : cap;
     }
@@ -1235,10 +1235,13 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
         // overrides: xcd_steps 0 = every XCD takes a band of every step; k_rotate 0 = every XCD walks k from 0
         // (whole steps per XCD not when one step carries the sum of several received partials: that step's
         // epilogue is heavy and would fall on one XCD)
-        p.xcd_steps = p.n_steps % 8 == 0 && p.num_cu % 8 == 0 && p.n_recv_more == 0 && tn.xcd_steps != 0;
-        // (measured with whole steps per XCD only; a ragged k tail stays the last k-tile of every work item,
-        // which keeps all earlier iterations of the 256x256 main loop branch-free)
-        p.k_rotate = p.xcd_steps && tn.k_rotate != 0 && p.K % BK == 0;
+        // (... or, with fewer steps than XCDs -- a group of steps launched on its own --, 8 / NB step groups x NB bands
+        // of tile columns, which needs NB to divide the tile columns and 8 / NB the steps)
+        const int tiles_n_ = (p.N + t.bn - 1) / t.bn;
+        bool cut = false;
+        for (int nb = 1; nb <= 8; nb *= 2)
+            cut = cut || (tiles_n_ % nb == 0 && p.n_steps % (8 / nb) == 0);
+        p.xcd_steps = cut && p.num_cu % 8 == 0 && p.n_recv_more == 0 && tn.xcd_steps != 0;
         // Step groups x column bands: per k-tile the 32 (or fewer) workgroups of an XCD that run side by side fetch
         // `a` left-operand bands of bm rows and `b` weight bands of bn columns, a = (step, tile row) pairs of the XCD
         // (at most its workgroups), b = the columns they spread over; the number of bands NB that makes a bm + b bn
@@ -1248,13 +1251,13 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
         if (p.xcd_steps) {
             const int tiles_m = (p.M + t.bm - 1) / t.bm, tiles_n = (p.N + t.bn - 1) / t.bn;
             const int per_cu = (t.bm == 128 && t.bn == 128 && !t.deep) ? 2 : 1;
-            const int items_x = tiles_m * tiles_n * (p.n_steps / 8);
+            const int items_x = tiles_m * tiles_n * p.n_steps / 8;
             const int wgs_x = items_x < p.num_cu * per_cu / 8 ? items_x : p.num_cu * per_cu / 8;
             long best = -1;
-            for (int nb = 1; nb <= 4; nb *= 2) {
+            for (int nb = 1; nb <= 8; nb *= 2) {
                 if (tiles_n % nb != 0 || p.n_steps % (8 / nb) != 0)
                     continue;
-                if (tn.xcd_bands > 0 && nb != tn.xcd_bands)
+                if (tn.xcd_bands > 0 && nb != tn.xcd_bands && p.n_steps % 8 == 0)
                     continue;                          // override: this many bands where the shape allows it
                 const int rows = p.n_steps / (8 / nb) * tiles_m;
                 const int a = rows < wgs_x ? rows : wgs_x;
@@ -1267,7 +1270,12 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
                     p.xcd_bands = nb;
                 }
             }
+            if (best < 0 && p.n_steps % 8 != 0)
+                p.xcd_steps = false;                   // (no cut fits: every XCD takes a band of every step)
         }
+        // (measured with whole steps per XCD only; a ragged k tail stays the last k-tile of every work item,
+        // which keeps all earlier iterations of the 256x256 main loop branch-free)
+        p.k_rotate = p.xcd_steps && tn.k_rotate != 0 && p.K % BK == 0;
     }
     if (p.splits > 1 && (p.ws == nullptr || p.counters == nullptr ||
                          (size_t)p.splits * p.M * p.N * sizeof(float) > p.ws_bytes || tiles > p.max_tiles ||

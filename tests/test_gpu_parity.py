@@ -530,9 +530,12 @@ def test_persistent_rank_step(m, tile, k):
         # (with CF_FUSED_COPY the reduce-scatter launch carries its deliveries itself where it brings B_in in through
         # LDS -- the 256x256 tile with the longer k ranges -- and the all-gather launch where k is whole k-tiles;
         # they have them copied in front otherwise: same results)
+        # (without CF_SERIAL: groups of steps per launch, the deliveries of a group on the copy stream under the launches
+        # before it)
         for flags in (cf.CF_PERSISTENT | cf.CF_SERIAL, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_GRAPH,
                       cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_POISON, cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY,
-                      cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY | cf.CF_GRAPH):
+                      cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY | cf.CF_GRAPH,
+                      cf.CF_PERSISTENT, cf.CF_PERSISTENT | cf.CF_GRAPH, cf.CF_PERSISTENT | cf.CF_POISON):
             for layout in (cf.CF_W_KN, cf.CF_W_NK):
                 run = H.RsRun(w, data, rank, layout, m=m, each=True)
                 run.O.fill_(float("nan"))
@@ -765,12 +768,16 @@ def test_persistent_needs_what_it_needs():
     data = inputs.make_rs(w)
     PS = cf.CF_PERSISTENT | cf.CF_SERIAL
     for kw, flags, status in (({}, PS, cf.CF_ERR_INVALID_ARG),                                     # no recv_each
-                              ({"each": True}, cf.CF_PERSISTENT, cf.CF_ERR_UNSUPPORTED),           # overlapped copies
                               ({"each": True}, PS | cf.CF_DEVICE_WAIT, cf.CF_ERR_UNSUPPORTED)):
         run = H.RsRun(w, data, 0, **kw)
         with pytest.raises(cf.CommFuseError) as ei:
             run.run_schedule(flags)
         assert ei.value.status == status, (kw, flags)
+    wd = inputs.scaled(inputs.CONFIGS["c5_dp"], p=4, m_chunk=4096)
+    dp = H.DpRun(wd, inputs.make_dp(wd), 0, each=True)
+    with pytest.raises(cf.CommFuseError) as ei:                  # two streams: the reduce-scatter and all-gather kinds only
+        dp.run_schedule(cf.CF_PERSISTENT)
+    assert ei.value.status == cf.CF_ERR_UNSUPPORTED
     run = H.RsRun(w, data, 0, each=True)                                                           # no send_each
     run.bufs = cf.make_buffers(run.A, run.W, run.O, run.stage, run.slot, run.send, None, run.each)
     with pytest.raises(cf.CommFuseError) as ei:
@@ -862,7 +869,7 @@ def _full_ref(name, rank):
 
 
 @pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_GRAPH, cf.CF_DEVICE_WAIT, PERSISTENT_SERIAL,
-                                   PERSISTENT_SERIAL | cf.CF_GRAPH, PERSISTENT_SERIAL | cf.CF_FUSED_COPY])
+                                   PERSISTENT_SERIAL | cf.CF_GRAPH, PERSISTENT_SERIAL | cf.CF_FUSED_COPY, cf.CF_PERSISTENT])
 @pytest.mark.parametrize("name", ["c2_rs_7b", "c4_rs_70b_down"])
 def test_full_size_rs(name, flags):
     w = inputs.CONFIGS[name]
@@ -886,7 +893,7 @@ def test_full_size_rs(name, flags):
 
 
 @pytest.mark.parametrize("flags", [0, cf.CF_FUSED_COPY | cf.CF_GRAPH, cf.CF_GRAPH, cf.CF_DEVICE_WAIT, PERSISTENT_SERIAL,
-                                   PERSISTENT_SERIAL | cf.CF_GRAPH, PERSISTENT_SERIAL | cf.CF_FUSED_COPY])
+                                   PERSISTENT_SERIAL | cf.CF_GRAPH, PERSISTENT_SERIAL | cf.CF_FUSED_COPY, cf.CF_PERSISTENT])
 @pytest.mark.parametrize("name", ["c3_ag_7b", "c4_ag_70b_up"])
 def test_full_size_ag(name, flags):
     w = inputs.CONFIGS[name]
@@ -912,7 +919,7 @@ def test_full_size_ag(name, flags):
         assert e <= gate and e <= tight, f"step {i}: {e:.3e}"
 
 
-@pytest.mark.parametrize("flags", [0, PERSISTENT_SERIAL, PERSISTENT_SERIAL | cf.CF_FUSED_COPY])
+@pytest.mark.parametrize("flags", [0, PERSISTENT_SERIAL, PERSISTENT_SERIAL | cf.CF_FUSED_COPY, cf.CF_PERSISTENT])
 def test_full_size_pair_70b(flags):
     """AG-GEMM (up) writes H in bf16; GEMM-RS (down) consumes it.  No activation between.  Set up as the
     benchmark sets it up (a landing buffer per hop, a B_out buffer per step, one compute stream for both
