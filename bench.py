@@ -536,6 +536,24 @@ def main() -> int:
             log(f"power probe: all-zero operands, 256 workgroups: {t*1e3:.1f} us = {up_w.flops/(t*1e-3)/1e12:.0f} TFLOP/s")
         del Xp, each_p, slot_p, Wp, Op, bufs_p
         torch.cuda.empty_cache()
+        # Context, not a target and not part of the path: the vendor library's plain GEMM (torch.matmul) on the two whole
+        # layers (no slicing, no B_in, no deliveries, bf16 output) under the same two kinds of operands, on this machine, in
+        # this run; weights stored [k x n] as the path stores them, and [n x k].  On torch's current stream: on another
+        # stream the library may pick a different kernel for want of a workspace.
+        power["library_gemm_us"] = {}
+        cur = torch.cuda.current_stream()
+        for data in (("random",) if which == "random" else ("zero",) if which == "zero" else ("random", "zero")):
+            for name, (gm, gn, gk) in (("down_8192x8192x3584", (dn.p * dn.m_chunk, dn.n, dn.k)), ("up_8192x3584x8192", (up_w.p * up_w.m_chunk, up_w.n, up_w.k))):
+                Al = mk(gm, gk) if data == "random" else torch.zeros((gm, gk), dtype=torch.bfloat16, device=H.DEV)
+                Wl = mk(gk, gn) * 0.02 if data == "random" else torch.zeros((gk, gn), dtype=torch.bfloat16, device=H.DEV)
+                Wt = Wl.t().contiguous()              # the same weights stored [n x k]
+                Ol = torch.empty((gm, gn), dtype=torch.bfloat16, device=H.DEV)
+                for order, fn in (("w_kn", lambda: torch.matmul(Al, Wl, out=Ol)), ("w_nk", lambda: torch.matmul(Al, Wt.t(), out=Ol))):
+                    t = time_calls(fn, cur, max(K, 30), W)
+                    power["library_gemm_us"][f"{name}_{order}_{data}"] = round(t * 1e3, 1)
+                    log(f"power probe: torch.matmul {name}, weights {order}, {data} operands: {t*1e3:.1f} us = {2.0*gm*gn*gk/(t*1e-3)/1e12:.0f} TFLOP/s")
+                del Al, Wl, Wt, Ol
+        torch.cuda.empty_cache()
 
     cf.device_status(None)                            # no step kernel gave up a device-side wait
 
