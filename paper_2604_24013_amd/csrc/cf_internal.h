@@ -49,6 +49,7 @@ struct GemmParams {
     bool k_rotate = false;   // persistent mode: XCD x starts its k loops x/8 of the way into the k range (set by the launcher)
     bool xcd_steps = false;  // persistent mode: XCD x runs steps x, x+8, ... whole (set by the launcher)
     int xcd_bands = 1;       // ... or, > 1: 8 / xcd_bands step groups x xcd_bands bands of tile columns (set by the launcher)
+    bool mfma16 = false;     // persistent mode, 256x256 tile: main loop on v_mfma_f32_16x16x32_bf16 (set by the launcher)
     const void *A_step[MAX_STEPS] = {};
     const float *recv_step[MAX_STEPS] = {};
     void *out_step[MAX_STEPS] = {};
@@ -104,6 +105,7 @@ struct Tuning {
     int k_rotate = -1;              // COMMFUSE_K_ROTATE = 0 | 1                           (-1 = unset)
     int xcd_bands = 0;              // COMMFUSE_XCD_BANDS = 1 | 2 | 4: column bands per step group (0 = unset: by shape)
     int stream_recv = -1;           // COMMFUSE_STREAM_RECV = 0 | 1                        (-1 = unset)
+    int mfma16 = -1;                // COMMFUSE_MFMA16 = 0 | 1: 16x16x32 MFMAs in the 256x256 persistent kernel (-1 = unset)
     int persist_wgs = 0;            // COMMFUSE_PERSIST_WGS = cap on the persistent kernel's grid (0 = unset)
     int carry = -1;                 // COMMFUSE_CARRY = 0: the one-launch reduce-scatter never carries its deliveries
                                     // under CF_FUSED_COPY (-1 = unset, 1: wherever the launch streams B_in)

@@ -1370,7 +1370,7 @@ static Tuning read_tuning_from_environment()
 {
     Tuning t;
     memset(&t, 0, sizeof(t));                      // (padding too: the struct is hashed byte-wise into graph keys)
-    t.deep = t.prefetch = t.xcd_steps = t.k_rotate = t.stream_recv = t.attn_qt = t.carry = -1;
+    t.deep = t.prefetch = t.xcd_steps = t.k_rotate = t.stream_recv = t.attn_qt = t.carry = t.mfma16 = -1;
     int bm = 0, bn = 0;
     if (const char *e = getenv("COMMFUSE_TILE"))
         if (sscanf(e, "%dx%d", &bm, &bn) == 2) {
@@ -1398,6 +1398,8 @@ static Tuning read_tuning_from_environment()
     }
     if (const char *e = getenv("COMMFUSE_CARRY"))
         t.carry = atoi(e) != 0;
+    if (const char *e = getenv("COMMFUSE_MFMA16"))
+        t.mfma16 = atoi(e) != 0;
     if (const char *e = getenv("COMMFUSE_PERSIST_WGS"))
         t.persist_wgs = atoi(e) > 0 ? atoi(e) : 0;
     if (const char *e = getenv("COMMFUSE_STREAM_RECV"))

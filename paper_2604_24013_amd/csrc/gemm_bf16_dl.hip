@@ -139,10 +139,18 @@ __device__ __forceinline__ int xcd_remap(int pid, int total)
 // by direct loads into an LDS landing area (no register is held while the load is in flight) and added to the
 // accumulators in mid-loop, so that the epilogue only stores.  The landing area takes the place of the third
 // left-operand stage (see the schedule below).
+// MF16: the 256x256 tile's main loop on v_mfma_f32_16x16x32_bf16 instead of v_mfma_f32_32x32x16_bf16 -- the same
+// flops from twice as many instructions that each write a quarter of the accumulator registers, which costs the chip
+// less power per flop (measured) and, where the launch is paced by the power limit, time.  A 32x32 sub-tile of the
+// accumulators is then four 16x16 tiles: registers 4g .. 4g+3 with g = 2x + y hold rows 16x + (lane & 15), columns
+// 16y + 4 (lane >> 4) .. + 3.  A k-tile is two 32-wide slices, each consumed in four quarter phases (one 32-row block
+// of the wave tile per phase).
 template <int BM, int BN, int WGM, int WGN, int NS, bool SPREAD, bool W_KN, bool OUT_BF16, bool A_T = false,
-          bool PERSIST = false, bool RLDS = false>
+          bool PERSIST = false, bool RLDS = false, bool MF16 = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams P, int tiles_m, int tiles_n)
 {
+    static_assert(!MF16 || (SPREAD && !A_T && NS == 2 && !RLDS),
+                  "16x16x32 main loop: 256x256 tile, left operand stored [m x k], B_in added in the epilogue");
     static_assert(!A_T || (W_KN && !OUT_BF16), "the transposed left operand comes with [k x n] weights and fp32 output");
     static_assert(!RLDS || (SPREAD && !OUT_BF16 && !A_T && NS == 2), "B_in through LDS: 256x256 tile, fp32 output");
     constexpr int NW = WGM * WGN;
@@ -309,7 +317,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         if constexpr (W_KN) {
             const int k = pos / W_ROWB, inrow = pos % W_ROWB;
             const int q = (inrow >> 6) ^ (k & 3);
-            const int gn = n0 + q * 32 + ((inrow >> 4) & 3) * 8;
+            // (MF16: the two 32-byte halves of a 64-byte group change places in the rows with odd k / 8: the sixteen-lane
+            // blocks of a transposing read then hold different 8-row groups of k for the SAME columns, and two
+            // blocks that are served together must not fall into the same banks)
+            const int c4 = ((inrow >> 4) & 3) ^ (MF16 ? ((k >> 3) & 1) << 1 : 0);
+            const int gn = n0 + q * 32 + c4 * 8;
             b_off[j] = gn < N ? (unsigned)(((int64_t)k * P.ldw + gn) * 2) : OOB;
         } else {
             int row, kc;
@@ -333,6 +345,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     };
     const int w_kstep = W_KN ? (int)(P.ldw * 2) : 2;   // bytes per unit of k along W
     const int a_kstep = A_T ? (int)(P.lda * 2) : 2;    // ... and along the left operand
+    // MF16 (whole tiles only: no lane is out of range): wave-load j of a tile fetches, lane by lane, what wave-load 0
+    // fetches 64 rows (16 k-rows of a [k x n] weight tile) further on, so one per-lane offset per operand is kept and
+    // the distance goes into the scalar part of the address
+    const int a_jstep = MF16 ? (int)(64 * P.lda * 2) : 0;
+    const int w_jstep = MF16 ? (int)((W_KN ? 16 : 64) * P.ldw * 2) : 0;
 
     // Direct load number `idx` (0 .. LPT-1: the A wave-loads, then the W wave-loads) of local k-tile
     // kt into `stage`.  A tile beyond the end of this split's k range is requested all the same, with
@@ -360,28 +377,28 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         const unsigned sw = lds_base + W_BASE + stage_w * B_BYTES + wave * 1024;
         if constexpr (WHOLE_K) {
             if constexpr (idx < A_LD)
-                direct_load_16(a_rsrc, a_off[idx], k0 * a_kstep, sa + idx * NW * 1024);
+                direct_load_16(a_rsrc, a_off[MF16 ? 0 : idx], k0 * a_kstep + idx * a_jstep, sa + idx * NW * 1024);
             else
-                direct_load_16(w_rsrc, b_off[idx - A_LD], k0 * w_kstep, sw + (idx - A_LD) * NW * 1024);
+                direct_load_16(w_rsrc, b_off[MF16 ? 0 : idx - A_LD], k0 * w_kstep + (idx - A_LD) * w_jstep, sw + (idx - A_LD) * NW * 1024);
             return;
         }
         const bool full = kt < nk && (k0 + BK) <= K;     // uniform: the common case needs no per-lane test
         if (full) {
             if constexpr (idx < A_LD)
-                direct_load_16(a_rsrc, a_off[idx], k0 * a_kstep, sa + idx * NW * 1024);
+                direct_load_16(a_rsrc, a_off[MF16 ? 0 : idx], k0 * a_kstep + idx * a_jstep, sa + idx * NW * 1024);
             else
-                direct_load_16(w_rsrc, b_off[idx - A_LD], k0 * w_kstep, sw + (idx - A_LD) * NW * 1024);
+                direct_load_16(w_rsrc, b_off[MF16 ? 0 : idx - A_LD], k0 * w_kstep + (idx - A_LD) * w_jstep, sw + (idx - A_LD) * NW * 1024);
         } else {
             const bool none = kt >= nk;
             const int klim = none ? -1 : K;              // chunks at k >= klim read as zero
             const int ks0 = none ? 0 : k0;
             if constexpr (idx < A_LD) {
-                const unsigned off = (k0 + chunk_k(idx, A_T, A_ROWB)) >= klim ? OOB : a_off[idx];
-                direct_load_16(a_rsrc, off, ks0 * a_kstep, sa + idx * NW * 1024);
+                const unsigned off = (k0 + chunk_k(idx, A_T, A_ROWB)) >= klim ? OOB : a_off[MF16 ? 0 : idx];
+                direct_load_16(a_rsrc, off, ks0 * a_kstep + idx * a_jstep, sa + idx * NW * 1024);
             } else {
                 constexpr int j = idx - A_LD;
-                const unsigned off = (k0 + chunk_k(j, W_KN, W_ROWB)) >= klim ? OOB : b_off[j];
-                direct_load_16(w_rsrc, off, ks0 * w_kstep, sw + j * NW * 1024);
+                const unsigned off = (k0 + chunk_k(j, W_KN, W_ROWB)) >= klim ? OOB : b_off[MF16 ? 0 : j];
+                direct_load_16(w_rsrc, off, ks0 * w_kstep + j * w_jstep, sw + j * NW * 1024);
             }
         }
     };
@@ -395,9 +412,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
 #pragma unroll
             for (int idx = lo; idx < hi; ++idx) {
                 if (idx < A_LD)
-                    direct_load_16(a_rsrc, a_off[idx < A_LD ? idx : 0], k0 * a_kstep, sa + idx * NW * 1024);
+                    direct_load_16(a_rsrc, a_off[(!MF16 && idx < A_LD) ? idx : 0], k0 * a_kstep + idx * a_jstep, sa + idx * NW * 1024);
                 else
-                    direct_load_16(w_rsrc, b_off[idx >= A_LD ? idx - A_LD : 0], k0 * w_kstep,
+                    direct_load_16(w_rsrc, b_off[(!MF16 && idx >= A_LD) ? idx - A_LD : 0], k0 * w_kstep + (idx - A_LD) * w_jstep,
                                    sw + (idx - A_LD) * NW * 1024);
             }
         } else {
@@ -416,14 +433,49 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         }
     };
 
-    f32x16_t acc[TM][TN];
+    // (MF16: the accumulators as the 16x16 tiles the MFMAs write, acc4[i][j][g] = registers 4g .. 4g+3 of sub-tile (i, j))
+    f32x16_t acc[MF16 ? 1 : TM][MF16 ? 1 : TN];
+    f32x4_t acc4[MF16 ? TM : 1][MF16 ? TN : 1][4];
+    if constexpr (MF16) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                acc[i][j][e] = 0.0f;
+                for (int g = 0; g < 4; ++g)
+                    acc4[i][j][g] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+    } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    acc[i][j][e] = 0.0f;
+    }
+    // registers 4g .. 4g+3 of sub-tile (i, j)
+    auto acc_get = [&](int i, int j, int g) __attribute__((always_inline)) {
+        if constexpr (MF16) {
+            return acc4[i][j][g];
+        } else {
+            f32x4_t o;
+            o[0] = acc[i][j][4 * g + 0];
+            o[1] = acc[i][j][4 * g + 1];
+            o[2] = acc[i][j][4 * g + 2];
+            o[3] = acc[i][j][4 * g + 3];
+            return o;
+        }
+    };
+    auto acc_set = [&](int i, int j, int g, f32x4_t v) __attribute__((always_inline)) {
+        if constexpr (MF16) {
+            acc4[i][j][g] = v;
+        } else {
+            acc[i][j][4 * g + 0] = v[0];
+            acc[i][j][4 * g + 1] = v[1];
+            acc[i][j][4 * g + 2] = v[2];
+            acc[i][j][4 * g + 3] = v[3];
+        }
+    };
 
     // All-gather with the delivery carried by the consumer (GemmParams::land_step): the left operand comes in from the
     // neighbour's buffer, and each of its k-tiles is stored on to the landing buffer by ONE of the workgroups that
@@ -440,7 +492,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
 #pragma unroll
         for (int j = 0; j < A_LD; ++j) {
             const u32x4_t t = *reinterpret_cast<const u32x4_t *>(smem + stage_a * A_BYTES + (j * NW + wave) * 1024 + lane * 16);
-            __builtin_amdgcn_raw_buffer_store_b128(t, la_rsrc, (int)a_off[j], k0 * 2, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(t, la_rsrc, (int)a_off[MF16 ? 0 : j], k0 * 2 + j * a_jstep, 0);
         }
         carry_at += tiles_n;
     };
@@ -477,6 +529,30 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         w_addr[0] = W_BASE + swz_row(wn * WTN + frow, fkc);
     }
 
+    // MF16: a fragment is 16 rows x 32 k: lane L holds row (L & 15), the 16-byte chunk (L >> 4) of the 32-wide slice;
+    // the second slice of a k-tile is reached by XOR-ing 64 into the offset, 16-row tiles lie 2 KiB apart.
+    constexpr int TN16 = WTN / 16;
+    int a_addr16 = 0;
+    // ([k x n] weights: one address per pair of 16-column tiles; the odd tile of a pair lies at that address ^ 32)
+    int w_addr16[(MF16 && W_KN) ? TN16 / 2 : 1];
+    if constexpr (MF16) {
+        static_assert(!MF16 || (TM == 4 && TN == 2), "quarter phases are written for the 128x64 wave tile");
+        a_addr16 = swz_row(wm * WTM + (lane & 15), lane >> 4);
+        if constexpr (W_KN) {
+            const int blk = lane >> 4, i16 = lane & 15;
+            const int kl = blk * 8 + (i16 >> 2);                             // k of (slice 0, first half)
+#pragma unroll
+            for (int t = 0; t < TN16; t += 2) {
+                const int nl = wn * WTN + t * 16 + (i16 & 3) * 4;
+                const int q = (nl >> 5) ^ (kl & 3);
+                w_addr16[t / 2] = W_BASE + kl * W_ROWB + (q << 6) + (((nl & 31) * 2) ^ (((kl >> 3) & 1) << 5));
+            }
+        } else {
+            w_addr16[0] = W_BASE + swz_row(wn * WTN + (lane & 15), lane >> 4);
+        }
+    } else {
+        w_addr16[0] = 0;
+    }
     auto read_frags = [&](int stage_a, int stage_w, int ks, bf16x8_t (&af)[TM], bf16x8_t (&wf)[TN]) __attribute__((always_inline)) {
         const unsigned char *st = smem + stage_a * A_BYTES;
         const unsigned char *stw = smem + stage_w * B_BYTES;     // (w_addr holds the weight region's base)
@@ -611,7 +687,182 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // the left-operand stage whose memory serves as the wave-private scratch of the epilogue's stores (and, RLDS, as
     // the landing area of B_in before)
     int land_stage = SPREAD ? NSA - 1 : 0;
-    if constexpr (SPREAD) {
+    if constexpr (SPREAD && MF16) {
+        // The schedule of the 256x256 tile (see the variant below for its reasoning) on 16x16x32 MFMAs.  A k-tile is two
+        // 32-wide slices; a slice is consumed in four quarter phases, phase p = the wave tile's 32-row block p:
+        // 2 left-operand fragments (16-row tiles x = 0, 1) x 4 weight fragments = 8 MFMAs, in four segments of two
+        // (segments 0, 1: x = 0; segments 2, 3: x = 1).  A phase is short (128 cycles of MFMA issue), so LDS reads and
+        // direct loads are dealt out thinly -- at most one fragment read and one direct load per segment -- and every
+        // fragment register is refilled as soon as its last MFMA has issued, a phase and a half before its next use:
+        // the left-operand fragments live in two buffers that alternate by phase (afA: even phases), and phase q reads
+        //     at segment 0: fragment x = 1 of phase q+1, into the other buffer (its last use was in phase q-1);
+        //     at segment 2: fragment x = 0 of phase q+2, into its own buffer;
+        // the weight fragments live in two buffers that alternate by slice; those of slice 1 are read one per phase in
+        // phases 0 .. 3, those of slice 0 of the next tile two per phase in phases 6 and 7 (segments 1 and 3).
+        //   steady state, tile kt (phases 0 .. 7 = slice 0 blocks 0 .. 3, slice 1 blocks 0 .. 3):
+        //     phases 0 .. 3: + one left-operand load of tile kt+NS each, into the stage tile kt-1 vacated
+        //     phase 6, after segment 0 (the last read of tile kt has been issued):
+        //              wait: tile kt+1 complete; barrier: tile kt has been read by all;
+        //              then the first reads of tile kt+1, and in phases 6 and 7 + two weight loads of tile kt+NS each
+        static_assert(A_LD == 4 && B_LD == 4, "load slots below: four loads per operand, tile and wave");
+        using p0_t = std::integral_constant<int, 0>;
+        using p1_t = std::integral_constant<int, 1>;
+        using p2_t = std::integral_constant<int, 2>;
+        using p3_t = std::integral_constant<int, 3>;
+        using c1 = std::integral_constant<int, 1>;
+        using c2 = std::integral_constant<int, 2>;
+        using on_t = std::true_type;
+        using off_t = std::false_type;
+        bf16x8_t afA[2], afB[2], wfA[4], wfB[4];
+        // the two MFMAs of segment seg of a phase on block PB: 16-row tile x = seg / 2, 16-column tiles 2 (seg & 1) + {0, 1}
+        auto mfma16_seg = [&](auto pb_tag, const bf16x8_t (&af)[2], const bf16x8_t (&wf)[4], auto seg_tag) __attribute__((always_inline)) {
+            constexpr int PB = decltype(pb_tag)::value, seg = decltype(seg_tag)::value;
+            constexpr int x = seg >> 1, j = seg & 1;
+#pragma unroll
+            for (int y = 0; y < 2; ++y) {
+                const int g = 2 * x + y;
+                acc4[MF16 ? PB : 0][MF16 ? j : 0][g] =
+                    __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[2 * j + y], af[x], acc4[MF16 ? PB : 0][MF16 ? j : 0][g], 0, 0, 0);
+            }
+        };
+        auto frag_a16 = [&](int stage_a, int sl, int t16) __attribute__((always_inline)) {
+            return *reinterpret_cast<const bf16x8_t *>(smem + stage_a * A_BYTES + (a_addr16 ^ (sl << 6)) + t16 * 2048);
+        };
+        auto frag_w16 = [&](int stage_w, int sl, auto t_tag) __attribute__((always_inline)) {
+            constexpr int t = decltype(t_tag)::value;
+            const unsigned char *stw = smem + stage_w * B_BYTES;
+            if constexpr (W_KN) {
+                const unsigned char *pw = stw + (w_addr16[(MF16 && W_KN) ? t / 2 : 0] ^ ((t & 1) << 5)) + sl * 32 * W_ROWB;
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(pw));
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t *)(pw + 4 * W_ROWB));
+                const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                return __builtin_bit_cast(bf16x8_t, both);
+            } else {
+                return *reinterpret_cast<const bf16x8_t *>(stw + (w_addr16[0] ^ (sl << 6)) + t * 2048);
+            }
+        };
+        constexpr int NRD_WF = W_KN ? 2 : 1;                 // LDS reads of one weight fragment
+        auto nothing = [&]() __attribute__((always_inline)) {};
+        // One quarter phase on block PB with the fragments (afc, wfc).
+        //   r1: fragment x = 1 of (stage s1, slice l1, block b1) into afo[1] at segment 0;  mid(): between segments 0 and 1;
+        //   nwf weight fragments w0, w0 + 1 of (stage sw, slice lw) into wfn at segments 1 and 3;
+        //   r2: fragment x = 0 of (s2, l2, b2) into afc[0] at segment 2;
+        //   ld1(), ld3(): direct loads issued at segments 1 and 3.
+        auto phase16 = [&](auto pb_tag, bf16x8_t (&afc)[2], const bf16x8_t (&wfc)[4], bf16x8_t (&afo)[2], bf16x8_t (&wfn)[4],
+                           auto r1_tag, int s1, int l1, int b1, auto mid, auto nwf_tag, int sw, int lw, auto w0_tag,
+                           auto r2_tag, int s2, int l2, int b2, auto ld1, auto ld3) __attribute__((always_inline)) {
+            constexpr bool R1 = decltype(r1_tag)::value, R2 = decltype(r2_tag)::value;
+            constexpr int NWF = decltype(nwf_tag)::value, W0 = decltype(w0_tag)::value;
+            if constexpr (R1)
+                afo[1] = frag_a16(s1, l1, 2 * b1 + 1);
+            mfma16_seg(pb_tag, afc, wfc, std::integral_constant<int, 0>{});
+            interleave_mfma_reads<R1 ? 1 : 0, 1>();
+            __builtin_amdgcn_sched_barrier(0);
+            mid();
+            if constexpr (NWF > 0)
+                wfn[W0] = frag_w16(sw, lw, std::integral_constant<int, W0>{});
+            ld1();
+            mfma16_seg(pb_tag, afc, wfc, std::integral_constant<int, 1>{});
+            interleave_mfma_reads<((NWF > 0) ? NRD_WF : 0), 1>();
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (R2)
+                afc[0] = frag_a16(s2, l2, 2 * b2);
+            mfma16_seg(pb_tag, afc, wfc, std::integral_constant<int, 2>{});
+            interleave_mfma_reads<R2 ? 1 : 0, 1>();
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (NWF > 1)
+                wfn[W0 + 1] = frag_w16(sw, lw, std::integral_constant<int, W0 + 1>{});
+            ld3();
+            mfma16_seg(pb_tag, afc, wfc, std::integral_constant<int, 3>{});
+            interleave_mfma_reads<((NWF > 1) ? NRD_WF : 0), 1>();
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        // Phases 0 .. 5 of a tile in stages (ca, cw); ldq(q): the direct load phase q (0 .. 3) issues (at its segment 1).
+        auto front16 = [&](int ca, int cw, auto ld0, auto ld1_, auto ld2, auto ld3_, auto ph2) __attribute__((always_inline)) {
+            phase16(p0_t{}, afA, wfA, afB, wfB, on_t{}, ca, 0, 1, nothing, c1{}, cw, 1, c0{}, on_t{}, ca, 0, 2, ld0, nothing);
+            phase16(p1_t{}, afB, wfA, afA, wfB, on_t{}, ca, 0, 2, nothing, c1{}, cw, 1, c1{}, on_t{}, ca, 0, 3, ld1_, nothing);
+            ph2(ld2);
+            phase16(p3_t{}, afB, wfA, afA, wfB, on_t{}, ca, 1, 0, nothing, c1{}, cw, 1, std::integral_constant<int, 3>{}, on_t{}, ca, 1, 1, ld3_, nothing);
+            phase16(p0_t{}, afA, wfB, afB, wfA, on_t{}, ca, 1, 1, nothing, c0{}, 0, 0, c0{}, on_t{}, ca, 1, 2, nothing, nothing);
+            phase16(p1_t{}, afB, wfB, afA, wfA, on_t{}, ca, 1, 2, nothing, c0{}, 0, 0, c0{}, on_t{}, ca, 1, 3, nothing, nothing);
+        };
+        // phase 2 of a tile in stages (ca, cw) as a plain phase
+        auto plain_ph2 = [&](int ca, int cw) __attribute__((always_inline)) {
+            return [&, ca, cw](auto ld2) __attribute__((always_inline)) {
+                phase16(p2_t{}, afA, wfA, afB, wfB, on_t{}, ca, 0, 3, nothing, c1{}, cw, 1, c2{}, on_t{}, ca, 1, 0, ld2, nothing);
+            };
+        };
+
+    #pragma unroll
+        for (int t = 0; t < NS; ++t)
+            issue_range(t, t, t, c0{}, cLPT{});
+        wait_vmcnt<(NS - 1) * LPT>();
+        __syncthreads();
+        afA[0] = frag_a16(0, 0, 0);
+        afA[1] = frag_a16(0, 0, 1);
+        afB[0] = frag_a16(0, 0, 2);
+        wfA[0] = frag_w16(0, 0, std::integral_constant<int, 0>{});
+        wfA[1] = frag_w16(0, 0, std::integral_constant<int, 1>{});
+        wfA[2] = frag_w16(0, 0, std::integral_constant<int, 2>{});
+        wfA[3] = frag_w16(0, 0, std::integral_constant<int, 3>{});
+        __builtin_amdgcn_sched_barrier(0);
+
+        int cur_a = 0, cur_w = 0;                        // stages of tile kt
+        int prev_a = NSA - 1;                            // left-operand stage of tile kt-1 (= of tile kt+NS)
+        auto body = [&](int kt, int ca, int cw, int pa, int na, int nw_, auto wk) __attribute__((always_inline)) {
+            auto la = [&](auto idx_tag) __attribute__((always_inline)) {       // a left-operand load of tile kt+NS
+                return [&, kt, pa](/*no args*/) __attribute__((always_inline)) { issue_load(kt + NS, pa, 0, decltype(idx_tag){}, wk); };
+            };
+            auto lw = [&](auto idx_tag) __attribute__((always_inline)) {       // a weight load of tile kt+NS
+                return [&, kt, cw]() __attribute__((always_inline)) { issue_load(kt + NS, 0, cw, decltype(idx_tag){}, wk); };
+            };
+            front16(ca, cw, la(std::integral_constant<int, 0>{}), la(std::integral_constant<int, 1>{}),
+                    la(std::integral_constant<int, 2>{}), la(std::integral_constant<int, 3>{}), plain_ph2(ca, cw));
+            auto publish = [&]() __attribute__((always_inline)) {
+                if (CARRY_A && kt == carry_at) {     // tile kt goes on to the landing buffer: its stores are the
+                    carry_tile(kt, ca);              // youngest requests and need not be awaited here
+                    wait_vmcnt<(NS - 2) * LPT + 2 * A_LD>();
+                } else {
+                    wait_vmcnt<(NS - 2) * LPT + A_LD>();
+                }
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            phase16(p2_t{}, afA, wfB, afB, wfA, on_t{}, ca, 1, 3, publish, c2{}, nw_, 0, c0{}, on_t{}, na, 0, 0,
+                    lw(std::integral_constant<int, 4>{}), lw(std::integral_constant<int, 5>{}));
+            phase16(p3_t{}, afB, wfB, afA, wfA, on_t{}, na, 0, 0, nothing, c2{}, nw_, 0, c2{}, on_t{}, na, 0, 1,
+                    lw(std::integral_constant<int, 6>{}), lw(std::integral_constant<int, 7>{}));
+        };
+        // first iteration that tests its loads (all of them when K is a multiple of the k-tile: none does)
+        const int tested_at = K % BK == 0 ? nk - 1 : ((rot == 0 && nk - 1 > NS) ? nk - 1 - NS : 0);
+        int kt = 0;
+        for (; kt < tested_at; ++kt) {
+            const int nxt_a = (cur_a + 1 == NSA) ? 0 : cur_a + 1;
+            const int nxt_w = (cur_w + 1 == NS) ? 0 : cur_w + 1;
+            body(kt, cur_a, cur_w, prev_a, nxt_a, nxt_w, std::true_type{});
+            prev_a = cur_a;
+            cur_a = nxt_a;
+            cur_w = nxt_w;
+        }
+        // the last tile of a work item: nothing follows it
+        auto last16 = [&](int ca, int cw) __attribute__((always_inline)) {
+            front16(ca, cw, nothing, nothing, nothing, nothing, plain_ph2(ca, cw));
+            phase16(p2_t{}, afA, wfB, afB, wfA, on_t{}, ca, 1, 3, nothing, c0{}, 0, 0, c0{}, off_t{}, 0, 0, 0, nothing, nothing);
+            if (CARRY_A && nk - 1 == carry_at)
+                carry_tile(nk - 1, ca);
+            phase16(p3_t{}, afB, wfB, afA, wfA, off_t{}, 0, 0, 0, nothing, c0{}, 0, 0, c0{}, off_t{}, 0, 0, 0, nothing, nothing);
+        };
+        for (; kt + 1 < nk; ++kt) {
+            const int nxt_a = (cur_a + 1 == NSA) ? 0 : cur_a + 1;
+            const int nxt_w = (cur_w + 1 == NS) ? 0 : cur_w + 1;
+            body(kt, cur_a, cur_w, prev_a, nxt_a, nxt_w, std::false_type{});
+            prev_a = cur_a;
+            cur_a = nxt_a;
+            cur_w = nxt_w;
+        }
+        if (nk > 0)
+            last16(cur_a, cur_w);
+    } else if constexpr (SPREAD) {
         // The left-operand tile has NS+1 stages, the weight tile NS (tile t lives in stages t mod (NS+1) and
         // t mod NS).  Loads return in issue order, so what is issued first must be what is needed first:
         //   prologue: tiles 0 .. NS-1 whole, in tile order; tile 0 is awaited, its first fragments fetched
@@ -908,6 +1159,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     }
     wait_vmcnt<0>();                                 // no direct load may outlive its LDS allocation
 
+    // Row and first column (of four) of accumulator registers 4g .. 4g+3 of this lane's 32x32 sub-tile (i, j).
+    auto e_row = [&](int i, int g) __attribute__((always_inline)) {
+        return MF16 ? m0 + wm * WTM + i * 32 + 16 * (g >> 1) + (lane & 15) : m0 + wm * WTM + i * 32 + (lane & 31);
+    };
+    auto e_col = [&](int j, int g) __attribute__((always_inline)) {
+        return MF16 ? n0 + wn * WTN + j * 32 + 16 * (g & 1) + 4 * (lane >> 4) : n0 + wn * WTN + j * 32 + g * 8 + (lane >> 5) * 4;
+    };
+
     // Split-K: every split parks its fp32 partial tile in the workspace; the split that finishes
     // last sums all partials in split order (so the result does not depend on which one that is),
     // then runs the epilogue.  No split ever waits for another.
@@ -922,18 +1181,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             __builtin_amdgcn_make_buffer_rsrc(P.ws + (size_t)split * plane, 0, (int)(plane * 4), 0x00020000);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            const int m = m0 + wm * WTM + i * 32 + (lane & 31);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int n = n0 + wn * WTN + j * 32 + g * 8 + (lane >> 5) * 4;
+                    const int m = e_row(i, g), n = e_col(j, g);
                     const int boff = (m < M && n < N) ? (int)(((unsigned)m * (unsigned)N + n) * 4u) : (int)OOB;
-                    f32x4_t o;
-                    o[0] = acc[i][j][4 * g + 0];
-                    o[1] = acc[i][j][4 * g + 1];
-                    o[2] = acc[i][j][4 * g + 2];
-                    o[3] = acc[i][j][4 * g + 3];
+                    const f32x4_t o = acc_get(i, j, g);
                     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, o), ws_rsrc, boff, 0, COHERENT);
                 }
         }
@@ -949,12 +1203,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             __hip_atomic_store(&P.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            const int m = m0 + wm * WTM + i * 32 + (lane & 31);
 #pragma unroll
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int n = n0 + wn * WTN + j * 32 + g * 8 + (lane >> 5) * 4;
+                    const int m = e_row(i, g), n = e_col(j, g);
                     const int boff = (m < M && n < N) ? (int)(((unsigned)m * (unsigned)N + n) * 4u) : (int)OOB;
                     f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
                     for (int sp = 0; sp < splits; ++sp) {
@@ -964,10 +1217,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                             __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(rs, boff, 0, COHERENT));
                         sum = sp == 0 ? v : sum + v;
                     }
-                    acc[i][j][4 * g + 0] = sum[0];
-                    acc[i][j][4 * g + 1] = sum[1];
-                    acc[i][j][4 * g + 2] = sum[2];
-                    acc[i][j][4 * g + 3] = sum[3];
+                    acc_set(i, j, g, sum);
                 }
         }
     }
@@ -986,14 +1236,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     const bool recv_coherent = cFlag != nullptr && !P.wait_at_start;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int m = m0 + wm * WTM + i * 32 + (lane & 31);
         unsigned eoff[TN][4];
         f32x4_t rv[TN][4];
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int n = n0 + wn * WTN + j * 32 + g * 8 + (lane >> 5) * 4;
+                const int m = e_row(i, g), n = e_col(j, g);
                 eoff[j][g] = (m < M && n < N) ? (unsigned)((int64_t)m * P.ldo + n) : OOB;
             }
         if (PF && pf_on) {
@@ -1045,11 +1294,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         for (int j = 0; j < TN; ++j) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                f32x4_t o;
-                o[0] = acc[i][j][4 * g + 0];
-                o[1] = acc[i][j][4 * g + 1];
-                o[2] = acc[i][j][4 * g + 2];
-                o[3] = acc[i][j][4 * g + 3];
+                f32x4_t o = acc_get(i, j, g);
                 if (has_recv && !streamed)
                     o = rv[j][g] + o;                                    // "O <- B_in + O"
                 if constexpr (OUT_BF16) {
@@ -1060,10 +1305,21 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                     h[1] = static_cast<__bf16>(o[1]);
                     h[2] = static_cast<__bf16>(o[2]);
                     h[3] = static_cast<__bf16>(o[3]);
+                    if constexpr (MF16) {
+                        // row 16 (g / 2) + (lane & 15), columns 32 j + 16 (g & 1) + 4 (lane >> 4) .. + 3 of the row block
+                        const int r = 16 * (g >> 1) + (lane & 15);
+                        const int ch = j * 4 + 2 * (g & 1) + (lane >> 5);
+                        *reinterpret_cast<bf16x4_t *>(scr + r * 128 + ((ch ^ (r & 7)) << 4) + ((lane >> 4) & 1) * 8) = h;
+                    } else
                     *reinterpret_cast<bf16x4_t *>(scr + (lane & 31) * 128 + (((j * 4 + g) ^ (lane & 7)) << 4) + (lane >> 5) * 8) = h;
                 } else {
                     // plane g of the 32x32 sub-tile (i, j), the rows permuted within the plane (row ^ chunk number:
                     // the chunks of a row lie 512 bytes apart and would all fall into one bank otherwise)
+                    if constexpr (MF16) {
+                        // chunk c = 4 (g & 1) + (lane >> 4) of row r = 16 (g / 2) + (lane & 15): plane c / 2, slot (r ^ c) + 32 (c & 1)
+                        const int r = 16 * (g >> 1) + (lane & 15), c = 4 * (g & 1) + (lane >> 4);
+                        *reinterpret_cast<f32x4_t *>(scr + (c >> 1) * 1024 + ((32 * (c & 1) + (r ^ c)) << 4)) = o;
+                    } else
                     *reinterpret_cast<f32x4_t *>(scr + g * 1024 + (((lane & 32) | ((lane & 31) ^ (2 * g + (lane >> 5)))) << 4)) = o;
                 }
             }
@@ -1133,27 +1389,37 @@ hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t
     if (p.n_steps > 0) {                             // persistent rank step: fp32 or bf16 output, either weight order
         if (p.a_t)
             return hipErrorInvalidValue;
+        // (256x256 tile: the main loop on 16x16x32 MFMAs where the launcher asks for it, GemmParams::mfma16)
+#define CF_LAUNCH_PERSIST(WKN, OBF, RL)                                                                                         \
+    do {                                                                                                                        \
+        if constexpr (SPREAD && NS == 2) {                                                                                      \
+            if (p.mfma16 && !(RL))                                                                                              \
+                hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, WKN, OBF, false, true, false, true>),    \
+                                   grid, block, 0, s, p, tiles_m, tiles_n);                                                     \
+            else                                                                                                                \
+                hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, WKN, OBF, false, true, RL>), grid, block, \
+                                   0, s, p, tiles_m, tiles_n);                                                                  \
+        } else {                                                                                                                \
+            hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, WKN, OBF, false, true, false>), grid, block,  \
+                               0, s, p, tiles_m, tiles_n);                                                                      \
+        }                                                                                                                       \
+    } while (0)
         if (w_kn) {
             if (out_bf16)
-                hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, true, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
-            else if constexpr (SPREAD && NS == 2) {
-                if (rlds)
-                    hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, false, false, true, true>), grid, block, 0, s, p, tiles_m, tiles_n);
-                else
-                    hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, false, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
-            } else
-                hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, true, false, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
+                CF_LAUNCH_PERSIST(true, true, false);
+            else if (SPREAD && NS == 2 && rlds)
+                CF_LAUNCH_PERSIST(true, false, true);
+            else
+                CF_LAUNCH_PERSIST(true, false, false);
         } else {
             if (out_bf16)
-                hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, false, true, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
-            else if constexpr (SPREAD && NS == 2) {
-                if (rlds)
-                    hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, false, false, false, true, true>), grid, block, 0, s, p, tiles_m, tiles_n);
-                else
-                    hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, false, false, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
-            } else
-                hipLaunchKernelGGL((gemm_bf16_dl_kernel<BM, BN, WGM, WGN, NS, SPREAD, false, false, false, true>), grid, block, 0, s, p, tiles_m, tiles_n);
+                CF_LAUNCH_PERSIST(false, true, false);
+            else if (SPREAD && NS == 2 && rlds)
+                CF_LAUNCH_PERSIST(false, false, true);
+            else
+                CF_LAUNCH_PERSIST(false, false, false);
         }
+#undef CF_LAUNCH_PERSIST
         return hipGetLastError();
     }
     if (p.a_t) {
@@ -1276,6 +1542,8 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
         // (measured with whole steps per XCD only; a ragged k tail stays the last k-tile of every work item,
         // which keeps all earlier iterations of the 256x256 main loop branch-free)
         p.k_rotate = p.xcd_steps && tn.k_rotate != 0 && p.K % BK == 0;
+        // the 256x256 tile's main loop on 16x16x32 MFMAs (override: COMMFUSE_MFMA16 = 0 | 1)
+        p.mfma16 = t.bm == 256 && t.bn == 256 && p.M % 256 == 0 && p.N % 256 == 0 && tn.mfma16 != 0;
     }
     if (p.splits > 1 && (p.ws == nullptr || p.counters == nullptr ||
                          (size_t)p.splits * p.M * p.N * sizeof(float) > p.ws_bytes || tiles > p.max_tiles ||

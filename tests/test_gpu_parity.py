@@ -666,6 +666,55 @@ def test_persistent_step_groups_and_column_bands(tile, bands):
         _tile_env(None)
 
 
+@pytest.mark.parametrize("k", [64, 192, 456, 1032])        # one k-tile, three, a ragged eighth, seventeen with a ragged tail
+@pytest.mark.parametrize("mfma16", ["1", "0"])
+def test_persistent_mfma16_main_loop(k, mfma16):
+    """The 256x256 tile of the one-launch rank step runs its main loop on 16x16x32 MFMAs where the steps are whole
+    tiles and B_in is added in the epilogue (COMMFUSE_MFMA16 = 0 keeps the 32x32x16 loop).  The accumulator
+    layout, the fragment reads and the order of the [k x n] weight tile in LDS all differ between the two, so both are
+    compared with the oracle here: reduce-scatter (every step's B_out and O), all-gather with fp32 and bf16 output,
+    both weight orders, granularity 1 and 2, the deliveries copied in front and carried by the kernel."""
+    rank = 5
+    os.environ["COMMFUSE_MFMA16"] = mfma16
+    _tile_env("256x256")
+    try:
+        for m, m_chunk, n in ((1, 256, 512), (2, 512, 768)):
+            w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=8, m_chunk=m_chunk, n=n, k=k)
+            data = inputs.make_rs(w, salt=81 + k)
+            ref = _oracle_rs(w, data, rank)
+            for layout in (cf.CF_W_KN, cf.CF_W_NK):
+                run = H.RsRun(w, data, rank, layout, m=m, each=True)
+                for t in run.each + run.send_each + [run.O]:
+                    t.fill_(float("nan"))
+                run.run_schedule(PERSISTENT_SERIAL)
+                cf.device_status(run.cs)
+                for i in range(w.p):
+                    got = H.to_host_f64(run.send_each[i] if i < w.p - 1 else run.O)
+                    e = H.rel_err(got, ref[i])
+                    assert e <= TIGHT_BF16, f"rs m {m} layout {layout} step {i}: {e:.3e}"
+            for out_dtype in ("bf16", "f32"):
+                wa = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=8, m_chunk=m_chunk, n=n, k=k, out_dtype=out_dtype)
+                da = inputs.make_ag(wa, salt=82 + k)
+                refa = _oracle_ag(wa, da, rank)
+                for layout, flags in ((cf.CF_W_KN, PERSISTENT_SERIAL), (cf.CF_W_NK, PERSISTENT_SERIAL | cf.CF_FUSED_COPY),
+                                      (cf.CF_W_KN, PERSISTENT_SERIAL | cf.CF_FUSED_COPY)):
+                    ag = H.AgRun(wa, da, rank, layout, m=m, each=True)
+                    ag.O.fill_(float("nan"))
+                    for t in ag.each:
+                        t.fill_(float("nan"))
+                    ag.run_schedule(flags)
+                    cf.device_status(ag.cs)
+                    o = H.to_host_f64(ag.O)
+                    assert not np.isnan(o).any(), f"ag {out_dtype} m {m} layout {layout} flags {flags}"
+                    e = H.rel_err(o, refa)
+                    assert e <= (TIGHT_BF16_OUT if out_dtype == "bf16" else TIGHT_BF16), f"ag {out_dtype} m {m} layout {layout} flags {flags}: {e:.3e}"
+                    for i in range(wa.p - 1):
+                        assert torch.equal(ag.each[i], ag.stage[i]), f"ag {out_dtype} m {m} layout {layout} flags {flags}: hop {i + 1}"
+    finally:
+        os.environ.pop("COMMFUSE_MFMA16", None)
+        _tile_env(None)
+
+
 @pytest.mark.parametrize("kind", ["rs", "ag"])
 def test_persistent_k_rotation(kind):
     """The persistent launch lets the workgroups of XCD x start their k loops x/8 of the way into the k range
