@@ -317,10 +317,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         if constexpr (W_KN) {
             const int k = pos / W_ROWB, inrow = pos % W_ROWB;
             const int q = (inrow >> 6) ^ (k & 3);
-            // (MF16: the two 32-byte halves of a 64-byte group change places in the rows with odd k / 8: the sixteen-lane
-            // blocks of a transposing read then hold different 8-row groups of k for the SAME columns, and two
-            // blocks that are served together must not fall into the same banks)
-            const int c4 = ((inrow >> 4) & 3) ^ (MF16 ? ((k >> 3) & 1) << 1 : 0);
+            // (MF16: the two 32-byte halves of a 64-byte group change places in the rows with odd k / 16: the sixteen-lane
+            // blocks of a transposing read then hold different 8-row groups of k for the SAME columns, and the two
+            // blocks that are served together -- lanes 0..15 and 16..31: k / 8 = 0 and 2, or 1 and 3, see the
+            // fragment addressing -- must not fall into the same banks)
+            const int c4 = ((inrow >> 4) & 3) ^ (MF16 ? ((k >> 4) & 1) << 1 : 0);
             const int gn = n0 + q * 32 + c4 * 8;
             b_off[j] = gn < N ? (unsigned)(((int64_t)k * P.ldw + gn) * 2) : OOB;
         } else {
@@ -346,10 +347,15 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     const int w_kstep = W_KN ? (int)(P.ldw * 2) : 2;   // bytes per unit of k along W
     const int a_kstep = A_T ? (int)(P.lda * 2) : 2;    // ... and along the left operand
     // MF16 (whole tiles only: no lane is out of range): wave-load j of a tile fetches, lane by lane, what wave-load 0
-    // fetches 64 rows (16 k-rows of a [k x n] weight tile) further on, so one per-lane offset per operand is kept and
-    // the distance goes into the scalar part of the address
+    // fetches 64 rows further on (a [k x n] weight tile: what wave-load j - 2 fetches 32 k-rows further on -- the
+    // 32-byte halves change places every 16 k-rows), so one per-lane offset per operand (two for [k x n] weights) is
+    // kept and the distance goes into the scalar part of the address
+    constexpr int W_JP = (MF16 && W_KN) ? 2 : 1;     // wave-loads of a weight tile with an offset register of their own
     const int a_jstep = MF16 ? (int)(64 * P.lda * 2) : 0;
     const int w_jstep = MF16 ? (int)((W_KN ? 16 : 64) * P.ldw * 2) : 0;
+    // per-lane offset register and scalar distance of weight wave-load j
+    auto w_reg = [](int j) { return MF16 ? j % W_JP : j; };
+    auto w_dist = [&](int j) __attribute__((always_inline)) { return (j - j % W_JP) * w_jstep; };
 
     // Direct load number `idx` (0 .. LPT-1: the A wave-loads, then the W wave-loads) of local k-tile
     // kt into `stage`.  A tile beyond the end of this split's k range is requested all the same, with
@@ -379,7 +385,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             if constexpr (idx < A_LD)
                 direct_load_16(a_rsrc, a_off[MF16 ? 0 : idx], k0 * a_kstep + idx * a_jstep, sa + idx * NW * 1024);
             else
-                direct_load_16(w_rsrc, b_off[MF16 ? 0 : idx - A_LD], k0 * w_kstep + (idx - A_LD) * w_jstep, sw + (idx - A_LD) * NW * 1024);
+                direct_load_16(w_rsrc, b_off[w_reg(idx - A_LD)], k0 * w_kstep + w_dist(idx - A_LD), sw + (idx - A_LD) * NW * 1024);
             return;
         }
         const bool full = kt < nk && (k0 + BK) <= K;     // uniform: the common case needs no per-lane test
@@ -387,7 +393,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             if constexpr (idx < A_LD)
                 direct_load_16(a_rsrc, a_off[MF16 ? 0 : idx], k0 * a_kstep + idx * a_jstep, sa + idx * NW * 1024);
             else
-                direct_load_16(w_rsrc, b_off[MF16 ? 0 : idx - A_LD], k0 * w_kstep + (idx - A_LD) * w_jstep, sw + (idx - A_LD) * NW * 1024);
+                direct_load_16(w_rsrc, b_off[w_reg(idx - A_LD)], k0 * w_kstep + w_dist(idx - A_LD), sw + (idx - A_LD) * NW * 1024);
         } else {
             const bool none = kt >= nk;
             const int klim = none ? -1 : K;              // chunks at k >= klim read as zero
@@ -397,8 +403,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 direct_load_16(a_rsrc, off, ks0 * a_kstep + idx * a_jstep, sa + idx * NW * 1024);
             } else {
                 constexpr int j = idx - A_LD;
-                const unsigned off = (k0 + chunk_k(j, W_KN, W_ROWB)) >= klim ? OOB : b_off[MF16 ? 0 : j];
-                direct_load_16(w_rsrc, off, ks0 * w_kstep + j * w_jstep, sw + j * NW * 1024);
+                const unsigned off = (k0 + chunk_k(j, W_KN, W_ROWB)) >= klim ? OOB : b_off[w_reg(j)];
+                direct_load_16(w_rsrc, off, ks0 * w_kstep + w_dist(j), sw + j * NW * 1024);
             }
         }
     };
@@ -414,7 +420,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 if (idx < A_LD)
                     direct_load_16(a_rsrc, a_off[(!MF16 && idx < A_LD) ? idx : 0], k0 * a_kstep + idx * a_jstep, sa + idx * NW * 1024);
                 else
-                    direct_load_16(w_rsrc, b_off[(!MF16 && idx >= A_LD) ? idx - A_LD : 0], k0 * w_kstep + (idx - A_LD) * w_jstep,
+                    direct_load_16(w_rsrc, b_off[idx >= A_LD ? w_reg(idx - A_LD) : 0], k0 * w_kstep + w_dist(idx - A_LD),
                                    sw + (idx - A_LD) * NW * 1024);
             }
         } else {
@@ -529,26 +535,30 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         w_addr[0] = W_BASE + swz_row(wn * WTN + frow, fkc);
     }
 
-    // MF16: a fragment is 16 rows x 32 k: lane L holds row (L & 15), the 16-byte chunk (L >> 4) of the 32-wide slice;
-    // the second slice of a k-tile is reached by XOR-ing 64 into the offset, 16-row tiles lie 2 KiB apart.
+    // MF16: a fragment is 16 rows x 32 k: lane L holds row (L & 15) and one 16-byte chunk (8 k) of the 32-wide slice --
+    // chunk 0, 2, 1, 3 for the lane blocks L >> 4 = 0, 1, 2, 3 (which eight k values sit in which slots of the
+    // contraction is free as long as both operands agree; a 16-byte read serves the lanes L and L + 32 together, and
+    // with an even and an odd chunk the two fall into different banks: counted, 4 conflict cycles per read
+    // otherwise).  The second slice of a k-tile is reached by XOR-ing 64 into the offset, 16-row tiles lie 2 KiB apart.
     constexpr int TN16 = WTN / 16;
     int a_addr16 = 0;
     // ([k x n] weights: one address per pair of 16-column tiles; the odd tile of a pair lies at that address ^ 32)
     int w_addr16[(MF16 && W_KN) ? TN16 / 2 : 1];
     if constexpr (MF16) {
         static_assert(!MF16 || (TM == 4 && TN == 2), "quarter phases are written for the 128x64 wave tile");
-        a_addr16 = swz_row(wm * WTM + (lane & 15), lane >> 4);
+        const int kch = (((lane >> 4) & 1) << 1) | (lane >> 5);          // this lane's chunk of a slice
+        a_addr16 = swz_row(wm * WTM + (lane & 15), kch);
         if constexpr (W_KN) {
-            const int blk = lane >> 4, i16 = lane & 15;
-            const int kl = blk * 8 + (i16 >> 2);                             // k of (slice 0, first half)
+            const int i16 = lane & 15;
+            const int kl = kch * 8 + (i16 >> 2);                             // k of (slice 0, first half)
 #pragma unroll
             for (int t = 0; t < TN16; t += 2) {
                 const int nl = wn * WTN + t * 16 + (i16 & 3) * 4;
                 const int q = (nl >> 5) ^ (kl & 3);
-                w_addr16[t / 2] = W_BASE + kl * W_ROWB + (q << 6) + (((nl & 31) * 2) ^ (((kl >> 3) & 1) << 5));
+                w_addr16[t / 2] = W_BASE + kl * W_ROWB + (q << 6) + (((nl & 31) * 2) ^ (((kl >> 4) & 1) << 5));
             }
         } else {
-            w_addr16[0] = W_BASE + swz_row(wn * WTN + (lane & 15), lane >> 4);
+            w_addr16[0] = W_BASE + swz_row(wn * WTN + (lane & 15), kch);
         }
     } else {
         w_addr16[0] = 0;

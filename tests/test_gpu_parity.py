@@ -997,7 +997,9 @@ def test_full_size_pair_70b(flags):
     # oracle: H = bf16(AG(X) W_up) (Alg. 1), then Alg. 2 on A = H
     H64 = oracle.round_to_bf16(_full_ref("c4_ag_70b_up", rank)[1])
     e = H.rel_err(H.to_host_f64(ag.O), H64)
-    assert e <= TIGHT_BF16_OUT, f"H: {e:.3e}"              # a one-ulp flip of a bf16 element at most
+    # (the reference is itself rounded to bf16 here, because the down-projection consumes it: where the fp32 sum lies
+    # next to a rounding boundary the two roundings differ by one ulp of the element, which is at most 2^-7 of it)
+    assert e <= 2 * TIGHT_BF16_OUT, f"H: {e:.3e}"
     ref = oracle.rs_rank_steps(H64, inputs.as_f64(ddn["W"], "bf16"),
                                [None] + [r.astype(np.float64) for r in ddn["R"][1:]], dn.p, rank)
     for i in range(dn.p):
