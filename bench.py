@@ -118,7 +118,7 @@ def main() -> int:
             best = None
             pers_pair = kind == cf.CF_KIND_RS_PAIR and getattr(run, "each", None) is not None
             for mode, extra in MODES if (kind in (cf.CF_KIND_RS, cf.CF_KIND_AG) and (fl == 0 or "persistent" in mode or mode in BASIC_NAMES)) \
-                    else (BASIC + tuple(m for m in MODES if "persistent" in m[0] and "carried" not in m[0] and "groups" not in m[0]) if pers_pair else BASIC):
+                    else (BASIC + tuple(m for m in MODES if "persistent" in m[0] and "groups" not in m[0]) if pers_pair else BASIC):
                 if fl != 0 and (extra & (cf.CF_FUSED_COPY | cf.CF_DEVICE_WAIT)):
                     continue
                 if (extra & cf.CF_PERSISTENT) and getattr(run, "each", None) is None:

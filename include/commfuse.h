@@ -346,6 +346,9 @@ enum {
                             (reduce-scatter: a tile other than 256x256, a k range under 18 k-tiles of 64,
                             or 20 with a ragged last one; all-gather: k not a multiple of 64; the other
                             kinds) the flag changes nothing: the deliveries are enqueued in front.
+                            With CF_FUSED_COPY (CF_KIND_RS_PAIR): the step that sums every arrival reads
+                            them from the partners' buffers (peer_stage) in its epilogue and stores each on
+                            to its landing buffer (recv_each); same sums, bit for bit.
                             Not with CF_DEVICE_WAIT.                                                  */
     CF_DEVICE_WAIT = 64u /* bf16 RS / AG only, needs a registered workspace: the compute
                             stream does not wait for the copy stream between steps;
@@ -376,7 +379,8 @@ enum {
  * ones in slot[t % 2] and are added to O before the step's GEMM; the last GEMM adds
  * its product to O in place), or, with recv_each set, keeps every arrival and sums
  * them in the last GEMM's epilogue; peer_sink[i] receives what step i sends to the
- * partner of round i+1.  CF_FUSED_COPY and CF_DEVICE_WAIT are not available for them. */
+ * partner of round i+1.  CF_DEVICE_WAIT is not available for them, CF_FUSED_COPY with
+ * CF_PERSISTENT only. */
 cf_status commfuse_run_schedule(const cf_layer_desc *desc, int kind, const cf_buffers *bufs,
                                 void *compute_stream, void *copy_stream, uint32_t flags);
 

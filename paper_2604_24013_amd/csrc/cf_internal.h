@@ -60,7 +60,10 @@ struct GemmParams {
     // neighbour's buffer, and every k-tile of the slice that comes in through LDS is stored on to land_step[s]
     // (same layout as A_step[s]) by one of the workgroups that load it.  Either way the emulated transfer happens
     // inside the kernel, under its main loop.  Null = the operand is already where recv_step[s] / A_step[s] points.
+    // A step whose B_in is loaded in the epilogue (any tile; the step of the pairwise schedule that sums every arrival)
+    // stores what it read on to land_step[s] there, and recv_more[b] on to land_more[b].
     void *land_step[MAX_STEPS] = {};
+    void *land_more[MAX_RECV_MORE] = {};
     const void *cp_src = nullptr;
     void *cp_dst = nullptr;
     size_t cp_bytes = 0;
@@ -130,6 +133,9 @@ TileChoice choose_tile_bf16(int M, int N, int K, int num_cu);
 hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, int num_cu);
 // True if launch_gemm_bf16 would run the kernel that honours GemmParams::recv_more for these operands.
 bool gemm_bf16_takes_recv_list(const GemmParams &p, bool w_kn);
+// True if a persistent launch whose steps load their arrivals in the epilogue (recv_step with recv_more, the pairwise
+// schedule) should read them from the senders' buffers and land them itself (land_step / land_more).
+bool gemm_bf16_lands_recv_list(const GemmParams &p, bool w_kn);
 // True if launch_gemm_bf16 would run this persistent launch (reduce_scatter: its steps add a received partial;
 // else an all-gather's) on a kernel that honours GemmParams::land_step (the delivery carried by the consumer)
 // for every step that receives.

@@ -900,6 +900,16 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
     // the add's 12; pairwise, p - 1 arrivals in one pass: 8 p instead of 12 p - 4).
     if ((flags & CF_FUSED_COPY) && is_dp_kind(kind) && do_copy && do_compute && slot_bytes > 0)
         carried = true;
+    // The pairwise reduce-scatter with CF_FUSED_COPY: the step that sums every arrival reads them from the partners'
+    // buffers in its epilogue and stores each on to its landing buffer (a copy's read and the launch in front saved).
+    if ((flags & CF_FUSED_COPY) && kind == CF_KIND_RS_PAIR && do_copy && do_compute && slot_bytes > 0 && r.mc > 0 &&
+        r.n > 0 && r.k > 0) {
+        cf::GemmParams probe;
+        probe.W = b->W;
+        fill_shape(probe, r);
+        probe.n_steps = S;
+        carried = cf::gemm_bf16_lands_recv_list(probe, r.w_kn);
+    }
     // Without CF_SERIAL (reduce-scatter and all-gather on two streams): the rank step as a few launches, each a group
     // of consecutive (sub-)steps that fills the chip about once, and the deliveries of a group copied on the copy
     // stream under the launches of the groups before it -- Fig. 1's overlap with a group of steps where the paper has
@@ -1050,6 +1060,14 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
                 if (last)
                     for (int t = 1; t < p - 1; ++t)
                         gp.recv_more[gp.n_recv_more++] = static_cast<const float *>(b->recv_each[t]);
+                if (last && carried) {               // read from the partners' buffers, land them here
+                    gp.recv_step[j] = static_cast<const float *>(b->peer_stage[0]);
+                    gp.land_step[j] = b->recv_each[0];
+                    for (int t = 1; t < p - 1; ++t) {
+                        gp.recv_more[t - 1] = static_cast<const float *>(b->peer_stage[t]);
+                        gp.land_more[t - 1] = b->recv_each[t];
+                    }
+                }
                 continue;
             }
             const int c = subslice_index(kind, p, m, r.rank, jj);
@@ -1177,10 +1195,10 @@ cf_status run_schedule_common(const Resolved &r, int kind, const cf_buffers *buf
     if (is_pair_kind(kind)) {
         if (cf_status st = check_pair_p(r.p))
             return st;
-        const bool dp_one_launch = kind == CF_KIND_DP_PAIR && (flags & CF_PERSISTENT) && !(flags & CF_DEVICE_WAIT);
-        if ((flags & (CF_FUSED_COPY | CF_DEVICE_WAIT)) && !dp_one_launch)
+        const bool one_launch = (flags & CF_PERSISTENT) && !(flags & CF_DEVICE_WAIT);
+        if ((flags & (CF_FUSED_COPY | CF_DEVICE_WAIT)) && !one_launch)
             return fail(CF_ERR_UNSUPPORTED, "CF_FUSED_COPY / CF_DEVICE_WAIT are not available for the pairwise kinds (but "
-                                            "CF_FUSED_COPY with CF_PERSISTENT for the pairwise gradient bucket)");
+                                            "CF_FUSED_COPY with CF_PERSISTENT is)");
     }
     if (flags & CF_DEVICE_WAIT) {
         if (flags & CF_FUSED_COPY)

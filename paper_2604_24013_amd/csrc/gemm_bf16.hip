@@ -315,6 +315,12 @@ bool gemm_bf16_takes_recv_list(const GemmParams &p, bool w_kn)
     return p.M > 0 && p.N > 0 && !staged_kernel_forced() && gemm_bf16_dl_supported(p, w_kn);
 }
 
+bool gemm_bf16_lands_recv_list(const GemmParams &p, bool w_kn)
+{
+    const Tuning tn = tuning();                      // COMMFUSE_CARRY=0 keeps the copies in front
+    return p.n_steps > 0 && gemm_bf16_takes_recv_list(p, w_kn) && (tn.carry >= 0 ? tn.carry != 0 : true);
+}
+
 // Tile of a launch: the per-step choice, the persistent rank step's cost model, then the overrides.
 static TileChoice tile_of_launch(const GemmParams &p, int num_cu)
 {

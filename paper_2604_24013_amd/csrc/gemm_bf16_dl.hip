@@ -1271,8 +1271,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                     rv[j][g] = __builtin_bit_cast(f32x4_t, recv_coherent
                                    ? __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, boff, 0, COHERENT_LD)
                                    : __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, boff, 0, 0));
-                    if constexpr (PERSIST && RLDS) {
-                        if (cLand != nullptr) {      // (a work item that could not stream still delivers)
+                    if constexpr (PERSIST) {
+                        // the delivery carried by the consumer: a work item that could not stream B_in, or a step
+                        // that sums several arrivals, stores what it read from the sender's buffer to the landing buffer
+                        if (cLand != nullptr) {
                             __amdgpu_buffer_rsrc_t le_rsrc =
                                 __builtin_amdgcn_make_buffer_rsrc(static_cast<float *>(cLand), 0, (int)r_bytes, 0x00020000);
                             __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, rv[j][g]), le_rsrc, boff, 0, 0);
@@ -1290,6 +1292,18 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                     for (int g = 0; g < 4; ++g)
                         tv[j][g] = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
                             m_rsrc, eoff[j][g] == OOB ? (int)OOB : (int)(eoff[j][g] * 4), 0, 0));
+                if constexpr (PERSIST) {
+                    if (P.land_more[b] != nullptr) {     // this arrival's landing buffer (delivery carried by the consumer)
+                        __amdgpu_buffer_rsrc_t lm_rsrc =
+                            __builtin_amdgcn_make_buffer_rsrc(static_cast<float *>(P.land_more[b]), 0, (int)r_bytes, 0x00020000);
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+#pragma unroll
+                            for (int g = 0; g < 4; ++g)
+                                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, tv[j][g]), lm_rsrc,
+                                                                       eoff[j][g] == OOB ? (int)OOB : (int)(eoff[j][g] * 4), 0, 0);
+                    }
+                }
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll

@@ -81,9 +81,11 @@ def test_rs_pair_reduced(shape, layout, dtype):
             # all steps in one launch: the same GEMMs and the same additions in the same order
             pers = H.RsPairRun(w, data, rank, layout, keep_all=True)
             PS = cf.CF_PERSISTENT | cf.CF_SERIAL
-            for flags in (PS, PS | cf.CF_GRAPH, PS | cf.CF_POISON):
+            # (CF_FUSED_COPY: no copy is launched; the last step reads the arrivals from the partners' buffers and
+            # lands each in its buffer)
+            for flags in (PS, PS | cf.CF_GRAPH, PS | cf.CF_POISON, PS | cf.CF_FUSED_COPY, PS | cf.CF_FUSED_COPY | cf.CF_GRAPH):
                 pers.O.fill_(float("nan"))
-                for t in pers.send_each:
+                for t in pers.send_each + pers.each:
                     t.fill_(float("nan"))
                 pers.run_schedule(flags)
                 pers.run_schedule(flags)
@@ -91,6 +93,7 @@ def test_rs_pair_reduced(shape, layout, dtype):
                 for i in range(p - 1):               # the partial every step sends to its partner
                     assert np.array_equal(H.to_host_f64(pers.send_each[i]), outs[i]), \
                         f"rank {rank} flags {flags} (persistent) B_out of step {i}"
+                    assert torch.equal(pers.each[i], pers.stage[i]), f"rank {rank} flags {flags}: delivery of round {i + 1}"
 
 
 def test_rs_pair_deferred_with_the_staged_kernel():
@@ -199,7 +202,8 @@ def _full_ref(name, rank):
 
 
 @pytest.mark.parametrize("keep_all", [False, True])
-@pytest.mark.parametrize("flags", [0, cf.CF_GRAPH, cf.CF_PERSISTENT | cf.CF_SERIAL])
+@pytest.mark.parametrize("flags", [0, cf.CF_GRAPH, cf.CF_PERSISTENT | cf.CF_SERIAL,
+                                   cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY])
 @pytest.mark.parametrize("name", ["c2_rs_7b", "c4_rs_70b_down"])
 def test_full_size_rs_pair(name, flags, keep_all):
     """Full benchmark sizes; every element of every step's output (the partials sent to the partners, then the
@@ -222,6 +226,7 @@ def test_full_size_rs_pair(name, flags, keep_all):
         assert e <= TOL_BF16 and e <= TIGHT_BF16, f"step {i}: {e:.3e}"
         if persistent and i < w.p - 1:
             assert torch.equal(run.sink[i], run.send_each[i])
+            assert torch.equal(run.each[i], run.stage[i]), f"delivery of round {i + 1}"
 
 
 def test_pair_rejects_what_it_cannot_do():
@@ -235,7 +240,7 @@ def test_pair_rejects_what_it_cannot_do():
         cf.rs_pair_step(d, 1, t, t, t[:4096], t[4096:8192], t[4096:8192], None)   # out aliases acc before the last step
     w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=4, m_chunk=64, n=64, k=64)
     run = H.RsPairRun(w, inputs.make_rs(w), 0)
-    for flags in (cf.CF_FUSED_COPY, cf.CF_DEVICE_WAIT):
+    for flags in (cf.CF_FUSED_COPY, cf.CF_DEVICE_WAIT):          # (CF_FUSED_COPY goes with CF_PERSISTENT only)
         with pytest.raises(cf.CommFuseError) as ei:
             run.run_schedule(flags)
         assert ei.value.status == cf.CF_ERR_UNSUPPORTED
