@@ -346,9 +346,11 @@ enum {
                             (reduce-scatter: a tile other than 256x256, a k range under 18 k-tiles of 64,
                             or 20 with a ragged last one; all-gather: k not a multiple of 64; the other
                             kinds) the flag changes nothing: the deliveries are enqueued in front.
-                            With CF_FUSED_COPY (CF_KIND_RS_PAIR): the step that sums every arrival reads
-                            them from the partners' buffers (peer_stage) in its epilogue and stores each on
-                            to its landing buffer (recv_each); same sums, bit for bit.
+                            With CF_FUSED_COPY (CF_KIND_RS_PAIR) and a registered workspace: the work items
+                            of step t-1 land the arrival of round t (peer_stage[t-1] -> recv_each[t-1]), each
+                            its own output tile's part, and count the tile up; the step that sums the
+                            arrivals waits per tile (bounded spin: commfuse_device_status reports a
+                            time-out).  Same sums, bit for bit.  Without a workspace the flag changes nothing.
                             Not with CF_DEVICE_WAIT.                                                  */
     CF_DEVICE_WAIT = 64u /* bf16 RS / AG only, needs a registered workspace: the compute
                             stream does not wait for the copy stream between steps;
@@ -443,7 +445,8 @@ cf_status commfuse_run_attn_schedule(const cf_attn_desc *desc, const cf_attn_buf
                                      void *copy_stream, uint32_t flags);
 
 /* Synchronises `hip_stream` and reports whether any step kernel since the last call gave up a
- * CF_DEVICE_WAIT wait (CF_ERR_HIP; the status word in the workspace is cleared).  CF_OK if none did
+ * bounded device-side wait -- CF_DEVICE_WAIT, or CF_KIND_RS_PAIR with CF_PERSISTENT | CF_FUSED_COPY -- (CF_ERR_HIP;
+ * the status word in the workspace is cleared).  CF_OK if none did
  * or no workspace is registered.  This is the one entry point that synchronises. */
 cf_status commfuse_device_status(void *hip_stream);
 

@@ -331,7 +331,8 @@ def set_workspace(buf, nbytes: int = 0, stream=None) -> None:
 
 
 def device_status(stream=None) -> None:
-    """Synchronises ``stream``; raises if a step kernel gave up a CF_DEVICE_WAIT wait."""
+    """Synchronises ``stream``; raises if a kernel gave up a bounded device-side wait (CF_DEVICE_WAIT, or the
+    pairwise reduce-scatter carrying its deliveries)."""
     _check(load().commfuse_device_status(_stream(stream)))
 
 

@@ -60,10 +60,17 @@ struct GemmParams {
     // neighbour's buffer, and every k-tile of the slice that comes in through LDS is stored on to land_step[s]
     // (same layout as A_step[s]) by one of the workgroups that load it.  Either way the emulated transfer happens
     // inside the kernel, under its main loop.  Null = the operand is already where recv_step[s] / A_step[s] points.
-    // A step whose B_in is loaded in the epilogue (any tile; the step of the pairwise schedule that sums every arrival)
-    // stores what it read on to land_step[s] there, and recv_more[b] on to land_more[b].
     void *land_step[MAX_STEPS] = {};
-    void *land_more[MAX_RECV_MORE] = {};
+    // Pairwise schedule, the deliveries carried by the launch: every work item of step s, once its own output tile is
+    // stored, copies that tile's part of tail_src[s] (the arrival that travels while step s computes, in the sender's
+    // buffer) to tail_dst[s] (its landing buffer; both laid out like the output), written through to memory, and then
+    // counts tile_ready[tile] up.  The last step's work item waits (bounded by spin_limit; a time-out sets bit 0 of
+    // *status) until its tile's count reaches ready_count, then reads recv_step / recv_more -- the landing buffers --
+    // past the caches.  tile_ready holds max_tiles words, all zero at launch.
+    const float *tail_src[MAX_STEPS] = {};
+    float *tail_dst[MAX_STEPS] = {};
+    unsigned *tile_ready = nullptr;
+    int ready_count = 0;
     const void *cp_src = nullptr;
     void *cp_dst = nullptr;
     size_t cp_bytes = 0;
@@ -133,9 +140,10 @@ TileChoice choose_tile_bf16(int M, int N, int K, int num_cu);
 hipError_t launch_gemm_bf16(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t s, int num_cu);
 // True if launch_gemm_bf16 would run the kernel that honours GemmParams::recv_more for these operands.
 bool gemm_bf16_takes_recv_list(const GemmParams &p, bool w_kn);
-// True if a persistent launch whose steps load their arrivals in the epilogue (recv_step with recv_more, the pairwise
-// schedule) should read them from the senders' buffers and land them itself (land_step / land_more).
-bool gemm_bf16_lands_recv_list(const GemmParams &p, bool w_kn);
+// Output tiles per step if launch_gemm_bf16 can run this persistent launch with GemmParams::tail_src / tile_ready (the
+// arrivals of the pairwise schedule landed by the work items of the steps before the one that sums them), else 0.
+// The caller provides that many zeroed counters.
+int gemm_bf16_tiles_landing_arrivals(const GemmParams &p, bool w_kn, int num_cu);
 // True if launch_gemm_bf16 would run this persistent launch (reduce_scatter: its steps add a received partial;
 // else an all-gather's) on a kernel that honours GemmParams::land_step (the delivery carried by the consumer)
 // for every step that receives.

@@ -900,15 +900,26 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
     // the add's 12; pairwise, p - 1 arrivals in one pass: 8 p instead of 12 p - 4).
     if ((flags & CF_FUSED_COPY) && is_dp_kind(kind) && do_copy && do_compute && slot_bytes > 0)
         carried = true;
-    // The pairwise reduce-scatter with CF_FUSED_COPY: the step that sums every arrival reads them from the partners'
-    // buffers in its epilogue and stores each on to its landing buffer (a copy's read and the launch in front saved).
+    // The pairwise reduce-scatter with CF_FUSED_COPY: the arrival of round t travels while step t - 1 computes, so the
+    // work items of step t - 1 land it -- each its own output tile's part, from the partner's buffer to the landing
+    // buffer, after its own stores -- and count the tile up; the last step's work item waits for its tile's count
+    // before it sums the arrivals.  Needs the registered workspace (a counter per output tile, the status word).
+    unsigned *pair_ready = nullptr, *pair_status = nullptr;
+    int pair_tiles = 0;
     if ((flags & CF_FUSED_COPY) && kind == CF_KIND_RS_PAIR && do_copy && do_compute && slot_bytes > 0 && r.mc > 0 &&
         r.n > 0 && r.k > 0) {
         cf::GemmParams probe;
         probe.W = b->W;
         fill_shape(probe, r);
         probe.n_steps = S;
-        carried = cf::gemm_bf16_lands_recv_list(probe, r.w_kn);
+        pair_tiles = cf::gemm_bf16_tiles_landing_arrivals(probe, r.w_kn, num_cu_of_current_device());
+        const Workspace ws = workspace_for(cs);
+        if (pair_tiles > 0 && ws.ptr != nullptr && ws.bytes >= WS_COUNTER_BYTES &&
+            (size_t)pair_tiles <= WS_TILE_COUNTER_BYTES / sizeof(unsigned)) {
+            pair_ready = static_cast<unsigned *>(ws.ptr);
+            pair_status = reinterpret_cast<unsigned *>(static_cast<char *>(ws.ptr) + WS_STATUS_OFFSET);
+            carried = true;
+        }
     }
     // Without CF_SERIAL (reduce-scatter and all-gather on two streams): the rank step as a few launches, each a group
     // of consecutive (sub-)steps that fills the chip about once, and the deliveries of a group copied on the copy
@@ -1060,13 +1071,16 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
                 if (last)
                     for (int t = 1; t < p - 1; ++t)
                         gp.recv_more[gp.n_recv_more++] = static_cast<const float *>(b->recv_each[t]);
-                if (last && carried) {               // read from the partners' buffers, land them here
-                    gp.recv_step[j] = static_cast<const float *>(b->peer_stage[0]);
-                    gp.land_step[j] = b->recv_each[0];
-                    for (int t = 1; t < p - 1; ++t) {
-                        gp.recv_more[t - 1] = static_cast<const float *>(b->peer_stage[t]);
-                        gp.land_more[t - 1] = b->recv_each[t];
-                    }
+                if (carried && !last) {              // this step's work items land the arrival of round j + 1
+                    gp.tail_src[j] = static_cast<const float *>(b->peer_stage[j]);
+                    gp.tail_dst[j] = static_cast<float *>(b->recv_each[j]);
+                }
+                if (carried && last) {
+                    gp.tile_ready = pair_ready;
+                    gp.ready_count = p - 1;
+                    gp.max_tiles = (int)(WS_TILE_COUNTER_BYTES / sizeof(unsigned));
+                    gp.status = pair_status;
+                    gp.spin_limit = spin_limit();
                 }
                 continue;
             }
@@ -1094,6 +1108,11 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
         }
         if (grouped && do_copy)                          // this group's deliveries have landed
             CF_HIP(hipStreamWaitEvent(cs, ev[1 + g0 / group], 0));
+        if (gp.tile_ready != nullptr) {                  // the tiles' counters start at zero (a fill kernel: capturable)
+            hipError_t e0 = cf::launch_set_words(gp.tile_ready, pair_tiles, 0u, cs);
+            if (e0 != hipSuccess)
+                return fail_hip(e0, "counter fill");
+        }
         hipError_t e = cf::launch_gemm_bf16(gp, r.w_kn, r.bf16_out, cs, gp.num_cu);
         if (e != hipSuccess)
             return fail_hip(e, "persistent rank-step launch");

@@ -315,12 +315,6 @@ bool gemm_bf16_takes_recv_list(const GemmParams &p, bool w_kn)
     return p.M > 0 && p.N > 0 && !staged_kernel_forced() && gemm_bf16_dl_supported(p, w_kn);
 }
 
-bool gemm_bf16_lands_recv_list(const GemmParams &p, bool w_kn)
-{
-    const Tuning tn = tuning();                      // COMMFUSE_CARRY=0 keeps the copies in front
-    return p.n_steps > 0 && gemm_bf16_takes_recv_list(p, w_kn) && (tn.carry >= 0 ? tn.carry != 0 : true);
-}
-
 // Tile of a launch: the per-step choice, the persistent rank step's cost model, then the overrides.
 static TileChoice tile_of_launch(const GemmParams &p, int num_cu)
 {
@@ -354,6 +348,17 @@ static TileChoice tile_of_launch(const GemmParams &p, int num_cu)
     if (tn.splitk >= 1)
         t.splitk = tn.splitk;
     return t;
+}
+
+int gemm_bf16_tiles_landing_arrivals(const GemmParams &p, bool w_kn, int num_cu)
+{
+    const Tuning tn = tuning();                      // COMMFUSE_CARRY=0 keeps the copies in front
+    if (p.n_steps < 2 || !gemm_bf16_takes_recv_list(p, w_kn) || (tn.carry >= 0 && tn.carry == 0))
+        return 0;
+    const TileChoice t = tile_of_launch(p, num_cu);
+    const int64_t tiles = (int64_t)((p.M + t.bm - 1) / t.bm) * ((p.N + t.bn - 1) / t.bn);
+    // every workgroup of the launch must be resident at once (a work item waits for others): one grid over the chip
+    return tiles <= 1 << 20 ? (int)tiles : 0;
 }
 
 bool gemm_bf16_carries_delivery(const GemmParams &p, bool w_kn, bool out_bf16, int num_cu, bool reduce_scatter)

@@ -665,7 +665,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     __amdgpu_buffer_rsrc_t r_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<float *>(cRecv), 0, cRecv != nullptr ? (int)r_bytes : 0, 0x00020000);
     const int pf_at = nk - 1 - P.pf_lead;             // iteration after whose tile loads the prefetch is issued
-    const bool pf_on = PF && cRecv != nullptr && splits == 1 && n_more == 0 && P.pf_lead > 0 && pf_at >= 0;
+    // Arrivals landed tile by tile by the work items of the steps before (GemmParams::tail_src): the last step's item
+    // waits for its own tile's count before it reads them, in the epilogue.
+    // (fp32 partial sums only, and never in the kernel that streams B_in: the launcher does not pick it for such a launch.)
+    constexpr bool TAILS = PERSIST && !RLDS && !OUT_BF16;
+    const bool wait_tiles = TAILS && P.tile_ready != nullptr && step_i == P.n_steps - 1;
+    const bool pf_on = PF && cRecv != nullptr && splits == 1 && n_more == 0 && P.pf_lead > 0 && pf_at >= 0 && !wait_tiles;
     f32x4_t pre[PF ? TM : 1][PF ? TN : 1][4];
     constexpr int COHERENT_LD = 1 | 16;               // buffer cache-policy bits sc0 | sc1
     auto prefetch_recv = [&](auto aux_tag) __attribute__((always_inline)) {
@@ -693,7 +698,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // A ragged k tail (the launcher then leaves the k order unrotated: it is the last k-tile) is requested in the
     // last two iterations before the final tile; those test their loads and come after the streamed ones.
     const int tested = (RLDS && K % BK != 0) ? (nk - 1 < 2 ? nk - 1 : 2) : 0;
-    const bool streamed = RLDS && cRecv != nullptr && cFlag == nullptr && n_more == 0 && splits == 1 &&
+    const bool streamed = RLDS && cRecv != nullptr && cFlag == nullptr && !wait_tiles && n_more == 0 && splits == 1 &&
                           P.stream_recv && nk >= 2 * RQ + 2 + tested && (tested == 0 || rot == 0);
     // the left-operand stage whose memory serves as the wave-private scratch of the epilogue's stores (and, RLDS, as
     // the landing area of B_in before)
@@ -1244,6 +1249,26 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     const bool has_recv = cRecv != nullptr;
     if (!P.wait_at_start && !pf_on)
         wait_delivery(false);                        // B_in has travelled under the main loop
+    if (wait_tiles) {
+        // The workgroups that landed this tile's arrivals wrote them through to memory and counted up afterwards;
+        // they hold earlier work items, so they are running or done.  One lane polls, at most spin_limit times.
+        if (tid == 0) {
+            unsigned n = 0;
+            while (__hip_atomic_load(&P.tile_ready[tile], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) < (unsigned)P.ready_count) {
+                if (++n >= P.spin_limit) {
+                    __hip_atomic_fetch_or(P.status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+                    break;
+                }
+                __builtin_amdgcn_s_sleep(32);
+            }
+            // (this item is the tile's only reader: the counter is left ready for the next launch)
+            __hip_atomic_store(&P.tile_ready[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        // the arrivals were written through another XCD's L2: drop what this one may hold of those lines, once per
+        // workgroup, so that the epilogue's loads can go through the caches (they read a line in several pieces)
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    }
     const bool recv_coherent = cFlag != nullptr && !P.wait_at_start;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
@@ -1271,10 +1296,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                     rv[j][g] = __builtin_bit_cast(f32x4_t, recv_coherent
                                    ? __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, boff, 0, COHERENT_LD)
                                    : __builtin_amdgcn_raw_buffer_load_b128(r_rsrc, boff, 0, 0));
-                    if constexpr (PERSIST) {
-                        // the delivery carried by the consumer: a work item that could not stream B_in, or a step
-                        // that sums several arrivals, stores what it read from the sender's buffer to the landing buffer
-                        if (cLand != nullptr) {
+                    if constexpr (PERSIST && RLDS) {
+                        if (cLand != nullptr) {      // (a work item that could not stream still delivers)
                             __amdgpu_buffer_rsrc_t le_rsrc =
                                 __builtin_amdgcn_make_buffer_rsrc(static_cast<float *>(cLand), 0, (int)r_bytes, 0x00020000);
                             __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, rv[j][g]), le_rsrc, boff, 0, 0);
@@ -1292,18 +1315,6 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                     for (int g = 0; g < 4; ++g)
                         tv[j][g] = __builtin_bit_cast(f32x4_t, __builtin_amdgcn_raw_buffer_load_b128(
                             m_rsrc, eoff[j][g] == OOB ? (int)OOB : (int)(eoff[j][g] * 4), 0, 0));
-                if constexpr (PERSIST) {
-                    if (P.land_more[b] != nullptr) {     // this arrival's landing buffer (delivery carried by the consumer)
-                        __amdgpu_buffer_rsrc_t lm_rsrc =
-                            __builtin_amdgcn_make_buffer_rsrc(static_cast<float *>(P.land_more[b]), 0, (int)r_bytes, 0x00020000);
-#pragma unroll
-                        for (int j = 0; j < TN; ++j)
-#pragma unroll
-                            for (int g = 0; g < 4; ++g)
-                                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4_t, tv[j][g]), lm_rsrc,
-                                                                       eoff[j][g] == OOB ? (int)OOB : (int)(eoff[j][g] * 4), 0, 0);
-                    }
-                }
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -1377,8 +1388,42 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             }
         }
     }
-    if constexpr (PERSIST)
+    if constexpr (PERSIST) {
+        // The arrival that travels while this step computes (pairwise schedule: the partner's partial for the own
+        // slice): this work item lands its own output tile's part of it -- from the sender's buffer to the landing
+        // buffer, written through to memory (plain stores and a write-back of the L2 before the count take twice the
+        // whole launch's time) -- and then counts the tile up for the step that sums the arrivals.
+        const float *const tsrc = TAILS ? P.tail_src[step_i] : nullptr;
+        if (TAILS && tsrc != nullptr) {
+            __amdgpu_buffer_rsrc_t ts_rsrc =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(tsrc), 0, (int)r_bytes, 0x00020000);
+            __amdgpu_buffer_rsrc_t td_rsrc = __builtin_amdgcn_make_buffer_rsrc(P.tail_dst[step_i], 0, (int)r_bytes, 0x00020000);
+            constexpr int CPR = WTN / 4;             // 16-byte chunks in a row of the wave's part
+            constexpr int RPI = 64 / CPR;            // rows per instruction
+            constexpr int TB = 16;                   // loads in flight per lane
+            static_assert(64 % CPR == 0 && (WTM / RPI) % TB == 0, "whole batches");
+            const int sn = n0 + wn * WTN + (lane % CPR) * 4;
+#pragma unroll 1
+            for (int b = 0; b < WTM / RPI; b += TB) {
+                u32x4_t v[TB];
+                int off[TB];
+#pragma unroll
+                for (int u = 0; u < TB; ++u) {
+                    const int sm = m0 + wm * WTM + (b + u) * RPI + lane / CPR;
+                    off[u] = (sm < M && sn < N) ? (int)(((int64_t)sm * P.ldo + sn) * 4) : (int)OOB;
+                    v[u] = __builtin_amdgcn_raw_buffer_load_b128(ts_rsrc, off[u], 0, 0);
+                }
+#pragma unroll
+                for (int u = 0; u < TB; ++u)
+                    __builtin_amdgcn_raw_buffer_store_b128(v[u], td_rsrc, off[u], 0, COHERENT_LD);
+            }
+            __builtin_amdgcn_s_waitcnt(0);           // this wave's stores are acknowledged
+            __syncthreads();                         // ... and every wave's
+            if (tid == 0)
+                __hip_atomic_fetch_add(&P.tile_ready[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         __syncthreads();                             // every wave is done with the LDS stages
+    }
     item += item_stride;
     } while (PERSIST && item < n_items);             // next work item
 }
@@ -1397,7 +1442,8 @@ hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t
         any_flag = any_flag || p.flag_step[j] != nullptr;
     const int nk_all = (p.K + BK - 1) / BK;
     [[maybe_unused]] const bool rlds = SPREAD && NS == 2 && any_recv && !out_bf16 && !p.a_t && p.stream_recv && !any_flag &&
-                                       p.n_recv_more == 0 && p.splits == 1 && nk_all >= 18 + (p.K % BK != 0 ? 2 : 0);
+                                       p.n_recv_more == 0 && p.splits == 1 && nk_all >= 18 + (p.K % BK != 0 ? 2 : 0) &&
+                                       p.tile_ready == nullptr;
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     int wgs = tiles_m * tiles_n * p.splits + p.cp_wgs;
     if (p.n_steps > 0) {                             // persistent: a grid that fills the chip once
@@ -1520,6 +1566,11 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
         for (int j = 0; j < p.n_steps; ++j)
             if (p.land_step[j] != nullptr && p.recv_step[j] == nullptr && !gemm_bf16_dl_carries_operand(p))
                 return hipErrorInvalidValue;          // callers ask gemm_bf16_carries_delivery first
+        if (p.tile_ready != nullptr && (out_bf16 || tiles > p.max_tiles || p.status == nullptr || p.spin_limit == 0))
+            return hipErrorInvalidValue;              // callers ask gemm_bf16_tiles_landing_arrivals first
+        for (int j = 0; j < p.n_steps; ++j)
+            if ((p.tail_src[j] != nullptr) != (p.tail_dst[j] != nullptr) || (p.tail_src[j] != nullptr && p.tile_ready == nullptr))
+                return hipErrorInvalidValue;
         p.splits = 1;
         p.cp_wgs = 0;
         p.cp_bytes = 0;
@@ -1532,7 +1583,8 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
         bool cut = false;
         for (int nb = 1; nb <= 8; nb *= 2)
             cut = cut || (tiles_n_ % nb == 0 && p.n_steps % (8 / nb) == 0);
-        p.xcd_steps = cut && p.num_cu % 8 == 0 && p.n_recv_more == 0 && tn.xcd_steps != 0;
+        // (... nor when work items hand arrivals on to the last step's: step-major order keeps the producers in front)
+        p.xcd_steps = cut && p.num_cu % 8 == 0 && p.n_recv_more == 0 && p.tile_ready == nullptr && tn.xcd_steps != 0;
         // Step groups x column bands: per k-tile the 32 (or fewer) workgroups of an XCD that run side by side fetch
         // `a` left-operand bands of bm rows and `b` weight bands of bn columns, a = (step, tile row) pairs of the XCD
         // (at most its workgroups), b = the columns they spread over; the number of bands NB that makes a bm + b bn

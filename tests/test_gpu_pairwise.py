@@ -5,6 +5,7 @@ Tolerances as in test_gpu_parity.py; the received partials are summed in fp32 in
 order, which adds at most (p-1) * 2^-24 relative to the largest partial sum, well inside
 the tight bf16 bound.  Small-integer inputs are compared bit for bit.
 """
+import contextlib
 import os
 
 import numpy as np
@@ -81,14 +82,20 @@ def test_rs_pair_reduced(shape, layout, dtype):
             # all steps in one launch: the same GEMMs and the same additions in the same order
             pers = H.RsPairRun(w, data, rank, layout, keep_all=True)
             PS = cf.CF_PERSISTENT | cf.CF_SERIAL
-            # (CF_FUSED_COPY: no copy is launched; the last step reads the arrivals from the partners' buffers and
-            # lands each in its buffer)
-            for flags in (PS, PS | cf.CF_GRAPH, PS | cf.CF_POISON, PS | cf.CF_FUSED_COPY, PS | cf.CF_FUSED_COPY | cf.CF_GRAPH):
+            # (CF_FUSED_COPY: no copy is launched; the work items of step t - 1 land the arrival of round t tile by
+            # tile, the last step's work items wait for their tile's count -- with a registered workspace; without
+            # one the copies go in front as without the flag)
+            FC = PS | cf.CF_FUSED_COPY
+            for flags, with_ws in ((PS, False), (PS | cf.CF_GRAPH, False), (PS | cf.CF_POISON, False), (FC, False),
+                                   (FC, True), (FC | cf.CF_GRAPH, True)):
                 pers.O.fill_(float("nan"))
                 for t in pers.send_each + pers.each:
                     t.fill_(float("nan"))
-                pers.run_schedule(flags)
-                pers.run_schedule(flags)
+                ws = H.Workspace(pers.desc, cf.CF_KIND_RS_PAIR) if with_ws else contextlib.nullcontext()
+                with ws:
+                    pers.run_schedule(flags)
+                    pers.run_schedule(flags)
+                    cf.device_status()               # no wait timed out
                 assert np.array_equal(H.to_host_f64(pers.O), outs[-1]), f"rank {rank} flags {flags} (persistent)"
                 for i in range(p - 1):               # the partial every step sends to its partner
                     assert np.array_equal(H.to_host_f64(pers.send_each[i]), outs[i]), \
@@ -219,6 +226,9 @@ def test_full_size_rs_pair(name, flags, keep_all):
         t.fill_(float("nan"))
     with H.Workspace(run.desc, cf.CF_KIND_RS_PAIR):       # as the benchmark runs it
         run.run_schedule(flags)
+        if flags & cf.CF_FUSED_COPY:
+            run.run_schedule(flags)                       # (the tiles' counters are ready for a second launch)
+        cf.device_status()
     for i in range(w.p):
         got = H.to_host_f64(run.sink[i] if i < w.p - 1 else run.O)
         assert not np.isnan(got).any(), f"step {i}"
@@ -244,3 +254,38 @@ def test_pair_rejects_what_it_cannot_do():
         with pytest.raises(cf.CommFuseError) as ei:
             run.run_schedule(flags)
         assert ei.value.status == cf.CF_ERR_UNSUPPORTED
+
+
+def test_rs_pair_carried_wait_is_bounded_and_recovers():
+    """The last step's wait for its tile's arrivals is a bounded spin.  With a limit of one poll, forced from the host,
+    a work item may give up (then the status call says so and the result is void); every kernel exits either way, and
+    the next launch -- its counters filled with zero in front -- is correct again."""
+    p, mc, n, k = 4, 256, 256, 128                   # one output tile per step: the four work items run side by side
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=p, m_chunk=mc, n=n, k=k)
+    data = inputs.make_rs(w, salt=17)
+    ref = _oracle_pair(w, data, 1)
+    run = H.RsPairRun(w, data, 1, keep_all=True)
+    FC = cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY
+    os.environ["COMMFUSE_SPIN_LIMIT"] = "1"
+    try:
+        with H.Workspace(run.desc, cf.CF_KIND_RS_PAIR):
+            run.run_schedule(FC)
+            try:
+                cf.device_status(run.cs)
+                timed_out = False
+            except cf.CommFuseError as e:
+                assert "gave up waiting" in str(e)
+                timed_out = True
+            if not timed_out:
+                assert H.rel_err(H.to_host_f64(run.O), ref[-1]) <= TIGHT_BF16
+            os.environ.pop("COMMFUSE_SPIN_LIMIT", None)
+            run.O.fill_(float("nan"))
+            for t in run.each:
+                t.fill_(float("nan"))
+            run.run_schedule(FC)
+            cf.device_status(run.cs)
+            assert H.rel_err(H.to_host_f64(run.O), ref[-1]) <= TIGHT_BF16
+            for i in range(p - 1):
+                assert torch.equal(run.each[i], run.stage[i])
+    finally:
+        os.environ.pop("COMMFUSE_SPIN_LIMIT", None)
