@@ -289,3 +289,34 @@ def test_rs_pair_carried_wait_is_bounded_and_recovers():
                 assert torch.equal(run.each[i], run.stage[i])
     finally:
         os.environ.pop("COMMFUSE_SPIN_LIMIT", None)
+
+
+@pytest.mark.parametrize("tile", ["128x128", "256x128", "256x256"])
+def test_rs_pair_carried_on_every_tile_shape(tile):
+    """The landing of the arrivals behind the work items and the per-tile wait, on each tile shape of the one-launch
+    kernel (the work item's part of an arrival is its own output tile), several tiles per step and ragged edges."""
+    p, mc, n, k = 8, 520, 776, 328
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=p, m_chunk=mc, n=n, k=k)
+    data = inputs.make_rs(w, salt=19)
+    rank = 6
+    ref = _oracle_pair(w, data, rank)
+    FC = cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY
+    os.environ["COMMFUSE_TILE"] = tile
+    try:
+        for layout in (cf.CF_W_KN, cf.CF_W_NK):
+            run = H.RsPairRun(w, data, rank, layout, keep_all=True)
+            with H.Workspace(run.desc, cf.CF_KIND_RS_PAIR):
+                for rep in range(2):
+                    run.O.fill_(float("nan"))
+                    for t in run.send_each + run.each:
+                        t.fill_(float("nan"))
+                    run.run_schedule(FC)
+                    cf.device_status(run.cs)
+                    for i in range(p):
+                        got = H.to_host_f64(run.send_each[i] if i < p - 1 else run.O)
+                        e = H.rel_err(got, ref[i])
+                        assert e <= TIGHT_BF16, f"layout {layout} step {i}: {e:.3e}"
+                    for i in range(p - 1):
+                        assert torch.equal(run.each[i], run.stage[i]), f"layout {layout}: delivery of round {i + 1}"
+    finally:
+        os.environ.pop("COMMFUSE_TILE", None)
