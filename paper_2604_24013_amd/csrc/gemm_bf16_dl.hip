@@ -671,8 +671,48 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     constexpr bool TAILS = PERSIST && !RLDS && !OUT_BF16;
     const bool wait_tiles = TAILS && P.tile_ready != nullptr && step_i == P.n_steps - 1;
     const bool pf_on = PF && cRecv != nullptr && splits == 1 && n_more == 0 && P.pf_lead > 0 && pf_at >= 0 && !wait_tiles;
-    f32x4_t pre[PF ? TM : 1][PF ? TN : 1][4];
+    // The arrival that travels while this step computes (pairwise schedule: the partner's partial for the own slice):
+    // this work item lands its own output tile's part of it -- from the sender's buffer to the landing buffer, written
+    // through to memory (plain stores and a write-back of the L2 before the count take twice the whole launch's time)
+    // -- and then counts the tile up for the step that sums the arrivals.  Every other workgroup of an XCD does so in
+    // front of its main loop, the others behind their epilogue: the work items of a round run in lock step, and this
+    // way one half copies while the other half multiplies instead of all 256 copying at once.
     constexpr int COHERENT_LD = 1 | 16;               // buffer cache-policy bits sc0 | sc1
+    const bool tail_early = TAILS && (((int)blockIdx.x >> 3) & 1) != 0;
+    auto land_arrival = [&]() __attribute__((always_inline)) {
+        const float *const tsrc = TAILS ? P.tail_src[step_i] : nullptr;
+        if (TAILS && tsrc != nullptr) {
+            __amdgpu_buffer_rsrc_t ts_rsrc =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(tsrc), 0, (int)r_bytes, 0x00020000);
+            __amdgpu_buffer_rsrc_t td_rsrc = __builtin_amdgcn_make_buffer_rsrc(P.tail_dst[step_i], 0, (int)r_bytes, 0x00020000);
+            constexpr int CPR = WTN / 4;             // 16-byte chunks in a row of the wave's part
+            constexpr int RPI = 64 / CPR;            // rows per instruction
+            constexpr int TB = 16;                   // loads in flight per lane
+            static_assert(64 % CPR == 0 && (WTM / RPI) % TB == 0, "whole batches");
+            const int sn = n0 + wn * WTN + (lane % CPR) * 4;
+#pragma unroll 1
+            for (int b = 0; b < WTM / RPI; b += TB) {
+                u32x4_t v[TB];
+                int off[TB];
+#pragma unroll
+                for (int u = 0; u < TB; ++u) {
+                    const int sm = m0 + wm * WTM + (b + u) * RPI + lane / CPR;
+                    off[u] = (sm < M && sn < N) ? (int)(((int64_t)sm * P.ldo + sn) * 4) : (int)OOB;
+                    v[u] = __builtin_amdgcn_raw_buffer_load_b128(ts_rsrc, off[u], 0, 0);
+                }
+#pragma unroll
+                for (int u = 0; u < TB; ++u)
+                    __builtin_amdgcn_raw_buffer_store_b128(v[u], td_rsrc, off[u], 0, COHERENT_LD);
+            }
+            __builtin_amdgcn_s_waitcnt(0);           // this wave's stores are acknowledged
+            __syncthreads();                         // ... and every wave's
+            if (tid == 0)
+                __hip_atomic_fetch_add(&P.tile_ready[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    };
+    if (TAILS && tail_early)
+        land_arrival();
+    f32x4_t pre[PF ? TM : 1][PF ? TN : 1][4];
     auto prefetch_recv = [&](auto aux_tag) __attribute__((always_inline)) {
         constexpr int AUX = decltype(aux_tag)::value;
 #pragma unroll
@@ -1389,39 +1429,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         }
     }
     if constexpr (PERSIST) {
-        // The arrival that travels while this step computes (pairwise schedule: the partner's partial for the own
-        // slice): this work item lands its own output tile's part of it -- from the sender's buffer to the landing
-        // buffer, written through to memory (plain stores and a write-back of the L2 before the count take twice the
-        // whole launch's time) -- and then counts the tile up for the step that sums the arrivals.
-        const float *const tsrc = TAILS ? P.tail_src[step_i] : nullptr;
-        if (TAILS && tsrc != nullptr) {
-            __amdgpu_buffer_rsrc_t ts_rsrc =
-                __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(tsrc), 0, (int)r_bytes, 0x00020000);
-            __amdgpu_buffer_rsrc_t td_rsrc = __builtin_amdgcn_make_buffer_rsrc(P.tail_dst[step_i], 0, (int)r_bytes, 0x00020000);
-            constexpr int CPR = WTN / 4;             // 16-byte chunks in a row of the wave's part
-            constexpr int RPI = 64 / CPR;            // rows per instruction
-            constexpr int TB = 16;                   // loads in flight per lane
-            static_assert(64 % CPR == 0 && (WTM / RPI) % TB == 0, "whole batches");
-            const int sn = n0 + wn * WTN + (lane % CPR) * 4;
-#pragma unroll 1
-            for (int b = 0; b < WTM / RPI; b += TB) {
-                u32x4_t v[TB];
-                int off[TB];
-#pragma unroll
-                for (int u = 0; u < TB; ++u) {
-                    const int sm = m0 + wm * WTM + (b + u) * RPI + lane / CPR;
-                    off[u] = (sm < M && sn < N) ? (int)(((int64_t)sm * P.ldo + sn) * 4) : (int)OOB;
-                    v[u] = __builtin_amdgcn_raw_buffer_load_b128(ts_rsrc, off[u], 0, 0);
-                }
-#pragma unroll
-                for (int u = 0; u < TB; ++u)
-                    __builtin_amdgcn_raw_buffer_store_b128(v[u], td_rsrc, off[u], 0, COHERENT_LD);
-            }
-            __builtin_amdgcn_s_waitcnt(0);           // this wave's stores are acknowledged
-            __syncthreads();                         // ... and every wave's
-            if (tid == 0)
-                __hip_atomic_fetch_add(&P.tile_ready[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        if (TAILS && !tail_early)
+            land_arrival();
         __syncthreads();                             // every wave is done with the LDS stages
     }
     item += item_stride;
