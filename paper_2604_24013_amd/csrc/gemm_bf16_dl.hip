@@ -110,6 +110,16 @@ __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
 }
 
+// One 16-byte-per-lane load from global memory into registers whose completion the CALLER awaits (vmcnt): issued
+// as inline assembly so that the compiler, which cannot count the requests between a load in one trip of a loop
+// and its use in the next, does not drain the whole request queue in front of the use.
+__device__ __forceinline__ u32x4_t load_16_unawaited(i32x4_t rsrc, unsigned voffset, int soffset)
+{
+    u32x4_t v;
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(v) : "v"(voffset), "s"(rsrc), "s"(soffset) : "memory");
+    return v;
+}
+
 // Scheduling hint for one slice phase: after each MFMA up to RPM LDS reads, until REMAIN reads are placed.
 template <int REMAIN, int RPM>
 __device__ __forceinline__ void interleave_mfma_reads()
@@ -678,9 +688,35 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
     // front of its main loop, the others behind their epilogue: the work items of a round run in lock step, and this
     // way one half copies while the other half multiplies instead of all 256 copying at once.
     constexpr int COHERENT_LD = 1 | 16;               // buffer cache-policy bits sc0 | sc1
-    const bool tail_early = TAILS && (((int)blockIdx.x >> 3) & 1) != 0;
-    auto land_arrival = [&]() __attribute__((always_inline)) {
-        const float *const tsrc = TAILS ? P.tail_src[step_i] : nullptr;
+    // The 16x16x32 main loop deals the copy over its k-tiles instead: one 16-byte load and the store of the one before
+    // per lane and k-tile, behind the k-tile's barrier (the wait in front of the next barrier covers them: they are
+    // older than the loads it lets pass), and what the k range leaves over is copied behind the epilogue.
+    constexpr bool TL_STREAM = TAILS && MF16;
+    constexpr int TL_CPR = WTN / 4, TL_RPI = 64 / TL_CPR, TL_N = WTM / TL_RPI;     // 16-byte chunks per row, rows and instructions per wave
+    const float *const tl_src = TAILS ? P.tail_src[step_i] : nullptr;
+    const bool tl_on = TL_STREAM && tl_src != nullptr;
+    const bool tail_early = TAILS && !tl_on && (((int)blockIdx.x >> 3) & 1) != 0;
+    const i32x4_t tl_srsrc = make_rsrc(tl_src, tl_src != nullptr ? r_bytes : 0u);
+    __amdgpu_buffer_rsrc_t tl_drsrc = __builtin_amdgcn_make_buffer_rsrc(
+        TAILS ? P.tail_dst[step_i] : nullptr, 0, tl_src != nullptr ? (int)r_bytes : 0, 0x00020000);
+    const int tl_row0 = m0 + wm * WTM + lane / TL_CPR, tl_col = n0 + wn * WTN + (lane % TL_CPR) * 4;
+    const int tl_voff = (tl_row0 < M && tl_col < N) ? (int)(((int64_t)tl_row0 * P.ldo + tl_col) * 4) : (int)OOB;
+    const int tl_stride = (int)((int64_t)TL_RPI * P.ldo * 4);                      // bytes from one instruction's rows to the next's
+    int tl_c = 0;                                    // instructions issued so far
+    u32x4_t tl_v = {0u, 0u, 0u, 0u};
+    auto tl_step = [&]() __attribute__((always_inline)) {
+        if (tl_on) {
+            if (tl_c > 0 && tl_c <= TL_N)
+                __builtin_amdgcn_raw_buffer_store_b128(tl_v, tl_drsrc, tl_voff, (tl_c - 1) * tl_stride, COHERENT_LD);
+            // (the load is awaited by the wait in front of the next k-tile's barrier: it is older than the four
+            // left-operand loads that wait lets pass)
+            if (tl_c < TL_N)
+                tl_v = load_16_unawaited(tl_srsrc, (unsigned)tl_voff, tl_c * tl_stride);
+            ++tl_c;
+        }
+    };
+    auto land_arrival = [&](int first) __attribute__((always_inline)) {
+        const float *const tsrc = tl_src;
         if (TAILS && tsrc != nullptr) {
             __amdgpu_buffer_rsrc_t ts_rsrc =
                 __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(tsrc), 0, (int)r_bytes, 0x00020000);
@@ -691,13 +727,13 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
             static_assert(64 % CPR == 0 && (WTM / RPI) % TB == 0, "whole batches");
             const int sn = n0 + wn * WTN + (lane % CPR) * 4;
 #pragma unroll 1
-            for (int b = 0; b < WTM / RPI; b += TB) {
+            for (int b = first; b < WTM / RPI; b += TB) {
                 u32x4_t v[TB];
                 int off[TB];
 #pragma unroll
                 for (int u = 0; u < TB; ++u) {
                     const int sm = m0 + wm * WTM + (b + u) * RPI + lane / CPR;
-                    off[u] = (sm < M && sn < N) ? (int)(((int64_t)sm * P.ldo + sn) * 4) : (int)OOB;
+                    off[u] = (b + u < WTM / RPI && sm < M && sn < N) ? (int)(((int64_t)sm * P.ldo + sn) * 4) : (int)OOB;
                     v[u] = __builtin_amdgcn_raw_buffer_load_b128(ts_rsrc, off[u], 0, 0);
                 }
 #pragma unroll
@@ -711,7 +747,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         }
     };
     if (TAILS && tail_early)
-        land_arrival();
+        land_arrival(0);
     f32x4_t pre[PF ? TM : 1][PF ? TN : 1][4];
     auto prefetch_recv = [&](auto aux_tag) __attribute__((always_inline)) {
         constexpr int AUX = decltype(aux_tag)::value;
@@ -882,6 +918,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                     wait_vmcnt<(NS - 2) * LPT + A_LD>();
                 }
                 __syncthreads();
+                if constexpr (TL_STREAM)
+                    tl_step();
                 __builtin_amdgcn_sched_barrier(0);
             };
             phase16(p2_t{}, afA, wfB, afB, wfA, on_t{}, ca, 1, 3, publish, c2{}, nw_, 0, c0{}, on_t{}, na, 0, 0,
@@ -1429,8 +1467,11 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
         }
     }
     if constexpr (PERSIST) {
-        if (TAILS && !tail_early)
-            land_arrival();
+        if (TAILS && !tail_early) {
+            if (tl_on && tl_c > 0 && tl_c <= TL_N)   // the instruction in flight when the main loop ended
+                __builtin_amdgcn_raw_buffer_store_b128(tl_v, tl_drsrc, tl_voff, (tl_c - 1) * tl_stride, COHERENT_LD);
+            land_arrival(tl_on ? (tl_c < TL_N ? tl_c : TL_N) : 0);
+        }
         __syncthreads();                             // every wave is done with the LDS stages
     }
     item += item_stride;
