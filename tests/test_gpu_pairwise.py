@@ -320,3 +320,35 @@ def test_rs_pair_carried_on_every_tile_shape(tile):
                         assert torch.equal(run.each[i], run.stage[i]), f"layout {layout}: delivery of round {i + 1}"
     finally:
         os.environ.pop("COMMFUSE_TILE", None)
+
+
+@pytest.mark.parametrize("k", [64, 192, 1096, 2304])
+def test_rs_pair_carried_under_the_16x16x32_main_loop(k):
+    """Whole 256x256 tiles: the kernel deals the landing of an arrival over the k-tiles of its main loop (one
+    16-byte load and one store per lane and k-tile) and copies what the k range leaves over behind the epilogue:
+    one k-tile (nothing dealt), three, seventeen with a ragged tail, thirty-six (everything dealt)."""
+    p, mc, n = 4, 512, 768
+    w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=p, m_chunk=mc, n=n, k=k)
+    data = inputs.make_rs(w, salt=23 + k)
+    rank = 1
+    ref = _oracle_pair(w, data, rank)
+    FC = cf.CF_PERSISTENT | cf.CF_SERIAL | cf.CF_FUSED_COPY
+    os.environ["COMMFUSE_TILE"] = "256x256"
+    try:
+        for layout in (cf.CF_W_KN, cf.CF_W_NK):
+            run = H.RsPairRun(w, data, rank, layout, keep_all=True)
+            with H.Workspace(run.desc, cf.CF_KIND_RS_PAIR):
+                for rep in range(2):
+                    run.O.fill_(float("nan"))
+                    for t in run.send_each + run.each:
+                        t.fill_(float("nan"))
+                    run.run_schedule(FC)
+                    cf.device_status(run.cs)
+                    for i in range(p):
+                        got = H.to_host_f64(run.send_each[i] if i < p - 1 else run.O)
+                        e = H.rel_err(got, ref[i])
+                        assert e <= TIGHT_BF16, f"layout {layout} step {i}: {e:.3e}"
+                    for i in range(p - 1):
+                        assert torch.equal(run.each[i], run.stage[i]), f"layout {layout}: delivery of round {i + 1}"
+    finally:
+        os.environ.pop("COMMFUSE_TILE", None)
