@@ -448,16 +448,18 @@ def main() -> int:
         fl_attn = 4.0 * Ba * ha * (Sa // pa) * Sa * 128
         fl_proj = 2.0 * mca * Da * ha * 128
         best = None
+        attn_by_mode = {}
         for mode, extra in MODES:
             if "groups" in mode:                         # (the grouped launches exist for the plain RS / AG kinds)
                 continue
             t = time_calls(lambda: cf.run_attn_schedule(adesc, abufs, cs, xs, extra), cs, max(K, 30), W)
+            attn_by_mode[mode] = round(t * 1e3, 1)
             if best is None or t < best[0]:
                 best = (t, mode)
         attention = {"attention_kernel_us": round(t_attn * 1e3, 1),
                      "attention_kernel_tflops": round(fl_attn / (t_attn * 1e-3) / 1e12, 1),
                      "frac_mfma_peak_attention_kernel": round(fl_attn / (t_attn * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-                     "rank_step_us": round(best[0] * 1e3, 1), "mode": best[1],
+                     "rank_step_us": round(best[0] * 1e3, 1), "mode": best[1], "rank_step_us_by_mode": attn_by_mode,
                      "rank_step_tflops": round(pa * (fl_attn + fl_proj) / (best[0] * 1e-3) / 1e12, 1),
                      "shape": "p=8, 8 of 64 heads per rank, head_dim 128, seq 8192, batch 1, W_o [1024 x 8192]"}
         log("attention", attention)

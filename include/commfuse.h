@@ -342,10 +342,13 @@ enum {
                             buffer (recv_each).  All-gather: the kernel takes the gathered slices from the
                             neighbours' buffers as its left operand, and every k-tile that comes in is
                             stored on to the landing buffer by one of the workgroups that load it.  (A row
-                            block lands without the padding of its rows.)  Where the launch cannot do that
-                            (reduce-scatter: a tile other than 256x256, a k range under 18 k-tiles of 64,
-                            or 20 with a ragged last one; all-gather: k not a multiple of 64; the other
-                            kinds) the flag changes nothing: the deliveries are enqueued in front.
+                            block lands without the padding of its rows.)  A reduce-scatter launch that
+                            cannot do that (a tile other than 256x256, a k range under 18 k-tiles of 64, or
+                            20 with a ragged last one; the projection of the attention layer) reads B_in
+                            from the neighbour's buffer in its epilogue, and the same work item copies its
+                            tile's part of it to the landing buffer beside its GEMM (packed partial sums,
+                            ldo == n).  Otherwise (all-gather: k not a multiple of 64; the other kinds) the
+                            flag changes nothing: the deliveries are enqueued in front.
                             With CF_FUSED_COPY (CF_KIND_RS_PAIR) and a registered workspace: the work items
                             of step t-1 land the arrival of round t (peer_stage[t-1] -> recv_each[t-1]), each
                             its own output tile's part, and count the tile up; the step that sums the

@@ -66,7 +66,9 @@ struct GemmParams {
     // buffer) to tail_dst[s] (its landing buffer; both laid out like the output), written through to memory, and then
     // counts tile_ready[tile] up.  The last step's work item waits (bounded by spin_limit; a time-out sets bit 0 of
     // *status) until its tile's count reaches ready_count, then reads recv_step / recv_more -- the landing buffers --
-    // past the caches.  tile_ready holds max_tiles words, all zero at launch.
+    // past the caches.  tile_ready holds max_tiles words, all zero at launch.  With tile_ready == nullptr nothing is
+    // counted and nobody waits: a reduce-scatter step whose B_in is loaded in its epilogue (recv_step[s] = the sender's
+    // buffer) lands that same B_in beside its GEMM this way (tail_src[s] = recv_step[s]).
     const float *tail_src[MAX_STEPS] = {};
     float *tail_dst[MAX_STEPS] = {};
     unsigned *tile_ready = nullptr;
@@ -144,6 +146,10 @@ bool gemm_bf16_takes_recv_list(const GemmParams &p, bool w_kn);
 // arrivals of the pairwise schedule landed by the work items of the steps before the one that sums them), else 0.
 // The caller provides that many zeroed counters.
 int gemm_bf16_tiles_landing_arrivals(const GemmParams &p, bool w_kn, int num_cu);
+// True if a persistent reduce-scatter launch that does NOT stream B_in (gemm_bf16_carries_delivery says no) can still
+// carry its deliveries: B_in read from the sender's buffer in the epilogue and landed by the same work item beside
+// its GEMM (GemmParams::tail_src without counters).  fp32 partial sums, direct-to-LDS kernel.
+bool gemm_bf16_lands_beside(const GemmParams &p, bool w_kn, bool out_bf16, int num_cu);
 // True if launch_gemm_bf16 would run this persistent launch (reduce_scatter: its steps add a received partial;
 // else an all-gather's) on a kernel that honours GemmParams::land_step (the delivery carried by the consumer)
 // for every step that receives.

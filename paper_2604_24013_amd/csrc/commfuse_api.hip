@@ -895,6 +895,18 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
         probe.n_steps = S;
         carried = cf::gemm_bf16_carries_delivery(probe, r.w_kn, r.bf16_out, num_cu_of_current_device(), kind == CF_KIND_RS);
     }
+    // A reduce-scatter launch that cannot stream B_in (a short k range, another tile, the projection of the attention
+    // layer) carries its deliveries the other way: the epilogue reads B_in from the neighbour's buffer, and the same
+    // work item copies its tile's part of it to the landing buffer beside its GEMM (no counter: nobody waits for it).
+    bool carried_beside = false;
+    if ((flags & CF_FUSED_COPY) && kind == CF_KIND_RS && !carried && do_copy && do_compute && slot_bytes > 0 && r.mc > 0 &&
+        r.n > 0 && r.k > 0 && r.ldo == r.n) {
+        cf::GemmParams probe;
+        probe.W = b->W;
+        fill_shape(probe, r);
+        probe.n_steps = S;
+        carried_beside = cf::gemm_bf16_lands_beside(probe, r.w_kn, r.bf16_out, num_cu_of_current_device());
+    }
     // The gradient bucket with CF_FUSED_COPY: the add kernels read the arrivals from the neighbours' buffers and
     // store them on to the landing buffers in the same pass (ring: 16 bytes per element instead of a copy's 8 plus
     // the add's 12; pairwise, p - 1 arrivals in one pass: 8 p instead of 12 p - 4).
@@ -928,7 +940,7 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
     // stream never waits for a kernel.
     int group = S;
     const bool grouped = !(flags & CF_SERIAL) && xs != cs && (kind == CF_KIND_RS || kind == CF_KIND_AG) && attn == nullptr &&
-                         !carried && p > 1 && slot_bytes > 0 && r.mc > 0 && r.n > 0 && r.k > 0;
+                         !carried && !carried_beside && p > 1 && slot_bytes > 0 && r.mc > 0 && r.n > 0 && r.k > 0;
     if (grouped) {
         cf::GemmParams probe;
         probe.W = b->W;
@@ -972,7 +984,7 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
         if (!do_compute)                                 // copies only: the compute stream still ends behind them
             CF_HIP(hipStreamWaitEvent(cs, ev[n_groups], 0));
     }
-    if (do_copy && slot_bytes > 0 && !carried && !grouped) {
+    if (do_copy && slot_bytes > 0 && !carried && !carried_beside && !grouped) {
         // all deliveries of the rank step are due now: one batched copy launch where the buffers allow it
         // (at most 16 hops of 16-byte-aligned whole hop buffers), else one hipMemcpyAsync per (sub-)step
         const void *srcs[cf::GemmParams::MAX_STEPS];
@@ -1091,6 +1103,11 @@ cf_status enqueue_persistent(const Resolved &r, int kind, const cf_buffers *b, h
                 if (carried && receives(jj)) {       // read from the neighbour's buffer, land it here
                     gp.recv_step[j] = reinterpret_cast<const float *>(stage_of(jj));
                     gp.land_step[j] = landing(jj);
+                }
+                if (carried_beside && receives(jj)) { // ... in the epilogue, and landed by a copy beside the GEMM
+                    gp.recv_step[j] = reinterpret_cast<const float *>(stage_of(jj));
+                    gp.tail_src[j] = gp.recv_step[j];
+                    gp.tail_dst[j] = static_cast<float *>(landing(jj));
                 }
                 gp.out_step[j] = sends(jj) ? static_cast<void *>(b->send_each[jj / m] + (size_t)(jj % m) * r.mc * r.ldo)
                                            : static_cast<void *>(static_cast<float *>(b->O) + (size_t)(jj % m) * r.mc * r.ldo);

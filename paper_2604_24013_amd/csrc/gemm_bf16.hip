@@ -361,6 +361,17 @@ int gemm_bf16_tiles_landing_arrivals(const GemmParams &p, bool w_kn, int num_cu)
     return tiles <= 1 << 20 ? (int)tiles : 0;
 }
 
+bool gemm_bf16_lands_beside(const GemmParams &p, bool w_kn, bool out_bf16, int num_cu)
+{
+    const Tuning tn = tuning();
+    if (p.n_steps <= 0 || out_bf16 || p.a_t || !gemm_bf16_takes_recv_list(p, w_kn) || (tn.carry >= 0 && tn.carry == 0))
+        return false;
+    for (int j = 0; j < p.n_steps; ++j)
+        if (p.flag_step[j] != nullptr)
+            return false;
+    return !gemm_bf16_dl_streams_recv(p, w_kn, out_bf16, tile_of_launch(p, num_cu));
+}
+
 bool gemm_bf16_carries_delivery(const GemmParams &p, bool w_kn, bool out_bf16, int num_cu, bool reduce_scatter)
 {
     if (p.M <= 0 || p.N <= 0 || p.n_steps <= 0 || staged_kernel_forced() || !gemm_bf16_dl_supported(p, w_kn))

@@ -740,10 +740,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_bf16_dl_kernel(GemmParams
                 for (int u = 0; u < TB; ++u)
                     __builtin_amdgcn_raw_buffer_store_b128(v[u], td_rsrc, off[u], 0, COHERENT_LD);
             }
-            __builtin_amdgcn_s_waitcnt(0);           // this wave's stores are acknowledged
-            __syncthreads();                         // ... and every wave's
-            if (tid == 0)
-                __hip_atomic_fetch_add(&P.tile_ready[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (P.tile_ready != nullptr) {           // (nobody waits for a copy that only lands this step's own B_in)
+                __builtin_amdgcn_s_waitcnt(0);       // this wave's stores are acknowledged
+                __syncthreads();                     // ... and every wave's
+                if (tid == 0)
+                    __hip_atomic_fetch_add(&P.tile_ready[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     };
     if (TAILS && tail_early)
@@ -1491,9 +1493,12 @@ hipError_t launch_cfg(const GemmParams &p, bool w_kn, bool out_bf16, hipStream_t
     for (int j = 0; j < p.n_steps; ++j)
         any_flag = any_flag || p.flag_step[j] != nullptr;
     const int nk_all = (p.K + BK - 1) / BK;
+    bool any_tail = false;                           // a step lands an arrival beside its GEMM (GemmParams::tail_src)
+    for (int j = 0; j < p.n_steps; ++j)
+        any_tail = any_tail || p.tail_src[j] != nullptr;
     [[maybe_unused]] const bool rlds = SPREAD && NS == 2 && any_recv && !out_bf16 && !p.a_t && p.stream_recv && !any_flag &&
                                        p.n_recv_more == 0 && p.splits == 1 && nk_all >= 18 + (p.K % BK != 0 ? 2 : 0) &&
-                                       p.tile_ready == nullptr;
+                                       p.tile_ready == nullptr && !any_tail;
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     int wgs = tiles_m * tiles_n * p.splits + p.cp_wgs;
     if (p.n_steps > 0) {                             // persistent: a grid that fills the chip once
@@ -1619,7 +1624,7 @@ hipError_t launch_gemm_bf16_dl(const GemmParams &p_in, bool w_kn, bool out_bf16,
         if (p.tile_ready != nullptr && (out_bf16 || tiles > p.max_tiles || p.status == nullptr || p.spin_limit == 0))
             return hipErrorInvalidValue;              // callers ask gemm_bf16_tiles_landing_arrivals first
         for (int j = 0; j < p.n_steps; ++j)
-            if ((p.tail_src[j] != nullptr) != (p.tail_dst[j] != nullptr) || (p.tail_src[j] != nullptr && p.tile_ready == nullptr))
+            if ((p.tail_src[j] != nullptr) != (p.tail_dst[j] != nullptr) || (p.tail_src[j] != nullptr && out_bf16))
                 return hipErrorInvalidValue;
         p.splits = 1;
         p.cp_wgs = 0;

@@ -682,16 +682,21 @@ def test_persistent_mfma16_main_loop(k, mfma16):
             w = inputs.scaled(inputs.CONFIGS["c2_rs_7b"], p=8, m_chunk=m_chunk, n=n, k=k)
             data = inputs.make_rs(w, salt=81 + k)
             ref = _oracle_rs(w, data, rank)
-            for layout in (cf.CF_W_KN, cf.CF_W_NK):
+            # (CF_FUSED_COPY: these k ranges are too short for B_in to be streamed, so the epilogue reads it from the
+            # neighbour's buffer and the work item lands it by a copy beside its GEMM)
+            for layout, flags in ((cf.CF_W_KN, PERSISTENT_SERIAL), (cf.CF_W_NK, PERSISTENT_SERIAL),
+                                  (cf.CF_W_KN, PERSISTENT_SERIAL | cf.CF_FUSED_COPY), (cf.CF_W_NK, PERSISTENT_SERIAL | cf.CF_FUSED_COPY)):
                 run = H.RsRun(w, data, rank, layout, m=m, each=True)
                 for t in run.each + run.send_each + [run.O]:
                     t.fill_(float("nan"))
-                run.run_schedule(PERSISTENT_SERIAL)
+                run.run_schedule(flags)
                 cf.device_status(run.cs)
                 for i in range(w.p):
                     got = H.to_host_f64(run.send_each[i] if i < w.p - 1 else run.O)
                     e = H.rel_err(got, ref[i])
-                    assert e <= TIGHT_BF16, f"rs m {m} layout {layout} step {i}: {e:.3e}"
+                    assert e <= TIGHT_BF16, f"rs m {m} layout {layout} flags {flags} step {i}: {e:.3e}"
+                for i in range(w.p - 1):
+                    assert torch.equal(run.each[i], run.stage[i]), f"rs m {m} layout {layout} flags {flags}: hop {i + 1}"
             for out_dtype in ("bf16", "f32"):
                 wa = inputs.scaled(inputs.CONFIGS["c3_ag_7b"], p=8, m_chunk=m_chunk, n=n, k=k, out_dtype=out_dtype)
                 da = inputs.make_ag(wa, salt=82 + k)
